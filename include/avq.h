@@ -1,0 +1,196 @@
+/*
+ * avq.h -- C ABI of the MI355X (gfx950) library for score-aware / anisotropic
+ * quantized maximum inner product search, after "Accelerating Large-Scale
+ * Inference with Anisotropic Vector Quantization" (arXiv 1908.10396).
+ *
+ * The problem (paper, Section 1): a database X = {x_i}, i < n, of points in R^d;
+ * for a query q return the points with the largest <q, x_i>. The library
+ * answers approximately: product-quantization codes assigned under the
+ * anisotropic loss eta*||r_par||^2 + ||r_perp||^2 (Sections 3.1, 3.2, 4.1) are
+ * scored through per-query lookup tables (Section 4.1), the best reorder_k
+ * candidates are re-scored exactly in fp32 and the best k returned.
+ *
+ * Conventions that hold for every call
+ *  - One GPU. All work runs on the HIP device that is current when avq_create
+ *    is called, on the stream passed in (NULL = the default stream). Calls are
+ *    asynchronous with respect to the host except where stated; outputs are
+ *    valid after the stream has been synchronised.
+ *  - "device pointer" = memory on that GPU allocated by the caller (e.g. a
+ *    torch tensor's data_ptr()); the library never frees it. "host or device"
+ *    = either; such arguments are copied with hipMemcpyDefault and the call
+ *    synchronises the stream.
+ *  - Matrices are row-major, dense. Floats are IEEE fp32, finite; behaviour
+ *    for NaN/Inf inputs is undefined.
+ *  - Every function returns AVQ_OK (0) or a negative avq_status; no C++
+ *    exception crosses the boundary. avq_last_error() gives a message for the
+ *    last failing call on the calling thread.
+ *  - A single avq_index must not be used from two threads at once, nor by two
+ *    overlapping calls on different streams: calls share per-index scratch.
+ */
+#ifndef AVQ_H
+#define AVQ_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    AVQ_OK = 0,
+    AVQ_EINVAL = -1, /* bad argument (shape, range, NULL)                   */
+    AVQ_ESTATE = -2, /* call out of order (search before codes exist, ...)   */
+    AVQ_ENOMEM = -3, /* device or host allocation failed                     */
+    AVQ_EHIP = -4    /* a HIP runtime call or kernel launch failed           */
+} avq_status;
+
+enum { AVQ_LUT_F32 = 0, AVQ_LUT_U8 = 1 };
+enum { AVQ_ETA_LIMIT = 0, AVQ_ETA_EXACT = 1, AVQ_ETA_EXPLICIT = 2 };
+
+/* Largest reorder_k / k / leaves_to_search the wave-level selection supports. */
+#define AVQ_MAX_SELECT 512
+
+typedef struct avq_index avq_index; /* opaque; owned by the library */
+
+typedef struct {
+    int32_t d;    /* dimension, >= 2                                            */
+    int32_t M;    /* number of PQ subspaces; d % M == 0 (Section 4.1)           */
+    int32_t bits; /* 4 or 8; codewords per subspace k_c = 1 << bits             */
+    float T;      /* threshold of the weight w(t) = I(t >= T), T >= 0 (Sec 3.2) */
+    int32_t eta_mode; /* AVQ_ETA_LIMIT: eta = max(1, (d-1) u/(1-u)), u = (T/||x_i||)^2
+                         (Eq. 3 used as a proxy, floored at 1 as Theorem 3.3 requires);
+                         AVQ_ETA_EXACT: h_par/h_perp of Section 3.2;
+                         AVQ_ETA_EXPLICIT: eta_explicit for every point.
+                         In the first two modes eta is evaluated per point from
+                         its own norm; u is clamped to 0.999; ||x|| = 0 -> 1.   */
+    float eta_explicit;
+    int32_t kmeans_iters;       /* Lloyd iterations for the PQ dictionaries      */
+    int32_t encode_passes;      /* max coordinate-descent passes in avq_encode   */
+    int32_t n_leaves;           /* 0 = flat index; > 0 = partition into leaves,
+                                   PQ on residuals to the leaf centers          */
+    int32_t leaf_kmeans_iters;  /* Lloyd iterations for the leaf centers         */
+    int32_t borrow_x;           /* 0: avq_encode/avq_set_data copy x;
+                                   1: keep the caller's device pointer, which
+                                   must stay valid and unchanged for the life
+                                   of the index                                  */
+    uint64_t seed;              /* seeds the draw of the initial codewords       */
+} avq_config;
+
+/* Validates cfg and allocates an empty index on the current device.
+ * AVQ_EINVAL: d < 2, M < 1, d % M != 0, bits not 4/8, T < 0, negative counts,
+ * eta_mode out of range, eta_explicit < 1 in explicit mode. */
+int avq_create(const avq_config *cfg, avq_index **out);
+void avq_destroy(avq_index *idx);
+
+/* Section 4 / 4.1, dictionary learning. x: device pointer [n_train][d].
+ * Learns the leaf centers (if n_leaves > 0; Lloyd's algorithm on the full
+ * vectors) and then the M dictionaries by Lloyd's algorithm per subspace
+ * under the l2 loss -- the dictionary of Section 5.1, which the paper also
+ * offers as the initialisation of Section 4.1 -- on x, or on the residuals to
+ * the nearest leaf center. Initial codeword j of a dictionary is the datapoint
+ * at index lo_j + h mod (hi_j - lo_j), [lo_j, hi_j) the j-th of k equal strata
+ * of the n_train rows and h a splitmix64 hash of (seed, dictionary, j).
+ * Distances and means are fp64; an empty cluster keeps its center.
+ * Needs n_train >= max(k_c, n_leaves). Synchronises the stream. */
+int avq_train(avq_index *idx, const float *x, int64_t n_train, void *hip_stream);
+
+/* Section 4.1, partition-assignment step, for every row of x (device pointer
+ * [n][d]): start from the l2-nearest codeword in each subspace, then cyclic
+ * coordinate descent over the subspaces, each time taking the codeword that
+ * minimises eta*||r_par||^2 + ||r_perp||^2 of the whole vector (Section 3.2)
+ * with the others fixed, lowest index on equal loss, until a pass changes
+ * nothing or encode_passes passes are done. Arithmetic is fp64. With leaves,
+ * x~ = center(leaf(x)) + PQ(residual) and the loss is taken against x itself.
+ * Replaces any previous database: stores the codes in the library's private
+ * blocked layout and x (copied or borrowed) for exact re-scoring.
+ * Needs dictionaries (avq_train or avq_set_codebooks). 0 < n < 2^31 - 512.
+ * Synchronises the stream. */
+int avq_encode(avq_index *idx, const float *x, int64_t n, void *hip_stream);
+
+/* The query path (Sections 2.2.2 and 4.1 plus exact re-scoring).
+ * queries: device [nq][d]; ids_out: device int32 [nq][k]; scores_out: device
+ * fp32 [nq][k]. Steps, all on the GPU:
+ *  (leaves only) score every leaf center by <q, center> and keep the
+ *    leaves_to_search best;
+ *  build the tables L[m][j] = <q^(m), c_j^(m)> in fp32 (fma chain over the
+ *    subspace's dimensions in index order);
+ *  lut_mode AVQ_LUT_U8: quantise them per query to 8 bits: lo_m = min_j L,
+ *    R = max_m(max_j L - lo_m), code = clamp(rne((L - lo_m) * (255/R)), 0, 255),
+ *    scale = R/255, bias = sum_m lo_m (R = 0: all codes 0, scale 0);
+ *  ADC: score every scanned point by the sum of its M table entries (fp32:
+ *    the two entries of a packed 4-bit byte are added first, then bytes are
+ *    accumulated in order; 8-bit tables: exact integer sum). With leaves the
+ *    score is s + <q, center> (fp32) or fma(acc, scale, bias + <q, center>);
+ *  keep the R = reorder_k best by (score descending, id ascending);
+ *  re-score those exactly, <q, x_i> as an fp32 fma chain in index order, and
+ *    return the k best in the same order.
+ * reorder_k == 0: no re-scoring; the k best ADC candidates are returned with
+ * their ADC scores (8-bit tables, flat index: fma(acc, scale, bias)).
+ * Rows with fewer than k candidates are padded with id -1, score -inf.
+ * AVQ_EINVAL: nq < 1, k < 1, reorder_k != 0 and < k, k or reorder_k >
+ * AVQ_MAX_SELECT, k > n, bad lut_mode, leaves_to_search outside
+ * [1, min(n_leaves, AVQ_MAX_SELECT)] on a partitioned index.
+ * AVQ_ESTATE: no codes yet. Does not synchronise (scratch may be grown with
+ * hipMalloc on the first call of a given size). */
+int avq_search(avq_index *idx, const float *queries, int32_t nq, int32_t k, int32_t reorder_k,
+               int32_t lut_mode, int32_t leaves_to_search, int32_t *ids_out, float *scores_out,
+               void *hip_stream);
+
+/* Section 1's definition, exactly: the k points with the largest <q, x_i>
+ * (fp32 fma chain in index order; ties by lower id) among all n stored
+ * points. Same argument layout as avq_search. Ground truth for recall. */
+int avq_brute_force(avq_index *idx, const float *queries, int32_t nq, int32_t k,
+                    int32_t *ids_out, float *scores_out, void *hip_stream);
+
+/* ---- injection and inspection (used to test every stage on its own) ---- */
+
+/* Dictionaries [M][k_c][d/M] fp32, host or device. */
+int avq_set_codebooks(avq_index *idx, const float *codebooks);
+int avq_get_codebooks(avq_index *idx, float *codebooks_out);
+/* Leaf centers [n_leaves][d] fp32, host or device (partitioned index only). */
+int avq_set_leaf_centers(avq_index *idx, const float *centers);
+int avq_get_leaf_centers(avq_index *idx, float *centers_out);
+/* Install a database without encoding it. x: device [n][d] (copied or
+ * borrowed as cfg.borrow_x says; may be NULL, then reorder_k must be 0 and
+ * avq_brute_force is unavailable). packed: host or device [n][ceil(M*bits/8)],
+ * the logical code layout: 8-bit codes one byte per subspace; 4-bit codes two
+ * per byte, subspace m in byte m/2, even m in the low nibble. leaf_assign:
+ * host or device int32 [n] (partitioned index) or NULL (flat). */
+int avq_set_database(avq_index *idx, const float *x, const uint8_t *packed,
+                     const int32_t *leaf_assign, int64_t n, void *hip_stream);
+/* Codes in the logical layout above / the leaf of every point. Host or device. */
+int avq_get_codes(avq_index *idx, uint8_t *packed_out);
+int avq_get_leaf_assign(avq_index *idx, int32_t *assign_out);
+int64_t avq_size(const avq_index *idx); /* n, or 0 */
+
+/* The tables avq_search would use. lut_out: device fp32 [nq][M][k_c]
+ * (AVQ_LUT_F32) or uint8 [nq][M][k_c] (AVQ_LUT_U8); scale_out/bias_out: device
+ * fp32 [nq], written in U8 mode only (may be NULL otherwise). */
+int avq_debug_lut(avq_index *idx, const float *queries, int32_t nq, int32_t lut_mode,
+                  void *lut_out, float *scale_out, float *bias_out, void *hip_stream);
+/* ADC score of every stored point, flat index only, produced by the same scan
+ * kernel as avq_search. scores_out: device [nq][n], fp32 (AVQ_LUT_F32) or
+ * int32 integer sums (AVQ_LUT_U8). */
+int avq_debug_adc_scores(avq_index *idx, const float *queries, int32_t nq, int32_t lut_mode,
+                         void *scores_out, void *hip_stream);
+/* Leaf selection alone: leaf_ids_out int32 [nq][L], leaf_ip_out fp32 [nq][L],
+ * device pointers; best leaf first. */
+int avq_debug_leaf_select(avq_index *idx, const float *queries, int32_t nq, int32_t L,
+                          int32_t *leaf_ids_out, float *leaf_ip_out, void *hip_stream);
+
+/* eta of Section 3.2 for one norm, on the host (no GPU needed):
+ * mode AVQ_ETA_LIMIT or AVQ_ETA_EXACT as in avq_config. */
+double avq_eta(int32_t d, double T, double norm, int32_t eta_mode);
+
+/* Launch-shape overrides for experiments; 0 restores the built-in choice.
+ * name: "scan_target_wgs", "scan_waves", "scan_qt". Returns AVQ_EINVAL for an
+ * unknown name. */
+int avq_set_tuning(avq_index *idx, const char *name, int32_t value);
+
+const char *avq_last_error(void);
+const char *avq_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AVQ_H */

@@ -1,0 +1,551 @@
+// C ABI of libavq (declared in include/avq.h): argument checking, the index
+// object, device buffers and the sequence of kernel launches of each call.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <new>
+
+#include "avq_internal.h"
+
+namespace avq {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+int DevBuf::reserve(size_t bytes)
+{
+    if (bytes <= cap) return AVQ_OK;
+    if (p) { (void)hipFree(p); p = nullptr; cap = 0; }
+    hipError_t e = hipMalloc(&p, bytes);
+    if (e != hipSuccess) {
+        p = nullptr;
+        set_error("hipMalloc(%zu) failed: %s", bytes, hipGetErrorString(e));
+        return e == hipErrorOutOfMemory ? AVQ_ENOMEM : AVQ_EHIP;
+    }
+    cap = bytes;
+    return AVQ_OK;
+}
+
+void DevBuf::release()
+{
+    if (p) (void)hipFree(p);
+    p = nullptr;
+    cap = 0;
+}
+
+} // namespace avq
+
+using namespace avq;
+
+struct avq_index {
+    avq_config cfg;
+    int kc = 0, ds = 0, NB = 0;
+    bool have_codebooks = false, have_centers = false;
+    DevBuf codebooks, centers, centers_t;
+    // database
+    int64_t n = 0, n_slots = 0, n_blocks = 0;
+    const float *x = nullptr;
+    DevBuf x_own, codes_logical, codes_blocked, assign, perm, leaf_blk;
+    // per-call scratch
+    DevBuf lut, lut8, scale, bias, partial, cand, leaf_ids, leaf_ip, tmp;
+    int tune_target_wgs = 0, tune_waves = 0, tune_qt = 0;
+};
+
+static int check_index(const avq_index *idx)
+{
+    if (!idx) { set_error("index is NULL"); return AVQ_EINVAL; }
+    return AVQ_OK;
+}
+
+extern "C" const char *avq_last_error(void) { return g_err; }
+extern "C" const char *avq_version(void) { return "avq 0.1 (gfx950)"; }
+
+extern "C" double avq_eta(int32_t d, double T, double norm, int32_t eta_mode)
+{
+    if (eta_mode != AVQ_ETA_LIMIT && eta_mode != AVQ_ETA_EXACT) return -1.0;
+    return eta_host(d, T, norm, eta_mode);
+}
+
+extern "C" int avq_create(const avq_config *cfg, avq_index **out)
+{
+    if (!cfg || !out) { set_error("avq_create: NULL argument"); return AVQ_EINVAL; }
+    *out = nullptr;
+    if (cfg->d < 2 || cfg->M < 1 || cfg->d % cfg->M != 0) {
+        set_error("avq_create: need d >= 2, M >= 1, d %% M == 0 (d=%d M=%d)", cfg->d, cfg->M);
+        return AVQ_EINVAL;
+    }
+    if (cfg->bits != 4 && cfg->bits != 8) { set_error("avq_create: bits must be 4 or 8"); return AVQ_EINVAL; }
+    if (!(cfg->T >= 0.0f)) { set_error("avq_create: T must be >= 0"); return AVQ_EINVAL; }
+    if (cfg->eta_mode < 0 || cfg->eta_mode > 2) { set_error("avq_create: bad eta_mode"); return AVQ_EINVAL; }
+    if (cfg->eta_mode == AVQ_ETA_EXPLICIT && !(cfg->eta_explicit >= 1.0f)) {
+        set_error("avq_create: eta_explicit must be >= 1");
+        return AVQ_EINVAL;
+    }
+    if (cfg->kmeans_iters < 0 || cfg->encode_passes < 0 || cfg->n_leaves < 0 || cfg->leaf_kmeans_iters < 0) {
+        set_error("avq_create: negative count");
+        return AVQ_EINVAL;
+    }
+    if (cfg->M > 256) { set_error("avq_create: M > 256 not supported"); return AVQ_EINVAL; }
+    avq_index *idx = new (std::nothrow) avq_index();
+    if (!idx) { set_error("avq_create: out of host memory"); return AVQ_ENOMEM; }
+    idx->cfg = *cfg;
+    idx->kc = 1 << cfg->bits;
+    idx->ds = cfg->d / cfg->M;
+    idx->NB = (cfg->M * cfg->bits + 7) / 8;
+    int rc = idx->codebooks.reserve(sizeof(float) * (size_t)cfg->M * idx->kc * idx->ds);
+    if (rc == AVQ_OK && cfg->n_leaves > 0) {
+        rc = idx->centers.reserve(sizeof(float) * (size_t)cfg->n_leaves * cfg->d);
+        if (rc == AVQ_OK) rc = idx->centers_t.reserve(sizeof(float) * (size_t)cfg->n_leaves * cfg->d);
+    }
+    if (rc != AVQ_OK) { avq_destroy(idx); return rc; }
+    *out = idx;
+    return AVQ_OK;
+}
+
+extern "C" void avq_destroy(avq_index *idx)
+{
+    if (!idx) return;
+    DevBuf *all[] = {&idx->codebooks, &idx->centers, &idx->centers_t, &idx->x_own, &idx->codes_logical,
+                     &idx->codes_blocked, &idx->assign, &idx->perm, &idx->leaf_blk, &idx->lut, &idx->lut8,
+                     &idx->scale, &idx->bias, &idx->partial, &idx->cand, &idx->leaf_ids, &idx->leaf_ip,
+                     &idx->tmp};
+    for (DevBuf *b : all) b->release();
+    delete idx;
+}
+
+extern "C" int64_t avq_size(const avq_index *idx) { return idx ? idx->n : 0; }
+
+extern "C" int avq_set_tuning(avq_index *idx, const char *name, int32_t value)
+{
+    AVQ_TRY(check_index(idx));
+    if (!name || value < 0) { set_error("avq_set_tuning: bad argument"); return AVQ_EINVAL; }
+    if (!strcmp(name, "scan_target_wgs")) idx->tune_target_wgs = value;
+    else if (!strcmp(name, "scan_waves")) idx->tune_waves = value;
+    else if (!strcmp(name, "scan_qt")) idx->tune_qt = value;
+    else { set_error("avq_set_tuning: unknown name '%s'", name); return AVQ_EINVAL; }
+    return AVQ_OK;
+}
+
+// ---- dictionaries and leaf centers -------------------------------------------------
+
+extern "C" int avq_set_codebooks(avq_index *idx, const float *codebooks)
+{
+    AVQ_TRY(check_index(idx));
+    if (!codebooks) { set_error("avq_set_codebooks: NULL"); return AVQ_EINVAL; }
+    AVQ_HIP(hipMemcpy(idx->codebooks.p, codebooks, sizeof(float) * (size_t)idx->cfg.M * idx->kc * idx->ds,
+                      hipMemcpyDefault));
+    idx->have_codebooks = true;
+    return AVQ_OK;
+}
+
+extern "C" int avq_get_codebooks(avq_index *idx, float *out)
+{
+    AVQ_TRY(check_index(idx));
+    if (!out) { set_error("avq_get_codebooks: NULL"); return AVQ_EINVAL; }
+    if (!idx->have_codebooks) { set_error("avq_get_codebooks: no dictionaries yet"); return AVQ_ESTATE; }
+    AVQ_HIP(hipMemcpy(out, idx->codebooks.p, sizeof(float) * (size_t)idx->cfg.M * idx->kc * idx->ds,
+                      hipMemcpyDefault));
+    return AVQ_OK;
+}
+
+static int refresh_centers_t(avq_index *idx, hipStream_t st)
+{
+    AVQ_TRY(launch_transpose(idx->centers.as<float>(), idx->cfg.n_leaves, idx->cfg.d,
+                             idx->centers_t.as<float>(), st));
+    AVQ_HIP(hipStreamSynchronize(st));
+    return AVQ_OK;
+}
+
+extern "C" int avq_set_leaf_centers(avq_index *idx, const float *centers)
+{
+    AVQ_TRY(check_index(idx));
+    if (idx->cfg.n_leaves <= 0) { set_error("avq_set_leaf_centers: flat index"); return AVQ_ESTATE; }
+    if (!centers) { set_error("avq_set_leaf_centers: NULL"); return AVQ_EINVAL; }
+    AVQ_HIP(hipMemcpy(idx->centers.p, centers, sizeof(float) * (size_t)idx->cfg.n_leaves * idx->cfg.d,
+                      hipMemcpyDefault));
+    AVQ_TRY(refresh_centers_t(idx, nullptr));
+    idx->have_centers = true;
+    return AVQ_OK;
+}
+
+extern "C" int avq_get_leaf_centers(avq_index *idx, float *out)
+{
+    AVQ_TRY(check_index(idx));
+    if (idx->cfg.n_leaves <= 0 || !idx->have_centers) {
+        set_error("avq_get_leaf_centers: no leaf centers");
+        return AVQ_ESTATE;
+    }
+    if (!out) { set_error("avq_get_leaf_centers: NULL"); return AVQ_EINVAL; }
+    AVQ_HIP(hipMemcpy(out, idx->centers.p, sizeof(float) * (size_t)idx->cfg.n_leaves * idx->cfg.d,
+                      hipMemcpyDefault));
+    return AVQ_OK;
+}
+
+extern "C" int avq_train(avq_index *idx, const float *x, int64_t n_train, void *hip_stream)
+{
+    AVQ_TRY(check_index(idx));
+    hipStream_t st = (hipStream_t)hip_stream;
+    const avq_config &c = idx->cfg;
+    if (!x || n_train < idx->kc || n_train < c.n_leaves || n_train > 0x7fffffff) {
+        set_error("avq_train: need a device pointer and max(k_c, n_leaves) <= n_train < 2^31");
+        return AVQ_EINVAL;
+    }
+    const int32_t *assign = nullptr;
+    if (c.n_leaves > 0) {
+        // leaf centers from at most 256 rows per leaf, then every training row to its leaf
+        const int64_t n_leaf_train = std::min<int64_t>(n_train, (int64_t)256 * c.n_leaves);
+        AVQ_TRY(kmeans_device(x, n_leaf_train, c.d, 0, c.d, c.n_leaves, c.leaf_kmeans_iters, c.seed, 0u,
+                              nullptr, nullptr, idx->centers.as<float>(), st));
+        AVQ_TRY(refresh_centers_t(idx, st));
+        idx->have_centers = true;
+        AVQ_TRY(idx->tmp.reserve(sizeof(int32_t) * (size_t)n_train));
+        AVQ_TRY(launch_assign_nearest(x, n_train, c.d, idx->centers.as<float>(), c.n_leaves,
+                                      idx->tmp.as<int32_t>(), st));
+        assign = idx->tmp.as<int32_t>();
+    }
+    for (int m = 0; m < c.M; ++m)
+        AVQ_TRY(kmeans_device(x, n_train, c.d, m * idx->ds, idx->ds, idx->kc, c.kmeans_iters, c.seed,
+                              (uint32_t)(1 + m), assign ? idx->centers.as<float>() : nullptr, assign,
+                              idx->codebooks.as<float>() + (size_t)m * idx->kc * idx->ds, st));
+    AVQ_HIP(hipStreamSynchronize(st));
+    idx->have_codebooks = true;
+    return AVQ_OK;
+}
+
+// ---- database ------------------------------------------------------------------------
+
+// codes_logical (and assign, if partitioned) are on the device; builds the blocked layout.
+static int install_database(avq_index *idx, const float *x, int64_t n, hipStream_t st)
+{
+    const avq_config &c = idx->cfg;
+    idx->n = 0;
+    if (x && !c.borrow_x) {
+        AVQ_TRY(idx->x_own.reserve(sizeof(float) * (size_t)n * c.d));
+        AVQ_HIP(hipMemcpyAsync(idx->x_own.p, x, sizeof(float) * (size_t)n * c.d, hipMemcpyDeviceToDevice, st));
+        idx->x = idx->x_own.as<float>();
+    } else {
+        idx->x = x;
+    }
+    if (c.n_leaves <= 0) {
+        idx->n_blocks = (n + kBlockPoints - 1) / kBlockPoints;
+        idx->n_slots = idx->n_blocks * kBlockPoints;
+        AVQ_TRY(idx->codes_blocked.reserve((size_t)idx->n_slots * idx->NB));
+        AVQ_TRY(launch_to_blocked(idx->codes_logical.as<uint8_t>(), n, idx->NB, nullptr,
+                                  idx->codes_blocked.as<uint8_t>(), idx->n_slots, st));
+    } else {
+        // group the points by leaf (ascending id inside a leaf), each leaf padded to whole blocks
+        std::vector<int32_t> assign(n);
+        AVQ_HIP(hipMemcpyAsync(assign.data(), idx->assign.p, sizeof(int32_t) * (size_t)n, hipMemcpyDeviceToHost, st));
+        AVQ_HIP(hipStreamSynchronize(st));
+        std::vector<int64_t> count(c.n_leaves, 0);
+        for (int64_t i = 0; i < n; ++i) {
+            if (assign[i] < 0 || assign[i] >= c.n_leaves) {
+                set_error("leaf assignment %d of point %lld out of range", assign[i], (long long)i);
+                return AVQ_EINVAL;
+            }
+            count[assign[i]]++;
+        }
+        std::vector<int32_t> leaf_blk(c.n_leaves + 1);
+        int64_t blk = 0;
+        for (int l = 0; l < c.n_leaves; ++l) {
+            leaf_blk[l] = (int32_t)blk;
+            blk += (count[l] + kBlockPoints - 1) / kBlockPoints;
+        }
+        leaf_blk[c.n_leaves] = (int32_t)blk;
+        if (blk * kBlockPoints > 0x7fffffff) { set_error("index too large"); return AVQ_EINVAL; }
+        idx->n_blocks = blk;
+        idx->n_slots = blk * kBlockPoints;
+        std::vector<int32_t> slot_of(n), perm((size_t)idx->n_slots, -1);
+        std::vector<int64_t> next(c.n_leaves);
+        for (int l = 0; l < c.n_leaves; ++l) next[l] = (int64_t)leaf_blk[l] * kBlockPoints;
+        for (int64_t i = 0; i < n; ++i) {
+            const int64_t s = next[assign[i]]++;
+            slot_of[i] = (int32_t)s;
+            perm[s] = (int32_t)i;
+        }
+        AVQ_TRY(idx->tmp.reserve(sizeof(int32_t) * (size_t)n));
+        AVQ_TRY(idx->perm.reserve(sizeof(int32_t) * (size_t)std::max<int64_t>(idx->n_slots, 1)));
+        AVQ_TRY(idx->leaf_blk.reserve(sizeof(int32_t) * (size_t)(c.n_leaves + 1)));
+        AVQ_TRY(idx->codes_blocked.reserve((size_t)std::max<int64_t>(idx->n_slots, 1) * idx->NB));
+        AVQ_HIP(hipMemcpyAsync(idx->tmp.p, slot_of.data(), sizeof(int32_t) * (size_t)n, hipMemcpyHostToDevice, st));
+        AVQ_HIP(hipMemcpyAsync(idx->perm.p, perm.data(), sizeof(int32_t) * (size_t)idx->n_slots,
+                               hipMemcpyHostToDevice, st));
+        AVQ_HIP(hipMemcpyAsync(idx->leaf_blk.p, leaf_blk.data(), sizeof(int32_t) * (size_t)(c.n_leaves + 1),
+                               hipMemcpyHostToDevice, st));
+        AVQ_TRY(launch_to_blocked(idx->codes_logical.as<uint8_t>(), n, idx->NB, idx->tmp.as<int32_t>(),
+                                  idx->codes_blocked.as<uint8_t>(), idx->n_slots, st));
+        AVQ_HIP(hipStreamSynchronize(st)); // host vectors go out of scope
+    }
+    AVQ_HIP(hipStreamSynchronize(st));
+    idx->n = n;
+    return AVQ_OK;
+}
+
+static int check_n(int64_t n)
+{
+    if (n < 1 || n >= 0x7fffffffll - 512) { set_error("n = %lld out of range", (long long)n); return AVQ_EINVAL; }
+    return AVQ_OK;
+}
+
+extern "C" int avq_set_database(avq_index *idx, const float *x, const uint8_t *packed,
+                                const int32_t *leaf_assign, int64_t n, void *hip_stream)
+{
+    AVQ_TRY(check_index(idx));
+    AVQ_TRY(check_n(n));
+    hipStream_t st = (hipStream_t)hip_stream;
+    const avq_config &c = idx->cfg;
+    if (!packed) { set_error("avq_set_database: packed is NULL"); return AVQ_EINVAL; }
+    if ((c.n_leaves > 0) != (leaf_assign != nullptr)) {
+        set_error("avq_set_database: leaf_assign must be given exactly for a partitioned index");
+        return AVQ_EINVAL;
+    }
+    if (c.n_leaves > 0 && !idx->have_centers) { set_error("avq_set_database: no leaf centers yet"); return AVQ_ESTATE; }
+    AVQ_TRY(idx->codes_logical.reserve((size_t)n * idx->NB));
+    AVQ_HIP(hipMemcpyAsync(idx->codes_logical.p, packed, (size_t)n * idx->NB, hipMemcpyDefault, st));
+    if (leaf_assign) {
+        AVQ_TRY(idx->assign.reserve(sizeof(int32_t) * (size_t)n));
+        AVQ_HIP(hipMemcpyAsync(idx->assign.p, leaf_assign, sizeof(int32_t) * (size_t)n, hipMemcpyDefault, st));
+    }
+    AVQ_HIP(hipStreamSynchronize(st));
+    return install_database(idx, x, n, st);
+}
+
+extern "C" int avq_encode(avq_index *idx, const float *x, int64_t n, void *hip_stream)
+{
+    AVQ_TRY(check_index(idx));
+    AVQ_TRY(check_n(n));
+    hipStream_t st = (hipStream_t)hip_stream;
+    const avq_config &c = idx->cfg;
+    if (!x) { set_error("avq_encode: x is NULL"); return AVQ_EINVAL; }
+    if (!idx->have_codebooks) { set_error("avq_encode: no dictionaries yet (avq_train first)"); return AVQ_ESTATE; }
+    if (c.n_leaves > 0 && !idx->have_centers) { set_error("avq_encode: no leaf centers yet"); return AVQ_ESTATE; }
+    AVQ_TRY(idx->codes_logical.reserve((size_t)n * idx->NB));
+    const int32_t *assign = nullptr;
+    if (c.n_leaves > 0) {
+        AVQ_TRY(idx->assign.reserve(sizeof(int32_t) * (size_t)n));
+        AVQ_TRY(launch_assign_nearest(x, n, c.d, idx->centers.as<float>(), c.n_leaves,
+                                      idx->assign.as<int32_t>(), st));
+        assign = idx->assign.as<int32_t>();
+    }
+    AVQ_TRY(launch_encode(x, n, c.d, c.M, idx->kc, c.bits, idx->codebooks.as<float>(),
+                          assign ? idx->centers.as<float>() : nullptr, assign, c.eta_mode, (double)c.T,
+                          (double)c.eta_explicit, c.encode_passes, idx->codes_logical.as<uint8_t>(), st));
+    return install_database(idx, x, n, st);
+}
+
+extern "C" int avq_get_codes(avq_index *idx, uint8_t *out)
+{
+    AVQ_TRY(check_index(idx));
+    if (idx->n <= 0) { set_error("avq_get_codes: no database"); return AVQ_ESTATE; }
+    if (!out) { set_error("avq_get_codes: NULL"); return AVQ_EINVAL; }
+    AVQ_HIP(hipMemcpy(out, idx->codes_logical.p, (size_t)idx->n * idx->NB, hipMemcpyDefault));
+    return AVQ_OK;
+}
+
+extern "C" int avq_get_leaf_assign(avq_index *idx, int32_t *out)
+{
+    AVQ_TRY(check_index(idx));
+    if (idx->n <= 0 || idx->cfg.n_leaves <= 0) { set_error("avq_get_leaf_assign: no partitioned database"); return AVQ_ESTATE; }
+    if (!out) { set_error("avq_get_leaf_assign: NULL"); return AVQ_EINVAL; }
+    AVQ_HIP(hipMemcpy(out, idx->assign.p, sizeof(int32_t) * (size_t)idx->n, hipMemcpyDefault));
+    return AVQ_OK;
+}
+
+// ---- query path ----------------------------------------------------------------------
+
+static int build_tables(avq_index *idx, const float *queries, int nq, int lut_mode, hipStream_t st)
+{
+    const avq_config &c = idx->cfg;
+    const size_t entries = (size_t)nq * c.M * idx->kc;
+    AVQ_TRY(idx->lut.reserve(entries * sizeof(float)));
+    if (lut_mode == AVQ_LUT_U8) {
+        AVQ_TRY(idx->lut8.reserve(entries));
+        AVQ_TRY(idx->scale.reserve(sizeof(float) * (size_t)nq));
+        AVQ_TRY(idx->bias.reserve(sizeof(float) * (size_t)nq));
+    }
+    return launch_lut(queries, nq, idx->codebooks.as<float>(), c.d, c.M, idx->kc, idx->lut.as<float>(),
+                      lut_mode == AVQ_LUT_U8 ? idx->lut8.as<uint8_t>() : nullptr, idx->scale.as<float>(),
+                      idx->bias.as<float>(), st);
+}
+
+static void fill_scan_params(const avq_index *idx, int nq, int R, int ns, ScanParams *p)
+{
+    memset(p, 0, sizeof(*p));
+    p->codes = idx->codes_blocked.as<uint8_t>();
+    p->n_blocks = idx->n_blocks;
+    p->n_valid = (int32_t)idx->n;
+    p->lut = idx->lut.as<float>();
+    p->lut8 = idx->lut8.as<uint8_t>();
+    p->scale = idx->scale.as<float>();
+    p->bias = idx->bias.as<float>();
+    p->B = nq;
+    p->M = idx->cfg.M;
+    p->bits = idx->cfg.bits;
+    p->NB = idx->NB;
+    p->R = R;
+    p->ns = ns;
+}
+
+// Chooses the flat scan's grid: query tiles x chunks of the block range.
+static void plan_flat(const avq_index *idx, const ScanShape &s, int nq, ScanParams *p)
+{
+    p->n_tiles = (nq + s.qt - 1) / s.qt;
+    const int target = idx->tune_target_wgs > 0 ? idx->tune_target_wgs : 1024;
+    int64_t chunks = (target + p->n_tiles - 1) / p->n_tiles;
+    const int64_t max_chunks = std::max<int64_t>(1, idx->n_blocks / s.waves);
+    chunks = std::max<int64_t>(1, std::min(chunks, max_chunks));
+    const int64_t bpc = (idx->n_blocks + chunks - 1) / chunks;
+    p->blocks_per_chunk = (int32_t)bpc;
+    p->n_chunks = (int32_t)((idx->n_blocks + bpc - 1) / bpc);
+}
+
+static int check_query_args(const avq_index *idx, const float *queries, int32_t nq, int32_t lut_mode)
+{
+    if (idx->n <= 0) { set_error("no database yet (avq_encode or avq_set_database first)"); return AVQ_ESTATE; }
+    if (!idx->have_codebooks) { set_error("no dictionaries yet"); return AVQ_ESTATE; }
+    if (!queries || nq < 1) { set_error("queries NULL or nq < 1"); return AVQ_EINVAL; }
+    if (lut_mode != AVQ_LUT_F32 && lut_mode != AVQ_LUT_U8) { set_error("bad lut_mode %d", lut_mode); return AVQ_EINVAL; }
+    return AVQ_OK;
+}
+
+extern "C" int avq_search(avq_index *idx, const float *queries, int32_t nq, int32_t k, int32_t reorder_k,
+                          int32_t lut_mode, int32_t leaves_to_search, int32_t *ids_out, float *scores_out,
+                          void *hip_stream)
+{
+    AVQ_TRY(check_index(idx));
+    AVQ_TRY(check_query_args(idx, queries, nq, lut_mode));
+    hipStream_t st = (hipStream_t)hip_stream;
+    const avq_config &c = idx->cfg;
+    const bool ivf = c.n_leaves > 0;
+    if (!ids_out || !scores_out) { set_error("avq_search: output pointer is NULL"); return AVQ_EINVAL; }
+    if (k < 1 || k > AVQ_MAX_SELECT || k > idx->n || (reorder_k != 0 && (reorder_k < k || reorder_k > AVQ_MAX_SELECT))) {
+        set_error("avq_search: need 1 <= k <= min(n, %d) and reorder_k == 0 or k <= reorder_k <= %d",
+                  AVQ_MAX_SELECT, AVQ_MAX_SELECT);
+        return AVQ_EINVAL;
+    }
+    if (reorder_k != 0 && !idx->x) { set_error("avq_search: re-scoring needs the datapoints"); return AVQ_ESTATE; }
+    if (ivf && (leaves_to_search < 1 || leaves_to_search > c.n_leaves || leaves_to_search > AVQ_MAX_SELECT)) {
+        set_error("avq_search: leaves_to_search must be in [1, min(n_leaves, %d)]", AVQ_MAX_SELECT);
+        return AVQ_EINVAL;
+    }
+    const int R = reorder_k ? reorder_k : k;
+    const int ns = (R + 63) / 64 <= 2 ? 2 : 8;
+    const int C = 64 * ns;
+    const bool u8 = lut_mode == AVQ_LUT_U8;
+
+    AVQ_TRY(build_tables(idx, queries, nq, lut_mode, st));
+    ScanParams p;
+    fill_scan_params(idx, nq, R, ns, &p);
+    ScanShape shape;
+    AVQ_TRY(scan_pick_shape(idx->NB, u8, ns, nq, ivf, idx->tune_qt, idx->tune_waves, &shape));
+    if (ivf) {
+        const int L = leaves_to_search;
+        AVQ_TRY(idx->leaf_ids.reserve(sizeof(int32_t) * (size_t)nq * L));
+        AVQ_TRY(idx->leaf_ip.reserve(sizeof(float) * (size_t)nq * L));
+        AVQ_TRY(launch_leaf_select(idx->centers_t.as<float>(), c.n_leaves, c.d, queries, nq, L,
+                                   idx->leaf_ids.as<int32_t>(), idx->leaf_ip.as<float>(), st));
+        p.perm = idx->perm.as<int32_t>();
+        p.leaf_ids = idx->leaf_ids.as<int32_t>();
+        p.leaf_ip = idx->leaf_ip.as<float>();
+        p.leaf_blk = idx->leaf_blk.as<int32_t>();
+        p.Lp = L;
+        p.n_tiles = nq;
+        p.n_chunks = 1;
+    } else {
+        plan_flat(idx, shape, nq, &p);
+    }
+    AVQ_TRY(idx->partial.reserve(sizeof(u64) * (size_t)p.n_tiles * shape.qt * p.n_chunks * C));
+    p.partial = idx->partial.as<u64>();
+    AVQ_TRY(launch_scan(p, u8, ivf, shape, st));
+    const u64 *cand = p.partial;
+    if (p.n_chunks > 1) {
+        AVQ_TRY(idx->cand.reserve(sizeof(u64) * (size_t)nq * C));
+        AVQ_TRY(launch_merge_partials(p.partial, nq, p.n_chunks, ns, idx->cand.as<u64>(), st));
+        cand = idx->cand.as<u64>();
+    }
+    const int key_kind = (u8 && !ivf) ? 1 : 0;
+    return launch_finalize(cand, ns, nq, R, k, reorder_k != 0, key_kind, idx->x, c.d, queries,
+                           idx->scale.as<float>(), idx->bias.as<float>(), ids_out, scores_out, st);
+}
+
+extern "C" int avq_brute_force(avq_index *idx, const float *queries, int32_t nq, int32_t k,
+                               int32_t *ids_out, float *scores_out, void *hip_stream)
+{
+    AVQ_TRY(check_index(idx));
+    if (idx->n <= 0 || !idx->x) { set_error("avq_brute_force: no datapoints stored"); return AVQ_ESTATE; }
+    if (!queries || nq < 1 || !ids_out || !scores_out || k < 1 || k > AVQ_MAX_SELECT || k > idx->n) {
+        set_error("avq_brute_force: bad argument");
+        return AVQ_EINVAL;
+    }
+    hipStream_t st = (hipStream_t)hip_stream;
+    const int ns = (k + 63) / 64;
+    const int chunks = brute_force_chunks(idx->n, nq);
+    AVQ_TRY(idx->partial.reserve(sizeof(u64) * (size_t)nq * chunks * 64 * ns));
+    AVQ_TRY(idx->cand.reserve(sizeof(u64) * (size_t)nq * 64 * ns));
+    return launch_brute_force(idx->x, idx->n, idx->cfg.d, queries, nq, k, idx->partial.as<u64>(), chunks,
+                              idx->cand.as<u64>(), ids_out, scores_out, st);
+}
+
+// ---- stage-level inspection -------------------------------------------------------------
+
+extern "C" int avq_debug_lut(avq_index *idx, const float *queries, int32_t nq, int32_t lut_mode,
+                             void *lut_out, float *scale_out, float *bias_out, void *hip_stream)
+{
+    AVQ_TRY(check_index(idx));
+    if (!idx->have_codebooks) { set_error("avq_debug_lut: no dictionaries yet"); return AVQ_ESTATE; }
+    if (!queries || nq < 1 || !lut_out) { set_error("avq_debug_lut: bad argument"); return AVQ_EINVAL; }
+    if (lut_mode != AVQ_LUT_F32 && lut_mode != AVQ_LUT_U8) { set_error("bad lut_mode"); return AVQ_EINVAL; }
+    if (lut_mode == AVQ_LUT_U8 && (!scale_out || !bias_out)) { set_error("avq_debug_lut: scale/bias NULL"); return AVQ_EINVAL; }
+    hipStream_t st = (hipStream_t)hip_stream;
+    const avq_config &c = idx->cfg;
+    if (lut_mode == AVQ_LUT_F32)
+        return launch_lut(queries, nq, idx->codebooks.as<float>(), c.d, c.M, idx->kc, (float *)lut_out, nullptr,
+                          nullptr, nullptr, st);
+    return launch_lut(queries, nq, idx->codebooks.as<float>(), c.d, c.M, idx->kc, nullptr, (uint8_t *)lut_out,
+                      scale_out, bias_out, st);
+}
+
+extern "C" int avq_debug_adc_scores(avq_index *idx, const float *queries, int32_t nq, int32_t lut_mode,
+                                    void *scores_out, void *hip_stream)
+{
+    AVQ_TRY(check_index(idx));
+    AVQ_TRY(check_query_args(idx, queries, nq, lut_mode));
+    if (idx->cfg.n_leaves > 0) { set_error("avq_debug_adc_scores: flat index only"); return AVQ_ESTATE; }
+    if (!scores_out) { set_error("avq_debug_adc_scores: NULL output"); return AVQ_EINVAL; }
+    hipStream_t st = (hipStream_t)hip_stream;
+    const bool u8 = lut_mode == AVQ_LUT_U8;
+    AVQ_TRY(build_tables(idx, queries, nq, lut_mode, st));
+    ScanParams p;
+    fill_scan_params(idx, nq, 1, 2, &p);
+    ScanShape shape;
+    AVQ_TRY(scan_pick_shape(idx->NB, u8, 2, nq, false, idx->tune_qt, idx->tune_waves, &shape));
+    plan_flat(idx, shape, nq, &p);
+    p.scores_out = scores_out;
+    p.score_stride = idx->n;
+    AVQ_TRY(idx->partial.reserve(64));
+    p.partial = idx->partial.as<u64>();
+    return launch_scan(p, u8, false, shape, st);
+}
+
+extern "C" int avq_debug_leaf_select(avq_index *idx, const float *queries, int32_t nq, int32_t L,
+                                     int32_t *leaf_ids_out, float *leaf_ip_out, void *hip_stream)
+{
+    AVQ_TRY(check_index(idx));
+    const avq_config &c = idx->cfg;
+    if (c.n_leaves <= 0 || !idx->have_centers) { set_error("avq_debug_leaf_select: no leaf centers"); return AVQ_ESTATE; }
+    if (!queries || nq < 1 || !leaf_ids_out || !leaf_ip_out || L < 1 || L > c.n_leaves || L > AVQ_MAX_SELECT) {
+        set_error("avq_debug_leaf_select: bad argument");
+        return AVQ_EINVAL;
+    }
+    return launch_leaf_select(idx->centers_t.as<float>(), c.n_leaves, c.d, queries, nq, L, leaf_ids_out,
+                              leaf_ip_out, (hipStream_t)hip_stream);
+}

@@ -1,0 +1,339 @@
+// Dictionary learning and encoding.
+//
+// Dictionaries: Lloyd's algorithm under the l2 loss, per subspace (paper
+// Section 4: the k-means objective; Section 5.1 learns the dictionary this way
+// and then assigns codes under the anisotropic loss; Section 4.1 names it as the
+// initialisation). Encoding: the partition-assignment step of Section 4.1 under
+// the loss eta*||r_par||^2 + ||r_perp||^2 of Section 3.2.
+//
+// All arithmetic here is fp64: the results are arg-mins, and they have to agree
+// with a plain reference evaluation except at exact ties.
+#include "avq_internal.h"
+
+namespace avq {
+
+// ---- eta (Section 3.2, Theorem 3.4) --------------------------------------------
+
+__host__ __device__ inline double clamp_ratio_sq(double T, double norm)
+{
+    const double r = T / norm;
+    const double u = r * r;
+    return u > 0.999 ? 0.999 : u;
+}
+
+// int_0^alpha sin^d by composite Simpson (smooth integrand, fixed fine grid).
+__host__ __device__ inline double sin_power_integral(int d, double alpha)
+{
+    const int N = 8192;
+    const double h = alpha / N;
+    double s = (d == 0 ? 2.0 : pow(sin(alpha), (double)d));
+    for (int i = 1; i < N; ++i) {
+        const double f = d == 0 ? 1.0 : pow(sin(i * h), (double)d);
+        s += (i & 1) ? 4.0 * f : 2.0 * f;
+    }
+    return s * h / 3.0;
+}
+
+__host__ __device__ inline double eta_of_norm(int d, double T, double norm, int mode, double eta_explicit)
+{
+    if (mode == AVQ_ETA_EXPLICIT) return eta_explicit;
+    if (!(norm > 0.0) || d < 2) return 1.0;
+    const double u = clamp_ratio_sq(T, norm);
+    if (mode == AVQ_ETA_EXACT) {
+        // eta = h_par / h_perp = (d-1) (I_{d-2} / I_d - 1), I_d = int_0^alpha sin^d,
+        // alpha = arccos(T / ||x||)
+        const double alpha = acos(sqrt(u));
+        return (double)(d - 1) * (sin_power_integral(d - 2, alpha) / sin_power_integral(d, alpha) - 1.0);
+    }
+    // the limit of Theorem 3.4 as a proxy, floored at 1 (Theorem 3.3: h_par >= h_perp)
+    const double eta = (double)(d - 1) * u / (1.0 - u);
+    return eta < 1.0 ? 1.0 : eta;
+}
+
+double eta_host(int d, double T, double norm, int mode) { return eta_of_norm(d, T, norm, mode, 1.0); }
+
+// ---- k-means ----------------------------------------------------------------------
+
+static inline uint64_t mix64(uint64_t z)
+{
+    // splitmix64 output function
+    z += 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+// Stratified draw of the initial codewords: index of codeword j among n rows.
+static int64_t init_index(uint64_t seed, uint32_t stream_id, int j, int k, int64_t n)
+{
+    const int64_t lo = (int64_t)(((__int128)j * n) / k);
+    const int64_t hi = (int64_t)(((__int128)(j + 1) * n) / k);
+    const uint64_t h = mix64(seed ^ mix64(((uint64_t)stream_id << 32) | (uint32_t)j));
+    return lo + (int64_t)(h % (uint64_t)(hi - lo));
+}
+
+__device__ __forceinline__ double sub_value(const float *__restrict__ x, int64_t i, int ld, int col,
+                                            const float *__restrict__ rc, const int32_t *__restrict__ ra)
+{
+    double v = (double)x[(size_t)i * ld + col];
+    if (rc) v -= (double)rc[(size_t)ra[i] * ld + col];
+    return v;
+}
+
+__global__ void init_centers_kernel(const float *__restrict__ x, int ld, int col0, int dim, int k,
+                                    const int64_t *__restrict__ idx, const float *__restrict__ rc,
+                                    const int32_t *__restrict__ ra, float *__restrict__ centers)
+{
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= k * dim) return;
+    const int j = t / dim, l = t % dim;
+    centers[t] = (float)sub_value(x, idx[j], ld, col0 + l, rc, ra);
+}
+
+// One thread per point: nearest center in fp64 squared l2 (lowest index on
+// ties); the point's values are staged in LDS, transposed, so the inner loop
+// reads them conflict-free; every lane reads the same center value.
+// ACCUM: add the point into sums/counts; else write the assignment.
+// ACCUM with k*dim <= kLdsAccMax: sums are first added up per workgroup in LDS.
+constexpr int kLdsAccMax = 4096;
+
+template <bool ACCUM>
+__global__ void __launch_bounds__(256)
+nearest_kernel(const float *__restrict__ x, int64_t n, int ld, int col0, int dim, int k,
+               const float *__restrict__ rc, const int32_t *__restrict__ ra,
+               const float *__restrict__ centers, double *__restrict__ sums,
+               unsigned long long *__restrict__ counts, int32_t *__restrict__ assign)
+{
+    extern __shared__ double xs[]; // [dim][blockDim.x], then (ACCUM, small k*dim) [k*dim] + [k]
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const bool valid = i < n;
+    const int bs = blockDim.x;
+    const bool lds_acc = ACCUM && k * dim <= kLdsAccMax;
+    double *lsum = xs + (size_t)dim * bs;
+    unsigned long long *lcnt = (unsigned long long *)(lsum + k * dim);
+    if (lds_acc) {
+        for (int t = threadIdx.x; t < k * dim; t += bs) lsum[t] = 0.0;
+        for (int t = threadIdx.x; t < k; t += bs) lcnt[t] = 0ull;
+        __syncthreads();
+    }
+    for (int l = 0; l < dim; ++l) xs[l * bs + threadIdx.x] = valid ? sub_value(x, i, ld, col0 + l, rc, ra) : 0.0;
+    int best = 0;
+    double bestd = INFINITY;
+    for (int j = 0; j < k; ++j) {
+        const float *c = centers + (size_t)j * dim;
+        double dd = 0.0;
+        for (int l = 0; l < dim; ++l) {
+            const double t = xs[l * bs + threadIdx.x] - (double)c[l];
+            dd += t * t;
+        }
+        if (dd < bestd) { bestd = dd; best = j; }
+    }
+    if (lds_acc) {
+        if (valid) {
+            for (int l = 0; l < dim; ++l) atomicAdd(&lsum[best * dim + l], xs[l * bs + threadIdx.x]);
+            atomicAdd(&lcnt[best], 1ull);
+        }
+        __syncthreads();
+        for (int t = threadIdx.x; t < k; t += bs) {
+            if (lcnt[t] == 0ull) continue;
+            atomicAdd(&counts[t], lcnt[t]);
+            for (int l = 0; l < dim; ++l) atomicAdd(&sums[(size_t)t * dim + l], lsum[t * dim + l]);
+        }
+        return;
+    }
+    if (!valid) return;
+    if (ACCUM) {
+        for (int l = 0; l < dim; ++l) atomicAdd(&sums[(size_t)best * dim + l], xs[l * bs + threadIdx.x]);
+        atomicAdd(&counts[best], 1ull);
+    } else {
+        assign[i] = best;
+    }
+}
+
+__global__ void update_centers_kernel(const double *__restrict__ sums,
+                                      const unsigned long long *__restrict__ counts, int k, int dim,
+                                      float *__restrict__ centers)
+{
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= k * dim) return;
+    const unsigned long long c = counts[t / dim];
+    if (c > 0) centers[t] = (float)(sums[t] / (double)c); // an empty cluster keeps its center
+}
+
+static int nearest_block_size(int dim)
+{
+    int bs = 256;
+    while (bs > 64 && (size_t)bs * dim * sizeof(double) > 120 * 1024) bs /= 2;
+    return bs;
+}
+
+int kmeans_device(const float *x, int64_t n, int ld, int col0, int dim, int k, int iters,
+                  uint64_t seed, uint32_t stream_id, const float *resid_centers,
+                  const int32_t *resid_assign, float *centers, hipStream_t st)
+{
+    if (n < k) { set_error("k-means: %lld points for %d centers", (long long)n, k); return AVQ_EINVAL; }
+    const int bs = nearest_block_size(dim);
+    if ((size_t)bs * dim * sizeof(double) > 150 * 1024) {
+        set_error("k-means: dimension %d too large", dim);
+        return AVQ_EINVAL;
+    }
+    std::vector<int64_t> idx(k);
+    for (int j = 0; j < k; ++j) idx[j] = init_index(seed, stream_id, j, k, n);
+    int64_t *idx_dev = nullptr;
+    double *sums = nullptr;
+    unsigned long long *counts = nullptr;
+    AVQ_HIP(hipMalloc(&idx_dev, sizeof(int64_t) * k));
+    AVQ_HIP(hipMalloc(&sums, sizeof(double) * (size_t)k * dim));
+    AVQ_HIP(hipMalloc(&counts, sizeof(unsigned long long) * k));
+    int rc = AVQ_OK;
+    auto body = [&]() -> int {
+        AVQ_HIP(hipMemcpyAsync(idx_dev, idx.data(), sizeof(int64_t) * k, hipMemcpyHostToDevice, st));
+        hipLaunchKernelGGL(init_centers_kernel, dim3((k * dim + 255) / 256), dim3(256), 0, st, x, ld,
+                           col0, dim, k, idx_dev, resid_centers, resid_assign, centers);
+        AVQ_HIP(hipGetLastError());
+        AVQ_HIP(hipFuncSetAttribute((const void *)nearest_kernel<true>,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+        const unsigned grid = (unsigned)((n + bs - 1) / bs);
+        for (int it = 0; it < iters; ++it) {
+            AVQ_HIP(hipMemsetAsync(sums, 0, sizeof(double) * (size_t)k * dim, st));
+            AVQ_HIP(hipMemsetAsync(counts, 0, sizeof(unsigned long long) * k, st));
+            const size_t lds = (size_t)bs * dim * sizeof(double) +
+                               (k * dim <= kLdsAccMax ? (size_t)(k * dim + k) * sizeof(double) : 0);
+            hipLaunchKernelGGL(nearest_kernel<true>, dim3(grid), dim3(bs), lds,
+                               st, x, n, ld, col0, dim, k, resid_centers, resid_assign, centers, sums,
+                               counts, (int32_t *)nullptr);
+            AVQ_HIP(hipGetLastError());
+            hipLaunchKernelGGL(update_centers_kernel, dim3((k * dim + 255) / 256), dim3(256), 0, st, sums,
+                               counts, k, dim, centers);
+            AVQ_HIP(hipGetLastError());
+        }
+        AVQ_HIP(hipStreamSynchronize(st));
+        return AVQ_OK;
+    };
+    rc = body();
+    (void)hipFree(idx_dev);
+    (void)hipFree(sums);
+    (void)hipFree(counts);
+    return rc;
+}
+
+int launch_assign_nearest(const float *x, int64_t n, int d, const float *centers, int k,
+                          int32_t *assign, hipStream_t st)
+{
+    const int bs = nearest_block_size(d);
+    if ((size_t)bs * d * sizeof(double) > 150 * 1024) {
+        set_error("assign: dimension %d too large", d);
+        return AVQ_EINVAL;
+    }
+    AVQ_HIP(hipFuncSetAttribute((const void *)nearest_kernel<false>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+    hipLaunchKernelGGL(nearest_kernel<false>, dim3((unsigned)((n + bs - 1) / bs)), dim3(bs),
+                       (size_t)bs * d * sizeof(double), st, x, n, d, 0, d, k, (const float *)nullptr,
+                       (const int32_t *)nullptr, centers, (double *)nullptr,
+                       (unsigned long long *)nullptr, assign);
+    AVQ_HIP(hipGetLastError());
+    return AVQ_OK;
+}
+
+// ---- encoding under the anisotropic loss ------------------------------------------
+
+constexpr int kMaxM = 256;
+
+// One thread per point. With r = x - x~, p = <r, x>, e = ||r||^2:
+// ||r_par||^2 = p^2/||x||^2 and ||r_perp||^2 = e - p^2/||x||^2, so the loss is
+// e + (eta - 1) p^2 / ||x||^2. p and e are sums over subspaces; changing the
+// codeword of subspace m only changes that subspace's terms.
+__global__ void __launch_bounds__(128)
+encode_kernel(const float *__restrict__ x, int64_t n, int d, int M, int kc, int bits,
+              const float *__restrict__ codebooks, const float *__restrict__ leaf_centers,
+              const int32_t *__restrict__ leaf_assign, int eta_mode, double T, double eta_explicit,
+              int passes, uint8_t *__restrict__ packed)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const int ds = d / M;
+    const float *xi = x + (size_t)i * d;
+    const float *ce = leaf_centers ? leaf_centers + (size_t)leaf_assign[i] * d : nullptr;
+    uint8_t code[kMaxM];
+
+    double nx2 = 0.0;
+    for (int l = 0; l < d; ++l) nx2 += (double)xi[l] * (double)xi[l];
+    const double eta = eta_of_norm(d, T, sqrt(nx2), eta_mode, eta_explicit);
+    const double w = nx2 > 0.0 ? (eta - 1.0) / nx2 : 0.0;
+
+    // terms of subspace m for codeword j: pm = <r^(m), x^(m)>, em = ||r^(m)||^2
+    auto terms = [&](int m, int j, double &pm, double &em) {
+        const float *c = codebooks + ((size_t)m * kc + j) * ds;
+        pm = 0.0;
+        em = 0.0;
+        for (int l = 0; l < ds; ++l) {
+            const double xv = (double)xi[m * ds + l];
+            const double r = (xv - (ce ? (double)ce[m * ds + l] : 0.0)) - (double)c[l];
+            pm += r * xv;
+            em += r * r;
+        }
+    };
+
+    // start: l2-nearest codeword of the (residual) sub-vector in every subspace
+    for (int m = 0; m < M; ++m) {
+        int best = 0;
+        double bestd = INFINITY;
+        for (int j = 0; j < kc; ++j) {
+            double pm, em;
+            terms(m, j, pm, em);
+            if (em < bestd) { bestd = em; best = j; }
+        }
+        code[m] = (uint8_t)best;
+    }
+    for (int pass = 0; pass < passes; ++pass) {
+        bool changed = false;
+        for (int m = 0; m < M; ++m) {
+            // p and e of the other subspaces, recomputed from scratch to avoid drift
+            double Pr = 0.0, Er = 0.0;
+            for (int m2 = 0; m2 < M; ++m2) {
+                if (m2 == m) continue;
+                double pm, em;
+                terms(m2, code[m2], pm, em);
+                Pr += pm;
+                Er += em;
+            }
+            int best = 0;
+            double bestv = INFINITY;
+            for (int j = 0; j < kc; ++j) {
+                double pm, em;
+                terms(m, j, pm, em);
+                const double p = Pr + pm, e = Er + em;
+                const double v = e + w * p * p;
+                if (v < bestv) { bestv = v; best = j; }
+            }
+            if (best != code[m]) { code[m] = (uint8_t)best; changed = true; }
+        }
+        if (!changed) break;
+    }
+    const int NB = (M * bits + 7) / 8;
+    uint8_t *out = packed + (size_t)i * NB;
+    if (bits == 8) {
+        for (int m = 0; m < M; ++m) out[m] = code[m];
+    } else {
+        for (int b = 0; b < NB; ++b) {
+            uint8_t v = code[2 * b] & 15;
+            if (2 * b + 1 < M) v |= (uint8_t)((code[2 * b + 1] & 15) << 4);
+            out[b] = v;
+        }
+    }
+}
+
+int launch_encode(const float *x, int64_t n, int d, int M, int kc, int bits,
+                  const float *codebooks, const float *leaf_centers, const int32_t *leaf_assign,
+                  int eta_mode, double T, double eta_explicit, int passes, uint8_t *packed,
+                  hipStream_t st)
+{
+    if (M > kMaxM) { set_error("encode: M = %d exceeds %d", M, kMaxM); return AVQ_EINVAL; }
+    hipLaunchKernelGGL(encode_kernel, dim3((unsigned)((n + 127) / 128)), dim3(128), 0, st, x, n, d, M, kc,
+                       bits, codebooks, leaf_centers, leaf_assign, eta_mode, T, eta_explicit, passes,
+                       packed);
+    AVQ_HIP(hipGetLastError());
+    return AVQ_OK;
+}
+
+} // namespace avq

@@ -1,0 +1,352 @@
+"""GPU parity: every stage of the HIP path against the CPU oracle, element by
+element, on the same seeded inputs. All calls go through the C ABI (via the
+ctypes binding). Bars: integer / index / byte results bit-exact; the fp32 path
+follows the oracle's operation order, so it is held to exact equality too
+(tighter than the 1e-5 relative tolerance the target states), and the
+tolerance is asserted separately so a regression shows which bar broke.
+"""
+import numpy as np
+import pytest
+
+import oracle
+import synth_inputs as si
+from util import unit_rows, unpack_codes
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+avq = pytest.importorskip("paper_1908_10396_amd")
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def make_case(seed, n, d, M, bits, nq, train_iters=4, n_train=None):
+    """Synthetic unit-norm data, oracle-trained dictionaries and oracle codes."""
+    rng = np.random.default_rng(seed)
+    x = unit_rows(rng, n, d)
+    q = unit_rows(rng, nq, d)
+    kc = 1 << bits
+    nt = min(n, n_train or 4000)
+    cb = oracle.train_pq(x[:max(nt, kc)], M, kc, train_iters, seed=seed)
+    codes = oracle.encode(x, cb, T=0.2, passes=3)
+    return dict(x=x, q=q, cb=cb, codes=codes, n=n, d=d, M=M, bits=bits, kc=kc)
+
+
+def make_index(case, **kw):
+    idx = avq.Index(case["d"], case["M"], case["bits"], T=0.2, **kw)
+    idx.set_codebooks(case["cb"])
+    xd = dev(case["x"])
+    idx.set_database(xd, oracle.pack_codes(case["codes"], case["bits"]))
+    return idx, xd
+
+
+CASES = {
+    # name: (n, d, M, bits, nq)  -- several 256-point blocks plus a ragged tail
+    "tiny_nb8": (10_000, 32, 16, 4, 100),
+    "glove_nb25": (6_011, 100, 50, 4, 37),
+    "large4_nb32": (3_333, 128, 64, 4, 21),
+    "large8_nb32": (2_500, 256, 32, 8, 19),
+    "generic_nb7": (1_999, 28, 14, 4, 9),
+    "odd_m_nb4": (1_030, 21, 7, 4, 5),
+    "bits8_nb3": (777, 12, 3, 8, 6),
+}
+
+
+@pytest.fixture(scope="module", params=list(CASES))
+def case(request):
+    n, d, M, bits, nq = CASES[request.param]
+    c = make_case(100 + list(CASES).index(request.param), n, d, M, bits, nq)
+    c["name"] = request.param
+    return c
+
+
+def test_lut_tables_match(case):
+    idx, _ = make_index(case)
+    qd = dev(case["q"])
+    L = idx.debug_lut(qd, avq.LUT_F32).cpu().numpy()
+    Q8, scale, bias = (t.cpu().numpy() for t in idx.debug_lut(qd, avq.LUT_U8))
+    for qi in range(case["q"].shape[0]):
+        Lo = oracle.lut_f32(case["q"][qi], case["cb"])
+        np.testing.assert_array_equal(L[qi], Lo)
+        Qo, so, bo = oracle.lut_u8(Lo)
+        np.testing.assert_array_equal(Q8[qi], Qo)
+        assert scale[qi] == so and bias[qi] == bo
+
+
+@pytest.mark.parametrize("nq", [1, 3, None])
+def test_adc_scores_match(case, nq):
+    # nq = 1, 3: one query per workgroup; None: the full batch (query-tiled kernels)
+    idx, _ = make_index(case)
+    q = case["q"] if nq is None else case["q"][:nq]
+    qd = dev(q)
+    sf = idx.debug_adc_scores(qd, avq.LUT_F32).cpu().numpy()
+    su = idx.debug_adc_scores(qd, avq.LUT_U8).cpu().numpy()
+    for qi in range(q.shape[0]):
+        kf, _, _ = oracle.adc_keys_flat(q[qi], case["cb"], case["codes"], case["bits"], 0)
+        np.testing.assert_allclose(sf[qi], kf, rtol=1e-5, atol=1e-6)     # the stated tolerance
+        np.testing.assert_array_equal(sf[qi], kf)                         # same operation order
+        ku, _, _ = oracle.adc_keys_flat(q[qi], case["cb"], case["codes"], case["bits"], 1)
+        np.testing.assert_array_equal(su[qi], ku.astype(np.int32))
+
+
+@pytest.mark.parametrize("lut_mode", [0, 1])
+@pytest.mark.parametrize("k,R", [(10, 0), (10, 100), (1, 1), (64, 128)])
+def test_search_matches(case, lut_mode, k, R):
+    idx, xd = make_index(case)
+    qd = dev(case["q"])
+    ids, sc = idx.search(qd, k, R, lut_mode)
+    oi, os_ = oracle.search(case["x"], case["cb"], case["codes"], case["bits"], case["q"], k, R, lut_mode)
+    np.testing.assert_array_equal(ids.cpu().numpy(), oi)
+    np.testing.assert_allclose(sc.cpu().numpy(), os_, rtol=1e-5, atol=1e-6)
+    np.testing.assert_array_equal(sc.cpu().numpy(), os_)
+    # single-query calls take the one-query-per-workgroup path
+    ids1, sc1 = idx.search(qd[:1].contiguous(), k, R, lut_mode)
+    np.testing.assert_array_equal(ids1.cpu().numpy(), oi[:1])
+    np.testing.assert_array_equal(sc1.cpu().numpy(), os_[:1])
+
+
+def test_search_is_deterministic_and_independent_of_launch_shape(case):
+    idx, xd = make_index(case)
+    qd = dev(case["q"])
+    base = [t.cpu().numpy() for t in idx.search(qd, 10, 100, 0)]
+    again = [t.cpu().numpy() for t in idx.search(qd, 10, 100, 0)]
+    np.testing.assert_array_equal(base[0], again[0])
+    np.testing.assert_array_equal(base[1], again[1])
+    for name, val in (("scan_target_wgs", 64), ("scan_target_wgs", 4096), ("scan_waves", 2), ("scan_qt", 1)):
+        idx.set_tuning(name, val)
+        got = [t.cpu().numpy() for t in idx.search(qd, 10, 100, 0)]
+        np.testing.assert_array_equal(base[0], got[0])
+        np.testing.assert_array_equal(base[1], got[1])
+        idx.set_tuning(name, 0)
+
+
+def test_brute_force_matches(case):
+    idx, xd = make_index(case)
+    qd = dev(case["q"])
+    for k in (1, 10, 100):
+        ids, sc = idx.brute_force(qd, k)
+        oi, os_ = oracle.brute_force(case["x"], case["q"], k)
+        np.testing.assert_array_equal(ids.cpu().numpy(), oi)
+        np.testing.assert_array_equal(sc.cpu().numpy(), os_)
+
+
+def test_large_reorder_512():
+    c = make_case(77, 5_000, 32, 16, 4, 12)
+    idx, xd = make_index(c)
+    qd = dev(c["q"])
+    for lut_mode in (0, 1):
+        for k, R in ((100, 500), (512, 512), (300, 0)):
+            ids, sc = idx.search(qd, k, R, lut_mode)
+            oi, os_ = oracle.search(c["x"], c["cb"], c["codes"], 4, c["q"], k, R, lut_mode)
+            np.testing.assert_array_equal(ids.cpu().numpy(), oi)
+            np.testing.assert_array_equal(sc.cpu().numpy(), os_)
+
+
+def test_degenerate_inputs():
+    # fewer points than one block; k == n; duplicate points and an all-zero query give
+    # massive ties that must break by lower id
+    rng = np.random.default_rng(5)
+    n, d, M, bits = 50, 16, 8, 4
+    x = unit_rows(rng, n, d)
+    x[10:20] = x[3]                      # duplicates
+    cb = oracle.train_pq(x, M, 16, 3, seed=1)
+    codes = oracle.encode(x, cb, T=0.2)
+    q = unit_rows(rng, 4, d)
+    q[1] = 0.0                           # every score equal
+    idx = avq.Index(d, M, bits)
+    idx.set_codebooks(cb)
+    xd = dev(x)
+    idx.set_database(xd, oracle.pack_codes(codes, bits))
+    qd = dev(q)
+    for lut_mode in (0, 1):
+        for k, R in ((50, 50), (10, 0), (7, 20), (50, 0)):
+            ids, sc = idx.search(qd, k, R, lut_mode)
+            oi, os_ = oracle.search(x, cb, codes, bits, q, k, R, lut_mode)
+            np.testing.assert_array_equal(ids.cpu().numpy(), oi)
+            np.testing.assert_array_equal(sc.cpu().numpy(), os_)
+    # one point
+    idx1 = avq.Index(d, M, bits)
+    idx1.set_codebooks(cb)
+    x1 = dev(x[:1])
+    idx1.set_database(x1, oracle.pack_codes(codes[:1], bits))
+    ids, sc = idx1.search(qd, 1, 1, 0)
+    assert ids.cpu().numpy().tolist() == [[0]] * 4
+
+
+def test_error_paths():
+    rng = np.random.default_rng(6)
+    idx = avq.Index(16, 8, 4)
+    q = dev(unit_rows(rng, 2, 16))
+    with pytest.raises(avq.AvqError) as e:
+        idx.search(q, 1, 0)
+    assert e.value.code == avq.AVQ_ESTATE
+    x = unit_rows(rng, 300, 16)
+    with pytest.raises(avq.AvqError) as e:
+        idx.encode(dev(x))
+    assert e.value.code == avq.AVQ_ESTATE           # no dictionaries yet
+    idx.train(dev(x))
+    idx.encode(dev(x))
+    for k, R in ((0, 0), (10, 5), (513, 0), (10, 600), (301, 0)):
+        with pytest.raises(avq.AvqError) as e:
+            idx.search(q, k, R)
+        assert e.value.code == avq.AVQ_EINVAL
+    with pytest.raises(avq.AvqError):
+        idx.search(q, 1, 0, lut_mode=2)
+    with pytest.raises(avq.AvqError):
+        idx.train(dev(x[:8]))                        # fewer rows than codewords
+
+
+# ---- training and encoding ---------------------------------------------------------
+
+@pytest.mark.parametrize("name", ["tiny_nb8", "glove_nb25", "large8_nb32", "odd_m_nb4"])
+def test_encode_matches(name):
+    n, d, M, bits, nq = CASES[name]
+    n = min(n, 3000)
+    c = make_case(11, n, d, M, bits, 2)
+    idx = avq.Index(d, M, bits, T=0.2, encode_passes=3)
+    idx.set_codebooks(c["cb"])
+    idx.encode(dev(c["x"]))
+    got = unpack_codes(idx.get_codes(), M, bits)
+    want = c["codes"]
+    mism = np.any(got != want, axis=1)
+    # fp64 on both sides: codes differ only at (near-)exact ties of the loss
+    assert mism.mean() <= 1e-3
+    if mism.any():
+        eta = oracle.eta_limit(d, 0.2)
+        xt_g = oracle.reconstruct(got[mism], c["cb"])
+        xt_w = oracle.reconstruct(want[mism], c["cb"])
+        for xi, a, b in zip(c["x"][mism], xt_g, xt_w):
+            assert oracle.aniso_loss(xi, a, eta) == pytest.approx(oracle.aniso_loss(xi, b, eta), rel=1e-9)
+
+
+def test_encode_eta_modes_and_norms():
+    # varying norms: eta is taken per point; explicit eta = 1 is plain nearest codeword
+    rng = np.random.default_rng(12)
+    n, d, M, bits = 1500, 32, 16, 4
+    x = unit_rows(rng, n, d) * np.exp(0.25 * rng.standard_normal((n, 1))).astype(np.float32)
+    cb = oracle.train_pq(x, M, 16, 4, seed=2)
+    for mode, kw in ((avq.ETA_LIMIT, {}), (avq.ETA_EXPLICIT, dict(eta_explicit=1.0)),
+                     (avq.ETA_EXPLICIT, dict(eta_explicit=6.5)), (avq.ETA_EXACT, {})):
+        idx = avq.Index(d, M, bits, T=0.2, eta_mode=mode, encode_passes=4, **kw)
+        idx.set_codebooks(cb)
+        nn = 200 if mode == avq.ETA_EXACT else n
+        idx.encode(dev(x[:nn]))
+        got = unpack_codes(idx.get_codes(), M, bits)
+        want = oracle.encode(x[:nn], cb, T=0.2, eta_mode=mode, eta_explicit=kw.get("eta_explicit", 1.0), passes=4)
+        assert np.mean(np.any(got != want, axis=1)) <= 2e-3
+
+
+def test_train_matches():
+    rng = np.random.default_rng(13)
+    n, d, M, bits = 5000, 32, 16, 4
+    x = unit_rows(rng, n, d)
+    idx = avq.Index(d, M, bits, kmeans_iters=6, seed=9)
+    idx.train(dev(x))
+    got = idx.get_codebooks()
+    want = oracle.train_pq(x, M, 16, 6, seed=9)
+    np.testing.assert_allclose(got, want, rtol=0, atol=1e-6)
+    # 8-bit dictionaries, wider subspaces
+    idx = avq.Index(32, 4, 8, kmeans_iters=3, seed=3)
+    idx.train(dev(x))
+    np.testing.assert_allclose(idx.get_codebooks(), oracle.train_pq(x, 4, 256, 3, seed=3), rtol=0, atol=1e-6)
+
+
+# ---- partitioned index --------------------------------------------------------------
+
+def make_ivf_case(seed, n, d, M, bits, nq, n_leaves):
+    rng = np.random.default_rng(seed)
+    cfg = dict(si.CONFIGS["glove"])
+    centers_mix = si.mixture_centers(40, d, seed)
+    x = si.mixture(n, d, 40, 0.3, seed, centers=centers_mix)
+    q = si.mixture(nq, d, 40, 0.3, seed, stream=si.STREAM_QUERIES, centers=centers_mix)
+    centers = oracle.kmeans(x[:4000], n_leaves, iters=4, seed=seed)
+    assign = oracle.assign_nearest(x, centers)
+    cb = oracle.train_pq(x[:4000], M, 1 << bits, 4, seed, leaf_centers=centers, leaf_assign=assign[:4000])
+    codes = oracle.encode(x, cb, T=0.2, passes=3, leaf_centers=centers, leaf_assign=assign)
+    return dict(x=x, q=q, cb=cb, codes=codes, centers=centers, assign=assign, d=d, M=M, bits=bits,
+                n_leaves=n_leaves)
+
+
+@pytest.fixture(scope="module")
+def ivf_case():
+    return make_ivf_case(31, 9_001, 100, 50, 4, 33, 37)
+
+
+def make_ivf_index(c):
+    idx = avq.Index(c["d"], c["M"], c["bits"], n_leaves=c["n_leaves"])
+    idx.set_codebooks(c["cb"])
+    idx.set_leaf_centers(c["centers"])
+    xd = dev(c["x"])
+    idx.set_database(xd, oracle.pack_codes(c["codes"], c["bits"]), c["assign"])
+    return idx, xd
+
+
+def test_leaf_select_matches(ivf_case):
+    c = ivf_case
+    idx, _ = make_ivf_index(c)
+    qd = dev(c["q"])
+    for L in (1, 5, 37):
+        ids, ip = idx.debug_leaf_select(qd, L)
+        for qi in range(c["q"].shape[0]):
+            oi, oip = oracle.leaf_select(c["centers"], c["q"][qi], L)
+            np.testing.assert_array_equal(ids[qi].cpu().numpy(), oi)
+            np.testing.assert_array_equal(ip[qi].cpu().numpy(), oip)
+
+
+@pytest.mark.parametrize("lut_mode", [0, 1])
+@pytest.mark.parametrize("k,R,L", [(10, 100, 5), (10, 0, 5), (20, 60, 37), (10, 100, 1)])
+def test_partitioned_search_matches(ivf_case, lut_mode, k, R, L):
+    c = ivf_case
+    idx, xd = make_ivf_index(c)
+    qd = dev(c["q"])
+    ids, sc = idx.search(qd, k, R, lut_mode, leaves_to_search=L)
+    oi, os_ = oracle.search(c["x"], c["cb"], c["codes"], c["bits"], c["q"], k, R, lut_mode,
+                            centers=c["centers"], assign=c["assign"], leaves_to_search=L)
+    np.testing.assert_array_equal(ids.cpu().numpy(), oi)
+    np.testing.assert_array_equal(sc.cpu().numpy(), os_)
+
+
+def test_partitioned_search_pads_when_leaves_are_small():
+    # more results asked for than the probed leaves hold: padded with id -1, score -inf
+    c = make_ivf_case(32, 400, 16, 8, 4, 7, 40)
+    idx, xd = make_ivf_index(c)
+    qd = dev(c["q"])
+    ids, sc = idx.search(qd, 60, 100, 0, leaves_to_search=2)
+    oi, os_ = oracle.search(c["x"], c["cb"], c["codes"], 4, c["q"], 60, 100, 0, centers=c["centers"],
+                            assign=c["assign"], leaves_to_search=2)
+    assert (oi == -1).any()
+    np.testing.assert_array_equal(ids.cpu().numpy(), oi)
+    np.testing.assert_array_equal(sc.cpu().numpy(), os_)
+
+
+def test_partitioned_train_and_encode(ivf_case):
+    c = ivf_case
+    x = c["x"]
+    idx = avq.Index(c["d"], c["M"], c["bits"], n_leaves=12, kmeans_iters=4, leaf_kmeans_iters=4,
+                    encode_passes=3, seed=4)
+    xd = dev(x)
+    idx.train(dev(x[:3000]))
+    centers = oracle.kmeans(x[:3000], 12, iters=4, seed=4)
+    np.testing.assert_allclose(idx.get_leaf_centers(), centers, rtol=0, atol=1e-6)
+    # from here on use the library's own centers so later stages are compared like for like
+    centers = idx.get_leaf_centers()
+    assign_t = oracle.assign_nearest(x[:3000], centers)
+    cb = oracle.train_pq(x[:3000], c["M"], 16, 4, 4, leaf_centers=centers, leaf_assign=assign_t)
+    np.testing.assert_allclose(idx.get_codebooks(), cb, rtol=0, atol=1e-6)
+    cb = idx.get_codebooks()
+    idx.encode(xd)
+    assign = oracle.assign_nearest(x, centers)
+    got_assign = idx.get_leaf_assign()
+    assert np.mean(got_assign != assign) <= 1e-3
+    codes = oracle.encode(x, cb, T=0.2, passes=3, leaf_centers=centers, leaf_assign=got_assign)
+    got = unpack_codes(idx.get_codes(), c["M"], c["bits"])
+    assert np.mean(np.any(got != codes, axis=1)) <= 1e-3
+    # and the index built by the library searches like the oracle on the library's own codes
+    qd = dev(c["q"])
+    ids, sc = idx.search(qd, 10, 100, 0, leaves_to_search=4)
+    oi, os_ = oracle.search(x, cb, got, c["bits"], c["q"], 10, 100, 0, centers=centers,
+                            assign=got_assign, leaves_to_search=4)
+    np.testing.assert_array_equal(ids.cpu().numpy(), oi)
+    np.testing.assert_array_equal(sc.cpu().numpy(), os_)
