@@ -183,9 +183,31 @@ int avq_debug_leaf_select(avq_index *idx, const float *queries, int32_t nq, int3
 double avq_eta(int32_t d, double T, double norm, int32_t eta_mode);
 
 /* Launch-shape overrides for experiments; 0 restores the built-in choice.
- * name: "scan_target_wgs", "scan_waves", "scan_qt". Returns AVQ_EINVAL for an
- * unknown name. */
+ * name: "scan_target_wgs" (workgroups the batch scan aims for), "scan_waves"
+ * (waves per scan workgroup), "scan_qt" (queries per tile), "small_batch_max"
+ * (v > 0: batches of fewer than v queries on a flat index take the block-maxima
+ * path; 1 disables that path), "small_batch_impl" (0: one fused kernel after
+ * the block-maxima scan; 1: the same algorithm as three kernels).
+ * Results never depend on these. Returns
+ * AVQ_EINVAL for an unknown name. */
 int avq_set_tuning(avq_index *idx, const char *name, int32_t value);
+
+/* Per-stage GPU time of avq_search, measured with HIP events recorded on the
+ * caller's stream around each stage's kernel (one event pair per stage per
+ * call while enabled; off by default). avq_profile_read waits for the recorded
+ * events, then writes the summed milliseconds and the number of launches per
+ * stage into ms_out[AVQ_N_STAGES] / launches_out[AVQ_N_STAGES] (host pointers);
+ * reset != 0 forgets the records. */
+enum { AVQ_STAGE_LEAF = 0,   /* leaf selection                                           */
+       AVQ_STAGE_LUT = 1,    /* table build                                              */
+       AVQ_STAGE_SCAN = 2,   /* the scan over all codes (batch: with candidate lists;
+                                small batch: block maxima only)                          */
+       AVQ_STAGE_MERGE = 3,  /* merge of per-chunk lists / selection of the best blocks  */
+       AVQ_STAGE_FINAL = 4,  /* exact re-scoring and final top-k                         */
+       AVQ_STAGE_RESCAN = 5, /* small batch: scan of the selected blocks                 */
+       AVQ_N_STAGES = 6 };
+int avq_profile_enable(avq_index *idx, int32_t on);
+int avq_profile_read(avq_index *idx, double *ms_out, int64_t *launches_out, int32_t reset);
 
 const char *avq_last_error(void);
 const char *avq_version(void);

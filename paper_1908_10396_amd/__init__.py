@@ -17,6 +17,7 @@ AVQ_OK, AVQ_EINVAL, AVQ_ESTATE, AVQ_ENOMEM, AVQ_EHIP = 0, -1, -2, -3, -4
 LUT_F32, LUT_U8 = 0, 1
 ETA_LIMIT, ETA_EXACT, ETA_EXPLICIT = 0, 1, 2
 MAX_SELECT = 512
+STAGES = ("leaf_select", "lut", "scan", "merge", "finalize", "rescan")
 
 # every symbol include/avq.h declares
 SYMBOLS = [
@@ -24,7 +25,7 @@ SYMBOLS = [
     "avq_set_codebooks", "avq_get_codebooks", "avq_set_leaf_centers", "avq_get_leaf_centers",
     "avq_set_database", "avq_get_codes", "avq_get_leaf_assign", "avq_size", "avq_debug_lut",
     "avq_debug_adc_scores", "avq_debug_leaf_select", "avq_eta", "avq_set_tuning",
-    "avq_last_error", "avq_version",
+    "avq_profile_enable", "avq_profile_read", "avq_last_error", "avq_version",
 ]
 
 
@@ -77,6 +78,8 @@ def lib():
         L.avq_eta.argtypes = [i32, C.c_double, C.c_double, i32]
         L.avq_eta.restype = C.c_double
         L.avq_set_tuning.argtypes = [vp, C.c_char_p, i32]
+        L.avq_profile_enable.argtypes = [vp, i32]
+        L.avq_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), i32]
         L.avq_last_error.restype = C.c_char_p
         L.avq_version.restype = C.c_char_p
         _lib = L
@@ -151,6 +154,16 @@ class Index:
 
     def set_tuning(self, name, value):
         _check(lib().avq_set_tuning(self._h, name.encode(), int(value)))
+
+    def profile_enable(self, on=True):
+        _check(lib().avq_profile_enable(self._h, 1 if on else 0))
+
+    def profile_read(self, reset=True):
+        """{stage: (milliseconds, launches)} since the last reset."""
+        ms = (C.c_double * len(STAGES))()
+        cnt = (C.c_int64 * len(STAGES))()
+        _check(lib().avq_profile_read(self._h, ms, cnt, 1 if reset else 0))
+        return {name: (ms[i], cnt[i]) for i, name in enumerate(STAGES)}
 
     # -- build ---------------------------------------------------------------------
     def train(self, x, stream=None):

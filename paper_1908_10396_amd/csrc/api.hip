@@ -57,7 +57,40 @@ struct avq_index {
     DevBuf x_own, codes_logical, codes_blocked, assign, perm, leaf_blk;
     // per-call scratch
     DevBuf lut, lut8, scale, bias, partial, cand, leaf_ids, leaf_ip, tmp;
-    int tune_target_wgs = 0, tune_waves = 0, tune_qt = 0;
+    int tune_target_wgs = 0, tune_waves = 0, tune_qt = 0, tune_small_batch = -1, tune_small_impl = 0;
+    DevBuf block_max;
+    // optional per-stage timing with HIP events recorded on the caller's stream
+    bool prof_on = false;
+    std::vector<hipEvent_t> prof_pool;
+    size_t prof_used = 0;
+    struct ProfRec { int stage; hipEvent_t a, b; };
+    std::vector<ProfRec> prof_recs;
+};
+
+// Records an event pair around one stage's launches while profiling is on.
+struct StageTimer {
+    avq_index *idx;
+    hipStream_t st;
+    hipEvent_t a = nullptr, b = nullptr;
+    int stage;
+    StageTimer(avq_index *i, int stage_, hipStream_t s) : idx(i), st(s), stage(stage_)
+    {
+        if (!idx->prof_on) return;
+        while (idx->prof_pool.size() < idx->prof_used + 2) {
+            hipEvent_t e;
+            if (hipEventCreate(&e) != hipSuccess) return;
+            idx->prof_pool.push_back(e);
+        }
+        a = idx->prof_pool[idx->prof_used++];
+        b = idx->prof_pool[idx->prof_used++];
+        (void)hipEventRecord(a, st);
+    }
+    ~StageTimer()
+    {
+        if (!a) return;
+        (void)hipEventRecord(b, st);
+        idx->prof_recs.push_back({stage, a, b});
+    }
 };
 
 static int check_index(const avq_index *idx)
@@ -117,8 +150,9 @@ extern "C" void avq_destroy(avq_index *idx)
     DevBuf *all[] = {&idx->codebooks, &idx->centers, &idx->centers_t, &idx->x_own, &idx->codes_logical,
                      &idx->codes_blocked, &idx->assign, &idx->perm, &idx->leaf_blk, &idx->lut, &idx->lut8,
                      &idx->scale, &idx->bias, &idx->partial, &idx->cand, &idx->leaf_ids, &idx->leaf_ip,
-                     &idx->tmp};
+                     &idx->tmp, &idx->block_max};
     for (DevBuf *b : all) b->release();
+    for (hipEvent_t e : idx->prof_pool) (void)hipEventDestroy(e);
     delete idx;
 }
 
@@ -131,7 +165,32 @@ extern "C" int avq_set_tuning(avq_index *idx, const char *name, int32_t value)
     if (!strcmp(name, "scan_target_wgs")) idx->tune_target_wgs = value;
     else if (!strcmp(name, "scan_waves")) idx->tune_waves = value;
     else if (!strcmp(name, "scan_qt")) idx->tune_qt = value;
+    else if (!strcmp(name, "small_batch_max")) idx->tune_small_batch = value - 1; // 0 = built-in
+    else if (!strcmp(name, "small_batch_impl")) idx->tune_small_impl = value;
     else { set_error("avq_set_tuning: unknown name '%s'", name); return AVQ_EINVAL; }
+    return AVQ_OK;
+}
+
+extern "C" int avq_profile_enable(avq_index *idx, int32_t on)
+{
+    AVQ_TRY(check_index(idx));
+    idx->prof_on = on != 0;
+    return AVQ_OK;
+}
+
+extern "C" int avq_profile_read(avq_index *idx, double *ms_out, int64_t *launches_out, int32_t reset)
+{
+    AVQ_TRY(check_index(idx));
+    if (!ms_out || !launches_out) { set_error("avq_profile_read: NULL output"); return AVQ_EINVAL; }
+    for (int s = 0; s < AVQ_N_STAGES; ++s) { ms_out[s] = 0.0; launches_out[s] = 0; }
+    for (const avq_index::ProfRec &r : idx->prof_recs) {
+        AVQ_HIP(hipEventSynchronize(r.b));
+        float ms = 0.0f;
+        AVQ_HIP(hipEventElapsedTime(&ms, r.a, r.b));
+        ms_out[r.stage] += (double)ms;
+        launches_out[r.stage] += 1;
+    }
+    if (reset) { idx->prof_recs.clear(); idx->prof_used = 0; }
     return AVQ_OK;
 }
 
@@ -442,17 +501,85 @@ extern "C" int avq_search(avq_index *idx, const float *queries, int32_t nq, int3
     const int C = 64 * ns;
     const bool u8 = lut_mode == AVQ_LUT_U8;
 
-    AVQ_TRY(build_tables(idx, queries, nq, lut_mode, st));
+    {
+        StageTimer t(idx, AVQ_STAGE_LUT, st);
+        AVQ_TRY(build_tables(idx, queries, nq, lut_mode, st));
+    }
     ScanParams p;
     fill_scan_params(idx, nq, R, ns, &p);
+    const int key_kind = (u8 && !ivf) ? 1 : 0;
+    const int small_max = idx->tune_small_batch >= 0 ? idx->tune_small_batch : 8;
+    if (!ivf && nq <= small_max) {
+        // A handful of queries: full scan recording block maxima, pick the R best blocks,
+        // scan only those with the list machinery.
+        AVQ_TRY(idx->block_max.reserve(sizeof(u64) * (size_t)nq * idx->n_blocks));
+        AVQ_TRY(idx->cand.reserve(sizeof(u64) * (size_t)nq * C));
+        AVQ_TRY(idx->partial.reserve(sizeof(u64) * (size_t)nq * C));
+        p.block_max = idx->block_max.as<u64>();
+        p.block_keys = idx->cand.as<u64>();
+        p.partial = idx->partial.as<u64>();
+        p.n_tiles = nq;
+        p.n_chunks = 1;
+        {
+            StageTimer t(idx, AVQ_STAGE_SCAN, st);
+            AVQ_TRY(launch_block_max(p, u8, idx->tune_waves > 0 ? idx->tune_waves : 4, st));
+        }
+        if (idx->tune_small_impl == 0) {
+            FinishParams f;
+            f.x = idx->x;
+            f.queries = queries;
+            f.d = c.d;
+            f.k = k;
+            f.reorder = reorder_k != 0;
+            f.stage_rows = small_finish_stage_rows(p, c.d, u8);
+            f.cand_stride = (int64_t)256 * R;
+            const size_t cand_bytes = sizeof(u64) * (size_t)nq * f.cand_stride;
+            const size_t sel_bytes = (sizeof(int32_t) * (size_t)nq * R + 15) & ~(size_t)15;
+            AVQ_TRY(idx->tmp.reserve(cand_bytes + sel_bytes + sizeof(SmallMeta) * (size_t)nq));
+            f.cand = idx->tmp.as<u64>();
+            f.sel_blk = (int32_t *)((char *)idx->tmp.p + cand_bytes);
+            f.meta = (SmallMeta *)((char *)idx->tmp.p + cand_bytes + sel_bytes);
+            f.ids_out = ids_out;
+            f.scores_out = scores_out;
+            {
+                StageTimer t(idx, AVQ_STAGE_MERGE, st);
+                AVQ_TRY(launch_small_select(p, f, st));
+            }
+            {
+                StageTimer t(idx, AVQ_STAGE_RESCAN, st);
+                AVQ_TRY(launch_small_rescan(p, f, u8, st));
+            }
+            StageTimer t(idx, AVQ_STAGE_FINAL, st);
+            return launch_small_final(p, f, u8, st);
+        }
+        // three-kernel variant of the same algorithm (kept as a cross-check)
+        {
+            StageTimer t(idx, AVQ_STAGE_MERGE, st);
+            AVQ_TRY(launch_select_keys(p.block_max, nq, idx->n_blocks, ns, R, idx->cand.as<u64>(), st));
+        }
+        ScanShape shape;
+        int rc = AVQ_EINVAL;
+        for (int w = 16; w >= 1 && rc != AVQ_OK; w /= 2) rc = scan_pick_shape(idx->NB, u8, ns, nq, true, 1, w, &shape);
+        AVQ_TRY(rc);
+        {
+            StageTimer t(idx, AVQ_STAGE_RESCAN, st);
+            AVQ_TRY(launch_scan(p, u8, SCAN_BLOCKLIST, shape, st));
+        }
+        StageTimer t(idx, AVQ_STAGE_FINAL, st);
+        return launch_finalize(p.partial, ns, nq, R, k, reorder_k != 0, key_kind, idx->x, c.d, queries,
+                               idx->scale.as<float>(), idx->bias.as<float>(), ids_out, scores_out, st);
+    }
     ScanShape shape;
     AVQ_TRY(scan_pick_shape(idx->NB, u8, ns, nq, ivf, idx->tune_qt, idx->tune_waves, &shape));
     if (ivf) {
         const int L = leaves_to_search;
         AVQ_TRY(idx->leaf_ids.reserve(sizeof(int32_t) * (size_t)nq * L));
         AVQ_TRY(idx->leaf_ip.reserve(sizeof(float) * (size_t)nq * L));
-        AVQ_TRY(launch_leaf_select(idx->centers_t.as<float>(), c.n_leaves, c.d, queries, nq, L,
-                                   idx->leaf_ids.as<int32_t>(), idx->leaf_ip.as<float>(), st));
+        {
+            StageTimer t(idx, AVQ_STAGE_LEAF, st);
+            AVQ_TRY(launch_leaf_select(idx->centers_t.as<float>(), c.n_leaves, c.d, queries, nq, L,
+                                       idx->leaf_ids.as<int32_t>(), idx->leaf_ip.as<float>(), st));
+        }
         p.perm = idx->perm.as<int32_t>();
         p.leaf_ids = idx->leaf_ids.as<int32_t>();
         p.leaf_ip = idx->leaf_ip.as<float>();
@@ -465,14 +592,18 @@ extern "C" int avq_search(avq_index *idx, const float *queries, int32_t nq, int3
     }
     AVQ_TRY(idx->partial.reserve(sizeof(u64) * (size_t)p.n_tiles * shape.qt * p.n_chunks * C));
     p.partial = idx->partial.as<u64>();
-    AVQ_TRY(launch_scan(p, u8, ivf, shape, st));
+    {
+        StageTimer t(idx, AVQ_STAGE_SCAN, st);
+        AVQ_TRY(launch_scan(p, u8, ivf ? SCAN_LEAVES : SCAN_CHUNK, shape, st));
+    }
     const u64 *cand = p.partial;
     if (p.n_chunks > 1) {
         AVQ_TRY(idx->cand.reserve(sizeof(u64) * (size_t)nq * C));
+        StageTimer t(idx, AVQ_STAGE_MERGE, st);
         AVQ_TRY(launch_merge_partials(p.partial, nq, p.n_chunks, ns, idx->cand.as<u64>(), st));
         cand = idx->cand.as<u64>();
     }
-    const int key_kind = (u8 && !ivf) ? 1 : 0;
+    StageTimer t(idx, AVQ_STAGE_FINAL, st);
     return launch_finalize(cand, ns, nq, R, k, reorder_k != 0, key_kind, idx->x, c.d, queries,
                            idx->scale.as<float>(), idx->bias.as<float>(), ids_out, scores_out, st);
 }
@@ -533,7 +664,7 @@ extern "C" int avq_debug_adc_scores(avq_index *idx, const float *queries, int32_
     p.score_stride = idx->n;
     AVQ_TRY(idx->partial.reserve(64));
     p.partial = idx->partial.as<u64>();
-    return launch_scan(p, u8, false, shape, st);
+    return launch_scan(p, u8, SCAN_CHUNK, shape, st);
 }
 
 extern "C" int avq_debug_leaf_select(avq_index *idx, const float *queries, int32_t nq, int32_t L,

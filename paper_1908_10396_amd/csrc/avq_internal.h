@@ -13,6 +13,8 @@ typedef unsigned long long u64;
 
 // Points are stored in blocks of 256: 64 lanes x 4 points per lane.
 constexpr int kBlockPoints = 256;
+// Dynamic LDS a kernel may ask for: the CU's 160 KiB less room for small static arrays.
+constexpr size_t kMaxDynLds = 159 * 1024;
 
 void set_error(const char *fmt, ...);
 
@@ -64,20 +66,49 @@ struct ScanParams {
     const float *leaf_ip;                        // [B][Lp]
     const int32_t *leaf_blk;                     // [n_leaves + 1] first block of each leaf
     int32_t Lp;
+    const u64 *block_keys; // block-list mode: [B][64*ns], the keys of the blocks to scan
+    u64 *block_max;        // block-max kernel: [B][n_blocks]
     u64 *partial;         // [n_tiles*QT][n_chunks][64*ns]
     void *scores_out;     // debug: [B][score_stride] fp32 or int32, else NULL
     int64_t score_stride;
 };
 struct ScanShape { int qt; int waves; size_t lds_bytes; };
 // Picks query-tile size and waves per workgroup that fit LDS. qt_hint/waves_hint 0 = auto.
-int scan_pick_shape(int NB, bool u8, int ns, int B, bool ivf, int qt_hint, int waves_hint,
+int scan_pick_shape(int NB, bool u8, int ns, int B, bool single, int qt_hint, int waves_hint,
                     ScanShape *out);
-int launch_scan(const ScanParams &p, bool u8, bool ivf, const ScanShape &shape, hipStream_t st);
+// SCAN_CHUNK: flat index, grid = query tiles x chunks; SCAN_LEAVES: partitioned index, one
+// workgroup per query over its probed leaves; SCAN_BLOCKLIST: flat index, one workgroup per
+// query over the blocks named by block_keys.
+enum { SCAN_CHUNK = 0, SCAN_LEAVES = 1, SCAN_BLOCKLIST = 2 };
+int launch_scan(const ScanParams &p, bool u8, int mode, const ScanShape &shape, hipStream_t st);
+// Full scan that only records the best key of every block (block_max[q][blk]).
+int launch_block_max(const ScanParams &p, bool u8, int waves, hipStream_t st);
+// Small batches, after launch_block_max: block selection, scan of the selected blocks,
+// final selection with exact re-scoring and output (three kernels).
+struct SmallMeta { u64 t1; uint32_t n_sel; uint32_t n_cand; };
+struct FinishParams {
+    const float *x;        // [n][d], may be NULL when reorder == 0
+    const float *queries;  // [B][d]
+    int32_t d, k, reorder;
+    int32_t stage_rows;    // rows of x staged in LDS per pass of the re-scoring (small_finish_stage_rows)
+    u64 *cand;             // scratch [B][cand_stride], cand_stride >= 256 * R
+    int64_t cand_stride;
+    int32_t *sel_blk;      // scratch [B][R]: the selected blocks
+    SmallMeta *meta;       // scratch [B]
+    int32_t *ids_out;      // [B][k]
+    float *scores_out;     // [B][k]
+};
+int small_finish_stage_rows(const ScanParams &p, int d, bool u8);
+int launch_small_select(const ScanParams &p, const FinishParams &f, hipStream_t st);
+int launch_small_rescan(const ScanParams &p, const FinishParams &f, bool u8, hipStream_t st);
+int launch_small_final(const ScanParams &p, const FinishParams &f, bool u8, hipStream_t st);
 
 // ---- select.hip ------------------------------------------------------------
 // Merges the per-chunk lists of every query into one sorted list cand[q][64*ns].
 int launch_merge_partials(const u64 *partial, int nq, int n_chunks, int ns, u64 *cand,
                           hipStream_t st);
+// The R largest of n unsorted keys per query: out[q][64*ns] sorted descending.
+int launch_select_keys(const u64 *keys, int nq, int64_t n, int ns, int R, u64 *out, hipStream_t st);
 // Final stage. reorder != 0: exact <q, x_id> for the first R candidates, then top-k.
 // reorder == 0: first k candidates; score decoded from the key (kind 0: fp32 key,
 // kind 1: integer sum -> fma(acc, scale, bias)).

@@ -10,7 +10,7 @@
 // streams its codes with dwordx4 loads; the NB % 4 left-over planes follow as
 // 256-byte dword rows. A block is exactly 256*NB bytes: no padding.
 //
-// Tables. Whatever the code width, the kernel sees NB byte positions with a
+// Tables. Whatever the code width, the kernels see NB byte positions with a
 // 256-entry table each, held in LDS for a tile of QT queries, entry = QT values
 // interleaved (one ds_read fetches a byte's entry for the whole tile):
 //   8-bit codes: T[b][v] = L[b][v];
@@ -19,15 +19,27 @@
 // Scores accumulate over b = 0..NB-1 in order, which is the summation order the
 // fp32 path is defined with.
 //
-// Selection. Each wave keeps, per query, a sorted list of the best 64*ns keys
-// in LDS and a 64-entry pending buffer; a lane whose score beats the current
-// R-th best appends to the buffer, a full buffer is sorted and merged (bitonic
-// networks across lanes). At the end the waves' lists are merged and written
-// out per (query, chunk).
+// Two selection schemes.
+//  * Batches (adc_scan_kernel, MODE_CHUNK / MODE_LEAVES): each wave keeps, per
+//    query, a sorted list of the best 64*ns keys in LDS and a 64-entry pending
+//    buffer; a lane whose score beats the current R-th best appends to the
+//    buffer, a full buffer is sorted and merged (bitonic networks across lanes).
+//    At the end the waves' lists are merged and written out per (query, chunk).
+//  * A handful of queries (block_max_kernel, then adc_scan_kernel in
+//    MODE_BLOCKLIST): with one query the threshold filter has nothing to work
+//    with -- every wave sees only a few hundred points -- so the full scan only
+//    records the best key of every 256-point block. The R best points all lie
+//    in the R blocks with the largest block maxima (R blocks whose maximum is
+//    >= t hold R points >= t, and every point outside them is below its own
+//    block's maximum, hence below t), so only those R blocks are scanned again
+//    with the list machinery above.
 #include "avq_internal.h"
 #include "wave_topk.h"
+#include "wg_select.h"
 
 namespace avq {
+
+enum { MODE_CHUNK = 0, MODE_LEAVES = 1, MODE_BLOCKLIST = 2 };
 
 template <int W> struct VecW;
 template <> struct VecW<1> { typedef uint32_t type; };
@@ -40,28 +52,165 @@ template <int W> __device__ __forceinline__ uint32_t vec_get(const typename VecW
     else return v[i];
 }
 
-// words per table entry
+// words per table entry: fp32 -> one float per query; 8-bit tables -> one u16 per query
+// (a lone query uses a full word)
 template <int QT, bool U8> struct EntryWords { static constexpr int value = U8 ? (QT >= 2 ? QT / 2 : 1) : QT; };
 
-template <int QT, bool U8, int NBT, bool IVF>
+// The code bytes of one block held by one lane.
+template <int NBT> struct BlockRegs {
+    uint4 rows[NBT / 4 ? NBT / 4 : 1];
+    uint32_t tails[NBT % 4 ? NBT % 4 : 1];
+};
+
+template <int NBT>
+__device__ __forceinline__ void load_block(BlockRegs<NBT> &r, const uint8_t *__restrict__ codes, int64_t blk,
+                                           int lane)
+{
+    if constexpr (NBT != 0) {
+        const uint8_t *base = codes + (size_t)blk * 256 * NBT;
+#pragma unroll
+        for (int j = 0; j < NBT / 4; ++j) r.rows[j] = ((const uint4 *)(base + (size_t)j * 1024))[lane];
+#pragma unroll
+        for (int t = 0; t < NBT % 4; ++t)
+            r.tails[t] = ((const uint32_t *)(base + (size_t)(NBT / 4) * 1024 + (size_t)t * 256))[lane];
+    }
+}
+
+// Fills the byte tables of the query tile starting at q0 (all threads of the workgroup).
+template <int QT, bool U8>
+__device__ __forceinline__ void build_tables(typename VecW<EntryWords<QT, U8>::value>::type *tbl,
+                                             const ScanParams &p, int q0, int NB)
+{
+    const int kc = 1 << p.bits;
+    const int items = QT * NB * 16; // (q, b, g): 16 consecutive byte values g*16 .. g*16+15
+    for (int it = threadIdx.x; it < items; it += blockDim.x) {
+        const int q = it % QT;
+        const int g = (it / QT) & 15;
+        const int b = it / (QT * 16);
+        const int gq = q0 + q;
+        const bool live = gq < p.B;
+        if constexpr (!U8) {
+            float *t = (float *)tbl;
+            const float *L = p.lut + (size_t)(live ? gq : 0) * p.M * kc;
+            if (p.bits == 8) {
+                for (int lo = 0; lo < 16; ++lo)
+                    t[(size_t)(b * 256 + g * 16 + lo) * QT + q] = live ? L[b * 256 + g * 16 + lo] : 0.0f;
+            } else {
+                const bool pair = 2 * b + 1 < p.M;
+                const float hi = (pair && live) ? L[(2 * b + 1) * 16 + g] : 0.0f;
+                for (int lo = 0; lo < 16; ++lo) {
+                    float v = live ? L[2 * b * 16 + lo] : 0.0f;
+                    if (pair) v = __fadd_rn(v, hi);
+                    t[(size_t)(b * 256 + g * 16 + lo) * QT + q] = v;
+                }
+            }
+        } else {
+            const uint8_t *L = p.lut8 + (size_t)(live ? gq : 0) * p.M * kc;
+            for (int lo = 0; lo < 16; ++lo) {
+                uint32_t v;
+                if (p.bits == 8) v = L[b * 256 + g * 16 + lo];
+                else v = (uint32_t)L[2 * b * 16 + lo] + ((2 * b + 1 < p.M) ? (uint32_t)L[(2 * b + 1) * 16 + g] : 0u);
+                if (!live) v = 0;
+                const size_t e = (size_t)(b * 256 + g * 16 + lo);
+                if constexpr (QT == 1) ((uint32_t *)tbl)[e] = v;
+                else ((uint16_t *)tbl)[e * QT + q] = (uint16_t)v;
+            }
+        }
+    }
+}
+
+// Scores of the lane's four points of one block against the query tile:
+// acc[i] = sum over byte positions, in order, of the table entries.
+template <int QT, bool U8, int NBT>
+__device__ __forceinline__ void accumulate_block(const typename VecW<EntryWords<QT, U8>::value>::type *tbl,
+                                                 const BlockRegs<NBT> &r, const uint8_t *__restrict__ codes,
+                                                 int64_t blk, int NB, int lane,
+                                                 typename VecW<EntryWords<QT, U8>::value>::type (&acc)[4])
+{
+    constexpr int WORDS = EntryWords<QT, U8>::value;
+    typedef typename VecW<WORDS>::type entry_t;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        if constexpr (WORDS == 1) acc[i] = 0u;
+        else acc[i] = (entry_t)(0u);
+    }
+    auto plane = [&](uint32_t w, int b) {
+        const entry_t *tb = tbl + (size_t)b * 256;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t byte = (w >> (8 * i)) & 0xffu;
+            const entry_t e = tb[byte];
+            if constexpr (U8) {
+                acc[i] += e;
+            } else {
+#pragma unroll
+                for (int k = 0; k < WORDS; ++k) {
+                    float a = __uint_as_float(vec_get<WORDS>(acc[i], k));
+                    a = __fadd_rn(a, __uint_as_float(vec_get<WORDS>(e, k)));
+                    if constexpr (WORDS == 1) acc[i] = __float_as_uint(a);
+                    else acc[i][k] = __float_as_uint(a);
+                }
+            }
+        }
+    };
+    if constexpr (NBT != 0) {
+#pragma unroll
+        for (int j = 0; j < NBT / 4; ++j) {
+            plane(r.rows[j].x, 4 * j + 0);
+            plane(r.rows[j].y, 4 * j + 1);
+            plane(r.rows[j].z, 4 * j + 2);
+            plane(r.rows[j].w, 4 * j + 3);
+        }
+#pragma unroll
+        for (int t = 0; t < NBT % 4; ++t) plane(r.tails[t], (NBT / 4) * 4 + t);
+    } else {
+        const int nfull = NB / 4, ntail = NB % 4;
+        const uint8_t *base = codes + (size_t)blk * 256 * NB;
+        for (int j = 0; j < nfull; ++j) {
+            const uint4 row = ((const uint4 *)(base + (size_t)j * 1024))[lane];
+            plane(row.x, 4 * j + 0);
+            plane(row.y, 4 * j + 1);
+            plane(row.z, 4 * j + 2);
+            plane(row.w, 4 * j + 3);
+        }
+        for (int t = 0; t < ntail; ++t) {
+            const uint32_t w = ((const uint32_t *)(base + (size_t)nfull * 1024 + (size_t)t * 256))[lane];
+            plane(w, 4 * nfull + t);
+        }
+    }
+}
+
+// Integer sum of query q from the packed accumulators.
+template <int QT, int WORDS>
+__device__ __forceinline__ int packed_sum(const typename VecW<WORDS>::type &a, int q)
+{
+    if constexpr (QT == 1) return (int)vec_get<WORDS>(a, 0);
+    else return (int)((vec_get<WORDS>(a, q >> 1) >> (16 * (q & 1))) & 0xffffu);
+}
+
+template <int QT, bool U8, int NBT, int MODE>
 __global__ void __launch_bounds__(QT > 1 ? 512 : 1024)
 adc_scan_kernel(const ScanParams p)
 {
     constexpr int WORDS = EntryWords<QT, U8>::value;
     typedef typename VecW<WORDS>::type entry_t;
+    constexpr bool LEAVES = MODE == MODE_LEAVES;
+    // With leaves the ranking key is a float even for 8-bit tables (it includes <q, center>).
+    constexpr bool FKEY = !U8 || LEAVES;
+    // Ids grow along a wave's scan only in MODE_CHUNK; there a score equal to the current
+    // R-th best can never enter the list, so the filter may be strict.
+    constexpr bool STRICT = MODE == MODE_CHUNK;
     extern __shared__ __align__(16) unsigned char smem[];
 
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
     const int n_waves = blockDim.x >> 6;
     const int NB = NBT ? NBT : p.NB;
-    const int kc = 1 << p.bits;
     const int C = 64 * p.ns;
 
     int tile, chunk;
-    if (IVF) { tile = blockIdx.x; chunk = 0; }
-    else { tile = blockIdx.x % p.n_tiles; chunk = blockIdx.x / p.n_tiles; }
+    if (MODE == MODE_CHUNK) { tile = blockIdx.x % p.n_tiles; chunk = blockIdx.x / p.n_tiles; }
+    else { tile = blockIdx.x; chunk = 0; }
     const int q0 = tile * QT;
 
     entry_t *tbl = (entry_t *)smem;
@@ -71,45 +220,8 @@ adc_scan_kernel(const ScanParams p)
     u64 *my_lists = lists + (size_t)wave * QT * C;
     u64 *my_pends = pends + (size_t)wave * QT * 64;
 
-    // ---- build the byte tables of this query tile --------------------------
-    {
-        const int items = QT * NB * 16; // (q, b, g): 16 consecutive byte values g*16 .. g*16+15
-        for (int it = tid; it < items; it += blockDim.x) {
-            const int q = it % QT;
-            const int g = (it / QT) & 15;
-            const int b = it / (QT * 16);
-            const int gq = q0 + q;
-            const bool live = gq < p.B;
-            if constexpr (!U8) {
-                float *t = (float *)tbl;
-                const float *L = p.lut + (size_t)(live ? gq : 0) * p.M * kc;
-                if (p.bits == 8) {
-                    for (int lo = 0; lo < 16; ++lo)
-                        t[(size_t)(b * 256 + g * 16 + lo) * QT + q] = live ? L[b * 256 + g * 16 + lo] : 0.0f;
-                } else {
-                    const bool pair = 2 * b + 1 < p.M;
-                    const float hi = (pair && live) ? L[(2 * b + 1) * 16 + g] : 0.0f;
-                    for (int lo = 0; lo < 16; ++lo) {
-                        float v = live ? L[2 * b * 16 + lo] : 0.0f;
-                        if (pair) v = __fadd_rn(v, hi);
-                        t[(size_t)(b * 256 + g * 16 + lo) * QT + q] = v;
-                    }
-                }
-            } else {
-                const uint8_t *L = p.lut8 + (size_t)(live ? gq : 0) * p.M * kc;
-                for (int lo = 0; lo < 16; ++lo) {
-                    uint32_t v;
-                    if (p.bits == 8) v = L[b * 256 + g * 16 + lo];
-                    else v = (uint32_t)L[2 * b * 16 + lo] + ((2 * b + 1 < p.M) ? (uint32_t)L[(2 * b + 1) * 16 + g] : 0u);
-                    if (!live) v = 0;
-                    const size_t e = (size_t)(b * 256 + g * 16 + lo);
-                    if constexpr (QT == 1) ((uint32_t *)tbl)[e] = v;
-                    else ((uint16_t *)tbl)[e * QT + q] = (uint16_t)v;
-                }
-            }
-        }
-        for (int i = lane; i < QT * C; i += 64) my_lists[i] = 0ull;
-    }
+    build_tables<QT, U8>(tbl, p, q0, NB);
+    for (int i = lane; i < QT * C; i += 64) my_lists[i] = 0ull;
     __syncthreads();
 
     // per-query filter state, wave-uniform
@@ -124,14 +236,12 @@ adc_scan_kernel(const ScanParams p)
         pend_cnt[q] = 0;
         q_scale[q] = 0.0f;
         q_off[q] = 0.0f;
-        if (IVF && U8) {
+        if (LEAVES && U8) {
             const int gq = q0 + q < p.B ? q0 + q : 0;
             q_scale[q] = p.scale[gq];
             q_off[q] = p.bias[gq];
         }
     }
-    // In the partitioned index the ranking key is a float even with 8-bit tables.
-    constexpr bool FKEY = !U8 || IVF;
 
     auto refresh_threshold = [&](int q) {
         const u64 kth = my_lists[(size_t)q * C + (p.R - 1)];
@@ -140,69 +250,19 @@ adc_scan_kernel(const ScanParams p)
     };
 
     // one block of 256 points: accumulate, then filter
-    auto process_block = [&](int64_t blk, const uint4 *rows, const uint32_t *tails, int nfull,
-                             int ntail, float seg_bias) {
+    auto process_block = [&](int64_t blk, const BlockRegs<NBT> &regs, float seg_bias) {
         entry_t acc[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            if constexpr (WORDS == 1) acc[i] = 0u;
-            else acc[i] = (entry_t)(0u);
-        }
-        auto plane = [&](uint32_t w, int b) {
-            const entry_t *tb = tbl + (size_t)b * 256;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const uint32_t byte = (w >> (8 * i)) & 0xffu;
-                const entry_t e = tb[byte];
-                if constexpr (U8) {
-                    acc[i] += e;
-                } else {
-#pragma unroll
-                    for (int k = 0; k < WORDS; ++k) {
-                        float a = __uint_as_float(vec_get<WORDS>(acc[i], k));
-                        a = __fadd_rn(a, __uint_as_float(vec_get<WORDS>(e, k)));
-                        if constexpr (WORDS == 1) acc[i] = __float_as_uint(a);
-                        else acc[i][k] = __float_as_uint(a);
-                    }
-                }
-            }
-        };
-        if constexpr (NBT != 0) {
-#pragma unroll
-            for (int j = 0; j < NBT / 4; ++j) {
-                plane(rows[j].x, 4 * j + 0);
-                plane(rows[j].y, 4 * j + 1);
-                plane(rows[j].z, 4 * j + 2);
-                plane(rows[j].w, 4 * j + 3);
-            }
-#pragma unroll
-            for (int t = 0; t < NBT % 4; ++t) plane(tails[t], (NBT / 4) * 4 + t);
-        } else {
-            const uint8_t *base = p.codes + (size_t)blk * 256 * NB;
-            for (int j = 0; j < nfull; ++j) {
-                const uint4 r = ((const uint4 *)(base + (size_t)j * 1024))[lane];
-                plane(r.x, 4 * j + 0);
-                plane(r.y, 4 * j + 1);
-                plane(r.z, 4 * j + 2);
-                plane(r.w, 4 * j + 3);
-            }
-            for (int t = 0; t < ntail; ++t) {
-                const uint32_t w = ((const uint32_t *)(base + (size_t)nfull * 1024 + (size_t)t * 256))[lane];
-                plane(w, 4 * nfull + t);
-            }
-        }
-
+        accumulate_block<QT, U8, NBT>(tbl, regs, p.codes, blk, NB, lane, acc);
         // score of (query q, point i of this lane)
         auto score_of = [&](int q, int i, float &sf, int &si) {
             sf = 0.0f;
             si = 0;
             if constexpr (!U8) {
                 sf = __uint_as_float(vec_get<WORDS>(acc[i], q));
-                if (IVF) sf = __fadd_rn(sf, seg_bias);
+                if (LEAVES) sf = __fadd_rn(sf, seg_bias);
             } else {
-                if constexpr (QT == 1) si = (int)vec_get<WORDS>(acc[i], 0);
-                else si = (int)((vec_get<WORDS>(acc[i], q >> 1) >> (16 * (q & 1))) & 0xffffu);
-                if (IVF) sf = __fmaf_rn((float)si, q_scale[q], __fadd_rn(q_off[q], seg_bias));
+                si = packed_sum<QT, WORDS>(acc[i], q);
+                if (LEAVES) sf = __fmaf_rn((float)si, q_scale[q], __fadd_rn(q_off[q], seg_bias));
             }
         };
         if (p.scores_out != nullptr) { // inspection mode: store every score, select nothing
@@ -230,13 +290,13 @@ adc_scan_kernel(const ScanParams p)
                 int si;
                 score_of(q, i, sf, si);
                 bool hit;
-                if (FKEY) hit = IVF ? (sf >= thr_f[q]) : (sf > thr_f[q]);
-                else hit = si > thr_i[q];
+                if (FKEY) hit = STRICT ? (sf > thr_f[q]) : (sf >= thr_f[q]);
+                else hit = STRICT ? (si > thr_i[q]) : (si >= thr_i[q]);
                 if (__builtin_amdgcn_ballot_w64(hit) == 0ull) continue;
                 // rare path: some lane has a candidate
                 const int64_t slot = blk * 256 + 4 * lane + i;
                 int32_t id;
-                if (IVF) { id = p.perm[slot]; hit = hit && id >= 0; }
+                if (LEAVES) { id = p.perm[slot]; hit = hit && id >= 0; }
                 else { id = (int32_t)slot; hit = hit && slot < p.n_valid; }
                 const uint32_t ord = FKEY ? ord_from_f32(sf) : (uint32_t)(si + 1);
                 if (wave_push(my_lists + (size_t)q * C, p.ns, my_pends + q * 64, pend_cnt[q], hit,
@@ -246,48 +306,36 @@ adc_scan_kernel(const ScanParams p)
         }
     };
 
-    // ---- stream the code blocks ---------------------------------------------
-    const int nfull = NB / 4, ntail = NB % 4;
-    constexpr int NROWS = NBT ? (NBT / 4 ? NBT / 4 : 1) : 1;
-    constexpr int NTAILS = NBT ? (NBT % 4 ? NBT % 4 : 1) : 1;
-    auto load_block = [&](int64_t blk, uint4 *rows, uint32_t *tails) {
-        if constexpr (NBT != 0) {
-            const uint8_t *base = p.codes + (size_t)blk * 256 * NBT;
-#pragma unroll
-            for (int j = 0; j < NBT / 4; ++j) rows[j] = ((const uint4 *)(base + (size_t)j * 1024))[lane];
-#pragma unroll
-            for (int t = 0; t < NBT % 4; ++t)
-                tails[t] = ((const uint32_t *)(base + (size_t)(NBT / 4) * 1024 + (size_t)t * 256))[lane];
-        }
-    };
+    // streams blocks first, first + step, ... < end with the next block's loads in flight
     auto scan_range = [&](int64_t first, int64_t end, int64_t step, float seg_bias) {
-        uint4 cur[NROWS], nxt[NROWS];
-        uint32_t cur_t[NTAILS], nxt_t[NTAILS];
-        if (first < end) load_block(first, cur, cur_t);
+        BlockRegs<NBT> cur, nxt;
+        if (first < end) load_block<NBT>(cur, p.codes, first, lane);
         for (int64_t blk = first; blk < end; blk += step) {
             const bool more = blk + step < end;
-            if (more) load_block(blk + step, nxt, nxt_t);
-            process_block(blk, cur, cur_t, nfull, ntail, seg_bias);
-            if (more) {
-#pragma unroll
-                for (int j = 0; j < NROWS; ++j) cur[j] = nxt[j];
-#pragma unroll
-                for (int t = 0; t < NTAILS; ++t) cur_t[t] = nxt_t[t];
-            }
+            if (more) load_block<NBT>(nxt, p.codes, blk + step, lane);
+            process_block(blk, cur, seg_bias);
+            if (more) cur = nxt;
         }
     };
 
-    if (!IVF) {
+    if (MODE == MODE_CHUNK) {
         const int64_t first = (int64_t)chunk * p.blocks_per_chunk;
         int64_t end = first + p.blocks_per_chunk;
         if (end > p.n_blocks) end = p.n_blocks;
         scan_range(first + wave, end, n_waves, 0.0f);
-    } else {
-        const int gq = q0; // QT == 1
+    } else if (MODE == MODE_LEAVES) {
         for (int j = wave; j < p.Lp; j += n_waves) {
-            const int leaf = p.leaf_ids[(size_t)gq * p.Lp + j];
+            const int leaf = p.leaf_ids[(size_t)q0 * p.Lp + j];
             if (leaf < 0) continue;
-            scan_range(p.leaf_blk[leaf], p.leaf_blk[leaf + 1], 1, p.leaf_ip[(size_t)gq * p.Lp + j]);
+            scan_range(p.leaf_blk[leaf], p.leaf_blk[leaf + 1], 1, p.leaf_ip[(size_t)q0 * p.Lp + j]);
+        }
+    } else {
+        // the R blocks with the largest block maxima, as keys whose id lies in the block
+        for (int j = wave; j < p.R; j += n_waves) {
+            const u64 key = p.block_keys[(size_t)q0 * C + j];
+            if (key == 0ull) continue;
+            const int64_t blk = (int64_t)(key_id(key) >> 8);
+            scan_range(blk, blk + 1, 1, 0.0f);
         }
     }
     if (p.scores_out != nullptr) return;
@@ -308,6 +356,356 @@ adc_scan_kernel(const ScanParams p)
     }
 }
 
+// Full scan of one query per grid.y: every wave scores one block and records the
+// block's best key (score, then lower id) in block_max[q][blk]. Nothing else is
+// written: 8 bytes out per 256 points read.
+template <bool U8, int NBT>
+__global__ void __launch_bounds__(1024)
+block_max_kernel(const ScanParams p)
+{
+    constexpr int WORDS = EntryWords<1, U8>::value;
+    typedef typename VecW<WORDS>::type entry_t;
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int n_waves = blockDim.x >> 6;
+    const int NB = NBT ? NBT : p.NB;
+    const int q = blockIdx.y;
+    const int64_t blk = (int64_t)blockIdx.x * n_waves + wave;
+    entry_t *tbl = (entry_t *)smem;
+
+    BlockRegs<NBT> regs;
+    const bool have = blk < p.n_blocks;
+    if (have) load_block<NBT>(regs, p.codes, blk, lane); // in flight while the tables are built
+    build_tables<1, U8>(tbl, p, q, NB);
+    __syncthreads();
+    if (!have) return;
+    entry_t acc[4];
+    accumulate_block<1, U8, NBT>(tbl, regs, p.codes, blk, NB, lane, acc);
+    // best of the lane's four points: higher ordering value, then lower id (= lower i)
+    uint32_t best = 0;
+    int best_i = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int64_t slot = blk * 256 + 4 * lane + i;
+        uint32_t ord = U8 ? (uint32_t)(acc[i] + 1u) : ord_from_f32(__uint_as_float(acc[i]));
+        if (slot >= p.n_valid) ord = 0u;
+        if (ord > best) { best = ord; best_i = i; }
+    }
+    uint32_t wmax = best;
+#pragma unroll
+    for (int m = 32; m > 0; m >>= 1) {
+        const uint32_t o = (uint32_t)__shfl_xor((int)wmax, m, 64);
+        wmax = o > wmax ? o : wmax;
+    }
+    const u64 owners = __builtin_amdgcn_ballot_w64(best == wmax);
+    const int owner = __builtin_ctzll(owners); // lowest lane = lowest id among equal scores
+    if (lane == owner)
+        p.block_max[(size_t)q * p.n_blocks + blk] =
+            wmax ? make_key(wmax, (int32_t)(blk * 256 + 4 * lane + best_i)) : 0ull;
+}
+
+// 16-entry tables of one query in LDS (4-bit codes): 2*NB tables of 16 entries, fp32
+// (U8 = false) or one byte each (U8 = true); for odd M the last table is all zero, so
+// that every code byte reads two entries. All threads of the workgroup take part.
+template <bool U8>
+__device__ __forceinline__ void nibble_tables_fill(unsigned char *tbl, const ScanParams &p, int q, int NB)
+{
+    const int live = p.M * 16, total = 2 * NB * 16;
+    if (U8) {
+        const uint8_t *L = p.lut8 + (size_t)q * live;
+        for (int e = threadIdx.x; e < total; e += blockDim.x) tbl[e] = e < live ? L[e] : (uint8_t)0;
+    } else {
+        const float *L = p.lut + (size_t)q * live;
+        for (int e = threadIdx.x; e < total; e += blockDim.x) ((float *)tbl)[e] = e < live ? L[e] : 0.0f;
+    }
+}
+
+// Scores of the lane's four points of one block against those tables: per code byte
+// the two entries are added first, then accumulated, byte positions in order.
+// regs holds the block's code bytes (NBT != 0; all of its loads are issued before
+// the first lookup, so a wave pays the memory latency once per block); with
+// NBT == 0 the rows are read from `base` as they are needed.
+template <bool U8, int NBT>
+__device__ __forceinline__ void nibble_accumulate(const unsigned char *tbl, const BlockRegs<NBT> &regs,
+                                                  const uint8_t *__restrict__ base, int NB, int lane,
+                                                  float (&accf)[4], uint32_t (&acci)[4])
+{
+    constexpr int ES = U8 ? 1 : 4;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { accf[i] = 0.0f; acci[i] = 0u; }
+    // The empty asm statement pins the accumulators once per row: integer sums may be
+    // reassociated freely, and left alone the compiler turns the block into one flat sum,
+    // reads every table entry first and spills. A row's 32 table reads stay in flight together.
+    auto pin = [&]() {
+        if constexpr (U8) asm volatile("" : "+v"(acci[0]), "+v"(acci[1]), "+v"(acci[2]), "+v"(acci[3]));
+        else asm volatile("" : "+v"(accf[0]), "+v"(accf[1]), "+v"(accf[2]), "+v"(accf[3]));
+    };
+    auto plane = [&](uint32_t w, const unsigned char *t) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t byte = (w >> (8 * i)) & 0xffu;
+            if constexpr (U8) {
+                acci[i] += (uint32_t)t[byte & 15u] + (uint32_t)t[16 + (byte >> 4)];
+            } else {
+                const float *T = (const float *)t;
+                const float v = __fadd_rn(T[byte & 15u], T[16 + (byte >> 4)]);
+                accf[i] = __fadd_rn(accf[i], v);
+            }
+        }
+    };
+    if constexpr (NBT != 0) {
+#pragma unroll
+        for (int j = 0; j < NBT / 4; ++j) {
+            const unsigned char *t = tbl + (size_t)j * 128 * ES;
+            plane(regs.rows[j].x, t);
+            plane(regs.rows[j].y, t + 32 * ES);
+            plane(regs.rows[j].z, t + 64 * ES);
+            plane(regs.rows[j].w, t + 96 * ES);
+            pin();
+        }
+#pragma unroll
+        for (int tt = 0; tt < NBT % 4; ++tt) plane(regs.tails[tt], tbl + (size_t)((NBT / 4) * 4 + tt) * 32 * ES);
+    } else {
+        const int nfull = NB / 4, ntail = NB % 4;
+        const unsigned char *t = tbl;
+        const uint4 *rowp = (const uint4 *)base + lane;
+        if (nfull > 0) {
+            uint4 cur = rowp[0];
+            for (int j = 0; j < nfull; ++j) {
+                const uint4 nxt = j + 1 < nfull ? rowp[(size_t)(j + 1) * 64] : cur;
+                plane(cur.x, t);
+                plane(cur.y, t + 32 * ES);
+                plane(cur.z, t + 64 * ES);
+                plane(cur.w, t + 96 * ES);
+                t += 128 * ES;
+                cur = nxt;
+                pin();
+            }
+        }
+        for (int tt = 0; tt < ntail; ++tt) {
+            plane(((const uint32_t *)(base + (size_t)nfull * 1024 + (size_t)tt * 256))[lane], t);
+            t += 32 * ES;
+        }
+    }
+}
+
+// The same for 4-bit codes, with the 16-entry tables themselves in LDS instead of
+// the 256-entry byte tables: twice the lookups, but the 16 entries of a table sit
+// in 16 different banks, so a wave's reads never conflict (random reads of a
+// 256-entry table cost about three times as many LDS cycles each), and there is
+// no 6400-entry table to build per workgroup. The two entries of a byte are added
+// first, then accumulated, exactly as the byte tables do.
+template <bool U8, int NBT>
+__global__ void __launch_bounds__(1024)
+block_max_nibble_kernel(const ScanParams p)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int n_waves = blockDim.x >> 6;
+    const int NB = NBT ? NBT : p.NB;
+    const int q = blockIdx.y;
+    const int64_t blk = (int64_t)blockIdx.x * n_waves + wave;
+
+    const bool have = blk < p.n_blocks;
+    BlockRegs<NBT> regs;
+    if (have) load_block<NBT>(regs, p.codes, blk, lane); // in flight while the tables are filled
+    nibble_tables_fill<U8>(smem, p, q, NB);
+    __syncthreads();
+    if (!have) return;
+
+    float accf[4];
+    uint32_t acci[4];
+    nibble_accumulate<U8, NBT>(smem, regs, p.codes + (size_t)blk * 256 * NB, NB, lane, accf, acci);
+    uint32_t best = 0;
+    int best_i = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int64_t slot = blk * 256 + 4 * lane + i;
+        uint32_t ord = U8 ? (acci[i] + 1u) : ord_from_f32(accf[i]);
+        if (slot >= p.n_valid) ord = 0u;
+        if (ord > best) { best = ord; best_i = i; }
+    }
+    uint32_t wmax = best;
+#pragma unroll
+    for (int m = 32; m > 0; m >>= 1) {
+        const uint32_t o = (uint32_t)__shfl_xor((int)wmax, m, 64);
+        wmax = o > wmax ? o : wmax;
+    }
+    const u64 owners = __builtin_amdgcn_ballot_w64(best == wmax);
+    const int owner = __builtin_ctzll(owners);
+    if (lane == owner)
+        p.block_max[(size_t)q * p.n_blocks + blk] =
+            wmax ? make_key(wmax, (int32_t)(blk * 256 + 4 * lane + best_i)) : 0ull;
+}
+
+// After the block-maxima scan, for a handful of queries, three short kernels:
+//  A. select_blocks_kernel (one workgroup per query): t1 = the R-th largest block
+//     maximum (exact, wg_select_threshold); the blocks whose maximum is >= t1 are listed.
+//  B. rescan_blocks_kernel (one wave per listed block, spread over the chip): every
+//     point with key >= t1 goes to a candidate buffer (at least R points qualify: the
+//     block maxima themselves).
+//  C. small_batch_final_kernel (one workgroup per query): t2 = the R-th largest
+//     candidate; the R candidates >= t2 are ranked by counting, (reorder) re-scored
+//     exactly, <q, x> as an fp32 fma chain, and the k best are written out.
+
+__global__ void __launch_bounds__(1024)
+select_blocks_kernel(const u64 *__restrict__ block_max, int64_t n_blocks, int R, int32_t *__restrict__ sel_blk,
+                     SmallMeta *__restrict__ meta)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    WgSelectScratch *sel = (WgSelectScratch *)smem;
+    __shared__ uint32_t n_sel;
+    const int tid = threadIdx.x, nt = blockDim.x;
+    const int q = blockIdx.x;
+    const u64 *bm = block_max + (size_t)q * n_blocks;
+    if (tid == 0) n_sel = 0u;
+    const u64 t1 = wg_select_threshold(bm, n_blocks, R, sel);
+    __syncthreads();
+    for (int64_t b = tid; b < n_blocks; b += nt) {
+        const u64 key = bm[b];
+        if (key >= t1 && key) sel_blk[(size_t)q * R + atomicAdd(&n_sel, 1u)] = (int32_t)b;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        meta[q].t1 = t1;
+        meta[q].n_sel = n_sel;
+        meta[q].n_cand = 0u;
+    }
+}
+
+// NIB: 4-bit codes with the 16-entry tables in LDS; else 256-entry byte tables.
+template <bool U8, int NBT, bool NIB>
+__global__ void __launch_bounds__(256)
+rescan_blocks_kernel(const ScanParams p, const FinishParams f)
+{
+    typedef uint32_t entry_t;
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n_waves = blockDim.x >> 6;
+    const int NB = NBT ? NBT : p.NB;
+    const int q = blockIdx.y;
+    const int j = blockIdx.x * n_waves + wave;
+    const int n_sel = (int)f.meta[q].n_sel;
+    if ((int)(blockIdx.x * n_waves) >= n_sel) return; // whole workgroup idle
+    const bool have = j < n_sel;
+    const int64_t blk = have ? f.sel_blk[(size_t)q * p.R + j] : 0;
+    BlockRegs<NBT> regs;
+    if (have) load_block<NBT>(regs, p.codes, blk, lane);
+    if (NIB) nibble_tables_fill<U8>(smem, p, q, NB);
+    else build_tables<1, U8>((entry_t *)smem, p, q, NB);
+    __syncthreads();
+    if (!have) return;
+    float sf[4];
+    uint32_t si[4];
+    if (NIB) {
+        nibble_accumulate<U8, NBT>(smem, regs, p.codes + (size_t)blk * 256 * NB, NB, lane, sf, si);
+    } else {
+        entry_t acc[4];
+        accumulate_block<1, U8, NBT>((const entry_t *)smem, regs, p.codes, blk, NB, lane, acc);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { si[i] = acc[i]; sf[i] = __uint_as_float(acc[i]); }
+    }
+    const u64 t1 = f.meta[q].t1;
+    u64 *cand = f.cand + (size_t)q * f.cand_stride;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int64_t slot = blk * 256 + 4 * lane + i;
+        const uint32_t ord = U8 ? (si[i] + 1u) : ord_from_f32(sf[i]);
+        const u64 key = make_key(ord, (int32_t)slot);
+        const bool hit = slot < p.n_valid && key >= t1;
+        const u64 mask = __builtin_amdgcn_ballot_w64(hit);
+        if (mask == 0ull) continue;
+        uint32_t base_pos = 0;
+        if (lane == 0) base_pos = atomicAdd(&f.meta[q].n_cand, (uint32_t)__builtin_popcountll(mask));
+        base_pos = (uint32_t)__shfl((int)base_pos, 0, 64);
+        if (hit) cand[base_pos + __builtin_popcountll(mask & ((1ull << lane) - 1ull))] = key;
+    }
+}
+
+// key_kind 1: the keys carry integer sums of 8-bit table codes (flat index); 0: fp32 scores.
+__global__ void __launch_bounds__(1024)
+small_batch_final_kernel(const FinishParams f, int R, int key_kind, const float *__restrict__ scale,
+                         const float *__restrict__ bias)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x, nt = blockDim.x;
+    const int q = blockIdx.x;
+
+    // LDS: final keys [R] x2 | counter | query [d] | then a region used first for the
+    // selection scratch, later for staging rows of x
+    u64 *fin = (u64 *)smem;                                                       // [R] candidates
+    u64 *fin2 = fin + R;                                                          // [R] re-scored
+    uint32_t *counters = (uint32_t *)(fin2 + R);                                  // [4]
+    float *qs = (float *)(counters + 4);                                          // [d]
+    unsigned char *region = (unsigned char *)(((uintptr_t)(qs + f.d) + 15) & ~(uintptr_t)15);
+    WgSelectScratch *sel = (WgSelectScratch *)region;
+    float *stage = (float *)region;                                               // [stage_rows][d + 1]
+
+    for (int l = tid; l < f.d; l += nt) qs[l] = f.queries[(size_t)q * f.d + l];
+    if (tid < 4) counters[tid] = 0u;
+    const int n_cand = (int)f.meta[q].n_cand;
+    const u64 *cand = f.cand + (size_t)q * f.cand_stride;
+    const u64 t2 = wg_select_threshold(cand, n_cand, R, sel);
+    __syncthreads();
+    for (int i = tid; i < n_cand; i += nt) {
+        const u64 key = cand[i];
+        if (key >= t2) fin[atomicAdd(&counters[0], 1u)] = key;
+    }
+    __syncthreads();
+    const int n_fin = (int)counters[0]; // min(R, n_cand)
+    const int k = f.k;
+    if (!f.reorder) {
+        for (int j = tid; j < n_fin; j += nt) {
+            const u64 mine = fin[j];
+            int rank = 0;
+#pragma unroll 8
+            for (int t = 0; t < n_fin; ++t) rank += fin[t] > mine;
+            if (rank < k) {
+                f.ids_out[(size_t)q * k + rank] = key_id(mine);
+                f.scores_out[(size_t)q * k + rank] =
+                    key_kind ? __fmaf_rn((float)(int)(key_ord(mine) - 1u), scale[q], bias[q]) : f32_from_ord(key_ord(mine));
+            }
+        }
+    } else {
+        // exact re-scoring: the candidates' rows are copied to LDS by the whole workgroup
+        // (coalesced, all loads in flight at once), then one thread per candidate runs the
+        // fma chain in index order. Row stride d + 1 keeps the threads on different banks.
+        const int d = f.d, ld = f.d + 1;
+        for (int r0 = 0; r0 < n_fin; r0 += f.stage_rows) {
+            const int rows = n_fin - r0 < f.stage_rows ? n_fin - r0 : f.stage_rows;
+            __syncthreads();
+            for (int e = tid; e < rows * d; e += nt) {
+                const int r = e / d, l = e - r * d;
+                stage[r * ld + l] = f.x[(size_t)key_id(fin[r0 + r]) * d + l];
+            }
+            __syncthreads();
+            for (int r = tid; r < rows; r += nt) {
+                const float *row = stage + r * ld;
+                float sc = 0.0f;
+#pragma unroll 4
+                for (int l = 0; l < d; ++l) sc = __fmaf_rn(qs[l], row[l], sc);
+                fin2[r0 + r] = make_key(ord_from_f32(sc), key_id(fin[r0 + r]));
+            }
+        }
+        __syncthreads();
+        for (int j = tid; j < n_fin; j += nt) {
+            const u64 mine = fin2[j];
+            int rank = 0;
+#pragma unroll 8
+            for (int t = 0; t < n_fin; ++t) rank += fin2[t] > mine;
+            if (rank < k) {
+                f.ids_out[(size_t)q * k + rank] = key_id(mine);
+                f.scores_out[(size_t)q * k + rank] = f32_from_ord(key_ord(mine));
+            }
+        }
+    }
+    for (int j = n_fin + tid; j < k; j += nt) { // fewer than k candidates exist
+        f.ids_out[(size_t)q * k + j] = -1;
+        f.scores_out[(size_t)q * k + j] = -INFINITY;
+    }
+}
+
 // ---- host side ---------------------------------------------------------------
 
 static size_t scan_lds_bytes(int NB, bool u8, int qt, int waves, int ns)
@@ -316,17 +714,19 @@ static size_t scan_lds_bytes(int NB, bool u8, int qt, int waves, int ns)
     return (size_t)NB * 256 * words * 4 + (size_t)waves * qt * (64 * ns + 64) * 8;
 }
 
-int scan_pick_shape(int NB, bool u8, int ns, int B, bool ivf, int qt_hint, int waves_hint,
+int scan_pick_shape(int NB, bool u8, int ns, int B, bool single, int qt_hint, int waves_hint,
                     ScanShape *out)
 {
-    const size_t lds_max = 160 * 1024;
+    const size_t lds_max = kMaxDynLds;
     int qts_f[] = {4, 1, 0}, qts_u[] = {8, 1, 0};
     const int *qts = u8 ? qts_u : qts_f;
     for (int i = 0; qts[i]; ++i) {
         int qt = qts[i];
-        if (ivf && qt != 1) continue;
-        if (qt_hint) { if (qt != qt_hint) continue; }
-        else if (qt > 1 && B < qt) continue; // small batches: one query per workgroup
+        if (single && qt != 1) continue;
+        if (!single) {
+            if (qt_hint) { if (qt != qt_hint) continue; }
+            else if (qt > 1 && B < qt) continue; // small batches: one query per workgroup
+        }
         int wlist[] = {16, 8, 4, 2, 1, 0};
         for (int j = 0; wlist[j]; ++j) {
             int w = wlist[j];
@@ -344,51 +744,195 @@ int scan_pick_shape(int NB, bool u8, int ns, int B, bool ivf, int qt_hint, int w
     return AVQ_EINVAL;
 }
 
-template <int QT, bool U8, int NBT, bool IVF>
+template <class K>
+static int set_max_lds(K kern, bool *done)
+{
+    if (!*done) {
+        AVQ_HIP(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynLds));
+        *done = true;
+    }
+    return AVQ_OK;
+}
+
+template <int QT, bool U8, int NBT, int MODE>
 static int launch_one(const ScanParams &p, const ScanShape &s, int grid, hipStream_t st)
 {
-    auto kern = adc_scan_kernel<QT, U8, NBT, IVF>;
+    auto kern = adc_scan_kernel<QT, U8, NBT, MODE>;
     static bool attr_done = false; // per instantiation
-    if (!attr_done) {
-        AVQ_HIP(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    160 * 1024));
-        attr_done = true;
-    }
+    AVQ_TRY(set_max_lds(kern, &attr_done));
     hipLaunchKernelGGL(kern, dim3(grid), dim3(s.waves * 64), s.lds_bytes, st, p);
     AVQ_HIP(hipGetLastError());
     return AVQ_OK;
 }
 
-template <int QT, bool U8, bool IVF>
+template <int QT, bool U8, int MODE>
 static int launch_nb(const ScanParams &p, const ScanShape &s, int grid, hipStream_t st)
 {
     switch (p.NB) {
-    case 8: return launch_one<QT, U8, 8, IVF>(p, s, grid, st);
-    case 25: return launch_one<QT, U8, 25, IVF>(p, s, grid, st);
-    case 32: return launch_one<QT, U8, 32, IVF>(p, s, grid, st);
-    default: return launch_one<QT, U8, 0, IVF>(p, s, grid, st);
+    case 8: return launch_one<QT, U8, 8, MODE>(p, s, grid, st);
+    case 25: return launch_one<QT, U8, 25, MODE>(p, s, grid, st);
+    case 32: return launch_one<QT, U8, 32, MODE>(p, s, grid, st);
+    default: return launch_one<QT, U8, 0, MODE>(p, s, grid, st);
     }
 }
 
-int launch_scan(const ScanParams &p, bool u8, bool ivf, const ScanShape &s, hipStream_t st)
+int launch_scan(const ScanParams &p, bool u8, int mode, const ScanShape &s, hipStream_t st)
 {
-    if (ivf) {
-        if (s.qt != 1) { set_error("scan: partitioned scan needs qt == 1"); return AVQ_EINVAL; }
+    if (mode == SCAN_LEAVES || mode == SCAN_BLOCKLIST) {
+        if (s.qt != 1) { set_error("scan: this mode needs qt == 1"); return AVQ_EINVAL; }
         const int grid = p.B;
-        return u8 ? launch_nb<1, true, true>(p, s, grid, st) : launch_nb<1, false, true>(p, s, grid, st);
+        if (mode == SCAN_LEAVES)
+            return u8 ? launch_nb<1, true, MODE_LEAVES>(p, s, grid, st) : launch_nb<1, false, MODE_LEAVES>(p, s, grid, st);
+        return u8 ? launch_nb<1, true, MODE_BLOCKLIST>(p, s, grid, st)
+                  : launch_nb<1, false, MODE_BLOCKLIST>(p, s, grid, st);
     }
     const int64_t grid64 = (int64_t)p.n_tiles * p.n_chunks;
     if (grid64 > 0x7fffffff) { set_error("scan: grid too large"); return AVQ_EINVAL; }
     const int grid = (int)grid64;
     if (!u8) {
-        if (s.qt == 1) return launch_nb<1, false, false>(p, s, grid, st);
-        if (s.qt == 4) return launch_nb<4, false, false>(p, s, grid, st);
+        if (s.qt == 1) return launch_nb<1, false, MODE_CHUNK>(p, s, grid, st);
+        if (s.qt == 4) return launch_nb<4, false, MODE_CHUNK>(p, s, grid, st);
     } else {
-        if (s.qt == 1) return launch_nb<1, true, false>(p, s, grid, st);
-        if (s.qt == 8) return launch_nb<8, true, false>(p, s, grid, st);
+        if (s.qt == 1) return launch_nb<1, true, MODE_CHUNK>(p, s, grid, st);
+        if (s.qt == 8) return launch_nb<8, true, MODE_CHUNK>(p, s, grid, st);
     }
     set_error("scan: unsupported query tile %d", s.qt);
     return AVQ_EINVAL;
+}
+
+template <bool U8, int NBT>
+static int launch_block_max_one(const ScanParams &p, int waves, hipStream_t st)
+{
+    auto kern = block_max_kernel<U8, NBT>;
+    static bool attr_done = false;
+    AVQ_TRY(set_max_lds(kern, &attr_done));
+    const size_t lds = (size_t)p.NB * 256 * 4;
+    const unsigned gx = (unsigned)((p.n_blocks + waves - 1) / waves);
+    hipLaunchKernelGGL(kern, dim3(gx, p.B), dim3(waves * 64), lds, st, p);
+    AVQ_HIP(hipGetLastError());
+    return AVQ_OK;
+}
+
+template <bool U8>
+static int launch_block_max_nb(const ScanParams &p, int waves, hipStream_t st)
+{
+    switch (p.NB) {
+    case 8: return launch_block_max_one<U8, 8>(p, waves, st);
+    case 25: return launch_block_max_one<U8, 25>(p, waves, st);
+    case 32: return launch_block_max_one<U8, 32>(p, waves, st);
+    default: return launch_block_max_one<U8, 0>(p, waves, st);
+    }
+}
+
+template <bool U8, int NBT>
+static int launch_block_max_nibble_one(const ScanParams &p, hipStream_t st)
+{
+    const int waves = 4;
+    const size_t lds = (size_t)2 * p.NB * 16 * (U8 ? 1 : 4);
+    const unsigned gx = (unsigned)((p.n_blocks + waves - 1) / waves);
+    hipLaunchKernelGGL((block_max_nibble_kernel<U8, NBT>), dim3(gx, p.B), dim3(waves * 64), lds, st, p);
+    AVQ_HIP(hipGetLastError());
+    return AVQ_OK;
+}
+
+template <bool U8>
+static int launch_block_max_nibble_nb(const ScanParams &p, hipStream_t st)
+{
+    switch (p.NB) {
+    case 8: return launch_block_max_nibble_one<U8, 8>(p, st);
+    case 25: return launch_block_max_nibble_one<U8, 25>(p, st);
+    case 32: return launch_block_max_nibble_one<U8, 32>(p, st);
+    default: return launch_block_max_nibble_one<U8, 0>(p, st);
+    }
+}
+
+static bool use_nibble_tables(const ScanParams &p) { return p.bits == 4 && (size_t)p.M * 64 <= 60 * 1024; }
+
+// LDS of the final kernel: keys, query, then max(selection scratch, row staging).
+static size_t small_final_fixed_bytes(int R, int d)
+{
+    return (((size_t)R * 16 + 16 + (size_t)d * 4) + 15) & ~(size_t)15;
+}
+
+int small_finish_stage_rows(const ScanParams &p, int d, bool u8)
+{
+    (void)u8;
+    const size_t row = (size_t)(d + 1) * 4;
+    const size_t avail = kMaxDynLds - small_final_fixed_bytes(p.R, d) - 256;
+    size_t want = (size_t)p.R * row;                       // all candidates at once if they fit
+    if (want > 96 * 1024) want = 96 * 1024;
+    if (want < sizeof(WgSelectScratch)) want = sizeof(WgSelectScratch);
+    if (want > avail) want = avail;
+    const int rows = (int)(want / row);
+    return rows < 1 ? 1 : (rows > p.R ? p.R : rows);
+}
+
+template <bool U8, int NBT, bool NIB>
+static int launch_rescan_one(const ScanParams &p, const FinishParams &f, hipStream_t st)
+{
+    auto kern = rescan_blocks_kernel<U8, NBT, NIB>;
+    static bool attr_done = false;
+    AVQ_TRY(set_max_lds(kern, &attr_done));
+    const int waves = 4;
+    const size_t lds = NIB ? (size_t)2 * p.NB * 16 * (U8 ? 1 : 4) : (size_t)p.NB * 256 * 4;
+    hipLaunchKernelGGL(kern, dim3((p.R + waves - 1) / waves, p.B), dim3(waves * 64), lds, st, p, f);
+    AVQ_HIP(hipGetLastError());
+    return AVQ_OK;
+}
+
+template <bool U8>
+static int launch_rescan_u(const ScanParams &p, const FinishParams &f, hipStream_t st)
+{
+    if (use_nibble_tables(p)) {
+        switch (p.NB) {
+        case 8: return launch_rescan_one<U8, 8, true>(p, f, st);
+        case 25: return launch_rescan_one<U8, 25, true>(p, f, st);
+        case 32: return launch_rescan_one<U8, 32, true>(p, f, st);
+        default: return launch_rescan_one<U8, 0, true>(p, f, st);
+        }
+    }
+    if (p.NB == 32) return launch_rescan_one<U8, 32, false>(p, f, st);
+    return launch_rescan_one<U8, 0, false>(p, f, st);
+}
+
+int launch_small_select(const ScanParams &p, const FinishParams &f, hipStream_t st)
+{
+    static bool attr = false;
+    AVQ_TRY(set_max_lds(select_blocks_kernel, &attr));
+    hipLaunchKernelGGL(select_blocks_kernel, dim3(p.B), dim3(1024), sizeof(WgSelectScratch), st, p.block_max,
+                       p.n_blocks, p.R, f.sel_blk, f.meta);
+    AVQ_HIP(hipGetLastError());
+    return AVQ_OK;
+}
+
+int launch_small_rescan(const ScanParams &p, const FinishParams &f, bool u8, hipStream_t st)
+{
+    if ((size_t)p.NB * 256 * 4 > kMaxDynLds && !use_nibble_tables(p)) {
+        set_error("small-batch rescan: tables do not fit LDS");
+        return AVQ_EINVAL;
+    }
+    return u8 ? launch_rescan_u<true>(p, f, st) : launch_rescan_u<false>(p, f, st);
+}
+
+int launch_small_final(const ScanParams &p, const FinishParams &f, bool u8, hipStream_t st)
+{
+    static bool attr = false;
+    AVQ_TRY(set_max_lds(small_batch_final_kernel, &attr));
+    size_t region = sizeof(WgSelectScratch);
+    const size_t stage = (size_t)f.stage_rows * (f.d + 1) * 4;
+    if (stage > region) region = stage;
+    const size_t lds = small_final_fixed_bytes(p.R, f.d) + region + 16;
+    hipLaunchKernelGGL(small_batch_final_kernel, dim3(p.B), dim3(1024), lds, st, f, p.R, u8 ? 1 : 0, p.scale, p.bias);
+    AVQ_HIP(hipGetLastError());
+    return AVQ_OK;
+}
+
+int launch_block_max(const ScanParams &p, bool u8, int waves, hipStream_t st)
+{
+    if (use_nibble_tables(p))
+        return u8 ? launch_block_max_nibble_nb<true>(p, st) : launch_block_max_nibble_nb<false>(p, st);
+    if ((size_t)p.NB * 256 * 4 > kMaxDynLds) { set_error("block max: tables do not fit LDS"); return AVQ_EINVAL; }
+    return u8 ? launch_block_max_nb<true>(p, waves, st) : launch_block_max_nb<false>(p, waves, st);
 }
 
 } // namespace avq

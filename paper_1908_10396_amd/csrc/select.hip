@@ -41,6 +41,52 @@ int launch_merge_partials(const u64 *partial, int nq, int n_chunks, int ns, u64 
     return AVQ_OK;
 }
 
+// ---- top-R of an unsorted key array (block maxima) ---------------------------------
+
+// One workgroup per query: every wave filters its share of the keys into its own
+// list, then the lists are merged pairwise up a tree.
+__global__ void __launch_bounds__(1024)
+select_keys_kernel(const u64 *__restrict__ keys, int64_t n, int ns, int R, u64 *__restrict__ out)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int C = 64 * ns;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n_waves = blockDim.x >> 6;
+    const int q = blockIdx.x;
+    u64 *lists = (u64 *)smem;                       // [W][C]
+    u64 *pends = lists + (size_t)n_waves * C;       // [W][64]
+    u64 *mine = lists + (size_t)wave * C;
+    u64 *pend = pends + (size_t)wave * 64;
+    wave_list_clear(mine, ns);
+    u64 thr = 0ull;
+    int cnt = 0;
+    const u64 *src = keys + (size_t)q * n;
+    for (int64_t base = (int64_t)wave * 64; base < n; base += (int64_t)n_waves * 64) {
+        const int64_t i = base + lane;
+        const u64 key = i < n ? src[i] : 0ull;
+        const bool hit = key > thr;
+        if (__builtin_amdgcn_ballot_w64(hit) == 0ull) continue;
+        if (wave_push(mine, ns, pend, cnt, hit, key)) thr = mine[R - 1];
+    }
+    if (cnt > 0) wave_list_flush(mine, ns, pend, cnt);
+    for (int stride = 1; stride < n_waves; stride *= 2) {
+        __syncthreads();
+        if ((wave % (2 * stride)) == 0 && wave + stride < n_waves)
+            wave_list_merge_from(mine, ns, lists + (size_t)(wave + stride) * C);
+    }
+    if (wave == 0)
+        for (int i = lane; i < C; i += 64) out[(size_t)q * C + i] = mine[i];
+}
+
+int launch_select_keys(const u64 *keys, int nq, int64_t n, int ns, int R, u64 *out, hipStream_t st)
+{
+    int waves = 16;
+    while (waves > 1 && (int64_t)waves * 128 > n) waves /= 2;
+    const size_t lds = (size_t)waves * (64 * ns + 64) * 8;
+    hipLaunchKernelGGL(select_keys_kernel, dim3(nq), dim3(waves * 64), lds, st, keys, n, ns, R, out);
+    AVQ_HIP(hipGetLastError());
+    return AVQ_OK;
+}
+
 // ---- exact re-scoring and final top-k -------------------------------------------
 
 // <q, x> as an fp32 fma chain in index order. qs: query in LDS.
@@ -217,12 +263,12 @@ int launch_brute_force(const float *x, int64_t n, int d, const float *queries, i
     };
     if (lds_for(8) <= 96 * 1024) {
         AVQ_HIP(hipFuncSetAttribute((const void *)brute_kernel<8>,
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynLds));
         hipLaunchKernelGGL(brute_kernel<8>, dim3(n_chunks, (nq + 7) / 8), dim3(waves * 64),
                            lds_for(8), st, x, n, d, queries, nq, ns, k, ppc, n_chunks, partial_ws);
-    } else if (lds_for(1) <= 160 * 1024) {
+    } else if (lds_for(1) <= kMaxDynLds) {
         AVQ_HIP(hipFuncSetAttribute((const void *)brute_kernel<1>,
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynLds));
         hipLaunchKernelGGL(brute_kernel<1>, dim3(n_chunks, nq), dim3(waves * 64), lds_for(1), st, x,
                            n, d, queries, nq, ns, k, ppc, n_chunks, partial_ws);
     } else {

@@ -192,7 +192,7 @@ int kmeans_device(const float *x, int64_t n, int ld, int col0, int dim, int k, i
                            col0, dim, k, idx_dev, resid_centers, resid_assign, centers);
         AVQ_HIP(hipGetLastError());
         AVQ_HIP(hipFuncSetAttribute((const void *)nearest_kernel<true>,
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynLds));
         const unsigned grid = (unsigned)((n + bs - 1) / bs);
         for (int it = 0; it < iters; ++it) {
             AVQ_HIP(hipMemsetAsync(sums, 0, sizeof(double) * (size_t)k * dim, st));
@@ -226,7 +226,7 @@ int launch_assign_nearest(const float *x, int64_t n, int d, const float *centers
         return AVQ_EINVAL;
     }
     AVQ_HIP(hipFuncSetAttribute((const void *)nearest_kernel<false>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynLds));
     hipLaunchKernelGGL(nearest_kernel<false>, dim3((unsigned)((n + bs - 1) / bs)), dim3(bs),
                        (size_t)bs * d * sizeof(double), st, x, n, d, 0, d, k, (const float *)nullptr,
                        (const int32_t *)nullptr, centers, (double *)nullptr,

@@ -114,12 +114,31 @@ def test_search_is_deterministic_and_independent_of_launch_shape(case):
     again = [t.cpu().numpy() for t in idx.search(qd, 10, 100, 0)]
     np.testing.assert_array_equal(base[0], again[0])
     np.testing.assert_array_equal(base[1], again[1])
-    for name, val in (("scan_target_wgs", 64), ("scan_target_wgs", 4096), ("scan_waves", 2), ("scan_qt", 1)):
+    for name, val in (("scan_target_wgs", 64), ("scan_target_wgs", 4096), ("scan_waves", 2), ("scan_qt", 1),
+                      ("small_batch_max", 1), ("small_batch_max", 1000)):
         idx.set_tuning(name, val)
         got = [t.cpu().numpy() for t in idx.search(qd, 10, 100, 0)]
         np.testing.assert_array_equal(base[0], got[0])
         np.testing.assert_array_equal(base[1], got[1])
         idx.set_tuning(name, 0)
+
+
+@pytest.mark.parametrize("lut_mode", [0, 1])
+def test_small_batch_paths_agree_with_oracle(case, lut_mode):
+    # a handful of queries: block-maxima scan + fused finish kernel (default), its
+    # three-kernel variant, and the batch kernels forced onto the same queries
+    idx, xd = make_index(case)
+    nq = 5
+    q = case["q"][:nq]
+    qd = dev(q)
+    for k, R in ((10, 100), (10, 0), (100, 512)):
+        oi, os_ = oracle.search(case["x"], case["cb"], case["codes"], case["bits"], q, k, R, lut_mode)
+        for name, val in (("small_batch_impl", 0), ("small_batch_impl", 1), ("small_batch_max", 1)):
+            idx.set_tuning(name, val)
+            ids, sc = idx.search(qd, k, R, lut_mode)
+            np.testing.assert_array_equal(ids.cpu().numpy(), oi, err_msg="%s=%d" % (name, val))
+            np.testing.assert_array_equal(sc.cpu().numpy(), os_, err_msg="%s=%d" % (name, val))
+            idx.set_tuning(name, 0)
 
 
 def test_brute_force_matches(case):
