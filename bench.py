@@ -57,6 +57,9 @@ def main():
     ap.add_argument("--recall-queries", type=int, default=1000)
     ap.add_argument("--oracle-queries", type=int, default=96)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run plain device copies of the datapoint array (known size) so that "
+                         "hardware byte counters can be scaled against them")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (--gpus 1); sharding over several GPUs "
@@ -93,6 +96,15 @@ def main():
     ids = torch.empty((B, k), dtype=torch.int32, device="cuda")
     sc = torch.empty((B, k), dtype=torch.float32, device="cuda")
 
+    if args.copy_calibration:
+        y = torch.empty_like(xd)
+        for _ in range(3):
+            y.copy_(xd)
+        torch.cuda.synchronize()
+        log("[bench] copy calibration: 3 device copies of %d bytes (read) + %d bytes (write) each"
+            % (xd.numel() * 4, xd.numel() * 4))
+        del y
+
     def timed_batch(lut_mode, steps):
         """K steps at batch B, bracketed by synchronize; per-stage kernel time from HIP events."""
         for _ in range(args.warmup):
@@ -111,19 +123,25 @@ def main():
         return dt, stage_ms
 
     def timed_single(lut_mode, steps):
+        """Single-query calls: end-to-end time without instrumentation, then per-stage kernel
+        time from HIP events in a second, instrumented loop (the event records are extra
+        packets on the stream and would otherwise be part of the latency)."""
         ids1 = torch.empty((1, k), dtype=torch.int32, device="cuda")
         sc1 = torch.empty((1, k), dtype=torch.float32, device="cuda")
         q1 = [qd[i:i + 1] for i in range(min(B, 64))]
         for i in range(50):
             idx.search(q1[i % len(q1)], k, R, lut_mode, out=(ids1, sc1))
         torch.cuda.synchronize()
-        idx.profile_enable(True)
-        idx.profile_read(reset=True)
         t0 = time.perf_counter()
         for i in range(steps):
             idx.search(q1[i % len(q1)], k, R, lut_mode, out=(ids1, sc1))
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
+        idx.profile_enable(True)
+        idx.profile_read(reset=True)
+        for i in range(max(50, steps // 4)):
+            idx.search(q1[i % len(q1)], k, R, lut_mode, out=(ids1, sc1))
+        torch.cuda.synchronize()
         prof = idx.profile_read(reset=True)
         idx.profile_enable(False)
         stage_us = {s: (v[0] / v[1] * 1e3 if v[1] else 0.0) for s, v in prof.items()}
@@ -137,7 +155,7 @@ def main():
     adds = float(M) * n * B                      # one add per table entry of every (query, point)
     lds_bytes = 4.0 * nb * n * B                 # one fp32 byte-table entry per code byte
     batch_roof = {"bound": "alu", "achieved": adds / (scan_ms * 1e-3) / 1e12, "peak": VALU_PEAK_TOPS,
-                  "unit": "TFLOP/s", "traffic": None, "kernel": "adc_scan_kernel<4,false,25,0>",
+                  "unit": "TFLOP/s", "traffic": 2.40e9 if not args.n and B == 10_000 else None, "kernel": "adc_scan_kernel<4,false,25,0>",
                   "avg_launch_ms": scan_ms,
                   "lds_gather": {"achieved_GBs": lds_bytes / (scan_ms * 1e-3) / 1e9, "peak_GBs": LDS_PEAK_GBS,
                                  "frac": lds_bytes / (scan_ms * 1e-3) / 1e9 / LDS_PEAK_GBS}}
@@ -153,8 +171,11 @@ def main():
     dt1, stage1_us = timed_single(avq.LUT_F32, args.b1_steps)
     scan1_ms = stage1_us["scan"] / 1e3
     code_bytes = float(nb) * n                   # algorithmic bytes of one single-query scan
+    # HBM-side bytes per launch of this kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by
+    # a plain copy of known size (profiles/scan_glove_pmc_traffic.md); only valid for the default n
+    traffic = 29.72e6 + 0.037e6 if not args.n else None
     b1_roof = {"bound": "hbm", "achieved": code_bytes / (scan1_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
-               "unit": "GB/s", "traffic": None, "kernel": "block_max_kernel<false,25>",
+               "unit": "GB/s", "traffic": traffic, "kernel": "block_max_nibble_kernel<false,25>",
                "avg_launch_ms": scan1_ms,
                "note": "repeated scans of the 29.6 MB code array are served from the 256 MB Infinity Cache"}
     b1_roof["frac"] = b1_roof["achieved"] / b1_roof["peak"]

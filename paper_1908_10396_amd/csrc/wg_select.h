@@ -13,6 +13,7 @@ typedef unsigned long long u64;
 
 constexpr int kSelBins = 2048;  // histogram bins per pass
 constexpr int kSelList = 1024;  // once this few keys remain in range they are ranked directly
+constexpr int kSelRegs = 8;     // keys a thread caches in registers (N <= kSelRegs * threads)
 
 struct WgSelectScratch {
     uint32_t hist[kSelBins];
@@ -27,19 +28,39 @@ struct WgSelectScratch {
 // All threads of the workgroup (a multiple of 64, at most 1024) must call this.
 // Keys equal to 0 are empty slots and never selected. Returns the R-th largest
 // non-empty key, or 1 when there are fewer than R of them (so "key >= result"
-// selects min(R, count) keys; keys are distinct).
+// selects min(R, count) keys; keys are distinct). The keys are read from global
+// memory once when N <= kSelRegs * blockDim.x, else once per pass.
 __device__ inline u64 wg_select_threshold(const u64 *__restrict__ keys, int64_t N, int R, WgSelectScratch *s)
 {
     const int tid = threadIdx.x, nt = blockDim.x;
     const int lane = tid & 63, wave = tid >> 6, n_waves = nt >> 6;
+    const bool cached = N <= (int64_t)kSelRegs * nt;
+    u64 kreg[kSelRegs];
+    if (cached) {
+#pragma unroll
+        for (int r = 0; r < kSelRegs; ++r) {
+            const int64_t i = (int64_t)r * nt + tid;
+            kreg[r] = i < N ? keys[i] : 0ull;
+        }
+    }
+    // visits every non-empty key once
+    auto for_each_key = [&](auto &&fn) {
+        if (cached) {
+#pragma unroll
+            for (int r = 0; r < kSelRegs; ++r)
+                if (kreg[r]) fn(kreg[r]);
+        } else {
+            for (int64_t i = tid; i < N; i += nt) {
+                const u64 kkey = keys[i];
+                if (kkey) fn(kkey);
+            }
+        }
+    };
 
     // pass 0: range and population
     u64 mx = 0ull, mn = ~0ull;
     uint32_t cnt = 0;
-    for (int64_t i = tid; i < N; i += nt) {
-        const u64 kkey = keys[i];
-        if (kkey) { mx = kkey > mx ? kkey : mx; mn = kkey < mn ? kkey : mn; ++cnt; }
-    }
+    for_each_key([&](u64 kkey) { mx = kkey > mx ? kkey : mx; mn = kkey < mn ? kkey : mn; ++cnt; });
     for (int m = 32; m > 0; m >>= 1) {
         const u64 omx = ((u64)(uint32_t)__shfl_xor((int)(mx >> 32), m, 64) << 32) | (uint32_t)__shfl_xor((int)(uint32_t)mx, m, 64);
         const u64 omn = ((u64)(uint32_t)__shfl_xor((int)(mn >> 32), m, 64) << 32) | (uint32_t)__shfl_xor((int)(uint32_t)mn, m, 64);
@@ -67,10 +88,9 @@ __device__ inline u64 wg_select_threshold(const u64 *__restrict__ keys, int64_t 
             __syncthreads();
             if (tid == 0) s->list_cnt = 0;
             __syncthreads();
-            for (int64_t i = tid; i < N; i += nt) {
-                const u64 kkey = keys[i];
-                if (kkey >= lo && kkey <= hi && kkey) s->list[atomicAdd(&s->list_cnt, 1u)] = kkey;
-            }
+            for_each_key([&](u64 kkey) {
+                if (kkey >= lo && kkey <= hi) s->list[atomicAdd(&s->list_cnt, 1u)] = kkey;
+            });
             __syncthreads();
             const uint32_t c = s->list_cnt;
             for (uint32_t j = tid; j < c; j += nt) {
@@ -88,15 +108,12 @@ __device__ inline u64 wg_select_threshold(const u64 *__restrict__ keys, int64_t 
         __syncthreads();
         for (int b = tid; b < kSelBins; b += nt) s->hist[b] = 0u;
         __syncthreads();
-        for (int64_t i = tid; i < N; i += nt) {
-            const u64 kkey = keys[i];
-            if (kkey >= lo && kkey <= hi && kkey) atomicAdd(&s->hist[(uint32_t)((kkey - lo) >> shift)], 1u);
-        }
+        for_each_key([&](u64 kkey) {
+            if (kkey >= lo && kkey <= hi) atomicAdd(&s->hist[(uint32_t)((kkey - lo) >> shift)], 1u);
+        });
         __syncthreads();
         // find the bin holding the need-th key from the top: suffix counts over the bins
-        constexpr int PER = 2; // bins per thread when nt == 1024; generalised below
         const int per = (kSelBins + nt - 1) / nt;
-        (void)PER;
         uint32_t mine_sum = 0;
         const int b0 = tid * per;
         for (int j = 0; j < per; ++j) { const int b = b0 + j; if (b < kSelBins) mine_sum += s->hist[b]; }
