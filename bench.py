@@ -51,7 +51,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--batch", type=int, default=10_000)
+    ap.add_argument("--config", default="glove", choices=["tiny", "glove", "glove_ivf", "large4", "large8"],
+                    help="workload (default: the Glove-shaped one the headline metric is quoted on)")
+    ap.add_argument("--batch", type=int, default=0, help="queries per step (default: the configuration's)")
     ap.add_argument("--n", type=int, default=0, help="override the number of points (debugging)")
     ap.add_argument("--b1-steps", type=int, default=2000)
     ap.add_argument("--recall-queries", type=int, default=1000)
@@ -70,20 +72,35 @@ def main():
     import paper_1908_10396_amd as avq
     import synth_inputs as si
 
-    cfg = dict(si.CONFIGS["glove"])
+    cfg = dict(si.CONFIGS[args.config])
     if args.n:
         cfg["n"] = args.n
     n, d, M, bits, k, R = cfg["n"], cfg["d"], cfg["M"], cfg["bits"], cfg["k"], cfg["reorder_k"]
-    B = args.batch
+    B = args.batch or cfg["nq"]
     nb = (M * bits + 7) // 8
+    n_leaves = cfg.get("n_leaves", 0)
+    Lp = cfg.get("leaves_to_search", 0)
+    glove_default = args.config == "glove" and not args.n
 
     t0 = time.time()
-    x = si.make_data(cfg)
     q = si.make_queries(cfg, B)
-    log("[bench] generated %d x %d points and %d queries in %.1fs" % (n, d, B, time.time() - t0))
-    xd = torch.from_numpy(x).cuda()
     qd = torch.from_numpy(q).cuda()
-    idx = avq.Index(d, M, bits, T=cfg["T"], kmeans_iters=20, encode_passes=10, seed=cfg["seed"])
+    if n * d * 4 <= 8 << 30:
+        x = si.make_data(cfg)
+        xd = torch.from_numpy(x).cuda()
+    else:
+        # too large to hold twice on the host: generate chunk by chunk straight into HBM
+        x = None
+        xd = torch.empty((n, d), dtype=torch.float32, device="cuda")
+        centers = si.mixture_centers(cfg["n_comp"], d, cfg["seed"])
+        for c, lo, hi in si._chunks(n):
+            xd[lo:hi] = torch.from_numpy(si.mixture_chunk(c, hi - lo, d, centers, cfg["sigma"], cfg["seed"],
+                                                          si.STREAM_DATA, cfg.get("lognormal_sigma"))).cuda()
+            if c % 16 == 0:
+                log("[bench] generated %d of %d rows" % (hi, n))
+    log("[bench] generated %d x %d points and %d queries in %.1fs" % (n, d, B, time.time() - t0))
+    idx = avq.Index(d, M, bits, T=cfg["T"], kmeans_iters=20, encode_passes=10, seed=cfg["seed"],
+                    n_leaves=n_leaves, leaf_kmeans_iters=10)
     t0 = time.time()
     idx.train(xd[: min(n, si.CHUNK)])
     t_train = time.time() - t0
@@ -108,13 +125,13 @@ def main():
     def timed_batch(lut_mode, steps):
         """K steps at batch B, bracketed by synchronize; per-stage kernel time from HIP events."""
         for _ in range(args.warmup):
-            idx.search(qd, k, R, lut_mode, out=(ids, sc))
+            idx.search(qd, k, R, lut_mode, Lp, out=(ids, sc))
         torch.cuda.synchronize()
         idx.profile_enable(True)
         idx.profile_read(reset=True)
         t0 = time.perf_counter()
         for _ in range(steps):
-            idx.search(qd, k, R, lut_mode, out=(ids, sc))
+            idx.search(qd, k, R, lut_mode, Lp, out=(ids, sc))
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
         prof = idx.profile_read(reset=True)
@@ -130,17 +147,17 @@ def main():
         sc1 = torch.empty((1, k), dtype=torch.float32, device="cuda")
         q1 = [qd[i:i + 1] for i in range(min(B, 64))]
         for i in range(50):
-            idx.search(q1[i % len(q1)], k, R, lut_mode, out=(ids1, sc1))
+            idx.search(q1[i % len(q1)], k, R, lut_mode, Lp, out=(ids1, sc1))
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(steps):
-            idx.search(q1[i % len(q1)], k, R, lut_mode, out=(ids1, sc1))
+            idx.search(q1[i % len(q1)], k, R, lut_mode, Lp, out=(ids1, sc1))
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
         idx.profile_enable(True)
         idx.profile_read(reset=True)
         for i in range(max(50, steps // 4)):
-            idx.search(q1[i % len(q1)], k, R, lut_mode, out=(ids1, sc1))
+            idx.search(q1[i % len(q1)], k, R, lut_mode, Lp, out=(ids1, sc1))
         torch.cuda.synchronize()
         prof = idx.profile_read(reset=True)
         idx.profile_enable(False)
@@ -152,10 +169,11 @@ def main():
     ms_per_step = dt / args.steps * 1e3
     qps = B * args.steps / dt
     scan_ms = stage_ms["scan"]
-    adds = float(M) * n * B                      # one add per table entry of every (query, point)
-    lds_bytes = 4.0 * nb * n * B                 # one fp32 byte-table entry per code byte
+    scanned = float(n) * (Lp / n_leaves if n_leaves else 1.0)   # points a query scans (expected, with leaves)
+    adds = float(M) * scanned * B                # one add per table entry of every (query, point)
+    lds_bytes = 4.0 * nb * scanned * B           # one fp32 byte-table entry per code byte
     batch_roof = {"bound": "alu", "achieved": adds / (scan_ms * 1e-3) / 1e12, "peak": VALU_PEAK_TOPS,
-                  "unit": "TFLOP/s", "traffic": 2.40e9 if not args.n and B == 10_000 else None, "kernel": "adc_scan_kernel<4,false,25,0>",
+                  "unit": "TFLOP/s", "traffic": 2.40e9 if glove_default and B == 10_000 else None, "kernel": "adc_scan_kernel<%s,false,%d,%d>" % ("1" if n_leaves else "4", nb if nb in (8, 25, 32) else 0, 1 if n_leaves else 0),
                   "avg_launch_ms": scan_ms,
                   "lds_gather": {"achieved_GBs": lds_bytes / (scan_ms * 1e-3) / 1e9, "peak_GBs": LDS_PEAK_GBS,
                                  "frac": lds_bytes / (scan_ms * 1e-3) / 1e9 / LDS_PEAK_GBS}}
@@ -170,12 +188,12 @@ def main():
     # ---- timed region 2: single queries (the HBM-bound regime) ---------------------------------
     dt1, stage1_us = timed_single(avq.LUT_F32, args.b1_steps)
     scan1_ms = stage1_us["scan"] / 1e3
-    code_bytes = float(nb) * n                   # algorithmic bytes of one single-query scan
+    code_bytes = float(nb) * scanned             # algorithmic bytes of one single-query scan
     # HBM-side bytes per launch of this kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by
     # a plain copy of known size (profiles/scan_glove_pmc_traffic.md); only valid for the default n
-    traffic = 29.72e6 + 0.037e6 if not args.n else None
+    traffic = 29.72e6 + 0.037e6 if glove_default else None
     b1_roof = {"bound": "hbm", "achieved": code_bytes / (scan1_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
-               "unit": "GB/s", "traffic": traffic, "kernel": "block_max_nibble_kernel<false,25>",
+               "unit": "GB/s", "traffic": traffic, "kernel": ("adc_scan_kernel<1,false,%d,1>" % nb) if n_leaves else ("block_max_nibble_kernel<false,%d>" % nb if bits == 4 else "block_max_kernel<false,%d>" % nb),
                "avg_launch_ms": scan1_ms,
                "note": "repeated scans of the 29.6 MB code array are served from the 256 MB Infinity Cache"}
     b1_roof["frac"] = b1_roof["achieved"] / b1_roof["peak"]
@@ -189,7 +207,7 @@ def main():
     gt_ids, _ = idx.brute_force(qd[:nr], k)
     recall = {}
     for name, mode in (("f32", avq.LUT_F32), ("u8", avq.LUT_U8)):
-        got_ids, _ = idx.search(qd[:nr], k, R, mode)
+        got_ids, _ = idx.search(qd[:nr], k, R, mode, Lp)
         torch.cuda.synchronize()
         g, t = got_ids.cpu().numpy(), gt_ids.cpu().numpy()
         recall[name] = float(np.mean([len(set(g[i]) & set(t[i])) / k for i in range(nr)]))
@@ -198,19 +216,22 @@ def main():
     # ---- CPU oracle on this host, bounded sample of the same workload ------------------------------
     cpu = None
     parity = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and x is not None:
         import oracle
         no = min(args.oracle_queries, B)
         cb = idx.get_codebooks()
-        codes = unpack4(idx.get_codes(), M)
+        codes = unpack4(idx.get_codes(), M) if bits == 4 else idx.get_codes()
+        okw = {}
+        if n_leaves:
+            okw = dict(centers=idx.get_leaf_centers(), assign=idx.get_leaf_assign(), leaves_to_search=Lp)
         t0 = time.perf_counter()
-        oi, os_ = oracle.search(x, cb, codes, bits, q[:no], k, R, avq.LUT_F32)
+        oi, os_ = oracle.search(x, cb, codes, bits, q[:no], k, R, avq.LUT_F32, **okw)
         dto = time.perf_counter() - t0
-        gi, gs = idx.search(qd[:no], k, R, avq.LUT_F32)
+        gi, gs = idx.search(qd[:no], k, R, avq.LUT_F32, Lp)
         torch.cuda.synchronize()
         parity = bool(np.array_equal(gi.cpu().numpy(), oi) and np.array_equal(gs.cpu().numpy(), os_))
-        o8, s8 = oracle.search(x, cb, codes, bits, q[:16], k, R, avq.LUT_U8)
-        g8, gs8 = idx.search(qd[:16], k, R, avq.LUT_U8)
+        o8, s8 = oracle.search(x, cb, codes, bits, q[:16], k, R, avq.LUT_U8, **okw)
+        g8, gs8 = idx.search(qd[:16], k, R, avq.LUT_U8, Lp)
         torch.cuda.synchronize()
         parity = parity and bool(np.array_equal(g8.cpu().numpy(), o8) and np.array_equal(gs8.cpu().numpy(), s8))
         cpu = {"value": no / dto, "unit": "queries/s", "cores": oracle.num_threads(), "kind": "oracle",
@@ -225,21 +246,23 @@ def main():
         "value": qps, "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "glove-shaped: n=%d d=%d PQ %dx16 (4-bit, %d B/point) T=0.2, batch %d, "
-                               "ADC top-%d re-ranked to top-%d" % (n, d, M, nb, B, R, k),
+        "config": {"workload": "%s: n=%d d=%d PQ %dx%d (%d-bit, %d B/point) T=0.2%s, batch %d, "
+                               "ADC top-%d re-ranked to top-%d"
+                               % (args.config, n, d, M, 1 << bits, bits, nb,
+                                  (", %d leaves, %d searched" % (n_leaves, Lp)) if n_leaves else "", B, R, k),
                    "lut": "f32", "train_s": t_train, "encode_s": t_encode},
         "recall_at_10": recall["f32"], "recall_at_10_u8": recall["u8"], "recall_queries": nr,
-        "adc_points_per_s": float(n) * B / (scan_ms * 1e-3),
-        "adc_codes_per_s": float(n) * B * M / (scan_ms * 1e-3),
+        "adc_points_per_s": scanned * B / (scan_ms * 1e-3),
+        "adc_codes_per_s": scanned * B * M / (scan_ms * 1e-3),
         "stage_ms": stage_ms,
         "u8": {"queries_per_s": qps8, "stage_ms": stage8_ms,
-               "adc_codes_per_s": float(n) * B * M / (stage8_ms["scan"] * 1e-3)},
+               "adc_codes_per_s": scanned * B * M / (stage8_ms["scan"] * 1e-3)},
         "roofline": b1_roof,
         "roofline_batch": batch_roof,
         "batch1": {"queries_per_s": args.b1_steps / dt1, "us_per_query": dt1 / args.b1_steps * 1e6,
                    "steps": args.b1_steps, "stage_us": stage1_us,
-                   "adc_points_per_s": float(n) / (scan1_ms * 1e-3),
-                   "adc_codes_per_s": float(n) * M / (scan1_ms * 1e-3),
+                   "adc_points_per_s": scanned / (scan1_ms * 1e-3),
+                   "adc_codes_per_s": scanned * M / (scan1_ms * 1e-3),
                    "hbm_frac": b1_roof["frac"],
                    "u8_us_per_query": dt1u / max(100, args.b1_steps // 2) * 1e6, "u8_stage_us": stage1u_us},
         "cpu_baseline": cpu, "matches_oracle": parity,

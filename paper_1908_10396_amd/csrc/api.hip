@@ -58,7 +58,7 @@ struct avq_index {
     // per-call scratch
     DevBuf lut, lut8, scale, bias, partial, cand, leaf_ids, leaf_ip, tmp;
     int tune_target_wgs = 0, tune_waves = 0, tune_qt = 0, tune_small_batch = -1, tune_small_impl = 0;
-    DevBuf block_max;
+    DevBuf block_max, lists;
     // optional per-stage timing with HIP events recorded on the caller's stream
     bool prof_on = false;
     std::vector<hipEvent_t> prof_pool;
@@ -150,7 +150,7 @@ extern "C" void avq_destroy(avq_index *idx)
     DevBuf *all[] = {&idx->codebooks, &idx->centers, &idx->centers_t, &idx->x_own, &idx->codes_logical,
                      &idx->codes_blocked, &idx->assign, &idx->perm, &idx->leaf_blk, &idx->lut, &idx->lut8,
                      &idx->scale, &idx->bias, &idx->partial, &idx->cand, &idx->leaf_ids, &idx->leaf_ip,
-                     &idx->tmp, &idx->block_max};
+                     &idx->tmp, &idx->block_max, &idx->lists};
     for (DevBuf *b : all) b->release();
     for (hipEvent_t e : idx->prof_pool) (void)hipEventDestroy(e);
     delete idx;
@@ -497,7 +497,7 @@ extern "C" int avq_search(avq_index *idx, const float *queries, int32_t nq, int3
         return AVQ_EINVAL;
     }
     const int R = reorder_k ? reorder_k : k;
-    const int ns = (R + 63) / 64 <= 2 ? 2 : 8;
+    const int ns = (R + 63) / 64;
     const int C = 64 * ns;
     const bool u8 = lut_mode == AVQ_LUT_U8;
 
@@ -592,6 +592,10 @@ extern "C" int avq_search(avq_index *idx, const float *queries, int32_t nq, int3
     }
     AVQ_TRY(idx->partial.reserve(sizeof(u64) * (size_t)p.n_tiles * shape.qt * p.n_chunks * C));
     p.partial = idx->partial.as<u64>();
+    if (shape.lists_global) {
+        AVQ_TRY(idx->lists.reserve(sizeof(u64) * (size_t)p.n_tiles * p.n_chunks * shape.waves * shape.qt * C));
+        p.lists_ws = idx->lists.as<u64>();
+    }
     {
         StageTimer t(idx, AVQ_STAGE_SCAN, st);
         AVQ_TRY(launch_scan(p, u8, ivf ? SCAN_LEAVES : SCAN_CHUNK, shape, st));
@@ -664,6 +668,10 @@ extern "C" int avq_debug_adc_scores(avq_index *idx, const float *queries, int32_
     p.score_stride = idx->n;
     AVQ_TRY(idx->partial.reserve(64));
     p.partial = idx->partial.as<u64>();
+    if (shape.lists_global) {
+        AVQ_TRY(idx->lists.reserve(sizeof(u64) * (size_t)p.n_tiles * p.n_chunks * shape.waves * shape.qt * 128));
+        p.lists_ws = idx->lists.as<u64>();
+    }
     return launch_scan(p, u8, SCAN_CHUNK, shape, st);
 }
 

@@ -69,10 +69,11 @@ struct ScanParams {
     const u64 *block_keys; // block-list mode: [B][64*ns], the keys of the blocks to scan
     u64 *block_max;        // block-max kernel: [B][n_blocks]
     u64 *partial;         // [n_tiles*QT][n_chunks][64*ns]
+    u64 *lists_ws;        // NULL: candidate lists in LDS; else scratch [grid][waves][QT][64*ns]
     void *scores_out;     // debug: [B][score_stride] fp32 or int32, else NULL
     int64_t score_stride;
 };
-struct ScanShape { int qt; int waves; size_t lds_bytes; };
+struct ScanShape { int qt; int waves; size_t lds_bytes; bool lists_global; };
 // Picks query-tile size and waves per workgroup that fit LDS. qt_hint/waves_hint 0 = auto.
 int scan_pick_shape(int NB, bool u8, int ns, int B, bool single, int qt_hint, int waves_hint,
                     ScanShape *out);

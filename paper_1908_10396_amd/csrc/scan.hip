@@ -215,8 +215,10 @@ adc_scan_kernel(const ScanParams p)
 
     entry_t *tbl = (entry_t *)smem;
     const size_t tbl_bytes = (size_t)NB * 256 * WORDS * 4;
-    u64 *lists = (u64 *)(smem + tbl_bytes);                    // [n_waves][QT][C]
-    u64 *pends = lists + (size_t)n_waves * QT * C;             // [n_waves][QT][64]
+    // candidate lists [n_waves][QT][C]: in LDS, or in a global scratch area when the tables
+    // need the LDS (they are touched only when a pending buffer is flushed)
+    u64 *lists = p.lists_ws ? p.lists_ws + (size_t)blockIdx.x * n_waves * QT * C : (u64 *)(smem + tbl_bytes);
+    u64 *pends = (u64 *)(smem + tbl_bytes) + (p.lists_ws ? 0 : (size_t)n_waves * QT * C); // [n_waves][QT][64]
     u64 *my_lists = lists + (size_t)wave * QT * C;
     u64 *my_pends = pends + (size_t)wave * QT * 64;
 
@@ -708,10 +710,10 @@ small_batch_final_kernel(const FinishParams f, int R, int key_kind, const float 
 
 // ---- host side ---------------------------------------------------------------
 
-static size_t scan_lds_bytes(int NB, bool u8, int qt, int waves, int ns)
+static size_t scan_lds_bytes(int NB, bool u8, int qt, int waves, int ns, bool lists_global)
 {
     const int words = u8 ? (qt >= 2 ? qt / 2 : 1) : qt;
-    return (size_t)NB * 256 * words * 4 + (size_t)waves * qt * (64 * ns + 64) * 8;
+    return (size_t)NB * 256 * words * 4 + (size_t)waves * qt * ((lists_global ? 0 : 64 * ns) + 64) * 8;
 }
 
 int scan_pick_shape(int NB, bool u8, int ns, int B, bool single, int qt_hint, int waves_hint,
@@ -733,9 +735,10 @@ int scan_pick_shape(int NB, bool u8, int ns, int B, bool single, int qt_hint, in
             if (qt > 1 && w > 8) continue; // the tiled kernels are compiled for <= 512 threads
             if (waves_hint) { if (w != waves_hint) continue; }
             else if (qt == 1 && w > 4) continue;
-            size_t need = scan_lds_bytes(NB, u8, qt, w, ns);
+            const bool lists_global = qt > 1; // tiled kernels: LDS goes to the tables
+            size_t need = scan_lds_bytes(NB, u8, qt, w, ns, lists_global);
             if (need <= lds_max) {
-                out->qt = qt; out->waves = w; out->lds_bytes = need;
+                out->qt = qt; out->waves = w; out->lds_bytes = need; out->lists_global = lists_global;
                 return AVQ_OK;
             }
         }

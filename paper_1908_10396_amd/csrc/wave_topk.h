@@ -5,7 +5,7 @@
 // lower id" -- the total order every selection stage uses. Key 0 is the empty
 // slot (no real candidate maps to it).
 //
-// A candidate list of C = 64*ns keys lives in LDS, sorted descending
+// A candidate list of C = 64*ns keys lives in LDS (or global memory), sorted descending
 // (list[0] is the best). A wave merges batches of 64 keys into it with bitonic
 // networks whose compare-exchanges run across lanes.
 #pragma once
@@ -66,10 +66,13 @@ __device__ __forceinline__ u64 wave_sort_desc(u64 v)
 
 __device__ __forceinline__ void wave_lds_fence()
 {
-    // LDS traffic between lanes of one wave: keep program order visible.
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    // Lists and pending buffers are exchanged between lanes of one wave through memory
+    // (LDS, or global memory for the lists of the batch kernels): make earlier stores
+    // visible and later loads fresh. Workgroup scope is enough: the waves of a workgroup
+    // share one L1, so this costs a wait and no cache action.
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
 }
 
 // Merges a batch p (one key per lane, sorted descending, empty lanes 0) into
