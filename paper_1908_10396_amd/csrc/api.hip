@@ -56,8 +56,9 @@ struct avq_index {
     const float *x = nullptr;
     DevBuf x_own, codes_logical, codes_blocked, assign, perm, leaf_blk;
     // per-call scratch
-    DevBuf lut, lut8, scale, bias, partial, cand, leaf_ids, leaf_ip, tmp;
+    DevBuf lut, lut8, scale, bias, partial, cand, leaf_ids, leaf_ip, tmp, thr;
     int tune_target_wgs = 0, tune_waves = 0, tune_qt = 0, tune_small_batch = -1, tune_small_impl = 0;
+    int tune_mfma = 0; // 0 = use the matrix-core scan where it applies, 1 = never
     DevBuf block_max, lists;
     // optional per-stage timing with HIP events recorded on the caller's stream
     bool prof_on = false;
@@ -150,7 +151,7 @@ extern "C" void avq_destroy(avq_index *idx)
     DevBuf *all[] = {&idx->codebooks, &idx->centers, &idx->centers_t, &idx->x_own, &idx->codes_logical,
                      &idx->codes_blocked, &idx->assign, &idx->perm, &idx->leaf_blk, &idx->lut, &idx->lut8,
                      &idx->scale, &idx->bias, &idx->partial, &idx->cand, &idx->leaf_ids, &idx->leaf_ip,
-                     &idx->tmp, &idx->block_max, &idx->lists};
+                     &idx->tmp, &idx->block_max, &idx->lists, &idx->thr};
     for (DevBuf *b : all) b->release();
     for (hipEvent_t e : idx->prof_pool) (void)hipEventDestroy(e);
     delete idx;
@@ -167,6 +168,7 @@ extern "C" int avq_set_tuning(avq_index *idx, const char *name, int32_t value)
     else if (!strcmp(name, "scan_qt")) idx->tune_qt = value;
     else if (!strcmp(name, "small_batch_max")) idx->tune_small_batch = value - 1; // 0 = built-in
     else if (!strcmp(name, "small_batch_impl")) idx->tune_small_impl = value;
+    else if (!strcmp(name, "scan_mfma")) idx->tune_mfma = value;
     else { set_error("avq_set_tuning: unknown name '%s'", name); return AVQ_EINVAL; }
     return AVQ_OK;
 }
@@ -467,6 +469,13 @@ static void plan_flat(const avq_index *idx, const ScanShape &s, int nq, ScanPara
     p->n_chunks = (int32_t)((idx->n_blocks + bpc - 1) / bpc);
 }
 
+// The matrix-core scan serves batches of 8-bit-table queries on a flat index of 4-bit codes.
+static bool use_mfma_scan(const avq_index *idx, int nq, int lut_mode)
+{
+    return idx->tune_mfma == 0 && lut_mode == AVQ_LUT_U8 && idx->cfg.n_leaves == 0 && nq >= 16 &&
+           scan_mfma_supported(idx->NB, idx->cfg.bits);
+}
+
 static int check_query_args(const avq_index *idx, const float *queries, int32_t nq, int32_t lut_mode)
 {
     if (idx->n <= 0) { set_error("no database yet (avq_encode or avq_set_database first)"); return AVQ_ESTATE; }
@@ -569,6 +578,31 @@ extern "C" int avq_search(avq_index *idx, const float *queries, int32_t nq, int3
         return launch_finalize(p.partial, ns, nq, R, k, reorder_k != 0, key_kind, idx->x, c.d, queries,
                                idx->scale.as<float>(), idx->bias.as<float>(), ids_out, scores_out, st);
     }
+    if (use_mfma_scan(idx, nq, lut_mode)) {
+        // 4-bit codes, 8-bit tables, flat index: the table sums are a one-hot contraction on the matrix cores
+        scan_mfma_plan(nq, idx->n_blocks, idx->tune_target_wgs, &p);
+        AVQ_TRY(idx->partial.reserve(sizeof(u64) * (size_t)nq * p.n_chunks * C));
+        AVQ_TRY(idx->lists.reserve(scan_mfma_lists_bytes(p)));
+        AVQ_TRY(idx->thr.reserve(sizeof(uint32_t) * (size_t)nq));
+        p.partial = idx->partial.as<u64>();
+        p.lists_ws = idx->lists.as<u64>();
+        p.thr_shared = idx->thr.as<uint32_t>();
+        {
+            StageTimer t(idx, AVQ_STAGE_SCAN, st);
+            AVQ_HIP(hipMemsetAsync(p.thr_shared, 0, sizeof(uint32_t) * (size_t)nq, st));
+            AVQ_TRY(launch_scan_mfma(p, st));
+        }
+        const u64 *cand = p.partial;
+        if (p.n_chunks > 1) {
+            AVQ_TRY(idx->cand.reserve(sizeof(u64) * (size_t)nq * C));
+            StageTimer t(idx, AVQ_STAGE_MERGE, st);
+            AVQ_TRY(launch_merge_partials(p.partial, nq, p.n_chunks, ns, idx->cand.as<u64>(), st));
+            cand = idx->cand.as<u64>();
+        }
+        StageTimer t(idx, AVQ_STAGE_FINAL, st);
+        return launch_finalize(cand, ns, nq, R, k, reorder_k != 0, key_kind, idx->x, c.d, queries,
+                               idx->scale.as<float>(), idx->bias.as<float>(), ids_out, scores_out, st);
+    }
     ScanShape shape;
     AVQ_TRY(scan_pick_shape(idx->NB, u8, ns, nq, ivf, idx->tune_qt, idx->tune_waves, &shape));
     if (ivf) {
@@ -661,6 +695,12 @@ extern "C" int avq_debug_adc_scores(avq_index *idx, const float *queries, int32_
     AVQ_TRY(build_tables(idx, queries, nq, lut_mode, st));
     ScanParams p;
     fill_scan_params(idx, nq, 1, 2, &p);
+    if (use_mfma_scan(idx, nq, lut_mode)) {
+        scan_mfma_plan(nq, idx->n_blocks, idx->tune_target_wgs, &p);
+        p.scores_out = scores_out;
+        p.score_stride = idx->n;
+        return launch_scan_mfma(p, st);
+    }
     ScanShape shape;
     AVQ_TRY(scan_pick_shape(idx->NB, u8, 2, nq, false, idx->tune_qt, idx->tune_waves, &shape));
     plan_flat(idx, shape, nq, &p);

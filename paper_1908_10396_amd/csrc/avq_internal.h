@@ -70,6 +70,7 @@ struct ScanParams {
     u64 *block_max;        // block-max kernel: [B][n_blocks]
     u64 *partial;         // [n_tiles*QT][n_chunks][64*ns]
     u64 *lists_ws;        // NULL: candidate lists in LDS; else scratch [grid][waves][QT][64*ns]
+    uint32_t *thr_shared; // matrix-core kernel: [B] best known R-th ordering value per query, zeroed before the launch
     void *scores_out;     // debug: [B][score_stride] fp32 or int32, else NULL
     int64_t score_stride;
 };
@@ -82,6 +83,13 @@ int scan_pick_shape(int NB, bool u8, int ns, int B, bool single, int qt_hint, in
 // query over the blocks named by block_keys.
 enum { SCAN_CHUNK = 0, SCAN_LEAVES = 1, SCAN_BLOCKLIST = 2 };
 int launch_scan(const ScanParams &p, bool u8, int mode, const ScanShape &shape, hipStream_t st);
+// The same flat scan for 4-bit codes and 8-bit tables on the matrix cores: one wave per
+// (32 queries, chunk); fills partial[q][chunk][64*ns]. scan_mfma_plan sets n_tiles, n_chunks
+// and blocks_per_chunk (target_waves 0 = built-in); lists_ws needs scan_mfma_lists_bytes.
+bool scan_mfma_supported(int NB, int bits);
+void scan_mfma_plan(int B, int64_t n_blocks, int target_waves, ScanParams *p);
+size_t scan_mfma_lists_bytes(const ScanParams &p);
+int launch_scan_mfma(const ScanParams &p, hipStream_t st);
 // Full scan that only records the best key of every block (block_max[q][blk]).
 int launch_block_max(const ScanParams &p, bool u8, int waves, hipStream_t st);
 // Small batches, after launch_block_max: block selection, scan of the selected blocks,

@@ -443,15 +443,21 @@ __device__ __forceinline__ void nibble_accumulate(const unsigned char *tbl, cons
         if constexpr (U8) asm volatile("" : "+v"(acci[0]), "+v"(acci[1]), "+v"(acci[2]), "+v"(acci[3]));
         else asm volatile("" : "+v"(accf[0]), "+v"(accf[1]), "+v"(accf[2]), "+v"(accf[3]));
     };
+    // The low and the high nibbles of the word's four bytes are masked out once, already
+    // scaled to table offsets, and pinned, so that each lookup costs one bit-field extract;
+    // left alone the compiler folds this back into a shift and a mask per nibble.
     auto plane = [&](uint32_t w, const unsigned char *t) {
+        uint32_t lo, hi;
+        if constexpr (U8) { lo = w & 0x0f0f0f0fu; hi = (w >> 4) & 0x0f0f0f0fu; }
+        else { lo = (w << 2) & 0x3c3c3c3cu; hi = (w >> 2) & 0x3c3c3c3cu; }
+        asm volatile("" : "+v"(lo), "+v"(hi));
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const uint32_t byte = (w >> (8 * i)) & 0xffu;
+            const uint32_t a = (lo >> (8 * i)) & 0xffu, b = (hi >> (8 * i)) & 0xffu;
             if constexpr (U8) {
-                acci[i] += (uint32_t)t[byte & 15u] + (uint32_t)t[16 + (byte >> 4)];
+                acci[i] += (uint32_t)t[a] + (uint32_t)t[16 + b];
             } else {
-                const float *T = (const float *)t;
-                const float v = __fadd_rn(T[byte & 15u], T[16 + (byte >> 4)]);
+                const float v = __fadd_rn(*(const float *)(t + a), *(const float *)(t + 64 + b));
                 accf[i] = __fadd_rn(accf[i], v);
             }
         }
@@ -502,7 +508,11 @@ template <bool U8, int NBT>
 __global__ void __launch_bounds__(1024)
 block_max_nibble_kernel(const ScanParams p)
 {
-    extern __shared__ __align__(16) unsigned char smem[];
+    // With the byte count fixed at compile time the tables are a static array: its LDS
+    // address is a constant that folds into the offset field of every table read.
+    extern __shared__ __align__(16) unsigned char dyn_smem[];
+    __shared__ __align__(16) unsigned char fixed_smem[NBT ? 2 * NBT * 16 * (U8 ? 1 : 4) : 16];
+    unsigned char *smem = NBT ? fixed_smem : dyn_smem;
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int n_waves = blockDim.x >> 6;
@@ -720,26 +730,34 @@ int scan_pick_shape(int NB, bool u8, int ns, int B, bool single, int qt_hint, in
                     ScanShape *out)
 {
     const size_t lds_max = kMaxDynLds;
-    int qts_f[] = {4, 1, 0}, qts_u[] = {8, 1, 0};
+    int qts_f[] = {4, 1, 0}, qts_u[] = {8, 4, 1, 0};
     const int *qts = u8 ? qts_u : qts_f;
-    for (int i = 0; qts[i]; ++i) {
-        int qt = qts[i];
-        if (single && qt != 1) continue;
-        if (!single) {
-            if (qt_hint) { if (qt != qt_hint) continue; }
-            else if (qt > 1 && B < qt) continue; // small batches: one query per workgroup
-        }
-        int wlist[] = {16, 8, 4, 2, 1, 0};
-        for (int j = 0; wlist[j]; ++j) {
-            int w = wlist[j];
-            if (qt > 1 && w > 8) continue; // the tiled kernels are compiled for <= 512 threads
-            if (waves_hint) { if (w != waves_hint) continue; }
-            else if (qt == 1 && w > 4) continue;
-            const bool lists_global = qt > 1; // tiled kernels: LDS goes to the tables
-            size_t need = scan_lds_bytes(NB, u8, qt, w, ns, lists_global);
-            if (need <= lds_max) {
-                out->qt = qt; out->waves = w; out->lds_bytes = need; out->lists_global = lists_global;
-                return AVQ_OK;
+    // First choice: the widest query tile that still leaves room for eight waves (two per
+    // SIMD hide the LDS latency of the lookups); failing that, the widest tile that fits.
+    for (int pass = 0; pass < 2; ++pass) {
+        for (int i = 0; qts[i]; ++i) {
+            int qt = qts[i];
+            if (single && qt != 1) continue;
+            if (pass == 0 && qt == 1 && !single) continue;
+            if (!single) {
+                if (qt_hint) { if (qt != qt_hint) continue; }
+                else if (qt > 1 && B < qt) continue; // small batches: one query per workgroup
+            }
+            int wlist[] = {16, 8, 4, 2, 1, 0};
+            for (int j = 0; wlist[j]; ++j) {
+                int w = wlist[j];
+                if (qt > 1 && w > 8) continue; // the tiled kernels are compiled for <= 512 threads
+                if (waves_hint) { if (w != waves_hint) continue; }
+                else {
+                    if (qt == 1 && w > 4) continue;
+                    if (pass == 0 && qt > 1 && w < 8) continue;
+                }
+                const bool lists_global = qt > 1; // tiled kernels: LDS goes to the tables
+                size_t need = scan_lds_bytes(NB, u8, qt, w, ns, lists_global);
+                if (need <= lds_max) {
+                    out->qt = qt; out->waves = w; out->lds_bytes = need; out->lists_global = lists_global;
+                    return AVQ_OK;
+                }
             }
         }
     }
@@ -797,6 +815,7 @@ int launch_scan(const ScanParams &p, bool u8, int mode, const ScanShape &s, hipS
         if (s.qt == 4) return launch_nb<4, false, MODE_CHUNK>(p, s, grid, st);
     } else {
         if (s.qt == 1) return launch_nb<1, true, MODE_CHUNK>(p, s, grid, st);
+        if (s.qt == 4) return launch_nb<4, true, MODE_CHUNK>(p, s, grid, st);
         if (s.qt == 8) return launch_nb<8, true, MODE_CHUNK>(p, s, grid, st);
     }
     set_error("scan: unsupported query tile %d", s.qt);

@@ -50,6 +50,7 @@ CASES = {
     "large8_nb32": (2_500, 256, 32, 8, 19),
     "generic_nb7": (1_999, 28, 14, 4, 9),
     "odd_m_nb4": (1_030, 21, 7, 4, 5),
+    "odd_m_nb25": (2_100, 98, 49, 4, 40),
     "bits8_nb3": (777, 12, 3, 8, 6),
 }
 
@@ -107,17 +108,19 @@ def test_search_matches(case, lut_mode, k, R):
     np.testing.assert_array_equal(sc1.cpu().numpy(), os_[:1])
 
 
-def test_search_is_deterministic_and_independent_of_launch_shape(case):
+@pytest.mark.parametrize("lut_mode", [0, 1])
+def test_search_is_deterministic_and_independent_of_launch_shape(case, lut_mode):
     idx, xd = make_index(case)
     qd = dev(case["q"])
-    base = [t.cpu().numpy() for t in idx.search(qd, 10, 100, 0)]
-    again = [t.cpu().numpy() for t in idx.search(qd, 10, 100, 0)]
+    base = [t.cpu().numpy() for t in idx.search(qd, 10, 100, lut_mode)]
+    again = [t.cpu().numpy() for t in idx.search(qd, 10, 100, lut_mode)]
     np.testing.assert_array_equal(base[0], again[0])
     np.testing.assert_array_equal(base[1], again[1])
-    for name, val in (("scan_target_wgs", 64), ("scan_target_wgs", 4096), ("scan_waves", 2), ("scan_qt", 1),
-                      ("small_batch_max", 1), ("small_batch_max", 1000)):
+    tiles = (1, 4) if lut_mode == 0 else (1, 4, 8)
+    for name, val in (("scan_target_wgs", 64), ("scan_target_wgs", 4096), ("scan_waves", 2),
+                      ("small_batch_max", 1), ("small_batch_max", 1000), ("scan_mfma", 1)) + tuple(("scan_qt", t) for t in tiles):
         idx.set_tuning(name, val)
-        got = [t.cpu().numpy() for t in idx.search(qd, 10, 100, 0)]
+        got = [t.cpu().numpy() for t in idx.search(qd, 10, 100, lut_mode)]
         np.testing.assert_array_equal(base[0], got[0])
         np.testing.assert_array_equal(base[1], got[1])
         idx.set_tuning(name, 0)
