@@ -583,13 +583,15 @@ extern "C" int avq_search(avq_index *idx, const float *queries, int32_t nq, int3
         scan_mfma_plan(nq, idx->n_blocks, idx->tune_target_wgs, &p);
         AVQ_TRY(idx->partial.reserve(sizeof(u64) * (size_t)nq * p.n_chunks * C));
         AVQ_TRY(idx->lists.reserve(scan_mfma_lists_bytes(p)));
-        AVQ_TRY(idx->thr.reserve(sizeof(uint32_t) * (size_t)nq));
+        const size_t thr_bytes = sizeof(uint32_t) * (size_t)nq * (1 + (size_t)p.n_chunks);
+        AVQ_TRY(idx->thr.reserve(thr_bytes));
         p.partial = idx->partial.as<u64>();
         p.lists_ws = idx->lists.as<u64>();
         p.thr_shared = idx->thr.as<uint32_t>();
+        p.kth_shared = p.thr_shared + nq;
         {
             StageTimer t(idx, AVQ_STAGE_SCAN, st);
-            AVQ_HIP(hipMemsetAsync(p.thr_shared, 0, sizeof(uint32_t) * (size_t)nq, st));
+            AVQ_HIP(hipMemsetAsync(p.thr_shared, 0, thr_bytes, st));
             AVQ_TRY(launch_scan_mfma(p, st));
         }
         const u64 *cand = p.partial;

@@ -70,7 +70,10 @@ struct ScanParams {
     u64 *block_max;        // block-max kernel: [B][n_blocks]
     u64 *partial;         // [n_tiles*QT][n_chunks][64*ns]
     u64 *lists_ws;        // NULL: candidate lists in LDS; else scratch [grid][waves][QT][64*ns]
-    uint32_t *thr_shared; // matrix-core kernel: [B] best known R-th ordering value per query, zeroed before the launch
+    // matrix-core kernel, both zeroed before the launch: [B] best known bound of the R-th best
+    // ordering value per query; [B][n_chunks] every wave's ceil(R/group)-th best
+    uint32_t *thr_shared, *kth_shared;
+    int32_t group;        // chunks per threshold group
     void *scores_out;     // debug: [B][score_stride] fp32 or int32, else NULL
     int64_t score_stride;
 };

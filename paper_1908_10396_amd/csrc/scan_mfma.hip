@@ -18,12 +18,21 @@
 //
 // A lane ends up with the scores of 16 points for one query (lanes l and l + 32 share
 // query l % 32). Scores above the query's threshold go to a lane-private pending
-// buffer in LDS; when a lane's buffer is half full the two buffers of the query are
+// buffer in LDS; when a lane's buffer is full the two buffers of the query are
 // sorted and merged into the query's candidate list (global scratch), which tightens
-// the threshold. The waves that scan different chunks for the same queries share
-// their thresholds through a global array (atomic max): any wave's R-th best score
-// is a lower bound of the final R-th best score, so points below it can be dropped
-// by every wave, whatever the timing.
+// the threshold.
+//
+// Thresholds are shared between the waves that scan different chunks for the same
+// queries, through global arrays and relaxed atomics; a stale value only lets more
+// points through. thr_shared[q] (atomic max) collects lower bounds of the final R-th
+// best score of query q, of two kinds:
+//  * any wave's own R-th best score;
+//  * for a group of g waves that run side by side, the smallest of their ceil(R/g)-th
+//    best scores (published in kth_shared[q][chunk]): that many points at or above it
+//    exist in every one of the g chunks, R in all. This one is close to the R-th best
+//    of the group's union, which no wave could compute alone, and cuts the keys that
+//    reach the lists roughly by the size of the group.
+// A wave reads its queries' bounds once per block, one block ahead of their use.
 #include "avq_internal.h"
 #include "wave_topk.h"
 
@@ -31,13 +40,53 @@ namespace avq {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
+typedef __attribute__((address_space(3))) u64 lds_u64;
 
 constexpr int kMfmaQueries = 32; // queries per wave
 constexpr int kMfmaPend = 32;    // pending keys per lane
 constexpr int kMfmaWaves = 4;    // waves per workgroup
 
-template <int NBT>
-__global__ void __launch_bounds__(kMfmaWaves * 64)
+// Rare path of the scan below, kept out of line so that it costs the scan no registers:
+// merges the pending keys of one query (cnt keys in each of two lane buffers of kMfmaPend
+// slots, at pend_a for lanes 0-31 and pend_b for lanes 32-63) into the query's list,
+// publishes the wave's kw-th best in kth_row[self], reads the group's (gsz entries of
+// kth_row) and returns the query's new lower bound of the final R-th best ordering value,
+// which it also publishes in *bound_q. Called by the whole wave with uniform arguments,
+// except cnt.
+__device__ __noinline__ uint32_t mfma_flush_query(const lds_u64 *pend_a, const lds_u64 *pend_b, int cnt_a, int cnt_b,
+                                                  u64 *list, int ns, int R, int kw, uint32_t *kth_row, int gsz,
+                                                  int self, uint32_t *bound_q)
+{
+    const int lane = lane_id();
+    uint32_t member = 0xffffffffu; // lane c < gsz: the kw-th best of the group's chunk c (in flight during the merge)
+    if (lane < gsz && lane != self)
+        member = __hip_atomic_load(kth_row + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    wave_lds_fence();
+    const int slot = lane & 31;
+    u64 key = 0ull;
+    if (lane < 32) { if (slot < cnt_a) key = pend_a[slot]; }
+    else { if (slot < cnt_b) key = pend_b[slot]; }
+    key = wave_sort_desc(key);
+    wave_list_insert_sorted(list, ns, key);
+    const uint32_t ord = key_ord(list[R - 1]);
+    const uint32_t ord_kw = key_ord(list[kw - 1]);
+    if (lane == self) member = ord_kw;
+#pragma unroll
+    for (int m = 32; m > 0; m >>= 1) {
+        const uint32_t o = (uint32_t)__shfl_xor((int)member, m, 64);
+        member = o < member ? o : member;
+    }
+    const uint32_t best = ord > member ? ord : member; // member: 0 while a chunk of the group has fewer than kw keys
+    if (lane == 0) {
+        if (ord_kw > 0u) __hip_atomic_store(kth_row + self, ord_kw, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (best > 0u) __hip_atomic_fetch_max(bound_q, best, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    return best;
+}
+
+// STORE: inspection mode, every score is written to scores_out and nothing is selected.
+template <int NBT, bool STORE>
+__global__ void __launch_bounds__(kMfmaWaves * 64, 2)
 adc_mfma_scan_kernel(const ScanParams p)
 {
     __shared__ __align__(16) uint32_t onehot[64];
@@ -56,7 +105,7 @@ adc_mfma_scan_kernel(const ScanParams p)
     const bool live = q < p.B;
     const int C = 64 * p.ns;
     const int off = 128 * p.M;
-    const bool store = p.scores_out != nullptr;
+    constexpr bool store = STORE;
 
     // table operands: position s takes subspaces 2s (lanes 0-31) and 2s + 1 (lanes 32-63)
     v4i bq[NBT];
@@ -70,41 +119,37 @@ adc_mfma_scan_kernel(const ScanParams p)
     }
 
     u64 *my_lists = nullptr;
-    u64 *my_pend = (u64 *)dyn_smem + ((size_t)wave * 64 + lane) * kMfmaPend;
-    if (!store) {
+    lds_u64 *const pend0 = (lds_u64 *)dyn_smem + (wave * 64 + lane) * kMfmaPend;
+    lds_u64 *const pend_end = pend0 + kMfmaPend;
+    lds_u64 *pend = pend0; // next free slot of this lane's pending buffer
+    if constexpr (!store) {
         my_lists = p.lists_ws + (size_t)gw * kMfmaQueries * C;
         for (int i = lane; i < kMfmaQueries * C; i += 64) my_lists[i] = 0ull;
         wave_lds_fence();
     }
-    int cnt = 0;                 // keys in this lane's pending buffer
-    uint32_t local_ord = 0u;     // ordering value of the R-th best key of this lane's query in this wave
-    uint32_t shared_ord = 0u;    // the same, best over all waves (as last read)
-    // A score enters when its ordering value (sum + 1) is >= the threshold's: later points
-    // of a wave can have lower ids than earlier ones, so equal scores must pass.
-    auto thr_of = [&]() -> int {
-        if (!live) return 0x7fffffff;
-        const uint32_t o = local_ord > shared_ord ? local_ord : shared_ord;
-        return (int)o - off - 2;
-    };
+    // the group of chunks whose waves share ceil(R / size)-th best scores
+    const int g0 = (chunk / p.group) * p.group;
+    const int gsz = p.n_chunks - g0 < p.group ? p.n_chunks - g0 : p.group;
+    const int kw = (p.R + gsz - 1) / gsz;
+    uint32_t bound_ord = 0u; // best known lower bound of the final R-th best ordering value of this lane's query
+    // A score enters when its ordering value (sum + 1) is >= the bound's: later points of a
+    // wave can have lower ids than earlier ones, so equal scores must pass.
+    auto thr_of = [&]() -> int { return live ? (int)bound_ord - off - 2 : 0x7fffffff; };
     int thr = thr_of();
 
-    // merges the pending keys of query jq (lanes jq and jq + 32) into its list
+    // flushes query jq (lanes jq and jq + 32 hold its pending keys)
     auto flush_query = [&](int jq) {
-        const int src = jq + 32 * h;
-        const int cnt_src = __shfl(cnt, src, 64);
-        wave_lds_fence();
-        u64 key = j < cnt_src ? ((const u64 *)dyn_smem)[((size_t)wave * 64 + src) * kMfmaPend + j] : 0ull;
-        key = wave_sort_desc(key);
-        u64 *list = my_lists + (size_t)jq * C;
-        wave_list_insert_sorted(list, p.ns, key);
-        const u64 kth = list[p.R - 1];
-        const uint32_t ord = key_ord(kth);
+        const int qq = tile * kMfmaQueries + jq; // < B: only live lanes collect keys
+        const int cnt = (int)(pend - pend0);
+        const int cnt_a = __builtin_amdgcn_readlane(cnt, jq), cnt_b = __builtin_amdgcn_readlane(cnt, jq + 32);
+        const lds_u64 *pa = (const lds_u64 *)dyn_smem + (wave * 64 + jq) * kMfmaPend;
+        const uint32_t best = mfma_flush_query(pa, pa + 32 * kMfmaPend, cnt_a, cnt_b, my_lists + (size_t)jq * C, p.ns, p.R,
+                                               kw, p.kth_shared + (size_t)qq * p.n_chunks + g0, gsz, chunk - g0,
+                                               p.thr_shared + qq);
         if (j == jq) {
-            cnt = 0;
-            local_ord = ord;
+            pend = pend0;
+            bound_ord = best > bound_ord ? best : bound_ord;
             thr = thr_of();
-            if (h == 0 && ord > 0u && live)
-                __hip_atomic_fetch_max(p.thr_shared + q, ord, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     };
 
@@ -113,85 +158,107 @@ adc_mfma_scan_kernel(const ScanParams p)
     if (end > p.n_blocks) end = p.n_blocks;
     const uint32_t nib_shift = 4u * (uint32_t)(1 - h); // brings this half-wave's nibble to bits 4..7 of each byte
 
-    for (int64_t blk = first; blk < end; ++blk) {
-        const uint8_t *base = p.codes + (size_t)blk * 256 * NBT;
-        if (!store && live) {
-            shared_ord = __hip_atomic_load(p.thr_shared + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            thr = thr_of();
+    // lane (j, h) takes the four points of lane slot H*32 + j of a block's rows
+    auto load_half = [&](uint32_t (&w)[NBT], int64_t hb) {
+        const uint8_t *base = p.codes + (size_t)(hb >> 1) * 256 * NBT;
+        const int slot = (int)(hb & 1) * 32 + j;
+#pragma unroll
+        for (int r = 0; r < NBT / 4; ++r) {
+            const uint4 t = ((const uint4 *)(base + (size_t)r * 1024))[slot];
+            w[4 * r] = t.x; w[4 * r + 1] = t.y; w[4 * r + 2] = t.z; w[4 * r + 3] = t.w;
         }
-#pragma unroll 1
-        for (int H = 0; H < 2; ++H) {
-            // lane (j, h) takes the four points of lane slot H*32 + j of the block's rows
-            const int slot = H * 32 + j;
-            uint32_t w[NBT];
 #pragma unroll
-            for (int r = 0; r < NBT / 4; ++r) {
-                const uint4 t = ((const uint4 *)(base + (size_t)r * 1024))[slot];
-                w[4 * r] = t.x; w[4 * r + 1] = t.y; w[4 * r + 2] = t.z; w[4 * r + 3] = t.w;
-            }
+        for (int t = 0; t < NBT % 4; ++t)
+            w[(NBT / 4) * 4 + t] = ((const uint32_t *)(base + (size_t)(NBT / 4) * 1024 + (size_t)t * 256))[slot];
+    };
+
+    uint32_t nxt_bound = 0u; // the shared bound, read one block ahead of its use
+    uint32_t w_cur[NBT], w_nxt[NBT];
+    if (first < end) load_half(w_cur, 2 * first);
+    for (int64_t hb = 2 * first; hb < 2 * end; ++hb) {
+        const int64_t blk = hb >> 1;
+        const int H = (int)(hb & 1);
+        if (hb + 1 < 2 * end) load_half(w_nxt, hb + 1);
+        if (!store && H == 0 && live) {
+            bound_ord = nxt_bound > bound_ord ? nxt_bound : bound_ord;
+            thr = thr_of();
+            nxt_bound = __hip_atomic_load(p.thr_shared + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        // this half-wave's nibble of every byte, times 16: the offset of its one-hot pattern
 #pragma unroll
-            for (int t = 0; t < NBT % 4; ++t)
-                w[(NBT / 4) * 4 + t] = ((const uint32_t *)(base + (size_t)(NBT / 4) * 1024 + (size_t)t * 256))[slot];
+        for (int b = 0; b < NBT; ++b) {
+            w_cur[b] = (w_cur[b] << nib_shift) & 0xf0f0f0f0u;
+            asm volatile("" : "+v"(w_cur[b])); // keeps the mask here: one bit-field extract per lookup below
+        }
+        // Chains of NBT matrix instructions, one per u (points 4i + u of the 32 lane slots), two
+        // at a time: a chain's next instruction needs the previous one's result, so two chains
+        // take turns (and the SIMD's other wave fills what is left). The one-hot operands of a
+        // step are read from LDS while the step before runs; scheduling barriers keep that order.
+        auto read_a = [&](int u, int s) -> v4i {
+            const uint32_t o = (w_cur[s] >> (8 * u)) & 0xffu;
+            return *(const v4i *)((const unsigned char *)onehot + o);
+        };
 #pragma unroll
-            for (int b = 0; b < NBT; ++b) w[b] <<= nib_shift;
+        for (int u0 = 0; u0 < 4; u0 += 2) {
+            v4i abuf[2][2];
+            v16i acc[2];
 #pragma unroll
-            for (int u0 = 0; u0 < 4; u0 += 2) {
-                // two independent accumulation chains: points 4i + u0 and 4i + u0 + 1
-                v16i acc[2];
+            for (int a = 0; a < 2; ++a) abuf[0][a] = read_a(u0 + a, 0);
 #pragma unroll
-                for (int a = 0; a < 2; ++a) acc[a] = v16i{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-                for (int s = 0; s < NBT; ++s) {
-#pragma unroll
-                    for (int a = 0; a < 2; ++a) {
-                        const uint32_t o = (w[s] >> (8 * (u0 + a))) & 0xf0u;
-                        const v4i av = *(const v4i *)((const unsigned char *)onehot + o);
-                        acc[a] = __builtin_amdgcn_mfma_i32_32x32x32_i8(av, bq[s], acc[a], 0, 0, 0);
-                    }
-                }
+            for (int s = 0; s < NBT; ++s) {
 #pragma unroll
                 for (int a = 0; a < 2; ++a) {
-                    // accumulator v of lane (j, h): point row 8*(v/4) + 4*h + v%4 of the 32, query j
-                    const int32_t id0 = (int32_t)(blk * 256) + H * 128 + 16 * h + (u0 + a);
-                    if (store) {
+                    if (s == 0)
+                        acc[a] = __builtin_amdgcn_mfma_i32_32x32x32_i8(abuf[0][a], bq[0], v16i{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, 0, 0, 0);
+                    else
+                        acc[a] = __builtin_amdgcn_mfma_i32_32x32x32_i8(abuf[s & 1][a], bq[s], acc[a], 0, 0, 0);
+                    if (s + 1 < NBT) abuf[(s + 1) & 1][a] = read_a(u0 + a, s + 1);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
 #pragma unroll
-                        for (int v = 0; v < 16; ++v) {
-                            const int32_t id = id0 + 32 * (v / 4) + 4 * (v % 4);
-                            if (live && id < p.n_valid)
-                                ((int32_t *)p.scores_out)[(size_t)q * p.score_stride + id] = acc[a][v] + off;
-                        }
-                        continue;
-                    }
-                    bool pushed = false;
+            for (int a = 0; a < 2; ++a) {
+                // accumulator v of lane (j, h): point row 8*(v/4) + 4*h + v%4 of the 32, query j
+                const int32_t id0 = (int32_t)(blk * 256) + H * 128 + 16 * h + u0 + a;
+                if constexpr (store) {
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
                         const int32_t id = id0 + 32 * (v / 4) + 4 * (v % 4);
-                        const bool hit = acc[a][v] > thr && id < p.n_valid;
-                        if (__builtin_amdgcn_ballot_w64(hit) == 0ull) continue;
-                        if (hit) {
-                            my_pend[cnt] = make_key((uint32_t)(acc[a][v] + off + 1), id);
-                            ++cnt;
-                        }
-                        pushed = true;
+                        if (live && id < p.n_valid)
+                            ((int32_t *)p.scores_out)[(size_t)q * p.score_stride + id] = acc[a][v] + off;
                     }
-                    if (pushed) {
-                        // a chain adds at most 16 keys to a lane: keep every buffer at most half full
-                        u64 full = __builtin_amdgcn_ballot_w64(cnt > kMfmaPend - 16);
+                } else {
+                    // Common case, one compare and one branch per accumulator: no lane has a candidate.
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const bool hit = acc[a][v] > thr;
+                        if (__builtin_expect(__builtin_amdgcn_ballot_w64(hit) == 0ull, 1)) continue;
+                        // some lane has a candidate (ids past the end are padding): it goes to the
+                        // lane's pending buffer; queries whose buffer is full are flushed first
+                        const int32_t id = id0 + 32 * (v / 4) + 4 * (v % 4);
+                        const bool want = hit && id < p.n_valid;
+                        u64 full = __builtin_amdgcn_ballot_w64(want && pend == pend_end);
                         while (full) {
                             const int jq = (int)(__builtin_ctzll(full) & 31);
                             flush_query(jq);
                             full &= ~((1ull << jq) | (1ull << (jq + 32)));
                         }
+                        if (want && acc[a][v] > thr) { // the flush may have raised the threshold
+                            *pend = make_key((uint32_t)(acc[a][v] + off + 1), id);
+                            ++pend;
+                        }
                     }
                 }
             }
         }
+#pragma unroll
+        for (int b = 0; b < NBT; ++b) w_cur[b] = w_nxt[b];
     }
     if (store) return;
 
     // drain, then hand the lists over: partial[q][chunk][C]
     {
-        u64 rest = __builtin_amdgcn_ballot_w64(cnt > 0);
+        u64 rest = __builtin_amdgcn_ballot_w64(pend != pend0);
         while (rest) {
             const int jq = (int)(__builtin_ctzll(rest) & 31);
             flush_query(jq);
@@ -218,14 +285,17 @@ bool scan_mfma_supported(int NB, int bits)
 void scan_mfma_plan(int B, int64_t n_blocks, int target_waves, ScanParams *p)
 {
     p->n_tiles = (B + kMfmaQueries - 1) / kMfmaQueries;
-    // two rounds of two waves per SIMD over 256 compute units, unless told otherwise
-    const int64_t target = target_waves > 0 ? target_waves : 4096;
-    int64_t chunks = (target + p->n_tiles / 2) / p->n_tiles;
+    // two waves per SIMD on 256 compute units, all resident at once, unless told otherwise
+    const int64_t target = target_waves > 0 ? target_waves : 2048;
+    int64_t chunks = target / p->n_tiles;
     const int64_t max_chunks = std::max<int64_t>(1, std::min<int64_t>(256, n_blocks / 4));
     chunks = std::max<int64_t>(1, std::min(chunks, max_chunks));
     const int64_t bpc = (n_blocks + chunks - 1) / chunks;
     p->blocks_per_chunk = (int32_t)bpc;
     p->n_chunks = (int32_t)((n_blocks + bpc - 1) / bpc);
+    // chunks whose waves are resident together form a threshold group
+    const int64_t resident = std::max<int64_t>(1, 2048 / p->n_tiles);
+    p->group = (int32_t)std::max<int64_t>(1, std::min<int64_t>(16, std::min<int64_t>(resident, p->n_chunks)));
 }
 
 size_t scan_mfma_lists_bytes(const ScanParams &p)
@@ -233,10 +303,10 @@ size_t scan_mfma_lists_bytes(const ScanParams &p)
     return sizeof(u64) * (size_t)p.n_tiles * p.n_chunks * kMfmaQueries * 64 * p.ns;
 }
 
-template <int NBT>
+template <int NBT, bool STORE>
 static int launch_mfma_one(const ScanParams &p, hipStream_t st)
 {
-    auto kern = adc_mfma_scan_kernel<NBT>;
+    auto kern = adc_mfma_scan_kernel<NBT, STORE>;
     static bool attr_done = false;
     if (!attr_done) {
         AVQ_HIP(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynLds));
@@ -254,15 +324,17 @@ static int launch_mfma_one(const ScanParams &p, hipStream_t st)
 int launch_scan_mfma(const ScanParams &p, hipStream_t st)
 {
     if (!scan_mfma_supported(p.NB, p.bits)) { set_error("scan: no matrix-core kernel for this code size"); return AVQ_EINVAL; }
-    if (p.scores_out == nullptr && (p.lists_ws == nullptr || p.thr_shared == nullptr || p.partial == nullptr)) {
+    if (p.scores_out == nullptr && (p.lists_ws == nullptr || p.thr_shared == nullptr || p.kth_shared == nullptr || p.partial == nullptr ||
+                                  p.group < 1)) {
         set_error("scan: matrix-core kernel needs its scratch buffers");
         return AVQ_EINVAL;
     }
     if (p.R < 1 || p.R > 64 * p.ns) { set_error("scan: R does not fit the lists"); return AVQ_EINVAL; }
+    const bool store = p.scores_out != nullptr;
     switch (p.NB) {
-    case 8: return launch_mfma_one<8>(p, st);
-    case 25: return launch_mfma_one<25>(p, st);
-    default: return launch_mfma_one<32>(p, st);
+    case 8: return store ? launch_mfma_one<8, true>(p, st) : launch_mfma_one<8, false>(p, st);
+    case 25: return store ? launch_mfma_one<25, true>(p, st) : launch_mfma_one<25, false>(p, st);
+    default: return store ? launch_mfma_one<32, true>(p, st) : launch_mfma_one<32, false>(p, st);
     }
 }
 
