@@ -40,21 +40,76 @@ namespace avq {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
-typedef __attribute__((address_space(3))) u64 lds_u64;
+typedef __attribute__((address_space(3))) uint32_t lds_u32;
 
 constexpr int kMfmaQueries = 32; // queries per wave
-constexpr int kMfmaPend = 32;    // pending keys per lane
+constexpr int kMfmaPend = 64;    // pending keys per lane
 constexpr int kMfmaWaves = 4;    // waves per workgroup
 
+// Inside the scan a key is 32 bits: (ordering value << 18) | (~id & 0x3ffff), with ids
+// counted from the chunk's first point. It orders like the 64-bit key (score, then lower
+// id) as long as a chunk has at most 2^18 points and ordering values stay below 2^14
+// (255 * 64 + 1 does); sorting and merging 32-bit keys costs half the shuffles.
+constexpr int kIdBits = 18;
+constexpr uint32_t kIdMask = (1u << kIdBits) - 1u;
+constexpr int kMfmaMaxChunkBlocks = (1 << kIdBits) / kBlockPoints;
+
+__device__ __forceinline__ uint32_t merge32_desc(uint32_t v) // lanes of a bitonic sequence -> descending
+{
+    const int lane = lane_id();
+#pragma unroll
+    for (int j = 32; j > 0; j >>= 1) {
+        const uint32_t o = (uint32_t)__shfl_xor((int)v, j, 64);
+        v = (lane & j) ? (o < v ? o : v) : (o > v ? o : v);
+    }
+    return v;
+}
+
+__device__ __forceinline__ uint32_t sort32_desc(uint32_t v) // one key per lane -> descending
+{
+    const int lane = lane_id();
+#pragma unroll
+    for (int k = 2; k <= 64; k <<= 1) {
+#pragma unroll
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            const uint32_t o = (uint32_t)__shfl_xor((int)v, j, 64);
+            const bool desc_block = (lane & k) == 0; // k == 64: always true
+            const bool lower = (lane & j) == 0;
+            v = (lower == desc_block) ? (o > v ? o : v) : (o < v ? o : v);
+        }
+    }
+    return v;
+}
+
+// Merges a batch (one key per lane, sorted descending, empty lanes 0) into a sorted list of
+// ns slots of 64 keys; keeps the 64*ns largest.
+__device__ __forceinline__ void list32_insert_sorted(uint32_t *list, int ns, uint32_t b)
+{
+    const int lane = lane_id();
+    if ((uint32_t)__shfl((int)b, 0, 64) <= list[ns * 64 - 1]) return; // best of the batch is below the whole list
+    for (int s = 0; s < ns; ++s) {
+        const uint32_t v = list[s * 64 + lane];
+        const uint32_t bmax = (uint32_t)__shfl((int)b, 0, 64);
+        const uint32_t vmin = (uint32_t)__shfl((int)v, 63, 64);
+        if (bmax == 0u) break;     // nothing left to place
+        if (bmax <= vmin) continue; // slot s keeps all its keys; the batch may still beat later slots
+        const uint32_t br = (uint32_t)__shfl((int)b, 63 - lane, 64);
+        const uint32_t hi = v > br ? v : br; // the 64 largest of slot + batch, bitonic
+        const uint32_t lo = v > br ? br : v; // the 64 smallest, bitonic
+        list[s * 64 + lane] = merge32_desc(hi);
+        if (s + 1 < ns) b = merge32_desc(lo);
+    }
+    wave_lds_fence();
+}
+
 // Rare path of the scan below, kept out of line so that it costs the scan no registers:
-// merges the pending keys of one query (cnt keys in each of two lane buffers of kMfmaPend
-// slots, at pend_a for lanes 0-31 and pend_b for lanes 32-63) into the query's list,
-// publishes the wave's kw-th best in kth_row[self], reads the group's (gsz entries of
-// kth_row) and returns the query's new lower bound of the final R-th best ordering value,
-// which it also publishes in *bound_q. Called by the whole wave with uniform arguments,
-// except cnt.
-__device__ __noinline__ uint32_t mfma_flush_query(const lds_u64 *pend_a, const lds_u64 *pend_b, int cnt_a, int cnt_b,
-                                                  u64 *list, int ns, int R, int kw, uint32_t *kth_row, int gsz,
+// merges the pending keys of one query (cnt_a keys at pend_a, the buffer of lane jq, and
+// cnt_b keys at pend_b, that of lane jq + 32) into the query's list, publishes the wave's
+// kw-th best in kth_row[self], reads the group's (gsz entries of kth_row) and returns the
+// query's new lower bound of the final R-th best ordering value, which it also publishes
+// in *bound_q. Called by the whole wave with uniform arguments.
+__device__ __noinline__ uint32_t mfma_flush_query(const lds_u32 *pend_a, const lds_u32 *pend_b, int cnt_a, int cnt_b,
+                                                  uint32_t *list, int ns, int R, int kw, uint32_t *kth_row, int gsz,
                                                   int self, uint32_t *bound_q)
 {
     const int lane = lane_id();
@@ -62,14 +117,10 @@ __device__ __noinline__ uint32_t mfma_flush_query(const lds_u64 *pend_a, const l
     if (lane < gsz && lane != self)
         member = __hip_atomic_load(kth_row + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     wave_lds_fence();
-    const int slot = lane & 31;
-    u64 key = 0ull;
-    if (lane < 32) { if (slot < cnt_a) key = pend_a[slot]; }
-    else { if (slot < cnt_b) key = pend_b[slot]; }
-    key = wave_sort_desc(key);
-    wave_list_insert_sorted(list, ns, key);
-    const uint32_t ord = key_ord(list[R - 1]);
-    const uint32_t ord_kw = key_ord(list[kw - 1]);
+    if (cnt_a > 0) list32_insert_sorted(list, ns, sort32_desc(lane < cnt_a ? pend_a[lane] : 0u));
+    if (cnt_b > 0) list32_insert_sorted(list, ns, sort32_desc(lane < cnt_b ? pend_b[lane] : 0u));
+    const uint32_t ord = list[R - 1] >> kIdBits;
+    const uint32_t ord_kw = list[kw - 1] >> kIdBits;
     if (lane == self) member = ord_kw;
 #pragma unroll
     for (int m = 32; m > 0; m >>= 1) {
@@ -90,7 +141,7 @@ __global__ void __launch_bounds__(kMfmaWaves * 64, 2)
 adc_mfma_scan_kernel(const ScanParams p)
 {
     __shared__ __align__(16) uint32_t onehot[64];
-    extern __shared__ __align__(16) unsigned char dyn_smem[]; // [waves][64 lanes][kMfmaPend] keys
+    extern __shared__ __align__(16) unsigned char dyn_smem[]; // [waves][64 lanes][kMfmaPend] 32-bit keys
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     if (threadIdx.x < 64) {
         const int c = threadIdx.x >> 2, dw = threadIdx.x & 3; // pattern c, dword dw
@@ -118,13 +169,13 @@ adc_mfma_scan_kernel(const ScanParams p)
                     (int)(r.w ^ 0x80808080u)};
     }
 
-    u64 *my_lists = nullptr;
-    lds_u64 *const pend0 = (lds_u64 *)dyn_smem + (wave * 64 + lane) * kMfmaPend;
-    lds_u64 *const pend_end = pend0 + kMfmaPend;
-    lds_u64 *pend = pend0; // next free slot of this lane's pending buffer
+    uint32_t *my_lists = nullptr; // [32 queries][C] 32-bit keys
+    lds_u32 *const pend0 = (lds_u32 *)dyn_smem + (wave * 64 + lane) * kMfmaPend;
+    lds_u32 *const pend_end = pend0 + kMfmaPend;
+    lds_u32 *pend = pend0; // next free slot of this lane's pending buffer
     if constexpr (!store) {
-        my_lists = p.lists_ws + (size_t)gw * kMfmaQueries * C;
-        for (int i = lane; i < kMfmaQueries * C; i += 64) my_lists[i] = 0ull;
+        my_lists = (uint32_t *)p.lists_ws + (size_t)gw * kMfmaQueries * C;
+        for (int i = lane; i < kMfmaQueries * C; i += 64) my_lists[i] = 0u;
         wave_lds_fence();
     }
     // the group of chunks whose waves share ceil(R / size)-th best scores
@@ -142,7 +193,7 @@ adc_mfma_scan_kernel(const ScanParams p)
         const int qq = tile * kMfmaQueries + jq; // < B: only live lanes collect keys
         const int cnt = (int)(pend - pend0);
         const int cnt_a = __builtin_amdgcn_readlane(cnt, jq), cnt_b = __builtin_amdgcn_readlane(cnt, jq + 32);
-        const lds_u64 *pa = (const lds_u64 *)dyn_smem + (wave * 64 + jq) * kMfmaPend;
+        const lds_u32 *pa = (const lds_u32 *)dyn_smem + (wave * 64 + jq) * kMfmaPend;
         const uint32_t best = mfma_flush_query(pa, pa + 32 * kMfmaPend, cnt_a, cnt_b, my_lists + (size_t)jq * C, p.ns, p.R,
                                                kw, p.kth_shared + (size_t)qq * p.n_chunks + g0, gsz, chunk - g0,
                                                p.thr_shared + qq);
@@ -156,6 +207,7 @@ adc_mfma_scan_kernel(const ScanParams p)
     const int64_t first = (int64_t)chunk * p.blocks_per_chunk;
     int64_t end = first + p.blocks_per_chunk;
     if (end > p.n_blocks) end = p.n_blocks;
+    const int32_t id_base = (int32_t)(first * kBlockPoints); // ids inside keys count from here
     const uint32_t nib_shift = 4u * (uint32_t)(1 - h); // brings this half-wave's nibble to bits 4..7 of each byte
 
     // lane (j, h) takes the four points of lane slot H*32 + j of a block's rows
@@ -244,7 +296,7 @@ adc_mfma_scan_kernel(const ScanParams p)
                             full &= ~((1ull << jq) | (1ull << (jq + 32)));
                         }
                         if (want && acc[a][v] > thr) { // the flush may have raised the threshold
-                            *pend = make_key((uint32_t)(acc[a][v] + off + 1), id);
+                            *pend = ((uint32_t)(acc[a][v] + off + 1) << kIdBits) | (~(uint32_t)(id - id_base) & kIdMask);
                             ++pend;
                         }
                     }
@@ -269,9 +321,12 @@ adc_mfma_scan_kernel(const ScanParams p)
     for (int jq = 0; jq < kMfmaQueries; ++jq) {
         const int qq = tile * kMfmaQueries + jq;
         if (qq >= p.B) break;
-        const u64 *list = my_lists + (size_t)jq * C;
+        const uint32_t *list = my_lists + (size_t)jq * C;
         u64 *out = p.partial + ((size_t)qq * p.n_chunks + chunk) * C;
-        for (int i = lane; i < C; i += 64) out[i] = list[i];
+        for (int i = lane; i < C; i += 64) {
+            const uint32_t k32 = list[i];
+            out[i] = k32 ? make_key(k32 >> kIdBits, id_base + (int32_t)(~k32 & kIdMask)) : 0ull;
+        }
     }
 }
 
@@ -289,7 +344,8 @@ void scan_mfma_plan(int B, int64_t n_blocks, int target_waves, ScanParams *p)
     const int64_t target = target_waves > 0 ? target_waves : 2048;
     int64_t chunks = target / p->n_tiles;
     const int64_t max_chunks = std::max<int64_t>(1, std::min<int64_t>(256, n_blocks / 4));
-    chunks = std::max<int64_t>(1, std::min(chunks, max_chunks));
+    const int64_t min_chunks = (n_blocks + kMfmaMaxChunkBlocks - 1) / kMfmaMaxChunkBlocks; // ids in 32-bit keys
+    chunks = std::max<int64_t>(std::max<int64_t>(1, min_chunks), std::min(chunks, max_chunks));
     const int64_t bpc = (n_blocks + chunks - 1) / chunks;
     p->blocks_per_chunk = (int32_t)bpc;
     p->n_chunks = (int32_t)((n_blocks + bpc - 1) / bpc);
@@ -315,7 +371,7 @@ static int launch_mfma_one(const ScanParams &p, hipStream_t st)
     const int64_t waves = (int64_t)p.n_tiles * p.n_chunks;
     const int64_t grid = (waves + kMfmaWaves - 1) / kMfmaWaves;
     if (grid > 0x7fffffff) { set_error("scan: grid too large"); return AVQ_EINVAL; }
-    const size_t lds = (size_t)kMfmaWaves * 64 * kMfmaPend * sizeof(u64);
+    const size_t lds = (size_t)kMfmaWaves * 64 * kMfmaPend * sizeof(uint32_t);
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kMfmaWaves * 64), lds, st, p);
     AVQ_HIP(hipGetLastError());
     return AVQ_OK;
@@ -330,6 +386,7 @@ int launch_scan_mfma(const ScanParams &p, hipStream_t st)
         return AVQ_EINVAL;
     }
     if (p.R < 1 || p.R > 64 * p.ns) { set_error("scan: R does not fit the lists"); return AVQ_EINVAL; }
+    if (p.blocks_per_chunk > kMfmaMaxChunkBlocks || p.M > 64) { set_error("scan: chunk or code too large for 32-bit keys"); return AVQ_EINVAL; }
     const bool store = p.scores_out != nullptr;
     switch (p.NB) {
     case 8: return store ? launch_mfma_one<8, true>(p, st) : launch_mfma_one<8, false>(p, st);
