@@ -635,6 +635,18 @@ rescan_blocks_kernel(const ScanParams p, const FinishParams f)
     }
 }
 
+// Number of keys of keys[0..c) above `mine`, counted by four neighbouring lanes (part =
+// lane & 3 takes every fourth key); all four must call it together.
+__device__ __forceinline__ int rank_by_four(const u64 *keys, int c, u64 mine, int part)
+{
+    int r = 0;
+#pragma unroll 4
+    for (int t = part; t < c; t += 4) r += keys[t] > mine;
+    r += __shfl_xor(r, 1, 64);
+    r += __shfl_xor(r, 2, 64);
+    return r;
+}
+
 // key_kind 1: the keys carry integer sums of 8-bit table codes (flat index); 0: fp32 scores.
 __global__ void __launch_bounds__(1024)
 small_batch_final_kernel(const FinishParams f, int R, int key_kind, const float *__restrict__ scale,
@@ -645,71 +657,91 @@ small_batch_final_kernel(const FinishParams f, int R, int key_kind, const float 
     const int q = blockIdx.x;
 
     // LDS: final keys [R] x2 | counter | query [d] | then a region used first for the
-    // selection scratch, later for staging rows of x
+    // selection (candidate keys or the selection scratch), later for staging rows of x
     u64 *fin = (u64 *)smem;                                                       // [R] candidates
     u64 *fin2 = fin + R;                                                          // [R] re-scored
     uint32_t *counters = (uint32_t *)(fin2 + R);                                  // [4]
     float *qs = (float *)(counters + 4);                                          // [d]
     unsigned char *region = (unsigned char *)(((uintptr_t)(qs + f.d) + 15) & ~(uintptr_t)15);
     WgSelectScratch *sel = (WgSelectScratch *)region;
+    u64 *clist = (u64 *)region;                                                   // [<= kSelList] candidate keys
     float *stage = (float *)region;                                               // [stage_rows][d + 1]
 
-    for (int l = tid; l < f.d; l += nt) qs[l] = f.queries[(size_t)q * f.d + l];
-    if (tid < 4) counters[tid] = 0u;
     const int n_cand = (int)f.meta[q].n_cand;
     const u64 *cand = f.cand + (size_t)q * f.cand_stride;
-    const u64 t2 = wg_select_threshold(cand, n_cand, R, sel);
-    __syncthreads();
-    for (int i = tid; i < n_cand; i += nt) {
-        const u64 key = cand[i];
-        if (key >= t2) fin[atomicAdd(&counters[0], 1u)] = key;
-    }
-    __syncthreads();
-    const int n_fin = (int)counters[0]; // min(R, n_cand)
-    const int k = f.k;
-    if (!f.reorder) {
-        for (int j = tid; j < n_fin; j += nt) {
-            const u64 mine = fin[j];
-            int rank = 0;
-#pragma unroll 8
-            for (int t = 0; t < n_fin; ++t) rank += fin[t] > mine;
-            if (rank < k) {
-                f.ids_out[(size_t)q * k + rank] = key_id(mine);
-                f.scores_out[(size_t)q * k + rank] =
-                    key_kind ? __fmaf_rn((float)(int)(key_ord(mine) - 1u), scale[q], bias[q]) : f32_from_ord(key_ord(mine));
-            }
+    for (int l = tid; l < f.d; l += nt) qs[l] = f.queries[(size_t)q * f.d + l];
+    if (tid < 4) counters[tid] = 0u;
+    int n_fin;
+    if (n_cand <= kSelList) {
+        // the usual case, a few hundred candidates: rank them all by counting and keep the
+        // R best, already in order
+        for (int i = tid; i < n_cand; i += nt) clist[i] = cand[i];
+        __syncthreads();
+        for (int j0 = 0; j0 < n_cand; j0 += nt / 4) {
+            const int j = j0 + (tid >> 2);
+            const u64 mine = j < n_cand ? clist[j] : ~0ull;
+            const int rank = rank_by_four(clist, n_cand, mine, tid & 3);
+            if (j < n_cand && (tid & 3) == 0 && rank < R) fin[rank] = mine;
         }
+        n_fin = n_cand < R ? n_cand : R;
+        __syncthreads();
     } else {
+        const u64 t2 = wg_select_threshold(cand, n_cand, R, sel);
+        __syncthreads();
+        for (int i = tid; i < n_cand; i += nt) {
+            const u64 key = cand[i];
+            if (key >= t2) fin[atomicAdd(&counters[0], 1u)] = key;
+        }
+        __syncthreads();
+        n_fin = (int)counters[0]; // min(R, n_cand)
+    }
+    const int k = f.k;
+    const u64 *ranked = fin;
+    if (f.reorder) {
         // exact re-scoring: the candidates' rows are copied to LDS by the whole workgroup
-        // (coalesced, all loads in flight at once), then one thread per candidate runs the
-        // fma chain in index order. Row stride d + 1 keeps the threads on different banks.
+        // (eight threads per row, all loads in flight at once), then one thread per candidate
+        // runs the fma chain in index order. Row stride d + 1 keeps the threads on different banks.
         const int d = f.d, ld = f.d + 1;
+        const bool vec = (d & 3) == 0;
         for (int r0 = 0; r0 < n_fin; r0 += f.stage_rows) {
             const int rows = n_fin - r0 < f.stage_rows ? n_fin - r0 : f.stage_rows;
             __syncthreads();
-            for (int e = tid; e < rows * d; e += nt) {
-                const int r = e / d, l = e - r * d;
-                stage[r * ld + l] = f.x[(size_t)key_id(fin[r0 + r]) * d + l];
+            for (int rb = 0; rb < rows; rb += nt / 8) {
+                const int r = rb + (tid >> 3);
+                if (r >= rows) continue;
+                const float *src = f.x + (size_t)key_id(fin[r0 + r]) * d;
+                float *dst = stage + r * ld;
+                if (vec) {
+                    for (int c4 = tid & 7; c4 < d / 4; c4 += 8) {
+                        const float4 v = ((const float4 *)src)[c4];
+                        dst[4 * c4] = v.x; dst[4 * c4 + 1] = v.y; dst[4 * c4 + 2] = v.z; dst[4 * c4 + 3] = v.w;
+                    }
+                } else {
+                    for (int l = tid & 7; l < d; l += 8) dst[l] = src[l];
+                }
             }
             __syncthreads();
             for (int r = tid; r < rows; r += nt) {
                 const float *row = stage + r * ld;
                 float sc = 0.0f;
-#pragma unroll 4
+#pragma unroll 20
                 for (int l = 0; l < d; ++l) sc = __fmaf_rn(qs[l], row[l], sc);
                 fin2[r0 + r] = make_key(ord_from_f32(sc), key_id(fin[r0 + r]));
             }
         }
         __syncthreads();
-        for (int j = tid; j < n_fin; j += nt) {
-            const u64 mine = fin2[j];
-            int rank = 0;
-#pragma unroll 8
-            for (int t = 0; t < n_fin; ++t) rank += fin2[t] > mine;
-            if (rank < k) {
-                f.ids_out[(size_t)q * k + rank] = key_id(mine);
-                f.scores_out[(size_t)q * k + rank] = f32_from_ord(key_ord(mine));
-            }
+        ranked = fin2;
+    }
+    for (int j0 = 0; j0 < n_fin; j0 += nt / 4) {
+        const int j = j0 + (tid >> 2);
+        const u64 mine = j < n_fin ? ranked[j] : ~0ull;
+        const int rank = rank_by_four(ranked, n_fin, mine, tid & 3);
+        if (j < n_fin && (tid & 3) == 0 && rank < k) {
+            f.ids_out[(size_t)q * k + rank] = key_id(mine);
+            float sc;
+            if (f.reorder || !key_kind) sc = f32_from_ord(key_ord(mine));
+            else sc = __fmaf_rn((float)(int)(key_ord(mine) - 1u), scale[q], bias[q]);
+            f.scores_out[(size_t)q * k + rank] = sc;
         }
     }
     for (int j = n_fin + tid; j < k; j += nt) { // fewer than k candidates exist
