@@ -568,7 +568,7 @@ extern "C" int avq_search(avq_index *idx, const float *queries, int32_t nq, int3
         }
         ScanShape shape;
         int rc = AVQ_EINVAL;
-        for (int w = 16; w >= 1 && rc != AVQ_OK; w /= 2) rc = scan_pick_shape(idx->NB, u8, ns, nq, true, 1, w, &shape);
+        for (int w = 16; w >= 1 && rc != AVQ_OK; w /= 2) rc = scan_pick_shape(idx->NB, idx->cfg.bits, u8, ns, nq, true, 1, w, &shape);
         AVQ_TRY(rc);
         {
             StageTimer t(idx, AVQ_STAGE_RESCAN, st);
@@ -606,7 +606,7 @@ extern "C" int avq_search(avq_index *idx, const float *queries, int32_t nq, int3
                                idx->scale.as<float>(), idx->bias.as<float>(), ids_out, scores_out, st);
     }
     ScanShape shape;
-    AVQ_TRY(scan_pick_shape(idx->NB, u8, ns, nq, ivf, idx->tune_qt, idx->tune_waves, &shape));
+    AVQ_TRY(scan_pick_shape(idx->NB, idx->cfg.bits, u8, ns, nq, ivf, idx->tune_qt, idx->tune_waves, &shape));
     if (ivf) {
         const int L = leaves_to_search;
         AVQ_TRY(idx->leaf_ids.reserve(sizeof(int32_t) * (size_t)nq * L));
@@ -704,7 +704,7 @@ extern "C" int avq_debug_adc_scores(avq_index *idx, const float *queries, int32_
         return launch_scan_mfma(p, st);
     }
     ScanShape shape;
-    AVQ_TRY(scan_pick_shape(idx->NB, u8, 2, nq, false, idx->tune_qt, idx->tune_waves, &shape));
+    AVQ_TRY(scan_pick_shape(idx->NB, idx->cfg.bits, u8, 2, nq, false, idx->tune_qt, idx->tune_waves, &shape));
     plan_flat(idx, shape, nq, &p);
     p.scores_out = scores_out;
     p.score_stride = idx->n;

@@ -79,7 +79,7 @@ struct ScanParams {
 };
 struct ScanShape { int qt; int waves; size_t lds_bytes; bool lists_global; };
 // Picks query-tile size and waves per workgroup that fit LDS. qt_hint/waves_hint 0 = auto.
-int scan_pick_shape(int NB, bool u8, int ns, int B, bool single, int qt_hint, int waves_hint,
+int scan_pick_shape(int NB, int bits, bool u8, int ns, int B, bool single, int qt_hint, int waves_hint,
                     ScanShape *out);
 // SCAN_CHUNK: flat index, grid = query tiles x chunks; SCAN_LEAVES: partitioned index, one
 // workgroup per query over its probed leaves; SCAN_BLOCKLIST: flat index, one workgroup per

@@ -45,6 +45,7 @@ template <int W> struct VecW;
 template <> struct VecW<1> { typedef uint32_t type; };
 template <> struct VecW<2> { typedef uint32_t type __attribute__((ext_vector_type(2))); };
 template <> struct VecW<4> { typedef uint32_t type __attribute__((ext_vector_type(4))); };
+template <> struct VecW<8> { typedef uint32_t type __attribute__((ext_vector_type(8))); };
 
 template <int W> __device__ __forceinline__ uint32_t vec_get(const typename VecW<W>::type &v, int i)
 {
@@ -55,6 +56,15 @@ template <int W> __device__ __forceinline__ uint32_t vec_get(const typename VecW
 // words per table entry: fp32 -> one float per query; 8-bit tables -> one u16 per query
 // (a lone query uses a full word)
 template <int QT, bool U8> struct EntryWords { static constexpr int value = U8 ? (QT >= 2 ? QT / 2 : 1) : QT; };
+
+// fp32 tables for a tile of 8 queries keep the 16-entry tables themselves (4-bit codes only):
+// table T = 2b + h (byte position b, low or high nibble) of query group g (4 queries) is 16
+// entries of 4 floats = 256 bytes, at (T * 2 + g) * 256. A wave's 64 reads of 16 bytes from
+// one such table touch every bank once (equal entries are broadcast), so they run at the full
+// LDS rate, where 16-byte reads at random into a 256-entry table lose more than half to bank
+// conflicts; two reads per byte instead of one still come out ahead, and the tables are
+// eight times smaller.
+template <int QT, bool U8> struct NibbleTiles { static constexpr bool value = !U8 && QT == 8; };
 
 // The code bytes of one block held by one lane.
 template <int NBT> struct BlockRegs {
@@ -82,6 +92,15 @@ __device__ __forceinline__ void build_tables(typename VecW<EntryWords<QT, U8>::v
                                              const ScanParams &p, int q0, int NB)
 {
     const int kc = 1 << p.bits;
+    if constexpr (NibbleTiles<QT, U8>::value) {
+        float *t = (float *)tbl;
+        for (int it = threadIdx.x; it < 2 * NB * 128; it += blockDim.x) {
+            const int qq = it & 3, e = (it >> 2) & 15, g = (it >> 6) & 1, T = it >> 7;
+            const int gq = q0 + 4 * g + qq;
+            t[it] = (gq < p.B && T < p.M) ? p.lut[((size_t)gq * p.M + T) * 16 + e] : 0.0f;
+        }
+        return;
+    }
     const int items = QT * NB * 16; // (q, b, g): 16 consecutive byte values g*16 .. g*16+15
     for (int it = threadIdx.x; it < items; it += blockDim.x) {
         const int q = it % QT;
@@ -135,6 +154,28 @@ __device__ __forceinline__ void accumulate_block(const typename VecW<EntryWords<
         else acc[i] = (entry_t)(0u);
     }
     auto plane = [&](uint32_t w, int b) {
+        if constexpr (NibbleTiles<QT, U8>::value) {
+            // both nibbles of the word's four bytes, times 16 (the entry size), masked out once
+            uint32_t wl = (w << 4) & 0xf0f0f0f0u, wh = w & 0xf0f0f0f0u;
+            asm volatile("" : "+v"(wl), "+v"(wh));
+            const unsigned char *tb = (const unsigned char *)tbl + (size_t)b * 1024; // tables 2b, 2b+1 x two groups
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t ol = (wl >> (8 * i)) & 0xffu, oh = (wh >> (8 * i)) & 0xffu;
+#pragma unroll
+                for (int g = 0; g < 2; ++g) {
+                    const float4 lo = *(const float4 *)(tb + g * 256 + ol);
+                    const float4 hi = *(const float4 *)(tb + 512 + g * 256 + oh);
+                    const float l4[4] = {lo.x, lo.y, lo.z, lo.w}, h4[4] = {hi.x, hi.y, hi.z, hi.w};
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const float v = __fadd_rn(l4[k], h4[k]);
+                        acc[i][4 * g + k] = __float_as_uint(__fadd_rn(__uint_as_float(acc[i][4 * g + k]), v));
+                    }
+                }
+            }
+            return;
+        }
         const entry_t *tb = tbl + (size_t)b * 256;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -189,7 +230,7 @@ __device__ __forceinline__ int packed_sum(const typename VecW<WORDS>::type &a, i
 }
 
 template <int QT, bool U8, int NBT, int MODE>
-__global__ void __launch_bounds__(QT > 1 ? 512 : 1024)
+__global__ void __launch_bounds__(QT > 1 ? 512 : 1024, (NibbleTiles<QT, U8>::value ? 4 : 1))
 adc_scan_kernel(const ScanParams p)
 {
     constexpr int WORDS = EntryWords<QT, U8>::value;
@@ -214,7 +255,7 @@ adc_scan_kernel(const ScanParams p)
     const int q0 = tile * QT;
 
     entry_t *tbl = (entry_t *)smem;
-    const size_t tbl_bytes = (size_t)NB * 256 * WORDS * 4;
+    const size_t tbl_bytes = NibbleTiles<QT, U8>::value ? (size_t)NB * QT * 128 : (size_t)NB * 256 * WORDS * 4;
     // candidate lists [n_waves][QT][C]: in LDS, or in a global scratch area when the tables
     // need the LDS (they are touched only when a pending buffer is flushed)
     u64 *lists = p.lists_ws ? p.lists_ws + (size_t)blockIdx.x * n_waves * QT * C : (u64 *)(smem + tbl_bytes);
@@ -310,6 +351,15 @@ adc_scan_kernel(const ScanParams p)
 
     // streams blocks first, first + step, ... < end with the next block's loads in flight
     auto scan_range = [&](int64_t first, int64_t end, int64_t step, float seg_bias) {
+        if constexpr (NibbleTiles<QT, U8>::value) {
+            // sixteen waves per compute unit hide the load latency; no second register buffer
+            for (int64_t blk = first; blk < end; blk += step) {
+                BlockRegs<NBT> cur;
+                load_block<NBT>(cur, p.codes, blk, lane);
+                process_block(blk, cur, seg_bias);
+            }
+            return;
+        }
         BlockRegs<NBT> cur, nxt;
         if (first < end) load_block<NBT>(cur, p.codes, first, lane);
         for (int64_t blk = first; blk < end; blk += step) {
@@ -755,14 +805,15 @@ small_batch_final_kernel(const FinishParams f, int R, int key_kind, const float 
 static size_t scan_lds_bytes(int NB, bool u8, int qt, int waves, int ns, bool lists_global)
 {
     const int words = u8 ? (qt >= 2 ? qt / 2 : 1) : qt;
-    return (size_t)NB * 256 * words * 4 + (size_t)waves * qt * ((lists_global ? 0 : 64 * ns) + 64) * 8;
+    const size_t tables = (!u8 && qt == 8) ? (size_t)NB * qt * 128 : (size_t)NB * 256 * words * 4;
+    return tables + (size_t)waves * qt * ((lists_global ? 0 : 64 * ns) + 64) * 8;
 }
 
-int scan_pick_shape(int NB, bool u8, int ns, int B, bool single, int qt_hint, int waves_hint,
+int scan_pick_shape(int NB, int bits, bool u8, int ns, int B, bool single, int qt_hint, int waves_hint,
                     ScanShape *out)
 {
     const size_t lds_max = kMaxDynLds;
-    int qts_f[] = {4, 1, 0}, qts_u[] = {8, 4, 1, 0};
+    int qts_f[] = {8, 4, 1, 0}, qts_u[] = {8, 4, 1, 0};
     const int *qts = u8 ? qts_u : qts_f;
     // First choice: the widest query tile that still leaves room for eight waves (two per
     // SIMD hide the LDS latency of the lookups); failing that, the widest tile that fits.
@@ -770,6 +821,7 @@ int scan_pick_shape(int NB, bool u8, int ns, int B, bool single, int qt_hint, in
         for (int i = 0; qts[i]; ++i) {
             int qt = qts[i];
             if (single && qt != 1) continue;
+            if (!u8 && qt == 8 && bits != 4) continue; // the fp32 tile of 8 keeps 16-entry tables
             if (pass == 0 && qt == 1 && !single) continue;
             if (!single) {
                 if (qt_hint) { if (qt != qt_hint) continue; }
@@ -845,6 +897,7 @@ int launch_scan(const ScanParams &p, bool u8, int mode, const ScanShape &s, hipS
     if (!u8) {
         if (s.qt == 1) return launch_nb<1, false, MODE_CHUNK>(p, s, grid, st);
         if (s.qt == 4) return launch_nb<4, false, MODE_CHUNK>(p, s, grid, st);
+        if (s.qt == 8 && p.bits == 4) return launch_nb<8, false, MODE_CHUNK>(p, s, grid, st);
     } else {
         if (s.qt == 1) return launch_nb<1, true, MODE_CHUNK>(p, s, grid, st);
         if (s.qt == 4) return launch_nb<4, true, MODE_CHUNK>(p, s, grid, st);
