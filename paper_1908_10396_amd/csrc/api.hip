@@ -510,15 +510,23 @@ extern "C" int avq_search(avq_index *idx, const float *queries, int32_t nq, int3
     const int C = 64 * ns;
     const bool u8 = lut_mode == AVQ_LUT_U8;
 
-    {
+    const int small_max = idx->tune_small_batch >= 0 ? idx->tune_small_batch : 8;
+    const bool small = !ivf && nq <= small_max;
+    // the single-query kernels compute short fp32 tables themselves (one launch less)
+    const bool fuse_tables = small && idx->tune_small_impl == 0 && small_batch_can_fuse_tables(c.bits, c.M, c.d, u8);
+    if (!fuse_tables) {
         StageTimer t(idx, AVQ_STAGE_LUT, st);
         AVQ_TRY(build_tables(idx, queries, nq, lut_mode, st));
     }
     ScanParams p;
     fill_scan_params(idx, nq, R, ns, &p);
+    if (fuse_tables) {
+        p.fuse_queries = queries;
+        p.fuse_codebooks = idx->codebooks.as<float>();
+        p.fuse_d = c.d;
+    }
     const int key_kind = (u8 && !ivf) ? 1 : 0;
-    const int small_max = idx->tune_small_batch >= 0 ? idx->tune_small_batch : 8;
-    if (!ivf && nq <= small_max) {
+    if (small) {
         // A handful of queries: full scan recording block maxima, pick the R best blocks,
         // scan only those with the list machinery.
         AVQ_TRY(idx->block_max.reserve(sizeof(u64) * (size_t)nq * idx->n_blocks));

@@ -56,6 +56,12 @@ struct ScanParams {
     int32_t n_valid;      // flat: ids >= n_valid are padding
     const int32_t *perm;  // partitioned: slot -> id, -1 = padding
     const float *lut;     // [B][M][kc]
+    // single-query kernels over 16-entry fp32 tables: when set, every workgroup computes the
+    // table entries itself (paper Section 4.1: <q^(m), c_j^(m)>, the same fma chain as the
+    // table kernel) and lut is not read
+    const float *fuse_queries;   // [B][fuse_d]
+    const float *fuse_codebooks; // [M][16][fuse_d / M]
+    int32_t fuse_d;
     const uint8_t *lut8;  // [B][M][kc]
     const float *scale;   // [B]
     const float *bias;    // [B]
@@ -93,6 +99,8 @@ bool scan_mfma_supported(int NB, int bits);
 void scan_mfma_plan(int B, int64_t n_blocks, int target_waves, ScanParams *p);
 size_t scan_mfma_lists_bytes(const ScanParams &p);
 int launch_scan_mfma(const ScanParams &p, hipStream_t st);
+// Whether the small-batch kernels can compute their own tables (fuse_* above).
+bool small_batch_can_fuse_tables(int bits, int M, int d, bool u8);
 // Full scan that only records the best key of every block (block_max[q][blk]).
 int launch_block_max(const ScanParams &p, bool u8, int waves, hipStream_t st);
 // Small batches, after launch_block_max: block selection, scan of the selected blocks,

@@ -467,6 +467,19 @@ __device__ __forceinline__ void nibble_tables_fill(unsigned char *tbl, const Sca
     if (U8) {
         const uint8_t *L = p.lut8 + (size_t)q * live;
         for (int e = threadIdx.x; e < total; e += blockDim.x) tbl[e] = e < live ? L[e] : (uint8_t)0;
+    } else if (p.fuse_queries != nullptr) {
+        // no table kernel ran: <q^(m), c_j^(m)> as an fma chain in index order, as it computes them
+        const int ds = p.fuse_d / p.M;
+        const float *qv = p.fuse_queries + (size_t)q * p.fuse_d;
+        for (int e = threadIdx.x; e < total; e += blockDim.x) {
+            float sacc = 0.0f;
+            if (e < live) {
+                const float *c = p.fuse_codebooks + (size_t)e * ds;
+                const float *qm = qv + (e >> 4) * ds;
+                for (int l = 0; l < ds; ++l) sacc = __fmaf_rn(qm[l], c[l], sacc);
+            }
+            ((float *)tbl)[e] = sacc;
+        }
     } else {
         const float *L = p.lut + (size_t)q * live;
         for (int e = threadIdx.x; e < total; e += blockDim.x) ((float *)tbl)[e] = e < live ? L[e] : 0.0f;
@@ -954,6 +967,12 @@ static int launch_block_max_nibble_nb(const ScanParams &p, hipStream_t st)
 }
 
 static bool use_nibble_tables(const ScanParams &p) { return p.bits == 4 && (size_t)p.M * 64 <= 60 * 1024; }
+
+bool small_batch_can_fuse_tables(int bits, int M, int d, bool u8)
+{
+    // fp32 tables of 4-bit codes with short subspaces: a few fma per entry, cheaper than a launch
+    return !u8 && bits == 4 && (size_t)M * 64 <= 60 * 1024 && d / M <= 8;
+}
 
 // LDS of the final kernel: keys, query, then max(selection scratch, row staging).
 static size_t small_final_fixed_bytes(int R, int d)
