@@ -10,10 +10,11 @@ built by the library itself (avq_train on the first 262,144 points, avq_encode
 under the anisotropic loss, T = 0.2) before the timed region.
 
 Prints one JSON line. `value` is queries/s over the timed steps at batch
-10,000 with fp32 tables. The same line carries the 8-bit-table rate, the
-batch-1 numbers (the HBM-bound regime), the roofline objects, Recall@10 against
-exact search, and the CPU oracle timed on this host on a bounded sample of the
-same workload.
+10,000 with fp32 tables; `roofline` describes the kernel that dominates those
+steps (the fp32 scan). The same line carries the 8-bit-table rate (matrix-core
+scan), the batch-1 numbers with their own roofline object (the HBM-bound
+regime, warm and cold cache), Recall@10 against exact search, and the CPU
+oracle timed on this host on a bounded sample of the same workload.
 """
 import argparse
 import json
@@ -29,10 +30,12 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
 # fp32 vector peak is 157.3 TFLOP/s counting an FMA as two flops: 78.6e12 single
-# operations per second. The scan's arithmetic is one add per table entry.
+# operations per second (256 CUs x 4 SIMDs x 32 lanes x 2.4 GHz). The scan's arithmetic
+# is plain adds of table entries.
 VALU_PEAK_TOPS = 157.3 / 2
-# LDS: 256 CUs x 128 B/clk x 2.4 GHz
-LDS_PEAK_GBS = 256 * 128 * 2.4
+# LDS: 256 CUs x 256 B/clk x 2.4 GHz (a conflict-free 16-byte gather reaches 224 B/clk/CU)
+LDS_PEAK_GBS = 256 * 256 * 2.4
+MFMA_I8_PEAK_TOPS = 5000.0       # dense int8, published
 
 
 def log(*a):
@@ -164,17 +167,44 @@ def main():
         stage_us = {s: (v[0] / v[1] * 1e3 if v[1] else 0.0) for s, v in prof.items()}
         return dt, stage_us
 
+    def cold_single_scan_us(lut_mode, reps=20):
+        """Scan-stage time of single-query calls when the codes are not in the Infinity Cache:
+        a 1 GiB buffer is read through before every call (outside the stage's event pair;
+        reading leaves no dirty lines whose write-back would compete with the scan)."""
+        ids1 = torch.empty((1, k), dtype=torch.int32, device="cuda")
+        sc1 = torch.empty((1, k), dtype=torch.float32, device="cuda")
+        evict = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
+        sink = torch.zeros((), dtype=torch.float32, device="cuda")
+        idx.profile_enable(True)
+        idx.profile_read(reset=True)
+        for i in range(reps):
+            sink += evict.sum()
+            idx.search(qd[i % min(B, 64):i % min(B, 64) + 1], k, R, lut_mode, Lp, out=(ids1, sc1))
+        torch.cuda.synchronize()
+        prof = idx.profile_read(reset=True)
+        idx.profile_enable(False)
+        del evict
+        return prof["scan"][0] / prof["scan"][1] * 1e3 if prof["scan"][1] else 0.0
+
     # ---- timed region 1: batches of B queries, fp32 tables (the headline) ------------------
     dt, stage_ms = timed_batch(avq.LUT_F32, args.steps)
     ms_per_step = dt / args.steps * 1e3
     qps = B * args.steps / dt
     scan_ms = stage_ms["scan"]
     scanned = float(n) * (Lp / n_leaves if n_leaves else 1.0)   # points a query scans (expected, with leaves)
-    adds = float(M) * scanned * B                # one add per table entry of every (query, point)
-    lds_bytes = 4.0 * nb * scanned * B           # one fp32 byte-table entry per code byte
+    # Arithmetic of the fp32 scan per (query, point): 4-bit codes on a flat index use the
+    # 16-entry tables (two entries of a byte are added, then accumulated: 2*NB adds, 8*NB bytes
+    # of LDS); byte tables take NB adds and 4*NB bytes.
+    nib_tile = bits == 4 and not n_leaves and B >= 8
+    adds = (2.0 if nib_tile else 1.0) * nb * scanned * B
+    lds_bytes = (8.0 if nib_tile else 4.0) * nb * scanned * B
+    if n_leaves:
+        scan_kernel = "adc_scan_kernel<1,false,%d,1>" % (nb if nb in (8, 25, 32) else 0)
+    else:
+        scan_kernel = "adc_scan_kernel<%d,false,%d,0>" % (8 if nib_tile else 4, nb if nb in (8, 25, 32) else 0)
     batch_roof = {"bound": "alu", "achieved": adds / (scan_ms * 1e-3) / 1e12, "peak": VALU_PEAK_TOPS,
-                  "unit": "TFLOP/s", "traffic": 2.40e9 if glove_default and B == 10_000 else None, "kernel": "adc_scan_kernel<%s,false,%d,%d>" % ("1" if n_leaves else "4", nb if nb in (8, 25, 32) else 0, 1 if n_leaves else 0),
-                  "avg_launch_ms": scan_ms,
+                  "unit": "TFLOP/s", "traffic": None, "kernel": scan_kernel, "avg_launch_ms": scan_ms,
+                  "note": "fp32 adds of table entries (no multiplies); the other binding unit is the LDS gather",
                   "lds_gather": {"achieved_GBs": lds_bytes / (scan_ms * 1e-3) / 1e9, "peak_GBs": LDS_PEAK_GBS,
                                  "frac": lds_bytes / (scan_ms * 1e-3) / 1e9 / LDS_PEAK_GBS}}
     batch_roof["frac"] = batch_roof["achieved"] / batch_roof["peak"]
@@ -184,6 +214,18 @@ def main():
     dt8, stage8_ms = timed_batch(avq.LUT_U8, max(2, args.steps // 2))
     qps8 = B * max(2, args.steps // 2) / dt8
     log("[bench] u8   batch %d: %.0f q/s, stages(ms) %s" % (B, qps8, stage8_ms))
+    u8_roof = None
+    if bits == 4 and not n_leaves and B >= 16 and nb in (8, 25, 32):
+        # one-hot contraction on int8 MFMA: 32 points x 32 queries x 32 positions per instruction,
+        # two subspaces (16 positions each) per instruction, NB instructions per (32 points, 32 queries)
+        n_pad = float((n + 255) // 256 * 256)
+        b_pad = float((B + 31) // 32 * 32)
+        ops = 2.0 * n_pad * b_pad * nb * 32
+        u8_roof = {"bound": "mfma", "achieved": ops / (stage8_ms["scan"] * 1e-3) / 1e12, "peak": MFMA_I8_PEAK_TOPS,
+                   "unit": "TOP/s", "kernel": "adc_mfma_scan_kernel<%d,false>" % nb,
+                   "avg_launch_ms": stage8_ms["scan"], "traffic": None,
+                   "note": "int8 multiply-adds issued; 16 of them per useful table add (one-hot operand)"}
+        u8_roof["frac"] = u8_roof["achieved"] / u8_roof["peak"]
 
     # ---- timed region 2: single queries (the HBM-bound regime) ---------------------------------
     dt1, stage1_us = timed_single(avq.LUT_F32, args.b1_steps)
@@ -195,9 +237,22 @@ def main():
     b1_roof = {"bound": "hbm", "achieved": code_bytes / (scan1_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
                "unit": "GB/s", "traffic": traffic, "kernel": ("adc_scan_kernel<1,false,%d,1>" % nb) if n_leaves else ("block_max_nibble_kernel<false,%d>" % nb if bits == 4 else "block_max_kernel<false,%d>" % nb),
                "avg_launch_ms": scan1_ms,
-               "note": "repeated scans of the 29.6 MB code array are served from the 256 MB Infinity Cache"}
+               "note": "repeated scans of a code array below 256 MB are served from the Infinity Cache (see cold)"}
     b1_roof["frac"] = b1_roof["achieved"] / b1_roof["peak"]
     log("[bench] fp32 batch 1: %.1f us/query end to end, stages(us) %s" % (dt1 / args.b1_steps * 1e6, stage1_us))
+    # what a HIP event pair reports around nothing: part of every per-stage figure above
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(200)]
+    torch.cuda.synchronize()
+    for a_, b_ in evs:
+        a_.record()
+        b_.record()
+    torch.cuda.synchronize()
+    ev_over_us = float(np.median([a_.elapsed_time(b_) for a_, b_ in evs])) * 1e3
+    b1_roof["event_pair_overhead_us"] = ev_over_us
+    cold_us = cold_single_scan_us(avq.LUT_F32)
+    b1_roof["cold"] = {"avg_launch_ms": cold_us / 1e3, "achieved": code_bytes / (cold_us * 1e-6) / 1e9 if cold_us else None,
+                       "note": "1 GiB read through the Infinity Cache before every call"}
+    log("[bench] fp32 batch 1, cold cache: scan %.1f us" % cold_us)
     dt1u, stage1u_us = timed_single(avq.LUT_U8, max(100, args.b1_steps // 2))
     log("[bench] u8   batch 1: %.1f us/query end to end, stages(us) %s"
         % (dt1u / max(100, args.b1_steps // 2) * 1e6, stage1u_us))
@@ -256,9 +311,9 @@ def main():
         "adc_codes_per_s": scanned * B * M / (scan_ms * 1e-3),
         "stage_ms": stage_ms,
         "u8": {"queries_per_s": qps8, "stage_ms": stage8_ms,
-               "adc_codes_per_s": scanned * B * M / (stage8_ms["scan"] * 1e-3)},
-        "roofline": b1_roof,
-        "roofline_batch": batch_roof,
+               "adc_codes_per_s": scanned * B * M / (stage8_ms["scan"] * 1e-3), "roofline": u8_roof},
+        "roofline": batch_roof,
+        "roofline_batch1": b1_roof,
         "batch1": {"queries_per_s": args.b1_steps / dt1, "us_per_query": dt1 / args.b1_steps * 1e6,
                    "steps": args.b1_steps, "stage_us": stage1_us,
                    "adc_points_per_s": scanned / (scan1_ms * 1e-3),
