@@ -18,7 +18,7 @@
 //
 // A lane ends up with the scores of 16 points for one query (lanes l and l + 32 share
 // query l % 32). Scores above the query's threshold go to a lane-private pending
-// buffer in LDS; when a lane's buffer is full the two buffers of the query are
+// buffer in LDS; when a lane's buffer is three quarters full the two buffers of the query are
 // sorted and merged into the query's candidate list (global scratch), which tightens
 // the threshold.
 //
@@ -245,17 +245,21 @@ adc_mfma_scan_kernel(const ScanParams p)
         // Chains of NBT matrix instructions, one per u (points 4i + u of the 32 lane slots), two
         // at a time: a chain's next instruction needs the previous one's result, so two chains
         // take turns (and the SIMD's other wave fills what is left). The one-hot operands of a
-        // step are read from LDS while the step before runs; scheduling barriers keep that order.
+        // step are read from LDS two steps ahead; scheduling barriers keep that order.
         auto read_a = [&](int u, int s) -> v4i {
             const uint32_t o = (w_cur[s] >> (8 * u)) & 0xffu;
             return *(const v4i *)((const unsigned char *)onehot + o);
         };
 #pragma unroll
         for (int u0 = 0; u0 < 4; u0 += 2) {
-            v4i abuf[2][2];
+            constexpr int kAhead = 2; // steps between an operand's LDS read and its use
+            v4i abuf[kAhead + 1][2];
             v16i acc[2];
 #pragma unroll
-            for (int a = 0; a < 2; ++a) abuf[0][a] = read_a(u0 + a, 0);
+            for (int t = 0; t < kAhead; ++t) {
+#pragma unroll
+                for (int a = 0; a < 2; ++a) abuf[t][a] = read_a(u0 + a, t);
+            }
 #pragma unroll
             for (int s = 0; s < NBT; ++s) {
 #pragma unroll
@@ -263,8 +267,8 @@ adc_mfma_scan_kernel(const ScanParams p)
                     if (s == 0)
                         acc[a] = __builtin_amdgcn_mfma_i32_32x32x32_i8(abuf[0][a], bq[0], v16i{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, 0, 0, 0);
                     else
-                        acc[a] = __builtin_amdgcn_mfma_i32_32x32x32_i8(abuf[s & 1][a], bq[s], acc[a], 0, 0, 0);
-                    if (s + 1 < NBT) abuf[(s + 1) & 1][a] = read_a(u0 + a, s + 1);
+                        acc[a] = __builtin_amdgcn_mfma_i32_32x32x32_i8(abuf[s % (kAhead + 1)][a], bq[s], acc[a], 0, 0, 0);
+                    if (s + kAhead < NBT) abuf[(s + kAhead) % (kAhead + 1)][a] = read_a(u0 + a, s + kAhead);
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -281,24 +285,24 @@ adc_mfma_scan_kernel(const ScanParams p)
                     }
                 } else {
                     // Common case, one compare and one branch per accumulator: no lane has a candidate.
+                    // Otherwise the lanes that have one append it to their pending buffers, which
+                    // always have room for a whole chain (ids past the end are padding).
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
                         const bool hit = acc[a][v] > thr;
                         if (__builtin_expect(__builtin_amdgcn_ballot_w64(hit) == 0ull, 1)) continue;
-                        // some lane has a candidate (ids past the end are padding): it goes to the
-                        // lane's pending buffer; queries whose buffer is full are flushed first
                         const int32_t id = id0 + 32 * (v / 4) + 4 * (v % 4);
-                        const bool want = hit && id < p.n_valid;
-                        u64 full = __builtin_amdgcn_ballot_w64(want && pend == pend_end);
-                        while (full) {
-                            const int jq = (int)(__builtin_ctzll(full) & 31);
-                            flush_query(jq);
-                            full &= ~((1ull << jq) | (1ull << (jq + 32)));
-                        }
-                        if (want && acc[a][v] > thr) { // the flush may have raised the threshold
+                        if (hit && id < p.n_valid) {
                             *pend = ((uint32_t)(acc[a][v] + off + 1) << kIdBits) | (~(uint32_t)(id - id_base) & kIdMask);
                             ++pend;
                         }
+                    }
+                    // a chain adds at most 16 keys to a lane: flush the queries with less room than that
+                    u64 need = __builtin_amdgcn_ballot_w64(pend_end - pend < 16);
+                    while (__builtin_expect(need != 0ull, 0)) {
+                        const int jq = (int)(__builtin_ctzll(need) & 31);
+                        flush_query(jq);
+                        need &= ~((1ull << jq) | (1ull << (jq + 32)));
                     }
                 }
             }
