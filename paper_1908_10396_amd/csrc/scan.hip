@@ -423,38 +423,43 @@ block_max_kernel(const ScanParams p)
     const int n_waves = blockDim.x >> 6;
     const int NB = NBT ? NBT : p.NB;
     const int q = blockIdx.y;
-    const int64_t blk = (int64_t)blockIdx.x * n_waves + wave;
     entry_t *tbl = (entry_t *)smem;
+    // the grid's waves take the blocks in turn: a workgroup builds its tables once for many blocks
+    const int64_t step = (int64_t)gridDim.x * n_waves;
+    int64_t blk = (int64_t)blockIdx.x * n_waves + wave;
 
-    BlockRegs<NBT> regs;
-    const bool have = blk < p.n_blocks;
-    if (have) load_block<NBT>(regs, p.codes, blk, lane); // in flight while the tables are built
+    BlockRegs<NBT> regs, nxt;
+    if (blk < p.n_blocks) load_block<NBT>(regs, p.codes, blk, lane); // in flight while the tables are built
     build_tables<1, U8>(tbl, p, q, NB);
     __syncthreads();
-    if (!have) return;
-    entry_t acc[4];
-    accumulate_block<1, U8, NBT>(tbl, regs, p.codes, blk, NB, lane, acc);
-    // best of the lane's four points: higher ordering value, then lower id (= lower i)
-    uint32_t best = 0;
-    int best_i = 0;
+    for (; blk < p.n_blocks; blk += step) {
+        const bool more = blk + step < p.n_blocks;
+        if (more) load_block<NBT>(nxt, p.codes, blk + step, lane);
+        entry_t acc[4];
+        accumulate_block<1, U8, NBT>(tbl, regs, p.codes, blk, NB, lane, acc);
+        // best of the lane's four points: higher ordering value, then lower id (= lower i)
+        uint32_t best = 0;
+        int best_i = 0;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int64_t slot = blk * 256 + 4 * lane + i;
-        uint32_t ord = U8 ? (uint32_t)(acc[i] + 1u) : ord_from_f32(__uint_as_float(acc[i]));
-        if (slot >= p.n_valid) ord = 0u;
-        if (ord > best) { best = ord; best_i = i; }
-    }
-    uint32_t wmax = best;
+        for (int i = 0; i < 4; ++i) {
+            const int64_t slot = blk * 256 + 4 * lane + i;
+            uint32_t ord = U8 ? (uint32_t)(acc[i] + 1u) : ord_from_f32(__uint_as_float(acc[i]));
+            if (slot >= p.n_valid) ord = 0u;
+            if (ord > best) { best = ord; best_i = i; }
+        }
+        uint32_t wmax = best;
 #pragma unroll
-    for (int m = 32; m > 0; m >>= 1) {
-        const uint32_t o = (uint32_t)__shfl_xor((int)wmax, m, 64);
-        wmax = o > wmax ? o : wmax;
+        for (int m = 32; m > 0; m >>= 1) {
+            const uint32_t o = (uint32_t)__shfl_xor((int)wmax, m, 64);
+            wmax = o > wmax ? o : wmax;
+        }
+        const u64 owners = __builtin_amdgcn_ballot_w64(best == wmax);
+        const int owner = __builtin_ctzll(owners); // lowest lane = lowest id among equal scores
+        if (lane == owner)
+            p.block_max[(size_t)q * p.n_blocks + blk] =
+                wmax ? make_key(wmax, (int32_t)(blk * 256 + 4 * lane + best_i)) : 0ull;
+        if (more) regs = nxt;
     }
-    const u64 owners = __builtin_amdgcn_ballot_w64(best == wmax);
-    const int owner = __builtin_ctzll(owners); // lowest lane = lowest id among equal scores
-    if (lane == owner)
-        p.block_max[(size_t)q * p.n_blocks + blk] =
-            wmax ? make_key(wmax, (int32_t)(blk * 256 + 4 * lane + best_i)) : 0ull;
 }
 
 // 16-entry tables of one query in LDS (4-bit codes): 2*NB tables of 16 entries, fp32
@@ -927,8 +932,11 @@ static int launch_block_max_one(const ScanParams &p, int waves, hipStream_t st)
     static bool attr_done = false;
     AVQ_TRY(set_max_lds(kern, &attr_done));
     const size_t lds = (size_t)p.NB * 256 * 4;
-    const unsigned gx = (unsigned)((p.n_blocks + waves - 1) / waves);
-    hipLaunchKernelGGL(kern, dim3(gx, p.B), dim3(waves * 64), lds, st, p);
+    // at most about four workgroups per compute unit and query: beyond that each one loops
+    int64_t gx = (p.n_blocks + waves - 1) / waves;
+    const int64_t cap = std::max<int64_t>(1, 1024 / p.B);
+    if (gx > cap) gx = cap;
+    hipLaunchKernelGGL(kern, dim3((unsigned)gx, p.B), dim3(waves * 64), lds, st, p);
     AVQ_HIP(hipGetLastError());
     return AVQ_OK;
 }

@@ -242,7 +242,9 @@ constexpr int kMaxM = 256;
 // One thread per point. With r = x - x~, p = <r, x>, e = ||r||^2:
 // ||r_par||^2 = p^2/||x||^2 and ||r_perp||^2 = e - p^2/||x||^2, so the loss is
 // e + (eta - 1) p^2 / ||x||^2. p and e are sums over subspaces; changing the
-// codeword of subspace m only changes that subspace's terms.
+// codeword of subspace m only changes that subspace's terms, so the terms of the
+// current codewords are kept per subspace and only summed again (in subspace order,
+// never updated in place: no drift) when another subspace is revisited.
 __global__ void __launch_bounds__(128)
 encode_kernel(const float *__restrict__ x, int64_t n, int d, int M, int kc, int bits,
               const float *__restrict__ codebooks, const float *__restrict__ leaf_centers,
@@ -255,6 +257,7 @@ encode_kernel(const float *__restrict__ x, int64_t n, int d, int M, int kc, int 
     const float *xi = x + (size_t)i * d;
     const float *ce = leaf_centers ? leaf_centers + (size_t)leaf_assign[i] * d : nullptr;
     uint8_t code[kMaxM];
+    double pm_cur[kMaxM], em_cur[kMaxM]; // terms of the current codeword of every subspace
 
     double nx2 = 0.0;
     for (int l = 0; l < d; ++l) nx2 += (double)xi[l] * (double)xi[l];
@@ -277,36 +280,41 @@ encode_kernel(const float *__restrict__ x, int64_t n, int d, int M, int kc, int 
     // start: l2-nearest codeword of the (residual) sub-vector in every subspace
     for (int m = 0; m < M; ++m) {
         int best = 0;
-        double bestd = INFINITY;
+        double bestd = INFINITY, bestp = 0.0;
         for (int j = 0; j < kc; ++j) {
             double pm, em;
             terms(m, j, pm, em);
-            if (em < bestd) { bestd = em; best = j; }
+            if (em < bestd) { bestd = em; bestp = pm; best = j; }
         }
         code[m] = (uint8_t)best;
+        pm_cur[m] = bestp;
+        em_cur[m] = bestd;
     }
     for (int pass = 0; pass < passes; ++pass) {
         bool changed = false;
         for (int m = 0; m < M; ++m) {
-            // p and e of the other subspaces, recomputed from scratch to avoid drift
+            // p and e of the other subspaces
             double Pr = 0.0, Er = 0.0;
             for (int m2 = 0; m2 < M; ++m2) {
                 if (m2 == m) continue;
-                double pm, em;
-                terms(m2, code[m2], pm, em);
-                Pr += pm;
-                Er += em;
+                Pr += pm_cur[m2];
+                Er += em_cur[m2];
             }
             int best = 0;
-            double bestv = INFINITY;
+            double bestv = INFINITY, bestp = 0.0, beste = 0.0;
             for (int j = 0; j < kc; ++j) {
                 double pm, em;
                 terms(m, j, pm, em);
                 const double p = Pr + pm, e = Er + em;
                 const double v = e + w * p * p;
-                if (v < bestv) { bestv = v; best = j; }
+                if (v < bestv) { bestv = v; best = j; bestp = pm; beste = em; }
             }
-            if (best != code[m]) { code[m] = (uint8_t)best; changed = true; }
+            if (best != code[m]) {
+                code[m] = (uint8_t)best;
+                pm_cur[m] = bestp;
+                em_cur[m] = beste;
+                changed = true;
+            }
         }
         if (!changed) break;
     }
