@@ -586,38 +586,43 @@ block_max_nibble_kernel(const ScanParams p)
     const int n_waves = blockDim.x >> 6;
     const int NB = NBT ? NBT : p.NB;
     const int q = blockIdx.y;
-    const int64_t blk = (int64_t)blockIdx.x * n_waves + wave;
+    // the grid's waves take the blocks in turn (one each unless the index is large): a
+    // workgroup fills its tables once for all of its blocks
+    const int64_t step = (int64_t)gridDim.x * n_waves;
+    int64_t blk = (int64_t)blockIdx.x * n_waves + wave;
 
-    const bool have = blk < p.n_blocks;
-    BlockRegs<NBT> regs;
-    if (have) load_block<NBT>(regs, p.codes, blk, lane); // in flight while the tables are filled
+    BlockRegs<NBT> regs, nxt;
+    if (blk < p.n_blocks) load_block<NBT>(regs, p.codes, blk, lane); // in flight while the tables are filled
     nibble_tables_fill<U8>(smem, p, q, NB);
     __syncthreads();
-    if (!have) return;
-
-    float accf[4];
-    uint32_t acci[4];
-    nibble_accumulate<U8, NBT>(smem, regs, p.codes + (size_t)blk * 256 * NB, NB, lane, accf, acci);
-    uint32_t best = 0;
-    int best_i = 0;
+    for (; blk < p.n_blocks; blk += step) {
+        const bool more = blk + step < p.n_blocks;
+        if (more) load_block<NBT>(nxt, p.codes, blk + step, lane);
+        float accf[4];
+        uint32_t acci[4];
+        nibble_accumulate<U8, NBT>(smem, regs, p.codes + (size_t)blk * 256 * NB, NB, lane, accf, acci);
+        uint32_t best = 0;
+        int best_i = 0;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int64_t slot = blk * 256 + 4 * lane + i;
-        uint32_t ord = U8 ? (acci[i] + 1u) : ord_from_f32(accf[i]);
-        if (slot >= p.n_valid) ord = 0u;
-        if (ord > best) { best = ord; best_i = i; }
-    }
-    uint32_t wmax = best;
+        for (int i = 0; i < 4; ++i) {
+            const int64_t slot = blk * 256 + 4 * lane + i;
+            uint32_t ord = U8 ? (acci[i] + 1u) : ord_from_f32(accf[i]);
+            if (slot >= p.n_valid) ord = 0u;
+            if (ord > best) { best = ord; best_i = i; }
+        }
+        uint32_t wmax = best;
 #pragma unroll
-    for (int m = 32; m > 0; m >>= 1) {
-        const uint32_t o = (uint32_t)__shfl_xor((int)wmax, m, 64);
-        wmax = o > wmax ? o : wmax;
+        for (int m = 32; m > 0; m >>= 1) {
+            const uint32_t o = (uint32_t)__shfl_xor((int)wmax, m, 64);
+            wmax = o > wmax ? o : wmax;
+        }
+        const u64 owners = __builtin_amdgcn_ballot_w64(best == wmax);
+        const int owner = __builtin_ctzll(owners);
+        if (lane == owner)
+            p.block_max[(size_t)q * p.n_blocks + blk] =
+                wmax ? make_key(wmax, (int32_t)(blk * 256 + 4 * lane + best_i)) : 0ull;
+        if (more) regs = nxt;
     }
-    const u64 owners = __builtin_amdgcn_ballot_w64(best == wmax);
-    const int owner = __builtin_ctzll(owners);
-    if (lane == owner)
-        p.block_max[(size_t)q * p.n_blocks + blk] =
-            wmax ? make_key(wmax, (int32_t)(blk * 256 + 4 * lane + best_i)) : 0ull;
 }
 
 // After the block-maxima scan, for a handful of queries, three short kernels:
@@ -957,8 +962,11 @@ static int launch_block_max_nibble_one(const ScanParams &p, hipStream_t st)
 {
     const int waves = 4;
     const size_t lds = (size_t)2 * p.NB * 16 * (U8 ? 1 : 4);
-    const unsigned gx = (unsigned)((p.n_blocks + waves - 1) / waves);
-    hipLaunchKernelGGL((block_max_nibble_kernel<U8, NBT>), dim3(gx, p.B), dim3(waves * 64), lds, st, p);
+    // at most eight workgroups per compute unit and query; beyond that each wave loops
+    int64_t gx = (p.n_blocks + waves - 1) / waves;
+    const int64_t cap = std::max<int64_t>(1, 2048 / p.B);
+    if (gx > cap) gx = cap;
+    hipLaunchKernelGGL((block_max_nibble_kernel<U8, NBT>), dim3((unsigned)gx, p.B), dim3(waves * 64), lds, st, p);
     AVQ_HIP(hipGetLastError());
     return AVQ_OK;
 }
