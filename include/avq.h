@@ -183,7 +183,8 @@ int avq_debug_leaf_select(avq_index *idx, const float *queries, int32_t nq, int3
 double avq_eta(int32_t d, double T, double norm, int32_t eta_mode);
 
 /* Launch-shape overrides for experiments; 0 restores the built-in choice.
- * name: "scan_target_wgs" (workgroups the batch scan aims for), "scan_waves"
+ * name: "scan_target_wgs" (workgroups the batch scan aims for; for small batches
+ * the most workgroups per query of the block-maxima scan), "scan_waves"
  * (waves per scan workgroup), "scan_qt" (queries per tile), "small_batch_max"
  * (v > 0: batches of fewer than v queries on a flat index take the block-maxima
  * path; 1 disables that path), "small_batch_impl" (0: one fused kernel after

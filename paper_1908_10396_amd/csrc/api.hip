@@ -537,6 +537,7 @@ extern "C" int avq_search(avq_index *idx, const float *queries, int32_t nq, int3
         p.partial = idx->partial.as<u64>();
         p.n_tiles = nq;
         p.n_chunks = 1;
+        p.max_wgs = idx->tune_target_wgs;
         {
             StageTimer t(idx, AVQ_STAGE_SCAN, st);
             AVQ_TRY(launch_block_max(p, u8, idx->tune_waves > 0 ? idx->tune_waves : 4, st));

@@ -80,6 +80,7 @@ struct ScanParams {
     // ordering value per query; [B][n_chunks] every wave's ceil(R/group)-th best
     uint32_t *thr_shared, *kth_shared;
     int32_t group;        // chunks per threshold group
+    int32_t max_wgs;      // block-max kernels: workgroups per query at most (0 = built-in); waves loop beyond it
     void *scores_out;     // debug: [B][score_stride] fp32 or int32, else NULL
     int64_t score_stride;
 };

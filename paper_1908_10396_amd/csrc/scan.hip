@@ -939,7 +939,7 @@ static int launch_block_max_one(const ScanParams &p, int waves, hipStream_t st)
     const size_t lds = (size_t)p.NB * 256 * 4;
     // at most about four workgroups per compute unit and query: beyond that each one loops
     int64_t gx = (p.n_blocks + waves - 1) / waves;
-    const int64_t cap = std::max<int64_t>(1, 1024 / p.B);
+    const int64_t cap = p.max_wgs > 0 ? p.max_wgs : std::max<int64_t>(1, 1024 / p.B);
     if (gx > cap) gx = cap;
     hipLaunchKernelGGL(kern, dim3((unsigned)gx, p.B), dim3(waves * 64), lds, st, p);
     AVQ_HIP(hipGetLastError());
@@ -964,7 +964,7 @@ static int launch_block_max_nibble_one(const ScanParams &p, hipStream_t st)
     const size_t lds = (size_t)2 * p.NB * 16 * (U8 ? 1 : 4);
     // at most eight workgroups per compute unit and query; beyond that each wave loops
     int64_t gx = (p.n_blocks + waves - 1) / waves;
-    const int64_t cap = std::max<int64_t>(1, 2048 / p.B);
+    const int64_t cap = p.max_wgs > 0 ? p.max_wgs : std::max<int64_t>(1, 2048 / p.B);
     if (gx > cap) gx = cap;
     hipLaunchKernelGGL((block_max_nibble_kernel<U8, NBT>), dim3((unsigned)gx, p.B), dim3(waves * 64), lds, st, p);
     AVQ_HIP(hipGetLastError());

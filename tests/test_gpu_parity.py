@@ -136,7 +136,9 @@ def test_small_batch_paths_agree_with_oracle(case, lut_mode):
     qd = dev(q)
     for k, R in ((10, 100), (10, 0), (100, 512)):
         oi, os_ = oracle.search(case["x"], case["cb"], case["codes"], case["bits"], q, k, R, lut_mode)
-        for name, val in (("small_batch_impl", 0), ("small_batch_impl", 1), ("small_batch_max", 1)):
+        # scan_target_wgs = 2: two workgroups per query, so every wave loops over many blocks
+        for name, val in (("small_batch_impl", 0), ("small_batch_impl", 1), ("small_batch_max", 1),
+                          ("scan_target_wgs", 2)):
             idx.set_tuning(name, val)
             ids, sc = idx.search(qd, k, R, lut_mode)
             np.testing.assert_array_equal(ids.cpu().numpy(), oi, err_msg="%s=%d" % (name, val))
