@@ -615,7 +615,10 @@ extern "C" int avq_search(avq_index *idx, const float *queries, int32_t nq, int3
                                idx->scale.as<float>(), idx->bias.as<float>(), ids_out, scores_out, st);
     }
     ScanShape shape;
-    AVQ_TRY(scan_pick_shape(idx->NB, idx->cfg.bits, u8, ns, nq, ivf, idx->tune_qt, idx->tune_waves, &shape));
+    // few queries on a partitioned index: sixteen waves per workgroup and several workgroups per query
+    const int waves_hint = idx->tune_waves > 0 ? idx->tune_waves : (ivf && nq <= 64 ? 16 : 0);
+    if (scan_pick_shape(idx->NB, idx->cfg.bits, u8, ns, nq, ivf, idx->tune_qt, waves_hint, &shape) != AVQ_OK)
+        AVQ_TRY(scan_pick_shape(idx->NB, idx->cfg.bits, u8, ns, nq, ivf, idx->tune_qt, idx->tune_waves, &shape));
     if (ivf) {
         const int L = leaves_to_search;
         AVQ_TRY(idx->leaf_ids.reserve(sizeof(int32_t) * (size_t)nq * L));
@@ -631,7 +634,11 @@ extern "C" int avq_search(avq_index *idx, const float *queries, int32_t nq, int3
         p.leaf_blk = idx->leaf_blk.as<int32_t>();
         p.Lp = L;
         p.n_tiles = nq;
-        p.n_chunks = 1;
+        // about one leaf per wave when the batch alone cannot fill the chip
+        const int target = idx->tune_target_wgs > 0 ? idx->tune_target_wgs : 512;
+        int chunks = target / nq;
+        const int max_chunks = (L + shape.waves - 1) / shape.waves;
+        p.n_chunks = std::max(1, std::min(chunks, max_chunks));
     } else {
         plan_flat(idx, shape, nq, &p);
     }

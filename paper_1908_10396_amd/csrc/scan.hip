@@ -250,7 +250,7 @@ adc_scan_kernel(const ScanParams p)
     const int C = 64 * p.ns;
 
     int tile, chunk;
-    if (MODE == MODE_CHUNK) { tile = blockIdx.x % p.n_tiles; chunk = blockIdx.x / p.n_tiles; }
+    if (MODE == MODE_CHUNK || MODE == MODE_LEAVES) { tile = blockIdx.x % p.n_tiles; chunk = blockIdx.x / p.n_tiles; }
     else { tile = blockIdx.x; chunk = 0; }
     const int q0 = tile * QT;
 
@@ -286,10 +286,31 @@ adc_scan_kernel(const ScanParams p)
         }
     }
 
+    // The filter of query q lets a point through when it can still be among the R best:
+    //  * it must beat the wave's own R-th best (a tie loses where ids only grow, STRICT);
+    //  * it must reach the smallest of the workgroup's waves' kw-th best scores, kw = ceil(R / waves):
+    //    every wave holds that many points at or above it, R in all (the waves scan disjoint
+    //    points for the same queries), so it is a lower bound of the final R-th best -- and a much
+    //    tighter one than the own R-th best while the lists are young. Ties must pass here.
+    // A list read while its owner merges into it shows an older or the newer kw-th best; both are valid.
+    const int kw = (p.R + n_waves - 1) / n_waves;
     auto refresh_threshold = [&](int q) {
-        const u64 kth = my_lists[(size_t)q * C + (p.R - 1)];
-        if (FKEY) thr_f[q] = kth ? f32_from_ord(key_ord(kth)) : -INFINITY;
-        else thr_i[q] = (int)key_ord(kth) - 1;
+        const uint32_t ord_own = key_ord(my_lists[(size_t)q * C + (p.R - 1)]); // 0: fewer than R yet
+        uint32_t ord_g = 0xffffffffu;
+        for (int w = 0; w < n_waves; ++w) {
+            const uint32_t o = key_ord(lists[((size_t)w * QT + q) * C + (kw - 1)]);
+            ord_g = o < ord_g ? o : ord_g; // 0 while a wave has fewer than kw
+        }
+        if (FKEY) {
+            // ordering values grow with the score: "reach ord_g" is "beat ord_g - 1"
+            const uint32_t t = STRICT ? (ord_g > 0u && ord_g - 1u > ord_own ? ord_g - 1u : ord_own)
+                                      : (ord_g > ord_own ? ord_g : ord_own);
+            thr_f[q] = t ? f32_from_ord(t) : -INFINITY;
+        } else {
+            // integer sums: ordering value = sum + 1
+            const int own = (int)ord_own - 1, grp = (int)ord_g - (STRICT ? 2 : 1);
+            thr_i[q] = grp > own ? grp : own;
+        }
     };
 
     // one block of 256 points: accumulate, then filter
@@ -365,6 +386,7 @@ adc_scan_kernel(const ScanParams p)
         for (int64_t blk = first; blk < end; blk += step) {
             const bool more = blk + step < end;
             if (more) load_block<NBT>(nxt, p.codes, blk + step, lane);
+            if (LEAVES && p.scores_out == nullptr) refresh_threshold(0); // the other waves' progress (QT == 1 here)
             process_block(blk, cur, seg_bias);
             if (more) cur = nxt;
         }
@@ -376,7 +398,8 @@ adc_scan_kernel(const ScanParams p)
         if (end > p.n_blocks) end = p.n_blocks;
         scan_range(first + wave, end, n_waves, 0.0f);
     } else if (MODE == MODE_LEAVES) {
-        for (int j = wave; j < p.Lp; j += n_waves) {
+        // the query's probed leaves, dealt to the waves of its n_chunks workgroups in turn
+        for (int j = chunk * n_waves + wave; j < p.Lp; j += p.n_chunks * n_waves) {
             const int leaf = p.leaf_ids[(size_t)q0 * p.Lp + j];
             if (leaf < 0) continue;
             scan_range(p.leaf_blk[leaf], p.leaf_blk[leaf + 1], 1, p.leaf_ip[(size_t)q0 * p.Lp + j]);
@@ -909,8 +932,10 @@ int launch_scan(const ScanParams &p, bool u8, int mode, const ScanShape &s, hipS
     if (mode == SCAN_LEAVES || mode == SCAN_BLOCKLIST) {
         if (s.qt != 1) { set_error("scan: this mode needs qt == 1"); return AVQ_EINVAL; }
         const int grid = p.B;
-        if (mode == SCAN_LEAVES)
-            return u8 ? launch_nb<1, true, MODE_LEAVES>(p, s, grid, st) : launch_nb<1, false, MODE_LEAVES>(p, s, grid, st);
+        if (mode == SCAN_LEAVES) {
+            const int lgrid = p.n_tiles * p.n_chunks; // n_tiles == B
+            return u8 ? launch_nb<1, true, MODE_LEAVES>(p, s, lgrid, st) : launch_nb<1, false, MODE_LEAVES>(p, s, lgrid, st);
+        }
         return u8 ? launch_nb<1, true, MODE_BLOCKLIST>(p, s, grid, st)
                   : launch_nb<1, false, MODE_BLOCKLIST>(p, s, grid, st);
     }
