@@ -50,17 +50,9 @@ __device__ inline u64 wg_select_threshold(const u64 *__restrict__ keys, int64_t 
             for (int r = 0; r < kSelRegs; ++r)
                 if (kreg[r]) fn(kreg[r]);
         } else {
-            // eight loads in flight per thread, then the work on them
-            for (int64_t i0 = tid; i0 < N; i0 += (int64_t)kSelRegs * nt) {
-                u64 batch[kSelRegs];
-#pragma unroll
-                for (int r = 0; r < kSelRegs; ++r) {
-                    const int64_t i = i0 + (int64_t)r * nt;
-                    batch[r] = i < N ? keys[i] : 0ull;
-                }
-#pragma unroll
-                for (int r = 0; r < kSelRegs; ++r)
-                    if (batch[r]) fn(batch[r]);
+            for (int64_t i = tid; i < N; i += nt) {
+                const u64 kkey = keys[i];
+                if (kkey) fn(kkey);
             }
         }
     };
