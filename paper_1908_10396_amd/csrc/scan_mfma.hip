@@ -81,25 +81,30 @@ __device__ __forceinline__ uint32_t sort32_desc(uint32_t v) // one key per lane 
     return v;
 }
 
-// Merges a batch (one key per lane, sorted descending, empty lanes 0) into a sorted list of
-// ns slots of 64 keys; keeps the 64*ns largest.
-__device__ __forceinline__ void list32_insert_sorted(uint32_t *list, int ns, uint32_t b)
+constexpr int kMfmaMaxNs = 8; // list slots of 64 keys (R <= 512)
+
+__device__ __forceinline__ uint32_t uniform_lane(uint32_t v, int src) // lane src's value, as a scalar
+{
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, src);
+}
+
+// Merges a batch (one key per lane, sorted descending, empty lanes 0) into a sorted list of ns
+// slots of 64 keys held in registers (v[s] = key s*64 + lane); keeps the 64*ns largest.
+__device__ __forceinline__ void list32_insert_sorted(uint32_t (&v)[kMfmaMaxNs], int ns, uint32_t b)
 {
     const int lane = lane_id();
-    if ((uint32_t)__shfl((int)b, 0, 64) <= list[ns * 64 - 1]) return; // best of the batch is below the whole list
-    for (int s = 0; s < ns; ++s) {
-        const uint32_t v = list[s * 64 + lane];
-        const uint32_t bmax = (uint32_t)__shfl((int)b, 0, 64);
-        const uint32_t vmin = (uint32_t)__shfl((int)v, 63, 64);
-        if (bmax == 0u) break;     // nothing left to place
+#pragma unroll
+    for (int s = 0; s < kMfmaMaxNs; ++s) {
+        if (s >= ns) break;
+        const uint32_t bmax = uniform_lane(b, 0), vmin = uniform_lane(v[s], 63);
+        if (bmax == 0u) break;      // nothing left to place
         if (bmax <= vmin) continue; // slot s keeps all its keys; the batch may still beat later slots
         const uint32_t br = (uint32_t)__shfl((int)b, 63 - lane, 64);
-        const uint32_t hi = v > br ? v : br; // the 64 largest of slot + batch, bitonic
-        const uint32_t lo = v > br ? br : v; // the 64 smallest, bitonic
-        list[s * 64 + lane] = merge32_desc(hi);
-        if (s + 1 < ns) b = merge32_desc(lo);
+        const uint32_t hi = v[s] > br ? v[s] : br; // the 64 largest of slot + batch, bitonic
+        const uint32_t lo = v[s] > br ? br : v[s]; // the 64 smallest, bitonic
+        v[s] = merge32_desc(hi);
+        b = merge32_desc(lo);
     }
-    wave_lds_fence();
 }
 
 // Rare path of the scan below, kept out of line so that it costs the scan no registers:
@@ -107,20 +112,31 @@ __device__ __forceinline__ void list32_insert_sorted(uint32_t *list, int ns, uin
 // cnt_b keys at pend_b, that of lane jq + 32) into the query's list, publishes the wave's
 // kw-th best in kth_row[self], reads the group's (gsz entries of kth_row) and returns the
 // query's new lower bound of the final R-th best ordering value, which it also publishes
-// in *bound_q. Called by the whole wave with uniform arguments.
+// in *bound_q. Called by the whole wave with uniform arguments. The list (global scratch)
+// is read once at the start, so that its latency passes while the keys are sorted, and
+// written back once.
 __device__ __noinline__ uint32_t mfma_flush_query(const lds_u32 *pend_a, const lds_u32 *pend_b, int cnt_a, int cnt_b,
                                                   uint32_t *list, int ns, int R, int kw, uint32_t *kth_row, int gsz,
                                                   int self, uint32_t *bound_q)
 {
     const int lane = lane_id();
-    uint32_t member = 0xffffffffu; // lane c < gsz: the kw-th best of the group's chunk c (in flight during the merge)
+    uint32_t member = 0xffffffffu; // lane c < gsz: the kw-th best of the group's chunk c
     if (lane < gsz && lane != self)
         member = __hip_atomic_load(kth_row + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    uint32_t v[kMfmaMaxNs];
+#pragma unroll
+    for (int s = 0; s < kMfmaMaxNs; ++s) v[s] = s < ns ? list[s * 64 + lane] : 0u;
     wave_lds_fence();
-    if (cnt_a > 0) list32_insert_sorted(list, ns, sort32_desc(lane < cnt_a ? pend_a[lane] : 0u));
-    if (cnt_b > 0) list32_insert_sorted(list, ns, sort32_desc(lane < cnt_b ? pend_b[lane] : 0u));
-    const uint32_t ord = list[R - 1] >> kIdBits;
-    const uint32_t ord_kw = list[kw - 1] >> kIdBits;
+    if (cnt_a > 0) list32_insert_sorted(v, ns, sort32_desc(lane < cnt_a ? pend_a[lane] : 0u));
+    if (cnt_b > 0) list32_insert_sorted(v, ns, sort32_desc(lane < cnt_b ? pend_b[lane] : 0u));
+    uint32_t ord = 0u, ord_kw = 0u;
+#pragma unroll
+    for (int s = 0; s < kMfmaMaxNs; ++s) {
+        if (s >= ns) break;
+        list[s * 64 + lane] = v[s];
+        if ((R - 1) >> 6 == s) ord = uniform_lane(v[s], (R - 1) & 63) >> kIdBits;
+        if ((kw - 1) >> 6 == s) ord_kw = uniform_lane(v[s], (kw - 1) & 63) >> kIdBits;
+    }
     if (lane == self) member = ord_kw;
 #pragma unroll
     for (int m = 32; m > 0; m >>= 1) {
@@ -132,6 +148,7 @@ __device__ __noinline__ uint32_t mfma_flush_query(const lds_u32 *pend_a, const l
         if (ord_kw > 0u) __hip_atomic_store(kth_row + self, ord_kw, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (best > 0u) __hip_atomic_fetch_max(bound_q, best, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
+    wave_lds_fence();
     return best;
 }
 
