@@ -97,7 +97,7 @@ __device__ __noinline__ void wave_list_insert_sorted(u64 *list, int ns, u64 p)
 }
 
 // Sorts the cnt (<= 64) pending keys and merges them into the list.
-__device__ __forceinline__ void wave_list_flush(u64 *list, int ns, const u64 *pend, int cnt)
+__device__ __noinline__ void wave_list_flush(u64 *list, int ns, const u64 *pend, int cnt)
 {
     wave_lds_fence();
     u64 p = lane_id() < cnt ? pend[lane_id()] : 0ull;
