@@ -54,7 +54,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", default="glove", choices=["tiny", "glove", "glove_ivf", "large4", "large8"],
+    ap.add_argument("--config", default="glove", choices=["tiny", "glove", "glove100", "glove_ivf", "large4", "large8"],
                     help="workload (default: the Glove-shaped one the headline metric is quoted on)")
     ap.add_argument("--batch", type=int, default=0, help="queries per step (default: the configuration's)")
     ap.add_argument("--n", type=int, default=0, help="override the number of points (debugging)")
@@ -199,9 +199,9 @@ def main():
     adds = (2.0 if nib_tile else 1.0) * nb * scanned * B
     lds_bytes = (8.0 if nib_tile else 4.0) * nb * scanned * B
     if n_leaves:
-        scan_kernel = "adc_scan_kernel<1,false,%d,1>" % (nb if nb in (8, 25, 32) else 0)
+        scan_kernel = "adc_scan_kernel<1,false,%d,1>" % (nb if nb in (8, 13, 25, 32) else 0)
     else:
-        scan_kernel = "adc_scan_kernel<%d,false,%d,0>" % (8 if nib_tile else 4, nb if nb in (8, 25, 32) else 0)
+        scan_kernel = "adc_scan_kernel<%d,false,%d,0>" % (8 if nib_tile else 4, nb if nb in (8, 13, 25, 32) else 0)
     batch_roof = {"bound": "alu", "achieved": adds / (scan_ms * 1e-3) / 1e12, "peak": VALU_PEAK_TOPS,
                   "unit": "TFLOP/s", "traffic": None, "kernel": scan_kernel, "avg_launch_ms": scan_ms,
                   "note": "fp32 adds of table entries (no multiplies); the other binding unit is the LDS gather",
@@ -215,7 +215,7 @@ def main():
     qps8 = B * max(2, args.steps // 2) / dt8
     log("[bench] u8   batch %d: %.0f q/s, stages(ms) %s" % (B, qps8, stage8_ms))
     u8_roof = None
-    if bits == 4 and not n_leaves and B >= 16 and nb in (8, 25, 32):
+    if bits == 4 and not n_leaves and B >= 16 and nb in (8, 13, 25, 32):
         # one-hot contraction on int8 MFMA: 32 points x 32 queries x 32 positions per instruction,
         # two subspaces (16 positions each) per instruction, NB instructions per (32 points, 32 queries)
         n_pad = float((n + 255) // 256 * 256)

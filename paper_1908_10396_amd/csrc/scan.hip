@@ -921,6 +921,7 @@ static int launch_nb(const ScanParams &p, const ScanShape &s, int grid, hipStrea
 {
     switch (p.NB) {
     case 8: return launch_one<QT, U8, 8, MODE>(p, s, grid, st);
+    case 13: return launch_one<QT, U8, 13, MODE>(p, s, grid, st);
     case 25: return launch_one<QT, U8, 25, MODE>(p, s, grid, st);
     case 32: return launch_one<QT, U8, 32, MODE>(p, s, grid, st);
     default: return launch_one<QT, U8, 0, MODE>(p, s, grid, st);
@@ -976,6 +977,7 @@ static int launch_block_max_nb(const ScanParams &p, int waves, hipStream_t st)
 {
     switch (p.NB) {
     case 8: return launch_block_max_one<U8, 8>(p, waves, st);
+    case 13: return launch_block_max_one<U8, 13>(p, waves, st);
     case 25: return launch_block_max_one<U8, 25>(p, waves, st);
     case 32: return launch_block_max_one<U8, 32>(p, waves, st);
     default: return launch_block_max_one<U8, 0>(p, waves, st);
@@ -1001,6 +1003,7 @@ static int launch_block_max_nibble_nb(const ScanParams &p, hipStream_t st)
 {
     switch (p.NB) {
     case 8: return launch_block_max_nibble_one<U8, 8>(p, st);
+    case 13: return launch_block_max_nibble_one<U8, 13>(p, st);
     case 25: return launch_block_max_nibble_one<U8, 25>(p, st);
     case 32: return launch_block_max_nibble_one<U8, 32>(p, st);
     default: return launch_block_max_nibble_one<U8, 0>(p, st);
@@ -1053,6 +1056,7 @@ static int launch_rescan_u(const ScanParams &p, const FinishParams &f, hipStream
     if (use_nibble_tables(p)) {
         switch (p.NB) {
         case 8: return launch_rescan_one<U8, 8, true>(p, f, st);
+        case 13: return launch_rescan_one<U8, 13, true>(p, f, st);
         case 25: return launch_rescan_one<U8, 25, true>(p, f, st);
         case 32: return launch_rescan_one<U8, 32, true>(p, f, st);
         default: return launch_rescan_one<U8, 0, true>(p, f, st);

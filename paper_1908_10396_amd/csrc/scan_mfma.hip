@@ -355,7 +355,7 @@ adc_mfma_scan_kernel(const ScanParams p)
 
 bool scan_mfma_supported(int NB, int bits)
 {
-    return bits == 4 && (NB == 8 || NB == 25 || NB == 32);
+    return bits == 4 && (NB == 8 || NB == 13 || NB == 25 || NB == 32);
 }
 
 void scan_mfma_plan(int B, int64_t n_blocks, int target_waves, ScanParams *p)
@@ -411,6 +411,7 @@ int launch_scan_mfma(const ScanParams &p, hipStream_t st)
     const bool store = p.scores_out != nullptr;
     switch (p.NB) {
     case 8: return store ? launch_mfma_one<8, true>(p, st) : launch_mfma_one<8, false>(p, st);
+    case 13: return store ? launch_mfma_one<13, true>(p, st) : launch_mfma_one<13, false>(p, st);
     case 25: return store ? launch_mfma_one<25, true>(p, st) : launch_mfma_one<25, false>(p, st);
     default: return store ? launch_mfma_one<32, true>(p, st) : launch_mfma_one<32, false>(p, st);
     }

@@ -51,6 +51,7 @@ CASES = {
     "generic_nb7": (1_999, 28, 14, 4, 9),
     "odd_m_nb4": (1_030, 21, 7, 4, 5),
     "odd_m_nb25": (2_100, 98, 49, 4, 40),
+    "bits100_nb13": (3_000, 100, 25, 4, 33),
     "bits8_nb3": (777, 12, 3, 8, 6),
 }
 
