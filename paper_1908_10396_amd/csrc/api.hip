@@ -8,6 +8,7 @@
 #include <new>
 
 #include "avq_internal.h"
+#include <cmath>
 
 namespace avq {
 
@@ -460,8 +461,20 @@ static void fill_scan_params(const avq_index *idx, int nq, int R, int ns, ScanPa
 static void plan_flat(const avq_index *idx, const ScanShape &s, int nq, ScanParams *p)
 {
     p->n_tiles = (nq + s.qt - 1) / s.qt;
-    const int target = idx->tune_target_wgs > 0 ? idx->tune_target_wgs : 1024;
+    // one resident set of workgroups: the fp32 tile of 8 runs two workgroups per compute unit
+    const int builtin = (s.qt == 8 && s.lists_global && idx->cfg.bits == 4) ? 512 : 1024;
+    const int target = idx->tune_target_wgs > 0 ? idx->tune_target_wgs : builtin;
     int64_t chunks = (target + p->n_tiles - 1) / p->n_tiles;
+    if (idx->tune_target_wgs <= 0 && p->n_tiles > target) {
+        // more tiles than fit at once: a few chunks per tile so that the last round of workgroups
+        // is nearly full (each extra chunk costs about 2 % in list handling)
+        double best = 0.0;
+        for (int c = 1; c <= 4; ++c) {
+            const double rounds = (double)p->n_tiles * c / target;
+            const double score = rounds / std::ceil(rounds) * (1.0 - 0.02 * (c - 1));
+            if (score > best) { best = score; chunks = c; }
+        }
+    }
     const int64_t max_chunks = std::max<int64_t>(1, idx->n_blocks / s.waves);
     chunks = std::max<int64_t>(1, std::min(chunks, max_chunks));
     const int64_t bpc = (idx->n_blocks + chunks - 1) / chunks;
