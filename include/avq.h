@@ -107,6 +107,26 @@ int avq_train(avq_index *idx, const float *x, int64_t n_train, void *hip_stream)
  * Synchronises the stream. */
 int avq_encode(avq_index *idx, const float *x, int64_t n, void *hip_stream);
 
+/* Section 4.2, codeword-update step for all dictionaries at once, with the
+ * codes of the last avq_encode / avq_set_database held fixed (Appendix 7.5):
+ * the anisotropic loss sum_i eta_i*||r_par,i||^2 + ||r_perp,i||^2 is a convex
+ * quadratic in the stacked codewords; its normal equations
+ *   (diag(count) + sum_i w_i s_i s_i^T) c = sum_i eta_i s_i,
+ *   w_i = (eta_i - 1)/||x_i||^2, s_i = x_i's coordinates placed at the slots
+ *   of the codewords point i uses,
+ * are solved by conjugate gradients from the current dictionaries, without
+ * forming the matrix (one pass over x per iteration), in fp64, until
+ * ||residual|| <= tol*||rhs|| or max_iters iterations. A codeword no point
+ * uses keeps its value. x: device [n][d], the rows the codes were made from
+ * (n must equal avq_size). The dictionaries are replaced in place (rounded to
+ * fp32); the stored codes stay as they are, so alternate with avq_encode to
+ * iterate Section 4.2. iters_out / rel_residual_out (host, may be NULL):
+ * iterations done and ||residual||/||rhs|| at exit.
+ * Flat index only (AVQ_EINVAL with leaves). AVQ_ESTATE: no codes yet.
+ * Allocates scratch with hipMalloc; synchronises the stream. */
+int avq_update_codebooks(avq_index *idx, const float *x, int64_t n, int32_t max_iters, double tol,
+                         int32_t *iters_out, double *rel_residual_out, void *hip_stream);
+
 /* The query path (Sections 2.2.2 and 4.1 plus exact re-scoring).
  * queries: device [nq][d]; ids_out: device int32 [nq][k]; scores_out: device
  * fp32 [nq][k]. Steps, all on the GPU:

@@ -21,7 +21,7 @@ STAGES = ("leaf_select", "lut", "scan", "merge", "finalize", "rescan")
 
 # every symbol include/avq.h declares
 SYMBOLS = [
-    "avq_create", "avq_destroy", "avq_train", "avq_encode", "avq_search", "avq_brute_force",
+    "avq_create", "avq_destroy", "avq_train", "avq_encode", "avq_update_codebooks", "avq_search", "avq_brute_force",
     "avq_set_codebooks", "avq_get_codebooks", "avq_set_leaf_centers", "avq_get_leaf_centers",
     "avq_set_database", "avq_get_codes", "avq_get_leaf_assign", "avq_size", "avq_debug_lut",
     "avq_debug_adc_scores", "avq_debug_leaf_select", "avq_eta", "avq_set_tuning",
@@ -61,6 +61,7 @@ def lib():
         L.avq_destroy.restype = None
         L.avq_train.argtypes = [vp, vp, i64, vp]
         L.avq_encode.argtypes = [vp, vp, i64, vp]
+        L.avq_update_codebooks.argtypes = [vp, vp, i64, i32, C.c_double, C.POINTER(i32), C.POINTER(C.c_double), vp]
         L.avq_search.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, vp, vp]
         L.avq_brute_force.argtypes = [vp, vp, i32, i32, vp, vp, vp]
         L.avq_set_codebooks.argtypes = [vp, vp]
@@ -177,6 +178,15 @@ class Index:
         if self.cfg.borrow_x:
             self._keep = [x]
         _check(lib().avq_encode(self._h, p, x.shape[0], _stream_ptr(stream)))
+
+    def update_codebooks(self, x, max_iters=1000, tol=1e-10, stream=None):
+        """Returns (iterations, relative residual)."""
+        torch = _torch()
+        p = _dev(x, torch.float32, "x")
+        it, rel = C.c_int32(0), C.c_double(0.0)
+        _check(lib().avq_update_codebooks(self._h, p, x.shape[0], max_iters, tol, C.byref(it), C.byref(rel),
+                                          _stream_ptr(stream)))
+        return it.value, rel.value
 
     def set_codebooks(self, codebooks):
         import numpy as np

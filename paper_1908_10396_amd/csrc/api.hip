@@ -404,6 +404,37 @@ extern "C" int avq_encode(avq_index *idx, const float *x, int64_t n, void *hip_s
     return install_database(idx, x, n, st);
 }
 
+extern "C" int avq_update_codebooks(avq_index *idx, const float *x, int64_t n, int32_t max_iters, double tol,
+                                    int32_t *iters_out, double *rel_residual_out, void *hip_stream)
+{
+    AVQ_TRY(check_index(idx));
+    hipStream_t st = (hipStream_t)hip_stream;
+    const avq_config &c = idx->cfg;
+    if (!x) { set_error("avq_update_codebooks: x is NULL"); return AVQ_EINVAL; }
+    if (c.n_leaves > 0) { set_error("avq_update_codebooks: flat index only"); return AVQ_EINVAL; }
+    if (idx->n <= 0) { set_error("avq_update_codebooks: no codes yet (avq_encode first)"); return AVQ_ESTATE; }
+    if (n != idx->n) {
+        set_error("avq_update_codebooks: n = %lld but the codes are of %lld points", (long long)n, (long long)idx->n);
+        return AVQ_EINVAL;
+    }
+    if (max_iters < 1 || !(tol >= 0.0)) { set_error("avq_update_codebooks: max_iters < 1 or tol < 0"); return AVQ_EINVAL; }
+    const int ds = c.d / c.M, D = c.M * idx->kc * ds;
+    DevBuf scratch;
+    int iters = 0;
+    double rel = 0.0;
+    int rc = scratch.reserve(pq_update_scratch_bytes(n, D, c.M * idx->kc));
+    if (rc == AVQ_OK)
+        rc = pq_joint_update_device(x, n, c.d, c.M, idx->kc, c.bits, idx->codes_logical.as<uint8_t>(), c.eta_mode,
+                                    (double)c.T, (double)c.eta_explicit, idx->codebooks.as<float>(), scratch.p,
+                                    max_iters, tol, &iters, &rel, st);
+    if (rc == AVQ_OK && hipStreamSynchronize(st) != hipSuccess) { set_error("avq_update_codebooks: stream error"); rc = AVQ_EHIP; }
+    scratch.release();
+    if (rc != AVQ_OK) return rc;
+    if (iters_out) *iters_out = iters;
+    if (rel_residual_out) *rel_residual_out = rel;
+    return AVQ_OK;
+}
+
 extern "C" int avq_get_codes(avq_index *idx, uint8_t *out)
 {
     AVQ_TRY(check_index(idx));

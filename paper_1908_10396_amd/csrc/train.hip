@@ -344,4 +344,246 @@ int launch_encode(const float *x, int64_t n, int d, int M, int kc, int bits,
     return AVQ_OK;
 }
 
+// ---- joint dictionary update under the anisotropic loss ---------------------------------
+//
+// Section 4.2 alternates assignment and codeword update; with the codes fixed the loss is a
+// convex quadratic in the stacked dictionaries c (D = M*kc*ds unknowns) and Appendix 7.5
+// gives its normal equations
+//     (sum_i B_i^T A_i B_i) c = sum_i h_par,i B_i^T x_i,
+//     A_i = h_perp,i I + (h_par,i - h_perp,i) x_i x_i^T / ||x_i||^2,
+// where B_i picks codeword code_i[m] of every dictionary m (x~_i = B_i c). With h_perp = 1,
+// h_par = eta_i and s_i = B_i^T x_i (x_i's coordinates scattered to its codewords' slots):
+//     A = diag(counts) + sum_i w_i s_i s_i^T,  w_i = (eta_i - 1)/||x_i||^2,  b = sum_i eta_i s_i.
+// A is never formed: conjugate gradients need only v -> A v, one pass over the points with
+// a gather of d values of v, a dot product and a scatter-add. Codewords no point uses keep
+// their value (unit diagonal, right-hand side = old value). All in fp64.
+
+__device__ __forceinline__ int code_at(const uint8_t *row, int m, int bits)
+{
+    return bits == 8 ? (int)row[m] : (int)((row[m >> 1] >> (4 * (m & 1))) & 15);
+}
+
+// One wave per point (grid-stride): w_i, counts, right-hand side and the rank-one part of A's diagonal.
+__global__ void __launch_bounds__(256)
+pq_update_setup_kernel(const float *__restrict__ x, int64_t n, int d, int M, int kc, int bits, int NB,
+                       const uint8_t *__restrict__ codes, int eta_mode, double T, double eta_explicit,
+                       double *__restrict__ w_out, double *__restrict__ eta_out, double *__restrict__ b,
+                       double *__restrict__ dA, unsigned int *__restrict__ cnt)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t wave0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int64_t n_waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+    const int ds = d / M;
+    for (int64_t i = wave0; i < n; i += n_waves) {
+        const float *xi = x + (size_t)i * d;
+        const uint8_t *ci = codes + (size_t)i * NB;
+        double part = 0.0;
+        for (int a = lane; a < d; a += 64) part += (double)xi[a] * (double)xi[a];
+        for (int m = 32; m > 0; m >>= 1) part += __shfl_xor(part, m, 64);
+        const double nx2 = part;
+        const double eta = eta_of_norm(d, T, sqrt(nx2), eta_mode, eta_explicit);
+        const double wi = nx2 > 0.0 ? (eta - 1.0) / nx2 : 0.0;
+        if (lane == 0) {
+            w_out[i] = wi;
+            eta_out[i] = eta;
+        }
+        for (int a = lane; a < d; a += 64) {
+            const int m = a / ds;
+            const int slot = m * kc + code_at(ci, m, bits);
+            unsafeAtomicAdd(&b[(size_t)slot * ds + (a - m * ds)], eta * (double)xi[a]);
+            if (wi != 0.0) unsafeAtomicAdd(&dA[(size_t)slot * ds + (a - m * ds)], wi * (double)xi[a] * (double)xi[a]);
+            if (a == m * ds) atomicAdd(&cnt[slot], 1u);
+        }
+    }
+}
+
+// y += sum_i w_i s_i (s_i^T v). One wave per point. With use_lds the sum is accumulated per
+// workgroup in LDS (D doubles) and added to y once per workgroup; otherwise (D too large for
+// LDS) every term goes to y directly.
+__global__ void __launch_bounds__(256)
+pq_update_matvec_kernel(const float *__restrict__ x, int64_t n, int d, int M, int kc, int bits, int NB,
+                        const uint8_t *__restrict__ codes, const double *__restrict__ w,
+                        const double *__restrict__ v, double *__restrict__ y, int D, int use_lds)
+{
+    extern __shared__ double acc_lds[]; // [D] when use_lds
+    double *acc = use_lds ? acc_lds : y;
+    if (use_lds) {
+        for (int r = threadIdx.x; r < D; r += blockDim.x) acc_lds[r] = 0.0;
+        __syncthreads();
+    }
+    const int lane = threadIdx.x & 63;
+    const int64_t wave0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int64_t n_waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+    const int ds = d / M;
+    for (int64_t i = wave0; i < n; i += n_waves) {
+        const float *xi = x + (size_t)i * d;
+        const uint8_t *ci = codes + (size_t)i * NB;
+        double t = 0.0;
+        for (int a = lane; a < d; a += 64) {
+            const int m = a / ds;
+            const int r = (m * kc + code_at(ci, m, bits)) * ds + (a - m * ds);
+            t += (double)xi[a] * v[r];
+        }
+        for (int m = 32; m > 0; m >>= 1) t += __shfl_xor(t, m, 64);
+        const double wt = w[i] * t;
+        if (wt != 0.0) {
+            for (int a = lane; a < d; a += 64) {
+                const int m = a / ds;
+                const int r = (m * kc + code_at(ci, m, bits)) * ds + (a - m * ds);
+                if (use_lds) atomicAdd(&acc_lds[r], wt * (double)xi[a]);
+                else unsafeAtomicAdd(&acc[r], wt * (double)xi[a]);
+            }
+        }
+    }
+    if (!use_lds) return;
+    __syncthreads();
+    for (int r = threadIdx.x; r < D; r += blockDim.x)
+        if (acc_lds[r] != 0.0) unsafeAtomicAdd(&y[r], acc_lds[r]);
+}
+
+// Conjugate gradients with the diagonal of A as preconditioner (exact in one step when every
+// eta_i = 1, where A is diagonal). state[0] = r.z, state[1] = b.b, state[2] = iterations done,
+// state[3] = r.r. One workgroup.
+// mode 0 (start, after y = A c0 is complete): r = b - y, z = r/dA, p = z, y = diag(count) * p.
+// mode 1 (step, after y = A p is complete): the usual update, then y = diag(count) * p for the next product.
+__global__ void __launch_bounds__(1024)
+pq_update_cg_kernel(int mode, int D, int ds, const unsigned int *__restrict__ cnt, const double *__restrict__ b,
+                    const double *__restrict__ dA, double *__restrict__ c, double *__restrict__ r,
+                    double *__restrict__ p, double *__restrict__ y, double *__restrict__ state, double tol2)
+{
+    __shared__ double red[1024];
+    const int tid = threadIdx.x, nt = blockDim.x;
+    auto reduce = [&](double v) -> double {
+        red[tid] = v;
+        __syncthreads();
+        for (int s = nt >> 1; s > 0; s >>= 1) {
+            if (tid < s) red[tid] += red[tid + s];
+            __syncthreads();
+        }
+        const double out = red[0];
+        __syncthreads();
+        return out;
+    };
+    auto diag = [&](int e) -> double { const unsigned int k = cnt[e / ds]; return k ? (double)k : 1.0; };
+    if (mode == 0) {
+        double rz = 0.0, rr = 0.0, bb = 0.0;
+        for (int e = tid; e < D; e += nt) {
+            const double re = b[e] - y[e];
+            const double ze = re / dA[e];
+            r[e] = re;
+            p[e] = ze;
+            rz += re * ze;
+            rr += re * re;
+            bb += b[e] * b[e];
+        }
+        rz = reduce(rz);
+        rr = reduce(rr);
+        bb = reduce(bb);
+        for (int e = tid; e < D; e += nt) y[e] = diag(e) * p[e];
+        if (tid == 0) { state[0] = rz; state[1] = bb; state[2] = 0.0; state[3] = rr; }
+        return;
+    }
+    const double rz = state[0];
+    if (rz == 0.0 || state[3] <= tol2 * state[1]) return; // converged: later steps of a burst do nothing
+    double pap = 0.0;
+    for (int e = tid; e < D; e += nt) pap += p[e] * y[e];
+    pap = reduce(pap);
+    const double alpha = rz / pap;
+    double rz2 = 0.0, rr2 = 0.0;
+    for (int e = tid; e < D; e += nt) {
+        c[e] += alpha * p[e];
+        const double re = r[e] - alpha * y[e];
+        r[e] = re;
+        rz2 += re * re / dA[e];
+        rr2 += re * re;
+    }
+    rz2 = reduce(rz2);
+    rr2 = reduce(rr2);
+    const double beta = rz2 / rz;
+    for (int e = tid; e < D; e += nt) {
+        const double pe = r[e] / dA[e] + beta * p[e];
+        p[e] = pe;
+        y[e] = diag(e) * pe;
+    }
+    if (tid == 0) { state[0] = rz2; state[2] += 1.0; state[3] = rr2; }
+}
+
+// c0 (the current dictionaries, as doubles), the right-hand side of unused codewords,
+// y = diag(count) * c0, and the counts added to A's diagonal
+__global__ void pq_update_init_kernel(int D, int ds, const unsigned int *__restrict__ cnt,
+                                      const float *__restrict__ codebooks, double *__restrict__ c,
+                                      double *__restrict__ b, double *__restrict__ y, double *__restrict__ dA)
+{
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= D) return;
+    const double c0 = (double)codebooks[e];
+    c[e] = c0;
+    const unsigned int k = cnt[e / ds];
+    if (k == 0u) b[e] = c0;
+    y[e] = (k ? (double)k : 1.0) * c0;
+    dA[e] += k ? (double)k : 1.0;
+}
+
+__global__ void pq_update_store_kernel(int D, const double *__restrict__ c, float *__restrict__ codebooks)
+{
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e < D) codebooks[e] = (float)c[e];
+}
+
+// scratch: doubles w[n], eta[n], then b, c, r, p, y, dA of D each, state[4]; then cnt[M*kc] unsigned
+size_t pq_update_scratch_bytes(int64_t n, int D, int slots)
+{
+    return sizeof(double) * ((size_t)2 * n + (size_t)6 * D + 4) + sizeof(unsigned int) * (size_t)slots;
+}
+
+int pq_joint_update_device(const float *x, int64_t n, int d, int M, int kc, int bits, const uint8_t *codes,
+                           int eta_mode, double T, double eta_explicit, float *codebooks, void *scratch,
+                           int max_iters, double tol, int *iters_out, double *rel_residual_out, hipStream_t st)
+{
+    const int ds = d / M, D = M * kc * ds, slots = M * kc, NB = (M * bits + 7) / 8;
+    const int use_lds = (size_t)D * sizeof(double) <= 64 * 1024;
+    double *w = (double *)scratch, *eta = w + n, *b = eta + n, *c = b + D, *r = c + D, *p = r + D, *y = p + D, *dA = y + D;
+    double *state = dA + D;
+    unsigned int *cnt = (unsigned int *)(state + 4);
+    AVQ_HIP(hipMemsetAsync(b, 0, sizeof(double) * ((size_t)6 * D + 4) + sizeof(unsigned int) * (size_t)slots, st));
+    const int grid = (int)std::min<int64_t>(1024, (n + 3) / 4);
+    hipLaunchKernelGGL(pq_update_setup_kernel, dim3(grid), dim3(256), 0, st, x, n, d, M, kc, bits, NB, codes,
+                       eta_mode, T, eta_explicit, w, eta, b, dA, cnt);
+    AVQ_HIP(hipGetLastError());
+    const int vgrid = (D + 255) / 256;
+    hipLaunchKernelGGL(pq_update_init_kernel, dim3(vgrid), dim3(256), 0, st, D, ds, cnt, codebooks, c, b, y, dA);
+    AVQ_HIP(hipGetLastError());
+    const size_t lds = use_lds ? sizeof(double) * (size_t)D : 0;
+    static bool attr_done = false;
+    if (!attr_done) {
+        AVQ_HIP(hipFuncSetAttribute((const void *)pq_update_matvec_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024));
+        attr_done = true;
+    }
+    // y = A c0
+    hipLaunchKernelGGL(pq_update_matvec_kernel, dim3(grid), dim3(256), lds, st, x, n, d, M, kc, bits, NB, codes, w, c, y, D, use_lds);
+    AVQ_HIP(hipGetLastError());
+    hipLaunchKernelGGL(pq_update_cg_kernel, dim3(1), dim3(1024), 0, st, 0, D, ds, cnt, b, dA, c, r, p, y, state, tol * tol);
+    AVQ_HIP(hipGetLastError());
+    double host_state[4] = {0, 0, 0, 0};
+    int done = 0;
+    const int check_every = 16;
+    while (done < max_iters) {
+        const int burst = std::min(check_every, max_iters - done);
+        for (int it = 0; it < burst; ++it) {
+            hipLaunchKernelGGL(pq_update_matvec_kernel, dim3(grid), dim3(256), lds, st, x, n, d, M, kc, bits, NB, codes, w, p, y, D, use_lds);
+            hipLaunchKernelGGL(pq_update_cg_kernel, dim3(1), dim3(1024), 0, st, 1, D, ds, cnt, b, dA, c, r, p, y, state, tol * tol);
+        }
+        AVQ_HIP(hipGetLastError());
+        done += burst;
+        AVQ_HIP(hipMemcpyAsync(host_state, state, sizeof(host_state), hipMemcpyDeviceToHost, st));
+        AVQ_HIP(hipStreamSynchronize(st));
+        if (host_state[1] == 0.0 || host_state[3] <= tol * tol * host_state[1]) break;
+    }
+    hipLaunchKernelGGL(pq_update_store_kernel, dim3(vgrid), dim3(256), 0, st, D, c, codebooks);
+    AVQ_HIP(hipGetLastError());
+    if (iters_out) *iters_out = (int)host_state[2];
+    if (rel_residual_out) *rel_residual_out = host_state[1] > 0.0 ? sqrt(host_state[3] / host_state[1]) : 0.0;
+    return AVQ_OK;
+}
+
 } // namespace avq

@@ -1,10 +1,12 @@
 """Quality of the quantisation on synthetic data, in the paper's own terms.
 
-    python -m paper_1908_10396_amd.quality [--config glove] [--queries 256] [--n N]
+    python -m paper_1908_10396_amd.quality [--config glove] [--queries 256] [--n N] [--alternations K]
 
-Encodes the same datapoints twice with the same dictionaries -- once with the
+Encodes the same datapoints with the same k-means dictionaries -- once with the
 reconstruction loss (eta = 1) and once with the anisotropic loss (eta from
-T = 0.2, Section 3.2) -- and reports, for the ADC scores without re-ranking:
+T = 0.2, Section 3.2) -- then, with --alternations K, K more rounds of
+Section 4.2's alternation (dictionary update with the codes fixed, then
+re-assignment), and reports, for the ADC scores without re-ranking:
 
  * Recall 1@N: how often the exact top-1 of a query is among its N best ADC
    scores (the metric of Section 5.2 / Figure 2a);
@@ -21,6 +23,7 @@ import argparse
 import json
 import os
 import sys
+import time
 
 import numpy as np
 
@@ -35,6 +38,8 @@ def main():
     ap.add_argument("--queries", type=int, default=256)
     ap.add_argument("--n", type=int, default=0, help="use only the first N points")
     ap.add_argument("--T", type=float, default=0.2)
+    ap.add_argument("--alternations", type=int, default=0,
+                    help="rounds of (dictionary update, re-assignment) under the anisotropic loss")
     args = ap.parse_args()
 
     import torch
@@ -60,11 +65,23 @@ def main():
 
     out = {"config": args.config, "n": n, "d": d, "M": M, "bits": bits, "T": args.T, "queries": args.queries,
            "eta_anisotropic": avq.eta(d, args.T, 1.0), "losses": {}}
-    for name, kw in (("reconstruction (eta = 1)", dict(eta_mode=avq.ETA_EXPLICIT, eta_explicit=1.0)),
-                     ("anisotropic (T = %g)" % args.T, dict(eta_mode=avq.ETA_LIMIT))):
+    variants = [("reconstruction (eta = 1)", dict(eta_mode=avq.ETA_EXPLICIT, eta_explicit=1.0), 0),
+                ("anisotropic (T = %g)" % args.T, dict(eta_mode=avq.ETA_LIMIT), 0)]
+    if args.alternations:
+        variants.append(("anisotropic + %d dictionary updates" % args.alternations, dict(eta_mode=avq.ETA_LIMIT),
+                         args.alternations))
+    for name, kw, rounds in variants:
         idx = avq.Index(d, M, bits, T=args.T, kmeans_iters=20, encode_passes=10, seed=cfg["seed"], **kw)
         idx.set_codebooks(codebooks)
         idx.encode(xd)
+        for r in range(rounds):
+            t0 = time.time()
+            iters, rel = idx.update_codebooks(xd, max_iters=2000, tol=1e-8)
+            t1 = time.time()
+            idx.encode(xd)
+            torch.cuda.synchronize()
+            print("  round %d: update %.3f s (%d CG iterations, residual %.1e), re-assignment %.3f s"
+                  % (r + 1, t1 - t0, iters, rel, time.time() - t1), file=sys.stderr, flush=True)
         if gt_ids is None:                                     # exact top-1 (the same for both encodings)
             gi, gs = idx.brute_force(qd, 1)
             gt_ids, gt_sc = gi.cpu().numpy()[:, 0], gs.cpu().numpy()[:, 0]

@@ -377,6 +377,124 @@ def test_partitioned_train_and_encode(ivf_case):
     np.testing.assert_array_equal(sc.cpu().numpy(), os_)
 
 
+@pytest.mark.parametrize("n,d,M,bits", [(4000, 8, 4, 4), (3000, 100, 50, 4), (1200, 8, 2, 8)])
+def test_update_codebooks_matches(n, d, M, bits):
+    # Section 4.2's codeword update for all dictionaries at once (Appendix 7.5): the library solves
+    # the normal equations by conjugate gradients without forming them, the oracle forms and
+    # factorises them. Both in fp64, results rounded to fp32; the iteration stops at a relative
+    # residual of 1e-12, far below fp32 resolution.
+    rng = np.random.default_rng(31)
+    x = unit_rows(rng, n, d) * np.exp(0.2 * rng.standard_normal((n, 1))).astype(np.float32)
+    kc = 1 << bits
+    cb = oracle.train_pq(x[:max(kc, min(n, 1500))], M, kc, 3, seed=4)
+    cb[0, 5] = 9.0                                             # far from every point: never assigned
+    idx = avq.Index(d, M, bits, T=0.2, encode_passes=3)
+    idx.set_codebooks(cb)
+    xd = dev(x)
+    idx.encode(xd)
+    codes = unpack_codes(idx.get_codes(), M, bits)
+    eta = np.array([oracle.eta_limit(d, 0.2, float(np.linalg.norm(xi.astype(np.float64)))) for xi in x])
+    want = oracle.pq_joint_update(x, codes, eta, cb)
+    iters, rel = idx.update_codebooks(xd, max_iters=4000, tol=1e-12)
+    got = idx.get_codebooks()
+    assert rel <= 1e-12 and 0 < iters <= 4000
+    np.testing.assert_allclose(got, want, rtol=2e-5, atol=2e-6)
+    # codewords that no point uses keep their value bit for bit
+    used = np.zeros((M, kc), bool)
+    for m in range(M):
+        used[m, np.unique(codes[:, m])] = True
+    assert not used[0, 5]
+    np.testing.assert_array_equal(got[~used], cb[~used])
+    # the update does not increase the loss it minimises
+    def total(cbx):
+        xt = oracle.reconstruct(codes, cbx)
+        return sum(oracle.aniso_loss(x[i], xt[i], eta[i]) for i in range(n))
+    assert total(got) <= total(cb) * (1 + 1e-9)
+    # the codes in the index are untouched and searches use the new dictionaries
+    np.testing.assert_array_equal(unpack_codes(idx.get_codes(), M, bits), codes)
+    q = unit_rows(rng, 3, d)
+    sc = idx.debug_adc_scores(dev(q), avq.LUT_F32).cpu().numpy()
+    for i in range(3):
+        np.testing.assert_array_equal(sc[i], oracle.adc_f32(oracle.lut_f32(q[i], got), codes, bits))
+
+
+def test_update_codebooks_reconstruction_loss_is_the_cluster_mean():
+    # eta = 1 everywhere: the normal equations are diagonal and the solution is the mean of the
+    # sub-vectors assigned to each codeword (the k-means update, Section 4.2 with h_par = h_perp)
+    rng = np.random.default_rng(32)
+    n, d, M, bits = 2500, 16, 8, 4
+    x = unit_rows(rng, n, d)
+    cb = oracle.train_pq(x, M, 16, 2, seed=5)
+    idx = avq.Index(d, M, bits, eta_mode=avq.ETA_EXPLICIT, eta_explicit=1.0)
+    idx.set_codebooks(cb)
+    xd = dev(x)
+    idx.encode(xd)
+    codes = unpack_codes(idx.get_codes(), M, bits)
+    iters, rel = idx.update_codebooks(xd, max_iters=50, tol=1e-13)
+    got = idx.get_codebooks()
+    assert iters <= 2
+    for m in range(M):
+        for j in range(16):
+            sel = codes[:, m] == j
+            if sel.any():
+                np.testing.assert_allclose(got[m, j], x[sel, 2 * m:2 * m + 2].astype(np.float64).mean(0), rtol=1e-6, atol=1e-7)
+
+
+def test_update_codebooks_single_dictionary_is_the_vq_update():
+    # M = 1: the joint system splits into one block per codeword, Theorem 4.2's closed form.
+    # 256 codewords of 36 dimensions = 9216 unknowns: more than the per-workgroup accumulator
+    # holds, so this also covers the variant that adds into device memory directly.
+    rng = np.random.default_rng(34)
+    n, d = 3000, 36
+    x = unit_rows(rng, n, d) * np.exp(0.2 * rng.standard_normal((n, 1))).astype(np.float32)
+    cb = oracle.train_pq(x, 1, 256, 2, seed=6)
+    idx = avq.Index(d, 1, 8, T=0.2, encode_passes=2)
+    idx.set_codebooks(cb)
+    xd = dev(x)
+    idx.encode(xd)
+    codes = unpack_codes(idx.get_codes(), 1, 8)[:, 0]
+    iters, rel = idx.update_codebooks(xd, max_iters=4000, tol=1e-12)
+    got = idx.get_codebooks()
+    assert rel <= 1e-12
+    eta = np.array([oracle.eta_limit(d, 0.2, float(np.linalg.norm(xi.astype(np.float64)))) for xi in x])
+    for j in range(256):
+        sel = codes == j
+        if sel.sum() == 0:
+            np.testing.assert_array_equal(got[0, j], cb[0, j])
+        else:
+            want = oracle.vq_update(x[sel], eta[sel], np.ones(int(sel.sum())))
+            np.testing.assert_allclose(got[0, j], want, rtol=2e-5, atol=2e-6)
+
+
+def test_update_codebooks_alternation_lowers_the_loss_and_rejects_bad_calls():
+    rng = np.random.default_rng(33)
+    n, d, M, bits = 6000, 32, 16, 4
+    x = unit_rows(rng, n, d)
+    xd = dev(x)
+    idx = avq.Index(d, M, bits, T=0.2, kmeans_iters=4, seed=2)
+    idx.train(xd)
+    eta = oracle.eta_limit(d, 0.2)
+    losses = []
+    for it in range(3):
+        idx.encode(xd)
+        codes = unpack_codes(idx.get_codes(), M, bits)
+        xt = oracle.reconstruct(codes, idx.get_codebooks())
+        losses.append(sum(oracle.aniso_loss(x[i], xt[i], eta) for i in range(n)))
+        idx.update_codebooks(xd)
+        xt = oracle.reconstruct(codes, idx.get_codebooks())
+        losses.append(sum(oracle.aniso_loss(x[i], xt[i], eta) for i in range(n)))
+    assert all(b <= a * (1 + 1e-7) for a, b in zip(losses, losses[1:])), losses
+    assert losses[-1] < 0.97 * losses[0], losses
+    with pytest.raises(avq.AvqError):
+        idx.update_codebooks(xd[:100].contiguous())
+    with pytest.raises(avq.AvqError):
+        idx.update_codebooks(xd, max_iters=0)
+    fresh = avq.Index(d, M, bits)
+    fresh.set_codebooks(idx.get_codebooks())
+    with pytest.raises(avq.AvqError):
+        fresh.update_codebooks(xd)
+
+
 def test_anisotropic_encoding_reduces_the_error_of_large_inner_products():
     # The point of the score-aware loss (Section 3, Figure 2b): with the same dictionaries, codes
     # assigned under the anisotropic loss estimate the inner products that matter -- those of a
