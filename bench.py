@@ -249,6 +249,22 @@ def main():
     torch.cuda.synchronize()
     ev_over_us = float(np.median([a_.elapsed_time(b_) for a_, b_ in evs])) * 1e3
     b1_roof["event_pair_overhead_us"] = ev_over_us
+    # the floor for this array on this machine: the scan's loads in the scan's launch shape, no lookups
+    words = idx.debug_stream_codes()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(200)]
+    torch.cuda.synchronize()
+    for a_, b_ in evs:
+        a_.record()
+        idx.debug_stream_codes(out=words)
+        b_.record()
+    torch.cuda.synchronize()
+    floor_us = float(np.median([a_.elapsed_time(b_) for a_, b_ in evs])) * 1e3
+    b1_roof["stream_floor"] = {"kernel": "stream_codes_kernel<%d>" % (nb if nb in (8, 13, 25, 32) else 0),
+                               "avg_launch_ms": floor_us / 1e3,
+                               "achieved": float(nb) * float(n) / (floor_us * 1e-6) / 1e9,
+                               "scan_over_floor": stage1_us["scan"] / floor_us if floor_us else None,
+                               "note": "the same loads and launch shape without table lookups, same event timing"}
+    log("[bench] code stream alone (no lookups): %.1f us" % floor_us)
     cold_us = cold_single_scan_us(avq.LUT_F32)
     b1_roof["cold"] = {"avg_launch_ms": cold_us / 1e3, "achieved": code_bytes / (cold_us * 1e-6) / 1e9 if cold_us else None,
                        "note": "1 GiB read through the Infinity Cache before every call"}

@@ -198,6 +198,15 @@ int avq_debug_adc_scores(avq_index *idx, const float *queries, int32_t nq, int32
 int avq_debug_leaf_select(avq_index *idx, const float *queries, int32_t nq, int32_t L,
                           int32_t *leaf_ids_out, float *leaf_ip_out, void *hip_stream);
 
+/* Measurement aid: reads the stored code array once (flat or partitioned), with
+ * the loads and the launch shape of the single-query ADC scan of Section 4.1 and
+ * none of its table lookups. words_out: device uint32 [ceil(n_slots/256)], one
+ * per block of 256 stored points: the xor of the block's 64*NB code words (a
+ * word holds the same code byte of four consecutive points). Its duration is
+ * the floor for a scan of this index on this machine. *n_blocks_out (host, may
+ * be NULL) receives the number of blocks; words_out may be NULL to query it. */
+int avq_debug_stream_codes(avq_index *idx, uint32_t *words_out, int64_t *n_blocks_out, void *hip_stream);
+
 /* eta of Section 3.2 for one norm, on the host (no GPU needed):
  * mode AVQ_ETA_LIMIT or AVQ_ETA_EXACT as in avq_config. */
 double avq_eta(int32_t d, double T, double norm, int32_t eta_mode);
@@ -210,7 +219,13 @@ double avq_eta(int32_t d, double T, double norm, int32_t eta_mode);
  * path; 1 disables that path), "small_batch_impl" (0: one fused kernel after
  * the block-maxima scan; 1: the same algorithm as three kernels), "scan_mfma"
  * (1: batches with 8-bit tables on 4-bit codes use the LDS-table scan instead
- * of the matrix-core scan; for that scan "scan_target_wgs" counts waves).
+ * of the matrix-core scan; for that scan "scan_target_wgs" counts waves),
+ * "scan_prefilter" (1: batches with fp32 tables on a flat index of 4-bit codes
+ * are scanned with the fp32 tables directly instead of taking candidates from
+ * the matrix-core scan over the 8-bit tables and re-scoring them in fp32;
+ * 2: candidates are taken as usual, but every odd query is treated as one
+ * whose candidates could not be verified and is scanned again with fp32
+ * tables).
  * Results never depend on these. Returns
  * AVQ_EINVAL for an unknown name. */
 int avq_set_tuning(avq_index *idx, const char *name, int32_t value);

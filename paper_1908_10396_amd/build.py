@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libavq.so")
-UNITS = ["api", "lut", "scan", "scan_mfma", "select", "ivf", "layout", "train"]
+UNITS = ["api", "lut", "scan", "scan_mfma", "refine", "select", "ivf", "layout", "train"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17",

@@ -81,6 +81,9 @@ struct ScanParams {
     uint32_t *thr_shared, *kth_shared;
     int32_t group;        // chunks per threshold group
     int32_t max_wgs;      // block-max kernels: workgroups per query at most (0 = built-in); waves loop beyond it
+    // flat scan of a compacted query list whose length only the device knows: tiles that start
+    // at or beyond *active_queries do nothing (NULL: all B queries are live)
+    const uint32_t *active_queries;
     void *scores_out;     // debug: [B][score_stride] fp32 or int32, else NULL
     int64_t score_stride;
 };
@@ -88,6 +91,7 @@ struct ScanShape { int qt; int waves; size_t lds_bytes; bool lists_global; };
 // Picks query-tile size and waves per workgroup that fit LDS. qt_hint/waves_hint 0 = auto.
 int scan_pick_shape(int NB, int bits, bool u8, int ns, int B, bool single, int qt_hint, int waves_hint,
                     ScanShape *out);
+int scan_shape_lists_in_lds(int NB, int ns, ScanShape *out); // fp32 tile of 8, 4-bit codes, lists in LDS
 // SCAN_CHUNK: flat index, grid = query tiles x chunks; SCAN_LEAVES: partitioned index, one
 // workgroup per query over its probed leaves; SCAN_BLOCKLIST: flat index, one workgroup per
 // query over the blocks named by block_keys.
@@ -104,6 +108,8 @@ int launch_scan_mfma(const ScanParams &p, hipStream_t st);
 bool small_batch_can_fuse_tables(int bits, int M, int d, bool u8);
 // Full scan that only records the best key of every block (block_max[q][blk]).
 int launch_block_max(const ScanParams &p, bool u8, int waves, hipStream_t st);
+// reads the blocked code array once, in the single-query scan's launch shape; out[blk] = xor of the block's words
+int launch_stream_codes(const uint8_t *codes, int64_t n_blocks, int NB, uint32_t *out, hipStream_t st);
 // Small batches, after launch_block_max: block selection, scan of the selected blocks,
 // final selection with exact re-scoring and output (three kernels).
 struct SmallMeta { u64 t1; uint32_t n_sel; uint32_t n_cand; };
@@ -126,8 +132,10 @@ int launch_small_final(const ScanParams &p, const FinishParams &f, bool u8, hipS
 
 // ---- select.hip ------------------------------------------------------------
 // Merges the per-chunk lists of every query into one sorted list cand[q][64*ns].
+// row_of / active (both NULL, or both set): query q's list goes to row row_of[q] of cand, and
+// only queries below *active are merged.
 int launch_merge_partials(const u64 *partial, int nq, int n_chunks, int ns, u64 *cand,
-                          hipStream_t st);
+                          hipStream_t st, const int32_t *row_of = nullptr, const uint32_t *active = nullptr);
 // The R largest of n unsorted keys per query: out[q][64*ns] sorted descending.
 int launch_select_keys(const u64 *keys, int nq, int64_t n, int ns, int R, u64 *out, hipStream_t st);
 // Final stage. reorder != 0: exact <q, x_id> for the first R candidates, then top-k.
@@ -140,6 +148,32 @@ int launch_brute_force(const float *x, int64_t n, int d, const float *queries, i
                        u64 *partial_ws, int n_chunks, u64 *cand_ws, int32_t *ids_out,
                        float *scores_out, hipStream_t st);
 int brute_force_chunks(int64_t n, int nq);
+
+// ---- refine.hip ------------------------------------------------------------
+// fp32-table search through the 8-bit-table scan (flat index, 4-bit codes). cand8[q][64*nsp]:
+// the Rp best points of every query by integer table sum, sorted. Every sum differs from the
+// exact one, in units of the query's scale, by at most M/2 (rounding of the table entries), so
+// a point outside the list cannot be among the R best by fp32 score once the list's last sum
+// is more than M + slack below its R-th. For the queries where that holds the kernel re-scores
+// the candidates in fp32 (the scan's own order of additions) and writes the R best, sorted, to
+// out[q][64*ns]; the others are appended to fail_list (count in *fail_count, zeroed by the
+// caller) and left to a plain fp32 scan.
+struct RefineParams {
+    const u64 *cand8;
+    int32_t Rp, nsp, R, ns, nq;
+    int32_t M, NB;
+    const float *lut;            // [nq][M][16]
+    const float *scale;          // [nq]
+    const uint8_t *codes;        // logical [n][NB]
+    u64 *out;                    // [nq][64*ns]
+    int32_t *fail_list;          // [nq]
+    uint32_t *fail_count;
+    int32_t force_fail_odd;      // testing aid: queries with an odd index count as unverified
+};
+int launch_refine_f32(const RefineParams &r, hipStream_t st);
+// dst[c] = src[row[c]] for c < *count (rows of row_floats floats); grid sized for max_rows
+int launch_gather_rows(const float *src, float *dst, const int32_t *row, const uint32_t *count, int max_rows,
+                       int row_floats, hipStream_t st);
 
 // ---- ivf.hip ---------------------------------------------------------------
 // centers_t: [d][n_leaves] (transposed). Writes the L best leaves per query.

@@ -253,6 +253,7 @@ adc_scan_kernel(const ScanParams p)
     if (MODE == MODE_CHUNK || MODE == MODE_LEAVES) { tile = blockIdx.x % p.n_tiles; chunk = blockIdx.x / p.n_tiles; }
     else { tile = blockIdx.x; chunk = 0; }
     const int q0 = tile * QT;
+    if (MODE == MODE_CHUNK && p.active_queries != nullptr && (uint32_t)q0 >= *p.active_queries) return;
 
     entry_t *tbl = (entry_t *)smem;
     const size_t tbl_bytes = NibbleTiles<QT, U8>::value ? (size_t)NB * QT * 128 : (size_t)NB * 256 * WORDS * 4;
@@ -287,34 +288,46 @@ adc_scan_kernel(const ScanParams p)
     }
 
     // The filter of query q lets a point through when it can still be among the R best:
-    //  * it must beat the wave's own R-th best (a tie loses where ids only grow, STRICT);
+    //  * it must beat the wave's own R-th best. A tie loses where ids only grow (STRICT) -- which
+    //    holds from one block to the next, not inside a block, whose points are taken four
+    //    interleaved sets of 64 at a time: a bound taken from the list in the middle of a block
+    //    lets ties pass (they are ordered by id when merged) and is tightened when the next block starts;
     //  * it must reach the smallest of the workgroup's waves' kw-th best scores, kw = ceil(R / waves):
     //    every wave holds that many points at or above it, R in all (the waves scan disjoint
     //    points for the same queries), so it is a lower bound of the final R-th best -- and a much
     //    tighter one than the own R-th best while the lists are young. Ties must pass here.
     // A list read while its owner merges into it shows an older or the newer kw-th best; both are valid.
     const int kw = (p.R + n_waves - 1) / n_waves;
-    auto refresh_threshold = [&](int q) {
+    uint32_t relaxed = 0u; // queries whose bound was taken in the middle of a block (wave-uniform)
+    auto refresh_threshold = [&](int q, bool mid_block) {
         const uint32_t ord_own = key_ord(my_lists[(size_t)q * C + (p.R - 1)]); // 0: fewer than R yet
         uint32_t ord_g = 0xffffffffu;
         for (int w = 0; w < n_waves; ++w) {
             const uint32_t o = key_ord(lists[((size_t)w * QT + q) * C + (kw - 1)]);
             ord_g = o < ord_g ? o : ord_g; // 0 while a wave has fewer than kw
         }
+        // "reach v" is "beat v - 1" in ordering values
+        if (STRICT && mid_block) relaxed |= 1u << q;
         if (FKEY) {
-            // ordering values grow with the score: "reach ord_g" is "beat ord_g - 1"
-            const uint32_t t = STRICT ? (ord_g > 0u && ord_g - 1u > ord_own ? ord_g - 1u : ord_own)
-                                      : (ord_g > ord_own ? ord_g : ord_own);
+            const uint32_t own = (STRICT && mid_block && ord_own > 0u) ? ord_own - 1u : ord_own;
+            const uint32_t t = STRICT ? (ord_g > 0u && ord_g - 1u > own ? ord_g - 1u : own)
+                                      : (ord_g > own ? ord_g : own);
             thr_f[q] = t ? f32_from_ord(t) : -INFINITY;
         } else {
             // integer sums: ordering value = sum + 1
-            const int own = (int)ord_own - 1, grp = (int)ord_g - (STRICT ? 2 : 1);
+            const int own = (int)ord_own - 1 - ((STRICT && mid_block) ? 1 : 0), grp = (int)ord_g - (STRICT ? 2 : 1);
             thr_i[q] = grp > own ? grp : own;
         }
     };
 
     // one block of 256 points: accumulate, then filter
     auto process_block = [&](int64_t blk, const BlockRegs<NBT> &regs, float seg_bias) {
+        if (STRICT && relaxed != 0u) {
+#pragma unroll
+            for (int q = 0; q < QT; ++q)
+                if ((relaxed >> q) & 1u) refresh_threshold(q, false);
+            relaxed = 0u;
+        }
         entry_t acc[4];
         accumulate_block<QT, U8, NBT>(tbl, regs, p.codes, blk, NB, lane, acc);
         // score of (query q, point i of this lane)
@@ -365,7 +378,7 @@ adc_scan_kernel(const ScanParams p)
                 const uint32_t ord = FKEY ? ord_from_f32(sf) : (uint32_t)(si + 1);
                 if (wave_push(my_lists + (size_t)q * C, p.ns, my_pends + q * 64, pend_cnt[q], hit,
                               make_key(ord, id)))
-                    refresh_threshold(q);
+                    refresh_threshold(q, true);
             }
         }
     };
@@ -386,7 +399,7 @@ adc_scan_kernel(const ScanParams p)
         for (int64_t blk = first; blk < end; blk += step) {
             const bool more = blk + step < end;
             if (more) load_block<NBT>(nxt, p.codes, blk + step, lane);
-            if (LEAVES && p.scores_out == nullptr) refresh_threshold(0); // the other waves' progress (QT == 1 here)
+            if (LEAVES && p.scores_out == nullptr) refresh_threshold(0, false); // the other waves' progress (QT == 1 here)
             process_block(blk, cur, seg_bias);
             if (more) cur = nxt;
         }
@@ -648,6 +661,55 @@ block_max_nibble_kernel(const ScanParams p)
     }
 }
 
+// The code stream alone: the same loads, in the same launch shape, as the single-query scan,
+// with the table lookups left out: every wave folds its blocks' words into one (xor) and
+// writes it. Its duration is what reading the code array once costs on the machine, the
+// floor a scan of that array can approach.
+template <int NBT>
+__global__ void __launch_bounds__(1024)
+stream_codes_kernel(const uint8_t *__restrict__ codes, int64_t n_blocks, int NB_rt, uint32_t *__restrict__ out)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int n_waves = blockDim.x >> 6;
+    const int NB = NBT ? NBT : NB_rt;
+    const int64_t step = (int64_t)gridDim.x * n_waves;
+    for (int64_t blk = (int64_t)blockIdx.x * n_waves + wave; blk < n_blocks; blk += step) {
+        uint32_t x = 0u;
+        if constexpr (NBT != 0) {
+            BlockRegs<NBT> regs;
+            load_block<NBT>(regs, codes, blk, lane);
+#pragma unroll
+            for (int j = 0; j < NBT / 4; ++j) x ^= regs.rows[j].x ^ regs.rows[j].y ^ regs.rows[j].z ^ regs.rows[j].w;
+#pragma unroll
+            for (int t = 0; t < NBT % 4; ++t) x ^= regs.tails[t];
+        } else {
+            const uint32_t *base = (const uint32_t *)(codes + (size_t)blk * 256 * NB);
+            for (int j = 0; j < NB; ++j) x ^= base[(size_t)j * 64 + lane];
+        }
+#pragma unroll
+        for (int m = 32; m > 0; m >>= 1) x ^= (uint32_t)__shfl_xor((int)x, m, 64);
+        if (lane == 0) out[blk] = x;
+    }
+}
+
+int launch_stream_codes(const uint8_t *codes, int64_t n_blocks, int NB, uint32_t *out, hipStream_t st)
+{
+    const int waves = 4;
+    int64_t gx = std::min<int64_t>((n_blocks + waves - 1) / waves, 2048);
+    if (gx < 1) gx = 1;
+    const dim3 grid((unsigned)gx), block(waves * 64);
+    switch (NB) {
+    case 8: hipLaunchKernelGGL(stream_codes_kernel<8>, grid, block, 0, st, codes, n_blocks, NB, out); break;
+    case 13: hipLaunchKernelGGL(stream_codes_kernel<13>, grid, block, 0, st, codes, n_blocks, NB, out); break;
+    case 25: hipLaunchKernelGGL(stream_codes_kernel<25>, grid, block, 0, st, codes, n_blocks, NB, out); break;
+    case 32: hipLaunchKernelGGL(stream_codes_kernel<32>, grid, block, 0, st, codes, n_blocks, NB, out); break;
+    default: hipLaunchKernelGGL(stream_codes_kernel<0>, grid, block, 0, st, codes, n_blocks, NB, out); break;
+    }
+    AVQ_HIP(hipGetLastError());
+    return AVQ_OK;
+}
+
 // After the block-maxima scan, for a handful of queries, three short kernels:
 //  A. select_blocks_kernel (one workgroup per query): t1 = the R-th largest block
 //     maximum (exact, wg_select_threshold); the blocks whose maximum is >= t1 are listed.
@@ -892,6 +954,23 @@ int scan_pick_shape(int NB, int bits, bool u8, int ns, int B, bool single, int q
         }
     }
     set_error("scan: no launch shape fits LDS (NB=%d ns=%d)", NB, ns);
+    return AVQ_EINVAL;
+}
+
+// The fp32 tile of 8 queries over 4-bit codes with its candidate lists in LDS instead of a
+// global scratch area (one workgroup per compute unit): for launches whose grid is sized for
+// a worst case that rarely happens, where scratch per workgroup would mostly go unused.
+int scan_shape_lists_in_lds(int NB, int ns, ScanShape *out)
+{
+    const int wlist[] = {8, 4, 2, 1, 0};
+    for (int j = 0; wlist[j]; ++j) {
+        const size_t need = scan_lds_bytes(NB, false, 8, wlist[j], ns, false);
+        if (need <= kMaxDynLds) {
+            out->qt = 8; out->waves = wlist[j]; out->lds_bytes = need; out->lists_global = false;
+            return AVQ_OK;
+        }
+    }
+    set_error("scan: lists do not fit LDS (NB=%d ns=%d)", NB, ns);
     return AVQ_EINVAL;
 }
 

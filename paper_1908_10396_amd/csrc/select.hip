@@ -11,8 +11,10 @@ namespace avq {
 // One workgroup per query; wave w merges chunks w, w + W, ...; wave 0 then
 // merges the waves' lists. cand[q][C] sorted descending.
 __global__ void __launch_bounds__(1024)
-merge_partials_kernel(const u64 *__restrict__ partial, int n_chunks, int ns, u64 *__restrict__ cand)
+merge_partials_kernel(const u64 *__restrict__ partial, int n_chunks, int ns, u64 *__restrict__ cand,
+                      const int32_t *__restrict__ row_of, const uint32_t *__restrict__ active)
 {
+    if (active != nullptr && blockIdx.x >= *active) return;
     extern __shared__ __align__(16) unsigned char smem[];
     const int C = 64 * ns;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n_waves = blockDim.x >> 6;
@@ -25,18 +27,19 @@ merge_partials_kernel(const u64 *__restrict__ partial, int n_chunks, int ns, u64
     __syncthreads();
     if (wave == 0) {
         for (int w = 1; w < n_waves; ++w) wave_list_merge_from(mine, ns, lists + (size_t)w * C);
-        for (int i = lane; i < C; i += 64) cand[(size_t)q * C + i] = mine[i];
+        const size_t row = row_of ? (size_t)row_of[q] : (size_t)q;
+        for (int i = lane; i < C; i += 64) cand[row * C + i] = mine[i];
     }
 }
 
 int launch_merge_partials(const u64 *partial, int nq, int n_chunks, int ns, u64 *cand,
-                          hipStream_t st)
+                          hipStream_t st, const int32_t *row_of, const uint32_t *active)
 {
     int waves = 1;
     while (waves < 16 && waves * 4 <= n_chunks) waves *= 2;
     const size_t lds = (size_t)waves * 64 * ns * 8;
     hipLaunchKernelGGL(merge_partials_kernel, dim3(nq), dim3(waves * 64), lds, st, partial,
-                       n_chunks, ns, cand);
+                       n_chunks, ns, cand, row_of, active);
     AVQ_HIP(hipGetLastError());
     return AVQ_OK;
 }

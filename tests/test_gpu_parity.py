@@ -119,12 +119,72 @@ def test_search_is_deterministic_and_independent_of_launch_shape(case, lut_mode)
     np.testing.assert_array_equal(base[1], again[1])
     tiles = (1, 4, 8) if (lut_mode == 1 or case["bits"] == 4) else (1, 4)
     for name, val in (("scan_target_wgs", 64), ("scan_target_wgs", 4096), ("scan_waves", 2),
-                      ("small_batch_max", 1), ("small_batch_max", 1000), ("scan_mfma", 1)) + tuple(("scan_qt", t) for t in tiles):
+                      ("small_batch_max", 1), ("small_batch_max", 1000), ("scan_mfma", 1), ("scan_prefilter", 1),
+                      ("scan_prefilter", 2)) + tuple(("scan_qt", t) for t in tiles):
         idx.set_tuning(name, val)
         got = [t.cpu().numpy() for t in idx.search(qd, 10, 100, lut_mode)]
         np.testing.assert_array_equal(base[0], got[0])
         np.testing.assert_array_equal(base[1], got[1])
         idx.set_tuning(name, 0)
+
+
+@pytest.mark.parametrize("prefilter", [0, 1, 2])
+def test_fp32_batches_with_flat_score_distributions(prefilter):
+    # Batches with fp32 tables take their candidates from the 8-bit-table scan and must notice
+    # when those cannot be proven complete: here 1,200 of 4,000 points are copies of three
+    # vectors, so for queries near one of them hundreds of points share the best integer sum
+    # (and the best fp32 score: ties go to the lower id), while other queries see ordinary data.
+    rng = np.random.default_rng(51)
+    n, d, M, bits, nq = 4000, 32, 16, 4, 48
+    x = unit_rows(rng, n, d)
+    protos = unit_rows(rng, 3, d)
+    dup = rng.permutation(n)[:1200]
+    x[dup] = protos[rng.integers(0, 3, 1200)]
+    q = unit_rows(rng, nq, d)
+    q[:24] = protos[rng.integers(0, 3, 24)] + 0.05 * rng.standard_normal((24, d)).astype(np.float32)
+    cb = oracle.train_pq(x, M, 16, 4, seed=3)
+    codes = oracle.encode(x, cb, T=0.2, passes=3)
+    idx = avq.Index(d, M, bits, T=0.2)
+    idx.set_codebooks(cb)
+    idx.set_database(dev(x), oracle.pack_codes(codes, bits))
+    idx.set_tuning("scan_prefilter", prefilter)
+    for k, R in ((10, 100), (5, 0), (20, 128)):
+        oi, os_ = oracle.search(x, cb, codes, bits, q, k, R, 0)
+        ids, sc = idx.search(dev(q), k, R, avq.LUT_F32)
+        np.testing.assert_array_equal(ids.cpu().numpy(), oi)
+        np.testing.assert_array_equal(sc.cpu().numpy(), os_)
+    # the same data with 8-bit tables, where equal sums are the rule: matrix-core scan (prefilter
+    # 0 and 2) and the LDS-table scan (1); equal scores inside one block of 256 points must
+    # still come out by id
+    idx.set_tuning("scan_mfma", 1 if prefilter == 1 else 0)
+    for k, R in ((10, 100), (5, 0)):
+        oi, os_ = oracle.search(x, cb, codes, bits, q, k, R, 1)
+        ids, sc = idx.search(dev(q), k, R, avq.LUT_U8)
+        np.testing.assert_array_equal(ids.cpu().numpy(), oi)
+        np.testing.assert_array_equal(sc.cpu().numpy(), os_)
+
+
+def test_equal_scores_inside_a_block_with_8bit_codes():
+    # 8-bit codes, both table kinds: duplicates make hundreds of equal scores per block
+    rng = np.random.default_rng(52)
+    n, d, M, bits, nq = 3000, 16, 4, 8, 24
+    x = unit_rows(rng, n, d)
+    protos = unit_rows(rng, 2, d)
+    dup = rng.permutation(n)[:1500]
+    x[dup] = protos[rng.integers(0, 2, 1500)]
+    q = unit_rows(rng, nq, d)
+    q[:12] = protos[rng.integers(0, 2, 12)] + 0.05 * rng.standard_normal((12, d)).astype(np.float32)
+    cb = oracle.train_pq(x, M, 256, 3, seed=3)
+    codes = oracle.encode(x, cb, T=0.2, passes=2)
+    idx = avq.Index(d, M, bits, T=0.2)
+    idx.set_codebooks(cb)
+    idx.set_database(dev(x), oracle.pack_codes(codes, bits))
+    for lut_mode in (0, 1):
+        for k, R in ((10, 100), (5, 0)):
+            oi, os_ = oracle.search(x, cb, codes, bits, q, k, R, lut_mode)
+            ids, sc = idx.search(dev(q), k, R, lut_mode)
+            np.testing.assert_array_equal(ids.cpu().numpy(), oi)
+            np.testing.assert_array_equal(sc.cpu().numpy(), os_)
 
 
 @pytest.mark.parametrize("lut_mode", [0, 1])
@@ -493,6 +553,27 @@ def test_update_codebooks_alternation_lowers_the_loss_and_rejects_bad_calls():
     fresh.set_codebooks(idx.get_codebooks())
     with pytest.raises(avq.AvqError):
         fresh.update_codebooks(xd)
+
+
+@pytest.mark.parametrize("n,d,M,bits", [(1000, 16, 16, 4), (2100, 98, 49, 4), (3000, 100, 25, 4), (700, 24, 3, 8)])
+def test_stream_codes_reads_every_code_byte_once(n, d, M, bits):
+    # the measurement kernel folds a block's words with xor; a word holds the same code byte of
+    # four consecutive points, padding points are all zero
+    rng = np.random.default_rng(41)
+    x = unit_rows(rng, n, d)
+    idx = avq.Index(d, M, bits, kmeans_iters=2, encode_passes=1)
+    idx.train(dev(x[:max(300, 1 << bits)]))
+    idx.encode(dev(x))
+    codes = idx.get_codes()
+    NB = codes.shape[1]
+    n_blocks = (n + 255) // 256
+    padded = np.zeros((n_blocks * 256, NB), np.uint8)
+    padded[:n] = codes
+    by = np.bitwise_xor.reduce(np.bitwise_xor.reduce(padded.reshape(n_blocks, 64, 4, NB), axis=3), axis=1)
+    want = by[:, 0].astype(np.uint32) | by[:, 1].astype(np.uint32) << 8 | by[:, 2].astype(np.uint32) << 16 \
+        | by[:, 3].astype(np.uint32) << 24
+    got = idx.debug_stream_codes().cpu().numpy().view(np.uint32)
+    np.testing.assert_array_equal(got, want)
 
 
 def test_anisotropic_encoding_reduces_the_error_of_large_inner_products():
