@@ -207,6 +207,13 @@ int avq_debug_leaf_select(avq_index *idx, const float *queries, int32_t nq, int3
  * be NULL) receives the number of blocks; words_out may be NULL to query it. */
 int avq_debug_stream_codes(avq_index *idx, uint32_t *words_out, int64_t *n_blocks_out, void *hip_stream);
 
+/* Measurement aid: after an avq_search with fp32 tables that took its candidates
+ * from the 8-bit-table scan (see "scan_prefilter" below), the number of queries
+ * of that call whose candidate lists could not be proven complete and were
+ * scanned again with fp32 tables. -1 if the last such search did not happen.
+ * Synchronises the device. */
+int avq_debug_unverified_queries(avq_index *idx, int32_t *count_out);
+
 /* eta of Section 3.2 for one norm, on the host (no GPU needed):
  * mode AVQ_ETA_LIMIT or AVQ_ETA_EXACT as in avq_config. */
 double avq_eta(int32_t d, double T, double norm, int32_t eta_mode);
@@ -224,8 +231,9 @@ double avq_eta(int32_t d, double T, double norm, int32_t eta_mode);
  * are scanned with the fp32 tables directly instead of taking candidates from
  * the matrix-core scan over the 8-bit tables and re-scoring them in fp32;
  * 2: candidates are taken as usual, but every odd query is treated as one
- * whose candidates could not be verified and is scanned again with fp32
- * tables).
+ * whose candidates cannot be used and is scanned again with fp32 tables),
+ * "prefilter_cap" (candidate keys that scan may keep per query and chunk of
+ * the index; a query that needs more is scanned again with fp32 tables).
  * Results never depend on these. Returns
  * AVQ_EINVAL for an unknown name. */
 int avq_set_tuning(avq_index *idx, const char *name, int32_t value);

@@ -24,7 +24,7 @@ SYMBOLS = [
     "avq_create", "avq_destroy", "avq_train", "avq_encode", "avq_update_codebooks", "avq_search", "avq_brute_force",
     "avq_set_codebooks", "avq_get_codebooks", "avq_set_leaf_centers", "avq_get_leaf_centers",
     "avq_set_database", "avq_get_codes", "avq_get_leaf_assign", "avq_size", "avq_debug_lut",
-    "avq_debug_adc_scores", "avq_debug_leaf_select", "avq_debug_stream_codes", "avq_eta", "avq_set_tuning",
+    "avq_debug_adc_scores", "avq_debug_leaf_select", "avq_debug_stream_codes", "avq_debug_unverified_queries", "avq_eta", "avq_set_tuning",
     "avq_profile_enable", "avq_profile_read", "avq_last_error", "avq_version",
 ]
 
@@ -77,6 +77,7 @@ def lib():
         L.avq_debug_adc_scores.argtypes = [vp, vp, i32, i32, vp, vp]
         L.avq_debug_leaf_select.argtypes = [vp, vp, i32, i32, vp, vp, vp]
         L.avq_debug_stream_codes.argtypes = [vp, vp, C.POINTER(i64), vp]
+        L.avq_debug_unverified_queries.argtypes = [vp, C.POINTER(i32)]
         L.avq_eta.argtypes = [i32, C.c_double, C.c_double, i32]
         L.avq_eta.restype = C.c_double
         L.avq_set_tuning.argtypes = [vp, C.c_char_p, i32]
@@ -291,6 +292,11 @@ class Index:
         _check(lib().avq_debug_adc_scores(self._h, qp, nq, lut_mode, out.data_ptr(),
                                           _stream_ptr(stream)))
         return out
+
+    def debug_unverified_queries(self):
+        c = C.c_int32(-1)
+        _check(lib().avq_debug_unverified_queries(self._h, C.byref(c)))
+        return c.value
 
     def debug_stream_codes(self, out=None, stream=None):
         """xor of every block's code words, uint32 [n_blocks] on the device (see avq.h)."""

@@ -62,7 +62,8 @@ struct avq_index {
     int tune_mfma = 0; // 0 = use the matrix-core scan where it applies, 1 = never
     int tune_prefilter = 0; // 0 = fp32-table batches go through the 8-bit-table scan where it applies, 1 = never,
                             // 2 = as 0 but odd queries always take the plain scan afterwards (exercises that branch)
-    DevBuf block_max, lists, refined, lut_fail, fail;
+    int tune_prefilter_cap = 0; // candidate keys per (query, chunk) of that scan, 0 = built-in
+    DevBuf block_max, lists, refined, lut_fail, fail, cand_keys;
     // optional per-stage timing with HIP events recorded on the caller's stream
     bool prof_on = false;
     std::vector<hipEvent_t> prof_pool;
@@ -155,7 +156,7 @@ extern "C" void avq_destroy(avq_index *idx)
                      &idx->codes_blocked, &idx->assign, &idx->perm, &idx->leaf_blk, &idx->lut, &idx->lut8,
                      &idx->scale, &idx->bias, &idx->partial, &idx->cand, &idx->leaf_ids, &idx->leaf_ip,
                      &idx->tmp, &idx->block_max, &idx->lists, &idx->thr, &idx->refined, &idx->lut_fail,
-                     &idx->fail};
+                     &idx->fail, &idx->cand_keys};
     for (DevBuf *b : all) b->release();
     for (hipEvent_t e : idx->prof_pool) (void)hipEventDestroy(e);
     delete idx;
@@ -174,6 +175,7 @@ extern "C" int avq_set_tuning(avq_index *idx, const char *name, int32_t value)
     else if (!strcmp(name, "small_batch_impl")) idx->tune_small_impl = value;
     else if (!strcmp(name, "scan_mfma")) idx->tune_mfma = value;
     else if (!strcmp(name, "scan_prefilter")) idx->tune_prefilter = value;
+    else if (!strcmp(name, "prefilter_cap")) idx->tune_prefilter_cap = value;
     else { set_error("avq_set_tuning: unknown name '%s'", name); return AVQ_EINVAL; }
     return AVQ_OK;
 }
@@ -524,96 +526,103 @@ static bool use_mfma_scan(const avq_index *idx, int nq, int lut_mode)
            scan_mfma_supported(idx->NB, idx->cfg.bits);
 }
 
-// Batches with fp32 tables on a flat index of 4-bit codes: candidates from the matrix-core scan
-// over the 8-bit tables, verified and re-scored in fp32. The candidate list must be several
-// times R for the verification to hold (the rounding margin of M units is a sizeable part of
-// the spread of the best sums), and lists hold 512 entries at most: R <= 128.
-static int prefilter_list_slots(const avq_index *idx, int nq, int lut_mode, int R)
+// Batches with fp32 tables on a flat index of 4-bit codes: the matrix-core scan over the 8-bit
+// tables collects every point that the rounding of the tables could still place among the R
+// best, and those are re-scored and ranked in fp32.
+static bool use_prefilter(const avq_index *idx, int nq, int lut_mode, int R)
 {
-    if (idx->tune_prefilter == 1 || idx->tune_mfma != 0 || lut_mode != AVQ_LUT_F32 || idx->cfg.n_leaves != 0 || nq < 16 ||
-        !scan_mfma_supported(idx->NB, idx->cfg.bits) || idx->cfg.M > 64 || R > 128)
-        return 0;
-    int slots = (4 * R + 63) / 64;
-    if ((int64_t)64 * slots >= idx->n) return 0; // the list would hold every point: nothing to filter
-    return slots;
+    return idx->tune_prefilter != 1 && idx->tune_mfma == 0 && lut_mode == AVQ_LUT_F32 && idx->cfg.n_leaves == 0 &&
+           nq >= 16 && scan_mfma_supported(idx->NB, idx->cfg.bits) && idx->cfg.M <= 64 && idx->n > R;
 }
 
 static int search_prefiltered(avq_index *idx, const float *queries, int nq, int k, int reorder_k, int R, int ns,
-                              int nsp, int32_t *ids_out, float *scores_out, hipStream_t st)
+                              int32_t *ids_out, float *scores_out, hipStream_t st)
 {
     const avq_config &c = idx->cfg;
-    const int C = 64 * ns, Cp = 64 * nsp, Rp = Cp;
-    // 1. matrix-core scan over the 8-bit tables, Rp candidates per query
+    const int C = 64 * ns;
+    // 1. matrix-core scan over the 8-bit tables in candidate mode
     ScanParams pm;
-    fill_scan_params(idx, nq, Rp, nsp, &pm);
+    fill_scan_params(idx, nq, R, ns, &pm);
     scan_mfma_plan(nq, idx->n_blocks, idx->tune_target_wgs, &pm);
-    // 2. the plain fp32 scan for the queries whose candidates cannot be verified: a grid for all
-    // of them (workgroups beyond the device-side count leave at once), many chunks so that a
-    // handful of such queries still spreads over the chip, lists in LDS
+    pm.cand_cap = idx->tune_prefilter_cap > 0 ? std::max(128, idx->tune_prefilter_cap) : std::max(2048, 16 * C);
+    // 2. the plain fp32 scan for the queries whose candidates cannot be used (no margin, a buffer
+    // that overflowed): its grid is cut on the device to the number of such queries
     ScanParams pf;
     fill_scan_params(idx, nq, R, ns, &pf);
     ScanShape shape;
-    AVQ_TRY(scan_shape_lists_in_lds(idx->NB, ns, &shape));
+    AVQ_TRY(scan_pick_shape(idx->NB, c.bits, false, ns, nq, false, 8, idx->tune_waves, &shape));
     pf.n_tiles = (nq + shape.qt - 1) / shape.qt;
-    int64_t chunks = std::max<int64_t>(4, std::min<int64_t>(64, 16384 / pf.n_tiles));
-    chunks = std::max<int64_t>(1, std::min<int64_t>(chunks, idx->n_blocks / shape.waves));
-    const int64_t bpc = (idx->n_blocks + chunks - 1) / chunks;
-    pf.blocks_per_chunk = (int32_t)bpc;
-    pf.n_chunks = (int32_t)((idx->n_blocks + bpc - 1) / bpc);
+    pf.n_chunks = (int32_t)std::max<int64_t>(1, std::min<int64_t>(64, idx->n_blocks / shape.waves)); // at most
+    pf.blocks_per_chunk = 0; // derived on the device
 
-    const size_t partial_m = sizeof(u64) * (size_t)nq * pm.n_chunks * Cp;
-    const size_t partial_f = sizeof(u64) * (size_t)pf.n_tiles * shape.qt * pf.n_chunks * C;
+    const size_t partial_m = sizeof(u64) * (size_t)nq * pm.n_chunks * C;
+    // the plain scan writes (live queries, rounded up to tiles) x chunks lists: at most max(kDynamicItems, tiles) tiles' worth
+    const size_t partial_f = sizeof(u64) * (size_t)std::max(kDynamicItems, pf.n_tiles) * shape.qt * C;
     AVQ_TRY(idx->partial.reserve(std::max(partial_m, partial_f)));
-    AVQ_TRY(idx->lists.reserve(scan_mfma_lists_bytes(pm)));
+    const size_t lists_f = shape.lists_global ? sizeof(u64) * (size_t)std::max(kDynamicItems, pf.n_tiles) * shape.waves * shape.qt * C : 0;
+    AVQ_TRY(idx->lists.reserve(std::max(scan_mfma_lists_bytes(pm), lists_f)));
     const size_t thr_bytes = sizeof(uint32_t) * (size_t)nq * (1 + (size_t)pm.n_chunks);
     AVQ_TRY(idx->thr.reserve(thr_bytes));
-    AVQ_TRY(idx->cand.reserve(sizeof(u64) * (size_t)nq * Cp));
+    AVQ_TRY(idx->cand.reserve(sizeof(u64) * (size_t)nq * C));
     AVQ_TRY(idx->refined.reserve(sizeof(u64) * (size_t)nq * C));
     const size_t row_floats = (size_t)c.M * idx->kc;
     AVQ_TRY(idx->lut_fail.reserve(sizeof(float) * (size_t)pf.n_tiles * shape.qt * row_floats));
-    AVQ_TRY(idx->fail.reserve(sizeof(int32_t) * ((size_t)nq + 4)));
+    // fail: [4] count | [nq] list | [nq] margins | [nq][chunks] candidate counts
+    AVQ_TRY(idx->fail.reserve(sizeof(int32_t) * (4 + (size_t)nq * (2 + (size_t)pm.n_chunks))));
+    AVQ_TRY(idx->cand_keys.reserve(sizeof(uint32_t) * (size_t)nq * pm.n_chunks * pm.cand_cap));
     uint32_t *fail_count = idx->fail.as<uint32_t>();
     int32_t *fail_list = idx->fail.as<int32_t>() + 4;
+    int32_t *margin = fail_list + nq;
 
     pm.partial = idx->partial.as<u64>();
     pm.lists_ws = idx->lists.as<u64>();
     pm.thr_shared = idx->thr.as<uint32_t>();
     pm.kth_shared = pm.thr_shared + nq;
+    pm.cand_keys = idx->cand_keys.as<uint32_t>();
+    pm.cand_cnt = (uint32_t *)(margin + nq);
+    pm.cand_margin = margin;
     {
         StageTimer t(idx, AVQ_STAGE_SCAN, st);
         AVQ_HIP(hipMemsetAsync(pm.thr_shared, 0, thr_bytes, st));
         AVQ_HIP(hipMemsetAsync(fail_count, 0, 16, st));
+        AVQ_TRY(launch_prefilter_margin(idx->lut.as<float>(), idx->scale.as<float>(), c.M, idx->NB, nq, margin, st));
         AVQ_TRY(launch_scan_mfma(pm, st));
     }
-    const u64 *cand8 = pm.partial;
+    const u64 *top = pm.partial;
     if (pm.n_chunks > 1) {
         StageTimer t(idx, AVQ_STAGE_MERGE, st);
-        AVQ_TRY(launch_merge_partials(pm.partial, nq, pm.n_chunks, nsp, idx->cand.as<u64>(), st));
-        cand8 = idx->cand.as<u64>();
+        AVQ_TRY(launch_merge_partials(pm.partial, nq, pm.n_chunks, ns, idx->cand.as<u64>(), st));
+        top = idx->cand.as<u64>();
     }
     {
         StageTimer t(idx, AVQ_STAGE_RESCAN, st);
-        RefineParams r;
-        r.cand8 = cand8;
-        r.Rp = Rp; r.nsp = nsp; r.R = R; r.ns = ns; r.nq = nq;
-        r.M = c.M; r.NB = idx->NB;
+        RefineCandParams r;
+        r.top = top;
+        r.R = R; r.ns = ns; r.nq = nq; r.M = c.M; r.NB = idx->NB;
+        r.n_chunks = pm.n_chunks;
+        r.cand_cap = pm.cand_cap;
+        r.chunk_points = (int64_t)pm.blocks_per_chunk * kBlockPoints;
+        r.cand_keys = pm.cand_keys;
+        r.cand_cnt = pm.cand_cnt;
+        r.margin = margin;
         r.lut = idx->lut.as<float>();
-        r.scale = idx->scale.as<float>();
         r.codes = idx->codes_logical.as<uint8_t>();
         r.out = idx->refined.as<u64>();
         r.fail_list = fail_list;
         r.fail_count = fail_count;
         r.force_fail_odd = idx->tune_prefilter == 2;
-        AVQ_TRY(launch_refine_f32(r, st));
-        // the unverified queries: their tables side by side, the plain scan over them, and their
-        // lists merged into their own rows of the refined candidates
+        AVQ_TRY(launch_refine_cand(r, st));
+        // the other queries: their tables side by side, the plain scan over them, and their lists
+        // merged into their own rows of the refined candidates
         AVQ_TRY(launch_gather_rows(idx->lut.as<float>(), idx->lut_fail.as<float>(), fail_list, fail_count, nq,
                                    (int)row_floats, st));
         pf.lut = idx->lut_fail.as<float>();
         pf.partial = idx->partial.as<u64>(); // the matrix-core scan's lists are merged by now
+        if (shape.lists_global) pf.lists_ws = idx->lists.as<u64>();
         pf.active_queries = fail_count;
         AVQ_TRY(launch_scan(pf, false, SCAN_CHUNK, shape, st));
-        AVQ_TRY(launch_merge_partials(pf.partial, nq, pf.n_chunks, ns, idx->refined.as<u64>(), st, fail_list, fail_count));
+        AVQ_TRY(launch_merge_partials(pf.partial, nq, pf.n_chunks, ns, idx->refined.as<u64>(), st, fail_list, fail_count,
+                                      shape.qt));
     }
     StageTimer t(idx, AVQ_STAGE_FINAL, st);
     return launch_finalize(idx->refined.as<u64>(), ns, nq, R, k, reorder_k != 0, 0, idx->x, c.d, queries,
@@ -658,12 +667,12 @@ extern "C" int avq_search(avq_index *idx, const float *queries, int32_t nq, int3
     const bool small = !ivf && nq <= small_max;
     // the single-query kernels compute short fp32 tables themselves (one launch less)
     const bool fuse_tables = small && idx->tune_small_impl == 0 && small_batch_can_fuse_tables(c.bits, c.M, c.d, u8);
-    const int prefilter_slots = small ? 0 : prefilter_list_slots(idx, nq, lut_mode, R);
+    const bool prefilter = !small && use_prefilter(idx, nq, lut_mode, R);
     if (!fuse_tables) {
         StageTimer t(idx, AVQ_STAGE_LUT, st);
-        AVQ_TRY(build_tables(idx, queries, nq, prefilter_slots ? AVQ_LUT_U8 : lut_mode, st));
+        AVQ_TRY(build_tables(idx, queries, nq, prefilter ? AVQ_LUT_U8 : lut_mode, st));
     }
-    if (prefilter_slots) return search_prefiltered(idx, queries, nq, k, reorder_k, R, ns, prefilter_slots, ids_out, scores_out, st);
+    if (prefilter) return search_prefiltered(idx, queries, nq, k, reorder_k, R, ns, ids_out, scores_out, st);
     ScanParams p;
     fill_scan_params(idx, nq, R, ns, &p);
     if (fuse_tables) {
@@ -886,6 +895,19 @@ extern "C" int avq_debug_stream_codes(avq_index *idx, uint32_t *words_out, int64
     if (n_blocks_out) *n_blocks_out = idx->n_blocks;
     if (!words_out) return AVQ_OK;
     return launch_stream_codes(idx->codes_blocked.as<uint8_t>(), idx->n_blocks, idx->NB, words_out, (hipStream_t)hip_stream);
+}
+
+extern "C" int avq_debug_unverified_queries(avq_index *idx, int32_t *count_out)
+{
+    AVQ_TRY(check_index(idx));
+    if (!count_out) { set_error("avq_debug_unverified_queries: NULL"); return AVQ_EINVAL; }
+    *count_out = -1;
+    if (!idx->fail.p) return AVQ_OK;
+    AVQ_HIP(hipDeviceSynchronize());
+    uint32_t c = 0;
+    AVQ_HIP(hipMemcpy(&c, idx->fail.p, sizeof(c), hipMemcpyDeviceToHost));
+    *count_out = (int32_t)c;
+    return AVQ_OK;
 }
 
 extern "C" int avq_debug_leaf_select(avq_index *idx, const float *queries, int32_t nq, int32_t L,

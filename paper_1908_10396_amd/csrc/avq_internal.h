@@ -80,18 +80,35 @@ struct ScanParams {
     // ordering value per query; [B][n_chunks] every wave's ceil(R/group)-th best
     uint32_t *thr_shared, *kth_shared;
     int32_t group;        // chunks per threshold group
+    // matrix-core kernel, candidate mode (cand_keys != NULL): every point whose sum is within
+    // cand_margin[q] (< 0 counts as 0) of the bound is appended, as a 32-bit chunk-local key, to
+    // cand_keys[q][chunk][cand_cap]; cand_cnt[q][chunk] = how many (cand_cap + 1: overflowed)
+    uint32_t *cand_keys, *cand_cnt;
+    const int32_t *cand_margin;
+    int32_t cand_cap;
     int32_t max_wgs;      // block-max kernels: workgroups per query at most (0 = built-in); waves loop beyond it
-    // flat scan of a compacted query list whose length only the device knows: tiles that start
-    // at or beyond *active_queries do nothing (NULL: all B queries are live)
+    // flat scan of a compacted query list whose length only the device knows (NULL: all B
+    // queries are live): the kernel derives tiles and chunks from *active_queries, n_chunks is
+    // then the most chunks a tile may be cut into, and the grid is scan_dynamic_grid()
     const uint32_t *active_queries;
     void *scores_out;     // debug: [B][score_stride] fp32 or int32, else NULL
     int64_t score_stride;
 };
+// A launch whose number of live query tiles is known only on the device: about kDynamicItems
+// workgroups share the work, so a few tiles are cut into many chunks (every one of them still
+// spreads over the chip) and many tiles into few; never more than max_chunks, never fewer than 1.
+// tiles * chunks <= max(kDynamicItems, tiles): a grid of max(kDynamicItems, all tiles) covers it.
+constexpr int kDynamicItems = 4096;
+__host__ __device__ inline int scan_dynamic_chunks(int tiles, int max_chunks)
+{
+    int c = tiles > 0 ? kDynamicItems / tiles : 1;
+    c = c < max_chunks ? c : max_chunks;
+    return c > 1 ? c : 1;
+}
 struct ScanShape { int qt; int waves; size_t lds_bytes; bool lists_global; };
 // Picks query-tile size and waves per workgroup that fit LDS. qt_hint/waves_hint 0 = auto.
 int scan_pick_shape(int NB, int bits, bool u8, int ns, int B, bool single, int qt_hint, int waves_hint,
                     ScanShape *out);
-int scan_shape_lists_in_lds(int NB, int ns, ScanShape *out); // fp32 tile of 8, 4-bit codes, lists in LDS
 // SCAN_CHUNK: flat index, grid = query tiles x chunks; SCAN_LEAVES: partitioned index, one
 // workgroup per query over its probed leaves; SCAN_BLOCKLIST: flat index, one workgroup per
 // query over the blocks named by block_keys.
@@ -132,10 +149,12 @@ int launch_small_final(const ScanParams &p, const FinishParams &f, bool u8, hipS
 
 // ---- select.hip ------------------------------------------------------------
 // Merges the per-chunk lists of every query into one sorted list cand[q][64*ns].
-// row_of / active (both NULL, or both set): query q's list goes to row row_of[q] of cand, and
-// only queries below *active are merged.
+// row_of / active (both NULL, or both set): query q's list goes to row row_of[q] of cand, only
+// queries below *active are merged, and the lists are those of a scan with active_queries set
+// (tile_queries per tile, at most n_chunks chunks).
 int launch_merge_partials(const u64 *partial, int nq, int n_chunks, int ns, u64 *cand,
-                          hipStream_t st, const int32_t *row_of = nullptr, const uint32_t *active = nullptr);
+                          hipStream_t st, const int32_t *row_of = nullptr, const uint32_t *active = nullptr,
+                          int tile_queries = 0);
 // The R largest of n unsorted keys per query: out[q][64*ns] sorted descending.
 int launch_select_keys(const u64 *keys, int nq, int64_t n, int ns, int R, u64 *out, hipStream_t st);
 // Final stage. reorder != 0: exact <q, x_id> for the first R candidates, then top-k.
@@ -150,27 +169,32 @@ int launch_brute_force(const float *x, int64_t n, int d, const float *queries, i
 int brute_force_chunks(int64_t n, int nq);
 
 // ---- refine.hip ------------------------------------------------------------
-// fp32-table search through the 8-bit-table scan (flat index, 4-bit codes). cand8[q][64*nsp]:
-// the Rp best points of every query by integer table sum, sorted. Every sum differs from the
-// exact one, in units of the query's scale, by at most M/2 (rounding of the table entries), so
-// a point outside the list cannot be among the R best by fp32 score once the list's last sum
-// is more than M + slack below its R-th. For the queries where that holds the kernel re-scores
-// the candidates in fp32 (the scan's own order of additions) and writes the R best, sorted, to
-// out[q][64*ns]; the others are appended to fail_list (count in *fail_count, zeroed by the
-// caller) and left to a plain fp32 scan.
-struct RefineParams {
-    const u64 *cand8;
-    int32_t Rp, nsp, R, ns, nq;
-    int32_t M, NB;
-    const float *lut;            // [nq][M][16]
-    const float *scale;          // [nq]
+// fp32-table search through the 8-bit-table scan (flat index, 4-bit codes). The matrix-core scan
+// in candidate mode (ScanParams::cand_*) keeps every point whose integer sum came within
+// margin[q] of its bound for the R-th best; top[q][64*ns] = the R best integer sums of query q
+// (merged over the chunks). Every sum differs from the exact one, in units of the query's
+// scale, by at most M/2 (rounding of the table entries), so with margin[q] >= M + slack no
+// other point can be among the R best by fp32 score: the kernel re-scores the kept points at
+// or above (R-th best sum - margin) in fp32 (the scan's own order of additions) and writes the
+// R best, sorted, to out[q][64*ns]. Queries without a usable margin or whose buffers
+// overflowed are appended to fail_list (count in *fail_count, zeroed by the caller) and left to
+// a plain fp32 scan. margin[q] comes from launch_prefilter_margin, before the scan.
+struct RefineCandParams {
+    const u64 *top;
+    int32_t R, ns, nq, M, NB;
+    int32_t n_chunks, cand_cap;
+    int64_t chunk_points;        // points per chunk of the scan (ids in the 32-bit keys count from the chunk's first)
+    const uint32_t *cand_keys, *cand_cnt;
+    const int32_t *margin;
+    const float *lut;
     const uint8_t *codes;        // logical [n][NB]
-    u64 *out;                    // [nq][64*ns]
-    int32_t *fail_list;          // [nq]
+    u64 *out;
+    int32_t *fail_list;
     uint32_t *fail_count;
-    int32_t force_fail_odd;      // testing aid: queries with an odd index count as unverified
+    int32_t force_fail_odd;
 };
-int launch_refine_f32(const RefineParams &r, hipStream_t st);
+int launch_prefilter_margin(const float *lut, const float *scale, int M, int NB, int nq, int32_t *margin, hipStream_t st);
+int launch_refine_cand(const RefineCandParams &r, hipStream_t st);
 // dst[c] = src[row[c]] for c < *count (rows of row_floats floats); grid sized for max_rows
 int launch_gather_rows(const float *src, float *dst, const int32_t *row, const uint32_t *count, int max_rows,
                        int row_floats, hipStream_t st);

@@ -9,82 +9,125 @@
 // (entries of a byte first, then the bytes in order) differs from the real s_i by at most
 // rho = (NB + 2) * 2^-24 * sum_m max_j |L[m][j]|.
 //
-// Let the candidates be the Rp points of largest acc (ties by lower id), acc_(R) the R-th
-// largest and acc_last the smallest of them. The R best candidates by acc all have fp32 score
-// >= bound = sum lo + (acc_(R) - E)/c - rho, so the R-th best fp32 score of the whole index
-// is >= bound; a point outside the list has acc <= acc_last and fp32 score
-// <= sum lo + (acc_last + E)/c + rho. If acc_last < acc_(R) - (2E + 2 rho c) that is
-// strictly below bound: no point outside the list is among the R best, and the R best of
-// the index are the R best of the candidates, which are then re-scored and ranked exactly.
-// Where the condition fails (lists too short for a flat score distribution, or tables with a
-// tiny range) the query is handed to the plain fp32 scan instead.
+// Let acc_(R) be the R-th largest integer sum of the index. The R points of largest acc all have
+// fp32 score >= bound = sum lo + (acc_(R) - E)/c - rho, so the R-th best fp32 score of the
+// index is >= bound; a point with acc < acc_(R) - margin, margin >= 2E + 2 rho c, has fp32 score
+// <= sum lo + (acc + E)/c + rho < bound: it is not among the R best, ties included. So the R
+// best by fp32 score are the R best of the candidate set {acc >= acc_(R) - margin}.
+//
+// The matrix-core scan in candidate mode keeps, per query and chunk, every point whose sum came
+// within the margin of its running lower bound of acc_(R); the bound never exceeds acc_(R), so the
+// candidate set is among the kept points. The margin is computed once per query, before the
+// scan. Here the kept points at or above acc_(R) - margin are re-scored in fp32, in the scan's
+// order of additions, and ranked. A query without a usable margin (tables with a tiny range) or
+// with more kept points than the buffers hold is handed to the plain fp32 scan instead.
 #include "avq_internal.h"
 #include "wave_topk.h"
 
 namespace avq {
 
+__global__ void __launch_bounds__(64)
+prefilter_margin_kernel(const float *__restrict__ lut, const float *__restrict__ scale, int M, int NB, int nq,
+                        int32_t *__restrict__ margin)
+{
+    const int q = blockIdx.x, lane = threadIdx.x;
+    float a = 0.0f;
+    if (lane < M) {
+        const float *L = lut + ((size_t)q * M + lane) * 16;
+        for (int j = 0; j < 16; ++j) a = fmaxf(a, fabsf(L[j]));
+    }
+    for (int m = 32; m > 0; m >>= 1) a += __shfl_xor(a, m, 64);
+    if (lane == 0) {
+        const float sc = scale[q];
+        const float rho = (float)(NB + 2) * 5.9604645e-8f * a * 1.01f;
+        const float marg_f = (float)M + 0.01f + (sc > 0.0f ? 2.02f * rho / sc : INFINITY);
+        margin[q] = marg_f < 1.0e6f ? (int32_t)ceilf(marg_f) + 1 : -1; // -1: no usable bound, the query is scanned plainly
+    }
+}
+
+int launch_prefilter_margin(const float *lut, const float *scale, int M, int NB, int nq, int32_t *margin, hipStream_t st)
+{
+    if (M > 64) { set_error("prefilter: M > 64"); return AVQ_EINVAL; }
+    hipLaunchKernelGGL(prefilter_margin_kernel, dim3(nq), dim3(64), 0, st, lut, scale, M, NB, nq, margin);
+    AVQ_HIP(hipGetLastError());
+    return AVQ_OK;
+}
+
+constexpr int kRefineMax = 2048; // candidates of one query that the refinement holds; more: plain scan
+
+
+template <int NBT>
 __global__ void __launch_bounds__(256)
-refine_f32_kernel(const RefineParams r)
+refine_cand_kernel(const RefineCandParams r)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x, nt = blockDim.x;
     const int q = blockIdx.x;
-    const int Cp = 64 * r.nsp, C = 64 * r.ns;
-    const int n_tab = 2 * r.NB; // odd M: one all-zero table, as in the scan kernels
-    float *tbl = (float *)smem;                                   // [n_tab][16]
-    u64 *keys = (u64 *)(smem + (((size_t)n_tab * 64 + 15) & ~(size_t)15)); // [Rp]
-    __shared__ float amax_sum;
-    __shared__ int n_cand_s;
+    const int C = 64 * r.ns;
+    const int n_tab = 2 * r.NB;
+    float *tbl = (float *)smem;                                               // [n_tab][16]
+    u64 *keys = (u64 *)(smem + (((size_t)n_tab * 64 + 15) & ~(size_t)15));    // [kRefineMax]
+    int32_t *ids = (int32_t *)(keys + kRefineMax);                            // [kRefineMax]
+    __shared__ int n_top_s, n_cand_s, bad_s;
 
     const float *L = r.lut + (size_t)q * r.M * 16;
     for (int e = tid; e < n_tab * 16; e += nt) tbl[e] = e < r.M * 16 ? L[e] : 0.0f;
-    if (tid == 0) { amax_sum = 0.0f; n_cand_s = 0; }
+    if (tid == 0) { n_top_s = 0; n_cand_s = 0; bad_s = 0; }
     __syncthreads();
-    // A = sum_m max_j |L[m][j]| and the number of candidates (the list is sorted, empty slots are 0)
-    if (tid < r.M) {
-        float a = 0.0f;
-        for (int j = 0; j < 16; ++j) a = fmaxf(a, fabsf(tbl[tid * 16 + j]));
-        atomicAdd(&amax_sum, a); // order of the additions does not matter: only an upper bound is needed (slack below)
-    }
-    const u64 *cand = r.cand8 + (size_t)q * Cp;
+    const u64 *top = r.top + (size_t)q * C;
     int mine = 0;
-    for (int i = tid; i < r.Rp; i += nt) mine += cand[i] != 0ull;
-    if (mine) atomicAdd(&n_cand_s, mine);
+    for (int i = tid; i < r.R; i += nt) mine += top[i] != 0ull;
+    if (mine) atomicAdd(&n_top_s, mine);
     __syncthreads();
-    const int n_cand = n_cand_s;
-    bool ok = true;
-    if (n_cand == r.Rp) {
-        // full list: points outside it exist, the gap between the R-th and the last sum must exceed the margin
-        const float scale = r.scale[q];
-        const float rho = (float)(r.NB + 2) * 5.9604645e-8f * amax_sum * 1.01f;
-        const float marg_f = (float)r.M + 0.01f + (scale > 0.0f ? 2.02f * rho / scale : INFINITY);
-        ok = false;
-        if (marg_f < 1.0e6f) {
-            const int64_t margin = (int64_t)ceilf(marg_f) + 1;
-            const int64_t acc_r = (int64_t)key_ord(cand[r.R - 1]);
-            const int64_t acc_last = (int64_t)key_ord(cand[r.Rp - 1]);
-            ok = acc_last < acc_r - margin;
+    const int margin = r.margin[q];
+    // fewer than R points in the whole index: the bound never rose above zero and every point was kept
+    const uint32_t ord_r = n_top_s == r.R ? key_ord(top[r.R - 1]) : 0u;
+    const uint32_t thr_ord = ord_r > (uint32_t)(margin > 0 ? margin : 0) ? ord_r - (uint32_t)margin : 0u;
+    if (margin >= 0) {
+        for (int c = 0; c < r.n_chunks; ++c) {
+            const uint32_t cnt = r.cand_cnt[(size_t)q * r.n_chunks + c];
+            if (cnt > (uint32_t)r.cand_cap) { if (tid == 0) bad_s = 1; break; } // uniform: cnt is
+            const uint32_t *src = r.cand_keys + ((size_t)q * r.n_chunks + c) * r.cand_cap;
+            const int32_t id_base = (int32_t)((int64_t)c * r.chunk_points);
+            for (uint32_t i = tid; i < cnt; i += nt) {
+                const uint32_t k32 = src[i];
+                if ((k32 >> 18) < thr_ord) continue;
+                const int slot = atomicAdd(&n_cand_s, 1);
+                if (slot < kRefineMax) ids[slot] = id_base + (int32_t)(~k32 & 0x3ffffu);
+            }
         }
     }
+    __syncthreads();
+    const int n_cand = n_cand_s;
+    bool ok = margin >= 0 && bad_s == 0 && n_cand <= kRefineMax;
     if (r.force_fail_odd && (q & 1)) ok = false;
     if (!ok) {
         if (tid == 0) r.fail_list[atomicAdd(r.fail_count, 1u)] = q;
         return;
     }
-    // exact fp32 table sums of the candidates: per code byte the two entries first, then the bytes in order
     for (int i = tid; i < n_cand; i += nt) {
-        const int32_t id = key_id(cand[i]);
+        const int32_t id = ids[i];
         const uint8_t *row = r.codes + (size_t)id * r.NB;
         float s = 0.0f;
-        for (int b = 0; b < r.NB; ++b) {
-            const uint32_t byte = row[b];
-            const float v = __fadd_rn(tbl[(2 * b) * 16 + (byte & 15u)], tbl[(2 * b + 1) * 16 + (byte >> 4)]);
-            s = __fadd_rn(s, v);
+        if constexpr (NBT != 0) {
+            uint32_t bytes[NBT];
+#pragma unroll
+            for (int b = 0; b < NBT; ++b) bytes[b] = row[b];
+#pragma unroll
+            for (int b = 0; b < NBT; ++b) {
+                const float v = __fadd_rn(tbl[(2 * b) * 16 + (bytes[b] & 15u)], tbl[(2 * b + 1) * 16 + (bytes[b] >> 4)]);
+                s = __fadd_rn(s, v);
+            }
+        } else {
+            for (int b = 0; b < r.NB; ++b) {
+                const uint32_t byte = row[b];
+                const float v = __fadd_rn(tbl[(2 * b) * 16 + (byte & 15u)], tbl[(2 * b + 1) * 16 + (byte >> 4)]);
+                s = __fadd_rn(s, v);
+            }
         }
         keys[i] = make_key(ord_from_f32(s), id);
     }
     __syncthreads();
-    // rank by counting, four lanes per key
     u64 *out = r.out + (size_t)q * C;
     for (int j0 = 0; j0 < n_cand; j0 += nt / 4) {
         const int j = j0 + (tid >> 2);
@@ -99,14 +142,17 @@ refine_f32_kernel(const RefineParams r)
     for (int i = n_fin + tid; i < C; i += nt) out[i] = 0ull;
 }
 
-int launch_refine_f32(const RefineParams &r, hipStream_t st)
+int launch_refine_cand(const RefineCandParams &r, hipStream_t st)
 {
-    if (r.M > 64 || r.Rp <= r.R || r.Rp > 64 * r.nsp || r.R > 64 * r.ns) {
-        set_error("refine: bad shape (M %d, R %d, Rp %d)", r.M, r.R, r.Rp);
-        return AVQ_EINVAL;
+    if (r.M > 64 || r.R > 64 * r.ns || r.cand_cap < 1) { set_error("refine: bad shape (M %d, R %d)", r.M, r.R); return AVQ_EINVAL; }
+    const size_t lds = (((size_t)2 * r.NB * 64 + 15) & ~(size_t)15) + (sizeof(u64) + sizeof(int32_t)) * (size_t)kRefineMax;
+    switch (r.NB) {
+    case 8: hipLaunchKernelGGL(refine_cand_kernel<8>, dim3(r.nq), dim3(256), lds, st, r); break;
+    case 13: hipLaunchKernelGGL(refine_cand_kernel<13>, dim3(r.nq), dim3(256), lds, st, r); break;
+    case 25: hipLaunchKernelGGL(refine_cand_kernel<25>, dim3(r.nq), dim3(256), lds, st, r); break;
+    case 32: hipLaunchKernelGGL(refine_cand_kernel<32>, dim3(r.nq), dim3(256), lds, st, r); break;
+    default: hipLaunchKernelGGL(refine_cand_kernel<0>, dim3(r.nq), dim3(256), lds, st, r); break;
     }
-    const size_t lds = (((size_t)2 * r.NB * 64 + 15) & ~(size_t)15) + sizeof(u64) * (size_t)r.Rp;
-    hipLaunchKernelGGL(refine_f32_kernel, dim3(r.nq), dim3(256), lds, st, r);
     AVQ_HIP(hipGetLastError());
     return AVQ_OK;
 }

@@ -250,10 +250,19 @@ adc_scan_kernel(const ScanParams p)
     const int C = 64 * p.ns;
 
     int tile, chunk;
-    if (MODE == MODE_CHUNK || MODE == MODE_LEAVES) { tile = blockIdx.x % p.n_tiles; chunk = blockIdx.x / p.n_tiles; }
+    int n_chunks = p.n_chunks, blocks_per_chunk = p.blocks_per_chunk;
+    if (MODE == MODE_CHUNK && p.active_queries != nullptr) {
+        // only the first *active_queries queries are live, a count the host does not know: the
+        // grid is cut to fit it here (see scan_dynamic_chunks)
+        const int tiles = ((int)*p.active_queries + QT - 1) / QT;
+        n_chunks = scan_dynamic_chunks(tiles, p.n_chunks);
+        if (tiles == 0 || (int)blockIdx.x >= tiles * n_chunks) return;
+        tile = blockIdx.x % tiles;
+        chunk = blockIdx.x / tiles;
+        blocks_per_chunk = (int)((p.n_blocks + n_chunks - 1) / n_chunks);
+    } else if (MODE == MODE_CHUNK || MODE == MODE_LEAVES) { tile = blockIdx.x % p.n_tiles; chunk = blockIdx.x / p.n_tiles; }
     else { tile = blockIdx.x; chunk = 0; }
     const int q0 = tile * QT;
-    if (MODE == MODE_CHUNK && p.active_queries != nullptr && (uint32_t)q0 >= *p.active_queries) return;
 
     entry_t *tbl = (entry_t *)smem;
     const size_t tbl_bytes = NibbleTiles<QT, U8>::value ? (size_t)NB * QT * 128 : (size_t)NB * 256 * WORDS * 4;
@@ -406,8 +415,8 @@ adc_scan_kernel(const ScanParams p)
     };
 
     if (MODE == MODE_CHUNK) {
-        const int64_t first = (int64_t)chunk * p.blocks_per_chunk;
-        int64_t end = first + p.blocks_per_chunk;
+        const int64_t first = (int64_t)chunk * blocks_per_chunk;
+        int64_t end = first + blocks_per_chunk;
         if (end > p.n_blocks) end = p.n_blocks;
         scan_range(first + wave, end, n_waves, 0.0f);
     } else if (MODE == MODE_LEAVES) {
@@ -439,7 +448,7 @@ adc_scan_kernel(const ScanParams p)
             if (w == wave) continue;
             wave_list_merge_from(mine, p.ns, lists + ((size_t)w * QT + q) * C);
         }
-        u64 *out = p.partial + ((size_t)(q0 + q) * p.n_chunks + chunk) * C;
+        u64 *out = p.partial + ((size_t)(q0 + q) * n_chunks + chunk) * C;
         for (int i = lane; i < C; i += 64) out[i] = mine[i];
     }
 }
@@ -957,23 +966,6 @@ int scan_pick_shape(int NB, int bits, bool u8, int ns, int B, bool single, int q
     return AVQ_EINVAL;
 }
 
-// The fp32 tile of 8 queries over 4-bit codes with its candidate lists in LDS instead of a
-// global scratch area (one workgroup per compute unit): for launches whose grid is sized for
-// a worst case that rarely happens, where scratch per workgroup would mostly go unused.
-int scan_shape_lists_in_lds(int NB, int ns, ScanShape *out)
-{
-    const int wlist[] = {8, 4, 2, 1, 0};
-    for (int j = 0; wlist[j]; ++j) {
-        const size_t need = scan_lds_bytes(NB, false, 8, wlist[j], ns, false);
-        if (need <= kMaxDynLds) {
-            out->qt = 8; out->waves = wlist[j]; out->lds_bytes = need; out->lists_global = false;
-            return AVQ_OK;
-        }
-    }
-    set_error("scan: lists do not fit LDS (NB=%d ns=%d)", NB, ns);
-    return AVQ_EINVAL;
-}
-
 template <class K>
 static int set_max_lds(K kern, bool *done)
 {
@@ -1019,7 +1011,7 @@ int launch_scan(const ScanParams &p, bool u8, int mode, const ScanShape &s, hipS
         return u8 ? launch_nb<1, true, MODE_BLOCKLIST>(p, s, grid, st)
                   : launch_nb<1, false, MODE_BLOCKLIST>(p, s, grid, st);
     }
-    const int64_t grid64 = (int64_t)p.n_tiles * p.n_chunks;
+    const int64_t grid64 = p.active_queries ? std::max<int64_t>(kDynamicItems, p.n_tiles) : (int64_t)p.n_tiles * p.n_chunks;
     if (grid64 > 0x7fffffff) { set_error("scan: grid too large"); return AVQ_EINVAL; }
     const int grid = (int)grid64;
     if (!u8) {

@@ -115,11 +115,25 @@ __device__ __forceinline__ void list32_insert_sorted(uint32_t (&v)[kMfmaMaxNs], 
 // in *bound_q. Called by the whole wave with uniform arguments. The list (global scratch)
 // is read once at the start, so that its latency passes while the keys are sorted, and
 // written back once.
-__device__ __noinline__ uint32_t mfma_flush_query(const lds_u32 *pend_a, const lds_u32 *pend_b, int cnt_a, int cnt_b,
-                                                  uint32_t *list, int ns, int R, int kw, uint32_t *kth_row, int gsz,
-                                                  int self, uint32_t *bound_q)
+// With cand_dst set, the pending keys are first appended, unsorted, at cand_dst[cand_pos]: the
+// scan then lets through every point within a margin below the bound, and all of them are
+// wanted later, not only those that make the list. The new fill count comes back in the
+// upper half of the result (cand_cap + 1 once the buffer has overflowed; nothing is written
+// past cand_cap).
+__device__ __noinline__ u64 mfma_flush_query(const lds_u32 *pend_a, const lds_u32 *pend_b, int cnt_a, int cnt_b,
+                                             uint32_t *list, int ns, int R, int kw, uint32_t *kth_row, int gsz,
+                                             int self, uint32_t *bound_q, uint32_t *cand_dst, int cand_pos, int cand_cap)
 {
     const int lane = lane_id();
+    if (cand_dst != nullptr) {
+        if (cand_pos + cnt_a + cnt_b <= cand_cap) {
+            if (lane < cnt_a) cand_dst[cand_pos + lane] = pend_a[lane];
+            if (lane < cnt_b) cand_dst[cand_pos + cnt_a + lane] = pend_b[lane];
+            cand_pos += cnt_a + cnt_b;
+        } else {
+            cand_pos = cand_cap + 1;
+        }
+    }
     uint32_t member = 0xffffffffu; // lane c < gsz: the kw-th best of the group's chunk c
     if (lane < gsz && lane != self)
         member = __hip_atomic_load(kth_row + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -149,7 +163,7 @@ __device__ __noinline__ uint32_t mfma_flush_query(const lds_u32 *pend_a, const l
         if (best > 0u) __hip_atomic_fetch_max(bound_q, best, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     wave_lds_fence();
-    return best;
+    return ((u64)(uint32_t)cand_pos << 32) | best;
 }
 
 // STORE: inspection mode, every score is written to scores_out and nothing is selected.
@@ -202,7 +216,13 @@ adc_mfma_scan_kernel(const ScanParams p)
     uint32_t bound_ord = 0u; // best known lower bound of the final R-th best ordering value of this lane's query
     // A score enters when its ordering value (sum + 1) is >= the bound's: later points of a
     // wave can have lower ids than earlier ones, so equal scores must pass.
-    auto thr_of = [&]() -> int { return live ? (int)bound_ord - off - 2 : 0x7fffffff; };
+    // Candidate mode (cand_keys set): everything within the query's margin below the bound passes
+    // too and is kept (see mfma_flush_query); the lists and bounds work as usual.
+    const bool cand_mode = p.cand_keys != nullptr;
+    int marg = 0;
+    if (cand_mode && live) { marg = p.cand_margin[q]; marg = marg > 0 ? marg : 0; }
+    int cpos = 0; // lanes 0-31: keys of this lane's query in its candidate buffer so far
+    auto thr_of = [&]() -> int { return live ? (int)bound_ord - off - 2 - marg : 0x7fffffff; };
     int thr = thr_of();
 
     // flushes query jq (lanes jq and jq + 32 hold its pending keys)
@@ -211,11 +231,14 @@ adc_mfma_scan_kernel(const ScanParams p)
         const int cnt = (int)(pend - pend0);
         const int cnt_a = __builtin_amdgcn_readlane(cnt, jq), cnt_b = __builtin_amdgcn_readlane(cnt, jq + 32);
         const lds_u32 *pa = (const lds_u32 *)dyn_smem + (wave * 64 + jq) * kMfmaPend;
-        const uint32_t best = mfma_flush_query(pa, pa + 32 * kMfmaPend, cnt_a, cnt_b, my_lists + (size_t)jq * C, p.ns, p.R,
-                                               kw, p.kth_shared + (size_t)qq * p.n_chunks + g0, gsz, chunk - g0,
-                                               p.thr_shared + qq);
+        uint32_t *cand_dst = cand_mode ? p.cand_keys + ((size_t)qq * p.n_chunks + chunk) * p.cand_cap : nullptr;
+        const u64 res = mfma_flush_query(pa, pa + 32 * kMfmaPend, cnt_a, cnt_b, my_lists + (size_t)jq * C, p.ns, p.R,
+                                         kw, p.kth_shared + (size_t)qq * p.n_chunks + g0, gsz, chunk - g0,
+                                         p.thr_shared + qq, cand_dst, __builtin_amdgcn_readlane(cpos, jq), p.cand_cap);
+        const uint32_t best = (uint32_t)res;
         if (j == jq) {
             pend = pend0;
+            cpos = (int)(res >> 32);
             bound_ord = best > bound_ord ? best : bound_ord;
             thr = thr_of();
         }
@@ -339,6 +362,7 @@ adc_mfma_scan_kernel(const ScanParams p)
         }
     }
     wave_lds_fence();
+    if (cand_mode && live && h == 0) p.cand_cnt[(size_t)q * p.n_chunks + chunk] = (uint32_t)cpos;
     for (int jq = 0; jq < kMfmaQueries; ++jq) {
         const int qq = tile * kMfmaQueries + jq;
         if (qq >= p.B) break;
@@ -407,6 +431,10 @@ int launch_scan_mfma(const ScanParams &p, hipStream_t st)
         return AVQ_EINVAL;
     }
     if (p.R < 1 || p.R > 64 * p.ns) { set_error("scan: R does not fit the lists"); return AVQ_EINVAL; }
+    if (p.cand_keys != nullptr && (p.cand_cnt == nullptr || p.cand_margin == nullptr || p.cand_cap < 128)) {
+        set_error("scan: candidate mode needs counts, margins and room for one flush");
+        return AVQ_EINVAL;
+    }
     if (p.blocks_per_chunk > kMfmaMaxChunkBlocks || p.M > 64) { set_error("scan: chunk or code too large for 32-bit keys"); return AVQ_EINVAL; }
     const bool store = p.scores_out != nullptr;
     switch (p.NB) {

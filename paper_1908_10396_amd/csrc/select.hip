@@ -12,9 +12,12 @@ namespace avq {
 // merges the waves' lists. cand[q][C] sorted descending.
 __global__ void __launch_bounds__(1024)
 merge_partials_kernel(const u64 *__restrict__ partial, int n_chunks, int ns, u64 *__restrict__ cand,
-                      const int32_t *__restrict__ row_of, const uint32_t *__restrict__ active)
+                      const int32_t *__restrict__ row_of, const uint32_t *__restrict__ active, int tile_queries)
 {
-    if (active != nullptr && blockIdx.x >= *active) return;
+    if (active != nullptr) {
+        if (blockIdx.x >= *active) return;
+        n_chunks = scan_dynamic_chunks(((int)*active + tile_queries - 1) / tile_queries, n_chunks);
+    }
     extern __shared__ __align__(16) unsigned char smem[];
     const int C = 64 * ns;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n_waves = blockDim.x >> 6;
@@ -33,13 +36,13 @@ merge_partials_kernel(const u64 *__restrict__ partial, int n_chunks, int ns, u64
 }
 
 int launch_merge_partials(const u64 *partial, int nq, int n_chunks, int ns, u64 *cand,
-                          hipStream_t st, const int32_t *row_of, const uint32_t *active)
+                          hipStream_t st, const int32_t *row_of, const uint32_t *active, int tile_queries)
 {
     int waves = 1;
     while (waves < 16 && waves * 4 <= n_chunks) waves *= 2;
     const size_t lds = (size_t)waves * 64 * ns * 8;
     hipLaunchKernelGGL(merge_partials_kernel, dim3(nq), dim3(waves * 64), lds, st, partial,
-                       n_chunks, ns, cand, row_of, active);
+                       n_chunks, ns, cand, row_of, active, tile_queries);
     AVQ_HIP(hipGetLastError());
     return AVQ_OK;
 }

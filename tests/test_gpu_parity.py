@@ -120,7 +120,7 @@ def test_search_is_deterministic_and_independent_of_launch_shape(case, lut_mode)
     tiles = (1, 4, 8) if (lut_mode == 1 or case["bits"] == 4) else (1, 4)
     for name, val in (("scan_target_wgs", 64), ("scan_target_wgs", 4096), ("scan_waves", 2),
                       ("small_batch_max", 1), ("small_batch_max", 1000), ("scan_mfma", 1), ("scan_prefilter", 1),
-                      ("scan_prefilter", 2)) + tuple(("scan_qt", t) for t in tiles):
+                      ("scan_prefilter", 2), ("prefilter_cap", 128), ("prefilter_cap", 300)) + tuple(("scan_qt", t) for t in tiles):
         idx.set_tuning(name, val)
         got = [t.cpu().numpy() for t in idx.search(qd, 10, 100, lut_mode)]
         np.testing.assert_array_equal(base[0], got[0])
