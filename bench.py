@@ -196,18 +196,48 @@ def main():
     # 16-entry tables (two entries of a byte are added, then accumulated: 2*NB adds, 8*NB bytes
     # of LDS); byte tables take NB adds and 4*NB bytes.
     nib_tile = bits == 4 and not n_leaves and B >= 8
-    adds = (2.0 if nib_tile else 1.0) * nb * scanned * B
-    lds_bytes = (8.0 if nib_tile else 4.0) * nb * scanned * B
-    if n_leaves:
-        scan_kernel = "adc_scan_kernel<1,false,%d,1>" % (nb if nb in (8, 13, 25, 32) else 0)
+    # batches with fp32 tables on a flat index of 4-bit codes take their candidates from the
+    # matrix-core scan over the 8-bit tables and re-score them in fp32 (exact, see include/avq.h)
+    prefiltered = bits == 4 and not n_leaves and B >= 16 and nb in (8, 13, 25, 32) and M <= 64
+    n_pad = float((n + 255) // 256 * 256)
+    b_pad = float((B + 31) // 32 * 32)
+    mfma_ops = 2.0 * n_pad * b_pad * nb * 32  # 32 points x 32 queries x 32 positions per instruction, NB per (32, 32)
+
+    def direct_roofline(ms):
+        adds = (2.0 if nib_tile else 1.0) * nb * scanned * B
+        lds_bytes = (8.0 if nib_tile else 4.0) * nb * scanned * B
+        if n_leaves:
+            kern = "adc_scan_kernel<1,false,%d,1>" % (nb if nb in (8, 13, 25, 32) else 0)
+        else:
+            kern = "adc_scan_kernel<%d,false,%d,0>" % (8 if nib_tile else 4, nb if nb in (8, 13, 25, 32) else 0)
+        r = {"bound": "alu", "achieved": adds / (ms * 1e-3) / 1e12, "peak": VALU_PEAK_TOPS,
+             "unit": "TFLOP/s", "traffic": None, "kernel": kern, "avg_launch_ms": ms,
+             "note": "fp32 adds of table entries (no multiplies); the other binding unit is the LDS gather",
+             "lds_gather": {"achieved_GBs": lds_bytes / (ms * 1e-3) / 1e9, "peak_GBs": LDS_PEAK_GBS,
+                            "frac": lds_bytes / (ms * 1e-3) / 1e9 / LDS_PEAK_GBS}}
+        r["frac"] = r["achieved"] / r["peak"]
+        return r
+
+    fp32_direct = None
+    if prefiltered:
+        unverified = idx.debug_unverified_queries()
+        batch_roof = {"bound": "mfma", "achieved": mfma_ops / (scan_ms * 1e-3) / 1e12, "peak": MFMA_I8_PEAK_TOPS,
+                      "unit": "TOP/s", "traffic": None, "kernel": "adc_mfma_scan_kernel<%d,false>" % nb,
+                      "avg_launch_ms": scan_ms,
+                      "note": "int8 multiply-adds issued by the candidate scan over the 8-bit tables (16 per useful "
+                              "table add: one-hot operand); the fp32 scores are formed for the kept points only",
+                      "queries_scanned_again_with_fp32_tables": unverified}
+        batch_roof["frac"] = batch_roof["achieved"] / batch_roof["peak"]
+        # the same step with every point scored in fp32 (the kernel the candidate scan replaces)
+        idx.set_tuning("scan_prefilter", 1)
+        dt_d, stage_d = timed_batch(avq.LUT_F32, max(2, args.steps // 5))
+        idx.set_tuning("scan_prefilter", 0)
+        fp32_direct = {"queries_per_s": B * max(2, args.steps // 5) / dt_d, "stage_ms": stage_d,
+                       "roofline": direct_roofline(stage_d["scan"])}
+        log("[bench] fp32 batch %d, every point scored in fp32: %.0f q/s, stages(ms) %s"
+            % (B, fp32_direct["queries_per_s"], stage_d))
     else:
-        scan_kernel = "adc_scan_kernel<%d,false,%d,0>" % (8 if nib_tile else 4, nb if nb in (8, 13, 25, 32) else 0)
-    batch_roof = {"bound": "alu", "achieved": adds / (scan_ms * 1e-3) / 1e12, "peak": VALU_PEAK_TOPS,
-                  "unit": "TFLOP/s", "traffic": None, "kernel": scan_kernel, "avg_launch_ms": scan_ms,
-                  "note": "fp32 adds of table entries (no multiplies); the other binding unit is the LDS gather",
-                  "lds_gather": {"achieved_GBs": lds_bytes / (scan_ms * 1e-3) / 1e9, "peak_GBs": LDS_PEAK_GBS,
-                                 "frac": lds_bytes / (scan_ms * 1e-3) / 1e9 / LDS_PEAK_GBS}}
-    batch_roof["frac"] = batch_roof["achieved"] / batch_roof["peak"]
+        batch_roof = direct_roofline(scan_ms)
     log("[bench] fp32 batch %d: %.2f ms/step, %.0f q/s, stages(ms) %s" % (B, ms_per_step, qps, stage_ms))
 
     # ---- same with 8-bit tables ---------------------------------------------------------------
@@ -218,10 +248,7 @@ def main():
     if bits == 4 and not n_leaves and B >= 16 and nb in (8, 13, 25, 32):
         # one-hot contraction on int8 MFMA: 32 points x 32 queries x 32 positions per instruction,
         # two subspaces (16 positions each) per instruction, NB instructions per (32 points, 32 queries)
-        n_pad = float((n + 255) // 256 * 256)
-        b_pad = float((B + 31) // 32 * 32)
-        ops = 2.0 * n_pad * b_pad * nb * 32
-        u8_roof = {"bound": "mfma", "achieved": ops / (stage8_ms["scan"] * 1e-3) / 1e12, "peak": MFMA_I8_PEAK_TOPS,
+        u8_roof = {"bound": "mfma", "achieved": mfma_ops / (stage8_ms["scan"] * 1e-3) / 1e12, "peak": MFMA_I8_PEAK_TOPS,
                    "unit": "TOP/s", "kernel": "adc_mfma_scan_kernel<%d,false>" % nb,
                    "avg_launch_ms": stage8_ms["scan"], "traffic": None,
                    "note": "int8 multiply-adds issued; 16 of them per useful table add (one-hot operand)"}
@@ -321,11 +348,14 @@ def main():
                                "ADC top-%d re-ranked to top-%d"
                                % (args.config, n, d, M, 1 << bits, bits, nb,
                                   (", %d leaves, %d searched" % (n_leaves, Lp)) if n_leaves else "", B, R, k),
-                   "lut": "f32", "train_s": t_train, "encode_s": t_encode},
+                   "lut": "f32", "train_s": t_train, "encode_s": t_encode,
+                   "scan": ("int8 matrix-core candidate scan + fp32 re-scoring of the kept points (results equal "
+                            "a full fp32 scan)") if prefiltered else "fp32 table sums of every point"},
         "recall_at_10": recall["f32"], "recall_at_10_u8": recall["u8"], "recall_queries": nr,
         "adc_points_per_s": scanned * B / (scan_ms * 1e-3),
         "adc_codes_per_s": scanned * B * M / (scan_ms * 1e-3),
         "stage_ms": stage_ms,
+        "fp32_every_point": fp32_direct,
         "u8": {"queries_per_s": qps8, "stage_ms": stage8_ms,
                "adc_codes_per_s": scanned * B * M / (stage8_ms["scan"] * 1e-3), "roofline": u8_roof},
         "roofline": batch_roof,

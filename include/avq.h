@@ -141,7 +141,15 @@ int avq_update_codebooks(avq_index *idx, const float *x, int64_t n, int32_t max_
  *    the two entries of a packed 4-bit byte are added first, then bytes are
  *    accumulated in order; 8-bit tables: exact integer sum). With leaves the
  *    score is s + <q, center> (fp32) or fma(acc, scale, bias + <q, center>);
- *  keep the R = reorder_k best by (score descending, id ascending);
+ *  keep the R = reorder_k best by (score descending, id ascending). Batches
+ *    (16 queries or more) with fp32 tables on a flat index of 4-bit codes do
+ *    not score every point in fp32: the 8-bit tables are built as well, the
+ *    integer sums of all points are formed on the matrix cores, every point
+ *    whose sum is within M + slack units of the R-th best sum is kept (the
+ *    rounding of the 8-bit tables moves a sum by at most M/2 units, so no
+ *    other point can be among the R best by fp32 score), and only those are
+ *    scored in fp32, in the order of additions given above. The R best and
+ *    their scores are exactly those of a full fp32 scan;
  *  re-score those exactly, <q, x_i> as an fp32 fma chain in index order, and
  *    return the k best in the same order.
  * reorder_k == 0: no re-scoring; the k best ADC candidates are returned with
@@ -188,9 +196,12 @@ int64_t avq_size(const avq_index *idx); /* n, or 0 */
  * fp32 [nq], written in U8 mode only (may be NULL otherwise). */
 int avq_debug_lut(avq_index *idx, const float *queries, int32_t nq, int32_t lut_mode,
                   void *lut_out, float *scale_out, float *bias_out, void *hip_stream);
-/* ADC score of every stored point, flat index only, produced by the same scan
- * kernel as avq_search. scores_out: device [nq][n], fp32 (AVQ_LUT_F32) or
- * int32 integer sums (AVQ_LUT_U8). */
+/* ADC score of every stored point, flat index only, produced by the scan
+ * kernels that form these sums in avq_search (fp32: the kernel over fp32
+ * tables, whose order of additions every fp32 score avq_search returns
+ * follows; 8-bit tables: the matrix-core kernel where it applies).
+ * scores_out: device [nq][n], fp32 (AVQ_LUT_F32) or int32 integer sums
+ * (AVQ_LUT_U8). */
 int avq_debug_adc_scores(avq_index *idx, const float *queries, int32_t nq, int32_t lut_mode,
                          void *scores_out, void *hip_stream);
 /* Leaf selection alone: leaf_ids_out int32 [nq][L], leaf_ip_out fp32 [nq][L],
