@@ -244,7 +244,10 @@ double avq_eta(int32_t d, double T, double norm, int32_t eta_mode);
  * 2: candidates are taken as usual, but every odd query is treated as one
  * whose candidates cannot be used and is scanned again with fp32 tables),
  * "prefilter_cap" (candidate keys that scan may keep per query and chunk of
- * the index; a query that needs more is scanned again with fp32 tables).
+ * the index; a query that needs more is scanned again with fp32 tables),
+ * "scan_sample" (1: that candidate scan keeps lists and raises its bounds as
+ * it goes, instead of scanning against bounds guessed from a sample of the
+ * index and checked afterwards).
  * Results never depend on these. Returns
  * AVQ_EINVAL for an unknown name. */
 int avq_set_tuning(avq_index *idx, const char *name, int32_t value);

@@ -62,6 +62,7 @@ struct avq_index {
     int tune_mfma = 0; // 0 = use the matrix-core scan where it applies, 1 = never
     int tune_prefilter = 0; // 0 = fp32-table batches go through the 8-bit-table scan where it applies, 1 = never,
                             // 2 = as 0 but odd queries always take the plain scan afterwards (exercises that branch)
+    int tune_sample = 0; // 0 = fp32-table batches guess the candidate scan's bounds from a sample where possible, 1 = never
     int tune_prefilter_cap = 0; // candidate keys per (query, chunk) of that scan, 0 = built-in
     DevBuf block_max, lists, refined, lut_fail, fail, cand_keys;
     // optional per-stage timing with HIP events recorded on the caller's stream
@@ -176,6 +177,7 @@ extern "C" int avq_set_tuning(avq_index *idx, const char *name, int32_t value)
     else if (!strcmp(name, "scan_mfma")) idx->tune_mfma = value;
     else if (!strcmp(name, "scan_prefilter")) idx->tune_prefilter = value;
     else if (!strcmp(name, "prefilter_cap")) idx->tune_prefilter_cap = value;
+    else if (!strcmp(name, "scan_sample")) idx->tune_sample = value;
     else { set_error("avq_set_tuning: unknown name '%s'", name); return AVQ_EINVAL; }
     return AVQ_OK;
 }
@@ -583,13 +585,26 @@ static int search_prefiltered(avq_index *idx, const float *queries, int nq, int 
     pm.cand_margin = margin;
     {
         StageTimer t(idx, AVQ_STAGE_SCAN, st);
-        AVQ_HIP(hipMemsetAsync(pm.thr_shared, 0, thr_bytes, st));
         AVQ_HIP(hipMemsetAsync(fail_count, 0, 16, st));
+        AVQ_HIP(hipMemsetAsync(pm.thr_shared, 0, thr_bytes, st));
         AVQ_TRY(launch_prefilter_margin(idx->lut.as<float>(), idx->scale.as<float>(), c.M, idx->NB, nq, margin, st));
+        // guess the bounds from a sample of the index and scan against them, where the index is large
+        // enough for that; otherwise the scan keeps lists and raises its bounds itself
+        ScanParams sample;
+        if (idx->tune_sample == 0 && scan_mfma_sample_plan(pm, &sample)) {
+            AVQ_TRY(launch_scan_mfma(sample, st));
+            const u64 *best = sample.partial;
+            if (sample.n_chunks > 1) {
+                AVQ_TRY(launch_merge_partials(sample.partial, nq, sample.n_chunks, sample.ns, idx->cand.as<u64>(), st));
+                best = idx->cand.as<u64>();
+            }
+            AVQ_TRY(launch_list_bound(best, sample.ns, sample.R, nq, pm.thr_shared, st));
+            pm.fixed_bound = 1;
+        }
         AVQ_TRY(launch_scan_mfma(pm, st));
     }
-    const u64 *top = pm.partial;
-    if (pm.n_chunks > 1) {
+    const u64 *top = pm.fixed_bound ? nullptr : pm.partial;
+    if (!pm.fixed_bound && pm.n_chunks > 1) {
         StageTimer t(idx, AVQ_STAGE_MERGE, st);
         AVQ_TRY(launch_merge_partials(pm.partial, nq, pm.n_chunks, ns, idx->cand.as<u64>(), st));
         top = idx->cand.as<u64>();
@@ -598,6 +613,7 @@ static int search_prefiltered(avq_index *idx, const float *queries, int nq, int 
         StageTimer t(idx, AVQ_STAGE_RESCAN, st);
         RefineCandParams r;
         r.top = top;
+        r.bound = pm.fixed_bound ? pm.thr_shared : nullptr;
         r.R = R; r.ns = ns; r.nq = nq; r.M = c.M; r.NB = idx->NB;
         r.n_chunks = pm.n_chunks;
         r.cand_cap = pm.cand_cap;

@@ -80,6 +80,9 @@ struct ScanParams {
     // ordering value per query; [B][n_chunks] every wave's ceil(R/group)-th best
     uint32_t *thr_shared, *kth_shared;
     int32_t group;        // chunks per threshold group
+    int32_t bounds_only;  // matrix-core kernel: publish bounds in thr_shared, write no lists (sampling launch)
+    int32_t block_stride; // matrix-core kernel: > 1: visit only every block_stride-th block of a chunk
+    int32_t fixed_bound;  // matrix-core kernel, candidate mode: thr_shared holds bounds that are not raised; no lists
     // matrix-core kernel, candidate mode (cand_keys != NULL): every point whose sum is within
     // cand_margin[q] (< 0 counts as 0) of the bound is appended, as a 32-bit chunk-local key, to
     // cand_keys[q][chunk][cand_cap]; cand_cnt[q][chunk] = how many (cand_cap + 1: overflowed)
@@ -98,7 +101,7 @@ struct ScanParams {
 // workgroups share the work, so a few tiles are cut into many chunks (every one of them still
 // spreads over the chip) and many tiles into few; never more than max_chunks, never fewer than 1.
 // tiles * chunks <= max(kDynamicItems, tiles): a grid of max(kDynamicItems, all tiles) covers it.
-constexpr int kDynamicItems = 4096;
+constexpr int kDynamicItems = 1024;
 __host__ __device__ inline int scan_dynamic_chunks(int tiles, int max_chunks)
 {
     int c = tiles > 0 ? kDynamicItems / tiles : 1;
@@ -120,6 +123,9 @@ int launch_scan(const ScanParams &p, bool u8, int mode, const ScanShape &shape, 
 bool scan_mfma_supported(int NB, int bits);
 void scan_mfma_plan(int B, int64_t n_blocks, int target_waves, ScanParams *p);
 size_t scan_mfma_lists_bytes(const ScanParams &p);
+// Fills *sample with the launch that guesses the bounds of a fixed-bound scan `full` (same
+// scratch; run it first, with thr_shared and kth_shared cleared). false: the index is too small.
+bool scan_mfma_sample_plan(const ScanParams &full, ScanParams *sample);
 int launch_scan_mfma(const ScanParams &p, hipStream_t st);
 // Whether the small-batch kernels can compute their own tables (fuse_* above).
 bool small_batch_can_fuse_tables(int bits, int M, int d, bool u8);
@@ -180,7 +186,11 @@ int brute_force_chunks(int64_t n, int nq);
 // overflowed are appended to fail_list (count in *fail_count, zeroed by the caller) and left to
 // a plain fp32 scan. margin[q] comes from launch_prefilter_margin, before the scan.
 struct RefineCandParams {
+    // one of the two: top[q][64*ns], the R best integer sums (a scan that kept lists), or bound[q],
+    // the ordering value of the fixed bound the scan used (then the kernel checks that R kept points
+    // reach it, else the query fails, and finds the R-th best sum itself)
     const u64 *top;
+    const uint32_t *bound;
     int32_t R, ns, nq, M, NB;
     int32_t n_chunks, cand_cap;
     int64_t chunk_points;        // points per chunk of the scan (ids in the 32-bit keys count from the chunk's first)
@@ -195,6 +205,8 @@ struct RefineCandParams {
 };
 int launch_prefilter_margin(const float *lut, const float *scale, int M, int NB, int nq, int32_t *margin, hipStream_t st);
 int launch_refine_cand(const RefineCandParams &r, hipStream_t st);
+// bound[q] = ordering value of the r-th key of the sorted list lists[q][64*ns] (0: fewer than r keys)
+int launch_list_bound(const u64 *lists, int ns, int r, int nq, uint32_t *bound, hipStream_t st);
 // dst[c] = src[row[c]] for c < *count (rows of row_floats floats); grid sized for max_rows
 int launch_gather_rows(const float *src, float *dst, const int32_t *row, const uint32_t *count, int max_rows,
                        int row_floats, hipStream_t st);

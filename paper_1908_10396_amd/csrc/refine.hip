@@ -53,7 +53,9 @@ int launch_prefilter_margin(const float *lut, const float *scale, int M, int NB,
     return AVQ_OK;
 }
 
-constexpr int kRefineMax = 2048; // candidates of one query that the refinement holds; more: plain scan
+constexpr int kMaxChunks = 256;  // chunks of the scan (scan_mfma_plan never makes more)
+constexpr int kGatherMax = 4096; // kept keys of one query that the refinement can look at; more: plain scan
+constexpr int kFinalMax = 2048;  // of those, the ones within the margin of the R-th best sum; more: plain scan
 
 
 template <int NBT>
@@ -66,41 +68,103 @@ refine_cand_kernel(const RefineCandParams r)
     const int C = 64 * r.ns;
     const int n_tab = 2 * r.NB;
     float *tbl = (float *)smem;                                               // [n_tab][16]
-    u64 *keys = (u64 *)(smem + (((size_t)n_tab * 64 + 15) & ~(size_t)15));    // [kRefineMax]
-    int32_t *ids = (int32_t *)(keys + kRefineMax);                            // [kRefineMax]
-    __shared__ int n_top_s, n_cand_s, bad_s;
+    u64 *keys = (u64 *)(smem + (((size_t)n_tab * 64 + 15) & ~(size_t)15));    // [kFinalMax]
+    int32_t *ids = (int32_t *)(keys + kFinalMax);                             // [kGatherMax]
+    uint32_t *ords = (uint32_t *)(ids + kGatherMax);                          // [kGatherMax] (fixed bounds only)
+    __shared__ int n_top_s, n_cand_s, bad_s, cnt_s, n_fin_s;
+    __shared__ uint32_t cnts[kMaxChunks];
 
     const float *L = r.lut + (size_t)q * r.M * 16;
     for (int e = tid; e < n_tab * 16; e += nt) tbl[e] = e < r.M * 16 ? L[e] : 0.0f;
-    if (tid == 0) { n_top_s = 0; n_cand_s = 0; bad_s = 0; }
+    if (tid == 0) { n_top_s = 0; n_cand_s = 0; bad_s = 0; cnt_s = 0; n_fin_s = 0; }
     __syncthreads();
-    const u64 *top = r.top + (size_t)q * C;
-    int mine = 0;
-    for (int i = tid; i < r.R; i += nt) mine += top[i] != 0ull;
-    if (mine) atomicAdd(&n_top_s, mine);
-    __syncthreads();
+    const bool fixed = r.bound != nullptr;
     const int margin = r.margin[q];
-    // fewer than R points in the whole index: the bound never rose above zero and every point was kept
-    const uint32_t ord_r = n_top_s == r.R ? key_ord(top[r.R - 1]) : 0u;
-    const uint32_t thr_ord = ord_r > (uint32_t)(margin > 0 ? margin : 0) ? ord_r - (uint32_t)margin : 0u;
-    if (margin >= 0) {
-        for (int c = 0; c < r.n_chunks; ++c) {
-            const uint32_t cnt = r.cand_cnt[(size_t)q * r.n_chunks + c];
-            if (cnt > (uint32_t)r.cand_cap) { if (tid == 0) bad_s = 1; break; } // uniform: cnt is
+    const uint32_t um = (uint32_t)(margin > 0 ? margin : 0);
+    uint32_t thr_ord = 0u; // keys below it are dropped while gathering
+    if (!fixed) {
+        const u64 *top = r.top + (size_t)q * C;
+        int mine = 0;
+        for (int i = tid; i < r.R; i += nt) mine += top[i] != 0ull;
+        if (mine) atomicAdd(&n_top_s, mine);
+        __syncthreads();
+        // fewer than R points in the whole index: the bound never rose above zero and every point was kept
+        const uint32_t ord_r = n_top_s == r.R ? key_ord(top[r.R - 1]) : 0u;
+        thr_ord = ord_r > um ? ord_r - um : 0u;
+    }
+    // the chunks' fill counts first (one load each, all in flight together), then every wave takes
+    // chunks in turn: no load waits for another
+    for (int c = tid; c < r.n_chunks; c += nt) {
+        const uint32_t cnt = r.cand_cnt[(size_t)q * r.n_chunks + c];
+        cnts[c] = cnt;
+        if (cnt > (uint32_t)r.cand_cap) bad_s = 1; // overflowed
+    }
+    __syncthreads();
+    if (margin >= 0 && bad_s == 0) {
+        const int lane = tid & 63, wave = tid >> 6, n_waves = nt >> 6;
+        for (int c = wave; c < r.n_chunks; c += n_waves) {
+            const uint32_t cnt = cnts[c];
             const uint32_t *src = r.cand_keys + ((size_t)q * r.n_chunks + c) * r.cand_cap;
             const int32_t id_base = (int32_t)((int64_t)c * r.chunk_points);
-            for (uint32_t i = tid; i < cnt; i += nt) {
+            for (uint32_t i = lane; i < cnt; i += 64) {
                 const uint32_t k32 = src[i];
                 if ((k32 >> 18) < thr_ord) continue;
                 const int slot = atomicAdd(&n_cand_s, 1);
-                if (slot < kRefineMax) ids[slot] = id_base + (int32_t)(~k32 & 0x3ffffu);
+                if (slot < kGatherMax) {
+                    ids[slot] = id_base + (int32_t)(~k32 & 0x3ffffu);
+                    if (fixed) ords[slot] = k32 >> 18;
+                }
             }
         }
     }
     __syncthreads();
-    const int n_cand = n_cand_s;
-    bool ok = margin >= 0 && bad_s == 0 && n_cand <= kRefineMax;
+    int n_cand = n_cand_s;
+    bool ok = margin >= 0 && bad_s == 0 && n_cand <= (fixed ? kGatherMax : kFinalMax);
     if (r.force_fail_odd && (q & 1)) ok = false;
+    if (ok && fixed) {
+        // The scan kept every point at or above bound - margin. If R of them reach the bound itself, the
+        // R-th best sum of the index does too, and nothing that matters was dropped. Then that R-th best
+        // sum is found by bisection (every thread counts its own keys), and only keys within the margin of
+        // it stay.
+        const uint32_t T = r.bound[q];
+        uint32_t mine[kGatherMax / 256];
+#pragma unroll
+        for (int k = 0; k < kGatherMax / 256; ++k) mine[k] = tid + k * 256 < n_cand ? ords[tid + k * 256] : 0u;
+        auto count_ge = [&](uint32_t v) -> int { // keys with ordering value >= v, over the workgroup
+            int c = 0;
+#pragma unroll
+            for (int k = 0; k < kGatherMax / 256; ++k) c += mine[k] >= v;
+            for (int m = 32; m > 0; m >>= 1) c += __shfl_xor(c, m, 64);
+            __syncthreads(); // cnt_s is free again
+            if (tid == 0) cnt_s = 0;
+            __syncthreads();
+            if ((tid & 63) == 0 && c) atomicAdd(&cnt_s, c);
+            __syncthreads();
+            return cnt_s;
+        };
+        if (T == 0u || count_ge(T) < r.R) {
+            ok = false;
+        } else {
+            uint32_t lo = T, hi = 1u << 14; // count_ge(lo) >= R > count_ge(hi): ordering values stay below 2^14
+            while (hi - lo > 1u) {
+                const uint32_t mid = (lo + hi) >> 1;
+                if (count_ge(mid) >= r.R) lo = mid; else hi = mid;
+            }
+            const uint32_t keep = lo > um ? lo - um : 0u; // lo = the R-th best sum's ordering value
+            __syncthreads();
+#pragma unroll
+            for (int k = 0; k < kGatherMax / 256; ++k) {
+                const int i = tid + k * 256;
+                const int32_t id = i < n_cand ? ids[i] : 0;
+                const bool stay = i < n_cand && mine[k] >= keep;
+                __syncthreads(); // every id of this round is read before any slot is overwritten
+                if (stay) ids[atomicAdd(&n_fin_s, 1)] = id; // slots 0 .. n_fin - 1 <= indices already read
+            }
+            __syncthreads();
+            n_cand = n_fin_s;
+            ok = n_cand <= kFinalMax;
+        }
+    }
     if (!ok) {
         if (tid == 0) r.fail_list[atomicAdd(r.fail_count, 1u)] = q;
         return;
@@ -142,10 +206,25 @@ refine_cand_kernel(const RefineCandParams r)
     for (int i = n_fin + tid; i < C; i += nt) out[i] = 0ull;
 }
 
+// bound[q] = ordering value of the r-th key of query q's sorted list (0 if there are fewer)
+__global__ void __launch_bounds__(256)
+list_bound_kernel(const u64 *__restrict__ lists, int C, int r, int nq, uint32_t *__restrict__ bound)
+{
+    const int q = blockIdx.x * blockDim.x + threadIdx.x;
+    if (q < nq) bound[q] = key_ord(lists[(size_t)q * C + (r - 1)]);
+}
+
+int launch_list_bound(const u64 *lists, int ns, int r, int nq, uint32_t *bound, hipStream_t st)
+{
+    hipLaunchKernelGGL(list_bound_kernel, dim3((nq + 255) / 256), dim3(256), 0, st, lists, 64 * ns, r, nq, bound);
+    AVQ_HIP(hipGetLastError());
+    return AVQ_OK;
+}
+
 int launch_refine_cand(const RefineCandParams &r, hipStream_t st)
 {
-    if (r.M > 64 || r.R > 64 * r.ns || r.cand_cap < 1) { set_error("refine: bad shape (M %d, R %d)", r.M, r.R); return AVQ_EINVAL; }
-    const size_t lds = (((size_t)2 * r.NB * 64 + 15) & ~(size_t)15) + (sizeof(u64) + sizeof(int32_t)) * (size_t)kRefineMax;
+    if (r.M > 64 || r.R > 64 * r.ns || r.cand_cap < 1 || r.n_chunks > kMaxChunks || (r.top == nullptr) == (r.bound == nullptr)) { set_error("refine: bad shape (M %d, R %d)", r.M, r.R); return AVQ_EINVAL; }
+    const size_t lds = (((size_t)2 * r.NB * 64 + 15) & ~(size_t)15) + sizeof(u64) * (size_t)kFinalMax + 2 * sizeof(int32_t) * (size_t)kGatherMax;
     switch (r.NB) {
     case 8: hipLaunchKernelGGL(refine_cand_kernel<8>, dim3(r.nq), dim3(256), lds, st, r); break;
     case 13: hipLaunchKernelGGL(refine_cand_kernel<13>, dim3(r.nq), dim3(256), lds, st, r); break;

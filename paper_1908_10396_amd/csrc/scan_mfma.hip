@@ -33,6 +33,18 @@
 //    of the group's union, which no wave could compute alone, and cuts the keys that
 //    reach the lists roughly by the size of the group.
 // A wave reads its queries' bounds once per block, one block ahead of their use.
+//
+// Guess and check (fixed_bound). While a list is young its bound is weak and nearly every
+// point passes; sorting those keys into lists is a fifth of the scan's time. For fp32-table
+// batches, which only need a superset of the R best (candidate mode), the bound is guessed
+// instead: a first launch of this kernel scores a sample of the points (every block_stride-th
+// block of every chunk) with short lists; the r-th best sum of the sample, r chosen so that
+// about four times R points of the whole index lie above it, becomes the query's bound in
+// thr_shared. The second launch scans everything against that fixed bound, appends what
+// reaches it (less the margin) to the candidate buffers and keeps no lists. Afterwards the
+// guess is checked per query: if at least R kept points reach the bound, the R-th best sum of
+// the index is at or above it and nothing was missed; otherwise the query is scanned again.
+#include <cmath>
 #include "avq_internal.h"
 #include "wave_topk.h"
 
@@ -166,6 +178,19 @@ __device__ __noinline__ u64 mfma_flush_query(const lds_u32 *pend_a, const lds_u3
     return ((u64)(uint32_t)cand_pos << 32) | best;
 }
 
+// The flush of the fixed-bound scan: the pending keys are appended to the candidate buffer and
+// that is all (no list, no bound to raise). Returns the new fill count (cand_cap + 1: overflowed).
+__device__ __noinline__ int mfma_dump_query(const lds_u32 *pend_a, const lds_u32 *pend_b, int cnt_a, int cnt_b,
+                                            uint32_t *cand_dst, int cand_pos, int cand_cap)
+{
+    const int lane = lane_id();
+    if (cand_pos + cnt_a + cnt_b > cand_cap) return cand_cap + 1;
+    if (lane < cnt_a) cand_dst[cand_pos + lane] = pend_a[lane];
+    if (lane < cnt_b) cand_dst[cand_pos + cnt_a + lane] = pend_b[lane];
+    wave_lds_fence();
+    return cand_pos + cnt_a + cnt_b;
+}
+
 // STORE: inspection mode, every score is written to scores_out and nothing is selected.
 template <int NBT, bool STORE>
 __global__ void __launch_bounds__(kMfmaWaves * 64, 2)
@@ -204,7 +229,10 @@ adc_mfma_scan_kernel(const ScanParams p)
     lds_u32 *const pend0 = (lds_u32 *)dyn_smem + (wave * 64 + lane) * kMfmaPend;
     lds_u32 *const pend_end = pend0 + kMfmaPend;
     lds_u32 *pend = pend0; // next free slot of this lane's pending buffer
-    if constexpr (!store) {
+    // fixed_bound: the bounds in thr_shared are taken as they are and never raised: every point at
+    // or above them (less the margin) goes to the candidate buffer, and no lists are kept
+    const bool fixed = !store && p.fixed_bound != 0;
+    if (!store && !fixed) {
         my_lists = (uint32_t *)p.lists_ws + (size_t)gw * kMfmaQueries * C;
         for (int i = lane; i < kMfmaQueries * C; i += 64) my_lists[i] = 0u;
         wave_lds_fence();
@@ -223,6 +251,8 @@ adc_mfma_scan_kernel(const ScanParams p)
     if (cand_mode && live) { marg = p.cand_margin[q]; marg = marg > 0 ? marg : 0; }
     int cpos = 0; // lanes 0-31: keys of this lane's query in its candidate buffer so far
     auto thr_of = [&]() -> int { return live ? (int)bound_ord - off - 2 - marg : 0x7fffffff; };
+    // a bound may already be there: that of an earlier launch over a sample of the same points (bounds_only)
+    if (!store && live) bound_ord = __hip_atomic_load(p.thr_shared + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     int thr = thr_of();
 
     // flushes query jq (lanes jq and jq + 32 hold its pending keys)
@@ -232,6 +262,12 @@ adc_mfma_scan_kernel(const ScanParams p)
         const int cnt_a = __builtin_amdgcn_readlane(cnt, jq), cnt_b = __builtin_amdgcn_readlane(cnt, jq + 32);
         const lds_u32 *pa = (const lds_u32 *)dyn_smem + (wave * 64 + jq) * kMfmaPend;
         uint32_t *cand_dst = cand_mode ? p.cand_keys + ((size_t)qq * p.n_chunks + chunk) * p.cand_cap : nullptr;
+        if (fixed) {
+            const int np = mfma_dump_query(pa, pa + 32 * kMfmaPend, cnt_a, cnt_b, cand_dst, __builtin_amdgcn_readlane(cpos, jq),
+                                           p.cand_cap);
+            if (j == jq) { pend = pend0; cpos = np; }
+            return;
+        }
         const u64 res = mfma_flush_query(pa, pa + 32 * kMfmaPend, cnt_a, cnt_b, my_lists + (size_t)jq * C, p.ns, p.R,
                                          kw, p.kth_shared + (size_t)qq * p.n_chunks + g0, gsz, chunk - g0,
                                          p.thr_shared + qq, cand_dst, __builtin_amdgcn_readlane(cpos, jq), p.cand_cap);
@@ -244,9 +280,12 @@ adc_mfma_scan_kernel(const ScanParams p)
         }
     };
 
+    // the chunk's blocks; a sampling launch takes only every block_stride-th of them
     const int64_t first = (int64_t)chunk * p.blocks_per_chunk;
     int64_t end = first + p.blocks_per_chunk;
     if (end > p.n_blocks) end = p.n_blocks;
+    const int64_t stride = p.block_stride > 1 ? p.block_stride : 1;
+    const int64_t n_half = end > first ? 2 * ((end - first + stride - 1) / stride) : 0; // half blocks to visit
     const int32_t id_base = (int32_t)(first * kBlockPoints); // ids inside keys count from here
     const uint32_t nib_shift = 4u * (uint32_t)(1 - h); // brings this half-wave's nibble to bits 4..7 of each byte
 
@@ -264,14 +303,16 @@ adc_mfma_scan_kernel(const ScanParams p)
             w[(NBT / 4) * 4 + t] = ((const uint32_t *)(base + (size_t)(NBT / 4) * 1024 + (size_t)t * 256))[slot];
     };
 
-    uint32_t nxt_bound = 0u; // the shared bound, read one block ahead of its use
+    uint32_t nxt_bound = bound_ord; // the shared bound, read one block ahead of its use
     uint32_t w_cur[NBT], w_nxt[NBT];
-    if (first < end) load_half(w_cur, 2 * first);
-    for (int64_t hb = 2 * first; hb < 2 * end; ++hb) {
+    auto half_of = [&](int64_t i) -> int64_t { return 2 * (first + (i >> 1) * stride) + (i & 1); };
+    if (n_half > 0) load_half(w_cur, half_of(0));
+    for (int64_t i = 0; i < n_half; ++i) {
+        const int64_t hb = half_of(i);
         const int64_t blk = hb >> 1;
         const int H = (int)(hb & 1);
-        if (hb + 1 < 2 * end) load_half(w_nxt, hb + 1);
-        if (!store && H == 0 && live) {
+        if (i + 1 < n_half) load_half(w_nxt, half_of(i + 1));
+        if (!store && !fixed && H == 0 && live) {
             bound_ord = nxt_bound > bound_ord ? nxt_bound : bound_ord;
             thr = thr_of();
             nxt_bound = __hip_atomic_load(p.thr_shared + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -362,7 +403,9 @@ adc_mfma_scan_kernel(const ScanParams p)
         }
     }
     wave_lds_fence();
+    if (p.bounds_only) return; // the flushes above have published this wave's bounds; its lists are not wanted
     if (cand_mode && live && h == 0) p.cand_cnt[(size_t)q * p.n_chunks + chunk] = (uint32_t)cpos;
+    if (fixed) return;
     for (int jq = 0; jq < kMfmaQueries; ++jq) {
         const int qq = tile * kMfmaQueries + jq;
         if (qq >= p.B) break;
@@ -399,6 +442,30 @@ void scan_mfma_plan(int B, int64_t n_blocks, int target_waves, ScanParams *p)
     p->group = (int32_t)std::max<int64_t>(1, std::min<int64_t>(16, std::min<int64_t>(resident, p->n_chunks)));
 }
 
+// The sampling launch for a fixed-bound scan planned in `full`: the same queries and chunks, 16
+// blocks of every chunk at equal distances, lists of r keys (see below). Returns
+// false when the index is too small for a sample to say much (then the caller scans with lists).
+bool scan_mfma_sample_plan(const ScanParams &full, ScanParams *sample)
+{
+    const int64_t per_chunk = 16;
+    if (full.scores_out != nullptr || full.blocks_per_chunk < 16 * per_chunk) return false;
+    *sample = full;
+    sample->block_stride = (int32_t)(full.blocks_per_chunk / per_chunk);
+    sample->bounds_only = 0;
+    sample->fixed_bound = 0;
+    sample->cand_keys = nullptr;
+    sample->cand_cnt = nullptr;
+    sample->cand_margin = nullptr;
+    // mu of the R best of the index fall into the sample on average (Poisson); the r-th best of the
+    // sample is below the R-th best of the index unless r or more of them do: r = mu + 3.5 sigma + 1
+    const double mu = (double)full.R * (double)per_chunk / (double)full.blocks_per_chunk;
+    int r = std::max(8, (int)std::ceil(mu + 3.5 * std::sqrt(mu) + 1.0));
+    if (r > 64 * kMfmaMaxNs) return false;
+    sample->R = r;
+    sample->ns = (r + 63) / 64;
+    return true;
+}
+
 size_t scan_mfma_lists_bytes(const ScanParams &p)
 {
     return sizeof(u64) * (size_t)p.n_tiles * p.n_chunks * kMfmaQueries * 64 * p.ns;
@@ -425,8 +492,13 @@ static int launch_mfma_one(const ScanParams &p, hipStream_t st)
 int launch_scan_mfma(const ScanParams &p, hipStream_t st)
 {
     if (!scan_mfma_supported(p.NB, p.bits)) { set_error("scan: no matrix-core kernel for this code size"); return AVQ_EINVAL; }
-    if (p.scores_out == nullptr && (p.lists_ws == nullptr || p.thr_shared == nullptr || p.kth_shared == nullptr || p.partial == nullptr ||
-                                  p.group < 1)) {
+    if (p.fixed_bound && (p.cand_keys == nullptr || p.thr_shared == nullptr)) {
+        set_error("scan: a fixed-bound scan needs bounds and candidate buffers");
+        return AVQ_EINVAL;
+    }
+    if (p.scores_out == nullptr && !p.fixed_bound &&
+        (p.lists_ws == nullptr || p.thr_shared == nullptr || p.kth_shared == nullptr || (p.partial == nullptr && !p.bounds_only) ||
+         p.group < 1)) {
         set_error("scan: matrix-core kernel needs its scratch buffers");
         return AVQ_EINVAL;
     }

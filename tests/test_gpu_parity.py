@@ -120,7 +120,7 @@ def test_search_is_deterministic_and_independent_of_launch_shape(case, lut_mode)
     tiles = (1, 4, 8) if (lut_mode == 1 or case["bits"] == 4) else (1, 4)
     for name, val in (("scan_target_wgs", 64), ("scan_target_wgs", 4096), ("scan_waves", 2),
                       ("small_batch_max", 1), ("small_batch_max", 1000), ("scan_mfma", 1), ("scan_prefilter", 1),
-                      ("scan_prefilter", 2), ("prefilter_cap", 128), ("prefilter_cap", 300)) + tuple(("scan_qt", t) for t in tiles):
+                      ("scan_prefilter", 2), ("prefilter_cap", 128), ("prefilter_cap", 300), ("scan_sample", 1)) + tuple(("scan_qt", t) for t in tiles):
         idx.set_tuning(name, val)
         got = [t.cpu().numpy() for t in idx.search(qd, 10, 100, lut_mode)]
         np.testing.assert_array_equal(base[0], got[0])
@@ -162,6 +162,46 @@ def test_fp32_batches_with_flat_score_distributions(prefilter):
         ids, sc = idx.search(dev(q), k, R, avq.LUT_U8)
         np.testing.assert_array_equal(ids.cpu().numpy(), oi)
         np.testing.assert_array_equal(sc.cpu().numpy(), os_)
+
+
+@pytest.mark.parametrize("variant", ["default", "lists", "odd_fail", "small_buffers"])
+def test_fp32_batches_scan_against_sampled_bounds(variant):
+    # Large chunks (here forced by asking for few waves) make the candidate scan of fp32-table
+    # batches guess its bounds from a sample of the blocks and check the guess afterwards. 6,000
+    # copies of one vector sit in the first blocks only: for queries near it the sample, which
+    # takes blocks at equal distances, says little about the best scores, and the check must
+    # notice where the guess was too high. Results must equal the oracle's in every variant.
+    rng = np.random.default_rng(61)
+    n, d, M, bits, nq = 300_000, 32, 16, 4, 64
+    x = unit_rows(rng, n, d)
+    proto = unit_rows(rng, 1, d)
+    x[rng.permutation(12_000)[:6000]] = proto[0]
+    q = unit_rows(rng, nq, d)
+    q[:8] = proto[0] + 0.1 * rng.standard_normal((8, d)).astype(np.float32)
+    idx = avq.Index(d, M, bits, T=0.2, kmeans_iters=4, encode_passes=2, seed=5)
+    xd = dev(x)
+    idx.train(xd[:20_000])
+    idx.encode(xd)
+    cb = idx.get_codebooks()
+    codes = unpack_codes(idx.get_codes(), M, bits)
+    idx.set_tuning("scan_target_wgs", 4)
+    if variant == "lists":
+        idx.set_tuning("scan_sample", 1)
+    elif variant == "odd_fail":
+        idx.set_tuning("scan_prefilter", 2)
+    elif variant == "small_buffers":
+        idx.set_tuning("prefilter_cap", 200)
+    for k, R in ((10, 100), (5, 0), (10, 500)):
+        oi, os_ = oracle.search(x, cb, codes, bits, q, k, R, 0)
+        ids, sc = idx.search(dev(q), k, R, avq.LUT_F32)
+        np.testing.assert_array_equal(ids.cpu().numpy(), oi)
+        np.testing.assert_array_equal(sc.cpu().numpy(), os_)
+        unverified = idx.debug_unverified_queries()
+        assert 0 <= unverified <= nq
+        if variant == "odd_fail":
+            assert unverified >= nq // 2
+        if variant == "default" and R == 100:
+            assert unverified < nq // 2          # the guess holds for ordinary queries
 
 
 def test_equal_scores_inside_a_block_with_8bit_codes():
