@@ -219,11 +219,13 @@ int avq_debug_leaf_select(avq_index *idx, const float *queries, int32_t nq, int3
 int avq_debug_stream_codes(avq_index *idx, uint32_t *words_out, int64_t *n_blocks_out, void *hip_stream);
 
 /* Measurement aid: after an avq_search with fp32 tables that took its candidates
- * from the 8-bit-table scan (see "scan_prefilter" below), the number of queries
- * of that call whose candidate lists could not be proven complete and were
- * scanned again with fp32 tables. -1 if the last such search did not happen.
- * Synchronises the device. */
-int avq_debug_unverified_queries(avq_index *idx, int32_t *count_out);
+ * from the 8-bit-table scan (see "scan_prefilter" below): counts_out[0] = the
+ * number of queries of that call that were scanned again with fp32 tables
+ * (-1 if no such search has happened), of which counts_out[1] because the scan
+ * kept more points than the refinement holds, counts_out[2] because the bound
+ * guessed from the sample was too high, counts_out[3] for other reasons (no
+ * usable margin, the "scan_prefilter" = 2 test mode). Synchronises the device. */
+int avq_debug_unverified_queries(avq_index *idx, int32_t *counts_out /* [4] */);
 
 /* eta of Section 3.2 for one norm, on the host (no GPU needed):
  * mode AVQ_ETA_LIMIT or AVQ_ETA_EXACT as in avq_config. */

@@ -293,10 +293,11 @@ class Index:
                                           _stream_ptr(stream)))
         return out
 
-    def debug_unverified_queries(self):
-        c = C.c_int32(-1)
-        _check(lib().avq_debug_unverified_queries(self._h, C.byref(c)))
-        return c.value
+    def debug_unverified_queries(self, reasons=False):
+        """Queries of the last fp32 batch that were scanned again; reasons=True: the four counts of avq.h."""
+        c = (C.c_int32 * 4)()
+        _check(lib().avq_debug_unverified_queries(self._h, c))
+        return list(c) if reasons else c[0]
 
     def debug_stream_codes(self, out=None, stream=None):
         """xor of every block's code words, uint32 [n_blocks] on the device (see avq.h)."""

@@ -554,7 +554,7 @@ static int search_prefiltered(avq_index *idx, const float *queries, int nq, int 
     ScanShape shape;
     AVQ_TRY(scan_pick_shape(idx->NB, c.bits, false, ns, nq, false, 8, idx->tune_waves, &shape));
     pf.n_tiles = (nq + shape.qt - 1) / shape.qt;
-    pf.n_chunks = (int32_t)std::max<int64_t>(1, std::min<int64_t>(64, idx->n_blocks / shape.waves)); // at most
+    pf.n_chunks = (int32_t)std::max<int64_t>(1, std::min<int64_t>(128, idx->n_blocks / shape.waves)); // at most
     pf.blocks_per_chunk = 0; // derived on the device
 
     const size_t partial_m = sizeof(u64) * (size_t)nq * pm.n_chunks * C;
@@ -913,16 +913,17 @@ extern "C" int avq_debug_stream_codes(avq_index *idx, uint32_t *words_out, int64
     return launch_stream_codes(idx->codes_blocked.as<uint8_t>(), idx->n_blocks, idx->NB, words_out, (hipStream_t)hip_stream);
 }
 
-extern "C" int avq_debug_unverified_queries(avq_index *idx, int32_t *count_out)
+extern "C" int avq_debug_unverified_queries(avq_index *idx, int32_t *counts_out)
 {
     AVQ_TRY(check_index(idx));
-    if (!count_out) { set_error("avq_debug_unverified_queries: NULL"); return AVQ_EINVAL; }
-    *count_out = -1;
+    if (!counts_out) { set_error("avq_debug_unverified_queries: NULL"); return AVQ_EINVAL; }
+    counts_out[0] = -1;
+    counts_out[1] = counts_out[2] = counts_out[3] = 0;
     if (!idx->fail.p) return AVQ_OK;
     AVQ_HIP(hipDeviceSynchronize());
-    uint32_t c = 0;
-    AVQ_HIP(hipMemcpy(&c, idx->fail.p, sizeof(c), hipMemcpyDeviceToHost));
-    *count_out = (int32_t)c;
+    uint32_t c[4] = {0, 0, 0, 0};
+    AVQ_HIP(hipMemcpy(c, idx->fail.p, sizeof(c), hipMemcpyDeviceToHost));
+    for (int i = 0; i < 4; ++i) counts_out[i] = (int32_t)c[i];
     return AVQ_OK;
 }
 

@@ -54,7 +54,7 @@ int launch_prefilter_margin(const float *lut, const float *scale, int M, int NB,
 }
 
 constexpr int kMaxChunks = 256;  // chunks of the scan (scan_mfma_plan never makes more)
-constexpr int kGatherMax = 4096; // kept keys of one query that the refinement can look at; more: plain scan
+constexpr int kKeysPerThread = 32; // kept keys of one query that the refinement can look at: 256 threads x 32; more: plain scan
 constexpr int kFinalMax = 2048;  // of those, the ones within the margin of the R-th best sum; more: plain scan
 
 
@@ -63,114 +63,120 @@ __global__ void __launch_bounds__(256)
 refine_cand_kernel(const RefineCandParams r)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    const int tid = threadIdx.x, nt = blockDim.x;
+    const int tid = threadIdx.x;
+    constexpr int nt = 256;
     const int q = blockIdx.x;
     const int C = 64 * r.ns;
     const int n_tab = 2 * r.NB;
     float *tbl = (float *)smem;                                               // [n_tab][16]
-    u64 *keys = (u64 *)(smem + (((size_t)n_tab * 64 + 15) & ~(size_t)15));    // [kFinalMax]
-    int32_t *ids = (int32_t *)(keys + kFinalMax);                             // [kGatherMax]
-    uint32_t *ords = (uint32_t *)(ids + kGatherMax);                          // [kGatherMax] (fixed bounds only)
-    __shared__ int n_top_s, n_cand_s, bad_s, cnt_s, n_fin_s;
-    __shared__ uint32_t cnts[kMaxChunks];
+    u64 *keys = (u64 *)(smem + (((size_t)n_tab * 64 + 15) & ~(size_t)15));    // [kFinalMax] fp32 keys of the finalists
+    int32_t *fin_ids = (int32_t *)(keys + kFinalMax);                         // [kFinalMax]
+    __shared__ int n_top_s, bad_s, cnt_s, n_fin_s;
+    __shared__ uint32_t first_of[kMaxChunks + 1]; // first_of[c] = kept keys in the chunks before c
 
     const float *L = r.lut + (size_t)q * r.M * 16;
     for (int e = tid; e < n_tab * 16; e += nt) tbl[e] = e < r.M * 16 ? L[e] : 0.0f;
-    if (tid == 0) { n_top_s = 0; n_cand_s = 0; bad_s = 0; cnt_s = 0; n_fin_s = 0; }
+    if (tid == 0) { n_top_s = 0; bad_s = 0; cnt_s = 0; n_fin_s = 0; }
+    // the chunks' fill counts (one load each, all in flight together) and their running sum
+    uint32_t my_cnt = 0u;
+    if (tid < r.n_chunks) my_cnt = r.cand_cnt[(size_t)q * r.n_chunks + tid];
     __syncthreads();
+    if (tid < r.n_chunks && my_cnt > (uint32_t)r.cand_cap) bad_s = 1; // that chunk's buffer overflowed
+    first_of[tid + 1 <= kMaxChunks ? tid + 1 : kMaxChunks] = my_cnt;  // tid 255 -> slot 256
+    if (tid == 0) first_of[0] = 0u;
+    __syncthreads();
+    for (int d = 1; d < kMaxChunks; d *= 2) { // inclusive scan over slots 1 .. kMaxChunks
+        const uint32_t add = tid + 1 > d ? first_of[tid + 1 - d] : 0u;
+        __syncthreads();
+        first_of[tid + 1] += add;
+        __syncthreads();
+    }
     const bool fixed = r.bound != nullptr;
     const int margin = r.margin[q];
     const uint32_t um = (uint32_t)(margin > 0 ? margin : 0);
-    uint32_t thr_ord = 0u; // keys below it are dropped while gathering
+    uint32_t keep = 0u; // ordering value from which a kept key is a finalist
     if (!fixed) {
         const u64 *top = r.top + (size_t)q * C;
-        int mine = 0;
-        for (int i = tid; i < r.R; i += nt) mine += top[i] != 0ull;
-        if (mine) atomicAdd(&n_top_s, mine);
+        int mine_top = 0;
+        for (int i = tid; i < r.R; i += nt) mine_top += top[i] != 0ull;
+        if (mine_top) atomicAdd(&n_top_s, mine_top);
         __syncthreads();
         // fewer than R points in the whole index: the bound never rose above zero and every point was kept
         const uint32_t ord_r = n_top_s == r.R ? key_ord(top[r.R - 1]) : 0u;
-        thr_ord = ord_r > um ? ord_r - um : 0u;
+        keep = ord_r > um ? ord_r - um : 0u;
     }
-    // the chunks' fill counts first (one load each, all in flight together), then every wave takes
-    // chunks in turn: no load waits for another
-    for (int c = tid; c < r.n_chunks; c += nt) {
-        const uint32_t cnt = r.cand_cnt[(size_t)q * r.n_chunks + c];
-        cnts[c] = cnt;
-        if (cnt > (uint32_t)r.cand_cap) bad_s = 1; // overflowed
-    }
-    __syncthreads();
-    if (margin >= 0 && bad_s == 0) {
-        const int lane = tid & 63, wave = tid >> 6, n_waves = nt >> 6;
-        for (int c = wave; c < r.n_chunks; c += n_waves) {
-            const uint32_t cnt = cnts[c];
-            const uint32_t *src = r.cand_keys + ((size_t)q * r.n_chunks + c) * r.cand_cap;
-            const int32_t id_base = (int32_t)((int64_t)c * r.chunk_points);
-            for (uint32_t i = lane; i < cnt; i += 64) {
-                const uint32_t k32 = src[i];
-                if ((k32 >> 18) < thr_ord) continue;
-                const int slot = atomicAdd(&n_cand_s, 1);
-                if (slot < kGatherMax) {
-                    ids[slot] = id_base + (int32_t)(~k32 & 0x3ffffu);
-                    if (fixed) ords[slot] = k32 >> 18;
-                }
+    const uint32_t total = first_of[r.n_chunks];
+    bool ok = margin >= 0 && bad_s == 0 && total <= (uint32_t)(nt * kKeysPerThread);
+    int why = margin >= 0 ? 1 : 3;
+    if (r.force_fail_odd && (q & 1)) { ok = false; why = 3; }
+    // every thread takes the kept keys tid, tid + 256, ... of the chunks laid end to end, into registers
+    uint32_t mine[kKeysPerThread];
+    if (ok) {
+        int c = 0;
+#pragma unroll
+        for (int k = 0; k < kKeysPerThread; ++k) {
+            const uint32_t flat = (uint32_t)(tid + k * nt);
+            mine[k] = 0u;
+            if (flat < total) {
+                while (flat >= first_of[c + 1]) ++c;
+                mine[k] = r.cand_keys[((size_t)q * r.n_chunks + c) * r.cand_cap + (flat - first_of[c])];
             }
         }
     }
-    __syncthreads();
-    int n_cand = n_cand_s;
-    bool ok = margin >= 0 && bad_s == 0 && n_cand <= (fixed ? kGatherMax : kFinalMax);
-    if (r.force_fail_odd && (q & 1)) ok = false;
     if (ok && fixed) {
         // The scan kept every point at or above bound - margin. If R of them reach the bound itself, the
         // R-th best sum of the index does too, and nothing that matters was dropped. Then that R-th best
         // sum is found by bisection (every thread counts its own keys), and only keys within the margin of
-        // it stay.
+        // it go on. (Unused slots hold 0: ordering value 0, below every bound.)
         const uint32_t T = r.bound[q];
-        uint32_t mine[kGatherMax / 256];
-#pragma unroll
-        for (int k = 0; k < kGatherMax / 256; ++k) mine[k] = tid + k * 256 < n_cand ? ords[tid + k * 256] : 0u;
         auto count_ge = [&](uint32_t v) -> int { // keys with ordering value >= v, over the workgroup
-            int c = 0;
+            int cn = 0;
 #pragma unroll
-            for (int k = 0; k < kGatherMax / 256; ++k) c += mine[k] >= v;
-            for (int m = 32; m > 0; m >>= 1) c += __shfl_xor(c, m, 64);
+            for (int k = 0; k < kKeysPerThread; ++k) cn += (mine[k] >> 18) >= v;
+            for (int m = 32; m > 0; m >>= 1) cn += __shfl_xor(cn, m, 64);
             __syncthreads(); // cnt_s is free again
             if (tid == 0) cnt_s = 0;
             __syncthreads();
-            if ((tid & 63) == 0 && c) atomicAdd(&cnt_s, c);
+            if ((tid & 63) == 0 && cn) atomicAdd(&cnt_s, cn);
             __syncthreads();
             return cnt_s;
         };
         if (T == 0u || count_ge(T) < r.R) {
             ok = false;
+            why = 2;
         } else {
             uint32_t lo = T, hi = 1u << 14; // count_ge(lo) >= R > count_ge(hi): ordering values stay below 2^14
             while (hi - lo > 1u) {
                 const uint32_t mid = (lo + hi) >> 1;
                 if (count_ge(mid) >= r.R) lo = mid; else hi = mid;
             }
-            const uint32_t keep = lo > um ? lo - um : 0u; // lo = the R-th best sum's ordering value
-            __syncthreads();
-#pragma unroll
-            for (int k = 0; k < kGatherMax / 256; ++k) {
-                const int i = tid + k * 256;
-                const int32_t id = i < n_cand ? ids[i] : 0;
-                const bool stay = i < n_cand && mine[k] >= keep;
-                __syncthreads(); // every id of this round is read before any slot is overwritten
-                if (stay) ids[atomicAdd(&n_fin_s, 1)] = id; // slots 0 .. n_fin - 1 <= indices already read
-            }
-            __syncthreads();
-            n_cand = n_fin_s;
-            ok = n_cand <= kFinalMax;
+            keep = lo > um ? lo - um : 0u; // lo = the R-th best sum's ordering value
         }
     }
+    if (ok) {
+        int c = 0;
+#pragma unroll
+        for (int k = 0; k < kKeysPerThread; ++k) {
+            const uint32_t flat = (uint32_t)(tid + k * nt);
+            if (flat < total && (mine[k] >> 18) >= keep) {
+                while (flat >= first_of[c + 1]) ++c;
+                const int slot = atomicAdd(&n_fin_s, 1);
+                if (slot < kFinalMax) fin_ids[slot] = (int32_t)((int64_t)c * r.chunk_points) + (int32_t)(~mine[k] & 0x3ffffu);
+            }
+        }
+        __syncthreads();
+        ok = n_fin_s <= kFinalMax;
+    }
     if (!ok) {
-        if (tid == 0) r.fail_list[atomicAdd(r.fail_count, 1u)] = q;
+        if (tid == 0) {
+            r.fail_list[atomicAdd(r.fail_count, 1u)] = q;
+            atomicAdd(r.fail_count + why, 1u); // statistics: 1 = too many kept points, 2 = bound guessed too high, 3 = other
+        }
         return;
     }
+    const int n_cand = n_fin_s;
     for (int i = tid; i < n_cand; i += nt) {
-        const int32_t id = ids[i];
+        const int32_t id = fin_ids[i];
         const uint8_t *row = r.codes + (size_t)id * r.NB;
         float s = 0.0f;
         if constexpr (NBT != 0) {
@@ -224,7 +230,7 @@ int launch_list_bound(const u64 *lists, int ns, int r, int nq, uint32_t *bound, 
 int launch_refine_cand(const RefineCandParams &r, hipStream_t st)
 {
     if (r.M > 64 || r.R > 64 * r.ns || r.cand_cap < 1 || r.n_chunks > kMaxChunks || (r.top == nullptr) == (r.bound == nullptr)) { set_error("refine: bad shape (M %d, R %d)", r.M, r.R); return AVQ_EINVAL; }
-    const size_t lds = (((size_t)2 * r.NB * 64 + 15) & ~(size_t)15) + sizeof(u64) * (size_t)kFinalMax + 2 * sizeof(int32_t) * (size_t)kGatherMax;
+    const size_t lds = (((size_t)2 * r.NB * 64 + 15) & ~(size_t)15) + (sizeof(u64) + sizeof(int32_t)) * (size_t)kFinalMax;
     switch (r.NB) {
     case 8: hipLaunchKernelGGL(refine_cand_kernel<8>, dim3(r.nq), dim3(256), lds, st, r); break;
     case 13: hipLaunchKernelGGL(refine_cand_kernel<13>, dim3(r.nq), dim3(256), lds, st, r); break;

@@ -457,9 +457,10 @@ bool scan_mfma_sample_plan(const ScanParams &full, ScanParams *sample)
     sample->cand_cnt = nullptr;
     sample->cand_margin = nullptr;
     // mu of the R best of the index fall into the sample on average (Poisson); the r-th best of the
-    // sample is below the R-th best of the index unless r or more of them do: r = mu + 3.5 sigma + 1
+    // sample is below the R-th best of the index unless r or more of them do: r = mu + 5 sigma + 1
+    // (a query for which that still happens costs a second scan, a few hundred microseconds per batch)
     const double mu = (double)full.R * (double)per_chunk / (double)full.blocks_per_chunk;
-    int r = std::max(8, (int)std::ceil(mu + 3.5 * std::sqrt(mu) + 1.0));
+    int r = std::max(8, (int)std::ceil(mu + 5.0 * std::sqrt(mu) + 1.0));
     if (r > 64 * kMfmaMaxNs) return false;
     sample->R = r;
     sample->ns = (r + 63) / 64;
