@@ -220,13 +220,25 @@ def main():
 
     fp32_direct = None
     if prefiltered:
-        unverified = idx.debug_unverified_queries()
-        batch_roof = {"bound": "mfma", "achieved": mfma_ops / (scan_ms * 1e-3) / 1e12, "peak": MFMA_I8_PEAK_TOPS,
+        unverified = idx.debug_unverified_queries(reasons=True)
+        # two launches of the kernel per step when the index is large enough for a sample (the library's
+        # rule: chunks of at least 256 blocks): 16 blocks per chunk first, then everything
+        n_blocks = (n + 255) // 256
+        n_tiles32 = (B + 31) // 32
+        chunks = max(1, min(2048 // n_tiles32, 256, n_blocks // 4))
+        bpc = -(-n_blocks // chunks)
+        sampled = bpc >= 256
+        launches = 2 if sampled else 1
+        ops_step = mfma_ops * (1.0 + (16.0 / bpc if sampled else 0.0))
+        batch_roof = {"bound": "mfma", "achieved": ops_step / (scan_ms * 1e-3) / 1e12, "peak": MFMA_I8_PEAK_TOPS,
                       "unit": "TOP/s", "traffic": None, "kernel": "adc_mfma_scan_kernel<%d,false>" % nb,
-                      "avg_launch_ms": scan_ms,
+                      "launches_per_step": launches, "avg_launch_ms": scan_ms / launches,
                       "note": "int8 multiply-adds issued by the candidate scan over the 8-bit tables (16 per useful "
-                              "table add: one-hot operand); the fp32 scores are formed for the kept points only",
-                      "queries_scanned_again_with_fp32_tables": unverified}
+                              "table add: one-hot operand), per step: a launch over a sample of the blocks that "
+                              "guesses the bounds, then the launch over all blocks; the fp32 scores are formed "
+                              "for the kept points only",
+                      "queries_scanned_again_with_fp32_tables": unverified[0],
+                      "of_which_too_many_kept_or_bound_too_high_or_other": unverified[1:]}
         batch_roof["frac"] = batch_roof["achieved"] / batch_roof["peak"]
         # the same step with every point scored in fp32 (the kernel the candidate scan replaces)
         idx.set_tuning("scan_prefilter", 1)
