@@ -84,6 +84,35 @@ def test_u8_lut_properties(M, bits, ds):
         assert (sc2, b2) == (scale, bias)
 
 
+@pytest.mark.parametrize("offset,spread", [(0.0, 1.0), (50.0, 1.0), (1000.0, 0.01), (-3.0, 30.0)])
+def test_points_outside_the_margin_of_the_integer_sums_cannot_rank_in_fp32(offset, spread):
+    # What the library's fp32 batches rely on (4-bit codes): with acc the integer sums over the 8-bit
+    # tables and acc_(R) the R-th largest of them, every one of the R best fp32 scores (ties by id)
+    # has acc >= acc_(R) - margin, margin = ceil(M + 0.01 + 2.02 rho / scale) + 1,
+    # rho = (NB + 2) 2^-24 1.01 sum_m max_j |L[m][j]|: rounding moves each of the M table entries by at
+    # most half a unit of scale, and the fp32 sum is within rho of the real one. Tables with a large
+    # common offset or a tiny spread make the fp32 rounding term matter.
+    rng = np.random.default_rng(77)
+    M, bits, n = 50, 4, 6000
+    NB = M // 2
+    codes = rng.integers(0, 16, (n, M)).astype(np.uint8)
+    worst = 0
+    for trial in range(6):
+        L = (offset + spread * rng.standard_normal((M, 16))).astype(np.float32)
+        Q8, scale, bias = oracle.lut_u8(L)
+        acc = oracle.adc_u8(Q8, codes).astype(np.int64)
+        s = oracle.adc_f32(L, codes, bits)
+        rho = (NB + 2) * 2.0 ** -24 * 1.01 * float(np.abs(L).max(1).astype(np.float64).sum())
+        margin = int(np.ceil(M + 0.01 + 2.02 * rho / float(scale))) + 1
+        by_f32 = np.lexsort((np.arange(n), -s.astype(np.float64)))      # score descending, id ascending
+        acc_sorted = np.sort(acc)[::-1]
+        for R in (1, 10, 100, 500):
+            need = acc_sorted[R - 1] - margin
+            assert acc[by_f32[:R]].min() >= need, (trial, R, margin)
+            worst = max(worst, int(acc_sorted[R - 1] - acc[by_f32[:R]].min()))
+    assert worst > 0   # the two orders do differ: the margin is doing something
+
+
 def test_u8_lut_rounding_half_even_and_degenerate():
     # one subspace, entries at exact multiples: (L - lo) * 255 / R lands on .5 values
     L = np.array([[0.0, 255.0, 0.5, 1.5, 2.5, 254.5, 100.0, 3.0] + [1.0] * 8], np.float32)
