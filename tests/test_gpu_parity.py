@@ -204,6 +204,30 @@ def test_fp32_batches_scan_against_sampled_bounds(variant):
             assert unverified < nq // 2          # the guess holds for ordinary queries
 
 
+@pytest.mark.parametrize("n,d,M,nq", [(280_001, 100, 50, 40), (300_300, 100, 25, 33), (270_000, 98, 49, 17)])
+def test_fp32_batches_sampled_bounds_other_code_sizes(n, d, M, nq):
+    # the same two-launch candidate scan for 25, 13 (odd M: a zero table at the end) and a
+    # non-specialised number of code bytes (M = 49: the scan with fp32 tables of every point),
+    # sizes that are no multiple of a block, batches that are no multiple of a tile
+    rng = np.random.default_rng(62)
+    x = unit_rows(rng, n, d)
+    q = unit_rows(rng, nq, d)
+    idx = avq.Index(d, M, 4, T=0.2, kmeans_iters=3, encode_passes=1, seed=6)
+    xd = dev(x)
+    idx.train(xd[:8_000])
+    idx.encode(xd)
+    cb = idx.get_codebooks()
+    codes = unpack_codes(idx.get_codes(), M, 4)
+    idx.set_tuning("scan_target_wgs", 4)
+    for k, R in ((10, 100), (1, 0), (10, 257)):
+        oi, os_ = oracle.search(x, cb, codes, 4, q, k, R, 0)
+        ids, sc = idx.search(dev(q), k, R, avq.LUT_F32)
+        np.testing.assert_array_equal(ids.cpu().numpy(), oi)
+        np.testing.assert_array_equal(sc.cpu().numpy(), os_)
+    if M != 49:
+        assert idx.debug_unverified_queries() >= 0      # the candidate path ran
+
+
 def test_equal_scores_inside_a_block_with_8bit_codes():
     # 8-bit codes, both table kinds: duplicates make hundreds of equal scores per block
     rng = np.random.default_rng(52)
