@@ -219,17 +219,17 @@ def main():
         return r
 
     fp32_direct = None
+    # the matrix-core scan takes two launches per step when the index is large enough for a sample (the
+    # library's rule: chunks of at least 256 blocks): 16 blocks per chunk first, then everything
+    n_blocks = (n + 255) // 256
+    n_tiles32 = (B + 31) // 32
+    chunks = max(1, min(2048 // n_tiles32, 256, n_blocks // 4))
+    bpc = -(-n_blocks // chunks)
+    sampled = bpc >= 256
+    launches = 2 if sampled else 1
+    ops_step = mfma_ops * (1.0 + (16.0 / bpc if sampled else 0.0))
     if prefiltered:
         unverified = idx.debug_unverified_queries(reasons=True)
-        # two launches of the kernel per step when the index is large enough for a sample (the library's
-        # rule: chunks of at least 256 blocks): 16 blocks per chunk first, then everything
-        n_blocks = (n + 255) // 256
-        n_tiles32 = (B + 31) // 32
-        chunks = max(1, min(2048 // n_tiles32, 256, n_blocks // 4))
-        bpc = -(-n_blocks // chunks)
-        sampled = bpc >= 256
-        launches = 2 if sampled else 1
-        ops_step = mfma_ops * (1.0 + (16.0 / bpc if sampled else 0.0))
         batch_roof = {"bound": "mfma", "achieved": ops_step / (scan_ms * 1e-3) / 1e12, "peak": MFMA_I8_PEAK_TOPS,
                       "unit": "TOP/s", "traffic": None, "kernel": "adc_mfma_scan_kernel<%d,false>" % nb,
                       "launches_per_step": launches, "avg_launch_ms": scan_ms / launches,
@@ -260,9 +260,9 @@ def main():
     if bits == 4 and not n_leaves and B >= 16 and nb in (8, 13, 25, 32):
         # one-hot contraction on int8 MFMA: 32 points x 32 queries x 32 positions per instruction,
         # two subspaces (16 positions each) per instruction, NB instructions per (32 points, 32 queries)
-        u8_roof = {"bound": "mfma", "achieved": mfma_ops / (stage8_ms["scan"] * 1e-3) / 1e12, "peak": MFMA_I8_PEAK_TOPS,
+        u8_roof = {"bound": "mfma", "achieved": ops_step / (stage8_ms["scan"] * 1e-3) / 1e12, "peak": MFMA_I8_PEAK_TOPS,
                    "unit": "TOP/s", "kernel": "adc_mfma_scan_kernel<%d,false>" % nb,
-                   "avg_launch_ms": stage8_ms["scan"], "traffic": None,
+                   "launches_per_step": launches, "avg_launch_ms": stage8_ms["scan"] / launches, "traffic": None,
                    "note": "int8 multiply-adds issued; 16 of them per useful table add (one-hot operand)"}
         u8_roof["frac"] = u8_roof["achieved"] / u8_roof["peak"]
 

@@ -149,7 +149,11 @@ int avq_update_codebooks(avq_index *idx, const float *x, int64_t n, int32_t max_
  *    rounding of the 8-bit tables moves a sum by at most M/2 units, so no
  *    other point can be among the R best by fp32 score), and only those are
  *    scored in fp32, in the order of additions given above. The R best and
- *    their scores are exactly those of a full fp32 scan;
+ *    their scores are exactly those of a full fp32 scan. (On large indexes
+ *    that scan, also when the search itself uses 8-bit tables, does not keep
+ *    sorted lists: it compares against a bound guessed from a sample of the
+ *    points and checked afterwards; a query whose guess fails is scanned
+ *    again, so results never depend on it);
  *  re-score those exactly, <q, x_i> as an fp32 fma chain in index order, and
  *    return the k best in the same order.
  * reorder_k == 0: no re-scoring; the k best ADC candidates are returned with

@@ -537,8 +537,22 @@ static bool use_prefilter(const avq_index *idx, int nq, int lut_mode, int R)
            nq >= 16 && scan_mfma_supported(idx->NB, idx->cfg.bits) && idx->cfg.M <= 64 && idx->n > R;
 }
 
+// Whether the matrix-core scan of this batch would be given bounds guessed from a sample.
+static bool mfma_scan_samples(const avq_index *idx, int nq, int R, int ns)
+{
+    if (idx->tune_sample != 0) return false;
+    ScanParams p, sample;
+    memset(&p, 0, sizeof(p));
+    p.R = R;
+    p.ns = ns;
+    scan_mfma_plan(nq, idx->n_blocks, idx->tune_target_wgs, &p);
+    return scan_mfma_sample_plan(p, &sample);
+}
+
+// u8: the 8-bit-table search itself through the same machinery (fixed bounds from a sample, kept
+// keys ranked by their integer sums: no margin, no fp32 tables); only called when the scan samples.
 static int search_prefiltered(avq_index *idx, const float *queries, int nq, int k, int reorder_k, int R, int ns,
-                              int32_t *ids_out, float *scores_out, hipStream_t st)
+                              bool u8, int32_t *ids_out, float *scores_out, hipStream_t st)
 {
     const avq_config &c = idx->cfg;
     const int C = 64 * ns;
@@ -552,7 +566,7 @@ static int search_prefiltered(avq_index *idx, const float *queries, int nq, int 
     ScanParams pf;
     fill_scan_params(idx, nq, R, ns, &pf);
     ScanShape shape;
-    AVQ_TRY(scan_pick_shape(idx->NB, c.bits, false, ns, nq, false, 8, idx->tune_waves, &shape));
+    AVQ_TRY(scan_pick_shape(idx->NB, c.bits, u8, ns, nq, false, 8, idx->tune_waves, &shape));
     pf.n_tiles = (nq + shape.qt - 1) / shape.qt;
     pf.n_chunks = (int32_t)std::max<int64_t>(1, std::min<int64_t>(128, idx->n_blocks / shape.waves)); // at most
     pf.blocks_per_chunk = 0; // derived on the device
@@ -567,7 +581,7 @@ static int search_prefiltered(avq_index *idx, const float *queries, int nq, int 
     AVQ_TRY(idx->thr.reserve(thr_bytes));
     AVQ_TRY(idx->cand.reserve(sizeof(u64) * (size_t)nq * C));
     AVQ_TRY(idx->refined.reserve(sizeof(u64) * (size_t)nq * C));
-    const size_t row_floats = (size_t)c.M * idx->kc;
+    const size_t row_floats = u8 ? (size_t)c.M * idx->kc / 4 : (size_t)c.M * idx->kc; // a query's tables, in 4-byte units
     AVQ_TRY(idx->lut_fail.reserve(sizeof(float) * (size_t)pf.n_tiles * shape.qt * row_floats));
     // fail: [4] count | [nq] list | [nq] margins | [nq][chunks] candidate counts
     AVQ_TRY(idx->fail.reserve(sizeof(int32_t) * (4 + (size_t)nq * (2 + (size_t)pm.n_chunks))));
@@ -582,12 +596,12 @@ static int search_prefiltered(avq_index *idx, const float *queries, int nq, int 
     pm.kth_shared = pm.thr_shared + nq;
     pm.cand_keys = idx->cand_keys.as<uint32_t>();
     pm.cand_cnt = (uint32_t *)(margin + nq);
-    pm.cand_margin = margin;
+    pm.cand_margin = u8 ? nullptr : margin;
     {
         StageTimer t(idx, AVQ_STAGE_SCAN, st);
         AVQ_HIP(hipMemsetAsync(fail_count, 0, 16, st));
         AVQ_HIP(hipMemsetAsync(pm.thr_shared, 0, thr_bytes, st));
-        AVQ_TRY(launch_prefilter_margin(idx->lut.as<float>(), idx->scale.as<float>(), c.M, idx->NB, nq, margin, st));
+        if (!u8) AVQ_TRY(launch_prefilter_margin(idx->lut.as<float>(), idx->scale.as<float>(), c.M, idx->NB, nq, margin, st));
         // guess the bounds from a sample of the index and scan against them, where the index is large
         // enough for that; otherwise the scan keeps lists and raises its bounds itself
         ScanParams sample;
@@ -620,8 +634,8 @@ static int search_prefiltered(avq_index *idx, const float *queries, int nq, int 
         r.chunk_points = (int64_t)pm.blocks_per_chunk * kBlockPoints;
         r.cand_keys = pm.cand_keys;
         r.cand_cnt = pm.cand_cnt;
-        r.margin = margin;
-        r.lut = idx->lut.as<float>();
+        r.margin = u8 ? nullptr : margin;
+        r.lut = u8 ? nullptr : idx->lut.as<float>();
         r.codes = idx->codes_logical.as<uint8_t>();
         r.out = idx->refined.as<u64>();
         r.fail_list = fail_list;
@@ -630,18 +644,19 @@ static int search_prefiltered(avq_index *idx, const float *queries, int nq, int 
         AVQ_TRY(launch_refine_cand(r, st));
         // the other queries: their tables side by side, the plain scan over them, and their lists
         // merged into their own rows of the refined candidates
-        AVQ_TRY(launch_gather_rows(idx->lut.as<float>(), idx->lut_fail.as<float>(), fail_list, fail_count, nq,
-                                   (int)row_floats, st));
+        AVQ_TRY(launch_gather_rows(u8 ? (const float *)idx->lut8.p : idx->lut.as<float>(), idx->lut_fail.as<float>(), fail_list,
+                                   fail_count, nq, (int)row_floats, st));
         pf.lut = idx->lut_fail.as<float>();
+        pf.lut8 = idx->lut_fail.as<uint8_t>();
         pf.partial = idx->partial.as<u64>(); // the matrix-core scan's lists are merged by now
         if (shape.lists_global) pf.lists_ws = idx->lists.as<u64>();
         pf.active_queries = fail_count;
-        AVQ_TRY(launch_scan(pf, false, SCAN_CHUNK, shape, st));
+        AVQ_TRY(launch_scan(pf, u8, SCAN_CHUNK, shape, st));
         AVQ_TRY(launch_merge_partials(pf.partial, nq, pf.n_chunks, ns, idx->refined.as<u64>(), st, fail_list, fail_count,
                                       shape.qt));
     }
     StageTimer t(idx, AVQ_STAGE_FINAL, st);
-    return launch_finalize(idx->refined.as<u64>(), ns, nq, R, k, reorder_k != 0, 0, idx->x, c.d, queries,
+    return launch_finalize(idx->refined.as<u64>(), ns, nq, R, k, reorder_k != 0, u8 ? 1 : 0, idx->x, c.d, queries,
                            idx->scale.as<float>(), idx->bias.as<float>(), ids_out, scores_out, st);
 }
 
@@ -688,7 +703,7 @@ extern "C" int avq_search(avq_index *idx, const float *queries, int32_t nq, int3
         StageTimer t(idx, AVQ_STAGE_LUT, st);
         AVQ_TRY(build_tables(idx, queries, nq, prefilter ? AVQ_LUT_U8 : lut_mode, st));
     }
-    if (prefilter) return search_prefiltered(idx, queries, nq, k, reorder_k, R, ns, ids_out, scores_out, st);
+    if (prefilter) return search_prefiltered(idx, queries, nq, k, reorder_k, R, ns, false, ids_out, scores_out, st);
     ScanParams p;
     fill_scan_params(idx, nq, R, ns, &p);
     if (fuse_tables) {
@@ -758,6 +773,8 @@ extern "C" int avq_search(avq_index *idx, const float *queries, int32_t nq, int3
         return launch_finalize(p.partial, ns, nq, R, k, reorder_k != 0, key_kind, idx->x, c.d, queries,
                                idx->scale.as<float>(), idx->bias.as<float>(), ids_out, scores_out, st);
     }
+    if (use_mfma_scan(idx, nq, lut_mode) && idx->tune_prefilter != 1 && c.M <= 64 && idx->n > R && mfma_scan_samples(idx, nq, R, ns))
+        return search_prefiltered(idx, queries, nq, k, reorder_k, R, ns, true, ids_out, scores_out, st);
     if (use_mfma_scan(idx, nq, lut_mode)) {
         // 4-bit codes, 8-bit tables, flat index: the table sums are a one-hot contraction on the matrix cores
         scan_mfma_plan(nq, idx->n_blocks, idx->tune_target_wgs, &p);

@@ -84,7 +84,7 @@ struct ScanParams {
     int32_t block_stride; // matrix-core kernel: > 1: visit only every block_stride-th block of a chunk
     int32_t fixed_bound;  // matrix-core kernel, candidate mode: thr_shared holds bounds that are not raised; no lists
     // matrix-core kernel, candidate mode (cand_keys != NULL): every point whose sum is within
-    // cand_margin[q] (< 0 counts as 0) of the bound is appended, as a 32-bit chunk-local key, to
+    // cand_margin[q] (< 0, or no array: 0) of the bound is appended, as a 32-bit chunk-local key, to
     // cand_keys[q][chunk][cand_cap]; cand_cnt[q][chunk] = how many (cand_cap + 1: overflowed)
     uint32_t *cand_keys, *cand_cnt;
     const int32_t *cand_margin;
@@ -196,7 +196,7 @@ struct RefineCandParams {
     int64_t chunk_points;        // points per chunk of the scan (ids in the 32-bit keys count from the chunk's first)
     const uint32_t *cand_keys, *cand_cnt;
     const int32_t *margin;
-    const float *lut;
+    const float *lut;            // NULL: rank the integer sums themselves (no margin, no re-scoring; margin and codes unused)
     const uint8_t *codes;        // logical [n][NB]
     u64 *out;
     int32_t *fail_list;

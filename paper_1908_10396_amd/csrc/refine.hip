@@ -74,8 +74,12 @@ refine_cand_kernel(const RefineCandParams r)
     __shared__ int n_top_s, bad_s, cnt_s, n_fin_s;
     __shared__ uint32_t first_of[kMaxChunks + 1]; // first_of[c] = kept keys in the chunks before c
 
-    const float *L = r.lut + (size_t)q * r.M * 16;
-    for (int e = tid; e < n_tab * 16; e += nt) tbl[e] = e < r.M * 16 ? L[e] : 0.0f;
+    // lut == NULL: the integer sums themselves are what is ranked (8-bit-table search): no margin, no re-scoring
+    const bool rescore = r.lut != nullptr;
+    if (rescore) {
+        const float *L = r.lut + (size_t)q * r.M * 16;
+        for (int e = tid; e < n_tab * 16; e += nt) tbl[e] = e < r.M * 16 ? L[e] : 0.0f;
+    }
     if (tid == 0) { n_top_s = 0; bad_s = 0; cnt_s = 0; n_fin_s = 0; }
     // the chunks' fill counts (one load each, all in flight together) and their running sum
     uint32_t my_cnt = 0u;
@@ -92,7 +96,7 @@ refine_cand_kernel(const RefineCandParams r)
         __syncthreads();
     }
     const bool fixed = r.bound != nullptr;
-    const int margin = r.margin[q];
+    const int margin = rescore ? r.margin[q] : 0;
     const uint32_t um = (uint32_t)(margin > 0 ? margin : 0);
     uint32_t keep = 0u; // ordering value from which a kept key is a finalist
     if (!fixed) {
@@ -161,7 +165,11 @@ refine_cand_kernel(const RefineCandParams r)
             if (flat < total && (mine[k] >> 18) >= keep) {
                 while (flat >= first_of[c + 1]) ++c;
                 const int slot = atomicAdd(&n_fin_s, 1);
-                if (slot < kFinalMax) fin_ids[slot] = (int32_t)((int64_t)c * r.chunk_points) + (int32_t)(~mine[k] & 0x3ffffu);
+                if (slot < kFinalMax) {
+                    const int32_t id = (int32_t)((int64_t)c * r.chunk_points) + (int32_t)(~mine[k] & 0x3ffffu);
+                    fin_ids[slot] = id;
+                    if (!rescore) keys[slot] = make_key(mine[k] >> 18, id);
+                }
             }
         }
         __syncthreads();
@@ -175,7 +183,7 @@ refine_cand_kernel(const RefineCandParams r)
         return;
     }
     const int n_cand = n_fin_s;
-    for (int i = tid; i < n_cand; i += nt) {
+    for (int i = tid; rescore && i < n_cand; i += nt) {
         const int32_t id = fin_ids[i];
         const uint8_t *row = r.codes + (size_t)id * r.NB;
         float s = 0.0f;
@@ -229,7 +237,7 @@ int launch_list_bound(const u64 *lists, int ns, int r, int nq, uint32_t *bound, 
 
 int launch_refine_cand(const RefineCandParams &r, hipStream_t st)
 {
-    if (r.M > 64 || r.R > 64 * r.ns || r.cand_cap < 1 || r.n_chunks > kMaxChunks || (r.top == nullptr) == (r.bound == nullptr)) { set_error("refine: bad shape (M %d, R %d)", r.M, r.R); return AVQ_EINVAL; }
+    if (r.M > 64 || r.R > 64 * r.ns || r.cand_cap < 1 || r.n_chunks > kMaxChunks || (r.lut != nullptr && r.margin == nullptr) || (r.top == nullptr) == (r.bound == nullptr)) { set_error("refine: bad shape (M %d, R %d)", r.M, r.R); return AVQ_EINVAL; }
     const size_t lds = (((size_t)2 * r.NB * 64 + 15) & ~(size_t)15) + (sizeof(u64) + sizeof(int32_t)) * (size_t)kFinalMax;
     switch (r.NB) {
     case 8: hipLaunchKernelGGL(refine_cand_kernel<8>, dim3(r.nq), dim3(256), lds, st, r); break;

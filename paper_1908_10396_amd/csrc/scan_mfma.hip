@@ -248,7 +248,7 @@ adc_mfma_scan_kernel(const ScanParams p)
     // too and is kept (see mfma_flush_query); the lists and bounds work as usual.
     const bool cand_mode = p.cand_keys != nullptr;
     int marg = 0;
-    if (cand_mode && live) { marg = p.cand_margin[q]; marg = marg > 0 ? marg : 0; }
+    if (cand_mode && live && p.cand_margin != nullptr) { marg = p.cand_margin[q]; marg = marg > 0 ? marg : 0; }
     int cpos = 0; // lanes 0-31: keys of this lane's query in its candidate buffer so far
     auto thr_of = [&]() -> int { return live ? (int)bound_ord - off - 2 - marg : 0x7fffffff; };
     // a bound may already be there: that of an earlier launch over a sample of the same points (bounds_only)
@@ -504,8 +504,8 @@ int launch_scan_mfma(const ScanParams &p, hipStream_t st)
         return AVQ_EINVAL;
     }
     if (p.R < 1 || p.R > 64 * p.ns) { set_error("scan: R does not fit the lists"); return AVQ_EINVAL; }
-    if (p.cand_keys != nullptr && (p.cand_cnt == nullptr || p.cand_margin == nullptr || p.cand_cap < 128)) {
-        set_error("scan: candidate mode needs counts, margins and room for one flush");
+    if (p.cand_keys != nullptr && (p.cand_cnt == nullptr || p.cand_cap < 128)) {
+        set_error("scan: candidate mode needs counts and room for one flush");
         return AVQ_EINVAL;
     }
     if (p.blocks_per_chunk > kMfmaMaxChunkBlocks || p.M > 64) { set_error("scan: chunk or code too large for 32-bit keys"); return AVQ_EINVAL; }

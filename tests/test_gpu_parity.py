@@ -202,6 +202,13 @@ def test_fp32_batches_scan_against_sampled_bounds(variant):
             assert unverified >= nq // 2
         if variant == "default" and R == 100:
             assert unverified < nq // 2          # the guess holds for ordinary queries
+    # the 8-bit-table search goes the same way (kept keys ranked by their integer sums; the 6,000 copies
+    # tie, far more of them than a list holds, and must come out by id)
+    for k, R in ((10, 100), (5, 0)):
+        oi, os_ = oracle.search(x, cb, codes, bits, q, k, R, 1)
+        ids, sc = idx.search(dev(q), k, R, avq.LUT_U8)
+        np.testing.assert_array_equal(ids.cpu().numpy(), oi)
+        np.testing.assert_array_equal(sc.cpu().numpy(), os_)
 
 
 @pytest.mark.parametrize("n,d,M,nq", [(280_001, 100, 50, 40), (300_300, 100, 25, 33), (270_000, 98, 49, 17)])
@@ -220,10 +227,11 @@ def test_fp32_batches_sampled_bounds_other_code_sizes(n, d, M, nq):
     codes = unpack_codes(idx.get_codes(), M, 4)
     idx.set_tuning("scan_target_wgs", 4)
     for k, R in ((10, 100), (1, 0), (10, 257)):
-        oi, os_ = oracle.search(x, cb, codes, 4, q, k, R, 0)
-        ids, sc = idx.search(dev(q), k, R, avq.LUT_F32)
-        np.testing.assert_array_equal(ids.cpu().numpy(), oi)
-        np.testing.assert_array_equal(sc.cpu().numpy(), os_)
+        for lut_mode in (avq.LUT_F32, avq.LUT_U8):
+            oi, os_ = oracle.search(x, cb, codes, 4, q, k, R, lut_mode)
+            ids, sc = idx.search(dev(q), k, R, lut_mode)
+            np.testing.assert_array_equal(ids.cpu().numpy(), oi)
+            np.testing.assert_array_equal(sc.cpu().numpy(), os_)
     if M != 49:
         assert idx.debug_unverified_queries() >= 0      # the candidate path ran
 
