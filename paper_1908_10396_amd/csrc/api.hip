@@ -551,7 +551,7 @@ static bool mfma_scan_samples(const avq_index *idx, int nq, int R, int ns)
 
 // u8: the 8-bit-table search itself through the same machinery (fixed bounds from a sample, kept
 // keys ranked by their integer sums: no margin, no fp32 tables); only called when the scan samples.
-static int search_prefiltered(avq_index *idx, const float *queries, int nq, int k, int reorder_k, int R, int ns,
+static int search_through_candidates(avq_index *idx, const float *queries, int nq, int k, int reorder_k, int R, int ns,
                               bool u8, int32_t *ids_out, float *scores_out, hipStream_t st)
 {
     const avq_config &c = idx->cfg;
@@ -703,7 +703,7 @@ extern "C" int avq_search(avq_index *idx, const float *queries, int32_t nq, int3
         StageTimer t(idx, AVQ_STAGE_LUT, st);
         AVQ_TRY(build_tables(idx, queries, nq, prefilter ? AVQ_LUT_U8 : lut_mode, st));
     }
-    if (prefilter) return search_prefiltered(idx, queries, nq, k, reorder_k, R, ns, false, ids_out, scores_out, st);
+    if (prefilter) return search_through_candidates(idx, queries, nq, k, reorder_k, R, ns, false, ids_out, scores_out, st);
     ScanParams p;
     fill_scan_params(idx, nq, R, ns, &p);
     if (fuse_tables) {
@@ -774,7 +774,7 @@ extern "C" int avq_search(avq_index *idx, const float *queries, int32_t nq, int3
                                idx->scale.as<float>(), idx->bias.as<float>(), ids_out, scores_out, st);
     }
     if (use_mfma_scan(idx, nq, lut_mode) && idx->tune_prefilter != 1 && c.M <= 64 && idx->n > R && mfma_scan_samples(idx, nq, R, ns))
-        return search_prefiltered(idx, queries, nq, k, reorder_k, R, ns, true, ids_out, scores_out, st);
+        return search_through_candidates(idx, queries, nq, k, reorder_k, R, ns, true, ids_out, scores_out, st);
     if (use_mfma_scan(idx, nq, lut_mode)) {
         // 4-bit codes, 8-bit tables, flat index: the table sums are a one-hot contraction on the matrix cores
         scan_mfma_plan(nq, idx->n_blocks, idx->tune_target_wgs, &p);
