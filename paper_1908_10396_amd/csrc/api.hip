@@ -53,7 +53,7 @@ struct avq_index {
     bool have_codebooks = false, have_centers = false;
     DevBuf codebooks, centers, centers_t;
     // database
-    int64_t n = 0, n_slots = 0, n_blocks = 0;
+    int64_t n = 0, n_slots = 0, n_blocks = 0, max_leaf_blocks = 0;
     const float *x = nullptr;
     DevBuf x_own, codes_logical, codes_blocked, assign, perm, leaf_blk;
     // per-call scratch
@@ -64,7 +64,7 @@ struct avq_index {
                             // 2 = as 0 but odd queries always take the plain scan afterwards (exercises that branch)
     int tune_sample = 0; // 0 = fp32-table batches guess the candidate scan's bounds from a sample where possible, 1 = never
     int tune_prefilter_cap = 0; // candidate keys per (query, chunk) of that scan, 0 = built-in
-    DevBuf block_max, lists, refined, lut_fail, fail, cand_keys;
+    DevBuf block_max, lists, refined, lut_fail, fail, cand_keys, groups, kept, fail_rows;
     // optional per-stage timing with HIP events recorded on the caller's stream
     bool prof_on = false;
     std::vector<hipEvent_t> prof_pool;
@@ -157,7 +157,7 @@ extern "C" void avq_destroy(avq_index *idx)
                      &idx->codes_blocked, &idx->assign, &idx->perm, &idx->leaf_blk, &idx->lut, &idx->lut8,
                      &idx->scale, &idx->bias, &idx->partial, &idx->cand, &idx->leaf_ids, &idx->leaf_ip,
                      &idx->tmp, &idx->block_max, &idx->lists, &idx->thr, &idx->refined, &idx->lut_fail,
-                     &idx->fail, &idx->cand_keys};
+                     &idx->fail, &idx->cand_keys, &idx->groups, &idx->kept, &idx->fail_rows};
     for (DevBuf *b : all) b->release();
     for (hipEvent_t e : idx->prof_pool) (void)hipEventDestroy(e);
     delete idx;
@@ -326,9 +326,11 @@ static int install_database(avq_index *idx, const float *x, int64_t n, hipStream
         }
         std::vector<int32_t> leaf_blk(c.n_leaves + 1);
         int64_t blk = 0;
+        idx->max_leaf_blocks = 0;
         for (int l = 0; l < c.n_leaves; ++l) {
             leaf_blk[l] = (int32_t)blk;
             blk += (count[l] + kBlockPoints - 1) / kBlockPoints;
+            idx->max_leaf_blocks = std::max<int64_t>(idx->max_leaf_blocks, (count[l] + kBlockPoints - 1) / kBlockPoints);
         }
         leaf_blk[c.n_leaves] = (int32_t)blk;
         if (blk * kBlockPoints > 0x7fffffff) { set_error("index too large"); return AVQ_EINVAL; }
@@ -660,6 +662,144 @@ static int search_through_candidates(avq_index *idx, const float *queries, int n
                            idx->scale.as<float>(), idx->bias.as<float>(), ids_out, scores_out, st);
 }
 
+// Batches on a partitioned index of 4-bit codes: the (query, leaf) pairs are regrouped by leaf and
+// every leaf is scanned once per 32 of its queries on the matrix cores, against a bound per query
+// that the query's best few leaves supply; the kept points are scored and ranked per query.
+static bool use_grouped_leaves(const avq_index *idx, int nq, int L, int R)
+{
+    return idx->tune_prefilter != 1 && idx->tune_mfma == 0 && idx->cfg.n_leaves > 0 && nq >= 64 && nq <= (1 << 16) &&
+           scan_mfma_supported(idx->NB, idx->cfg.bits) && idx->cfg.M <= 64 && L >= 16 && L <= 512 &&
+           idx->cfg.n_leaves <= (1 << 21) && idx->max_leaf_blocks <= 1024 && R <= 2048;
+}
+
+static int search_leaves_grouped(avq_index *idx, const float *queries, int nq, int k, int reorder_k, int R, int ns, int L,
+                                 bool u8, int32_t *ids_out, float *scores_out, hipStream_t st)
+{
+    const avq_config &c = idx->cfg;
+    const int C = 64 * ns;
+    AVQ_TRY(idx->leaf_ids.reserve(sizeof(int32_t) * (size_t)nq * L));
+    AVQ_TRY(idx->leaf_ip.reserve(sizeof(float) * (size_t)nq * L));
+    {
+        StageTimer t(idx, AVQ_STAGE_LEAF, st);
+        AVQ_TRY(launch_leaf_select(idx->centers_t.as<float>(), c.n_leaves, c.d, queries, nq, L,
+                                   idx->leaf_ids.as<int32_t>(), idx->leaf_ip.as<float>(), st));
+    }
+    // scratch: [4] counts | [nq] unverified queries | [nq] margins | [nq] bounds | [nq] kept counts
+    AVQ_TRY(idx->fail.reserve(sizeof(int32_t) * (4 + (size_t)4 * nq)));
+    uint32_t *fail_count = idx->fail.as<uint32_t>();
+    int32_t *fail_list = idx->fail.as<int32_t>() + 4;
+    int32_t *margin = fail_list + nq;
+    uint32_t *bound = (uint32_t *)(margin + nq);
+    uint32_t *kept_cnt = bound + nq;
+    const int kept_cap = idx->tune_prefilter_cap > 0 ? std::min(4096, std::max(128, idx->tune_prefilter_cap)) : 2048;
+    AVQ_TRY(idx->kept.reserve(sizeof(u64) * (size_t)nq * kept_cap));
+    AVQ_TRY(idx->groups.reserve(sizeof(uint32_t) * group_by_leaf_words(nq, L, c.n_leaves)));
+    AVQ_TRY(idx->cand.reserve(sizeof(u64) * (size_t)nq * C));
+    AVQ_TRY(idx->refined.reserve(sizeof(u64) * (size_t)nq * C));
+
+    // the plain scan over leaves, used twice: over the first leaves of every query for the bounds, and
+    // over all leaves of the queries that are handed back
+    ScanShape shape;
+    const int waves_hint = idx->tune_waves > 0 ? idx->tune_waves : 0;
+    AVQ_TRY(scan_pick_shape(idx->NB, c.bits, u8, ns, nq, true, idx->tune_qt, waves_hint, &shape));
+    ScanParams pl;
+    fill_scan_params(idx, nq, R, ns, &pl);
+    pl.perm = idx->perm.as<int32_t>();
+    pl.leaf_ids = idx->leaf_ids.as<int32_t>();
+    pl.leaf_ip = idx->leaf_ip.as<float>();
+    pl.leaf_blk = idx->leaf_blk.as<int32_t>();
+    pl.n_tiles = nq;
+    pl.n_chunks = 1;
+    AVQ_TRY(idx->partial.reserve(sizeof(u64) * (size_t)nq * C));
+    pl.partial = idx->partial.as<u64>();
+    if (shape.lists_global) {
+        AVQ_TRY(idx->lists.reserve(sizeof(u64) * (size_t)nq * shape.waves * shape.qt * C));
+        pl.lists_ws = idx->lists.as<u64>();
+    }
+    const int bound_leaves = std::min(L, std::max(8, (L + 11) / 12));
+    LeafGroups g;
+    {
+        StageTimer t(idx, AVQ_STAGE_SCAN, st);
+        AVQ_HIP(hipMemsetAsync(fail_count, 0, 16, st));
+        AVQ_HIP(hipMemsetAsync(kept_cnt, 0, sizeof(uint32_t) * (size_t)nq, st));
+        if (!u8) AVQ_TRY(launch_prefilter_margin(idx->lut.as<float>(), idx->scale.as<float>(), c.M, idx->NB, nq, margin, st));
+        ScanParams pb = pl;
+        pb.Lp = bound_leaves;
+        pb.leaf_stride = L;
+        AVQ_TRY(launch_scan(pb, u8, SCAN_LEAVES, shape, st));
+        AVQ_TRY(launch_list_bound(pb.partial, ns, R, nq, bound, st));
+        AVQ_TRY(launch_group_by_leaf(idx->leaf_ids.as<int32_t>(), nq, L, c.n_leaves, idx->groups.as<uint32_t>(), &g, st));
+        ScanParams pi;
+        fill_scan_params(idx, nq, R, ns, &pi);
+        pi.n_valid = 0x7fffffff; // padding slots are told from points by perm, afterwards
+        pi.leaf_blk = idx->leaf_blk.as<int32_t>();
+        pi.leaf_ip = idx->leaf_ip.as<float>();
+        pi.Lp = L;
+        pi.leaf_stride = L;
+        pi.item_list = g.item_list;
+        pi.n_items = g.n_items;
+        pi.qlist = g.qlist;
+        pi.leaf_off = g.leaf_off;
+        pi.leaf_cnt = g.leaf_cnt;
+        pi.max_items = g.max_items;
+        pi.item_bound = bound;
+        pi.cand_margin = u8 ? nullptr : margin;
+        pi.kept = idx->kept.as<u64>();
+        pi.kept_cnt = kept_cnt;
+        pi.kept_cap = kept_cap;
+        AVQ_TRY(launch_scan_mfma(pi, st));
+    }
+    {
+        StageTimer t(idx, AVQ_STAGE_RESCAN, st);
+        IvfRefineParams r;
+        r.kept = idx->kept.as<u64>();
+        r.kept_cnt = kept_cnt;
+        r.kept_cap = kept_cap;
+        r.R = R; r.ns = ns; r.nq = nq; r.M = c.M; r.NB = idx->NB; r.leaf_stride = L;
+        r.lut = u8 ? nullptr : idx->lut.as<float>();
+        r.scale = idx->scale.as<float>();
+        r.bias = idx->bias.as<float>();
+        r.leaf_ip = idx->leaf_ip.as<float>();
+        r.margin = u8 ? nullptr : margin;
+        r.leaf_blk = idx->leaf_blk.as<int32_t>();
+        r.perm = idx->perm.as<int32_t>();
+        r.codes = idx->codes_logical.as<uint8_t>();
+        r.out = idx->refined.as<u64>();
+        r.fail_list = fail_list;
+        r.fail_count = fail_count;
+        r.force_fail_odd = idx->tune_prefilter == 2;
+        AVQ_TRY(launch_ivf_refine(r, st));
+        // the queries handed back: their rows (tables, scale, bias, probed leaves) side by side, the plain
+        // scan over all their leaves, and their lists into their own rows of the refined candidates
+        const size_t lut_row = u8 ? (size_t)c.M * idx->kc / 4 : (size_t)c.M * idx->kc; // 4-byte units
+        AVQ_TRY(idx->lut_fail.reserve(sizeof(float) * (size_t)nq * lut_row));
+        AVQ_TRY(idx->fail_rows.reserve(sizeof(float) * (size_t)nq * (2 + (size_t)2 * L)));
+        float *scale_c = idx->fail_rows.as<float>(), *bias_c = scale_c + nq;
+        float *ip_c = bias_c + nq;
+        int32_t *ids_c = (int32_t *)(ip_c + (size_t)nq * L);
+        AVQ_TRY(launch_gather_rows(u8 ? (const float *)idx->lut8.p : idx->lut.as<float>(), idx->lut_fail.as<float>(), fail_list,
+                                   fail_count, nq, (int)lut_row, st));
+        AVQ_TRY(launch_gather_rows(idx->scale.as<float>(), scale_c, fail_list, fail_count, nq, 1, st));
+        AVQ_TRY(launch_gather_rows(idx->bias.as<float>(), bias_c, fail_list, fail_count, nq, 1, st));
+        AVQ_TRY(launch_gather_rows(idx->leaf_ip.as<float>(), ip_c, fail_list, fail_count, nq, L, st));
+        AVQ_TRY(launch_gather_rows((const float *)idx->leaf_ids.p, (float *)ids_c, fail_list, fail_count, nq, L, st));
+        ScanParams pf = pl;
+        pf.lut = idx->lut_fail.as<float>();
+        pf.lut8 = idx->lut_fail.as<uint8_t>();
+        pf.scale = scale_c;
+        pf.bias = bias_c;
+        pf.leaf_ip = ip_c;
+        pf.leaf_ids = ids_c;
+        pf.Lp = L;
+        pf.active_queries = fail_count;
+        AVQ_TRY(launch_scan(pf, u8, SCAN_LEAVES, shape, st));
+        AVQ_TRY(launch_merge_partials(pf.partial, nq, 1, ns, idx->refined.as<u64>(), st, fail_list, fail_count, 0));
+    }
+    StageTimer t(idx, AVQ_STAGE_FINAL, st);
+    return launch_finalize(idx->refined.as<u64>(), ns, nq, R, k, reorder_k != 0, 0, idx->x, c.d, queries,
+                           idx->scale.as<float>(), idx->bias.as<float>(), ids_out, scores_out, st);
+}
+
 static int check_query_args(const avq_index *idx, const float *queries, int32_t nq, int32_t lut_mode)
 {
     if (idx->n <= 0) { set_error("no database yet (avq_encode or avq_set_database first)"); return AVQ_ESTATE; }
@@ -699,10 +839,12 @@ extern "C" int avq_search(avq_index *idx, const float *queries, int32_t nq, int3
     // the single-query kernels compute short fp32 tables themselves (one launch less)
     const bool fuse_tables = small && idx->tune_small_impl == 0 && small_batch_can_fuse_tables(c.bits, c.M, c.d, u8);
     const bool prefilter = !small && use_prefilter(idx, nq, lut_mode, R);
+    const bool grouped = ivf && use_grouped_leaves(idx, nq, leaves_to_search, R);
     if (!fuse_tables) {
         StageTimer t(idx, AVQ_STAGE_LUT, st);
-        AVQ_TRY(build_tables(idx, queries, nq, prefilter ? AVQ_LUT_U8 : lut_mode, st));
+        AVQ_TRY(build_tables(idx, queries, nq, (prefilter || grouped) ? AVQ_LUT_U8 : lut_mode, st));
     }
+    if (grouped) return search_leaves_grouped(idx, queries, nq, k, reorder_k, R, ns, leaves_to_search, u8, ids_out, scores_out, st);
     if (prefilter) return search_through_candidates(idx, queries, nq, k, reorder_k, R, ns, false, ids_out, scores_out, st);
     ScanParams p;
     fill_scan_params(idx, nq, R, ns, &p);

@@ -89,6 +89,19 @@ struct ScanParams {
     uint32_t *cand_keys, *cand_cnt;
     const int32_t *cand_margin;
     int32_t cand_cap;
+    // matrix-core kernel over a partitioned index (item_list != NULL; fixed bounds, no lists): wave w
+    // takes item_list[w] = leaf << 11 | tile, i.e. the blocks of that leaf against the 32 entries from
+    // qlist[leaf_off[leaf] + 32 * tile] on (leaf_cnt[leaf] of them in all; an entry is query << 9 | slot
+    // of the leaf in the query's probe list). A point is kept when fma(sum, scale[q], bias[q] +
+    // leaf_ip[q][slot]) can still reach item_bound[q] (less cand_margin[q] units when given): its key goes
+    // to kept[q][kept_cap] as (slot << 21 | leaf) << 32 | 32-bit key (ids count from the leaf's first
+    // slot), kept_cnt[q] counts them (beyond kept_cap: overflowed). max_items bounds *n_items.
+    const uint32_t *item_list, *n_items, *qlist, *leaf_off, *leaf_cnt;
+    const uint32_t *item_bound; // [B] ordering values of fp32 scores (ord_from_f32), 0: no bound
+    u64 *kept;
+    uint32_t *kept_cnt;
+    int32_t kept_cap, max_items;
+    int32_t leaf_stride;  // partitioned scans: row stride of leaf_ids / leaf_ip when it is not Lp (0: Lp)
     int32_t max_wgs;      // block-max kernels: workgroups per query at most (0 = built-in); waves loop beyond it
     // flat scan of a compacted query list whose length only the device knows (NULL: all B
     // queries are live): the kernel derives tiles and chunks from *active_queries, n_chunks is
@@ -157,7 +170,7 @@ int launch_small_final(const ScanParams &p, const FinishParams &f, bool u8, hipS
 // Merges the per-chunk lists of every query into one sorted list cand[q][64*ns].
 // row_of / active (both NULL, or both set): query q's list goes to row row_of[q] of cand, only
 // queries below *active are merged, and the lists are those of a scan with active_queries set
-// (tile_queries per tile, at most n_chunks chunks).
+// (tile_queries per tile, at most n_chunks chunks; tile_queries 0: exactly n_chunks chunks).
 int launch_merge_partials(const u64 *partial, int nq, int n_chunks, int ns, u64 *cand,
                           hipStream_t st, const int32_t *row_of = nullptr, const uint32_t *active = nullptr,
                           int tile_queries = 0);
@@ -207,12 +220,39 @@ int launch_prefilter_margin(const float *lut, const float *scale, int M, int NB,
 int launch_refine_cand(const RefineCandParams &r, hipStream_t st);
 // bound[q] = ordering value of the r-th key of the sorted list lists[q][64*ns] (0: fewer than r keys)
 int launch_list_bound(const u64 *lists, int ns, int r, int nq, uint32_t *bound, hipStream_t st);
+// The kept keys of the matrix-core scan over a partitioned index (ScanParams::kept): per query the R
+// best by score, sorted, to out[q][64*ns]. The score of a kept point is fma(sum, scale, bias + leaf_ip)
+// (lut == NULL, 8-bit-table search) or, with fp32 tables, the fp32 table sum plus leaf_ip, formed for
+// the points whose 8-bit estimate is within margin[q] units of the R-th best estimate. Padding slots
+// (perm < 0) are dropped. Queries whose buffer overflowed go to fail_list.
+struct IvfRefineParams {
+    const u64 *kept;
+    const uint32_t *kept_cnt;
+    int32_t kept_cap, R, ns, nq, M, NB, leaf_stride;
+    const float *lut, *scale, *bias, *leaf_ip;
+    const int32_t *margin, *leaf_blk, *perm;
+    const uint8_t *codes; // logical [n][NB]
+    u64 *out;
+    int32_t *fail_list;
+    uint32_t *fail_count;
+    int32_t force_fail_odd;
+};
+int launch_ivf_refine(const IvfRefineParams &r, hipStream_t st);
 // dst[c] = src[row[c]] for c < *count (rows of row_floats floats); grid sized for max_rows
 int launch_gather_rows(const float *src, float *dst, const int32_t *row, const uint32_t *count, int max_rows,
                        int row_floats, hipStream_t st);
 
 // ---- ivf.hip ---------------------------------------------------------------
 // centers_t: [d][n_leaves] (transposed). Writes the L best leaves per query.
+// The (query, probed leaf) pairs of a batch regrouped by leaf, for the matrix-core scan (see
+// ScanParams::item_list). ws: group_by_leaf_words(...) 32-bit words of device scratch.
+struct LeafGroups {
+    uint32_t *leaf_cnt, *leaf_off, *item_off, *fill, *n_items, *qlist, *item_list;
+    int32_t max_items; // every 32 pairs of a leaf are an item: at most pairs / 32 + n_leaves of them
+};
+inline size_t group_by_leaf_max_items(int nq, int Lp, int n_leaves) { return ((size_t)nq * Lp + 31) / 32 + (size_t)n_leaves; }
+size_t group_by_leaf_words(int nq, int Lp, int n_leaves);
+int launch_group_by_leaf(const int32_t *leaf_ids, int nq, int Lp, int n_leaves, uint32_t *ws, LeafGroups *g, hipStream_t st);
 int launch_leaf_select(const float *centers_t, int n_leaves, int d, const float *queries, int nq,
                        int L, int32_t *leaf_ids, float *leaf_ip, hipStream_t st);
 int launch_transpose(const float *in, int rows, int cols, float *out, hipStream_t st);

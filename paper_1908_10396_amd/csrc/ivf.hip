@@ -79,6 +79,107 @@ int launch_leaf_select(const float *centers_t, int n_leaves, int d, const float 
     return AVQ_OK;
 }
 
+// ---- queries grouped by probed leaf ------------------------------------------------------
+//
+// The matrix-core scan shares a leaf's code stream among 32 queries, so the (query, probed
+// leaf) pairs of a batch (Section 5.3: every query scans a few leaves of the partition) are
+// regrouped by leaf: leaf_cnt[l] pairs probe leaf l, they are listed from qlist[leaf_off[l]]
+// on as query << 9 | slot (slot = position of the leaf in the query's probe list), and every
+// 32 of them are one work item, item_list[i] = leaf << 11 | tile. The order of a leaf's pairs
+// depends on the order of atomic operations; no result depends on it.
+
+__global__ void __launch_bounds__(256)
+group_count_kernel(const int32_t *__restrict__ leaf_ids, int64_t n_pairs, uint32_t *__restrict__ leaf_cnt)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_pairs) return;
+    const int32_t leaf = leaf_ids[i];
+    if (leaf >= 0) atomicAdd(&leaf_cnt[leaf], 1u);
+}
+
+// One workgroup: running sums of the pair counts and of the item counts; clears the fill cursors.
+__global__ void __launch_bounds__(1024)
+group_offsets_kernel(const uint32_t *__restrict__ leaf_cnt, int n_leaves, uint32_t *__restrict__ leaf_off,
+                     uint32_t *__restrict__ item_off, uint32_t *__restrict__ fill, uint32_t *__restrict__ n_items)
+{
+    __shared__ uint32_t part_p[1024], part_i[1024];
+    const int tid = threadIdx.x, nt = blockDim.x;
+    const int per = (n_leaves + nt - 1) / nt;
+    const int lo = tid * per, hi = lo + per < n_leaves ? lo + per : n_leaves;
+    uint32_t sp = 0u, si = 0u;
+    for (int l = lo; l < hi; ++l) { sp += leaf_cnt[l]; si += (leaf_cnt[l] + 31u) / 32u; }
+    part_p[tid] = sp;
+    part_i[tid] = si;
+    __syncthreads();
+    for (int d = 1; d < nt; d *= 2) { // inclusive scans
+        const uint32_t ap = tid >= d ? part_p[tid - d] : 0u, ai = tid >= d ? part_i[tid - d] : 0u;
+        __syncthreads();
+        part_p[tid] += ap;
+        part_i[tid] += ai;
+        __syncthreads();
+    }
+    uint32_t op = part_p[tid] - sp, oi = part_i[tid] - si; // exclusive
+    for (int l = lo; l < hi; ++l) {
+        leaf_off[l] = op;
+        item_off[l] = oi;
+        fill[l] = 0u;
+        op += leaf_cnt[l];
+        oi += (leaf_cnt[l] + 31u) / 32u;
+    }
+    if (tid == nt - 1) *n_items = part_i[tid];
+}
+
+__global__ void __launch_bounds__(256)
+group_fill_kernel(const int32_t *__restrict__ leaf_ids, int64_t n_pairs, int Lp, const uint32_t *__restrict__ leaf_off,
+                  uint32_t *__restrict__ fill, uint32_t *__restrict__ qlist)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_pairs) return;
+    const int32_t leaf = leaf_ids[i];
+    if (leaf < 0) return;
+    const uint32_t q = (uint32_t)(i / Lp), slot = (uint32_t)(i % Lp);
+    qlist[leaf_off[leaf] + atomicAdd(&fill[leaf], 1u)] = (q << 9) | slot;
+}
+
+__global__ void __launch_bounds__(256)
+group_items_kernel(const uint32_t *__restrict__ leaf_cnt, const uint32_t *__restrict__ item_off, int n_leaves,
+                   uint32_t *__restrict__ item_list)
+{
+    const int l = blockIdx.x * blockDim.x + threadIdx.x;
+    if (l >= n_leaves) return;
+    const uint32_t tiles = (leaf_cnt[l] + 31u) / 32u;
+    for (uint32_t t = 0; t < tiles; ++t) item_list[item_off[l] + t] = ((uint32_t)l << 11) | t;
+}
+
+size_t group_by_leaf_words(int nq, int Lp, int n_leaves)
+{
+    return (size_t)4 * n_leaves + 4 + (size_t)nq * Lp + group_by_leaf_max_items(nq, Lp, n_leaves);
+}
+
+int launch_group_by_leaf(const int32_t *leaf_ids, int nq, int Lp, int n_leaves, uint32_t *ws, LeafGroups *g, hipStream_t st)
+{
+    if (Lp > 512 || nq > (1 << 16) || n_leaves > (1 << 21)) { set_error("grouping by leaf: batch or partition too large"); return AVQ_EINVAL; }
+    g->leaf_cnt = ws;
+    g->leaf_off = g->leaf_cnt + n_leaves;
+    g->item_off = g->leaf_off + n_leaves;
+    g->fill = g->item_off + n_leaves;
+    g->n_items = g->fill + n_leaves;
+    g->qlist = g->n_items + 4;
+    g->item_list = g->qlist + (size_t)nq * Lp;
+    g->max_items = (int32_t)group_by_leaf_max_items(nq, Lp, n_leaves);
+    const int64_t n_pairs = (int64_t)nq * Lp;
+    AVQ_HIP(hipMemsetAsync(g->leaf_cnt, 0, sizeof(uint32_t) * (size_t)n_leaves, st));
+    hipLaunchKernelGGL(group_count_kernel, dim3((unsigned)((n_pairs + 255) / 256)), dim3(256), 0, st, leaf_ids, n_pairs, g->leaf_cnt);
+    hipLaunchKernelGGL(group_offsets_kernel, dim3(1), dim3(1024), 0, st, g->leaf_cnt, n_leaves, g->leaf_off, g->item_off, g->fill,
+                       g->n_items);
+    hipLaunchKernelGGL(group_fill_kernel, dim3((unsigned)((n_pairs + 255) / 256)), dim3(256), 0, st, leaf_ids, n_pairs, Lp, g->leaf_off,
+                       g->fill, g->qlist);
+    hipLaunchKernelGGL(group_items_kernel, dim3((n_leaves + 255) / 256), dim3(256), 0, st, g->leaf_cnt, g->item_off, n_leaves,
+                       g->item_list);
+    AVQ_HIP(hipGetLastError());
+    return AVQ_OK;
+}
+
 __global__ void transpose_kernel(const float *__restrict__ in, int rows, int cols,
                                  float *__restrict__ out)
 {

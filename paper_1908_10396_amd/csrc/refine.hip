@@ -250,6 +250,179 @@ int launch_refine_cand(const RefineCandParams &r, hipStream_t st)
     return AVQ_OK;
 }
 
+// ---- partitioned index ------------------------------------------------------------------------
+//
+// With leaves (Section 5.3) a point's score is its table sum plus <q, center of its leaf>, so the
+// integer sums of different leaves do not compare; the estimate a = fma(sum, scale, bias + leaf_ip)
+// does. The scan kept every point whose estimate could reach a bound known to be at or below the
+// R-th best score (the R-th best of the query's first few leaves, scanned with the tables the search
+// asked for). Here: the estimates of the kept points, the R-th best of them by bisection over the
+// ordering values, and then either the R best estimates themselves (8-bit tables: the estimate is the
+// score) or, for fp32 tables, the fp32 scores of the points within margin * scale of it (the estimate
+// is within half of that of the fp32 score, by the argument at the top of this file).
+
+constexpr int kIvfKeysPerThread = 16; // 4096 kept keys per query at most
+
+template <int NBT>
+__global__ void __launch_bounds__(256)
+ivf_refine_kernel(const IvfRefineParams r)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x;
+    constexpr int nt = 256;
+    const int q = blockIdx.x;
+    const int C = 64 * r.ns;
+    const int n_tab = 2 * r.NB;
+    const bool rescore = r.lut != nullptr;
+    float *tbl = (float *)smem;                                               // [n_tab][16] (fp32 tables only)
+    u64 *keys = (u64 *)(smem + (((size_t)n_tab * 64 + 15) & ~(size_t)15));    // [kFinalMax]
+    int32_t *fin_ids = (int32_t *)(keys + kFinalMax);                         // [kFinalMax]
+    float *fin_ip = (float *)(fin_ids + kFinalMax);                           // [kFinalMax]
+    __shared__ int cnt_s, n_fin_s;
+
+    if (rescore) {
+        const float *L = r.lut + (size_t)q * r.M * 16;
+        for (int e = tid; e < n_tab * 16; e += nt) tbl[e] = e < r.M * 16 ? L[e] : 0.0f;
+    }
+    if (tid == 0) { cnt_s = 0; n_fin_s = 0; }
+    __syncthreads();
+    const uint32_t total = r.kept_cnt[q];
+    const int margin = rescore ? r.margin[q] : 0;
+    bool ok = total <= (uint32_t)r.kept_cap && total <= (uint32_t)(nt * kIvfKeysPerThread) && margin >= 0;
+    int why = margin >= 0 ? 1 : 3;
+    if (r.force_fail_odd && (q & 1)) { ok = false; why = 3; }
+    const float scale = r.scale[q], bias = r.bias[q];
+    uint32_t est[kIvfKeysPerThread]; // ordering value of the estimate, 0: no point
+    int32_t ids[kIvfKeysPerThread];
+    float ips[kIvfKeysPerThread];
+    if (ok) {
+#pragma unroll
+        for (int k = 0; k < kIvfKeysPerThread; ++k) {
+            const uint32_t i = (uint32_t)(tid + k * nt);
+            est[k] = 0u;
+            ids[k] = -1;
+            ips[k] = 0.0f;
+            if (i < total) {
+                const u64 e = r.kept[(size_t)q * r.kept_cap + i];
+                const uint32_t hi = (uint32_t)(e >> 32), k32 = (uint32_t)e;
+                const int leaf = (int)(hi & 0x1fffffu), slot = (int)(hi >> 21);
+                const int32_t id = r.perm[(size_t)r.leaf_blk[leaf] * kBlockPoints + (~k32 & 0x3ffffu)];
+                if (id >= 0) {
+                    const float ip = r.leaf_ip[(size_t)q * r.leaf_stride + slot];
+                    const int sum = (int)(k32 >> 18) - 1;
+                    ids[k] = id;
+                    ips[k] = ip;
+                    est[k] = ord_from_f32(__fmaf_rn((float)sum, scale, __fadd_rn(bias, ip)));
+                }
+            }
+        }
+    }
+    uint32_t keep = 0u;
+    if (ok) {
+        auto count_ge = [&](uint32_t v) -> int {
+            int cn = 0;
+#pragma unroll
+            for (int k = 0; k < kIvfKeysPerThread; ++k) cn += est[k] >= v && est[k] != 0u;
+            for (int m = 32; m > 0; m >>= 1) cn += __shfl_xor(cn, m, 64);
+            __syncthreads();
+            if (tid == 0) cnt_s = 0;
+            __syncthreads();
+            if ((tid & 63) == 0 && cn) atomicAdd(&cnt_s, cn);
+            __syncthreads();
+            return cnt_s;
+        };
+        if (count_ge(1u) >= r.R) {
+            // ordering value of the R-th best estimate: the largest v with at least R estimates >= v
+            uint32_t lo = 1u, hi = 0xffffffffu; // count_ge(lo) >= R; count_ge(hi) < R (no finite score maps to it)
+            while (hi - lo > 1u) {
+                const uint32_t mid = lo + ((hi - lo) >> 1);
+                if (count_ge(mid) >= r.R) lo = mid; else hi = mid;
+            }
+            keep = lo;
+            if (rescore) {
+                // estimates within margin units of scale below it, with a little room for the rounding here
+                const float a_r = f32_from_ord(lo);
+                const float t = a_r - ((float)margin * scale + 4.0e-6f * fabsf(a_r));
+                keep = ord_from_f32(t);
+            }
+        } // fewer than R points were kept: they are all there is (keep = 0)
+#pragma unroll
+        for (int k = 0; k < kIvfKeysPerThread; ++k) {
+            if (est[k] != 0u && est[k] >= keep) {
+                const int slot = atomicAdd(&n_fin_s, 1);
+                if (slot < kFinalMax) {
+                    fin_ids[slot] = ids[k];
+                    fin_ip[slot] = ips[k];
+                    if (!rescore) keys[slot] = make_key(est[k], ids[k]);
+                }
+            }
+        }
+        __syncthreads();
+        ok = n_fin_s <= kFinalMax;
+    }
+    if (!ok) {
+        if (tid == 0) {
+            r.fail_list[atomicAdd(r.fail_count, 1u)] = q;
+            atomicAdd(r.fail_count + why, 1u);
+        }
+        return;
+    }
+    const int n_cand = n_fin_s;
+    for (int i = tid; rescore && i < n_cand; i += nt) {
+        const int32_t id = fin_ids[i];
+        const uint8_t *row = r.codes + (size_t)id * r.NB;
+        float s = 0.0f;
+        if constexpr (NBT != 0) {
+            uint32_t bytes[NBT];
+#pragma unroll
+            for (int b = 0; b < NBT; ++b) bytes[b] = row[b];
+#pragma unroll
+            for (int b = 0; b < NBT; ++b) {
+                const float v = __fadd_rn(tbl[(2 * b) * 16 + (bytes[b] & 15u)], tbl[(2 * b + 1) * 16 + (bytes[b] >> 4)]);
+                s = __fadd_rn(s, v);
+            }
+        } else {
+            for (int b = 0; b < r.NB; ++b) {
+                const uint32_t byte = row[b];
+                const float v = __fadd_rn(tbl[(2 * b) * 16 + (byte & 15u)], tbl[(2 * b + 1) * 16 + (byte >> 4)]);
+                s = __fadd_rn(s, v);
+            }
+        }
+        keys[i] = make_key(ord_from_f32(__fadd_rn(s, fin_ip[i])), id);
+    }
+    __syncthreads();
+    u64 *out = r.out + (size_t)q * C;
+    for (int j0 = 0; j0 < n_cand; j0 += nt / 4) {
+        const int j = j0 + (tid >> 2);
+        const u64 k = j < n_cand ? keys[j] : ~0ull;
+        int rank = 0;
+        for (int t = tid & 3; t < n_cand; t += 4) rank += keys[t] > k;
+        rank += __shfl_xor(rank, 1, 64);
+        rank += __shfl_xor(rank, 2, 64);
+        if (j < n_cand && (tid & 3) == 0 && rank < r.R) out[rank] = k;
+    }
+    const int n_fin = n_cand < r.R ? n_cand : r.R;
+    for (int i = n_fin + tid; i < C; i += nt) out[i] = 0ull;
+}
+
+int launch_ivf_refine(const IvfRefineParams &r, hipStream_t st)
+{
+    if (r.M > 64 || r.R > 64 * r.ns || r.kept_cap < 1 || r.kept_cap > 256 * kIvfKeysPerThread || (r.lut != nullptr && r.margin == nullptr)) {
+        set_error("refine (leaves): bad shape (M %d, R %d, capacity %d)", r.M, r.R, r.kept_cap);
+        return AVQ_EINVAL;
+    }
+    const size_t lds = (((size_t)2 * r.NB * 64 + 15) & ~(size_t)15) + (sizeof(u64) + sizeof(int32_t) + sizeof(float)) * (size_t)kFinalMax;
+    switch (r.NB) {
+    case 8: hipLaunchKernelGGL(ivf_refine_kernel<8>, dim3(r.nq), dim3(256), lds, st, r); break;
+    case 13: hipLaunchKernelGGL(ivf_refine_kernel<13>, dim3(r.nq), dim3(256), lds, st, r); break;
+    case 25: hipLaunchKernelGGL(ivf_refine_kernel<25>, dim3(r.nq), dim3(256), lds, st, r); break;
+    case 32: hipLaunchKernelGGL(ivf_refine_kernel<32>, dim3(r.nq), dim3(256), lds, st, r); break;
+    default: hipLaunchKernelGGL(ivf_refine_kernel<0>, dim3(r.nq), dim3(256), lds, st, r); break;
+    }
+    AVQ_HIP(hipGetLastError());
+    return AVQ_OK;
+}
+
 __global__ void __launch_bounds__(256)
 gather_rows_kernel(const float *__restrict__ src, float *__restrict__ dst, const int32_t *__restrict__ row,
                    const uint32_t *__restrict__ count, int row_floats)

@@ -260,8 +260,12 @@ adc_scan_kernel(const ScanParams p)
         tile = blockIdx.x % tiles;
         chunk = blockIdx.x / tiles;
         blocks_per_chunk = (int)((p.n_blocks + n_chunks - 1) / n_chunks);
-    } else if (MODE == MODE_CHUNK || MODE == MODE_LEAVES) { tile = blockIdx.x % p.n_tiles; chunk = blockIdx.x / p.n_tiles; }
-    else { tile = blockIdx.x; chunk = 0; }
+    } else if (MODE == MODE_CHUNK || MODE == MODE_LEAVES) {
+        tile = blockIdx.x % p.n_tiles;
+        chunk = blockIdx.x / p.n_tiles;
+        // partitioned index, compacted query list: only the first *active_queries rows are live
+        if (MODE == MODE_LEAVES && p.active_queries != nullptr && (uint32_t)tile >= *p.active_queries) return;
+    } else { tile = blockIdx.x; chunk = 0; }
     const int q0 = tile * QT;
 
     entry_t *tbl = (entry_t *)smem;
@@ -421,10 +425,11 @@ adc_scan_kernel(const ScanParams p)
         scan_range(first + wave, end, n_waves, 0.0f);
     } else if (MODE == MODE_LEAVES) {
         // the query's probed leaves, dealt to the waves of its n_chunks workgroups in turn
+        const int leaf_stride = p.leaf_stride ? p.leaf_stride : p.Lp; // a scan of the first Lp leaves of longer rows
         for (int j = chunk * n_waves + wave; j < p.Lp; j += p.n_chunks * n_waves) {
-            const int leaf = p.leaf_ids[(size_t)q0 * p.Lp + j];
+            const int leaf = p.leaf_ids[(size_t)q0 * leaf_stride + j];
             if (leaf < 0) continue;
-            scan_range(p.leaf_blk[leaf], p.leaf_blk[leaf + 1], 1, p.leaf_ip[(size_t)q0 * p.Lp + j]);
+            scan_range(p.leaf_blk[leaf], p.leaf_blk[leaf + 1], 1, p.leaf_ip[(size_t)q0 * leaf_stride + j]);
         }
     } else {
         // the R blocks with the largest block maxima, as keys whose id lies in the block

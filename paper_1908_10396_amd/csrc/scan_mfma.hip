@@ -191,6 +191,24 @@ __device__ __noinline__ int mfma_dump_query(const lds_u32 *pend_a, const lds_u32
     return cand_pos + cnt_a + cnt_b;
 }
 
+// The same for a partitioned index, where many waves (one per leaf) keep points of the same query:
+// room in the query's buffer is taken with one atomic add per flush; `hi` (leaf and its slot in the
+// query's probe list) goes into the upper half of every entry. A count beyond the capacity tells
+// the reader that keys were dropped.
+__device__ __noinline__ void mfma_dump_item(const lds_u32 *pend_a, const lds_u32 *pend_b, int cnt_a, int cnt_b, u64 *dst,
+                                            uint32_t *count, int cap, uint32_t hi)
+{
+    const int lane = lane_id();
+    uint32_t base = 0u;
+    if (lane == 0) base = atomicAdd(count, (uint32_t)(cnt_a + cnt_b));
+    base = (uint32_t)__builtin_amdgcn_readfirstlane((int)base);
+    if (base + (uint32_t)(cnt_a + cnt_b) <= (uint32_t)cap) {
+        if (lane < cnt_a) dst[base + lane] = ((u64)hi << 32) | pend_a[lane];
+        if (lane < cnt_b) dst[base + cnt_a + lane] = ((u64)hi << 32) | pend_b[lane];
+    }
+    wave_lds_fence();
+}
+
 // STORE: inspection mode, every score is written to scores_out and nothing is selected.
 template <int NBT, bool STORE>
 __global__ void __launch_bounds__(kMfmaWaves * 64, 2)
@@ -204,12 +222,35 @@ adc_mfma_scan_kernel(const ScanParams p)
         onehot[threadIdx.x] = (dw == (c >> 2)) ? (1u << (8 * (c & 3))) : 0u;
     }
     __syncthreads();
-    const int64_t gw = (int64_t)blockIdx.x * kMfmaWaves + wave; // wave index over (chunk, tile)
-    if (gw >= (int64_t)p.n_tiles * p.n_chunks) return;
-    const int tile = (int)(gw % p.n_tiles), chunk = (int)(gw / p.n_tiles);
+    const int64_t gw = (int64_t)blockIdx.x * kMfmaWaves + wave; // wave index over (chunk, tile), or over the items
     const int j = lane & 31, h = lane >> 5;
-    const int q = tile * kMfmaQueries + j;
-    const bool live = q < p.B;
+    const bool items = p.item_list != nullptr;
+    int tile = 0, chunk = 0, q = 0;
+    bool live = false;
+    int64_t first = 0, end = 0;
+    uint32_t item_hi = 0u; // items: leaf slot << 21 | leaf of this lane's query
+    if (items) {
+        if (gw >= (int64_t)*p.n_items) return;
+        const uint32_t it = p.item_list[gw];
+        const int leaf = (int)(it >> 11), t = (int)(it & 2047u);
+        const int at = t * kMfmaQueries + j;
+        live = (uint32_t)at < p.leaf_cnt[leaf];
+        const uint32_t entry = live ? p.qlist[p.leaf_off[leaf] + at] : 0u;
+        q = (int)(entry >> 9);
+        item_hi = ((entry & 511u) << 21) | (uint32_t)leaf;
+        first = p.leaf_blk[leaf];
+        end = p.leaf_blk[leaf + 1];
+    } else {
+        if (gw >= (int64_t)p.n_tiles * p.n_chunks) return;
+        tile = (int)(gw % p.n_tiles);
+        chunk = (int)(gw / p.n_tiles);
+        q = tile * kMfmaQueries + j;
+        live = q < p.B;
+        // the chunk's blocks
+        first = (int64_t)chunk * p.blocks_per_chunk;
+        end = first + p.blocks_per_chunk;
+        if (end > p.n_blocks) end = p.n_blocks;
+    }
     const int C = 64 * p.ns;
     const int off = 128 * p.M;
     constexpr bool store = STORE;
@@ -231,7 +272,7 @@ adc_mfma_scan_kernel(const ScanParams p)
     lds_u32 *pend = pend0; // next free slot of this lane's pending buffer
     // fixed_bound: the bounds in thr_shared are taken as they are and never raised: every point at
     // or above them (less the margin) goes to the candidate buffer, and no lists are kept
-    const bool fixed = !store && p.fixed_bound != 0;
+    const bool fixed = !store && (p.fixed_bound != 0 || items);
     if (!store && !fixed) {
         my_lists = (uint32_t *)p.lists_ws + (size_t)gw * kMfmaQueries * C;
         for (int i = lane; i < kMfmaQueries * C; i += 64) my_lists[i] = 0u;
@@ -248,20 +289,39 @@ adc_mfma_scan_kernel(const ScanParams p)
     // too and is kept (see mfma_flush_query); the lists and bounds work as usual.
     const bool cand_mode = p.cand_keys != nullptr;
     int marg = 0;
-    if (cand_mode && live && p.cand_margin != nullptr) { marg = p.cand_margin[q]; marg = marg > 0 ? marg : 0; }
+    if ((cand_mode || items) && live && p.cand_margin != nullptr) { marg = p.cand_margin[q]; marg = marg > 0 ? marg : 0; }
     int cpos = 0; // lanes 0-31: keys of this lane's query in its candidate buffer so far
     auto thr_of = [&]() -> int { return live ? (int)bound_ord - off - 2 - marg : 0x7fffffff; };
     // a bound may already be there: that of an earlier launch over a sample of the same points (bounds_only)
-    if (!store && live) bound_ord = __hip_atomic_load(p.thr_shared + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (!store && !items && live) bound_ord = __hip_atomic_load(p.thr_shared + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     int thr = thr_of();
+    if (items && live) {
+        // fma(sum, scale, off_q) >= bound can only hold from sum = floor((bound - off_q) / scale) - 2 on (two
+        // units for the rounding of this estimate); no bound, or tables without a range: everything is kept
+        const uint32_t bound_o = p.item_bound[q]; // ordering value of the fp32 bound, 0: none
+        const float sc = p.scale[q], bound = bound_o ? f32_from_ord(bound_o) : -INFINITY;
+        const float off_q = __fadd_rn(p.bias[q], p.leaf_ip[(size_t)q * (p.leaf_stride ? p.leaf_stride : p.Lp) + (item_hi >> 21)]);
+        thr = -0x7fffffff;
+        if (sc > 0.0f && bound > -INFINITY) {
+            float a_f = floorf((bound - off_q) / sc);
+            a_f = fminf(fmaxf(a_f, -1.0e9f), 1.0e9f);
+            thr = (int)a_f - marg - 3 - off;
+        }
+    }
 
     // flushes query jq (lanes jq and jq + 32 hold its pending keys)
     auto flush_query = [&](int jq) {
-        const int qq = tile * kMfmaQueries + jq; // < B: only live lanes collect keys
+        const int qq = tile * kMfmaQueries + jq; // < B: only live lanes collect keys (not used with items)
         const int cnt = (int)(pend - pend0);
         const int cnt_a = __builtin_amdgcn_readlane(cnt, jq), cnt_b = __builtin_amdgcn_readlane(cnt, jq + 32);
         const lds_u32 *pa = (const lds_u32 *)dyn_smem + (wave * 64 + jq) * kMfmaPend;
         uint32_t *cand_dst = cand_mode ? p.cand_keys + ((size_t)qq * p.n_chunks + chunk) * p.cand_cap : nullptr;
+        if (items) {
+            mfma_dump_item(pa, pa + 32 * kMfmaPend, cnt_a, cnt_b, p.kept + (size_t)__builtin_amdgcn_readlane(q, jq) * p.kept_cap,
+                           p.kept_cnt + __builtin_amdgcn_readlane(q, jq), p.kept_cap, (uint32_t)__builtin_amdgcn_readlane((int)item_hi, jq));
+            if (j == jq) pend = pend0;
+            return;
+        }
         if (fixed) {
             const int np = mfma_dump_query(pa, pa + 32 * kMfmaPend, cnt_a, cnt_b, cand_dst, __builtin_amdgcn_readlane(cpos, jq),
                                            p.cand_cap);
@@ -280,10 +340,7 @@ adc_mfma_scan_kernel(const ScanParams p)
         }
     };
 
-    // the chunk's blocks; a sampling launch takes only every block_stride-th of them
-    const int64_t first = (int64_t)chunk * p.blocks_per_chunk;
-    int64_t end = first + p.blocks_per_chunk;
-    if (end > p.n_blocks) end = p.n_blocks;
+    // a sampling launch takes only every block_stride-th of its blocks
     const int64_t stride = p.block_stride > 1 ? p.block_stride : 1;
     const int64_t n_half = end > first ? 2 * ((end - first + stride - 1) / stride) : 0; // half blocks to visit
     const int32_t id_base = (int32_t)(first * kBlockPoints); // ids inside keys count from here
@@ -404,7 +461,7 @@ adc_mfma_scan_kernel(const ScanParams p)
     }
     wave_lds_fence();
     if (p.bounds_only) return; // the flushes above have published this wave's bounds; its lists are not wanted
-    if (cand_mode && live && h == 0) p.cand_cnt[(size_t)q * p.n_chunks + chunk] = (uint32_t)cpos;
+    if (cand_mode && !items && live && h == 0) p.cand_cnt[(size_t)q * p.n_chunks + chunk] = (uint32_t)cpos;
     if (fixed) return;
     for (int jq = 0; jq < kMfmaQueries; ++jq) {
         const int qq = tile * kMfmaQueries + jq;
@@ -481,7 +538,7 @@ static int launch_mfma_one(const ScanParams &p, hipStream_t st)
         AVQ_HIP(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynLds));
         attr_done = true;
     }
-    const int64_t waves = (int64_t)p.n_tiles * p.n_chunks;
+    const int64_t waves = p.item_list ? (int64_t)p.max_items : (int64_t)p.n_tiles * p.n_chunks;
     const int64_t grid = (waves + kMfmaWaves - 1) / kMfmaWaves;
     if (grid > 0x7fffffff) { set_error("scan: grid too large"); return AVQ_EINVAL; }
     const size_t lds = (size_t)kMfmaWaves * 64 * kMfmaPend * sizeof(uint32_t);
@@ -493,6 +550,19 @@ static int launch_mfma_one(const ScanParams &p, hipStream_t st)
 int launch_scan_mfma(const ScanParams &p, hipStream_t st)
 {
     if (!scan_mfma_supported(p.NB, p.bits)) { set_error("scan: no matrix-core kernel for this code size"); return AVQ_EINVAL; }
+    if (p.item_list != nullptr) {
+        if (!p.n_items || !p.qlist || !p.leaf_off || !p.leaf_cnt || !p.leaf_blk || !p.leaf_ip || !p.item_bound || !p.kept ||
+            !p.kept_cnt || p.kept_cap < 128 || p.max_items < 1 || !p.scale || !p.bias || p.scores_out || p.M > 64) {
+            set_error("scan: the matrix-core kernel over leaves needs its lists, bounds and buffers");
+            return AVQ_EINVAL;
+        }
+        switch (p.NB) {
+        case 8: return launch_mfma_one<8, false>(p, st);
+        case 13: return launch_mfma_one<13, false>(p, st);
+        case 25: return launch_mfma_one<25, false>(p, st);
+        default: return launch_mfma_one<32, false>(p, st);
+        }
+    }
     if (p.fixed_bound && (p.cand_keys == nullptr || p.thr_shared == nullptr)) {
         set_error("scan: a fixed-bound scan needs bounds and candidate buffers");
         return AVQ_EINVAL;

@@ -16,7 +16,7 @@ merge_partials_kernel(const u64 *__restrict__ partial, int n_chunks, int ns, u64
 {
     if (active != nullptr) {
         if (blockIdx.x >= *active) return;
-        n_chunks = scan_dynamic_chunks(((int)*active + tile_queries - 1) / tile_queries, n_chunks);
+        if (tile_queries > 0) n_chunks = scan_dynamic_chunks(((int)*active + tile_queries - 1) / tile_queries, n_chunks);
     }
     extern __shared__ __align__(16) unsigned char smem[];
     const int C = 64 * ns;

@@ -465,6 +465,37 @@ def test_partitioned_search_matches(ivf_case, lut_mode, k, R, L):
     np.testing.assert_array_equal(sc.cpu().numpy(), os_)
 
 
+@pytest.fixture(scope="module")
+def ivf_batch_case():
+    # enough queries and probed leaves for the search that regroups the (query, leaf) pairs by leaf
+    return make_ivf_case(33, 40_007, 32, 16, 4, 130, 150)
+
+
+@pytest.mark.parametrize("lut_mode", [0, 1])
+@pytest.mark.parametrize("variant", ["default", "plain", "odd_back", "small_buffers"])
+def test_partitioned_batches_grouped_by_leaf(ivf_batch_case, lut_mode, variant):
+    # batches of 64 queries or more probing 16 leaves or more: leaves scanned on the matrix cores, 32
+    # queries at a time, kept points scored per query; "plain": the one-query-per-workgroup scan;
+    # "odd_back" / "small_buffers": every other query, or most of them, handed back to that scan
+    c = ivf_batch_case
+    idx, xd = make_ivf_index(c)
+    if variant == "plain":
+        idx.set_tuning("scan_prefilter", 1)
+    elif variant == "odd_back":
+        idx.set_tuning("scan_prefilter", 2)
+    elif variant == "small_buffers":
+        idx.set_tuning("prefilter_cap", 128)
+    qd = dev(c["q"])
+    for k, R, L in ((10, 100, 40), (10, 0, 16), (5, 300, 150), (100, 0, 25)):
+        ids, sc = idx.search(qd, k, R, lut_mode, leaves_to_search=L)
+        oi, os_ = oracle.search(c["x"], c["cb"], c["codes"], c["bits"], c["q"], k, R, lut_mode,
+                                centers=c["centers"], assign=c["assign"], leaves_to_search=L)
+        np.testing.assert_array_equal(ids.cpu().numpy(), oi, err_msg="k=%d R=%d L=%d" % (k, R, L))
+        np.testing.assert_array_equal(sc.cpu().numpy(), os_, err_msg="k=%d R=%d L=%d" % (k, R, L))
+    if variant == "odd_back":
+        assert idx.debug_unverified_queries() >= 65
+
+
 def test_partitioned_search_pads_when_leaves_are_small():
     # more results asked for than the probed leaves hold: padded with id -1, score -inf
     c = make_ivf_case(32, 400, 16, 8, 4, 7, 40)
