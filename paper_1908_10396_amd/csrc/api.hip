@@ -62,6 +62,7 @@ struct avq_index {
     int tune_mfma = 0; // 0 = use the matrix-core scan where it applies, 1 = never
     int tune_prefilter = 0; // 0 = fp32-table batches go through the 8-bit-table scan where it applies, 1 = never,
                             // 2 = as 0 but odd queries always take the plain scan afterwards (exercises that branch)
+    int tune_bound_leaves = 0; // leaves per query that supply the bound of the grouped scan over leaves, 0 = built-in
     int tune_sample = 0; // 0 = fp32-table batches guess the candidate scan's bounds from a sample where possible, 1 = never
     int tune_prefilter_cap = 0; // candidate keys per (query, chunk) of that scan, 0 = built-in
     DevBuf block_max, lists, refined, lut_fail, fail, cand_keys, groups, kept, fail_rows;
@@ -178,6 +179,7 @@ extern "C" int avq_set_tuning(avq_index *idx, const char *name, int32_t value)
     else if (!strcmp(name, "scan_prefilter")) idx->tune_prefilter = value;
     else if (!strcmp(name, "prefilter_cap")) idx->tune_prefilter_cap = value;
     else if (!strcmp(name, "scan_sample")) idx->tune_sample = value;
+    else if (!strcmp(name, "bound_leaves")) idx->tune_bound_leaves = value;
     else { set_error("avq_set_tuning: unknown name '%s'", name); return AVQ_EINVAL; }
     return AVQ_OK;
 }
@@ -716,7 +718,7 @@ static int search_leaves_grouped(avq_index *idx, const float *queries, int nq, i
         AVQ_TRY(idx->lists.reserve(sizeof(u64) * (size_t)nq * shape.waves * shape.qt * C));
         pl.lists_ws = idx->lists.as<u64>();
     }
-    const int bound_leaves = std::min(L, std::max(8, (L + 11) / 12));
+    const int bound_leaves = idx->tune_bound_leaves > 0 ? std::min(L, idx->tune_bound_leaves) : std::min(L, std::max(8, (L + 11) / 12));
     LeafGroups g;
     {
         StageTimer t(idx, AVQ_STAGE_SCAN, st);

@@ -192,19 +192,22 @@ __device__ __noinline__ int mfma_dump_query(const lds_u32 *pend_a, const lds_u32
 }
 
 // The same for a partitioned index, where many waves (one per leaf) keep points of the same query:
-// room in the query's buffer is taken with one atomic add per flush; `hi` (leaf and its slot in the
-// query's probe list) goes into the upper half of every entry. A count beyond the capacity tells
-// the reader that keys were dropped.
-__device__ __noinline__ void mfma_dump_item(const lds_u32 *pend_a, const lds_u32 *pend_b, int cnt_a, int cnt_b, u64 *dst,
-                                            uint32_t *count, int cap, uint32_t hi)
+// all 32 queries of the wave are flushed together. Lane j takes room for its own and lane j + 32's
+// pending keys in query q's buffer with one atomic add (32 of them in flight at once, not one
+// round trip per query), then every lane copies its keys; `hi` (leaf and its slot in the query's
+// probe list) goes into the upper half of every entry. A count beyond the capacity tells the
+// reader that keys were dropped. cnt: this lane's pending keys, at pend0.
+__device__ __noinline__ void mfma_dump_items(const lds_u32 *pend0, int cnt, int q, uint32_t hi, u64 *kept, uint32_t *kept_cnt, int cap)
 {
     const int lane = lane_id();
+    const int other = __shfl_xor(cnt, 32, 64);
+    const int total = cnt + other;
     uint32_t base = 0u;
-    if (lane == 0) base = atomicAdd(count, (uint32_t)(cnt_a + cnt_b));
-    base = (uint32_t)__builtin_amdgcn_readfirstlane((int)base);
-    if (base + (uint32_t)(cnt_a + cnt_b) <= (uint32_t)cap) {
-        if (lane < cnt_a) dst[base + lane] = ((u64)hi << 32) | pend_a[lane];
-        if (lane < cnt_b) dst[base + cnt_a + lane] = ((u64)hi << 32) | pend_b[lane];
+    if (lane < 32 && total > 0) base = atomicAdd(kept_cnt + q, (uint32_t)total);
+    base = (uint32_t)__shfl((int)base, lane & 31, 64);
+    if (base + (uint32_t)total <= (uint32_t)cap) {
+        u64 *dst = kept + (size_t)q * cap + base + (lane >= 32 ? (uint32_t)other : 0u);
+        for (int i = 0; i < cnt; ++i) dst[i] = ((u64)hi << 32) | pend0[i];
     }
     wave_lds_fence();
 }
@@ -316,12 +319,6 @@ adc_mfma_scan_kernel(const ScanParams p)
         const int cnt_a = __builtin_amdgcn_readlane(cnt, jq), cnt_b = __builtin_amdgcn_readlane(cnt, jq + 32);
         const lds_u32 *pa = (const lds_u32 *)dyn_smem + (wave * 64 + jq) * kMfmaPend;
         uint32_t *cand_dst = cand_mode ? p.cand_keys + ((size_t)qq * p.n_chunks + chunk) * p.cand_cap : nullptr;
-        if (items) {
-            mfma_dump_item(pa, pa + 32 * kMfmaPend, cnt_a, cnt_b, p.kept + (size_t)__builtin_amdgcn_readlane(q, jq) * p.kept_cap,
-                           p.kept_cnt + __builtin_amdgcn_readlane(q, jq), p.kept_cap, (uint32_t)__builtin_amdgcn_readlane((int)item_hi, jq));
-            if (j == jq) pend = pend0;
-            return;
-        }
         if (fixed) {
             const int np = mfma_dump_query(pa, pa + 32 * kMfmaPend, cnt_a, cnt_b, cand_dst, __builtin_amdgcn_readlane(cpos, jq),
                                            p.cand_cap);
@@ -437,6 +434,11 @@ adc_mfma_scan_kernel(const ScanParams p)
                     }
                     // a chain adds at most 16 keys to a lane: flush the queries with less room than that
                     u64 need = __builtin_amdgcn_ballot_w64(pend_end - pend < 16);
+                    if (items && __builtin_expect(need != 0ull, 0)) { // every query of the wave at once
+                        mfma_dump_items(pend0, (int)(pend - pend0), q, item_hi, p.kept, p.kept_cnt, p.kept_cap);
+                        pend = pend0;
+                        need = 0ull;
+                    }
                     while (__builtin_expect(need != 0ull, 0)) {
                         const int jq = (int)(__builtin_ctzll(need) & 31);
                         flush_query(jq);
@@ -453,6 +455,11 @@ adc_mfma_scan_kernel(const ScanParams p)
     // drain, then hand the lists over: partial[q][chunk][C]
     {
         u64 rest = __builtin_amdgcn_ballot_w64(pend != pend0);
+        if (items && rest) {
+            mfma_dump_items(pend0, (int)(pend - pend0), q, item_hi, p.kept, p.kept_cnt, p.kept_cap);
+            pend = pend0;
+            rest = 0ull;
+        }
         while (rest) {
             const int jq = (int)(__builtin_ctzll(rest) & 31);
             flush_query(jq);

@@ -471,6 +471,20 @@ def ivf_batch_case():
     return make_ivf_case(33, 40_007, 32, 16, 4, 130, 150)
 
 
+def test_leaf_select_for_batches_matches(ivf_batch_case):
+    # a batch, every fifth query checked
+    c = ivf_batch_case
+    idx, _ = make_ivf_index(c)
+    qd = dev(c["q"])
+    for L in (1, 16, 100, 150):
+        ids, ip = idx.debug_leaf_select(qd, L)
+        ids, ip = ids.cpu().numpy(), ip.cpu().numpy()
+        for qi in range(0, c["q"].shape[0], 7):
+            oi, oip = oracle.leaf_select(c["centers"], c["q"][qi], L)
+            np.testing.assert_array_equal(ids[qi], oi)
+            np.testing.assert_array_equal(ip[qi], oip)
+
+
 @pytest.mark.parametrize("lut_mode", [0, 1])
 @pytest.mark.parametrize("variant", ["default", "plain", "odd_back", "small_buffers"])
 def test_partitioned_batches_grouped_by_leaf(ivf_batch_case, lut_mode, variant):
