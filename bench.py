@@ -228,7 +228,20 @@ def main():
     sampled = bpc >= 256
     launches = 2 if sampled else 1
     ops_step = mfma_ops * (1.0 + (16.0 / bpc if sampled else 0.0))
-    if prefiltered:
+    grouped = bool(n_leaves) and bits == 4 and B >= 64 and nb in (8, 13, 25, 32) and M <= 64 and 16 <= Lp <= 512
+    if grouped:
+        # partitioned index: the (query, leaf) pairs regrouped by leaf, leaves scanned on the matrix cores;
+        # the scan stage also holds the bounds pass over every query's best leaves and the regrouping
+        unverified = idx.debug_unverified_queries(reasons=True)
+        ops = 2.0 * scanned * B * nb * 32
+        batch_roof = {"bound": "mfma", "achieved": ops / (scan_ms * 1e-3) / 1e12, "peak": MFMA_I8_PEAK_TOPS, "unit": "TOP/s",
+                      "traffic": None, "kernel": "adc_mfma_scan_kernel<%d,false>" % nb, "avg_launch_ms": scan_ms,
+                      "note": "int8 multiply-adds of the scan over leaves (32 queries per leaf and work item); the stage "
+                              "time also covers the bounds pass (adc_scan_kernel<1,...,1> over each query's best leaves) "
+                              "and the regrouping of the (query, leaf) pairs",
+                      "queries_scanned_again": unverified[0]}
+        batch_roof["frac"] = batch_roof["achieved"] / batch_roof["peak"]
+    elif prefiltered:
         unverified = idx.debug_unverified_queries(reasons=True)
         batch_roof = {"bound": "mfma", "achieved": ops_step / (scan_ms * 1e-3) / 1e12, "peak": MFMA_I8_PEAK_TOPS,
                       "unit": "TOP/s", "traffic": None, "kernel": "adc_mfma_scan_kernel<%d,false>" % nb,

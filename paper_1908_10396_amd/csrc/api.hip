@@ -681,10 +681,13 @@ static int search_leaves_grouped(avq_index *idx, const float *queries, int nq, i
     const int C = 64 * ns;
     AVQ_TRY(idx->leaf_ids.reserve(sizeof(int32_t) * (size_t)nq * L));
     AVQ_TRY(idx->leaf_ip.reserve(sizeof(float) * (size_t)nq * L));
+    AVQ_TRY(idx->groups.reserve(sizeof(uint32_t) * group_by_leaf_words(nq, L, c.n_leaves)));
+    LeafGroups g;
     {
         StageTimer t(idx, AVQ_STAGE_LEAF, st);
+        AVQ_TRY(group_by_leaf_prepare(nq, L, c.n_leaves, idx->groups.as<uint32_t>(), &g, st));
         AVQ_TRY(launch_leaf_select(idx->centers_t.as<float>(), c.n_leaves, c.d, queries, nq, L,
-                                   idx->leaf_ids.as<int32_t>(), idx->leaf_ip.as<float>(), st));
+                                   idx->leaf_ids.as<int32_t>(), idx->leaf_ip.as<float>(), st, g.leaf_cnt));
     }
     // scratch: [4] counts | [nq] unverified queries | [nq] margins | [nq] bounds | [nq] kept counts
     AVQ_TRY(idx->fail.reserve(sizeof(int32_t) * (4 + (size_t)4 * nq)));
@@ -695,7 +698,6 @@ static int search_leaves_grouped(avq_index *idx, const float *queries, int nq, i
     uint32_t *kept_cnt = bound + nq;
     const int kept_cap = idx->tune_prefilter_cap > 0 ? std::min(4096, std::max(128, idx->tune_prefilter_cap)) : 2048;
     AVQ_TRY(idx->kept.reserve(sizeof(u64) * (size_t)nq * kept_cap));
-    AVQ_TRY(idx->groups.reserve(sizeof(uint32_t) * group_by_leaf_words(nq, L, c.n_leaves)));
     AVQ_TRY(idx->cand.reserve(sizeof(u64) * (size_t)nq * C));
     AVQ_TRY(idx->refined.reserve(sizeof(u64) * (size_t)nq * C));
 
@@ -719,7 +721,6 @@ static int search_leaves_grouped(avq_index *idx, const float *queries, int nq, i
         pl.lists_ws = idx->lists.as<u64>();
     }
     const int bound_leaves = idx->tune_bound_leaves > 0 ? std::min(L, idx->tune_bound_leaves) : std::min(L, std::max(8, (L + 11) / 12));
-    LeafGroups g;
     {
         StageTimer t(idx, AVQ_STAGE_SCAN, st);
         AVQ_HIP(hipMemsetAsync(fail_count, 0, 16, st));
@@ -730,7 +731,7 @@ static int search_leaves_grouped(avq_index *idx, const float *queries, int nq, i
         pb.leaf_stride = L;
         AVQ_TRY(launch_scan(pb, u8, SCAN_LEAVES, shape, st));
         AVQ_TRY(launch_list_bound(pb.partial, ns, R, nq, bound, st));
-        AVQ_TRY(launch_group_by_leaf(idx->leaf_ids.as<int32_t>(), nq, L, c.n_leaves, idx->groups.as<uint32_t>(), &g, st));
+        AVQ_TRY(launch_group_by_leaf(idx->leaf_ids.as<int32_t>(), nq, L, c.n_leaves, g, st));
         ScanParams pi;
         fill_scan_params(idx, nq, R, ns, &pi);
         pi.n_valid = 0x7fffffff; // padding slots are told from points by perm, afterwards

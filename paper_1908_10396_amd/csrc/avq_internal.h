@@ -252,9 +252,12 @@ struct LeafGroups {
 };
 inline size_t group_by_leaf_max_items(int nq, int Lp, int n_leaves) { return ((size_t)nq * Lp + 31) / 32 + (size_t)n_leaves; }
 size_t group_by_leaf_words(int nq, int Lp, int n_leaves);
-int launch_group_by_leaf(const int32_t *leaf_ids, int nq, int Lp, int n_leaves, uint32_t *ws, LeafGroups *g, hipStream_t st);
+// prepare (lays out ws, clears the counts) -> launch_leaf_select(..., g.leaf_cnt) -> launch_group_by_leaf
+int group_by_leaf_prepare(int nq, int Lp, int n_leaves, uint32_t *ws, LeafGroups *g, hipStream_t st);
+int launch_group_by_leaf(const int32_t *leaf_ids, int nq, int Lp, int n_leaves, const LeafGroups &g, hipStream_t st);
+// leaf_cnt (optional): incremented once per selected (query, leaf) pair
 int launch_leaf_select(const float *centers_t, int n_leaves, int d, const float *queries, int nq,
-                       int L, int32_t *leaf_ids, float *leaf_ip, hipStream_t st);
+                       int L, int32_t *leaf_ids, float *leaf_ip, hipStream_t st, uint32_t *leaf_cnt = nullptr);
 int launch_transpose(const float *in, int rows, int cols, float *out, hipStream_t st);
 
 // ---- layout.hip ------------------------------------------------------------

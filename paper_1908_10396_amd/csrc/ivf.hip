@@ -13,7 +13,7 @@ namespace avq {
 __global__ void __launch_bounds__(1024)
 leaf_select_kernel(const float *__restrict__ centers_t, int n_leaves, int d,
                    const float *__restrict__ queries, int L, int ns,
-                   int32_t *__restrict__ leaf_ids, float *__restrict__ leaf_ip)
+                   int32_t *__restrict__ leaf_ids, float *__restrict__ leaf_ip, uint32_t *__restrict__ leaf_cnt)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const int C = 64 * ns;
@@ -56,11 +56,12 @@ leaf_select_kernel(const float *__restrict__ centers_t, int n_leaves, int d,
         const u64 key = list[j];
         leaf_ids[(size_t)q * L + j] = key ? key_id(key) : -1;
         leaf_ip[(size_t)q * L + j] = key ? f32_from_ord(key_ord(key)) : -INFINITY;
+        if (leaf_cnt != nullptr && key) atomicAdd(&leaf_cnt[key_id(key)], 1u); // how many queries probe each leaf
     }
 }
 
 int launch_leaf_select(const float *centers_t, int n_leaves, int d, const float *queries, int nq,
-                       int L, int32_t *leaf_ids, float *leaf_ip, hipStream_t st)
+                       int L, int32_t *leaf_ids, float *leaf_ip, hipStream_t st, uint32_t *leaf_cnt)
 {
     const int ns = (L + 63) / 64;
     // few queries: as many waves as there are 64-leaf groups (at most 16); batches: four
@@ -74,7 +75,7 @@ int launch_leaf_select(const float *centers_t, int n_leaves, int d, const float 
         attr_done = true;
     }
     hipLaunchKernelGGL(leaf_select_kernel, dim3(nq), dim3(waves * 64), lds, st, centers_t, n_leaves, d,
-                       queries, L, ns, leaf_ids, leaf_ip);
+                       queries, L, ns, leaf_ids, leaf_ip, leaf_cnt);
     AVQ_HIP(hipGetLastError());
     return AVQ_OK;
 }
@@ -87,15 +88,6 @@ int launch_leaf_select(const float *centers_t, int n_leaves, int d, const float 
 // on as query << 9 | slot (slot = position of the leaf in the query's probe list), and every
 // 32 of them are one work item, item_list[i] = leaf << 11 | tile. The order of a leaf's pairs
 // depends on the order of atomic operations; no result depends on it.
-
-__global__ void __launch_bounds__(256)
-group_count_kernel(const int32_t *__restrict__ leaf_ids, int64_t n_pairs, uint32_t *__restrict__ leaf_cnt)
-{
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n_pairs) return;
-    const int32_t leaf = leaf_ids[i];
-    if (leaf >= 0) atomicAdd(&leaf_cnt[leaf], 1u);
-}
 
 // One workgroup: running sums of the pair counts and of the item counts; clears the fill cursors.
 __global__ void __launch_bounds__(1024)
@@ -156,7 +148,9 @@ size_t group_by_leaf_words(int nq, int Lp, int n_leaves)
     return (size_t)4 * n_leaves + 4 + (size_t)nq * Lp + group_by_leaf_max_items(nq, Lp, n_leaves);
 }
 
-int launch_group_by_leaf(const int32_t *leaf_ids, int nq, int Lp, int n_leaves, uint32_t *ws, LeafGroups *g, hipStream_t st)
+// Lays the scratch out and clears the pair counts; leaf selection then counts (launch_leaf_select's
+// leaf_cnt), and launch_group_by_leaf does the rest.
+int group_by_leaf_prepare(int nq, int Lp, int n_leaves, uint32_t *ws, LeafGroups *g, hipStream_t st)
 {
     if (Lp > 512 || nq > (1 << 16) || n_leaves > (1 << 21)) { set_error("grouping by leaf: batch or partition too large"); return AVQ_EINVAL; }
     g->leaf_cnt = ws;
@@ -167,15 +161,19 @@ int launch_group_by_leaf(const int32_t *leaf_ids, int nq, int Lp, int n_leaves, 
     g->qlist = g->n_items + 4;
     g->item_list = g->qlist + (size_t)nq * Lp;
     g->max_items = (int32_t)group_by_leaf_max_items(nq, Lp, n_leaves);
-    const int64_t n_pairs = (int64_t)nq * Lp;
     AVQ_HIP(hipMemsetAsync(g->leaf_cnt, 0, sizeof(uint32_t) * (size_t)n_leaves, st));
-    hipLaunchKernelGGL(group_count_kernel, dim3((unsigned)((n_pairs + 255) / 256)), dim3(256), 0, st, leaf_ids, n_pairs, g->leaf_cnt);
-    hipLaunchKernelGGL(group_offsets_kernel, dim3(1), dim3(1024), 0, st, g->leaf_cnt, n_leaves, g->leaf_off, g->item_off, g->fill,
-                       g->n_items);
-    hipLaunchKernelGGL(group_fill_kernel, dim3((unsigned)((n_pairs + 255) / 256)), dim3(256), 0, st, leaf_ids, n_pairs, Lp, g->leaf_off,
-                       g->fill, g->qlist);
-    hipLaunchKernelGGL(group_items_kernel, dim3((n_leaves + 255) / 256), dim3(256), 0, st, g->leaf_cnt, g->item_off, n_leaves,
-                       g->item_list);
+    return AVQ_OK;
+}
+
+int launch_group_by_leaf(const int32_t *leaf_ids, int nq, int Lp, int n_leaves, const LeafGroups &g, hipStream_t st)
+{
+    const int64_t n_pairs = (int64_t)nq * Lp;
+    hipLaunchKernelGGL(group_offsets_kernel, dim3(1), dim3(1024), 0, st, g.leaf_cnt, n_leaves, g.leaf_off, g.item_off, g.fill,
+                       g.n_items);
+    hipLaunchKernelGGL(group_fill_kernel, dim3((unsigned)((n_pairs + 255) / 256)), dim3(256), 0, st, leaf_ids, n_pairs, Lp, g.leaf_off,
+                       g.fill, g.qlist);
+    hipLaunchKernelGGL(group_items_kernel, dim3((n_leaves + 255) / 256), dim3(256), 0, st, g.leaf_cnt, g.item_off, n_leaves,
+                       g.item_list);
     AVQ_HIP(hipGetLastError());
     return AVQ_OK;
 }
