@@ -153,7 +153,14 @@ int avq_update_codebooks(avq_index *idx, const float *x, int64_t n, int32_t max_
  *    that scan, also when the search itself uses 8-bit tables, does not keep
  *    sorted lists: it compares against a bound guessed from a sample of the
  *    points and checked afterwards; a query whose guess fails is scanned
- *    again, so results never depend on it);
+ *    again, so results never depend on it.) Batches of 64 queries or more
+ *    that probe 16 leaves or more of a partitioned index of 4-bit codes are
+ *    regrouped by leaf: a leaf's codes are scored once per 32 of the queries
+ *    that probe it (8-bit tables, matrix cores), every point whose estimate
+ *    fma(sum, scale, bias + <q, center>) can reach the R-th best score of the
+ *    query's first few leaves is kept, and the kept points are scored per
+ *    query as above (fp32 tables: fp32 sums of the points within the rounding
+ *    margin); same results;
  *  re-score those exactly, <q, x_i> as an fp32 fma chain in index order, and
  *    return the k best in the same order.
  * reorder_k == 0: no re-scoring; the k best ADC candidates are returned with
@@ -253,7 +260,11 @@ double avq_eta(int32_t d, double T, double norm, int32_t eta_mode);
  * the index; a query that needs more is scanned again with fp32 tables),
  * "scan_sample" (1: that candidate scan keeps lists and raises its bounds as
  * it goes, instead of scanning against bounds guessed from a sample of the
- * index and checked afterwards).
+ * index and checked afterwards), "bound_leaves" (batches on a partitioned
+ * index: how many of a query's best leaves are scanned first, one query at a
+ * time, for the bound that the scan of all leaves, regrouped by leaf, runs
+ * against; "scan_prefilter" = 1 also switches that regrouped scan off,
+ * "prefilter_cap" is its kept keys per query).
  * Results never depend on these. Returns
  * AVQ_EINVAL for an unknown name. */
 int avq_set_tuning(avq_index *idx, const char *name, int32_t value);
