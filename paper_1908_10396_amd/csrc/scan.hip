@@ -447,6 +447,20 @@ adc_scan_kernel(const ScanParams p)
     for (int q = 0; q < QT; ++q)
         if (pend_cnt[q] > 0) wave_list_flush(my_lists + (size_t)q * C, p.ns, my_pends + q * 64, pend_cnt[q]);
     __syncthreads();
+    if constexpr (QT == 1) {
+        // one query, many waves: the lists are merged pairwise up a tree (log2(waves) merges on the critical
+        // path instead of waves - 1), wave 0 ends up with the result
+        for (int stride = 1; stride < n_waves; stride *= 2) {
+            if ((wave % (2 * stride)) == 0 && wave + stride < n_waves)
+                wave_list_merge_from(my_lists, p.ns, lists + (size_t)(wave + stride) * C);
+            __syncthreads();
+        }
+        if (wave == 0) {
+            u64 *out = p.partial + ((size_t)q0 * n_chunks + chunk) * C;
+            for (int i = lane; i < C; i += 64) out[i] = my_lists[i];
+        }
+        return;
+    }
     for (int q = wave; q < QT; q += n_waves) {
         u64 *mine = my_lists + (size_t)q * C;
         for (int w = 0; w < n_waves; ++w) {
