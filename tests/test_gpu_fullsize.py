@@ -101,3 +101,35 @@ def test_library_codes_are_the_oracles_codes_on_a_sample(glove):
     # training sample: the library's dictionaries against the oracle's k-means on the same rows
     cb = oracle.train_pq(g["x"][: si.CHUNK], cfg["M"], 16, 20, seed=cfg["seed"])
     np.testing.assert_allclose(g["cb"], cb, rtol=0, atol=2e-6)
+
+
+@pytest.mark.parametrize("lut_mode", [0, 1])
+def test_full_partitioned_batch_matches_oracle_on_sampled_queries(lut_mode):
+    # the partitioned Glove-shaped workload as bench.py --config glove_ivf runs it (2,000 leaves, 100
+    # probed, 10,000 queries per launch: leaves scanned on the matrix cores, pairs regrouped by leaf)
+    cfg = si.CONFIGS["glove_ivf"]
+    x = si.make_data(cfg)
+    q = si.make_queries(cfg, cfg["nq"])
+    xd = torch.from_numpy(x).cuda()
+    qd = torch.from_numpy(q).cuda()
+    idx = avq.Index(cfg["d"], cfg["M"], cfg["bits"], T=cfg["T"], n_leaves=cfg["n_leaves"], kmeans_iters=10,
+                    encode_passes=5, seed=cfg["seed"])
+    idx.train(xd[: si.CHUNK])
+    idx.encode(xd)
+    k, R, L = cfg["k"], cfg["reorder_k"], cfg["leaves_to_search"]
+    ids, sc = idx.search(qd, k, R, lut_mode, leaves_to_search=L)
+    ids, sc = ids.cpu().numpy(), sc.cpu().numpy()
+    sample = [0, 1, 2500, 4097, 7777, 9999]
+    oi, os_ = oracle.search(x, idx.get_codebooks(), unpack_codes(idx.get_codes(), cfg["M"], cfg["bits"]), cfg["bits"],
+                            q[sample], k, R, lut_mode, centers=idx.get_leaf_centers(), assign=idx.get_leaf_assign(),
+                            leaves_to_search=L)
+    np.testing.assert_array_equal(ids[sample], oi)
+    np.testing.assert_array_equal(sc[sample], os_)
+    assert np.all(np.diff(sc, axis=1) <= 0)
+    back = idx.debug_unverified_queries()
+    assert 0 <= back < cfg["nq"] // 4          # most queries stay on the regrouped path
+    # the one-query-per-workgroup scan gives the same batch
+    idx.set_tuning("scan_prefilter", 1)
+    ids2, sc2 = idx.search(qd, k, R, lut_mode, leaves_to_search=L)
+    np.testing.assert_array_equal(ids2.cpu().numpy(), ids)
+    np.testing.assert_array_equal(sc2.cpu().numpy(), sc)
