@@ -60,10 +60,149 @@ leaf_select_kernel(const float *__restrict__ centers_t, int n_leaves, int d,
     }
 }
 
+// The same for large batches, without lists. A workgroup takes eight queries: every thread scores
+// its leaves against all eight (eight fma chains fed by one load of each center value; the kernel
+// above loads every value once per query) and the scores go to LDS. Then each wave takes one of the
+// queries: the ordering value of the L-th best score by bisection (a lane counts its share of the
+// scores, no barriers), the scores at or above it are collected and ranked by counting.
+constexpr int kLeafTile = 8;
+
+__global__ void __launch_bounds__(512)
+leaf_select_tile_kernel(const float *__restrict__ centers_t, int n_leaves, int d, const float *__restrict__ queries, int nq,
+                        int L, int32_t *__restrict__ leaf_ids, float *__restrict__ leaf_ip, uint32_t *__restrict__ leaf_cnt)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr int nt = 512, n_waves = 8;
+    const int q0 = blockIdx.x * kLeafTile;
+    uint32_t *ords = (uint32_t *)smem;                                  // [8][n_leaves] ordering values of the scores
+    float *qs = (float *)(ords + (size_t)kLeafTile * n_leaves);         // [d][8]
+    u64 *fin = (u64 *)(qs + (size_t)d * kLeafTile);                     // [8 waves][n_fin_max]
+    const int n_fin_max = L;
+    for (int e = tid; e < d * kLeafTile; e += nt) {
+        const int l = e / kLeafTile, t = e % kLeafTile;
+        qs[e] = q0 + t < nq ? queries[(size_t)(q0 + t) * d + l] : 0.0f;
+    }
+    __syncthreads();
+    for (int leaf = tid; leaf < n_leaves; leaf += nt) {
+        const float *col = centers_t + leaf;
+        float s[kLeafTile];
+#pragma unroll
+        for (int t = 0; t < kLeafTile; ++t) s[t] = 0.0f;
+        // sixteen center values in flight at a time
+        for (int l0 = 0; l0 < d; l0 += 16) {
+            float c[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) c[i] = l0 + i < d ? col[(size_t)(l0 + i) * n_leaves] : 0.0f;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                if (l0 + i >= d) break;
+                const float *ql = qs + (l0 + i) * kLeafTile;
+                const float4 qa = *(const float4 *)ql, qb = *(const float4 *)(ql + 4);
+                s[0] = __fmaf_rn(qa.x, c[i], s[0]); s[1] = __fmaf_rn(qa.y, c[i], s[1]);
+                s[2] = __fmaf_rn(qa.z, c[i], s[2]); s[3] = __fmaf_rn(qa.w, c[i], s[3]);
+                s[4] = __fmaf_rn(qb.x, c[i], s[4]); s[5] = __fmaf_rn(qb.y, c[i], s[5]);
+                s[6] = __fmaf_rn(qb.z, c[i], s[6]); s[7] = __fmaf_rn(qb.w, c[i], s[7]);
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < kLeafTile; ++t) ords[(size_t)t * n_leaves + leaf] = ord_from_f32(s[t]);
+    }
+    __syncthreads();
+    const int want = L < n_leaves ? L : n_leaves;
+    u64 *my_fin = fin + (size_t)wave * n_fin_max;
+    for (int t = wave; t < kLeafTile; t += n_waves) {
+        const int q = q0 + t;
+        if (q >= nq) break;
+        const uint32_t *o = ords + (size_t)t * n_leaves;
+        // up to 2048 leaves: a lane's share of the scores stays in registers through the bisection
+        constexpr int kReg = 32;
+        const bool in_regs = n_leaves <= kReg * 64;
+        uint32_t mine[kReg];
+        if (in_regs) {
+#pragma unroll
+            for (int i = 0; i < kReg; ++i) mine[i] = lane + i * 64 < n_leaves ? o[lane + i * 64] : 0u;
+        }
+        auto count_ge = [&](uint32_t v) -> int {
+            if (in_regs) { // v >= 1 in every call, so the zeros that stand for "no leaf" never count
+                int cr = 0;
+#pragma unroll
+                for (int i = 0; i < kReg; ++i) cr += mine[i] >= v;
+                for (int m = 32; m > 0; m >>= 1) cr += __shfl_xor(cr, m, 64);
+                return cr;
+            }
+            int cn = 0;
+            int leaf = lane;
+            for (; leaf + 7 * 64 < n_leaves; leaf += 8 * 64) { // eight reads in flight
+                uint32_t r[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) r[i] = o[leaf + i * 64];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) cn += r[i] >= v;
+            }
+            for (; leaf < n_leaves; leaf += 64) cn += o[leaf] >= v;
+            for (int m = 32; m > 0; m >>= 1) cn += __shfl_xor(cn, m, 64);
+            return cn;
+        };
+        uint32_t lo = 0u, hi = 0xffffffffu; // count_ge(lo) >= want > count_ge(hi)
+        while (hi - lo > 1u) {
+            const uint32_t mid = lo + ((hi - lo) >> 1);
+            if (count_ge(mid) >= want) lo = mid; else hi = mid;
+        }
+        // the `want` best: every score above the L-th best, then scores equal to it in leaf order (equal
+        // scores rank by id) until there are `want`
+        const int n_gt = count_ge(lo + 1u);
+        int at_gt = 0, at_eq = n_gt;
+        for (int base = 0; base < n_leaves; base += 64) {
+            const int leaf = base + lane;
+            const uint32_t ov = leaf < n_leaves ? o[leaf] : 0u;
+            const bool gt = leaf < n_leaves && ov > lo, eq = leaf < n_leaves && ov == lo;
+            const u64 m_gt = __builtin_amdgcn_ballot_w64(gt), m_eq = __builtin_amdgcn_ballot_w64(eq);
+            const u64 below = (1ull << lane) - 1ull;
+            if (gt) my_fin[at_gt + __builtin_popcountll(m_gt & below)] = make_key(ov, leaf);
+            const int e_at = at_eq + __builtin_popcountll(m_eq & below);
+            if (eq && e_at < want) my_fin[e_at] = make_key(ov, leaf);
+            at_gt += __builtin_popcountll(m_gt);
+            at_eq += __builtin_popcountll(m_eq);
+        }
+        wave_lds_fence();
+        const int nf = want;
+        for (int j = lane; j < nf; j += 64) {
+            const u64 k = my_fin[j];
+            int rank = 0;
+            for (int i = 0; i < nf; ++i) rank += my_fin[i] > k;
+            if (rank < L) {
+                leaf_ids[(size_t)q * L + rank] = key_id(k);
+                leaf_ip[(size_t)q * L + rank] = f32_from_ord(key_ord(k));
+                if (leaf_cnt != nullptr) atomicAdd(&leaf_cnt[key_id(k)], 1u);
+            }
+        }
+        for (int j = want + lane; j < L; j += 64) { // fewer leaves than asked for
+            leaf_ids[(size_t)q * L + j] = -1;
+            leaf_ip[(size_t)q * L + j] = -INFINITY;
+        }
+        wave_lds_fence();
+    }
+}
+
 int launch_leaf_select(const float *centers_t, int n_leaves, int d, const float *queries, int nq,
                        int L, int32_t *leaf_ids, float *leaf_ip, hipStream_t st, uint32_t *leaf_cnt)
 {
     const int ns = (L + 63) / 64;
+    if (nq >= 2048) {
+        const size_t lds = (size_t)kLeafTile * n_leaves * 4 + (size_t)d * kLeafTile * 4 + (size_t)8 * L * 8;
+        if (lds <= kMaxDynLds) {
+            static bool tile_attr_done = false;
+            if (!tile_attr_done) {
+                AVQ_HIP(hipFuncSetAttribute((const void *)leaf_select_tile_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynLds));
+                tile_attr_done = true;
+            }
+            hipLaunchKernelGGL(leaf_select_tile_kernel, dim3((nq + kLeafTile - 1) / kLeafTile), dim3(512), lds, st, centers_t, n_leaves,
+                               d, queries, nq, L, leaf_ids, leaf_ip, leaf_cnt);
+            AVQ_HIP(hipGetLastError());
+            return AVQ_OK;
+        }
+    }
     // few queries: as many waves as there are 64-leaf groups (at most 16); batches: four
     int waves = nq >= 1024 ? 4 : 16;
     while (waves > 1 && (waves / 2) * 64 >= n_leaves) waves /= 2;

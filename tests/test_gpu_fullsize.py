@@ -126,6 +126,15 @@ def test_full_partitioned_batch_matches_oracle_on_sampled_queries(lut_mode):
     np.testing.assert_array_equal(ids[sample], oi)
     np.testing.assert_array_equal(sc[sample], os_)
     assert np.all(np.diff(sc, axis=1) <= 0)
+    if lut_mode == 0:
+        # leaf selection of the whole batch (one wave per query at this size)
+        lids, lip = idx.debug_leaf_select(qd, L)
+        lids, lip = lids.cpu().numpy(), lip.cpu().numpy()
+        centers = idx.get_leaf_centers()
+        for qi in sample:
+            li, lp = oracle.leaf_select(centers, q[qi], L)
+            np.testing.assert_array_equal(lids[qi], li)
+            np.testing.assert_array_equal(lip[qi], lp)
     back = idx.debug_unverified_queries()
     assert 0 <= back < cfg["nq"] // 4          # most queries stay on the regrouped path
     # the one-query-per-workgroup scan gives the same batch
