@@ -729,8 +729,12 @@ static int search_leaves_grouped(avq_index *idx, const float *queries, int nq, i
         ScanParams pb = pl;
         pb.Lp = bound_leaves;
         pb.leaf_stride = L;
-        AVQ_TRY(launch_scan(pb, u8, SCAN_LEAVES, shape, st));
-        AVQ_TRY(launch_list_bound(pb.partial, ns, R, nq, bound, st));
+        if (idx->max_leaf_blocks <= kLeafBoundMaxBlocks) {
+            AVQ_TRY(launch_leaf_bound(pb, u8, (int)idx->max_leaf_blocks, (int)((idx->n_blocks + c.n_leaves - 1) / c.n_leaves), bound, st));
+        } else {
+            AVQ_TRY(launch_scan(pb, u8, SCAN_LEAVES, shape, st));
+            AVQ_TRY(launch_list_bound(pb.partial, ns, R, nq, bound, st));
+        }
         AVQ_TRY(launch_group_by_leaf(idx->leaf_ids.as<int32_t>(), nq, L, c.n_leaves, g, st));
         ScanParams pi;
         fill_scan_params(idx, nq, R, ns, &pi);
@@ -786,6 +790,9 @@ static int search_leaves_grouped(avq_index *idx, const float *queries, int nq, i
         AVQ_TRY(launch_gather_rows(idx->bias.as<float>(), bias_c, fail_list, fail_count, nq, 1, st));
         AVQ_TRY(launch_gather_rows(idx->leaf_ip.as<float>(), ip_c, fail_list, fail_count, nq, L, st));
         AVQ_TRY(launch_gather_rows((const float *)idx->leaf_ids.p, (float *)ids_c, fail_list, fail_count, nq, L, st));
+        // few queries, one workgroup each: as many waves per workgroup as the kernel takes
+        ScanShape shape_f;
+        AVQ_TRY(scan_pick_shape(idx->NB, c.bits, u8, ns, nq, true, idx->tune_qt, waves_hint ? waves_hint : 16, &shape_f));
         ScanParams pf = pl;
         pf.lut = idx->lut_fail.as<float>();
         pf.lut8 = idx->lut_fail.as<uint8_t>();
@@ -795,7 +802,7 @@ static int search_leaves_grouped(avq_index *idx, const float *queries, int nq, i
         pf.leaf_ids = ids_c;
         pf.Lp = L;
         pf.active_queries = fail_count;
-        AVQ_TRY(launch_scan(pf, u8, SCAN_LEAVES, shape, st));
+        AVQ_TRY(launch_scan(pf, u8, SCAN_LEAVES, shape_f, st));
         AVQ_TRY(launch_merge_partials(pf.partial, nq, 1, ns, idx->refined.as<u64>(), st, fail_list, fail_count, 0));
     }
     StageTimer t(idx, AVQ_STAGE_FINAL, st);

@@ -144,6 +144,13 @@ int launch_scan_mfma(const ScanParams &p, hipStream_t st);
 bool small_batch_can_fuse_tables(int bits, int M, int d, bool u8);
 // Full scan that only records the best key of every block (block_max[q][blk]).
 int launch_block_max(const ScanParams &p, bool u8, int waves, hipStream_t st);
+// Partitioned index, 4-bit codes, specialised code sizes: bound[q] = ordering value of the R-th best score
+// (tables as in `u8`) among the points of the first p.Lp leaves of row q of leaf_ids (row stride
+// leaf_stride) that fit its LDS, 0 if fewer than R; needs perm, leaf_blk, leaf_ip, lut / lut8, scale, bias.
+// max_leaf_blocks <= kLeafBoundMaxBlocks.
+constexpr int kLeafBoundMaxBlocks = 96;
+int launch_leaf_bound(const ScanParams &p, bool u8, int max_leaf_blocks, int mean_leaf_blocks, uint32_t *bound,
+                      hipStream_t st);
 // reads the blocked code array once, in the single-query scan's launch shape; out[blk] = xor of the block's words
 int launch_stream_codes(const uint8_t *codes, int64_t n_blocks, int NB, uint32_t *out, hipStream_t st);
 // Small batches, after launch_block_max: block selection, scan of the selected blocks,

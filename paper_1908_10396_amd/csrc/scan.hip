@@ -738,6 +738,133 @@ int launch_stream_codes(const uint8_t *codes, int64_t n_blocks, int NB, uint32_t
     return AVQ_OK;
 }
 
+// Bounds for the scan over leaves that is regrouped by leaf: bound[q] = ordering value of the R-th
+// best score among the points of query q's first p.Lp probed leaves (as many of them as fit
+// cap_blocks blocks; any subset of the query's points gives a valid bound), 0 if they hold fewer
+// than R points. Scores as the one-query-per-workgroup scan forms them: fp32 table sum (entries of
+// a byte first, bytes in order) + <q, center>, or fma(integer sum, scale, bias + <q, center>). One
+// workgroup per query: 16-entry tables in LDS, a wave per block, all scores to LDS, then the R-th
+// best by bisection over the ordering values. No lists.
+template <bool U8, int NBT>
+__global__ void __launch_bounds__(512)
+leaf_bound_kernel(const ScanParams p, int cap_blocks, uint32_t *__restrict__ bound)
+{
+    static_assert(NBT != 0, "specialised code sizes only");
+    constexpr int nt = 512, n_waves = 8, kSample = 1024, kShort = 2048;
+    extern __shared__ __align__(16) unsigned char dyn_smem[];
+    __shared__ __align__(16) unsigned char tables[2 * NBT * 16 * (U8 ? 1 : 4)];
+    __shared__ int first_blk[65], blk_of[65]; // probed leaf j: its blocks start at blk_of[j], at position first_blk[j] here
+    __shared__ int wave_cnt[2][n_waves], short_n;
+    uint32_t *ords = (uint32_t *)dyn_smem;      // [cap_blocks * 256], 0 = no point
+    uint32_t *shortlist = ords + (size_t)cap_blocks * 256; // [kShort]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int q = blockIdx.x;
+    const int stride = p.leaf_stride ? p.leaf_stride : p.Lp;
+    const int Lb = p.Lp < 64 ? p.Lp : 64;
+    if (tid < Lb) { // the leaves' block ranges, one thread each: the loads overlap
+        const int leaf = p.leaf_ids[(size_t)q * stride + tid];
+        blk_of[tid] = leaf >= 0 ? p.leaf_blk[leaf] : 0;
+        first_blk[tid] = leaf >= 0 ? p.leaf_blk[leaf + 1] - p.leaf_blk[leaf] : 0; // block count for now
+    }
+    nibble_tables_fill<U8>(tables, p, q, NBT);
+    __syncthreads();
+    if (tid == 0) {
+        int at = 0;
+        for (int j = 0; j < Lb; ++j) {
+            int nb = first_blk[j];
+            if (at + nb > cap_blocks) nb = 0; // does not fit: left out
+            first_blk[j] = at;
+            at += nb;
+        }
+        first_blk[Lb] = at;
+        short_n = 0;
+    }
+    __syncthreads();
+    const int total = first_blk[Lb];
+    const float scale = U8 ? p.scale[q] : 0.0f, bias = U8 ? p.bias[q] : 0.0f;
+    for (int b = wave; b < total; b += n_waves) {
+        int j = 0;
+        while (b >= first_blk[j + 1]) ++j;
+        const int64_t blk = (int64_t)blk_of[j] + (b - first_blk[j]);
+        const float ip = p.leaf_ip[(size_t)q * stride + j];
+        BlockRegs<NBT> regs;
+        load_block<NBT>(regs, p.codes, blk, lane);
+        const int4 ids = ((const int4 *)(p.perm + (size_t)blk * 256))[lane];
+        float accf[4];
+        uint32_t acci[4];
+        nibble_accumulate<U8, NBT>(tables, regs, p.codes + (size_t)blk * 256 * NBT, NBT, lane, accf, acci);
+        const int idv[4] = {ids.x, ids.y, ids.z, ids.w};
+        uint4 o;
+        uint32_t *ov = (uint32_t *)&o;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float sc = U8 ? __fmaf_rn((float)(int)acci[i], scale, __fadd_rn(bias, ip)) : __fadd_rn(accf[i], ip);
+            ov[i] = idv[i] >= 0 ? ord_from_f32(sc) : 0u;
+        }
+        ((uint4 *)(ords + (size_t)b * 256))[lane] = o;
+    }
+    __syncthreads();
+    const int n = total * 256;
+    // number of a[at(i)], i < m, that are >= v (v >= 1: empty slots never count), known to every thread;
+    // one barrier per call: the waves' counts go to alternating halves of wave_cnt
+    int parity = 0;
+    auto count_ge = [&](const uint32_t *a, int m, uint32_t v, auto at) -> int {
+        int cn = 0; // the loop is uniform over the wave: every lane sees every ballot
+        for (int base = wave * 64; base < m; base += 4 * nt) {
+            uint32_t r[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = base + u * nt + lane;
+                r[u] = i < m ? a[at(i)] : 0u;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) cn += __popcll(__builtin_amdgcn_ballot_w64(r[u] >= v));
+        }
+        if (lane == 0) wave_cnt[parity][wave] = cn;
+        __syncthreads();
+        int tot = 0;
+#pragma unroll
+        for (int w = 0; w < n_waves; ++w) tot += wave_cnt[parity][w];
+        parity ^= 1;
+        return tot;
+    };
+    // largest v in [lo, 2^32) with at least R values >= v, given that lo has
+    auto rth_best = [&](const uint32_t *a, int m, int R, uint32_t lo, auto at) -> uint32_t {
+        uint32_t hi = 0xffffffffu; // no value reaches it
+        while (hi - lo > 1u) {
+            const uint32_t mid = lo + ((hi - lo) >> 1);
+            if (count_ge(a, m, mid, at) >= R) lo = mid; else hi = mid;
+        }
+        return lo;
+    };
+    auto plain = [](int i) { return i; };
+    uint32_t result = 0u;
+    bool done = false;
+    // Most values are far below the answer: a bound T0 from an evenly spread sample (its rank there chosen so
+    // that, in all likelihood, at least R values overall reach T0), one pass that copies the values >= T0 to
+    // a short list, and the R-th best of that list. When the guess fails, the search over all values below.
+    const float mu = (float)p.R * (float)kSample / (float)(n > 0 ? n : 1);
+    const int rs = (int)(mu + 3.0f * sqrtf(mu) + 2.0f);
+    if (n >= 4 * kSample && rs <= kSample / 2) {
+        auto spread = [n](int i) { return (int)(((int64_t)i * n) >> 10); };
+        if (count_ge(ords, kSample, 1u, spread) >= rs) {
+            const uint32_t t0 = rth_best(ords, kSample, rs, 1u, spread);
+            const int reach = count_ge(ords, n, t0, plain);
+            if (reach >= p.R && reach <= kShort) {
+                for (int i = tid; i < n; i += nt) {
+                    const uint32_t v = ords[i];
+                    if (v >= t0) shortlist[atomicAdd(&short_n, 1)] = v;
+                }
+                __syncthreads();
+                result = rth_best(shortlist, reach, p.R, t0, plain);
+                done = true;
+            }
+        }
+    }
+    if (!done && count_ge(ords, n, 1u, plain) >= p.R) result = rth_best(ords, n, p.R, 1u, plain);
+    if (tid == 0) bound[q] = result;
+}
+
 // After the block-maxima scan, for a handful of queries, three short kernels:
 //  A. select_blocks_kernel (one workgroup per query): t1 = the R-th largest block
 //     maximum (exact, wg_select_threshold); the blocks whose maximum is >= t1 are listed.
@@ -993,6 +1120,42 @@ static int set_max_lds(K kern, bool *done)
         *done = true;
     }
     return AVQ_OK;
+}
+
+template <bool U8, int NBT>
+static int launch_leaf_bound_one(const ScanParams &p, int cap_blocks, uint32_t *bound, hipStream_t st)
+{
+    auto kern = leaf_bound_kernel<U8, NBT>;
+    static bool attr_done = false; // the tables are static LDS on top of this
+    if (!attr_done) {
+        AVQ_HIP(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLeafBoundMaxBlocks * 1024 + 8192));
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(p.B), dim3(512), (size_t)cap_blocks * 1024 + 8192, st, p, cap_blocks, bound);
+    AVQ_HIP(hipGetLastError());
+    return AVQ_OK;
+}
+
+int launch_leaf_bound(const ScanParams &p, bool u8, int max_leaf_blocks, int mean_leaf_blocks, uint32_t *bound, hipStream_t st)
+{
+    if (p.bits != 4 || !p.leaf_ids || !p.leaf_ip || !p.leaf_blk || !p.perm || p.Lp < 1 || p.R < 1) {
+        set_error("leaf bounds: bad arguments");
+        return AVQ_EINVAL;
+    }
+    const int Lb = std::min(p.Lp, 64);
+    // room for leaves half again as large as the mean (probed leaves tend to be the larger ones), never more
+    // than the largest ones need; several workgroups per compute unit as long as this stays small
+    int64_t cap = (int64_t)Lb * std::max(1, mean_leaf_blocks) * 3 / 2 + 4;
+    cap = std::min<int64_t>(cap, (int64_t)Lb * std::max(1, max_leaf_blocks));
+    if (max_leaf_blocks > kLeafBoundMaxBlocks) { set_error("leaf bounds: leaves of %d blocks are too large", max_leaf_blocks); return AVQ_EINVAL; }
+    const int cap_blocks = (int)std::max<int64_t>(std::max(1, max_leaf_blocks), std::min<int64_t>(kLeafBoundMaxBlocks, cap));
+    switch (p.NB) {
+    case 8: return u8 ? launch_leaf_bound_one<true, 8>(p, cap_blocks, bound, st) : launch_leaf_bound_one<false, 8>(p, cap_blocks, bound, st);
+    case 13: return u8 ? launch_leaf_bound_one<true, 13>(p, cap_blocks, bound, st) : launch_leaf_bound_one<false, 13>(p, cap_blocks, bound, st);
+    case 25: return u8 ? launch_leaf_bound_one<true, 25>(p, cap_blocks, bound, st) : launch_leaf_bound_one<false, 25>(p, cap_blocks, bound, st);
+    case 32: return u8 ? launch_leaf_bound_one<true, 32>(p, cap_blocks, bound, st) : launch_leaf_bound_one<false, 32>(p, cap_blocks, bound, st);
+    default: set_error("leaf bounds: code size %d not specialised", p.NB); return AVQ_EINVAL;
+    }
 }
 
 template <int QT, bool U8, int NBT, int MODE>
