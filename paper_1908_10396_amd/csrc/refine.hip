@@ -23,6 +23,7 @@
 // with more kept points than the buffers hold is handed to the plain fp32 scan instead.
 #include "avq_internal.h"
 #include "wave_topk.h"
+#include <type_traits>
 
 namespace avq {
 
@@ -278,13 +279,14 @@ ivf_refine_kernel(const IvfRefineParams r)
     u64 *keys = (u64 *)(smem + (((size_t)n_tab * 64 + 15) & ~(size_t)15));    // [kFinalMax]
     int32_t *fin_ids = (int32_t *)(keys + kFinalMax);                         // [kFinalMax]
     float *fin_ip = (float *)(fin_ids + kFinalMax);                           // [kFinalMax]
-    __shared__ int cnt_s, n_fin_s;
+    __shared__ int n_fin_s, wave_cnt[2][4];
+    __shared__ uint32_t wave_ext[2][4];
 
     if (rescore) {
         const float *L = r.lut + (size_t)q * r.M * 16;
         for (int e = tid; e < n_tab * 16; e += nt) tbl[e] = e < r.M * 16 ? L[e] : 0.0f;
     }
-    if (tid == 0) { cnt_s = 0; n_fin_s = 0; }
+    if (tid == 0) n_fin_s = 0;
     __syncthreads();
     const uint32_t total = r.kept_cnt[q];
     const int margin = rescore ? r.margin[q] : 0;
@@ -319,21 +321,40 @@ ivf_refine_kernel(const IvfRefineParams r)
     }
     uint32_t keep = 0u;
     if (ok) {
+        // estimates >= v over the workgroup, v >= 1; one barrier per call, the waves' counts in alternating rows
+        int parity = 0;
         auto count_ge = [&](uint32_t v) -> int {
             int cn = 0;
 #pragma unroll
-            for (int k = 0; k < kIvfKeysPerThread; ++k) cn += est[k] >= v && est[k] != 0u;
-            for (int m = 32; m > 0; m >>= 1) cn += __shfl_xor(cn, m, 64);
+            for (int k = 0; k < kIvfKeysPerThread; ++k) cn += __popcll(__builtin_amdgcn_ballot_w64(est[k] >= v));
+            if ((tid & 63) == 0) wave_cnt[parity][tid >> 6] = cn;
             __syncthreads();
-            if (tid == 0) cnt_s = 0;
-            __syncthreads();
-            if ((tid & 63) == 0 && cn) atomicAdd(&cnt_s, cn);
-            __syncthreads();
-            return cnt_s;
+            const int tot = wave_cnt[parity][0] + wave_cnt[parity][1] + wave_cnt[parity][2] + wave_cnt[parity][3];
+            parity ^= 1;
+            return tot;
         };
-        if (count_ge(1u) >= r.R) {
+        // smallest and largest estimate: the search runs between them
+        uint32_t emin = 0xffffffffu, emax = 0u;
+#pragma unroll
+        for (int k = 0; k < kIvfKeysPerThread; ++k) {
+            emax = est[k] > emax ? est[k] : emax;
+            emin = est[k] != 0u && est[k] < emin ? est[k] : emin;
+        }
+        for (int m = 32; m > 0; m >>= 1) {
+            const uint32_t a = (uint32_t)__shfl_xor((int)emax, m, 64), b2 = (uint32_t)__shfl_xor((int)emin, m, 64);
+            emax = a > emax ? a : emax;
+            emin = b2 < emin ? b2 : emin;
+        }
+        if ((tid & 63) == 0) { wave_ext[0][tid >> 6] = emin; wave_ext[1][tid >> 6] = emax; }
+        __syncthreads();
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            emin = wave_ext[0][w] < emin ? wave_ext[0][w] : emin;
+            emax = wave_ext[1][w] > emax ? wave_ext[1][w] : emax;
+        }
+        if (emax != 0u && count_ge(emin) >= r.R) {
             // ordering value of the R-th best estimate: the largest v with at least R estimates >= v
-            uint32_t lo = 1u, hi = 0xffffffffu; // count_ge(lo) >= R; count_ge(hi) < R (no finite score maps to it)
+            uint32_t lo = emin, hi = emax == 0xffffffffu ? emax : emax + 1u; // count_ge(lo) >= R > count_ge(hi) (no finite score maps to 2^32 - 1)
             while (hi - lo > 1u) {
                 const uint32_t mid = lo + ((hi - lo) >> 1);
                 if (count_ge(mid) >= r.R) lo = mid; else hi = mid;
@@ -390,17 +411,34 @@ ivf_refine_kernel(const IvfRefineParams r)
         }
         keys[i] = make_key(ord_from_f32(__fadd_rn(s, fin_ip[i])), id);
     }
+    if (tid == 0 && (n_cand & 1)) keys[n_cand] = 0ull; // n_cand odd: below kFinalMax, which is even
     __syncthreads();
     u64 *out = r.out + (size_t)q * C;
-    for (int j0 = 0; j0 < n_cand; j0 += nt / 4) {
-        const int j = j0 + (tid >> 2);
-        const u64 k = j < n_cand ? keys[j] : ~0ull;
-        int rank = 0;
-        for (int t = tid & 3; t < n_cand; t += 4) rank += keys[t] > k;
-        rank += __shfl_xor(rank, 1, 64);
-        rank += __shfl_xor(rank, 2, 64);
-        if (j < n_cand && (tid & 3) == 0 && rank < r.R) out[rank] = k;
-    }
+    // rank by counting: a thread holds its own keys (PER of them) and reads all keys, two at a time, at
+    // addresses the whole wave shares
+    auto rank_all = [&](auto per_tag) {
+        constexpr int PER = decltype(per_tag)::value;
+        u64 mine[PER];
+        int rank[PER];
+#pragma unroll
+        for (int k = 0; k < PER; ++k) {
+            const int j = tid + k * nt;
+            mine[k] = j < n_cand ? keys[j] : ~0ull;
+            rank[k] = 0;
+        }
+        for (int t = 0; t < n_cand; t += 2) {
+            const ulonglong2 two = *(const ulonglong2 *)(keys + t);
+#pragma unroll
+            for (int k = 0; k < PER; ++k) rank[k] += (int)(two.x > mine[k]) + (int)(two.y > mine[k]);
+        }
+#pragma unroll
+        for (int k = 0; k < PER; ++k)
+            if (tid + k * nt < n_cand && rank[k] < r.R) out[rank[k]] = mine[k];
+    };
+    if (n_cand <= nt) rank_all(std::integral_constant<int, 1>());
+    else if (n_cand <= 2 * nt) rank_all(std::integral_constant<int, 2>());
+    else if (n_cand <= 4 * nt) rank_all(std::integral_constant<int, 4>());
+    else rank_all(std::integral_constant<int, kFinalMax / nt>());
     const int n_fin = n_cand < r.R ? n_cand : r.R;
     for (int i = n_fin + tid; i < C; i += nt) out[i] = 0ull;
 }
