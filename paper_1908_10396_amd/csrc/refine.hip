@@ -23,7 +23,6 @@
 // with more kept points than the buffers hold is handed to the plain fp32 scan instead.
 #include "avq_internal.h"
 #include "wave_topk.h"
-#include <type_traits>
 
 namespace avq {
 
@@ -59,6 +58,39 @@ constexpr int kKeysPerThread = 32; // kept keys of one query that the refinement
 constexpr int kFinalMax = 2048;  // of those, the ones within the margin of the R-th best sum; more: plain scan
 
 
+// out[rank] = key for the R best of keys[0 .. n_cand) (distinct, in LDS, n_cand <= kFinalMax, keys[n_cand] = 0 when
+// n_cand is odd), ranks by counting: a thread holds its own keys (PER of them) and reads all keys, two at a
+// time, at addresses the whole wave shares. 256 threads.
+template <int PER>
+__device__ __forceinline__ void rank_and_store_per(const u64 *keys, int n_cand, int R, u64 *__restrict__ out, int tid)
+{
+    constexpr int nt = 256;
+    u64 mine[PER];
+    int rank[PER];
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+        const int j = tid + k * nt;
+        mine[k] = j < n_cand ? keys[j] : ~0ull;
+        rank[k] = 0;
+    }
+    for (int t = 0; t < n_cand; t += 2) {
+        const ulonglong2 two = *(const ulonglong2 *)(keys + t);
+#pragma unroll
+        for (int k = 0; k < PER; ++k) rank[k] += (int)(two.x > mine[k]) + (int)(two.y > mine[k]);
+    }
+#pragma unroll
+    for (int k = 0; k < PER; ++k)
+        if (tid + k * nt < n_cand && rank[k] < R) out[rank[k]] = mine[k];
+}
+
+__device__ __forceinline__ void rank_and_store(const u64 *keys, int n_cand, int R, u64 *__restrict__ out, int tid)
+{
+    if (n_cand <= 256) rank_and_store_per<1>(keys, n_cand, R, out, tid);
+    else if (n_cand <= 512) rank_and_store_per<2>(keys, n_cand, R, out, tid);
+    else if (n_cand <= 1024) rank_and_store_per<4>(keys, n_cand, R, out, tid);
+    else rank_and_store_per<kFinalMax / 256>(keys, n_cand, R, out, tid);
+}
+
 template <int NBT>
 __global__ void __launch_bounds__(256)
 refine_cand_kernel(const RefineCandParams r)
@@ -72,7 +104,7 @@ refine_cand_kernel(const RefineCandParams r)
     float *tbl = (float *)smem;                                               // [n_tab][16]
     u64 *keys = (u64 *)(smem + (((size_t)n_tab * 64 + 15) & ~(size_t)15));    // [kFinalMax] fp32 keys of the finalists
     int32_t *fin_ids = (int32_t *)(keys + kFinalMax);                         // [kFinalMax]
-    __shared__ int n_top_s, bad_s, cnt_s, n_fin_s;
+    __shared__ int n_top_s, bad_s, n_fin_s, wave_cnt[2][4];
     __shared__ uint32_t first_of[kMaxChunks + 1]; // first_of[c] = kept keys in the chunks before c
 
     // lut == NULL: the integer sums themselves are what is ranked (8-bit-table search): no margin, no re-scoring
@@ -81,7 +113,7 @@ refine_cand_kernel(const RefineCandParams r)
         const float *L = r.lut + (size_t)q * r.M * 16;
         for (int e = tid; e < n_tab * 16; e += nt) tbl[e] = e < r.M * 16 ? L[e] : 0.0f;
     }
-    if (tid == 0) { n_top_s = 0; bad_s = 0; cnt_s = 0; n_fin_s = 0; }
+    if (tid == 0) { n_top_s = 0; bad_s = 0; n_fin_s = 0; }
     // the chunks' fill counts (one load each, all in flight together) and their running sum
     uint32_t my_cnt = 0u;
     if (tid < r.n_chunks) my_cnt = r.cand_cnt[(size_t)q * r.n_chunks + tid];
@@ -134,17 +166,18 @@ refine_cand_kernel(const RefineCandParams r)
         // sum is found by bisection (every thread counts its own keys), and only keys within the margin of
         // it go on. (Unused slots hold 0: ordering value 0, below every bound.)
         const uint32_t T = r.bound[q];
-        auto count_ge = [&](uint32_t v) -> int { // keys with ordering value >= v, over the workgroup
+        // keys with ordering value >= v (v >= 1), over the workgroup; one barrier per call, the waves' counts
+        // in alternating rows
+        int parity = 0;
+        auto count_ge = [&](uint32_t v) -> int {
             int cn = 0;
 #pragma unroll
-            for (int k = 0; k < kKeysPerThread; ++k) cn += (mine[k] >> 18) >= v;
-            for (int m = 32; m > 0; m >>= 1) cn += __shfl_xor(cn, m, 64);
-            __syncthreads(); // cnt_s is free again
-            if (tid == 0) cnt_s = 0;
+            for (int k = 0; k < kKeysPerThread; ++k) cn += __popcll(__builtin_amdgcn_ballot_w64((mine[k] >> 18) >= v));
+            if ((tid & 63) == 0) wave_cnt[parity][tid >> 6] = cn;
             __syncthreads();
-            if ((tid & 63) == 0 && cn) atomicAdd(&cnt_s, cn);
-            __syncthreads();
-            return cnt_s;
+            const int tot = wave_cnt[parity][0] + wave_cnt[parity][1] + wave_cnt[parity][2] + wave_cnt[parity][3];
+            parity ^= 1;
+            return tot;
         };
         if (T == 0u || count_ge(T) < r.R) {
             ok = false;
@@ -206,17 +239,10 @@ refine_cand_kernel(const RefineCandParams r)
         }
         keys[i] = make_key(ord_from_f32(s), id);
     }
+    if (tid == 0 && (n_cand & 1)) keys[n_cand] = 0ull; // n_cand odd: below kFinalMax, which is even
     __syncthreads();
     u64 *out = r.out + (size_t)q * C;
-    for (int j0 = 0; j0 < n_cand; j0 += nt / 4) {
-        const int j = j0 + (tid >> 2);
-        const u64 k = j < n_cand ? keys[j] : ~0ull;
-        int rank = 0;
-        for (int t = tid & 3; t < n_cand; t += 4) rank += keys[t] > k;
-        rank += __shfl_xor(rank, 1, 64);
-        rank += __shfl_xor(rank, 2, 64);
-        if (j < n_cand && (tid & 3) == 0 && rank < r.R) out[rank] = k;
-    }
+    rank_and_store(keys, n_cand, r.R, out, tid);
     const int n_fin = n_cand < r.R ? n_cand : r.R;
     for (int i = n_fin + tid; i < C; i += nt) out[i] = 0ull;
 }
@@ -414,31 +440,7 @@ ivf_refine_kernel(const IvfRefineParams r)
     if (tid == 0 && (n_cand & 1)) keys[n_cand] = 0ull; // n_cand odd: below kFinalMax, which is even
     __syncthreads();
     u64 *out = r.out + (size_t)q * C;
-    // rank by counting: a thread holds its own keys (PER of them) and reads all keys, two at a time, at
-    // addresses the whole wave shares
-    auto rank_all = [&](auto per_tag) {
-        constexpr int PER = decltype(per_tag)::value;
-        u64 mine[PER];
-        int rank[PER];
-#pragma unroll
-        for (int k = 0; k < PER; ++k) {
-            const int j = tid + k * nt;
-            mine[k] = j < n_cand ? keys[j] : ~0ull;
-            rank[k] = 0;
-        }
-        for (int t = 0; t < n_cand; t += 2) {
-            const ulonglong2 two = *(const ulonglong2 *)(keys + t);
-#pragma unroll
-            for (int k = 0; k < PER; ++k) rank[k] += (int)(two.x > mine[k]) + (int)(two.y > mine[k]);
-        }
-#pragma unroll
-        for (int k = 0; k < PER; ++k)
-            if (tid + k * nt < n_cand && rank[k] < r.R) out[rank[k]] = mine[k];
-    };
-    if (n_cand <= nt) rank_all(std::integral_constant<int, 1>());
-    else if (n_cand <= 2 * nt) rank_all(std::integral_constant<int, 2>());
-    else if (n_cand <= 4 * nt) rank_all(std::integral_constant<int, 4>());
-    else rank_all(std::integral_constant<int, kFinalMax / nt>());
+    rank_and_store(keys, n_cand, r.R, out, tid);
     const int n_fin = n_cand < r.R ? n_cand : r.R;
     for (int i = n_fin + tid; i < C; i += nt) out[i] = 0ull;
 }
