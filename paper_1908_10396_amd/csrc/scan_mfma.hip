@@ -51,6 +51,7 @@
 namespace avq {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v8i __attribute__((ext_vector_type(8)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef __attribute__((address_space(3))) uint32_t lds_u32;
 
@@ -217,14 +218,22 @@ template <int NBT, bool STORE>
 __global__ void __launch_bounds__(kMfmaWaves * 64, 2)
 adc_mfma_scan_kernel(const ScanParams p)
 {
-    __shared__ __align__(16) uint32_t onehot[64];
+    // entry t = g0 + 4 * g1, 16 bytes: the compressed one-hot patterns of a code byte whose low nibble lies in
+    // group g0 (codes 4 g0 .. 4 g0 + 3) and whose high nibble lies in group g1: bytes 0-7 for the low nibble, a 1
+    // in the first slot of group g0; bytes 8-15 for the high nibble, a 1 in the second slot of group g1
+    __shared__ __align__(16) uint32_t pat_tab[64];
     extern __shared__ __align__(16) unsigned char dyn_smem[]; // [waves][64 lanes][kMfmaPend] 32-bit keys
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    if (threadIdx.x < 64) {
-        const int c = threadIdx.x >> 2, dw = threadIdx.x & 3; // pattern c, dword dw
-        onehot[threadIdx.x] = (dw == (c >> 2)) ? (1u << (8 * (c & 3))) : 0u;
+    if (threadIdx.x < 16) {
+        const int t = threadIdx.x, g0 = t & 3, g1 = t >> 2;
+        const uint32_t lo = 1u << (16 * (g0 & 1)), hi = 1u << (8 + 16 * (g1 & 1));
+        pat_tab[4 * t + 0] = g0 < 2 ? lo : 0u;
+        pat_tab[4 * t + 1] = g0 < 2 ? 0u : lo;
+        pat_tab[4 * t + 2] = g1 < 2 ? hi : 0u;
+        pat_tab[4 * t + 3] = g1 < 2 ? 0u : hi;
     }
     __syncthreads();
+    constexpr int NS = (NBT + 1) / 2; // matrix instructions per chain: two code bytes (four subspaces) each
     const int64_t gw = (int64_t)blockIdx.x * kMfmaWaves + wave; // wave index over (chunk, tile), or over the items
     const int j = lane & 31, h = lane >> 5;
     const bool items = p.item_list != nullptr;
@@ -258,15 +267,21 @@ adc_mfma_scan_kernel(const ScanParams p)
     const int off = 128 * p.M;
     constexpr bool store = STORE;
 
-    // table operands: position s takes subspaces 2s (lanes 0-31) and 2s + 1 (lanes 32-63)
-    v4i bq[NBT];
+    // table operands: step s covers subspaces 4s .. 4s + 3; this lane's first sixteen bytes meet the
+    // patterns of lanes 0-31 (code byte 2s), its last sixteen those of lanes 32-63 (code byte 2s + 1),
+    // lanes 0-31 here the low nibbles' (even subspaces), lanes 32-63 the high nibbles'
+    v8i bq[NS];
 #pragma unroll
-    for (int s = 0; s < NBT; ++s) {
-        const int row = 2 * s + h;
-        uint4 r = make_uint4(0x80808080u, 0x80808080u, 0x80808080u, 0x80808080u); // -> 0
-        if (live && row < p.M) r = *(const uint4 *)(p.lut8 + ((size_t)q * p.M + row) * 16);
-        bq[s] = v4i{(int)(r.x ^ 0x80808080u), (int)(r.y ^ 0x80808080u), (int)(r.z ^ 0x80808080u),
-                    (int)(r.w ^ 0x80808080u)};
+    for (int s = 0; s < NS; ++s) {
+        uint4 r[2];
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            const int row = 4 * s + 2 * c + h;
+            r[c] = make_uint4(0x80808080u, 0x80808080u, 0x80808080u, 0x80808080u); // -> 0
+            if (live && row < p.M) r[c] = *(const uint4 *)(p.lut8 + ((size_t)q * p.M + row) * 16);
+        }
+        bq[s] = v8i{(int)(r[0].x ^ 0x80808080u), (int)(r[0].y ^ 0x80808080u), (int)(r[0].z ^ 0x80808080u), (int)(r[0].w ^ 0x80808080u),
+                    (int)(r[1].x ^ 0x80808080u), (int)(r[1].y ^ 0x80808080u), (int)(r[1].z ^ 0x80808080u), (int)(r[1].w ^ 0x80808080u)};
     }
 
     uint32_t *my_lists = nullptr; // [32 queries][C] 32-bit keys
@@ -341,24 +356,25 @@ adc_mfma_scan_kernel(const ScanParams p)
     const int64_t stride = p.block_stride > 1 ? p.block_stride : 1;
     const int64_t n_half = end > first ? 2 * ((end - first + stride - 1) / stride) : 0; // half blocks to visit
     const int32_t id_base = (int32_t)(first * kBlockPoints); // ids inside keys count from here
-    const uint32_t nib_shift = 4u * (uint32_t)(1 - h); // brings this half-wave's nibble to bits 4..7 of each byte
-
-    // lane (j, h) takes the four points of lane slot H*32 + j of a block's rows
-    auto load_half = [&](uint32_t (&w)[NBT], int64_t hb) {
+    // lane (j, h) takes code bytes h, h + 2, ... of the four points of lane slot H*32 + j of a block's rows
+    auto plane_off = [](int b) -> int { // byte plane b of a block: offset of slot 0's word
+        return b < 4 * (NBT / 4) ? (b / 4) * 1024 + (b % 4) * 4 : (NBT / 4) * 1024 + (b - 4 * (NBT / 4)) * 256;
+    };
+    auto load_half = [&](uint32_t (&w)[NS], int64_t hb) {
         const uint8_t *base = p.codes + (size_t)(hb >> 1) * 256 * NBT;
         const int slot = (int)(hb & 1) * 32 + j;
 #pragma unroll
-        for (int r = 0; r < NBT / 4; ++r) {
-            const uint4 t = ((const uint4 *)(base + (size_t)r * 1024))[slot];
-            w[4 * r] = t.x; w[4 * r + 1] = t.y; w[4 * r + 2] = t.z; w[4 * r + 3] = t.w;
+        for (int s = 0; s < NS; ++s) {
+            const int b0 = 2 * s, b1 = 2 * s + 1;
+            const int stride0 = b0 < 4 * (NBT / 4) ? 16 : 4, stride1 = b1 < 4 * (NBT / 4) ? 16 : 4; // per slot
+            const int o0 = plane_off(b0) + slot * stride0, o1 = plane_off(b1) + slot * stride1;
+            if (b1 < NBT) w[s] = *(const uint32_t *)(base + (h ? o1 : o0));
+            else w[s] = h ? 0u : *(const uint32_t *)(base + o0); // no such byte: code 0 against a zero table
         }
-#pragma unroll
-        for (int t = 0; t < NBT % 4; ++t)
-            w[(NBT / 4) * 4 + t] = ((const uint32_t *)(base + (size_t)(NBT / 4) * 1024 + (size_t)t * 256))[slot];
     };
 
     uint32_t nxt_bound = bound_ord; // the shared bound, read one block ahead of its use
-    uint32_t w_cur[NBT], w_nxt[NBT];
+    uint32_t w_cur[NS], w_nxt[NS];
     auto half_of = [&](int64_t i) -> int64_t { return 2 * (first + (i >> 1) * stride) + (i & 1); };
     if (n_half > 0) load_half(w_cur, half_of(0));
     for (int64_t i = 0; i < n_half; ++i) {
@@ -371,24 +387,32 @@ adc_mfma_scan_kernel(const ScanParams p)
             thr = thr_of();
             nxt_bound = __hip_atomic_load(p.thr_shared + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-        // this half-wave's nibble of every byte, times 16: the offset of its one-hot pattern
+        // per code byte (low nibble 4 g0 + p0, high nibble 4 g1 + p1): the offset 16 (g0 + 4 g1) of its pattern
+        // entry, and p0 + 4 p1 in both nibbles of a byte: copied to all four bytes that is the index operand
+        // (every first slot selects p0, every second slot p1; only the slots that hold a 1 matter)
+        uint32_t grp16[NS], sel2[NS];
 #pragma unroll
-        for (int b = 0; b < NBT; ++b) {
-            w_cur[b] = (w_cur[b] << nib_shift) & 0xf0f0f0f0u;
-            asm volatile("" : "+v"(w_cur[b])); // keeps the mask here: one bit-field extract per lookup below
+        for (int b = 0; b < NS; ++b) {
+            const uint32_t w = w_cur[b];
+            grp16[b] = ((w << 2) & 0x30303030u) | (w & 0xc0c0c0c0u);
+            const uint32_t v = (w & 0x03030303u) | ((w >> 2) & 0x0c0c0c0cu);
+            sel2[b] = v | (v << 4);
+            asm volatile("" : "+v"(grp16[b]), "+v"(sel2[b])); // keeps the masks here: one extract and one permute per step below
         }
-        // Chains of NBT matrix instructions, one per u (points 4i + u of the 32 lane slots), two
+        // Chains of NS matrix instructions, one per u (points 4i + u of the 32 lane slots), two
         // at a time: a chain's next instruction needs the previous one's result, so two chains
-        // take turns (and the SIMD's other wave fills what is left). The one-hot operands of a
+        // take turns (and the SIMD's other wave fills what is left). The pattern operands of a
         // step are read from LDS two steps ahead; scheduling barriers keep that order.
-        auto read_a = [&](int u, int s) -> v4i {
-            const uint32_t o = (w_cur[s] >> (8 * u)) & 0xffu;
-            return *(const v4i *)((const unsigned char *)onehot + o);
+        struct Pattern { v4i a; int idx; };
+        auto read_a = [&](int u, int s) -> Pattern {
+            const uint32_t o = (grp16[s] >> (8 * u)) & 0xffu;
+            return Pattern{*(const v4i *)((const unsigned char *)pat_tab + o),
+                           (int)__builtin_amdgcn_perm(sel2[s], sel2[s], 0x01010101u * (uint32_t)u)};
         };
 #pragma unroll
         for (int u0 = 0; u0 < 4; u0 += 2) {
             constexpr int kAhead = 2; // steps between an operand's LDS read and its use
-            v4i abuf[kAhead + 1][2];
+            Pattern abuf[kAhead + 1][2];
             v16i acc[2];
 #pragma unroll
             for (int t = 0; t < kAhead; ++t) {
@@ -396,14 +420,15 @@ adc_mfma_scan_kernel(const ScanParams p)
                 for (int a = 0; a < 2; ++a) abuf[t][a] = read_a(u0 + a, t);
             }
 #pragma unroll
-            for (int s = 0; s < NBT; ++s) {
+            for (int s = 0; s < NS; ++s) {
 #pragma unroll
                 for (int a = 0; a < 2; ++a) {
+                    const Pattern &pa = abuf[s % (kAhead + 1)][a];
                     if (s == 0)
-                        acc[a] = __builtin_amdgcn_mfma_i32_32x32x32_i8(abuf[0][a], bq[0], v16i{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, 0, 0, 0);
+                        acc[a] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(pa.a, bq[0], v16i{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, pa.idx, 0, 0);
                     else
-                        acc[a] = __builtin_amdgcn_mfma_i32_32x32x32_i8(abuf[s % (kAhead + 1)][a], bq[s], acc[a], 0, 0, 0);
-                    if (s + kAhead < NBT) abuf[(s + kAhead) % (kAhead + 1)][a] = read_a(u0 + a, s + kAhead);
+                        acc[a] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(pa.a, bq[s], acc[a], pa.idx, 0, 0);
+                    if (s + kAhead < NS) abuf[(s + kAhead) % (kAhead + 1)][a] = read_a(u0 + a, s + kAhead);
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -448,7 +473,7 @@ adc_mfma_scan_kernel(const ScanParams p)
             }
         }
 #pragma unroll
-        for (int b = 0; b < NBT; ++b) w_cur[b] = w_nxt[b];
+        for (int b = 0; b < NS; ++b) w_cur[b] = w_nxt[b];
     }
     if (store) return;
 
