@@ -201,7 +201,11 @@ def main():
     prefiltered = bits == 4 and not n_leaves and B >= 16 and nb in (8, 13, 25, 32) and M <= 64
     n_pad = float((n + 255) // 256 * 256)
     b_pad = float((B + 31) // 32 * 32)
-    mfma_ops = 2.0 * n_pad * b_pad * nb * 32  # 32 points x 32 queries x 32 positions per instruction, NB per (32, 32)
+    # the sparse matrix instruction multiplies 32 points x 32 queries over 32 stored positions (64 logical ones: two
+    # code bytes, four subspaces); ceil(NB / 2) instructions per (32, 32). Counted: the multiply-adds it executes,
+    # which is what the dense int8 peak prices; the dense contraction it stands for has twice as many.
+    steps_per_pair = (nb + 1) // 2
+    mfma_ops = 2.0 * n_pad * b_pad * steps_per_pair * 32
 
     def direct_roofline(ms):
         adds = (2.0 if nib_tile else 1.0) * nb * scanned * B
@@ -233,11 +237,11 @@ def main():
         # partitioned index: the (query, leaf) pairs regrouped by leaf, leaves scanned on the matrix cores;
         # the scan stage also holds the bounds pass over every query's best leaves and the regrouping
         unverified = idx.debug_unverified_queries(reasons=True)
-        ops = 2.0 * scanned * B * nb * 32
+        ops = 2.0 * scanned * B * steps_per_pair * 32
         batch_roof = {"bound": "mfma", "achieved": ops / (scan_ms * 1e-3) / 1e12, "peak": MFMA_I8_PEAK_TOPS, "unit": "TOP/s",
                       "traffic": None, "kernel": "adc_mfma_scan_kernel<%d,false>" % nb, "avg_launch_ms": scan_ms,
-                      "note": "int8 multiply-adds of the scan over leaves (32 queries per leaf and work item); the stage "
-                              "time also covers the bounds pass (adc_scan_kernel<1,...,1> over each query's best leaves) "
+                      "note": "int8 multiply-adds executed by the scan over leaves (sparse instruction, 32 queries per leaf and work item); the stage "
+                              "time also covers the bounds pass (leaf_bound_kernel over each query's best leaves) "
                               "and the regrouping of the (query, leaf) pairs",
                       "queries_scanned_again": unverified[0]}
         batch_roof["frac"] = batch_roof["achieved"] / batch_roof["peak"]
@@ -249,10 +253,11 @@ def main():
                       "unit": "TOP/s", "traffic": (0.32e9 + 0.05e9) if (glove_default and B == 10000) else None,
                       "kernel": "adc_mfma_scan_kernel<%d,false>" % nb,
                       "launches_per_step": launches, "avg_launch_ms": scan_ms / launches,
-                      "note": "int8 multiply-adds issued by the candidate scan over the 8-bit tables (16 per useful "
-                              "table add: one-hot operand), per step: a launch over a sample of the blocks that "
-                              "guesses the bounds, then the launch over all blocks; the fp32 scores are formed "
-                              "for the kept points only",
+                      "note": "int8 multiply-adds executed by the candidate scan over the 8-bit tables "
+                              "(v_smfmac_i32_32x32x64_i8: the one-hot operand is 2:4 sparse, so an instruction covers 64 "
+                              "positions with 32 multiply-adds per output; 8 executed per useful table add), per step: a "
+                              "launch over a sample of the blocks that guesses the bounds, then the launch over all "
+                              "blocks; the fp32 scores are formed for the kept points only",
                       "queries_scanned_again_with_fp32_tables": unverified[0],
                       "of_which_too_many_kept_or_bound_too_high_or_other": unverified[1:]}
         batch_roof["frac"] = batch_roof["achieved"] / batch_roof["peak"]
@@ -274,12 +279,12 @@ def main():
     log("[bench] u8   batch %d: %.0f q/s, stages(ms) %s" % (B, qps8, stage8_ms))
     u8_roof = None
     if bits == 4 and not n_leaves and B >= 16 and nb in (8, 13, 25, 32):
-        # one-hot contraction on int8 MFMA: 32 points x 32 queries x 32 positions per instruction,
-        # two subspaces (16 positions each) per instruction, NB instructions per (32 points, 32 queries)
+        # one-hot contraction on the sparse int8 matrix instruction: 32 points x 32 queries, four subspaces (64
+        # positions, 32 of them stored) per instruction, ceil(NB / 2) instructions per (32 points, 32 queries)
         u8_roof = {"bound": "mfma", "achieved": ops_step / (stage8_ms["scan"] * 1e-3) / 1e12, "peak": MFMA_I8_PEAK_TOPS,
                    "unit": "TOP/s", "kernel": "adc_mfma_scan_kernel<%d,false>" % nb,
                    "launches_per_step": launches, "avg_launch_ms": stage8_ms["scan"] / launches, "traffic": None,
-                   "note": "int8 multiply-adds issued; 16 of them per useful table add (one-hot operand)"}
+                   "note": "int8 multiply-adds executed (sparse instruction); 8 of them per useful table add (one-hot operand)"}
         u8_roof["frac"] = u8_roof["achieved"] / u8_roof["peak"]
 
     # ---- timed region 2: single queries (the HBM-bound regime) ---------------------------------

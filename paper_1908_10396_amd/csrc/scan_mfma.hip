@@ -3,18 +3,31 @@
 // With 16 codewords per subspace the table sum  sum_m Q[q][m][code[n][m]]  is a dense
 // contraction of a one-hot matrix with the tables: row n of A has, for every subspace,
 // sixteen 0/1 bytes with the 1 at the point's code; column q of B holds the sixteen
-// table bytes of every subspace. v_mfma_i32_32x32x32_i8 multiplies 32 points by 32
-// queries over 32 such positions (two subspaces: lanes 0-31 carry one, lanes 32-63 the
-// other) and accumulates exact 32-bit integers, so the result is the integer sum the
-// 8-bit path is defined by, bit for bit. Tables are biased by -128 to fit the signed
-// operand; the bias, 128 per subspace, is added back when a key is made.
+// table bytes of every subspace. A one-hot row has one non-zero in sixteen positions, so
+// it fits the 2:4 structured sparsity of v_smfmac_i32_32x32x64_i8: that instruction
+// multiplies 32 points by 32 queries over 64 positions (four subspaces, two code bytes)
+// in the time the dense instruction takes for 32, from a compressed A operand (for every
+// group of four positions two values, and two bits each that say where in the group they
+// sit) and accumulates exact 32-bit integers, so the result is the integer sum the 8-bit
+// path is defined by, bit for bit. Tables are biased by -128 to fit the signed operand;
+// the bias, 128 per subspace, is added back when a key is made.
 //
-// One wave owns 32 queries and a chunk of the blocks. Its B operands (25 registers
-// of 16 bytes for 50 subspaces) stay in registers for the whole scan; the A operand
-// of a (point, subspace) is one 16-byte read from a 256-byte LDS table of the sixteen
-// one-hot patterns, addressed by the code -- no bank conflicts, since the patterns
-// cover every bank once. The order of the sum does not matter (integers), so any
-// pairing of operand positions with subspaces is valid as long as A and B agree.
+// Operand layout of the instruction (one lane: row or column lane % 32, half lane / 32):
+// A, 16 compressed bytes per lane, bytes 0-7 pair with the B lanes of half 0, bytes 8-15 with
+// those of half 1, in both cases with B bytes 16 * (A's half) .. + 15: compressed bytes 2g and
+// 2g + 1 are the two values of the group of B bytes 4g .. 4g + 3, and bits 2i, 2i + 1 of the
+// lane's index operand give the position of compressed byte i inside its group. Nothing
+// requires the two positions of a group to differ or to be ordered; a value of 0 contributes
+// nothing wherever its position points.
+//
+// One wave owns 32 queries and a chunk of the blocks. Its B operands (13 register groups
+// of 32 bytes for 50 subspaces) stay in registers for the whole scan. Lanes 0-31 take the
+// even code bytes of their four points, lanes 32-63 the odd ones; the A operand of a
+// (point, code byte) is one 16-byte read from a 256-byte LDS table of the sixteen value
+// patterns (which groups hold the 1 of the low and of the high nibble; no bank conflicts,
+// the patterns cover every bank once), and its index operand is the code byte itself copied
+// to all four bytes (one permute). The order of the sum does not matter (integers), so any
+// pairing of operand positions with table entries is valid as long as A and B agree.
 //
 // A lane ends up with the scores of 16 points for one query (lanes l and l + 32 share
 // query l % 32). Scores above the query's threshold go to a lane-private pending
@@ -218,19 +231,22 @@ template <int NBT, bool STORE>
 __global__ void __launch_bounds__(kMfmaWaves * 64, 2)
 adc_mfma_scan_kernel(const ScanParams p)
 {
-    // entry t = g0 + 4 * g1, 16 bytes: the compressed one-hot patterns of a code byte whose low nibble lies in
-    // group g0 (codes 4 g0 .. 4 g0 + 3) and whose high nibble lies in group g1: bytes 0-7 for the low nibble, a 1
-    // in the first slot of group g0; bytes 8-15 for the high nibble, a 1 in the second slot of group g1
+    // A lane's operand is 16 compressed bytes: two halves of four groups, two slots per group; a slot holds a
+    // value and, in the index operand, which of its group's four positions the value sits at. The sixteen codes
+    // of a code byte's low nibble take the first slots of groups 0 and 2 of both halves (code 4 g + p: half g / 2,
+    // group 2 (g % 2), position p), those of its high nibble the first slots of groups 1 and 3. The index operand
+    // has one nibble per group (first slot's position in its low two bits): even nibbles belong to the low code
+    // nibble, odd ones to the high one, so the code byte itself, copied to all four bytes, is the index operand.
+    // Entry t = g0 + 4 * g1 of this table is the pattern of values for a byte with groups g0 and g1.
     __shared__ __align__(16) uint32_t pat_tab[64];
     extern __shared__ __align__(16) unsigned char dyn_smem[]; // [waves][64 lanes][kMfmaPend] 32-bit keys
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6); // uniform: block and chunk arithmetic stays scalar
     if (threadIdx.x < 16) {
         const int t = threadIdx.x, g0 = t & 3, g1 = t >> 2;
-        const uint32_t lo = 1u << (16 * (g0 & 1)), hi = 1u << (8 + 16 * (g1 & 1));
-        pat_tab[4 * t + 0] = g0 < 2 ? lo : 0u;
-        pat_tab[4 * t + 1] = g0 < 2 ? 0u : lo;
-        pat_tab[4 * t + 2] = g1 < 2 ? hi : 0u;
-        pat_tab[4 * t + 3] = g1 < 2 ? 0u : hi;
+        const int b0 = 8 * (g0 >> 1) + 4 * (g0 & 1), b1 = 8 * (g1 >> 1) + 4 * (g1 & 1) + 2; // compressed bytes that hold a 1
+        for (int wd = 0; wd < 4; ++wd)
+            pat_tab[4 * t + wd] = (b0 / 4 == wd ? 1u << (8 * (b0 % 4)) : 0u) | (b1 / 4 == wd ? 1u << (8 * (b1 % 4)) : 0u);
     }
     __syncthreads();
     constexpr int NS = (NBT + 1) / 2; // matrix instructions per chain: two code bytes (four subspaces) each
@@ -267,21 +283,23 @@ adc_mfma_scan_kernel(const ScanParams p)
     const int off = 128 * p.M;
     constexpr bool store = STORE;
 
-    // table operands: step s covers subspaces 4s .. 4s + 3; this lane's first sixteen bytes meet the
-    // patterns of lanes 0-31 (code byte 2s), its last sixteen those of lanes 32-63 (code byte 2s + 1),
-    // lanes 0-31 here the low nibbles' (even subspaces), lanes 32-63 the high nibbles'
+    // table operands: step s covers subspaces 4s .. 4s + 3. This lane's first sixteen bytes meet the patterns
+    // of lanes 0-31 (code byte 2s), its last sixteen those of lanes 32-63 (code byte 2s + 1); of each, bytes
+    // 0-3 and 8-11 are the entries 8h .. 8h + 7 of the low nibble's table, bytes 4-7 and 12-15 those of the high
+    // nibble's (the layout of the patterns above)
     v8i bq[NS];
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
-        uint4 r[2];
+        uint2 r[4]; // [code byte][nibble]
 #pragma unroll
-        for (int c = 0; c < 2; ++c) {
-            const int row = 4 * s + 2 * c + h;
-            r[c] = make_uint4(0x80808080u, 0x80808080u, 0x80808080u, 0x80808080u); // -> 0
-            if (live && row < p.M) r[c] = *(const uint4 *)(p.lut8 + ((size_t)q * p.M + row) * 16);
+        for (int c = 0; c < 4; ++c) {
+            const int row = 4 * s + c;
+            r[c] = make_uint2(0x80808080u, 0x80808080u); // -> 0
+            if (live && row < p.M) r[c] = *(const uint2 *)(p.lut8 + ((size_t)q * p.M + row) * 16 + 8 * h);
+            r[c].x ^= 0x80808080u;
+            r[c].y ^= 0x80808080u;
         }
-        bq[s] = v8i{(int)(r[0].x ^ 0x80808080u), (int)(r[0].y ^ 0x80808080u), (int)(r[0].z ^ 0x80808080u), (int)(r[0].w ^ 0x80808080u),
-                    (int)(r[1].x ^ 0x80808080u), (int)(r[1].y ^ 0x80808080u), (int)(r[1].z ^ 0x80808080u), (int)(r[1].w ^ 0x80808080u)};
+        bq[s] = v8i{(int)r[0].x, (int)r[1].x, (int)r[0].y, (int)r[1].y, (int)r[2].x, (int)r[3].x, (int)r[2].y, (int)r[3].y};
     }
 
     uint32_t *my_lists = nullptr; // [32 queries][C] 32-bit keys
@@ -356,20 +374,19 @@ adc_mfma_scan_kernel(const ScanParams p)
     const int64_t stride = p.block_stride > 1 ? p.block_stride : 1;
     const int64_t n_half = end > first ? 2 * ((end - first + stride - 1) / stride) : 0; // half blocks to visit
     const int32_t id_base = (int32_t)(first * kBlockPoints); // ids inside keys count from here
-    // lane (j, h) takes code bytes h, h + 2, ... of the four points of lane slot H*32 + j of a block's rows
-    auto plane_off = [](int b) -> int { // byte plane b of a block: offset of slot 0's word
-        return b < 4 * (NBT / 4) ? (b / 4) * 1024 + (b % 4) * 4 : (NBT / 4) * 1024 + (b - 4 * (NBT / 4)) * 256;
-    };
+    // lane (j, h) takes code bytes h, h + 2, ... of the four points of lane slot H*32 + j of a block's rows:
+    // a uniform base per half block, this lane's offsets (rows of four byte planes, 16 bytes per slot; then
+    // single planes, 4 bytes per slot), and a constant per byte
+    const uint32_t lane_row = 16u * (uint32_t)j + 4u * (uint32_t)h, lane_tail = 4u * (uint32_t)j + 256u * (uint32_t)h;
     auto load_half = [&](uint32_t (&w)[NS], int64_t hb) {
         const uint8_t *base = p.codes + (size_t)(hb >> 1) * 256 * NBT;
-        const int slot = (int)(hb & 1) * 32 + j;
+        const uint8_t *base_row = base + (hb & 1) * 512, *base_tail = base + (NBT / 4) * 1024 + (hb & 1) * 128;
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
-            const int b0 = 2 * s, b1 = 2 * s + 1;
-            const int stride0 = b0 < 4 * (NBT / 4) ? 16 : 4, stride1 = b1 < 4 * (NBT / 4) ? 16 : 4; // per slot
-            const int o0 = plane_off(b0) + slot * stride0, o1 = plane_off(b1) + slot * stride1;
-            if (b1 < NBT) w[s] = *(const uint32_t *)(base + (h ? o1 : o0));
-            else w[s] = h ? 0u : *(const uint32_t *)(base + o0); // no such byte: code 0 against a zero table
+            const int b0 = 2 * s; // the byte of lanes 0-31; lanes 32-63 take b0 + 1, in the same row or the next plane
+            if (b0 < 4 * (NBT / 4)) w[s] = *(const uint32_t *)(base_row + ((b0 / 4) * 1024 + (b0 % 4) * 4) + lane_row);
+            else if (b0 + 1 < NBT) w[s] = *(const uint32_t *)(base_tail + (b0 - 4 * (NBT / 4)) * 256 + lane_tail);
+            else w[s] = h ? 0u : *(const uint32_t *)(base_tail + (b0 - 4 * (NBT / 4)) * 256 + lane_tail); // no such byte: code 0 against a zero table
         }
     };
 
@@ -387,17 +404,12 @@ adc_mfma_scan_kernel(const ScanParams p)
             thr = thr_of();
             nxt_bound = __hip_atomic_load(p.thr_shared + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-        // per code byte (low nibble 4 g0 + p0, high nibble 4 g1 + p1): the offset 16 (g0 + 4 g1) of its pattern
-        // entry, and p0 + 4 p1 in both nibbles of a byte: copied to all four bytes that is the index operand
-        // (every first slot selects p0, every second slot p1; only the slots that hold a 1 matter)
-        uint32_t grp16[NS], sel2[NS];
+        // per code byte (low nibble 4 g0 + p0, high nibble 4 g1 + p1): the offset 16 (g0 + 4 g1) of its pattern entry
+        uint32_t grp16[NS];
 #pragma unroll
         for (int b = 0; b < NS; ++b) {
-            const uint32_t w = w_cur[b];
-            grp16[b] = ((w << 2) & 0x30303030u) | (w & 0xc0c0c0c0u);
-            const uint32_t v = (w & 0x03030303u) | ((w >> 2) & 0x0c0c0c0cu);
-            sel2[b] = v | (v << 4);
-            asm volatile("" : "+v"(grp16[b]), "+v"(sel2[b])); // keeps the masks here: one extract and one permute per step below
+            grp16[b] = ((w_cur[b] << 2) & 0x30303030u) | (w_cur[b] & 0xc0c0c0c0u);
+            asm volatile("" : "+v"(grp16[b])); // keeps the mask here: one extract per step below
         }
         // Chains of NS matrix instructions, one per u (points 4i + u of the 32 lane slots), two
         // at a time: a chain's next instruction needs the previous one's result, so two chains
@@ -407,7 +419,7 @@ adc_mfma_scan_kernel(const ScanParams p)
         auto read_a = [&](int u, int s) -> Pattern {
             const uint32_t o = (grp16[s] >> (8 * u)) & 0xffu;
             return Pattern{*(const v4i *)((const unsigned char *)pat_tab + o),
-                           (int)__builtin_amdgcn_perm(sel2[s], sel2[s], 0x01010101u * (uint32_t)u)};
+                           (int)__builtin_amdgcn_perm(w_cur[s], w_cur[s], 0x01010101u * (uint32_t)u)};
         };
 #pragma unroll
         for (int u0 = 0; u0 < 4; u0 += 2) {
