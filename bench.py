@@ -60,7 +60,8 @@ def main():
     ap.add_argument("--n", type=int, default=0, help="override the number of points (debugging)")
     ap.add_argument("--b1-steps", type=int, default=2000)
     ap.add_argument("--recall-queries", type=int, default=1000)
-    ap.add_argument("--oracle-queries", type=int, default=96)
+    ap.add_argument("--oracle-queries", type=int, default=0,
+                    help="queries of the CPU baseline sample (default: about 15 s of oracle work on 16 threads)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain device copies of the datapoint array (known size) so that "
@@ -349,7 +350,9 @@ def main():
     parity = None
     if not args.no_cpu_baseline and x is not None:
         import oracle
-        no = min(args.oracle_queries, B)
+        # the oracle does about 1e2 queries/s at the Glove shape on 16 threads; its time goes with points x subspaces
+        auto = int(1536 * (1183514.0 * 50.0) / max(1.0, scanned * M))
+        no = min(args.oracle_queries if args.oracle_queries > 0 else max(16, auto), B)
         cb = idx.get_codebooks()
         codes = unpack4(idx.get_codes(), M) if bits == 4 else idx.get_codes()
         okw = {}
