@@ -224,15 +224,17 @@ def main():
         return r
 
     fp32_direct = None
-    # the matrix-core scan takes two launches per step when the index is large enough for a sample (the
-    # library's rule: chunks of at least 256 blocks): 16 blocks per chunk first, then everything
+    # the matrix-core scan takes two launches per step unless the chunks are very short (the library's rule:
+    # at least 4 blocks): about one block in 32 of every chunk first (2 to 16 per chunk), then everything
     n_blocks = (n + 255) // 256
     n_tiles32 = (B + 31) // 32
     chunks = max(1, min(2048 // n_tiles32, 256, n_blocks // 4))
     bpc = -(-n_blocks // chunks)
-    sampled = bpc >= 256
+    sampled = bpc >= 4
     launches = 2 if sampled else 1
-    ops_step = mfma_ops * (1.0 + (16.0 / bpc if sampled else 0.0))
+    per_chunk = max(2, min(16, (bpc + 31) // 32))
+    visited = -(-bpc // max(1, bpc // per_chunk))
+    ops_step = mfma_ops * (1.0 + (float(visited) / bpc if sampled else 0.0))
     grouped = bool(n_leaves) and bits == 4 and B >= 64 and nb in (8, 13, 25, 32) and M <= 64 and 16 <= Lp <= 512
     if grouped:
         # partitioned index: the (query, leaf) pairs regrouped by leaf, leaves scanned on the matrix cores;

@@ -543,15 +543,18 @@ void scan_mfma_plan(int B, int64_t n_blocks, int target_waves, ScanParams *p)
     p->group = (int32_t)std::max<int64_t>(1, std::min<int64_t>(16, std::min<int64_t>(resident, p->n_chunks)));
 }
 
-// The sampling launch for a fixed-bound scan planned in `full`: the same queries and chunks, 16
-// blocks of every chunk at equal distances, lists of r keys (see below). Returns
-// false when the index is too small for a sample to say much (then the caller scans with lists).
+// The sampling launch for a fixed-bound scan planned in `full`: the same queries and chunks, a few
+// blocks of every chunk at equal distances (about one in 32, at most 16 per chunk), lists of r keys
+// (see below). Returns false when the chunks are too short for that (then the caller scans with lists).
 bool scan_mfma_sample_plan(const ScanParams &full, ScanParams *sample)
 {
-    const int64_t per_chunk = 16;
-    if (full.scores_out != nullptr || full.blocks_per_chunk < 16 * per_chunk) return false;
+    const int64_t bpc = full.blocks_per_chunk;
+    if (full.scores_out != nullptr || bpc < 4) return false;
+    const int64_t per_chunk = std::max<int64_t>(2, std::min<int64_t>(16, (bpc + 31) / 32));
+    const int64_t stride = bpc / per_chunk; // >= 2
+    const int64_t visited = (bpc + stride - 1) / stride;
     *sample = full;
-    sample->block_stride = (int32_t)(full.blocks_per_chunk / per_chunk);
+    sample->block_stride = (int32_t)stride;
     sample->bounds_only = 0;
     sample->fixed_bound = 0;
     sample->cand_keys = nullptr;
@@ -560,7 +563,7 @@ bool scan_mfma_sample_plan(const ScanParams &full, ScanParams *sample)
     // mu of the R best of the index fall into the sample on average (Poisson); the r-th best of the
     // sample is below the R-th best of the index unless r or more of them do: r = mu + 5 sigma + 1
     // (a query for which that still happens costs a second scan, a few hundred microseconds per batch)
-    const double mu = (double)full.R * (double)per_chunk / (double)full.blocks_per_chunk;
+    const double mu = (double)full.R * (double)visited / (double)bpc;
     int r = std::max(8, (int)std::ceil(mu + 5.0 * std::sqrt(mu) + 1.0));
     if (r > 64 * kMfmaMaxNs) return false;
     sample->R = r;

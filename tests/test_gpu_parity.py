@@ -211,6 +211,33 @@ def test_fp32_batches_scan_against_sampled_bounds(variant):
         np.testing.assert_array_equal(sc.cpu().numpy(), os_)
 
 
+@pytest.mark.parametrize("nq", [16, 100, 700])
+def test_mid_size_batches_sample_short_chunks(nq):
+    # Few queries mean many short chunks (here 5 to 37 blocks each, default launch shape): the candidate scan
+    # still takes its bounds from a sample (two or more blocks of every chunk); with lists every query would
+    # keep more points than the refinement holds and be scanned again. Results equal the oracle's, and
+    # ordinary queries are not handed back.
+    rng = np.random.default_rng(77 + nq)
+    n, d, M, bits = 300_000, 100, 50, 4
+    x = unit_rows(rng, n, d)
+    q = unit_rows(rng, nq, d)
+    idx = avq.Index(d, M, bits, T=0.2, kmeans_iters=3, encode_passes=1, seed=9)
+    xd = dev(x)
+    idx.train(xd[:20_000])
+    idx.encode(xd)
+    cb = idx.get_codebooks()
+    codes = unpack_codes(idx.get_codes(), M, bits)
+    qs = q[:min(nq, 48)]   # the oracle's share
+    for k, R in ((10, 100), (10, 300)):
+        for lut_mode in (avq.LUT_F32, avq.LUT_U8):
+            ids, sc = idx.search(dev(q), k, R, lut_mode)
+            if lut_mode == avq.LUT_F32:
+                assert idx.debug_unverified_queries() <= max(1, nq // 50)
+            oi, os_ = oracle.search(x, cb, codes, bits, qs, k, R, lut_mode)
+            np.testing.assert_array_equal(ids.cpu().numpy()[:len(qs)], oi)
+            np.testing.assert_array_equal(sc.cpu().numpy()[:len(qs)], os_)
+
+
 @pytest.mark.parametrize("n,d,M,nq", [(280_001, 100, 50, 40), (300_300, 100, 25, 33), (270_000, 98, 49, 17)])
 def test_fp32_batches_sampled_bounds_other_code_sizes(n, d, M, nq):
     # the same two-launch candidate scan for 25, 13 (odd M: a zero table at the end) and a
