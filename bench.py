@@ -235,7 +235,8 @@ def main():
     per_chunk = max(2, min(16, (bpc + 31) // 32))
     visited = -(-bpc // max(1, bpc // per_chunk))
     ops_step = mfma_ops * (1.0 + (float(visited) / bpc if sampled else 0.0))
-    grouped = bool(n_leaves) and bits == 4 and B >= 64 and nb in (8, 13, 25, 32) and M <= 64 and 16 <= Lp <= 512
+    grouped = (bool(n_leaves) and bits == 4 and B >= 64 and B * Lp >= 131072 and nb in (8, 13, 25, 32) and M <= 64
+               and 16 <= Lp <= 512)   # the library's rule
     if grouped:
         # partitioned index: the (query, leaf) pairs regrouped by leaf, leaves scanned on the matrix cores;
         # the scan stage also holds the bounds pass over every query's best leaves and the regrouping

@@ -153,9 +153,9 @@ int avq_update_codebooks(avq_index *idx, const float *x, int64_t n, int32_t max_
  *    that scan, also when the search itself uses 8-bit tables, does not keep
  *    sorted lists: it compares against a bound guessed from a sample of the
  *    points and checked afterwards; a query whose guess fails is scanned
- *    again, so results never depend on it.) Batches of 64 queries or more
- *    that probe 16 leaves or more of a partitioned index of 4-bit codes are
- *    regrouped by leaf: a leaf's codes are scored once per 32 of the queries
+ *    again, so results never depend on it.) Large batches on a partitioned
+ *    index of 4-bit codes (131072 (query, probed leaf) pairs or more, 16
+ *    leaves or more per query; see avq_set_tuning) are regrouped by leaf: a leaf's codes are scored once per 32 of the queries
  *    that probe it (8-bit tables, matrix cores), every point whose estimate
  *    fma(sum, scale, bias + <q, center>) can reach the R-th best score of the
  *    query's first few leaves is kept, and the kept points are scored per
@@ -264,7 +264,9 @@ double avq_eta(int32_t d, double T, double norm, int32_t eta_mode);
  * index: how many of a query's best leaves are scanned first, one query at a
  * time, for the bound that the scan of all leaves, regrouped by leaf, runs
  * against; "scan_prefilter" = 1 also switches that regrouped scan off,
- * "prefilter_cap" is its kept keys per query).
+ * "prefilter_cap" is its kept keys per query), "group_min_pairs" (queries x
+ * probed leaves from which a batch on a partitioned index is regrouped by
+ * leaf; built in: 131072, below that one workgroup per query is faster).
  * Results never depend on these. Returns
  * AVQ_EINVAL for an unknown name. */
 int avq_set_tuning(avq_index *idx, const char *name, int32_t value);

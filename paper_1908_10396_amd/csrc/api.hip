@@ -63,6 +63,7 @@ struct avq_index {
     int tune_prefilter = 0; // 0 = fp32-table batches go through the 8-bit-table scan where it applies, 1 = never,
                             // 2 = as 0 but odd queries always take the plain scan afterwards (exercises that branch)
     int tune_bound_leaves = 0; // leaves per query that supply the bound of the grouped scan over leaves, 0 = built-in
+    int tune_group_min = 0; // (query, leaf) pairs from which a batch on a partitioned index is regrouped by leaf; 0 = built in
     int tune_sample = 0; // 0 = fp32-table batches guess the candidate scan's bounds from a sample where possible, 1 = never
     int tune_prefilter_cap = 0; // candidate keys per (query, chunk) of that scan, 0 = built-in
     DevBuf block_max, lists, refined, lut_fail, fail, cand_keys, groups, kept, fail_rows;
@@ -179,6 +180,7 @@ extern "C" int avq_set_tuning(avq_index *idx, const char *name, int32_t value)
     else if (!strcmp(name, "scan_prefilter")) idx->tune_prefilter = value;
     else if (!strcmp(name, "prefilter_cap")) idx->tune_prefilter_cap = value;
     else if (!strcmp(name, "scan_sample")) idx->tune_sample = value;
+    else if (!strcmp(name, "group_min_pairs")) idx->tune_group_min = value;
     else if (!strcmp(name, "bound_leaves")) idx->tune_bound_leaves = value;
     else { set_error("avq_set_tuning: unknown name '%s'", name); return AVQ_EINVAL; }
     return AVQ_OK;
@@ -669,7 +671,11 @@ static int search_through_candidates(avq_index *idx, const float *queries, int n
 // that the query's best few leaves supply; the kept points are scored and ranked per query.
 static bool use_grouped_leaves(const avq_index *idx, int nq, int L, int R)
 {
+    // below about 1.3e5 pairs (1,300 queries x 100 leaves) one workgroup per query is faster: regrouping, bounds and
+    // the hand-over of kept points cost a fixed 0.2 ms
+    const int64_t min_pairs = idx->tune_group_min > 0 ? idx->tune_group_min : 131072;
     return idx->tune_prefilter != 1 && idx->tune_mfma == 0 && idx->cfg.n_leaves > 0 && nq >= 64 && nq <= (1 << 16) &&
+           (int64_t)nq * L >= min_pairs &&
            scan_mfma_supported(idx->NB, idx->cfg.bits) && idx->cfg.M <= 64 && L >= 16 && L <= 512 &&
            idx->cfg.n_leaves <= (1 << 21) && idx->max_leaf_blocks <= 1024 && R <= 2048;
 }

@@ -515,11 +515,12 @@ def test_leaf_select_for_batches_matches(ivf_batch_case):
 @pytest.mark.parametrize("lut_mode", [0, 1])
 @pytest.mark.parametrize("variant", ["default", "plain", "odd_back", "small_buffers"])
 def test_partitioned_batches_grouped_by_leaf(ivf_batch_case, lut_mode, variant):
-    # batches of 64 queries or more probing 16 leaves or more: leaves scanned on the matrix cores, 32
+    # batches of 64 queries or more probing 16 leaves or more (large ones by default, any when asked): leaves scanned on the matrix cores, 32
     # queries at a time, kept points scored per query; "plain": the one-query-per-workgroup scan;
     # "odd_back" / "small_buffers": every other query, or most of them, handed back to that scan
     c = ivf_batch_case
     idx, xd = make_ivf_index(c)
+    idx.set_tuning("group_min_pairs", 1)   # regroup whatever the batch size (built in: from 131,072 pairs)
     if variant == "plain":
         idx.set_tuning("scan_prefilter", 1)
     elif variant == "odd_back":
