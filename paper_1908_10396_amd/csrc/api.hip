@@ -850,7 +850,9 @@ extern "C" int avq_search(avq_index *idx, const float *queries, int32_t nq, int3
     const int C = 64 * ns;
     const bool u8 = lut_mode == AVQ_LUT_U8;
 
-    const int small_max = idx->tune_small_batch >= 0 ? idx->tune_small_batch : 8;
+    // 4-bit codes: the block-maxima path costs about 4.5 us per query and million points, the batch scans a fixed
+    // 0.5 ms per million points up to a few hundred queries: measured crossover near 120 queries
+    const int small_max = idx->tune_small_batch >= 0 ? idx->tune_small_batch : (c.bits == 4 ? 95 : 8);
     const bool small = !ivf && nq <= small_max;
     // the single-query kernels compute short fp32 tables themselves (one launch less)
     const bool fuse_tables = small && idx->tune_small_impl == 0 && small_batch_can_fuse_tables(c.bits, c.M, c.d, u8);

@@ -147,6 +147,7 @@ def test_fp32_batches_with_flat_score_distributions(prefilter):
     idx = avq.Index(d, M, bits, T=0.2)
     idx.set_codebooks(cb)
     idx.set_database(dev(x), oracle.pack_codes(codes, bits))
+    idx.set_tuning("small_batch_max", 1)     # the batch kernels, not the block-maxima path of small batches
     idx.set_tuning("scan_prefilter", prefilter)
     for k, R in ((10, 100), (5, 0), (20, 128)):
         oi, os_ = oracle.search(x, cb, codes, bits, q, k, R, 0)
@@ -185,6 +186,7 @@ def test_fp32_batches_scan_against_sampled_bounds(variant):
     cb = idx.get_codebooks()
     codes = unpack_codes(idx.get_codes(), M, bits)
     idx.set_tuning("scan_target_wgs", 4)
+    idx.set_tuning("small_batch_max", 1)     # the batch kernels, not the block-maxima path of small batches
     if variant == "lists":
         idx.set_tuning("scan_sample", 1)
     elif variant == "odd_fail":
@@ -227,6 +229,7 @@ def test_mid_size_batches_sample_short_chunks(nq):
     idx.encode(xd)
     cb = idx.get_codebooks()
     codes = unpack_codes(idx.get_codes(), M, bits)
+    idx.set_tuning("small_batch_max", 1)     # the batch kernels also for the 16 queries
     qs = q[:min(nq, 48)]   # the oracle's share
     for k, R in ((10, 100), (10, 300)):
         for lut_mode in (avq.LUT_F32, avq.LUT_U8):
@@ -253,6 +256,7 @@ def test_fp32_batches_sampled_bounds_other_code_sizes(n, d, M, nq):
     cb = idx.get_codebooks()
     codes = unpack_codes(idx.get_codes(), M, 4)
     idx.set_tuning("scan_target_wgs", 4)
+    idx.set_tuning("small_batch_max", 1)     # the batch kernels, not the block-maxima path of small batches
     for k, R in ((10, 100), (1, 0), (10, 257)):
         for lut_mode in (avq.LUT_F32, avq.LUT_U8):
             oi, os_ = oracle.search(x, cb, codes, 4, q, k, R, lut_mode)
