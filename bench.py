@@ -265,6 +265,10 @@ def main():
                       "queries_scanned_again_with_fp32_tables": unverified[0],
                       "of_which_too_many_kept_or_bound_too_high_or_other": unverified[1:]}
         batch_roof["frac"] = batch_roof["achieved"] / batch_roof["peak"]
+        # for orientation: the dense one-hot contraction the sparse instruction stands for (twice the executed
+        # operations), and the table adds the method itself asks for (M per query and point)
+        batch_roof["dense_equivalent_frac"] = 2.0 * batch_roof["frac"] * (nb / (2.0 * steps_per_pair))
+        batch_roof["table_adds_per_s"] = float(M) * scanned * B / (scan_ms * 1e-3)
         # the same step with every point scored in fp32 (the kernel the candidate scan replaces)
         idx.set_tuning("scan_prefilter", 1)
         dt_d, stage_d = timed_batch(avq.LUT_F32, max(2, args.steps // 5))

@@ -431,6 +431,8 @@ adc_mfma_scan_kernel(const ScanParams p)
 #pragma unroll
                 for (int a = 0; a < 2; ++a) abuf[t][a] = read_a(u0 + a, t);
             }
+            // a wave inside its chains goes before one that is comparing or storing candidates (2.5 % per launch, measured)
+            __builtin_amdgcn_s_setprio(2);
 #pragma unroll
             for (int s = 0; s < NS; ++s) {
 #pragma unroll
@@ -444,6 +446,7 @@ adc_mfma_scan_kernel(const ScanParams p)
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
+            __builtin_amdgcn_s_setprio(0);
 #pragma unroll
             for (int a = 0; a < 2; ++a) {
                 // accumulator v of lane (j, h): point row 8*(v/4) + 4*h + v%4 of the 32, query j
