@@ -64,7 +64,7 @@ struct avq_index {
                             // 2 = as 0 but odd queries always take the plain scan afterwards (exercises that branch)
     int tune_bound_leaves = 0; // leaves per query that supply the bound of the grouped scan over leaves, 0 = built-in
     int tune_group_min = 0; // (query, leaf) pairs from which a batch on a partitioned index is regrouped by leaf; 0 = built in
-    int tune_sample = 0; // 0 = fp32-table batches guess the candidate scan's bounds from a sample where possible, 1 = never
+    int tune_sample = 0; // 0 = batches guess the candidate scan's bounds from a sample where possible, 1 = never, 2 = from a sample scanned with lists
     int tune_prefilter_cap = 0; // candidate keys per (query, chunk) of that scan, 0 = built-in
     DevBuf block_max, lists, refined, lut_fail, fail, cand_keys, groups, kept, fail_rows;
     // optional per-stage timing with HIP events recorded on the caller's stream
@@ -546,7 +546,7 @@ static bool use_prefilter(const avq_index *idx, int nq, int lut_mode, int R)
 // Whether the matrix-core scan of this batch would be given bounds guessed from a sample.
 static bool mfma_scan_samples(const avq_index *idx, int nq, int R, int ns)
 {
-    if (idx->tune_sample != 0) return false;
+    if (idx->tune_sample == 1) return false;
     ScanParams p, sample;
     memset(&p, 0, sizeof(p));
     p.R = R;
@@ -611,14 +611,25 @@ static int search_through_candidates(avq_index *idx, const float *queries, int n
         // guess the bounds from a sample of the index and scan against them, where the index is large
         // enough for that; otherwise the scan keeps lists and raises its bounds itself
         ScanParams sample;
-        if (idx->tune_sample == 0 && scan_mfma_sample_plan(pm, &sample)) {
-            AVQ_TRY(launch_scan_mfma(sample, st));
-            const u64 *best = sample.partial;
-            if (sample.n_chunks > 1) {
-                AVQ_TRY(launch_merge_partials(sample.partial, nq, sample.n_chunks, sample.ns, idx->cand.as<u64>(), st));
-                best = idx->cand.as<u64>();
+        if (idx->tune_sample != 1 && scan_mfma_sample_plan(pm, &sample)) {
+            // The r-th best sum of the sample. With enough waves per query it comes without lists: every wave
+            // records the best sum of each of its 32 disjoint point classes, and the r-th largest of a query's
+            // class maxima is the r-th best of the sample unless two of those fell into one class (then it is a
+            // little lower, which only keeps more points). Otherwise, or when asked, from sorted lists.
+            const int classes = sample.n_chunks * 32;
+            if (idx->tune_sample != 2 && classes >= 8 * sample.R) {
+                sample.sample_max = (uint32_t *)idx->lists.p; // the lists' scratch: no launch here keeps lists
+                AVQ_TRY(launch_scan_mfma(sample, st));
+                AVQ_TRY(launch_sample_bound(sample.sample_max, classes, sample.R, nq, pm.thr_shared, st));
+            } else {
+                AVQ_TRY(launch_scan_mfma(sample, st));
+                const u64 *best = sample.partial;
+                if (sample.n_chunks > 1) {
+                    AVQ_TRY(launch_merge_partials(sample.partial, nq, sample.n_chunks, sample.ns, idx->cand.as<u64>(), st));
+                    best = idx->cand.as<u64>();
+                }
+                AVQ_TRY(launch_list_bound(best, sample.ns, sample.R, nq, pm.thr_shared, st));
             }
-            AVQ_TRY(launch_list_bound(best, sample.ns, sample.R, nq, pm.thr_shared, st));
             pm.fixed_bound = 1;
         }
         AVQ_TRY(launch_scan_mfma(pm, st));

@@ -82,6 +82,9 @@ struct ScanParams {
     int32_t group;        // chunks per threshold group
     int32_t bounds_only;  // matrix-core kernel: publish bounds in thr_shared, write no lists (sampling launch)
     int32_t block_stride; // matrix-core kernel: > 1: visit only every block_stride-th block of a chunk
+    // matrix-core kernel, sampling launch without lists: [B][n_chunks][32] ordering values (0: none), the best sum of
+    // each of the 32 disjoint point classes (lane half x accumulator) of every wave; nothing else is written
+    uint32_t *sample_max;
     int32_t fixed_bound;  // matrix-core kernel, candidate mode: thr_shared holds bounds that are not raised; no lists
     // matrix-core kernel, candidate mode (cand_keys != NULL): every point whose sum is within
     // cand_margin[q] (< 0, or no array: 0) of the bound is appended, as a 32-bit chunk-local key, to
@@ -226,6 +229,8 @@ struct RefineCandParams {
 int launch_prefilter_margin(const float *lut, const float *scale, int M, int NB, int nq, int32_t *margin, hipStream_t st);
 int launch_refine_cand(const RefineCandParams &r, hipStream_t st);
 // bound[q] = ordering value of the r-th key of the sorted list lists[q][64*ns] (0: fewer than r keys)
+// bound[q] = the r-th largest of the S = n_chunks * 32 ordering values of query q in sample_max (0 if fewer are non-zero)
+int launch_sample_bound(const uint32_t *sample_max, int S, int r, int nq, uint32_t *bound, hipStream_t st);
 int launch_list_bound(const u64 *lists, int ns, int r, int nq, uint32_t *bound, hipStream_t st);
 // The kept keys of the matrix-core scan over a partitioned index (ScanParams::kept): per query the R
 // best by score, sorted, to out[q][64*ns]. The score of a kept point is fma(sum, scale, bias + leaf_ip)

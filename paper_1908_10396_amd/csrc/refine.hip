@@ -255,6 +255,43 @@ list_bound_kernel(const u64 *__restrict__ lists, int C, int r, int nq, uint32_t 
     if (q < nq) bound[q] = key_ord(lists[(size_t)q * C + (r - 1)]);
 }
 
+// bound[q] = the r-th largest of query q's S class maxima (ordering values below 2^14; 0 = no point), 0 if fewer
+// than r are non-zero. One wave per query: bisection, every lane counting its share.
+__global__ void __launch_bounds__(256)
+sample_bound_kernel(const uint32_t *__restrict__ smax, int S, int r, int nq, uint32_t *__restrict__ bound)
+{
+    const int lane = threadIdx.x & 63;
+    const int q = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (q >= nq) return;
+    const uint32_t *v = smax + (size_t)q * S;
+    auto count_ge = [&](uint32_t t) -> int {
+        int cn = 0;
+        for (int base = 0; base < S; base += 64) {
+            const int i = base + lane;
+            cn += __popcll(__builtin_amdgcn_ballot_w64(i < S && v[i] >= t));
+        }
+        return cn;
+    };
+    uint32_t lo = 0u;
+    if (count_ge(1u) >= r) {
+        lo = 1u;
+        uint32_t hi = 1u << 14; // count_ge(lo) >= r > count_ge(hi)
+        while (hi - lo > 1u) {
+            const uint32_t mid = (lo + hi) >> 1;
+            if (count_ge(mid) >= r) lo = mid; else hi = mid;
+        }
+    }
+    if (lane == 0) bound[q] = lo;
+}
+
+int launch_sample_bound(const uint32_t *sample_max, int S, int r, int nq, uint32_t *bound, hipStream_t st)
+{
+    if (S < 1 || r < 1) { set_error("sample bound: bad shape"); return AVQ_EINVAL; }
+    hipLaunchKernelGGL(sample_bound_kernel, dim3((nq + 3) / 4), dim3(256), 0, st, sample_max, S, r, nq, bound);
+    AVQ_HIP(hipGetLastError());
+    return AVQ_OK;
+}
+
 int launch_list_bound(const u64 *lists, int ns, int r, int nq, uint32_t *bound, hipStream_t st)
 {
     hipLaunchKernelGGL(list_bound_kernel, dim3((nq + 255) / 256), dim3(256), 0, st, lists, 64 * ns, r, nq, bound);

@@ -390,6 +390,11 @@ adc_mfma_scan_kernel(const ScanParams p)
         }
     };
 
+    // sampling launch without lists (store variant only): the best sum of each of this lane's 16 point classes
+    constexpr int32_t kNone = -0x7fffffff;
+    int32_t smax[16];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) smax[v] = kNone;
     uint32_t nxt_bound = bound_ord; // the shared bound, read one block ahead of its use
     uint32_t w_cur[NS], w_nxt[NS];
     auto half_of = [&](int64_t i) -> int64_t { return 2 * (first + (i >> 1) * stride) + (i & 1); };
@@ -452,11 +457,21 @@ adc_mfma_scan_kernel(const ScanParams p)
                 // accumulator v of lane (j, h): point row 8*(v/4) + 4*h + v%4 of the 32, query j
                 const int32_t id0 = (int32_t)(blk * 256) + H * 128 + 16 * h + u0 + a;
                 if constexpr (store) {
+                    if (p.sample_max != nullptr) {
+                        const bool whole = (blk + 1) * 256 <= (int64_t)p.n_valid; // no padding slots in this block
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const int32_t id = id0 + 32 * (v / 4) + 4 * (v % 4);
-                        if (live && id < p.n_valid)
-                            ((int32_t *)p.scores_out)[(size_t)q * p.score_stride + id] = acc[a][v] + off;
+                        for (int v = 0; v < 16; ++v) {
+                            int32_t sum = acc[a][v];
+                            if (!whole && id0 + 32 * (v / 4) + 4 * (v % 4) >= p.n_valid) sum = kNone;
+                            smax[v] = sum > smax[v] ? sum : smax[v];
+                        }
+                    } else {
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) {
+                            const int32_t id = id0 + 32 * (v / 4) + 4 * (v % 4);
+                            if (live && id < p.n_valid)
+                                ((int32_t *)p.scores_out)[(size_t)q * p.score_stride + id] = acc[a][v] + off;
+                        }
                     }
                 } else {
                     // Common case, one compare and one branch per accumulator: no lane has a candidate.
@@ -490,7 +505,14 @@ adc_mfma_scan_kernel(const ScanParams p)
 #pragma unroll
         for (int b = 0; b < NS; ++b) w_cur[b] = w_nxt[b];
     }
-    if (store) return;
+    if (store) {
+        if (p.sample_max != nullptr && live) {
+            uint32_t *dst = p.sample_max + ((size_t)q * p.n_chunks + chunk) * 32 + 16 * h;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) dst[v] = smax[v] == kNone ? 0u : (uint32_t)(smax[v] + off + 1);
+        }
+        return;
+    }
 
     // drain, then hand the lists over: partial[q][chunk][C]
     {
@@ -563,6 +585,7 @@ bool scan_mfma_sample_plan(const ScanParams &full, ScanParams *sample)
     sample->cand_keys = nullptr;
     sample->cand_cnt = nullptr;
     sample->cand_margin = nullptr;
+    sample->sample_max = nullptr;
     // mu of the R best of the index fall into the sample on average (Poisson); the r-th best of the
     // sample is below the R-th best of the index unless r or more of them do: r = mu + 5 sigma + 1
     // (a query for which that still happens costs a second scan, a few hundred microseconds per batch)
@@ -617,19 +640,19 @@ int launch_scan_mfma(const ScanParams &p, hipStream_t st)
         set_error("scan: a fixed-bound scan needs bounds and candidate buffers");
         return AVQ_EINVAL;
     }
-    if (p.scores_out == nullptr && !p.fixed_bound &&
+    if (p.scores_out == nullptr && p.sample_max == nullptr && !p.fixed_bound &&
         (p.lists_ws == nullptr || p.thr_shared == nullptr || p.kth_shared == nullptr || (p.partial == nullptr && !p.bounds_only) ||
          p.group < 1)) {
         set_error("scan: matrix-core kernel needs its scratch buffers");
         return AVQ_EINVAL;
     }
-    if (p.R < 1 || p.R > 64 * p.ns) { set_error("scan: R does not fit the lists"); return AVQ_EINVAL; }
+    if (p.sample_max == nullptr && (p.R < 1 || p.R > 64 * p.ns)) { set_error("scan: R does not fit the lists"); return AVQ_EINVAL; }
     if (p.cand_keys != nullptr && (p.cand_cnt == nullptr || p.cand_cap < 128)) {
         set_error("scan: candidate mode needs counts and room for one flush");
         return AVQ_EINVAL;
     }
     if (p.blocks_per_chunk > kMfmaMaxChunkBlocks || p.M > 64) { set_error("scan: chunk or code too large for 32-bit keys"); return AVQ_EINVAL; }
-    const bool store = p.scores_out != nullptr;
+    const bool store = p.scores_out != nullptr || p.sample_max != nullptr;
     switch (p.NB) {
     case 8: return store ? launch_mfma_one<8, true>(p, st) : launch_mfma_one<8, false>(p, st);
     case 13: return store ? launch_mfma_one<13, true>(p, st) : launch_mfma_one<13, false>(p, st);

@@ -120,7 +120,7 @@ def test_search_is_deterministic_and_independent_of_launch_shape(case, lut_mode)
     tiles = (1, 4, 8) if (lut_mode == 1 or case["bits"] == 4) else (1, 4)
     for name, val in (("scan_target_wgs", 64), ("scan_target_wgs", 4096), ("scan_waves", 2),
                       ("small_batch_max", 1), ("small_batch_max", 1000), ("scan_mfma", 1), ("scan_prefilter", 1),
-                      ("scan_prefilter", 2), ("prefilter_cap", 128), ("prefilter_cap", 300), ("scan_sample", 1)) + tuple(("scan_qt", t) for t in tiles):
+                      ("scan_prefilter", 2), ("prefilter_cap", 128), ("prefilter_cap", 300), ("scan_sample", 1), ("scan_sample", 2)) + tuple(("scan_qt", t) for t in tiles):
         idx.set_tuning(name, val)
         got = [t.cpu().numpy() for t in idx.search(qd, 10, 100, lut_mode)]
         np.testing.assert_array_equal(base[0], got[0])
@@ -165,7 +165,7 @@ def test_fp32_batches_with_flat_score_distributions(prefilter):
         np.testing.assert_array_equal(sc.cpu().numpy(), os_)
 
 
-@pytest.mark.parametrize("variant", ["default", "lists", "odd_fail", "small_buffers"])
+@pytest.mark.parametrize("variant", ["default", "lists", "sample_lists", "odd_fail", "small_buffers"])
 def test_fp32_batches_scan_against_sampled_bounds(variant):
     # Large chunks (here forced by asking for few waves) make the candidate scan of fp32-table
     # batches guess its bounds from a sample of the blocks and check the guess afterwards. 6,000
@@ -189,6 +189,8 @@ def test_fp32_batches_scan_against_sampled_bounds(variant):
     idx.set_tuning("small_batch_max", 1)     # the batch kernels, not the block-maxima path of small batches
     if variant == "lists":
         idx.set_tuning("scan_sample", 1)
+    elif variant == "sample_lists":
+        idx.set_tuning("scan_sample", 2)
     elif variant == "odd_fail":
         idx.set_tuning("scan_prefilter", 2)
     elif variant == "small_buffers":
