@@ -247,7 +247,7 @@ double avq_eta(int32_t d, double T, double norm, int32_t eta_mode);
  * the most workgroups per query of the block-maxima scan), "scan_waves"
  * (waves per scan workgroup), "scan_qt" (queries per tile), "small_batch_max"
  * (v > 0: batches of fewer than v queries on a flat index take the block-maxima
- * path; 1 disables that path; built in: 96 with 4-bit codes, 9 with 8-bit codes), "small_batch_impl" (0: one fused kernel after
+ * path; 1 disables that path; built in: 36 with 4-bit codes, 9 with 8-bit codes), "small_batch_impl" (0: one fused kernel after
  * the block-maxima scan; 1: the same algorithm as three kernels), "scan_mfma"
  * (1: batches with 8-bit tables on 4-bit codes use the LDS-table scan instead
  * of the matrix-core scan; for that scan "scan_target_wgs" counts waves),
@@ -260,7 +260,8 @@ double avq_eta(int32_t d, double T, double norm, int32_t eta_mode);
  * the index; a query that needs more is scanned again with fp32 tables),
  * "scan_sample" (1: that candidate scan keeps lists and raises its bounds as
  * it goes, instead of scanning against bounds guessed from a sample of the
- * index and checked afterwards), "bound_leaves" (batches on a partitioned
+ * index and checked afterwards; 2: the sample itself is scanned with sorted
+ * lists instead of per-class maxima), "bound_leaves" (batches on a partitioned
  * index: how many of a query's best leaves are scanned first, one query at a
  * time, for the bound that the scan of all leaves, regrouped by leaf, runs
  * against; "scan_prefilter" = 1 also switches that regrouped scan off,

@@ -617,7 +617,7 @@ static int search_through_candidates(avq_index *idx, const float *queries, int n
             // class maxima is the r-th best of the sample unless two of those fell into one class (then it is a
             // little lower, which only keeps more points). Otherwise, or when asked, from sorted lists.
             const int classes = sample.n_chunks * 32;
-            if (idx->tune_sample != 2 && classes >= 8 * sample.R) {
+            if (idx->tune_sample != 2 && classes >= 8 * sample.R && classes <= 8192) {
                 sample.sample_max = (uint32_t *)idx->lists.p; // the lists' scratch: no launch here keeps lists
                 AVQ_TRY(launch_scan_mfma(sample, st));
                 AVQ_TRY(launch_sample_bound(sample.sample_max, classes, sample.R, nq, pm.thr_shared, st));
@@ -862,8 +862,8 @@ extern "C" int avq_search(avq_index *idx, const float *queries, int32_t nq, int3
     const bool u8 = lut_mode == AVQ_LUT_U8;
 
     // 4-bit codes: the block-maxima path costs about 4.5 us per query and million points, the batch scans a fixed
-    // 0.5 ms per million points up to a few hundred queries: measured crossover near 120 queries
-    const int small_max = idx->tune_small_batch >= 0 ? idx->tune_small_batch : (c.bits == 4 ? 95 : 8);
+    // 0.2 ms per million points up to a few hundred queries: measured crossover near 36 queries
+    const int small_max = idx->tune_small_batch >= 0 ? idx->tune_small_batch : (c.bits == 4 ? 35 : 8);
     const bool small = !ivf && nq <= small_max;
     // the single-query kernels compute short fp32 tables themselves (one launch less)
     const bool fuse_tables = small && idx->tune_small_impl == 0 && small_batch_can_fuse_tables(c.bits, c.M, c.d, u8);

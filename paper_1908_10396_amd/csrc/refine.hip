@@ -256,19 +256,34 @@ list_bound_kernel(const u64 *__restrict__ lists, int C, int r, int nq, uint32_t 
 }
 
 // bound[q] = the r-th largest of query q's S class maxima (ordering values below 2^14; 0 = no point), 0 if fewer
-// than r are non-zero. One wave per query: bisection, every lane counting its share.
+// than r are non-zero. Bisection over the ordering values with the maxima in registers, 32 per lane at most:
+// one wave per query (S <= 2048), or the four waves of a workgroup together (WIDE, S <= 8192; one barrier per round).
+template <bool WIDE>
 __global__ void __launch_bounds__(256)
 sample_bound_kernel(const uint32_t *__restrict__ smax, int S, int r, int nq, uint32_t *__restrict__ bound)
 {
-    const int lane = threadIdx.x & 63;
-    const int q = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (q >= nq) return;
+    __shared__ int wave_cnt[2][4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int q = WIDE ? (int)blockIdx.x : (int)blockIdx.x * 4 + wave;
+    if (q >= nq) return; // WIDE: the whole workgroup leaves
     const uint32_t *v = smax + (size_t)q * S;
-    auto count_ge = [&](uint32_t t) -> int {
+    const int first = WIDE ? threadIdx.x : lane, step = WIDE ? 256 : 64;
+    uint32_t mine[32];
+#pragma unroll
+    for (int k = 0; k < 32; ++k) {
+        const int i = first + k * step;
+        mine[k] = i < S ? v[i] : 0u;
+    }
+    int parity = 0;
+    auto count_ge = [&](uint32_t t) -> int { // t >= 1
         int cn = 0;
-        for (int base = 0; base < S; base += 64) {
-            const int i = base + lane;
-            cn += __popcll(__builtin_amdgcn_ballot_w64(i < S && v[i] >= t));
+#pragma unroll
+        for (int k = 0; k < 32; ++k) cn += __popcll(__builtin_amdgcn_ballot_w64(mine[k] >= t));
+        if (WIDE) {
+            if (lane == 0) wave_cnt[parity][wave] = cn;
+            __syncthreads();
+            cn = wave_cnt[parity][0] + wave_cnt[parity][1] + wave_cnt[parity][2] + wave_cnt[parity][3];
+            parity ^= 1;
         }
         return cn;
     };
@@ -281,13 +296,14 @@ sample_bound_kernel(const uint32_t *__restrict__ smax, int S, int r, int nq, uin
             if (count_ge(mid) >= r) lo = mid; else hi = mid;
         }
     }
-    if (lane == 0) bound[q] = lo;
+    if ((WIDE ? threadIdx.x : lane) == 0) bound[q] = lo;
 }
 
 int launch_sample_bound(const uint32_t *sample_max, int S, int r, int nq, uint32_t *bound, hipStream_t st)
 {
-    if (S < 1 || r < 1) { set_error("sample bound: bad shape"); return AVQ_EINVAL; }
-    hipLaunchKernelGGL(sample_bound_kernel, dim3((nq + 3) / 4), dim3(256), 0, st, sample_max, S, r, nq, bound);
+    if (S < 1 || S > 8192 || r < 1) { set_error("sample bound: bad shape (%d maxima)", S); return AVQ_EINVAL; }
+    if (S <= 2048) hipLaunchKernelGGL(sample_bound_kernel<false>, dim3((nq + 3) / 4), dim3(256), 0, st, sample_max, S, r, nq, bound);
+    else hipLaunchKernelGGL(sample_bound_kernel<true>, dim3(nq), dim3(256), 0, st, sample_max, S, r, nq, bound);
     AVQ_HIP(hipGetLastError());
     return AVQ_OK;
 }
