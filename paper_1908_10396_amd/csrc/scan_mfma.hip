@@ -474,17 +474,33 @@ adc_mfma_scan_kernel(const ScanParams p)
                         }
                     }
                 } else {
-                    // Common case, one compare and one branch per accumulator: no lane has a candidate.
-                    // Otherwise the lanes that have one append it to their pending buffers, which
-                    // always have room for a whole chain (ids past the end are padding).
+                    // A compare whose result decides a branch costs a wave far more than the compare itself (the
+                    // branch waits for it), so the sixteen accumulators are first folded by maxima: one compare and
+                    // one branch when no lane has a candidate in the whole chain, else one per group of four
+                    // accumulators, and one per accumulator only inside a group that has one. The lanes that have a
+                    // candidate append it to their pending buffers, which always have room for a whole chain (ids
+                    // past the end are padding).
+                    auto max4 = [](int32_t x, int32_t y, int32_t z, int32_t w) -> int32_t {
+                        const int32_t m = x > y ? x : y, n = z > w ? z : w;
+                        return m > n ? m : n;
+                    };
+                    int32_t gmax[4];
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const bool hit = acc[a][v] > thr;
-                        if (__builtin_expect(__builtin_amdgcn_ballot_w64(hit) == 0ull, 1)) continue;
-                        const int32_t id = id0 + 32 * (v / 4) + 4 * (v % 4);
-                        if (hit && id < p.n_valid) {
-                            *pend = ((uint32_t)(acc[a][v] + off + 1) << kIdBits) | (~(uint32_t)(id - id_base) & kIdMask);
-                            ++pend;
+                    for (int g = 0; g < 4; ++g) gmax[g] = max4(acc[a][4 * g], acc[a][4 * g + 1], acc[a][4 * g + 2], acc[a][4 * g + 3]);
+                    if (__builtin_expect(__builtin_amdgcn_ballot_w64(max4(gmax[0], gmax[1], gmax[2], gmax[3]) > thr) != 0ull, 0)) {
+#pragma unroll
+                        for (int g = 0; g < 4; ++g) {
+                            if (__builtin_amdgcn_ballot_w64(gmax[g] > thr) == 0ull) continue;
+#pragma unroll
+                            for (int v = 4 * g; v < 4 * g + 4; ++v) {
+                                const bool hit = acc[a][v] > thr;
+                                if (__builtin_amdgcn_ballot_w64(hit) == 0ull) continue;
+                                const int32_t id = id0 + 32 * (v / 4) + 4 * (v % 4);
+                                if (hit && id < p.n_valid) {
+                                    *pend = ((uint32_t)(acc[a][v] + off + 1) << kIdBits) | (~(uint32_t)(id - id_base) & kIdMask);
+                                    ++pend;
+                                }
+                            }
                         }
                     }
                     // a chain adds at most 16 keys to a lane: flush the queries with less room than that
