@@ -67,6 +67,7 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef __attribute__((address_space(3))) uint32_t lds_u32;
+typedef __attribute__((address_space(3))) v16i lds_v16i;
 
 constexpr int kMfmaQueries = 32; // queries per wave
 constexpr int kMfmaPend = 64;    // pending keys per lane
@@ -239,10 +240,12 @@ adc_mfma_scan_kernel(const ScanParams p)
     // nibble, odd ones to the high one, so the code byte itself, copied to all four bytes, is the index operand.
     // Entry t = g0 + 4 * g1 of this table is the pattern of values for a byte with groups g0 and g1.
     __shared__ __align__(16) uint32_t pat_tab[64];
+    __shared__ __align__(16) uint32_t zeros16[16]; // accumulators start from here: four LDS reads instead of eight register moves
     extern __shared__ __align__(16) unsigned char dyn_smem[]; // [waves][64 lanes][kMfmaPend] 32-bit keys
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6); // uniform: block and chunk arithmetic stays scalar
     if (threadIdx.x < 16) {
+        zeros16[threadIdx.x] = 0u;
         const int t = threadIdx.x, g0 = t & 3, g1 = t >> 2;
         const int b0 = 8 * (g0 >> 1) + 4 * (g0 & 1), b1 = 8 * (g1 >> 1) + 4 * (g1 & 1) + 2; // compressed bytes that hold a 1
         for (int wd = 0; wd < 4; ++wd)
@@ -430,7 +433,14 @@ adc_mfma_scan_kernel(const ScanParams p)
         for (int u0 = 0; u0 < 4; u0 += 2) {
             constexpr int kAhead = 2; // steps between an operand's LDS read and its use
             Pattern abuf[kAhead + 1][2];
-            v16i acc[2];
+            v16i acc[2], zero_acc[2];
+#pragma unroll
+            for (int a = 0; a < 2; ++a) {
+                // the address passes through an empty asm statement so that the read stays here, one per chain
+                uint32_t za = (uint32_t)(uintptr_t)(const lds_u32 *)zeros16;
+                asm volatile("" : "+v"(za));
+                zero_acc[a] = *(const lds_v16i *)(uintptr_t)za;
+            }
 #pragma unroll
             for (int t = 0; t < kAhead; ++t) {
 #pragma unroll
@@ -444,7 +454,7 @@ adc_mfma_scan_kernel(const ScanParams p)
                 for (int a = 0; a < 2; ++a) {
                     const Pattern &pa = abuf[s % (kAhead + 1)][a];
                     if (s == 0)
-                        acc[a] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(pa.a, bq[0], v16i{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, pa.idx, 0, 0);
+                        acc[a] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(pa.a, bq[0], zero_acc[a], pa.idx, 0, 0);
                     else
                         acc[a] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(pa.a, bq[s], acc[a], pa.idx, 0, 0);
                     if (s + kAhead < NS) abuf[(s + kAhead) % (kAhead + 1)][a] = read_a(u0 + a, s + kAhead);
