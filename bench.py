@@ -228,7 +228,19 @@ def main():
     # at least 4 blocks): about one block in 32 of every chunk first (2 to 16 per chunk), then everything
     n_blocks = (n + 255) // 256
     n_tiles32 = (B + 31) // 32
-    chunks = max(1, min(2048 // n_tiles32, 256, n_blocks // 4))
+    # waves of a launch = tiles x chunks, in whole rounds of 2048 resident waves (the library's rule: the fewest
+    # rounds, up to 4, that leave under 3 % of the last one empty, else the fullest)
+    target, best = 2048, 0.0
+    for rounds in range(1, 5):
+        c = rounds * 2048 // n_tiles32
+        if c < 1:
+            continue
+        fill = c * n_tiles32 / (rounds * 2048.0)
+        if fill > best + 1e-9:
+            best, target = fill, rounds * 2048
+        if fill >= 0.97:
+            break
+    chunks = max(1, min(target // n_tiles32, 256, n_blocks // 4))
     bpc = -(-n_blocks // chunks)
     sampled = bpc >= 4
     launches = 2 if sampled else 1

@@ -580,8 +580,21 @@ bool scan_mfma_supported(int NB, int bits)
 void scan_mfma_plan(int B, int64_t n_blocks, int target_waves, ScanParams *p)
 {
     p->n_tiles = (B + kMfmaQueries - 1) / kMfmaQueries;
-    // two waves per SIMD on 256 compute units, all resident at once, unless told otherwise
-    const int64_t target = target_waves > 0 ? target_waves : 2048;
+    // Two waves per SIMD on 256 compute units are resident at once: 2048. All waves of a launch do the same
+    // work, so a launch takes whole rounds of 2048 waves; unless told otherwise, the number of rounds (1 to 4)
+    // is the smallest that leaves less than 3 % of the last round empty, else the one that leaves least
+    // (313 tiles: 6 chunks fill 92 % of one round, 13 chunks 99 % of two).
+    int64_t target = target_waves > 0 ? target_waves : 2048;
+    if (target_waves <= 0) {
+        double best = 0.0;
+        for (int r = 1; r <= 4; ++r) {
+            const int64_t c = (int64_t)r * 2048 / p->n_tiles;
+            if (c < 1) continue;
+            const double fill = (double)(c * p->n_tiles) / (double)(r * 2048);
+            if (fill > best + 1e-9) { best = fill; target = (int64_t)r * 2048; }
+            if (fill >= 0.97) break;
+        }
+    }
     int64_t chunks = target / p->n_tiles;
     const int64_t max_chunks = std::max<int64_t>(1, std::min<int64_t>(256, n_blocks / 4));
     const int64_t min_chunks = (n_blocks + kMfmaMaxChunkBlocks - 1) / kMfmaMaxChunkBlocks; // ids in 32-bit keys
