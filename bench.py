@@ -266,7 +266,7 @@ def main():
         # HBM-side bytes of the launch over all blocks from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a
         # plain copy of known size (profiles/scan_glove_pmc_traffic.md); only valid for the default workload
         batch_roof = {"bound": "mfma", "achieved": ops_step / (scan_ms * 1e-3) / 1e12, "peak": MFMA_I8_PEAK_TOPS,
-                      "unit": "TOP/s", "traffic": (0.33e9 + 0.05e9) if (glove_default and B == 10000) else None,
+                      "unit": "TOP/s", "traffic": (0.38e9 + 0.05e9) if (glove_default and B == 10000) else None,
                       "kernel": "adc_mfma_scan_kernel<%d,false>" % nb,
                       "launches_per_step": launches, "avg_launch_ms": scan_ms / launches,
                       "note": "int8 multiply-adds executed by the candidate scan over the 8-bit tables "
