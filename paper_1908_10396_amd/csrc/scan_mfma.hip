@@ -228,7 +228,7 @@ __device__ __noinline__ void mfma_dump_items(const lds_u32 *pend0, int cnt, int 
 }
 
 // STORE: inspection mode, every score is written to scores_out and nothing is selected.
-template <int NBT, bool STORE>
+template <int NBT, bool STORE, bool ITEMS>
 __global__ void __launch_bounds__(kMfmaWaves * 64, 2)
 adc_mfma_scan_kernel(const ScanParams p)
 {
@@ -255,7 +255,7 @@ adc_mfma_scan_kernel(const ScanParams p)
     constexpr int NS = (NBT + 1) / 2; // matrix instructions per chain: two code bytes (four subspaces) each
     const int64_t gw = (int64_t)blockIdx.x * kMfmaWaves + wave; // wave index over (chunk, tile), or over the items
     const int j = lane & 31, h = lane >> 5;
-    const bool items = p.item_list != nullptr;
+    constexpr bool items = ITEMS; // work items (leaf, 32 of its queries) instead of (query tile, chunk)
     int tile = 0, chunk = 0, q = 0;
     bool live = false;
     int64_t first = 0, end = 0;
@@ -494,10 +494,23 @@ adc_mfma_scan_kernel(const ScanParams p)
                         const int32_t m = x > y ? x : y, n = z > w ? z : w;
                         return m > n ? m : n;
                     };
+                    if (items) {
+                        // over leaves the bound comes from a query's first few leaves only and most accumulators
+                        // hold a candidate in some lane: no tests that skip, one predicated append per accumulator
+                        // (padding slots are told from points afterwards)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) {
+                            if (acc[a][v] > thr) {
+                                const int32_t id = id0 + 32 * (v / 4) + 4 * (v % 4);
+                                *pend = ((uint32_t)(acc[a][v] + off + 1) << kIdBits) | (~(uint32_t)(id - id_base) & kIdMask);
+                                ++pend;
+                            }
+                        }
+                    }
                     int32_t gmax[4];
 #pragma unroll
                     for (int g = 0; g < 4; ++g) gmax[g] = max4(acc[a][4 * g], acc[a][4 * g + 1], acc[a][4 * g + 2], acc[a][4 * g + 3]);
-                    if (__builtin_expect(__builtin_amdgcn_ballot_w64(max4(gmax[0], gmax[1], gmax[2], gmax[3]) > thr) != 0ull, 0)) {
+                    if (!items && __builtin_expect(__builtin_amdgcn_ballot_w64(max4(gmax[0], gmax[1], gmax[2], gmax[3]) > thr) != 0ull, 0)) {
 #pragma unroll
                         for (int g = 0; g < 4; ++g) {
                             if (__builtin_amdgcn_ballot_w64(gmax[g] > thr) == 0ull) continue;
@@ -641,10 +654,10 @@ size_t scan_mfma_lists_bytes(const ScanParams &p)
     return sizeof(u64) * (size_t)p.n_tiles * p.n_chunks * kMfmaQueries * 64 * p.ns;
 }
 
-template <int NBT, bool STORE>
+template <int NBT, bool STORE, bool ITEMS>
 static int launch_mfma_one(const ScanParams &p, hipStream_t st)
 {
-    auto kern = adc_mfma_scan_kernel<NBT, STORE>;
+    auto kern = adc_mfma_scan_kernel<NBT, STORE, ITEMS>;
     static bool attr_done = false;
     if (!attr_done) {
         AVQ_HIP(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynLds));
@@ -669,10 +682,10 @@ int launch_scan_mfma(const ScanParams &p, hipStream_t st)
             return AVQ_EINVAL;
         }
         switch (p.NB) {
-        case 8: return launch_mfma_one<8, false>(p, st);
-        case 13: return launch_mfma_one<13, false>(p, st);
-        case 25: return launch_mfma_one<25, false>(p, st);
-        default: return launch_mfma_one<32, false>(p, st);
+        case 8: return launch_mfma_one<8, false, true>(p, st);
+        case 13: return launch_mfma_one<13, false, true>(p, st);
+        case 25: return launch_mfma_one<25, false, true>(p, st);
+        default: return launch_mfma_one<32, false, true>(p, st);
         }
     }
     if (p.fixed_bound && (p.cand_keys == nullptr || p.thr_shared == nullptr)) {
@@ -693,10 +706,10 @@ int launch_scan_mfma(const ScanParams &p, hipStream_t st)
     if (p.blocks_per_chunk > kMfmaMaxChunkBlocks || p.M > 64) { set_error("scan: chunk or code too large for 32-bit keys"); return AVQ_EINVAL; }
     const bool store = p.scores_out != nullptr || p.sample_max != nullptr;
     switch (p.NB) {
-    case 8: return store ? launch_mfma_one<8, true>(p, st) : launch_mfma_one<8, false>(p, st);
-    case 13: return store ? launch_mfma_one<13, true>(p, st) : launch_mfma_one<13, false>(p, st);
-    case 25: return store ? launch_mfma_one<25, true>(p, st) : launch_mfma_one<25, false>(p, st);
-    default: return store ? launch_mfma_one<32, true>(p, st) : launch_mfma_one<32, false>(p, st);
+    case 8: return store ? launch_mfma_one<8, true, false>(p, st) : launch_mfma_one<8, false, false>(p, st);
+    case 13: return store ? launch_mfma_one<13, true, false>(p, st) : launch_mfma_one<13, false, false>(p, st);
+    case 25: return store ? launch_mfma_one<25, true, false>(p, st) : launch_mfma_one<25, false, false>(p, st);
+    default: return store ? launch_mfma_one<32, true, false>(p, st) : launch_mfma_one<32, false, false>(p, st);
     }
 }
 
