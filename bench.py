@@ -255,7 +255,7 @@ def main():
         unverified = idx.debug_unverified_queries(reasons=True)
         ops = 2.0 * scanned * B * steps_per_pair * 32
         batch_roof = {"bound": "mfma", "achieved": ops / (scan_ms * 1e-3) / 1e12, "peak": MFMA_I8_PEAK_TOPS, "unit": "TOP/s",
-                      "traffic": None, "kernel": "adc_mfma_scan_kernel<%d,false,true>" % nb, "avg_launch_ms": scan_ms,
+                      "traffic": None, "kernel": "adc_mfma_scan_kernel<%d,false,true,true>" % nb, "avg_launch_ms": scan_ms,
                       "note": "int8 multiply-adds executed by the scan over leaves (sparse instruction, 32 queries per leaf and work item); the stage "
                               "time also covers the bounds pass (leaf_bound_kernel over each query's best leaves) "
                               "and the regrouping of the (query, leaf) pairs",
@@ -267,7 +267,7 @@ def main():
         # plain copy of known size (profiles/scan_glove_pmc_traffic.md); only valid for the default workload
         batch_roof = {"bound": "mfma", "achieved": ops_step / (scan_ms * 1e-3) / 1e12, "peak": MFMA_I8_PEAK_TOPS,
                       "unit": "TOP/s", "traffic": (0.38e9 + 0.05e9) if (glove_default and B == 10000) else None,
-                      "kernel": "adc_mfma_scan_kernel<%d,false,false>" % nb,
+                      "kernel": "adc_mfma_scan_kernel<%d,false,false,%s>" % (nb, "true" if sampled else "false"),
                       "launches_per_step": launches, "avg_launch_ms": scan_ms / launches,
                       "note": "int8 multiply-adds executed by the candidate scan over the 8-bit tables "
                               "(v_smfmac_i32_32x32x64_i8: the one-hot operand is 2:4 sparse, so an instruction covers 64 "
@@ -302,7 +302,7 @@ def main():
         # one-hot contraction on the sparse int8 matrix instruction: 32 points x 32 queries, four subspaces (64
         # positions, 32 of them stored) per instruction, ceil(NB / 2) instructions per (32 points, 32 queries)
         u8_roof = {"bound": "mfma", "achieved": ops_step / (stage8_ms["scan"] * 1e-3) / 1e12, "peak": MFMA_I8_PEAK_TOPS,
-                   "unit": "TOP/s", "kernel": "adc_mfma_scan_kernel<%d,false,false>" % nb,
+                   "unit": "TOP/s", "kernel": "adc_mfma_scan_kernel<%d,false,false,%s>" % (nb, "true" if sampled else "false"),
                    "launches_per_step": launches, "avg_launch_ms": stage8_ms["scan"] / launches, "traffic": None,
                    "note": "int8 multiply-adds executed (sparse instruction); 8 of them per useful table add (one-hot operand)"}
         u8_roof["frac"] = u8_roof["achieved"] / u8_roof["peak"]

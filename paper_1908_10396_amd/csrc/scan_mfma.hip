@@ -228,7 +228,7 @@ __device__ __noinline__ void mfma_dump_items(const lds_u32 *pend0, int cnt, int 
 }
 
 // STORE: inspection mode, every score is written to scores_out and nothing is selected.
-template <int NBT, bool STORE, bool ITEMS>
+template <int NBT, bool STORE, bool ITEMS, bool FIXED>
 __global__ void __launch_bounds__(kMfmaWaves * 64, 2)
 adc_mfma_scan_kernel(const ScanParams p)
 {
@@ -311,7 +311,7 @@ adc_mfma_scan_kernel(const ScanParams p)
     lds_u32 *pend = pend0; // next free slot of this lane's pending buffer
     // fixed_bound: the bounds in thr_shared are taken as they are and never raised: every point at
     // or above them (less the margin) goes to the candidate buffer, and no lists are kept
-    const bool fixed = !store && (p.fixed_bound != 0 || items);
+    constexpr bool fixed = !store && (FIXED || items); // FIXED: what the host found in p.fixed_bound
     if (!store && !fixed) {
         my_lists = (uint32_t *)p.lists_ws + (size_t)gw * kMfmaQueries * C;
         for (int i = lane; i < kMfmaQueries * C; i += 64) my_lists[i] = 0u;
@@ -654,10 +654,10 @@ size_t scan_mfma_lists_bytes(const ScanParams &p)
     return sizeof(u64) * (size_t)p.n_tiles * p.n_chunks * kMfmaQueries * 64 * p.ns;
 }
 
-template <int NBT, bool STORE, bool ITEMS>
+template <int NBT, bool STORE, bool ITEMS, bool FIXED>
 static int launch_mfma_one(const ScanParams &p, hipStream_t st)
 {
-    auto kern = adc_mfma_scan_kernel<NBT, STORE, ITEMS>;
+    auto kern = adc_mfma_scan_kernel<NBT, STORE, ITEMS, FIXED>;
     static bool attr_done = false;
     if (!attr_done) {
         AVQ_HIP(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynLds));
@@ -672,6 +672,14 @@ static int launch_mfma_one(const ScanParams &p, hipStream_t st)
     return AVQ_OK;
 }
 
+// flat index: the store variant (scores or class maxima), the scan against fixed bounds, or the scan with lists
+template <int NBT>
+static int launch_mfma_mode(const ScanParams &p, bool store, hipStream_t st)
+{
+    if (store) return launch_mfma_one<NBT, true, false, false>(p, st);
+    return p.fixed_bound ? launch_mfma_one<NBT, false, false, true>(p, st) : launch_mfma_one<NBT, false, false, false>(p, st);
+}
+
 int launch_scan_mfma(const ScanParams &p, hipStream_t st)
 {
     if (!scan_mfma_supported(p.NB, p.bits)) { set_error("scan: no matrix-core kernel for this code size"); return AVQ_EINVAL; }
@@ -682,10 +690,10 @@ int launch_scan_mfma(const ScanParams &p, hipStream_t st)
             return AVQ_EINVAL;
         }
         switch (p.NB) {
-        case 8: return launch_mfma_one<8, false, true>(p, st);
-        case 13: return launch_mfma_one<13, false, true>(p, st);
-        case 25: return launch_mfma_one<25, false, true>(p, st);
-        default: return launch_mfma_one<32, false, true>(p, st);
+        case 8: return launch_mfma_one<8, false, true, true>(p, st);
+        case 13: return launch_mfma_one<13, false, true, true>(p, st);
+        case 25: return launch_mfma_one<25, false, true, true>(p, st);
+        default: return launch_mfma_one<32, false, true, true>(p, st);
         }
     }
     if (p.fixed_bound && (p.cand_keys == nullptr || p.thr_shared == nullptr)) {
@@ -706,10 +714,10 @@ int launch_scan_mfma(const ScanParams &p, hipStream_t st)
     if (p.blocks_per_chunk > kMfmaMaxChunkBlocks || p.M > 64) { set_error("scan: chunk or code too large for 32-bit keys"); return AVQ_EINVAL; }
     const bool store = p.scores_out != nullptr || p.sample_max != nullptr;
     switch (p.NB) {
-    case 8: return store ? launch_mfma_one<8, true, false>(p, st) : launch_mfma_one<8, false, false>(p, st);
-    case 13: return store ? launch_mfma_one<13, true, false>(p, st) : launch_mfma_one<13, false, false>(p, st);
-    case 25: return store ? launch_mfma_one<25, true, false>(p, st) : launch_mfma_one<25, false, false>(p, st);
-    default: return store ? launch_mfma_one<32, true, false>(p, st) : launch_mfma_one<32, false, false>(p, st);
+    case 8: return launch_mfma_mode<8>(p, store, st);
+    case 13: return launch_mfma_mode<13>(p, store, st);
+    case 25: return launch_mfma_mode<25>(p, store, st);
+    default: return launch_mfma_mode<32>(p, store, st);
     }
 }
 
