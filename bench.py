@@ -243,10 +243,8 @@ def main():
     chunks = max(1, min(target // n_tiles32, 256, n_blocks // 4))
     bpc = -(-n_blocks // chunks)
     sampled = bpc >= 4
-    launches = 2 if sampled else 1
     per_chunk = max(2, min(16, (bpc + 31) // 32))
     visited = -(-bpc // max(1, bpc // per_chunk))
-    ops_step = mfma_ops * (1.0 + (float(visited) / bpc if sampled else 0.0))
     grouped = (bool(n_leaves) and bits == 4 and B >= 64 and B * Lp >= 131072 and nb in (8, 13, 25, 32) and M <= 64
                and 16 <= Lp <= 512)   # the library's rule
     if grouped:
@@ -265,15 +263,17 @@ def main():
         unverified = idx.debug_unverified_queries(reasons=True)
         # HBM-side bytes of the launch over all blocks from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a
         # plain copy of known size (profiles/scan_glove_pmc_traffic.md); only valid for the default workload
-        batch_roof = {"bound": "mfma", "achieved": ops_step / (scan_ms * 1e-3) / 1e12, "peak": MFMA_I8_PEAK_TOPS,
+        batch_roof = {"bound": "mfma", "achieved": mfma_ops / (scan_ms * 1e-3) / 1e12, "peak": MFMA_I8_PEAK_TOPS,
                       "unit": "TOP/s", "traffic": (0.38e9 + 0.05e9) if (glove_default and B == 10000) else None,
                       "kernel": "adc_mfma_scan_kernel<%d,false,false,%s>" % (nb, "true" if sampled else "false"),
-                      "launches_per_step": launches, "avg_launch_ms": scan_ms / launches,
-                      "note": "int8 multiply-adds executed by the candidate scan over the 8-bit tables "
-                              "(v_smfmac_i32_32x32x64_i8: the one-hot operand is 2:4 sparse, so an instruction covers 64 "
-                              "positions with 32 multiply-adds per output; 8 executed per useful table add), per step: a "
-                              "launch over a sample of the blocks that guesses the bounds, then the launch over all "
-                              "blocks; the fp32 scores are formed for the kept points only",
+                      "launches_per_step": 1, "avg_launch_ms": scan_ms,
+                      "sample_stage_ms": stage_ms.get("sample", 0.0),
+                      "note": "int8 multiply-adds executed by the launch over all blocks of the candidate scan over the "
+                              "8-bit tables (v_smfmac_i32_32x32x64_i8: the one-hot operand is 2:4 sparse, so an instruction "
+                              "covers 64 positions with 32 multiply-adds per output; 8 executed per useful table add). "
+                              "Before it, timed apart (sample_stage_ms): margins, a launch of the store variant over a "
+                              "sample of the blocks (%.1f %% of these operations) and the bounds guessed from it; the fp32 "
+                              "scores are formed for the kept points only" % (100.0 * visited / bpc if sampled else 0.0),
                       "queries_scanned_again_with_fp32_tables": unverified[0],
                       "of_which_too_many_kept_or_bound_too_high_or_other": unverified[1:]}
         batch_roof["frac"] = batch_roof["achieved"] / batch_roof["peak"]
@@ -301,9 +301,10 @@ def main():
     if bits == 4 and not n_leaves and B >= 16 and nb in (8, 13, 25, 32):
         # one-hot contraction on the sparse int8 matrix instruction: 32 points x 32 queries, four subspaces (64
         # positions, 32 of them stored) per instruction, ceil(NB / 2) instructions per (32 points, 32 queries)
-        u8_roof = {"bound": "mfma", "achieved": ops_step / (stage8_ms["scan"] * 1e-3) / 1e12, "peak": MFMA_I8_PEAK_TOPS,
+        u8_roof = {"bound": "mfma", "achieved": mfma_ops / (stage8_ms["scan"] * 1e-3) / 1e12, "peak": MFMA_I8_PEAK_TOPS,
                    "unit": "TOP/s", "kernel": "adc_mfma_scan_kernel<%d,false,false,%s>" % (nb, "true" if sampled else "false"),
-                   "launches_per_step": launches, "avg_launch_ms": stage8_ms["scan"] / launches, "traffic": None,
+                   "launches_per_step": 1, "avg_launch_ms": stage8_ms["scan"], "sample_stage_ms": stage8_ms.get("sample", 0.0),
+                   "traffic": None,
                    "note": "int8 multiply-adds executed (sparse instruction); 8 of them per useful table add (one-hot operand)"}
         u8_roof["frac"] = u8_roof["achieved"] / u8_roof["peak"]
 

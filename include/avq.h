@@ -284,8 +284,11 @@ enum { AVQ_STAGE_LEAF = 0,   /* leaf selection                                  
                                 small batch: block maxima only)                          */
        AVQ_STAGE_MERGE = 3,  /* merge of per-chunk lists / selection of the best blocks  */
        AVQ_STAGE_FINAL = 4,  /* exact re-scoring and final top-k                         */
-       AVQ_STAGE_RESCAN = 5, /* small batch: scan of the selected blocks                 */
-       AVQ_N_STAGES = 6 };
+       AVQ_STAGE_RESCAN = 5, /* small batch: scan of the selected blocks; batches: scoring
+                                of the kept points and the queries scanned again         */
+       AVQ_STAGE_SAMPLE = 6, /* batches through the candidate scan: margins, the launch
+                                over a sample of the blocks and the bounds guessed from it */
+       AVQ_N_STAGES = 7 };
 int avq_profile_enable(avq_index *idx, int32_t on);
 int avq_profile_read(avq_index *idx, double *ms_out, int64_t *launches_out, int32_t reset);
 

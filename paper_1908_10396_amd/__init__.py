@@ -17,7 +17,7 @@ AVQ_OK, AVQ_EINVAL, AVQ_ESTATE, AVQ_ENOMEM, AVQ_EHIP = 0, -1, -2, -3, -4
 LUT_F32, LUT_U8 = 0, 1
 ETA_LIMIT, ETA_EXACT, ETA_EXPLICIT = 0, 1, 2
 MAX_SELECT = 512
-STAGES = ("leaf_select", "lut", "scan", "merge", "finalize", "rescan")
+STAGES = ("leaf_select", "lut", "scan", "merge", "finalize", "rescan", "sample")
 
 # every symbol include/avq.h declares
 SYMBOLS = [

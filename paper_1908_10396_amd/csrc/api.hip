@@ -604,7 +604,7 @@ static int search_through_candidates(avq_index *idx, const float *queries, int n
     pm.cand_cnt = (uint32_t *)(margin + nq);
     pm.cand_margin = u8 ? nullptr : margin;
     {
-        StageTimer t(idx, AVQ_STAGE_SCAN, st);
+        StageTimer t(idx, AVQ_STAGE_SAMPLE, st);
         AVQ_HIP(hipMemsetAsync(fail_count, 0, 16, st));
         AVQ_HIP(hipMemsetAsync(pm.thr_shared, 0, thr_bytes, st));
         if (!u8) AVQ_TRY(launch_prefilter_margin(idx->lut.as<float>(), idx->scale.as<float>(), c.M, idx->NB, nq, margin, st));
@@ -632,6 +632,9 @@ static int search_through_candidates(avq_index *idx, const float *queries, int n
             }
             pm.fixed_bound = 1;
         }
+    }
+    {
+        StageTimer t(idx, AVQ_STAGE_SCAN, st); // the launch over all blocks, nothing else
         AVQ_TRY(launch_scan_mfma(pm, st));
     }
     const u64 *top = pm.fixed_bound ? nullptr : pm.partial;
