@@ -254,9 +254,10 @@ def main():
         ops = 2.0 * scanned * B * steps_per_pair * 32
         batch_roof = {"bound": "mfma", "achieved": ops / (scan_ms * 1e-3) / 1e12, "peak": MFMA_I8_PEAK_TOPS, "unit": "TOP/s",
                       "traffic": None, "kernel": "adc_mfma_scan_kernel<%d,false,true,true>" % nb, "avg_launch_ms": scan_ms,
-                      "note": "int8 multiply-adds executed by the scan over leaves (sparse instruction, 32 queries per leaf and work item); the stage "
-                              "time also covers the bounds pass (leaf_bound_kernel over each query's best leaves) "
-                              "and the regrouping of the (query, leaf) pairs",
+                      "sample_stage_ms": stage_ms.get("sample", 0.0),
+                      "note": "int8 multiply-adds executed by the scan over leaves (sparse instruction, 32 queries per leaf "
+                              "and work item); before it, timed apart (sample_stage_ms): the bounds pass (leaf_bound_kernel "
+                              "over each query's best leaves) and the regrouping of the (query, leaf) pairs",
                       "queries_scanned_again": unverified[0]}
         batch_roof["frac"] = batch_roof["achieved"] / batch_roof["peak"]
     elif prefiltered:

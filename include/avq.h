@@ -287,7 +287,9 @@ enum { AVQ_STAGE_LEAF = 0,   /* leaf selection                                  
        AVQ_STAGE_RESCAN = 5, /* small batch: scan of the selected blocks; batches: scoring
                                 of the kept points and the queries scanned again         */
        AVQ_STAGE_SAMPLE = 6, /* batches through the candidate scan: margins, the launch
-                                over a sample of the blocks and the bounds guessed from it */
+                                over a sample of the blocks and the bounds guessed from it;
+                                partitioned batches regrouped by leaf: margins, bounds from
+                                each query's first leaves, regrouping                     */
        AVQ_N_STAGES = 7 };
 int avq_profile_enable(avq_index *idx, int32_t on);
 int avq_profile_read(avq_index *idx, double *ms_out, int64_t *launches_out, int32_t reset);

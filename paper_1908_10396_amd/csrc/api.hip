@@ -741,8 +741,9 @@ static int search_leaves_grouped(avq_index *idx, const float *queries, int nq, i
         pl.lists_ws = idx->lists.as<u64>();
     }
     const int bound_leaves = idx->tune_bound_leaves > 0 ? std::min(L, idx->tune_bound_leaves) : std::min(L, std::max(8, (L + 11) / 12));
+    ScanParams pi;
     {
-        StageTimer t(idx, AVQ_STAGE_SCAN, st);
+        StageTimer t(idx, AVQ_STAGE_SAMPLE, st); // here: margins, bounds from the first leaves, regrouping
         AVQ_HIP(hipMemsetAsync(fail_count, 0, 16, st));
         AVQ_HIP(hipMemsetAsync(kept_cnt, 0, sizeof(uint32_t) * (size_t)nq, st));
         if (!u8) AVQ_TRY(launch_prefilter_margin(idx->lut.as<float>(), idx->scale.as<float>(), c.M, idx->NB, nq, margin, st));
@@ -756,7 +757,6 @@ static int search_leaves_grouped(avq_index *idx, const float *queries, int nq, i
             AVQ_TRY(launch_list_bound(pb.partial, ns, R, nq, bound, st));
         }
         AVQ_TRY(launch_group_by_leaf(idx->leaf_ids.as<int32_t>(), nq, L, c.n_leaves, g, st));
-        ScanParams pi;
         fill_scan_params(idx, nq, R, ns, &pi);
         pi.n_valid = 0x7fffffff; // padding slots are told from points by perm, afterwards
         pi.leaf_blk = idx->leaf_blk.as<int32_t>();
@@ -774,6 +774,9 @@ static int search_leaves_grouped(avq_index *idx, const float *queries, int nq, i
         pi.kept = idx->kept.as<u64>();
         pi.kept_cnt = kept_cnt;
         pi.kept_cap = kept_cap;
+    }
+    {
+        StageTimer t(idx, AVQ_STAGE_SCAN, st); // the scan over all leaves, nothing else
         AVQ_TRY(launch_scan_mfma(pi, st));
     }
     {
