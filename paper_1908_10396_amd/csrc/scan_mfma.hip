@@ -47,16 +47,23 @@
 //    reach the lists roughly by the size of the group.
 // A wave reads its queries' bounds once per block, one block ahead of their use.
 //
-// Guess and check (fixed_bound). While a list is young its bound is weak and nearly every
-// point passes; sorting those keys into lists is a fifth of the scan's time. For fp32-table
-// batches, which only need a superset of the R best (candidate mode), the bound is guessed
-// instead: a first launch of this kernel scores a sample of the points (every block_stride-th
-// block of every chunk) with short lists; the r-th best sum of the sample, r chosen so that
-// about four times R points of the whole index lie above it, becomes the query's bound in
-// thr_shared. The second launch scans everything against that fixed bound, appends what
-// reaches it (less the margin) to the candidate buffers and keeps no lists. Afterwards the
-// guess is checked per query: if at least R kept points reach the bound, the R-th best sum of
-// the index is at or above it and nothing was missed; otherwise the query is scanned again.
+// Guess and check (the FIXED instantiation). While a list is young its bound is weak and nearly
+// every point passes; sorting those keys into lists is a fifth of the scan's time. Batches, which
+// only need a superset of the R best (candidate mode), scan against a guessed bound instead: a first
+// launch (the STORE instantiation with sample_max set) scores a sample of the points, every
+// block_stride-th block of every chunk, and keeps no lists either: a lane's 16 accumulators see 16
+// disjoint classes of points, so the wave records the best sum of each of its 32 classes per query,
+// and the r-th largest of a query's class maxima (r chosen so that a few times R points of the whole
+// index lie above it) becomes the query's bound in thr_shared. The second launch scans everything
+// against that fixed bound, appends what reaches it (less the margin) to the candidate buffers and
+// keeps no lists. Afterwards the guess is checked per query: if at least R kept points reach the
+// bound, the R-th best sum of the index is at or above it and nothing was missed; otherwise the
+// query is scanned again. (A sample scanned with lists, block_stride > 1 in the list instantiation,
+// remains for queries with too few classes.)
+//
+// Template parameters: STORE (scores or class maxima are written, nothing is selected), ITEMS (work
+// items of a partitioned index, one leaf and 32 of its queries per wave, instead of query tile x
+// chunk), FIXED (bounds are given and never raised, no lists).
 #include <cmath>
 #include "avq_internal.h"
 #include "wave_topk.h"
