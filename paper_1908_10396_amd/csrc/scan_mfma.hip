@@ -628,8 +628,10 @@ void scan_mfma_plan(int B, int64_t n_blocks, int target_waves, ScanParams *p)
 }
 
 // The sampling launch for a fixed-bound scan planned in `full`: the same queries and chunks, a few
-// blocks of every chunk at equal distances (about one in 32, at most 16 per chunk), lists of r keys
-// (see below). Returns false when the chunks are too short for that (then the caller scans with lists).
+// blocks of every chunk at equal distances (about one in 32, at most 16 per chunk); sample->R is the rank r
+// whose sum becomes the bound (see below), sample->ns the list slots for it should the caller scan the
+// sample with lists (it sets sample_max to take class maxima instead). Returns false when the chunks are too
+// short for a sample (then the caller scans with lists).
 bool scan_mfma_sample_plan(const ScanParams &full, ScanParams *sample)
 {
     const int64_t bpc = full.blocks_per_chunk;
