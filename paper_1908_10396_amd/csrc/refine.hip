@@ -102,8 +102,7 @@ refine_cand_kernel(const RefineCandParams r)
     const int C = 64 * r.ns;
     const int n_tab = 2 * r.NB;
     float *tbl = (float *)smem;                                               // [n_tab][16]
-    u64 *keys = (u64 *)(smem + (((size_t)n_tab * 64 + 15) & ~(size_t)15));    // [kFinalMax] fp32 keys of the finalists
-    int32_t *fin_ids = (int32_t *)(keys + kFinalMax);                         // [kFinalMax]
+    u64 *keys = (u64 *)(smem + (((size_t)n_tab * 64 + 15) & ~(size_t)15));    // [kFinalMax] ids of the finalists, then their fp32 keys
     __shared__ int n_top_s, bad_s, n_fin_s, wave_cnt[2][4];
     __shared__ uint32_t first_of[kMaxChunks + 1]; // first_of[c] = kept keys in the chunks before c
 
@@ -201,8 +200,7 @@ refine_cand_kernel(const RefineCandParams r)
                 const int slot = atomicAdd(&n_fin_s, 1);
                 if (slot < kFinalMax) {
                     const int32_t id = (int32_t)((int64_t)c * r.chunk_points) + (int32_t)(~mine[k] & 0x3ffffu);
-                    fin_ids[slot] = id;
-                    if (!rescore) keys[slot] = make_key(mine[k] >> 18, id);
+                    keys[slot] = rescore ? (u64)(uint32_t)id : make_key(mine[k] >> 18, id);
                 }
             }
         }
@@ -218,7 +216,7 @@ refine_cand_kernel(const RefineCandParams r)
     }
     const int n_cand = n_fin_s;
     for (int i = tid; rescore && i < n_cand; i += nt) {
-        const int32_t id = fin_ids[i];
+        const int32_t id = (int32_t)(uint32_t)keys[i]; // replaced by the key below, by this thread
         const uint8_t *row = r.codes + (size_t)id * r.NB;
         float s = 0.0f;
         if constexpr (NBT != 0) {
@@ -318,7 +316,7 @@ int launch_list_bound(const u64 *lists, int ns, int r, int nq, uint32_t *bound, 
 int launch_refine_cand(const RefineCandParams &r, hipStream_t st)
 {
     if (r.M > 64 || r.R > 64 * r.ns || r.cand_cap < 1 || r.n_chunks > kMaxChunks || (r.lut != nullptr && r.margin == nullptr) || (r.top == nullptr) == (r.bound == nullptr)) { set_error("refine: bad shape (M %d, R %d)", r.M, r.R); return AVQ_EINVAL; }
-    const size_t lds = (((size_t)2 * r.NB * 64 + 15) & ~(size_t)15) + (sizeof(u64) + sizeof(int32_t)) * (size_t)kFinalMax;
+    const size_t lds = (((size_t)2 * r.NB * 64 + 15) & ~(size_t)15) + sizeof(u64) * (size_t)kFinalMax;
     switch (r.NB) {
     case 8: hipLaunchKernelGGL(refine_cand_kernel<8>, dim3(r.nq), dim3(256), lds, st, r); break;
     case 13: hipLaunchKernelGGL(refine_cand_kernel<13>, dim3(r.nq), dim3(256), lds, st, r); break;
