@@ -100,8 +100,23 @@ __device__ __forceinline__ float dot_chain(const float *qs, const float *__restr
 {
     float s = 0.0f;
     if ((d & 3) == 0 && (((uintptr_t)row) & 15) == 0) {
+        // five 16-byte loads in flight at a time (the chain itself is serial): a row of 100 floats in five rounds
         const float4 *r4 = (const float4 *)row;
-        for (int l = 0; l < d / 4; ++l) {
+        const int n4 = d / 4;
+        int l = 0;
+        for (; l + 5 <= n4; l += 5) {
+            float4 v[5];
+#pragma unroll
+            for (int u = 0; u < 5; ++u) v[u] = r4[l + u];
+#pragma unroll
+            for (int u = 0; u < 5; ++u) {
+                s = __fmaf_rn(qs[4 * (l + u) + 0], v[u].x, s);
+                s = __fmaf_rn(qs[4 * (l + u) + 1], v[u].y, s);
+                s = __fmaf_rn(qs[4 * (l + u) + 2], v[u].z, s);
+                s = __fmaf_rn(qs[4 * (l + u) + 3], v[u].w, s);
+            }
+        }
+        for (; l < n4; ++l) {
             const float4 v = r4[l];
             s = __fmaf_rn(qs[4 * l + 0], v.x, s);
             s = __fmaf_rn(qs[4 * l + 1], v.y, s);
