@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <atomic>
 #include <string>
 #include <vector>
 
@@ -33,6 +34,20 @@ void set_error(const char *fmt, ...);
         int rc_ = (call);          \
         if (rc_ != AVQ_OK) return rc_; \
     } while (0)
+
+// Raises a kernel's dynamic-LDS limit once per device; safe to call from several threads
+// (the attribute is per device and setting it twice is harmless).
+struct LdsLimitOnce { std::atomic<uint64_t> devices{0}; };
+inline int set_lds_limit(const void *kernel, size_t bytes, LdsLimitOnce *once)
+{
+    int dev = 0;
+    AVQ_HIP(hipGetDevice(&dev));
+    const uint64_t bit = 1ull << (dev & 63);
+    if (once->devices.load(std::memory_order_acquire) & bit) return AVQ_OK;
+    AVQ_HIP(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+    once->devices.fetch_or(bit, std::memory_order_release);
+    return AVQ_OK;
+}
 
 // Grow-only device buffer.
 struct DevBuf {

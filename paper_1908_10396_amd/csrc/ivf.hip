@@ -192,11 +192,8 @@ int launch_leaf_select(const float *centers_t, int n_leaves, int d, const float 
     if (nq >= 2048) {
         const size_t lds = (size_t)kLeafTile * n_leaves * 4 + (size_t)d * kLeafTile * 4 + (size_t)8 * L * 8;
         if (lds <= kMaxDynLds) {
-            static bool tile_attr_done = false;
-            if (!tile_attr_done) {
-                AVQ_HIP(hipFuncSetAttribute((const void *)leaf_select_tile_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynLds));
-                tile_attr_done = true;
-            }
+            static LdsLimitOnce tile_attr_done;
+            AVQ_TRY(set_lds_limit((const void *)leaf_select_tile_kernel, kMaxDynLds, &tile_attr_done));
             hipLaunchKernelGGL(leaf_select_tile_kernel, dim3((nq + kLeafTile - 1) / kLeafTile), dim3(512), lds, st, centers_t, n_leaves,
                                d, queries, nq, L, leaf_ids, leaf_ip, leaf_cnt);
             AVQ_HIP(hipGetLastError());
@@ -208,11 +205,8 @@ int launch_leaf_select(const float *centers_t, int n_leaves, int d, const float 
     while (waves > 1 && (waves / 2) * 64 >= n_leaves) waves /= 2;
     const size_t lds = (size_t)waves * (64 * ns + 64) * 8 + (size_t)d * 4;
     if (lds > kMaxDynLds) { set_error("leaf select: L = %d too large", L); return AVQ_EINVAL; }
-    static bool attr_done = false;
-    if (!attr_done) {
-        AVQ_HIP(hipFuncSetAttribute((const void *)leaf_select_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynLds));
-        attr_done = true;
-    }
+    static LdsLimitOnce attr_done;
+    AVQ_TRY(set_lds_limit((const void *)leaf_select_kernel, kMaxDynLds, &attr_done));
     hipLaunchKernelGGL(leaf_select_kernel, dim3(nq), dim3(waves * 64), lds, st, centers_t, n_leaves, d,
                        queries, L, ns, leaf_ids, leaf_ip, leaf_cnt);
     AVQ_HIP(hipGetLastError());

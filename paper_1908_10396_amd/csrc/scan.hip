@@ -1113,24 +1113,17 @@ int scan_pick_shape(int NB, int bits, bool u8, int ns, int B, bool single, int q
 }
 
 template <class K>
-static int set_max_lds(K kern, bool *done)
+static int set_max_lds(K kern, LdsLimitOnce *once)
 {
-    if (!*done) {
-        AVQ_HIP(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynLds));
-        *done = true;
-    }
-    return AVQ_OK;
+    return set_lds_limit((const void *)kern, kMaxDynLds, once);
 }
 
 template <bool U8, int NBT>
 static int launch_leaf_bound_one(const ScanParams &p, int cap_blocks, uint32_t *bound, hipStream_t st)
 {
     auto kern = leaf_bound_kernel<U8, NBT>;
-    static bool attr_done = false; // the tables are static LDS on top of this
-    if (!attr_done) {
-        AVQ_HIP(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLeafBoundMaxBlocks * 1024 + 8192));
-        attr_done = true;
-    }
+    static LdsLimitOnce attr_done; // the tables are static LDS on top of this
+    AVQ_TRY(set_lds_limit((const void *)kern, kLeafBoundMaxBlocks * 1024 + 8192, &attr_done));
     hipLaunchKernelGGL(kern, dim3(p.B), dim3(512), (size_t)cap_blocks * 1024 + 8192, st, p, cap_blocks, bound);
     AVQ_HIP(hipGetLastError());
     return AVQ_OK;
@@ -1162,7 +1155,7 @@ template <int QT, bool U8, int NBT, int MODE>
 static int launch_one(const ScanParams &p, const ScanShape &s, int grid, hipStream_t st)
 {
     auto kern = adc_scan_kernel<QT, U8, NBT, MODE>;
-    static bool attr_done = false; // per instantiation
+    static LdsLimitOnce attr_done; // per instantiation
     AVQ_TRY(set_max_lds(kern, &attr_done));
     hipLaunchKernelGGL(kern, dim3(grid), dim3(s.waves * 64), s.lds_bytes, st, p);
     AVQ_HIP(hipGetLastError());
@@ -1213,7 +1206,7 @@ template <bool U8, int NBT>
 static int launch_block_max_one(const ScanParams &p, int waves, hipStream_t st)
 {
     auto kern = block_max_kernel<U8, NBT>;
-    static bool attr_done = false;
+    static LdsLimitOnce attr_done;
     AVQ_TRY(set_max_lds(kern, &attr_done));
     const size_t lds = (size_t)p.NB * 256 * 4;
     // at most about four workgroups per compute unit and query: beyond that each one loops
@@ -1294,7 +1287,7 @@ template <bool U8, int NBT, bool NIB>
 static int launch_rescan_one(const ScanParams &p, const FinishParams &f, hipStream_t st)
 {
     auto kern = rescan_blocks_kernel<U8, NBT, NIB>;
-    static bool attr_done = false;
+    static LdsLimitOnce attr_done;
     AVQ_TRY(set_max_lds(kern, &attr_done));
     const int waves = 4;
     const size_t lds = NIB ? (size_t)2 * p.NB * 16 * (U8 ? 1 : 4) : (size_t)p.NB * 256 * 4;
@@ -1321,7 +1314,7 @@ static int launch_rescan_u(const ScanParams &p, const FinishParams &f, hipStream
 
 int launch_small_select(const ScanParams &p, const FinishParams &f, hipStream_t st)
 {
-    static bool attr = false;
+    static LdsLimitOnce attr;
     AVQ_TRY(set_max_lds(select_blocks_kernel, &attr));
     hipLaunchKernelGGL(select_blocks_kernel, dim3(p.B), dim3(1024), sizeof(WgSelectScratch), st, p.block_max,
                        p.n_blocks, p.R, f.sel_blk, f.meta);
@@ -1340,7 +1333,7 @@ int launch_small_rescan(const ScanParams &p, const FinishParams &f, bool u8, hip
 
 int launch_small_final(const ScanParams &p, const FinishParams &f, bool u8, hipStream_t st)
 {
-    static bool attr = false;
+    static LdsLimitOnce attr;
     AVQ_TRY(set_max_lds(small_batch_final_kernel, &attr));
     size_t region = sizeof(WgSelectScratch);
     const size_t stage = (size_t)f.stage_rows * (f.d + 1) * 4;

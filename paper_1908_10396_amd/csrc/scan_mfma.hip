@@ -667,11 +667,8 @@ template <int NBT, bool STORE, bool ITEMS, bool FIXED>
 static int launch_mfma_one(const ScanParams &p, hipStream_t st)
 {
     auto kern = adc_mfma_scan_kernel<NBT, STORE, ITEMS, FIXED>;
-    static bool attr_done = false;
-    if (!attr_done) {
-        AVQ_HIP(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynLds));
-        attr_done = true;
-    }
+    static LdsLimitOnce attr_done; // per instantiation
+    AVQ_TRY(set_lds_limit((const void *)kern, kMaxDynLds, &attr_done));
     const int64_t waves = p.item_list ? (int64_t)p.max_items : (int64_t)p.n_tiles * p.n_chunks;
     const int64_t grid = (waves + kMfmaWaves - 1) / kMfmaWaves;
     if (grid > 0x7fffffff) { set_error("scan: grid too large"); return AVQ_EINVAL; }

@@ -554,11 +554,8 @@ int pq_joint_update_device(const float *x, int64_t n, int d, int M, int kc, int 
     hipLaunchKernelGGL(pq_update_init_kernel, dim3(vgrid), dim3(256), 0, st, D, ds, cnt, codebooks, c, b, y, dA);
     AVQ_HIP(hipGetLastError());
     const size_t lds = use_lds ? sizeof(double) * (size_t)D : 0;
-    static bool attr_done = false;
-    if (!attr_done) {
-        AVQ_HIP(hipFuncSetAttribute((const void *)pq_update_matvec_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024));
-        attr_done = true;
-    }
+    static LdsLimitOnce attr_done;
+    AVQ_TRY(set_lds_limit((const void *)pq_update_matvec_kernel, 64 * 1024, &attr_done));
     // y = A c0
     hipLaunchKernelGGL(pq_update_matvec_kernel, dim3(grid), dim3(256), lds, st, x, n, d, M, kc, bits, NB, codes, w, c, y, D, use_lds);
     AVQ_HIP(hipGetLastError());
