@@ -175,6 +175,32 @@ int avq_search(avq_index *idx, const float *queries, int32_t nq, int32_t k, int3
                int32_t lut_mode, int32_t leaves_to_search, int32_t *ids_out, float *scores_out,
                void *hip_stream);
 
+/* avq_search for callers that cannot allocate device memory: code that runs under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc. Same
+ * results as avq_search for the same arguments, on a flat index, for a handful
+ * of queries per call: it runs the launches avq_search uses for up to 35 queries
+ * (block maxima of the whole code array, selection of the best blocks, scan of
+ * those, exact re-scoring), and takes every scratch buffer of those kernels
+ * (tables, block maxima, selected blocks, candidate keys) from one array of
+ * AVQ_NOALLOC_SCRATCH_BYTES that is part of the library's code object: each GPU
+ * the library is loaded on holds its own copy from load time until the process
+ * ends. The call itself allocates nothing, frees nothing, records no events and
+ * does not synchronise; the array's address on the current device is looked up
+ * once, on the first call. queries / ids_out / scores_out: device pointers as
+ * for avq_search.
+ * AVQ_EINVAL: a partitioned index; nq > AVQ_NOALLOC_MAX_QUERIES; a request whose
+ * scratch (about 8 bytes per query and 256 stored points, plus 2 KiB per query
+ * and unit of reorder_k, plus the tables) exceeds the array -- the message
+ * states the bytes needed; the argument errors of avq_search.
+ * All calls on one GPU share that GPU's array, whatever the index or stream: two
+ * calls that overlap in time on one GPU race; issue them on one stream or order
+ * them with events. The array keeps the previous call's contents; nothing in it
+ * needs clearing between calls (every kernel writes what the next one reads). */
+#define AVQ_NOALLOC_SCRATCH_BYTES (64u << 20)
+#define AVQ_NOALLOC_MAX_QUERIES 32
+int avq_search_noalloc(avq_index *idx, const float *queries, int32_t nq, int32_t k, int32_t reorder_k,
+                       int32_t lut_mode, int32_t *ids_out, float *scores_out, void *hip_stream);
+
 /* Section 1's definition, exactly: the k points with the largest <q, x_i>
  * (fp32 fma chain in index order; ties by lower id) among all n stored
  * points. Same argument layout as avq_search. Ground truth for recall. */

@@ -21,7 +21,7 @@ STAGES = ("leaf_select", "lut", "scan", "merge", "finalize", "rescan", "sample")
 
 # every symbol include/avq.h declares
 SYMBOLS = [
-    "avq_create", "avq_destroy", "avq_train", "avq_encode", "avq_update_codebooks", "avq_search", "avq_brute_force",
+    "avq_create", "avq_destroy", "avq_train", "avq_encode", "avq_update_codebooks", "avq_search", "avq_search_noalloc", "avq_brute_force",
     "avq_set_codebooks", "avq_get_codebooks", "avq_set_leaf_centers", "avq_get_leaf_centers",
     "avq_set_database", "avq_get_codes", "avq_get_leaf_assign", "avq_size", "avq_debug_lut",
     "avq_debug_adc_scores", "avq_debug_leaf_select", "avq_debug_stream_codes", "avq_debug_unverified_queries", "avq_eta", "avq_set_tuning",
@@ -63,6 +63,7 @@ def lib():
         L.avq_encode.argtypes = [vp, vp, i64, vp]
         L.avq_update_codebooks.argtypes = [vp, vp, i64, i32, C.c_double, C.POINTER(i32), C.POINTER(C.c_double), vp]
         L.avq_search.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, vp, vp]
+        L.avq_search_noalloc.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp]
         L.avq_brute_force.argtypes = [vp, vp, i32, i32, vp, vp, vp]
         L.avq_set_codebooks.argtypes = [vp, vp]
         L.avq_get_codebooks.argtypes = [vp, vp]
@@ -255,6 +256,16 @@ class Index:
         _check(lib().avq_search(self._h, qp, nq, k, reorder_k, lut_mode, leaves_to_search,
                                 _dev(ids, torch.int32, "ids"), _dev(sc, torch.float32, "scores"),
                                 _stream_ptr(stream)))
+        return ids, sc
+
+    def search_noalloc(self, queries, k, reorder_k, lut_mode=LUT_F32, out=None, stream=None):
+        """avq_search_noalloc: the caller supplies `out` = (ids, scores) so that nothing is allocated."""
+        torch = _torch()
+        qp = _dev(queries, torch.float32, "queries")
+        ids, sc = out
+        _check(lib().avq_search_noalloc(self._h, qp, queries.shape[0], k, reorder_k, lut_mode,
+                                        _dev(ids, torch.int32, "ids"), _dev(sc, torch.float32, "scores"),
+                                        _stream_ptr(stream)))
         return ids, sc
 
     def brute_force(self, queries, k, stream=None):

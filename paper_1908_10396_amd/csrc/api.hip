@@ -5,6 +5,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <mutex>
 #include <new>
 
 #include "avq_internal.h"
@@ -81,9 +82,9 @@ struct StageTimer {
     hipStream_t st;
     hipEvent_t a = nullptr, b = nullptr;
     int stage;
-    StageTimer(avq_index *i, int stage_, hipStream_t s) : idx(i), st(s), stage(stage_)
+    StageTimer(avq_index *i, int stage_, hipStream_t s, bool enabled = true) : idx(i), st(s), stage(stage_)
     {
-        if (!idx->prof_on) return;
+        if (!idx->prof_on || !enabled) return; // (creating an event allocates)
         while (idx->prof_pool.size() < idx->prof_used + 2) {
             hipEvent_t e;
             if (hipEventCreate(&e) != hipSuccess) return;
@@ -842,15 +843,114 @@ static int check_query_args(const avq_index *idx, const float *queries, int32_t 
     return AVQ_OK;
 }
 
-extern "C" int avq_search(avq_index *idx, const float *queries, int32_t nq, int32_t k, int32_t reorder_k,
-                          int32_t lut_mode, int32_t leaves_to_search, int32_t *ids_out, float *scores_out,
-                          void *hip_stream)
+// ---- a handful of queries on a flat index ------------------------------------------------
+// Full scan recording block maxima, selection of the R best blocks, scan of those, final
+// selection with exact re-scoring. Its device scratch is described by SmallWs, so that the
+// same launches can run from buffers the index owns (avq_search) or from the library's static
+// scratch array (avq_search_noalloc).
+struct SmallWs {
+    float *lut;          // [nq][M][kc]      (unused when the scan computes its own tables)
+    uint8_t *lut8;       // [nq][M][kc]      (8-bit tables only)
+    float *scale, *bias; // [nq]             (8-bit tables only)
+    u64 *block_max;      // [nq][n_blocks]
+    u64 *cand;           // [nq][256 * R]
+    int32_t *sel_blk;    // [nq][R]
+    SmallMeta *meta;     // [nq]
+};
+
+// Lays the scratch out from `base` (256-byte aligned pieces); returns the bytes needed.
+// base == NULL: only the size.
+static size_t small_ws_carve(const avq_index *idx, int nq, int R, unsigned char *base, SmallWs *w)
+{
+    size_t off = 0;
+    auto take = [&](size_t bytes) -> void * {
+        const size_t at = (off + 255) & ~(size_t)255;
+        off = at + bytes;
+        return base ? (void *)(base + at) : nullptr;
+    };
+    const size_t entries = (size_t)nq * idx->cfg.M * idx->kc;
+    w->lut = (float *)take(entries * sizeof(float));
+    w->lut8 = (uint8_t *)take(entries);
+    w->scale = (float *)take(sizeof(float) * (size_t)nq);
+    w->bias = (float *)take(sizeof(float) * (size_t)nq);
+    w->block_max = (u64 *)take(sizeof(u64) * (size_t)nq * idx->n_blocks);
+    w->cand = (u64 *)take(sizeof(u64) * (size_t)nq * 256 * R);
+    w->sel_blk = (int32_t *)take(sizeof(int32_t) * (size_t)nq * R);
+    w->meta = (SmallMeta *)take(sizeof(SmallMeta) * (size_t)nq);
+    return off;
+}
+
+static int small_ws_from_index(avq_index *idx, int nq, int R, SmallWs *w)
+{
+    const size_t bytes = small_ws_carve(idx, nq, R, nullptr, w);
+    AVQ_TRY(idx->tmp.reserve(bytes));
+    small_ws_carve(idx, nq, R, (unsigned char *)idx->tmp.p, w);
+    return AVQ_OK;
+}
+
+// Launches only: no allocation, no synchronisation. timers: per-stage event pairs while profiling is on.
+static int search_small(avq_index *idx, const float *queries, int nq, int k, int reorder_k, bool u8, bool fuse_tables,
+                        const SmallWs &w, bool timers, int32_t *ids_out, float *scores_out, hipStream_t st)
+{
+    const avq_config &c = idx->cfg;
+    const int R = reorder_k ? reorder_k : k;
+    const int ns = (R + 63) / 64;
+    if (!fuse_tables) {
+        StageTimer t(idx, AVQ_STAGE_LUT, st, timers);
+        AVQ_TRY(launch_lut(queries, nq, idx->codebooks.as<float>(), c.d, c.M, idx->kc, w.lut, u8 ? w.lut8 : nullptr, w.scale,
+                           w.bias, st));
+    }
+    ScanParams p;
+    fill_scan_params(idx, nq, R, ns, &p);
+    p.lut = w.lut;
+    p.lut8 = w.lut8;
+    p.scale = w.scale;
+    p.bias = w.bias;
+    if (fuse_tables) {
+        p.fuse_queries = queries;
+        p.fuse_codebooks = idx->codebooks.as<float>();
+        p.fuse_d = c.d;
+    }
+    p.block_max = w.block_max;
+    p.n_tiles = nq;
+    p.n_chunks = 1;
+    p.max_wgs = idx->tune_target_wgs;
+    {
+        StageTimer t(idx, AVQ_STAGE_SCAN, st, timers);
+        AVQ_TRY(launch_block_max(p, u8, idx->tune_waves > 0 ? idx->tune_waves : 4, st));
+    }
+    FinishParams f;
+    f.x = idx->x;
+    f.queries = queries;
+    f.d = c.d;
+    f.k = k;
+    f.reorder = reorder_k != 0;
+    f.stage_rows = small_finish_stage_rows(p, c.d, u8);
+    f.cand_stride = (int64_t)256 * R;
+    f.cand = w.cand;
+    f.sel_blk = w.sel_blk;
+    f.meta = w.meta;
+    f.ids_out = ids_out;
+    f.scores_out = scores_out;
+    {
+        StageTimer t(idx, AVQ_STAGE_MERGE, st, timers);
+        AVQ_TRY(launch_small_select(p, f, st));
+    }
+    {
+        StageTimer t(idx, AVQ_STAGE_RESCAN, st, timers);
+        AVQ_TRY(launch_small_rescan(p, f, u8, st));
+    }
+    StageTimer t(idx, AVQ_STAGE_FINAL, st, timers);
+    return launch_small_final(p, f, u8, st);
+}
+
+
+static int check_search_args(const avq_index *idx, const float *queries, int32_t nq, int32_t k, int32_t reorder_k,
+                             int32_t lut_mode, int32_t leaves_to_search, const int32_t *ids_out, const float *scores_out)
 {
     AVQ_TRY(check_index(idx));
     AVQ_TRY(check_query_args(idx, queries, nq, lut_mode));
-    hipStream_t st = (hipStream_t)hip_stream;
     const avq_config &c = idx->cfg;
-    const bool ivf = c.n_leaves > 0;
     if (!ids_out || !scores_out) { set_error("avq_search: output pointer is NULL"); return AVQ_EINVAL; }
     if (k < 1 || k > AVQ_MAX_SELECT || k > idx->n || (reorder_k != 0 && (reorder_k < k || reorder_k > AVQ_MAX_SELECT))) {
         set_error("avq_search: need 1 <= k <= min(n, %d) and reorder_k == 0 or k <= reorder_k <= %d",
@@ -858,10 +958,21 @@ extern "C" int avq_search(avq_index *idx, const float *queries, int32_t nq, int3
         return AVQ_EINVAL;
     }
     if (reorder_k != 0 && !idx->x) { set_error("avq_search: re-scoring needs the datapoints"); return AVQ_ESTATE; }
-    if (ivf && (leaves_to_search < 1 || leaves_to_search > c.n_leaves || leaves_to_search > AVQ_MAX_SELECT)) {
+    if (c.n_leaves > 0 && (leaves_to_search < 1 || leaves_to_search > c.n_leaves || leaves_to_search > AVQ_MAX_SELECT)) {
         set_error("avq_search: leaves_to_search must be in [1, min(n_leaves, %d)]", AVQ_MAX_SELECT);
         return AVQ_EINVAL;
     }
+    return AVQ_OK;
+}
+
+extern "C" int avq_search(avq_index *idx, const float *queries, int32_t nq, int32_t k, int32_t reorder_k,
+                          int32_t lut_mode, int32_t leaves_to_search, int32_t *ids_out, float *scores_out,
+                          void *hip_stream)
+{
+    AVQ_TRY(check_search_args(idx, queries, nq, k, reorder_k, lut_mode, leaves_to_search, ids_out, scores_out));
+    hipStream_t st = (hipStream_t)hip_stream;
+    const avq_config &c = idx->cfg;
+    const bool ivf = c.n_leaves > 0;
     const int R = reorder_k ? reorder_k : k;
     const int ns = (R + 63) / 64;
     const int C = 64 * ns;
@@ -875,6 +986,11 @@ extern "C" int avq_search(avq_index *idx, const float *queries, int32_t nq, int3
     const bool fuse_tables = small && idx->tune_small_impl == 0 && small_batch_can_fuse_tables(c.bits, c.M, c.d, u8);
     const bool prefilter = !small && use_prefilter(idx, nq, lut_mode, R);
     const bool grouped = ivf && use_grouped_leaves(idx, nq, leaves_to_search, R);
+    if (small && idx->tune_small_impl == 0) {
+        SmallWs w;
+        AVQ_TRY(small_ws_from_index(idx, nq, R, &w));
+        return search_small(idx, queries, nq, k, reorder_k, u8, fuse_tables, w, true, ids_out, scores_out, st);
+    }
     if (!fuse_tables) {
         StageTimer t(idx, AVQ_STAGE_LUT, st);
         AVQ_TRY(build_tables(idx, queries, nq, (prefilter || grouped) ? AVQ_LUT_U8 : lut_mode, st));
@@ -883,15 +999,9 @@ extern "C" int avq_search(avq_index *idx, const float *queries, int32_t nq, int3
     if (prefilter) return search_through_candidates(idx, queries, nq, k, reorder_k, R, ns, false, ids_out, scores_out, st);
     ScanParams p;
     fill_scan_params(idx, nq, R, ns, &p);
-    if (fuse_tables) {
-        p.fuse_queries = queries;
-        p.fuse_codebooks = idx->codebooks.as<float>();
-        p.fuse_d = c.d;
-    }
     const int key_kind = (u8 && !ivf) ? 1 : 0;
     if (small) {
-        // A handful of queries: full scan recording block maxima, pick the R best blocks,
-        // scan only those with the list machinery.
+        // three-kernel variant of the same algorithm (kept as a cross-check)
         AVQ_TRY(idx->block_max.reserve(sizeof(u64) * (size_t)nq * idx->n_blocks));
         AVQ_TRY(idx->cand.reserve(sizeof(u64) * (size_t)nq * C));
         AVQ_TRY(idx->partial.reserve(sizeof(u64) * (size_t)nq * C));
@@ -905,42 +1015,13 @@ extern "C" int avq_search(avq_index *idx, const float *queries, int32_t nq, int3
             StageTimer t(idx, AVQ_STAGE_SCAN, st);
             AVQ_TRY(launch_block_max(p, u8, idx->tune_waves > 0 ? idx->tune_waves : 4, st));
         }
-        if (idx->tune_small_impl == 0) {
-            FinishParams f;
-            f.x = idx->x;
-            f.queries = queries;
-            f.d = c.d;
-            f.k = k;
-            f.reorder = reorder_k != 0;
-            f.stage_rows = small_finish_stage_rows(p, c.d, u8);
-            f.cand_stride = (int64_t)256 * R;
-            const size_t cand_bytes = sizeof(u64) * (size_t)nq * f.cand_stride;
-            const size_t sel_bytes = (sizeof(int32_t) * (size_t)nq * R + 15) & ~(size_t)15;
-            AVQ_TRY(idx->tmp.reserve(cand_bytes + sel_bytes + sizeof(SmallMeta) * (size_t)nq));
-            f.cand = idx->tmp.as<u64>();
-            f.sel_blk = (int32_t *)((char *)idx->tmp.p + cand_bytes);
-            f.meta = (SmallMeta *)((char *)idx->tmp.p + cand_bytes + sel_bytes);
-            f.ids_out = ids_out;
-            f.scores_out = scores_out;
-            {
-                StageTimer t(idx, AVQ_STAGE_MERGE, st);
-                AVQ_TRY(launch_small_select(p, f, st));
-            }
-            {
-                StageTimer t(idx, AVQ_STAGE_RESCAN, st);
-                AVQ_TRY(launch_small_rescan(p, f, u8, st));
-            }
-            StageTimer t(idx, AVQ_STAGE_FINAL, st);
-            return launch_small_final(p, f, u8, st);
-        }
-        // three-kernel variant of the same algorithm (kept as a cross-check)
         {
             StageTimer t(idx, AVQ_STAGE_MERGE, st);
             AVQ_TRY(launch_select_keys(p.block_max, nq, idx->n_blocks, ns, R, idx->cand.as<u64>(), st));
         }
         ScanShape shape;
         int rc = AVQ_EINVAL;
-        for (int w = 16; w >= 1 && rc != AVQ_OK; w /= 2) rc = scan_pick_shape(idx->NB, idx->cfg.bits, u8, ns, nq, true, 1, w, &shape);
+        for (int w16 = 16; w16 >= 1 && rc != AVQ_OK; w16 /= 2) rc = scan_pick_shape(idx->NB, idx->cfg.bits, u8, ns, nq, true, 1, w16, &shape);
         AVQ_TRY(rc);
         {
             StageTimer t(idx, AVQ_STAGE_RESCAN, st);
@@ -1027,6 +1108,63 @@ extern "C" int avq_search(avq_index *idx, const float *queries, int32_t nq, int3
     StageTimer t(idx, AVQ_STAGE_FINAL, st);
     return launch_finalize(cand, ns, nq, R, k, reorder_k != 0, key_kind, idx->x, c.d, queries,
                            idx->scale.as<float>(), idx->bias.as<float>(), ids_out, scores_out, st);
+}
+
+// ---- the entry point that allocates nothing ---------------------------------------------
+// Device scratch of avq_search_noalloc: one array per GPU, part of the library's code object,
+// held from the moment the library is loaded on that GPU until the process ends. In host code
+// the array's name only stands for the symbol; the address on the current device comes from
+// hipGetSymbolAddress and is looked up once per device.
+static __device__ __align__(256) unsigned char scratch[AVQ_NOALLOC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static unsigned char *g_scratch_ptr[kMaxDevices] = {};
+
+static int noalloc_scratch(unsigned char **out)
+{
+    int dev = -1;
+    AVQ_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) { set_error("avq_search_noalloc: device %d not supported", dev); return AVQ_EINVAL; }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        unsigned char *ptr = nullptr;
+        AVQ_HIP(hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) { set_error("avq_search_noalloc: no address for the scratch array"); return AVQ_EHIP; }
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return AVQ_OK;
+}
+
+extern "C" int avq_search_noalloc(avq_index *idx, const float *queries, int32_t nq, int32_t k, int32_t reorder_k,
+                                  int32_t lut_mode, int32_t *ids_out, float *scores_out, void *hip_stream)
+{
+    AVQ_TRY(check_index(idx));
+    const avq_config &c = idx->cfg;
+    if (c.n_leaves > 0) { set_error("avq_search_noalloc: flat index only"); return AVQ_EINVAL; }
+    AVQ_TRY(check_search_args(idx, queries, nq, k, reorder_k, lut_mode, 0, ids_out, scores_out));
+    if (nq > AVQ_NOALLOC_MAX_QUERIES) {
+        set_error("avq_search_noalloc: at most %d queries per call (got %d)", AVQ_NOALLOC_MAX_QUERIES, nq);
+        return AVQ_EINVAL;
+    }
+    const int R = reorder_k ? reorder_k : k;
+    const bool u8 = lut_mode == AVQ_LUT_U8;
+    SmallWs w;
+    const size_t need = small_ws_carve(idx, nq, R, nullptr, &w);
+    if (need > (size_t)AVQ_NOALLOC_SCRATCH_BYTES) {
+        set_error("avq_search_noalloc: %d queries x %lld points with reorder_k %d need %zu bytes of scratch, the library holds %zu",
+                  nq, (long long)idx->n, reorder_k, need, (size_t)AVQ_NOALLOC_SCRATCH_BYTES);
+        return AVQ_EINVAL;
+    }
+    if ((size_t)idx->NB * 256 * 4 > kMaxDynLds && !(c.bits == 4 && (size_t)c.M * 64 <= 60 * 1024)) {
+        set_error("avq_search_noalloc: the tables of this index do not fit the single-query kernels");
+        return AVQ_EINVAL;
+    }
+    unsigned char *base = nullptr;
+    AVQ_TRY(noalloc_scratch(&base));
+    small_ws_carve(idx, nq, R, base, &w);
+    const bool fuse_tables = small_batch_can_fuse_tables(c.bits, c.M, c.d, u8);
+    return search_small(idx, queries, nq, k, reorder_k, u8, fuse_tables, w, false, ids_out, scores_out, (hipStream_t)hip_stream);
 }
 
 extern "C" int avq_brute_force(avq_index *idx, const float *queries, int32_t nq, int32_t k,
