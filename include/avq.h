@@ -273,8 +273,11 @@ double avq_eta(int32_t d, double T, double norm, int32_t eta_mode);
  * the most workgroups per query of the block-maxima scan), "scan_waves"
  * (waves per scan workgroup), "scan_qt" (queries per tile), "small_batch_max"
  * (v > 0: batches of fewer than v queries on a flat index take the block-maxima
- * path; 1 disables that path; built in: 36 with 4-bit codes, 9 with 8-bit codes), "small_batch_impl" (0: one fused kernel after
- * the block-maxima scan; 1: the same algorithm as three kernels), "scan_mfma"
+ * path; 1 disables that path; built in: 36 with 4-bit codes, 9 with 8-bit codes), "small_batch_impl" (0: built in: where
+ * the code size has the kernels for it (8, 13, 25 or 32 code bytes per point) the full scan records, per block
+ * of 256 points, the largest sum of 8-bit images of the table entries -- a bound of the block's scores -- and
+ * only the blocks whose bound can reach the R-th best score are scored exactly; 2: the full scan always records
+ * exact block maxima; 1: that algorithm as three separate kernels), "scan_mfma"
  * (1: batches with 8-bit tables on 4-bit codes use the LDS-table scan instead
  * of the matrix-core scan; for that scan "scan_target_wgs" counts waves),
  * "scan_prefilter" (1: batches with fp32 tables on a flat index of 4-bit codes

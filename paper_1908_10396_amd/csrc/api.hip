@@ -854,9 +854,19 @@ struct SmallWs {
     float *scale, *bias; // [nq]             (8-bit tables only)
     u64 *block_max;      // [nq][n_blocks]
     u64 *cand;           // [nq][256 * R]
-    int32_t *sel_blk;    // [nq][R]
+    int32_t *sel_blk;    // [nq][R], or [nq][n_blocks] on the block-bound path
     SmallMeta *meta;     // [nq]
+    uint32_t *block_bound; // [nq][n_blocks]   (block-bound path)
+    BoundMeta *bound_meta; // [nq]             (block-bound path)
+    uint8_t *bound_tbl;    // [nq][NB][256]    (block-bound path)
 };
+
+// 0: the scan records block maxima of 8-bit sums (bounds of the scores) where the code size has its
+// kernels; 2 (tuning "small_batch_impl"): always the exact block maxima.
+static bool small_uses_bounds(const avq_index *idx)
+{
+    return idx->tune_small_impl == 0 && block_bound_supported(idx->NB, idx->cfg.bits);
+}
 
 // Lays the scratch out from `base` (256-byte aligned pieces); returns the bytes needed.
 // base == NULL: only the size.
@@ -875,8 +885,12 @@ static size_t small_ws_carve(const avq_index *idx, int nq, int R, unsigned char 
     w->bias = (float *)take(sizeof(float) * (size_t)nq);
     w->block_max = (u64 *)take(sizeof(u64) * (size_t)nq * idx->n_blocks);
     w->cand = (u64 *)take(sizeof(u64) * (size_t)nq * 256 * R);
-    w->sel_blk = (int32_t *)take(sizeof(int32_t) * (size_t)nq * R);
+    const bool bounds = small_uses_bounds(idx);
+    w->sel_blk = (int32_t *)take(sizeof(int32_t) * (size_t)nq * (bounds ? (size_t)idx->n_blocks : (size_t)R));
     w->meta = (SmallMeta *)take(sizeof(SmallMeta) * (size_t)nq);
+    w->block_bound = (uint32_t *)take(bounds ? sizeof(uint32_t) * (size_t)nq * idx->n_blocks : 0);
+    w->bound_meta = (BoundMeta *)take(bounds ? sizeof(BoundMeta) * (size_t)nq : 0);
+    w->bound_tbl = (uint8_t *)take(bounds ? (size_t)nq * idx->NB * 256 : 0);
     return off;
 }
 
@@ -895,6 +909,7 @@ static int search_small(avq_index *idx, const float *queries, int nq, int k, int
     const avq_config &c = idx->cfg;
     const int R = reorder_k ? reorder_k : k;
     const int ns = (R + 63) / 64;
+    const bool bounds = small_uses_bounds(idx);
     if (!fuse_tables) {
         StageTimer t(idx, AVQ_STAGE_LUT, st, timers);
         AVQ_TRY(launch_lut(queries, nq, idx->codebooks.as<float>(), c.d, c.M, idx->kc, w.lut, u8 ? w.lut8 : nullptr, w.scale,
@@ -915,11 +930,21 @@ static int search_small(avq_index *idx, const float *queries, int nq, int k, int
     p.n_tiles = nq;
     p.n_chunks = 1;
     p.max_wgs = idx->tune_target_wgs;
+    p.block_bound = w.block_bound;
+    p.bound_meta = w.bound_meta;
+    p.lut_out = fuse_tables ? w.lut : nullptr;
+    p.bound_tbl = w.bound_tbl;
+    if (bounds) {
+        StageTimer t(idx, AVQ_STAGE_LUT, st, timers);
+        AVQ_TRY(launch_bound_tables(p, u8, st));
+    }
     {
         StageTimer t(idx, AVQ_STAGE_SCAN, st, timers);
-        AVQ_TRY(launch_block_max(p, u8, idx->tune_waves > 0 ? idx->tune_waves : 4, st));
+        if (bounds) AVQ_TRY(launch_block_bound(p, idx->tune_waves, st));
+        else AVQ_TRY(launch_block_max(p, u8, idx->tune_waves > 0 ? idx->tune_waves : 4, st));
     }
     FinishParams f;
+    memset(&f, 0, sizeof(f));
     f.x = idx->x;
     f.queries = queries;
     f.d = c.d;
@@ -932,13 +957,27 @@ static int search_small(avq_index *idx, const float *queries, int nq, int k, int
     f.meta = w.meta;
     f.ids_out = ids_out;
     f.scores_out = scores_out;
+    if (bounds) {
+        f.block_max = w.block_max;
+        f.n_blocks = idx->n_blocks;
+        f.n_valid = (int32_t)idx->n;
+        f.NB = idx->NB;
+        f.M = c.M;
+        f.bits = c.bits;
+        f.u8 = u8 ? 1 : 0;
+        f.codes_logical = idx->codes_logical.as<uint8_t>();
+        f.lut = w.lut;
+        f.lut8 = w.lut8;
+    }
     {
         StageTimer t(idx, AVQ_STAGE_MERGE, st, timers);
-        AVQ_TRY(launch_small_select(p, f, st));
+        if (bounds) AVQ_TRY(launch_select_bound_blocks(p, f, u8, st));
+        else AVQ_TRY(launch_small_select(p, f, st));
     }
     {
         StageTimer t(idx, AVQ_STAGE_RESCAN, st, timers);
-        AVQ_TRY(launch_small_rescan(p, f, u8, st));
+        if (bounds) AVQ_TRY(launch_rescan_listed(p, f, u8, st));
+        else AVQ_TRY(launch_small_rescan(p, f, u8, st));
     }
     StageTimer t(idx, AVQ_STAGE_FINAL, st, timers);
     return launch_small_final(p, f, u8, st);
@@ -983,10 +1022,10 @@ extern "C" int avq_search(avq_index *idx, const float *queries, int32_t nq, int3
     const int small_max = idx->tune_small_batch >= 0 ? idx->tune_small_batch : (c.bits == 4 ? 35 : 8);
     const bool small = !ivf && nq <= small_max;
     // the single-query kernels compute short fp32 tables themselves (one launch less)
-    const bool fuse_tables = small && idx->tune_small_impl == 0 && small_batch_can_fuse_tables(c.bits, c.M, c.d, u8);
+    const bool fuse_tables = small && idx->tune_small_impl != 1 && small_batch_can_fuse_tables(c.bits, c.M, c.d, u8);
     const bool prefilter = !small && use_prefilter(idx, nq, lut_mode, R);
     const bool grouped = ivf && use_grouped_leaves(idx, nq, leaves_to_search, R);
-    if (small && idx->tune_small_impl == 0) {
+    if (small && idx->tune_small_impl != 1) {
         SmallWs w;
         AVQ_TRY(small_ws_from_index(idx, nq, R, &w));
         return search_small(idx, queries, nq, k, reorder_k, u8, fuse_tables, w, true, ids_out, scores_out, st);

@@ -65,6 +65,9 @@ int launch_lut(const float *queries, int nq, const float *codebooks, int d, int 
                float *lut_f32, uint8_t *lut_u8, float *scale, float *bias, hipStream_t st);
 
 // ---- scan.hip --------------------------------------------------------------
+// What relates the 8-bit sums of the block-bound kernel to fp32 scores (see scan.hip): the sum of the byte
+// positions' smallest entries, the sum of their largest magnitudes, and the units per score unit.
+struct BoundMeta { double sum_lo, amax; float c; int32_t pad; };
 struct ScanParams {
     const uint8_t *codes; // blocked layout
     int64_t n_blocks;     // blocks in the whole index
@@ -88,7 +91,14 @@ struct ScanParams {
     const int32_t *leaf_blk;                     // [n_leaves + 1] first block of each leaf
     int32_t Lp;
     const u64 *block_keys; // block-list mode: [B][64*ns], the keys of the blocks to scan
-    u64 *block_max;        // block-max kernel: [B][n_blocks]
+    u64 *block_max;        // block-max kernel: [B][n_blocks]; rescan of listed blocks: best key of the j-th listed block
+    // block-bound scan (small batches, specialised code sizes): [B][n_blocks] block maxima of the 8-bit sums;
+    // [B] what the margin of those sums follows from (fp32 tables); lut_out (may be NULL): when the table kernel of
+    // that scan computes the fp32 tables itself (fuse_queries), [B][M][16] receives them
+    uint32_t *block_bound;
+    struct BoundMeta *bound_meta;
+    float *lut_out;
+    uint8_t *bound_tbl;    // [B][NB][256] the byte tables of the block-bound scan (made by launch_bound_tables)
     u64 *partial;         // [n_tiles*QT][n_chunks][64*ns]
     u64 *lists_ws;        // NULL: candidate lists in LDS; else scratch [grid][waves][QT][64*ns]
     // matrix-core kernel, both zeroed before the launch: [B] best known bound of the R-th best
@@ -181,12 +191,27 @@ struct FinishParams {
     int32_t stage_rows;    // rows of x staged in LDS per pass of the re-scoring (small_finish_stage_rows)
     u64 *cand;             // scratch [B][cand_stride], cand_stride >= 256 * R
     int64_t cand_stride;
-    int32_t *sel_blk;      // scratch [B][R]: the selected blocks
+    int32_t *sel_blk;      // scratch: the selected blocks, [B][R] (block maxima) or [B][n_blocks] (block bounds)
     SmallMeta *meta;       // scratch [B]
     int32_t *ids_out;      // [B][k]
     float *scores_out;     // [B][k]
+    // block-bound path only: what the final kernel needs to rebuild a candidate list that overflowed
+    // (more than cand_stride points at or above the bound: heavy duplication). NULL block_max: never.
+    const u64 *block_max;        // [B][n_blocks], entry j = best key of the j-th listed block
+    int64_t n_blocks;
+    int32_t n_valid, NB, M, bits, u8;
+    const uint8_t *codes_logical; // [n][NB]
+    const float *lut;             // [B][M][kc] fp32 tables (u8 == 0)
+    const uint8_t *lut8;          // [B][M][kc] 8-bit tables (u8 == 1)
 };
 int small_finish_stage_rows(const ScanParams &p, int d, bool u8);
+// The same search through block maxima of 8-bit sums (bounds, not scores: scan.hip): specialised code
+// sizes only. launch_bound_tables -> launch_block_bound -> launch_select_bound_blocks -> launch_rescan_listed -> launch_small_final.
+bool block_bound_supported(int NB, int bits);
+int launch_bound_tables(const ScanParams &p, bool u8, hipStream_t st);
+int launch_block_bound(const ScanParams &p, int waves, hipStream_t st);
+int launch_select_bound_blocks(const ScanParams &p, const FinishParams &f, bool u8, hipStream_t st);
+int launch_rescan_listed(const ScanParams &p, const FinishParams &f, bool u8, hipStream_t st);
 int launch_small_select(const ScanParams &p, const FinishParams &f, hipStream_t st);
 int launch_small_rescan(const ScanParams &p, const FinishParams &f, bool u8, hipStream_t st);
 int launch_small_final(const ScanParams &p, const FinishParams &f, bool u8, hipStream_t st);

@@ -948,6 +948,376 @@ rescan_blocks_kernel(const ScanParams p, const FinishParams f)
     }
 }
 
+// ---- a handful of queries: block bounds from 8-bit tables, then exact scores of few blocks ----
+//
+// The full scan of a single query is bound by reading the codes only if a point's score costs
+// almost nothing, and a table lookup in LDS costs the same 64 lanes x 4 bytes per instruction
+// whatever the entry holds. So the full scan does not form the scores at all: per byte
+// position b it holds a 256-entry table of *bytes*, U[b][v], an 8-bit image of the entry (or,
+// for 4-bit codes, of the sum of the two entries) that byte value v stands for. 256 bytes are
+// 64 LDS words, one per bank: a wave's reads of such a table never conflict, one read and one
+// integer add per code byte. The integer sum I of a point determines its score within a margin:
+//   fp32 tables:  U[b][v] = rne((t_b(v) - lo_b) * c), t_b(v) the fp32 entry (4-bit codes: the fp32
+//     sum of the two entries of byte v, which is also the first step of the defined order of
+//     additions), lo_b = min_v t_b(v), c = 255 / max_b(max_v t_b(v) - lo_b). Each term moves by at
+//     most 1/2 + 4e-5 units of 1/c (rounding to the nearest integer plus the two fp32 roundings
+//     before it), and the fp32 score s (NB - 1 additions in order, each within 2^-24 of the partial
+//     sum's magnitude, at most A = sum_b max_v |t_b(v)|) is within rho = NB * 2^-24 * A of the real
+//     sum, so  | s - (sum_b lo_b + I / c) | <= E / c + rho,  E = NB * (1/2 + 4e-5).
+//   8-bit tables, 4-bit codes: U[b][v] = (Q[2b][v & 15] + Q[2b+1][v >> 4] + 1) >> 1, so the exact
+//     integer score lies in [2 I - NB, 2 I];   8-bit tables, 8-bit codes: U = Q, I is the score.
+// Let theta be the R-th largest of the block maxima of I. R blocks hold a point with I >= theta each,
+// so the R-th best score is at least low(theta), and a point with I < theta - m, m = the margin in
+// units of I that makes high(I) < low(theta), is not among the R best. Hence: the blocks whose
+// maximum reaches theta - m are scored exactly, and of their points those at or above low(theta)
+// become candidates -- a superset of the R best by the exact scores, whatever the data.
+// block_bound_kernel writes the block maxima of I; select_bound_blocks_kernel finds theta (a
+// histogram: I < 8192) and lists the blocks; rescan_listed_blocks_kernel scores them exactly.
+
+// The byte tables U of one query (one workgroup each), written to bound_tbl[q][NB][256] for the scan to copy
+// into LDS: made once here, not once per workgroup of the scan, because a scan of a few microseconds cannot
+// hide the making (6400 entries at 25 code bytes: as much work as scanning four blocks) behind its loads.
+// U8: the search uses 8-bit tables; WIDE: 8-bit codes (else 4-bit codes, two per byte). With 4-bit codes
+// the 16-entry tables are read (p.lut, p.lut8) or, for fp32 tables when p.fuse_queries is set, computed
+// here (the fma chain of the table kernel) and left in p.lut_out for the kernels that follow.
+template <bool U8, bool WIDE>
+__global__ void __launch_bounds__(1024)
+bound_tables_kernel(const ScanParams p)
+{
+    constexpr int kMaxNB = 32;
+    __shared__ __align__(16) float nib[WIDE ? 4 : 2 * kMaxNB * 16]; // 4-bit codes: the 16-entry tables (8-bit tables: as bytes)
+    __shared__ float tmin[2 * kMaxNB], tmax[2 * kMaxNB], lo_s[kMaxNB], c_s;
+    const int tid = threadIdx.x, nt = blockDim.x;
+    const int lane = tid & 63, wave = tid >> 6, n_waves = nt >> 6;
+    const int q = blockIdx.x;
+    const int NB = p.NB;
+    uint32_t *out = (uint32_t *)(p.bound_tbl + (size_t)q * NB * 256);
+    if constexpr (U8 && WIDE) {
+        const uint32_t *L = (const uint32_t *)(p.lut8 + (size_t)q * NB * 256);
+        for (int it = tid; it < NB * 64; it += nt) out[it] = L[it];
+        return;
+    }
+    if constexpr (U8 && !WIDE) {
+        unsigned char *n8 = (unsigned char *)nib;
+        const int live = p.M * 16;
+        const uint8_t *L = p.lut8 + (size_t)q * live;
+        for (int e = tid; e < 2 * NB * 16; e += nt) n8[e] = e < live ? L[e] : (uint8_t)0;
+        __syncthreads();
+        for (int it = tid; it < NB * 64; it += nt) {
+            const int b = it >> 6, v0 = (it & 63) * 4;
+            const uint32_t hi = n8[32 * b + 16 + (v0 >> 4)];
+            uint32_t pack = 0;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) pack |= (((uint32_t)n8[32 * b + (v0 & 15) + k] + hi + 1u) >> 1) << (8 * k);
+            out[it] = pack;
+        }
+        return;
+    }
+    if constexpr (!U8) {
+        const float *Lw = nullptr;
+        if constexpr (WIDE) {
+            Lw = p.lut + (size_t)q * NB * 256;
+            for (int b = wave; b < NB; b += n_waves) {
+                const float4 e = ((const float4 *)(Lw + (size_t)b * 256))[lane];
+                float mn = fminf(fminf(e.x, e.y), fminf(e.z, e.w)), mx = fmaxf(fmaxf(e.x, e.y), fmaxf(e.z, e.w));
+#pragma unroll
+                for (int m = 32; m > 0; m >>= 1) {
+                    mn = fminf(mn, __shfl_xor(mn, m, 64));
+                    mx = fmaxf(mx, __shfl_xor(mx, m, 64));
+                }
+                if (lane == 0) { tmin[b] = mn; tmax[b] = mx; }
+            }
+        } else {
+            // one entry per thread (2 * NB * 16 <= 1024 = blockDim.x); a table's 16 entries sit in 16 neighbouring
+            // lanes: its extremes by four exchanges
+            const int live = p.M * 16, e = tid;
+            float v = 0.0f;
+            if (e < live) {
+                if (p.fuse_queries != nullptr) {
+                    const int ds = p.fuse_d / p.M;
+                    const float *c = p.fuse_codebooks + (size_t)e * ds;
+                    const float *qm = p.fuse_queries + (size_t)q * p.fuse_d + (e >> 4) * ds;
+                    for (int l = 0; l < ds; ++l) v = __fmaf_rn(qm[l], c[l], v);
+                    if (p.lut_out != nullptr) p.lut_out[(size_t)q * live + e] = v;
+                } else {
+                    v = p.lut[(size_t)q * live + e];
+                }
+            }
+            float mn = v, mx = v;
+#pragma unroll
+            for (int m = 1; m < 16; m <<= 1) {
+                mn = fminf(mn, __shfl_xor(mn, m, 64));
+                mx = fmaxf(mx, __shfl_xor(mx, m, 64));
+            }
+            if (e < 2 * NB * 16) {
+                nib[e] = v;
+                if ((e & 15) == 0) { tmin[e >> 4] = mn; tmax[e >> 4] = mx; }
+            }
+        }
+        __syncthreads();
+        // Range of every byte position's entries (fp32 addition is monotone: the extremes of the sums of two
+        // entries are the sums of the extremes), the units per score unit, and what the margin follows from.
+        if (wave == 0) {
+            float lo = 0.0f, hi = 0.0f;
+            if (lane < NB) {
+                if constexpr (WIDE) { lo = tmin[lane]; hi = tmax[lane]; }
+                else { lo = __fadd_rn(tmin[2 * lane], tmin[2 * lane + 1]); hi = __fadd_rn(tmax[2 * lane], tmax[2 * lane + 1]); }
+                lo_s[lane] = lo;
+            }
+            float range = lane < NB ? __fsub_rn(hi, lo) : 0.0f;
+            double sum_lo = (double)lo, amax = (double)fmaxf(fabsf(lo), fabsf(hi));
+#pragma unroll
+            for (int m = 32; m > 0; m >>= 1) {
+                range = fmaxf(range, __shfl_xor(range, m, 64));
+                sum_lo += __shfl_xor(sum_lo, m, 64);
+                amax += __shfl_xor(amax, m, 64);
+            }
+            const float c = range > 1e-30f ? __fdiv_rn(255.0f, range) : 0.0f;
+            if (lane == 0) {
+                c_s = c;
+                BoundMeta bm;
+                bm.sum_lo = sum_lo; bm.amax = amax; bm.c = c; bm.pad = 0;
+                p.bound_meta[q] = bm;
+            }
+        }
+        __syncthreads();
+        const float c = c_s;
+        for (int it = tid; it < NB * 64; it += nt) {
+            const int b = it >> 6, v0 = (it & 63) * 4;
+            const float lo_b = lo_s[b];
+            float t[4];
+            if constexpr (WIDE) {
+                const float4 e = ((const float4 *)(Lw + (size_t)b * 256))[it & 63];
+                t[0] = e.x; t[1] = e.y; t[2] = e.z; t[3] = e.w;
+            } else {
+                const float hi = nib[32 * b + 16 + (v0 >> 4)];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) t[k] = __fadd_rn(nib[32 * b + (v0 & 15) + k], hi);
+            }
+            uint32_t pack = 0;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                float u = rintf(__fmul_rn(__fsub_rn(t[k], lo_b), c));
+                u = fminf(fmaxf(u, 0.0f), 255.0f);
+                pack |= (uint32_t)u << (8 * k);
+            }
+            out[it] = pack;
+        }
+    }
+}
+
+// The full scan: block maxima of the sums of the byte tables' entries. A wave's loads come back in the order
+// they were issued, so the workgroup's copy of the tables is asked for before the wave's first block of codes.
+template <int NBT>
+__global__ void __launch_bounds__(1024)
+block_bound_kernel(const ScanParams p)
+{
+    static_assert(NBT != 0 && NBT <= 32, "specialised code sizes only");
+    constexpr int kWords = NBT * 64, kPer = 8; // table words per thread: kWords <= 2048 = kPer * 256 <= kPer * blockDim.x
+    __shared__ __align__(16) unsigned char tbl8[NBT * 256];
+    const int tid = threadIdx.x, nt = blockDim.x;
+    const int lane = tid & 63, wave = tid >> 6, n_waves = nt >> 6;
+    const int q = blockIdx.y;
+    const int64_t step = (int64_t)gridDim.x * n_waves;
+    int64_t blk = (int64_t)blockIdx.x * n_waves + wave;
+    BlockRegs<NBT> regs, nxt;
+    {
+        const uint32_t *src = (const uint32_t *)(p.bound_tbl + (size_t)q * NBT * 256);
+        uint32_t tv[kPer];
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            const int it = tid + i * nt;
+            tv[i] = it < kWords ? src[it] : 0u;
+        }
+        asm volatile("" ::: "memory");
+        if (blk < p.n_blocks) load_block<NBT>(regs, p.codes, blk, lane);
+        asm volatile("" ::: "memory");
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            const int it = tid + i * nt;
+            if (it < kWords) ((uint32_t *)tbl8)[it] = tv[i];
+        }
+    }
+    __syncthreads();
+
+    for (; blk < p.n_blocks; blk += step) {
+        const bool more = blk + step < p.n_blocks;
+        if (more) load_block<NBT>(nxt, p.codes, blk + step, lane);
+        uint32_t acc[4] = {0u, 0u, 0u, 0u};
+        auto plane = [&](uint32_t w, const unsigned char *t) {
+            acc[0] += t[w & 0xffu];
+            acc[1] += t[(w >> 8) & 0xffu];
+            acc[2] += t[(w >> 16) & 0xffu];
+            acc[3] += t[w >> 24];
+        };
+#pragma unroll
+        for (int j = 0; j < NBT / 4; ++j) {
+            const unsigned char *t = tbl8 + (size_t)j * 1024;
+            plane(regs.rows[j].x, t);
+            plane(regs.rows[j].y, t + 256);
+            plane(regs.rows[j].z, t + 512);
+            plane(regs.rows[j].w, t + 768);
+            // keeps a row's sixteen reads together and the sums in four registers (see nibble_accumulate)
+            asm volatile("" : "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3]));
+        }
+#pragma unroll
+        for (int tt = 0; tt < NBT % 4; ++tt) plane(regs.tails[tt], tbl8 + (size_t)((NBT / 4) * 4 + tt) * 256);
+        uint32_t best = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (blk * 256 + 4 * lane + i < p.n_valid) best = acc[i] > best ? acc[i] : best;
+#pragma unroll
+        for (int m = 32; m > 0; m >>= 1) {
+            const uint32_t o = (uint32_t)__shfl_xor((int)best, m, 64);
+            best = o > best ? o : best;
+        }
+        if (lane == 0) p.block_bound[(size_t)q * p.n_blocks + blk] = best;
+        if (more) regs = nxt;
+    }
+}
+
+// One workgroup per query: theta = the R-th largest block maximum of the 8-bit sums, the list of the blocks
+// whose maximum reaches theta - margin, and the lower bound of the R-th best exact score as a key
+// threshold (meta[q].t1). kind 0: fp32 tables (margin and bound from bound_meta, see above), 1: 8-bit
+// tables on 4-bit codes (sums halved), 2: 8-bit tables on 8-bit codes (sums exact).
+__global__ void __launch_bounds__(1024)
+select_bound_blocks_kernel(const uint32_t *__restrict__ block_bound, int64_t n_blocks, int R, int NB, int kind,
+                           const BoundMeta *__restrict__ bound_meta, int32_t *__restrict__ sel_blk,
+                           SmallMeta *__restrict__ meta)
+{
+    constexpr int kBins = 8192; // sums are at most 255 * 32
+    __shared__ uint32_t hist[kBins];
+    __shared__ uint32_t wave_sum[16];
+    __shared__ uint32_t theta_s, n_sel;
+    const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63, wave = tid >> 6, n_waves = nt >> 6;
+    const int q = blockIdx.x;
+    const uint32_t *bb = block_bound + (size_t)q * n_blocks;
+    for (int b = tid; b < kBins; b += nt) hist[b] = 0u;
+    if (tid == 0) { theta_s = 0u; n_sel = 0u; }
+    __syncthreads();
+    for (int64_t b = tid; b < n_blocks; b += nt) atomicAdd(&hist[bb[b] < kBins ? bb[b] : kBins - 1], 1u);
+    __syncthreads();
+    const uint32_t need = (uint32_t)(n_blocks < R ? n_blocks : R);
+    const int per = kBins / 1024; // bins per thread (nt == 1024)
+    uint32_t mine = 0;
+    for (int j = 0; j < per; ++j) mine += hist[tid * per + j];
+    uint32_t suf = mine;
+    for (int m = 1; m < 64; m <<= 1) {
+        const uint32_t o = (uint32_t)__shfl_down((int)suf, m, 64);
+        if (lane + m < 64) suf += o;
+    }
+    if (lane == 0) wave_sum[wave] = suf;
+    __syncthreads();
+    uint32_t above = suf - mine;
+    for (int w = wave + 1; w < n_waves; ++w) above += wave_sum[w];
+    for (int j = per - 1; j >= 0; --j) {
+        const uint32_t h = hist[tid * per + j];
+        if (above < need && need <= above + h) theta_s = (uint32_t)(tid * per + j);
+        above += h;
+    }
+    __syncthreads();
+    const int theta = (int)theta_s;
+    int margin;
+    u64 t1;
+    if (kind == 0) {
+        const BoundMeta bm = bound_meta[q];
+        const double E = (double)NB * (0.5 + 4e-5);
+        const double rho = (double)NB * 5.9604644775390625e-8 * bm.amax * 1.000001;
+        const double c = (double)bm.c;
+        if (c > 0.0) {
+            margin = (int)ceil(2.0 * E + 2.0 * rho * c) + 1;
+            const double low = bm.sum_lo + ((double)theta - E) / c - rho;
+            float lf = (float)(low - fabs(low) * 1e-7 - 1e-30);
+            if ((double)lf > low) lf = nextafterf(lf, -INFINITY);
+            t1 = (u64)ord_from_f32(lf) << 32;
+        } else {
+            margin = kBins; // flat tables: every block, every point
+            t1 = 1ull;
+        }
+    } else if (kind == 1) {
+        margin = (NB + 1) / 2;
+        const int low = 2 * theta - NB;
+        t1 = (u64)(uint32_t)((low > 0 ? low : 0) + 1) << 32;
+    } else {
+        margin = 0;
+        t1 = (u64)(uint32_t)(theta + 1) << 32;
+    }
+    if (n_blocks < R) t1 = 1ull; // fewer blocks than R: no R points are known to reach any bound
+    const uint32_t cut = theta > margin ? (uint32_t)(theta - margin) : 0u;
+    for (int64_t b = tid; b < n_blocks; b += nt)
+        if (bb[b] >= cut) sel_blk[(size_t)q * n_blocks + atomicAdd(&n_sel, 1u)] = (int32_t)b;
+    __syncthreads();
+    if (tid == 0) {
+        meta[q].t1 = t1;
+        meta[q].n_sel = n_sel;
+        meta[q].n_cand = 0u;
+    }
+}
+
+// Exact scores of the listed blocks of every query, the waves of a query's workgroups taking the blocks
+// in turn: every point whose key reaches meta[q].t1 is appended to the query's candidates (beyond
+// f.cand_stride of them the count keeps running and the keys are dropped: the final kernel then
+// rebuilds the candidates from block_max), and block_max[q][j] receives the best key of the j-th listed block.
+template <bool U8, int NBT, bool NIB>
+__global__ void __launch_bounds__(256)
+rescan_listed_blocks_kernel(const ScanParams p, const FinishParams f)
+{
+    typedef uint32_t entry_t;
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n_waves = blockDim.x >> 6;
+    const int NB = NBT ? NBT : p.NB;
+    const int q = blockIdx.y;
+    const int n_sel = (int)f.meta[q].n_sel;
+    if ((int)(blockIdx.x * n_waves) >= n_sel) return; // whole workgroup idle
+    const int step = (int)gridDim.x * n_waves;
+    int j = blockIdx.x * n_waves + wave;
+    const int32_t *sel = f.sel_blk + (size_t)q * p.n_blocks;
+    BlockRegs<NBT> regs;
+    int64_t blk = j < n_sel ? sel[j] : 0;
+    if (j < n_sel) load_block<NBT>(regs, p.codes, blk, lane);
+    if (NIB) nibble_tables_fill<U8>(smem, p, q, NB);
+    else build_tables<1, U8>((entry_t *)smem, p, q, NB);
+    __syncthreads();
+    const u64 t1 = f.meta[q].t1;
+    u64 *cand = f.cand + (size_t)q * f.cand_stride;
+    for (; j < n_sel; j += step) {
+        float sf[4];
+        uint32_t si[4];
+        if (NIB) {
+            nibble_accumulate<U8, NBT>(smem, regs, p.codes + (size_t)blk * 256 * NB, NB, lane, sf, si);
+        } else {
+            entry_t acc[4];
+            accumulate_block<1, U8, NBT>((const entry_t *)smem, regs, p.codes, blk, NB, lane, acc);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { si[i] = acc[i]; sf[i] = __uint_as_float(acc[i]); }
+        }
+        const int64_t this_blk = blk;
+        if (j + step < n_sel) { // the next block's codes travel while this one's candidates are written
+            blk = sel[j + step];
+            load_block<NBT>(regs, p.codes, blk, lane);
+        }
+        u64 best = 0ull;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int64_t slot = this_blk * 256 + 4 * lane + i;
+            const uint32_t ord = U8 ? (si[i] + 1u) : ord_from_f32(sf[i]);
+            const u64 key = slot < p.n_valid ? make_key(ord, (int32_t)slot) : 0ull;
+            best = key > best ? key : best;
+            const bool hit = key >= t1 && key != 0ull;
+            const u64 mask = __builtin_amdgcn_ballot_w64(hit);
+            if (mask == 0ull) continue;
+            uint32_t base_pos = 0;
+            if (lane == 0) base_pos = atomicAdd(&f.meta[q].n_cand, (uint32_t)__builtin_popcountll(mask));
+            base_pos = (uint32_t)__shfl((int)base_pos, 0, 64);
+            const u64 at = (u64)base_pos + (u64)__builtin_popcountll(mask & ((1ull << lane) - 1ull));
+            if (hit && at < (u64)f.cand_stride) cand[at] = key;
+        }
+#pragma unroll
+        for (int m = 32; m > 0; m >>= 1) best = umax64(best, shfl_xor_u64(best, m));
+        if (lane == 0) p.block_max[(size_t)q * p.n_blocks + j] = best;
+    }
+}
+
 // Number of keys of keys[0..c) above `mine`, counted by four neighbouring lanes (part =
 // lane & 3 takes every fourth key); all four must call it together.
 __device__ __forceinline__ int rank_by_four(const u64 *keys, int c, u64 mine, int part)
@@ -980,10 +1350,69 @@ small_batch_final_kernel(const FinishParams f, int R, int key_kind, const float 
     u64 *clist = (u64 *)region;                                                   // [<= kSelList] candidate keys
     float *stage = (float *)region;                                               // [stage_rows][d + 1]
 
-    const int n_cand = (int)f.meta[q].n_cand;
-    const u64 *cand = f.cand + (size_t)q * f.cand_stride;
+    int n_cand = (int)f.meta[q].n_cand;
+    u64 *cand = f.cand + (size_t)q * f.cand_stride;
     for (int l = tid; l < f.d; l += nt) qs[l] = f.queries[(size_t)q * f.d + l];
     if (tid < 4) counters[tid] = 0u;
+    if (f.meta[q].n_cand > (uint32_t)f.cand_stride && f.block_max != nullptr) {
+        // More points reached the bound than the buffer holds (a heap of equal scores at the top). The listed
+        // blocks' exact maxima are known: the R best points lie in the R blocks with the largest maxima, at or
+        // above the R-th largest of them, t. Those blocks are scored again here, point by point from the logical
+        // codes and the tables in global memory, in the defined order of additions; at most 256 R keys reach t.
+        const int n_sel = (int)f.meta[q].n_sel;
+        const u64 *bm = f.block_max + (size_t)q * f.n_blocks;
+        const int32_t *selb = f.sel_blk + (size_t)q * f.n_blocks;
+        const u64 t = wg_select_threshold(bm, n_sel, R, sel);
+        __syncthreads();
+        const int lane = tid & 63, wave = tid >> 6, n_waves = nt >> 6;
+        const int kc = 1 << f.bits;
+        for (int j = wave; j < n_sel; j += n_waves) {
+            const u64 top = bm[j];
+            if (top < t || top == 0ull) continue;
+            const int64_t blk = selb[j];
+            for (int i = 0; i < 4; ++i) {
+                const int64_t id = blk * 256 + 64 * i + lane;
+                if (id >= f.n_valid) continue;
+                const uint8_t *row = f.codes_logical + (size_t)id * f.NB;
+                uint32_t ord;
+                if (f.u8) {
+                    const uint8_t *L = f.lut8 + (size_t)q * f.M * kc;
+                    uint32_t acc = 0;
+                    if (f.bits == 8) {
+                        for (int b = 0; b < f.NB; ++b) acc += L[b * 256 + row[b]];
+                    } else {
+                        for (int b = 0; b < f.NB; ++b) {
+                            acc += L[2 * b * 16 + (row[b] & 15)];
+                            if (2 * b + 1 < f.M) acc += L[(2 * b + 1) * 16 + (row[b] >> 4)];
+                        }
+                    }
+                    ord = acc + 1u;
+                } else {
+                    const float *L = f.lut + (size_t)q * f.M * kc;
+                    float acc = 0.0f;
+                    if (f.bits == 8) {
+                        for (int b = 0; b < f.NB; ++b) acc = __fadd_rn(acc, L[b * 256 + row[b]]);
+                    } else {
+                        for (int b = 0; b < f.NB; ++b) {
+                            float v = L[2 * b * 16 + (row[b] & 15)];
+                            v = __fadd_rn(v, 2 * b + 1 < f.M ? L[(2 * b + 1) * 16 + (row[b] >> 4)] : 0.0f);
+                            acc = __fadd_rn(acc, v);
+                        }
+                    }
+                    ord = ord_from_f32(acc);
+                }
+                const u64 key = make_key(ord, (int32_t)id);
+                if (key >= t) {
+                    const uint32_t at = atomicAdd(&counters[1], 1u);
+                    if ((int64_t)at < f.cand_stride) cand[at] = key;
+                }
+            }
+        }
+        __threadfence_block();
+        __syncthreads();
+        n_cand = (int)(counters[1] < (uint32_t)f.cand_stride ? counters[1] : (uint32_t)f.cand_stride);
+        __syncthreads();
+    }
     int n_fin;
     if (n_cand <= kSelList) {
         // the usual case, a few hundred candidates: rank them all by counting and keep the
@@ -1310,6 +1739,103 @@ static int launch_rescan_u(const ScanParams &p, const FinishParams &f, hipStream
     }
     if (p.NB == 32) return launch_rescan_one<U8, 32, false>(p, f, st);
     return launch_rescan_one<U8, 0, false>(p, f, st);
+}
+
+bool block_bound_supported(int NB, int bits)
+{
+    return (bits == 4 || bits == 8) && (NB == 8 || NB == 13 || NB == 25 || NB == 32);
+}
+
+template <int NBT>
+static int launch_block_bound_one(const ScanParams &p, int waves, hipStream_t st)
+{
+    // one block per wave while they all fit the chip at once (the table copy is cheap, and small workgroups
+    // spread evenly over the compute units); beyond that the waves take the blocks in turn
+    if (waves <= 0) waves = 4;
+    const int64_t cap = p.max_wgs > 0 ? p.max_wgs : std::max<int64_t>(1, 2048 / p.B);
+    int64_t gx = std::min<int64_t>((p.n_blocks + waves - 1) / waves, cap);
+    if (gx < 1) gx = 1;
+    hipLaunchKernelGGL((block_bound_kernel<NBT>), dim3((unsigned)gx, p.B), dim3(waves * 64), 0, st, p);
+    AVQ_HIP(hipGetLastError());
+    return AVQ_OK;
+}
+
+int launch_bound_tables(const ScanParams &p, bool u8, hipStream_t st)
+{
+    const dim3 grid(p.B), block(1024);
+    if (p.bits == 8) {
+        if (u8) hipLaunchKernelGGL((bound_tables_kernel<true, true>), grid, block, 0, st, p);
+        else hipLaunchKernelGGL((bound_tables_kernel<false, true>), grid, block, 0, st, p);
+    } else {
+        if (u8) hipLaunchKernelGGL((bound_tables_kernel<true, false>), grid, block, 0, st, p);
+        else hipLaunchKernelGGL((bound_tables_kernel<false, false>), grid, block, 0, st, p);
+    }
+    AVQ_HIP(hipGetLastError());
+    return AVQ_OK;
+}
+
+int launch_block_bound(const ScanParams &p, int waves, hipStream_t st)
+{
+    if (waves < 0 || waves > 16) waves = 0;
+    if (waves > 0 && waves < 4) waves = 4; // the table copy counts on 256 threads
+    switch (p.NB) {
+    case 8: return launch_block_bound_one<8>(p, waves, st);
+    case 13: return launch_block_bound_one<13>(p, waves, st);
+    case 25: return launch_block_bound_one<25>(p, waves, st);
+    case 32: return launch_block_bound_one<32>(p, waves, st);
+    default: set_error("block bounds: unsupported code size %d", p.NB); return AVQ_EINVAL;
+    }
+}
+
+int launch_select_bound_blocks(const ScanParams &p, const FinishParams &f, bool u8, hipStream_t st)
+{
+    const int kind = !u8 ? 0 : (p.bits == 4 ? 1 : 2);
+    hipLaunchKernelGGL(select_bound_blocks_kernel, dim3(p.B), dim3(1024), 0, st, p.block_bound, p.n_blocks, p.R, p.NB, kind,
+                       p.bound_meta, f.sel_blk, f.meta);
+    AVQ_HIP(hipGetLastError());
+    return AVQ_OK;
+}
+
+template <bool U8, int NBT, bool NIB>
+static int launch_rescan_listed_one(const ScanParams &p, const FinishParams &f, hipStream_t st)
+{
+    auto kern = rescan_listed_blocks_kernel<U8, NBT, NIB>;
+    static LdsLimitOnce attr_done;
+    AVQ_TRY(set_max_lds(kern, &attr_done));
+    const int waves = 4;
+    const size_t lds = NIB ? (size_t)2 * p.NB * 16 * (U8 ? 1 : 4) : (size_t)p.NB * 256 * 4;
+    // a wave per listed block while there are few (the usual case), in turns beyond
+    const int64_t gx = std::min<int64_t>((p.n_blocks + waves - 1) / waves, std::max<int64_t>(16, 256 / p.B));
+    hipLaunchKernelGGL(kern, dim3((unsigned)gx, p.B), dim3(waves * 64), lds, st, p, f);
+    AVQ_HIP(hipGetLastError());
+    return AVQ_OK;
+}
+
+template <bool U8>
+static int launch_rescan_listed_u(const ScanParams &p, const FinishParams &f, hipStream_t st)
+{
+    if (p.bits == 4) {
+        switch (p.NB) {
+        case 8: return launch_rescan_listed_one<U8, 8, true>(p, f, st);
+        case 13: return launch_rescan_listed_one<U8, 13, true>(p, f, st);
+        case 25: return launch_rescan_listed_one<U8, 25, true>(p, f, st);
+        case 32: return launch_rescan_listed_one<U8, 32, true>(p, f, st);
+        }
+    } else {
+        switch (p.NB) {
+        case 8: return launch_rescan_listed_one<U8, 8, false>(p, f, st);
+        case 13: return launch_rescan_listed_one<U8, 13, false>(p, f, st);
+        case 25: return launch_rescan_listed_one<U8, 25, false>(p, f, st);
+        case 32: return launch_rescan_listed_one<U8, 32, false>(p, f, st);
+        }
+    }
+    set_error("rescan of listed blocks: unsupported code size %d", p.NB);
+    return AVQ_EINVAL;
+}
+
+int launch_rescan_listed(const ScanParams &p, const FinishParams &f, bool u8, hipStream_t st)
+{
+    return u8 ? launch_rescan_listed_u<true>(p, f, st) : launch_rescan_listed_u<false>(p, f, st);
 }
 
 int launch_small_select(const ScanParams &p, const FinishParams &f, hipStream_t st)

@@ -751,3 +751,53 @@ def test_anisotropic_encoding_reduces_the_error_of_large_inner_products():
         exact = gs[:, 0].cpu().numpy()
         errs[name] = float(np.mean(np.abs(est - exact) / np.abs(exact)))
     assert errs["aniso"] < 0.9 * errs["l2"], errs
+
+
+@pytest.mark.parametrize("bits,M,d", [(4, 50, 100), (4, 25, 100), (4, 64, 128), (8, 32, 256), (8, 8, 64)])
+@pytest.mark.parametrize("lut_mode", [0, 1])
+def test_small_batches_through_block_bounds_with_a_heap_of_equal_scores(bits, M, d, lut_mode):
+    # A handful of queries at the code sizes whose full scan records block maxima of 8-bit sums (bounds of the
+    # scores) instead of scores. 30,000 points share the code word that is best for query 0: more points reach
+    # the bound than the candidate buffer of reorder_k = 100 holds (25,600), so that query's candidates are
+    # rebuilt from the exact block maxima; ties are ordered by id. The other queries see the heap somewhere
+    # in the middle of their ranking. Compared with the oracle and with the scan over exact block maxima.
+    rng = np.random.default_rng(1000 + 10 * M + bits + lut_mode)
+    n, kc, nq = 41_003, 1 << bits, 5
+    x = unit_rows(rng, n, d)
+    q = unit_rows(rng, nq, d)
+    cb = oracle.train_pq(x[:2000], M, kc, 2, seed=7)
+    codes = rng.integers(0, kc, (n, M), dtype=np.uint8)
+    best = np.argmax(oracle.lut_f32(q[0], cb), axis=1).astype(np.uint8)
+    codes[5_000:35_000] = best
+    case = dict(x=x, q=q, cb=cb, codes=codes, n=n, d=d, M=M, bits=bits, kc=kc)
+    idx, xd = make_index(case)
+    qd = dev(q)
+    for k, R in ((10, 100), (100, 0), (7, 7)):
+        oi, os_ = oracle.search(x, cb, codes, bits, q, k, R, lut_mode)
+        if R == 0:
+            assert list(oi[0]) == list(range(5_000, 5_000 + k))
+        for impl in (0, 2):
+            idx.set_tuning("small_batch_impl", impl)
+            idx.set_tuning("small_batch_max", 1000)
+            ids, sc = idx.search(qd, k, R, lut_mode)
+            np.testing.assert_array_equal(ids.cpu().numpy(), oi)
+            np.testing.assert_array_equal(sc.cpu().numpy(), os_)
+            ids1, sc1 = idx.search(qd[:1].contiguous(), k, R, lut_mode)
+            np.testing.assert_array_equal(ids1.cpu().numpy(), oi[:1])
+            np.testing.assert_array_equal(sc1.cpu().numpy(), os_[:1])
+        idx.set_tuning("small_batch_impl", 0)
+
+
+def test_small_batch_block_bounds_degenerate_tables():
+    # all dictionaries zero: every table entry, every 8-bit sum and every score is 0; every block is listed and
+    # every point reaches the bound. The answer is the lowest ids.
+    n, d, M = 30_001, 32, 16
+    idx = avq.Index(d, M, 4, T=0.2)
+    idx.set_codebooks(np.zeros((M, 16, d // M), np.float32))
+    rng = np.random.default_rng(3)
+    idx.set_database(None, rng.integers(0, 256, (n, M // 2), dtype=np.uint8))
+    qd = dev(unit_rows(rng, 2, d))
+    for lut_mode in (0, 1):
+        ids, sc = idx.search(qd, 20, 0, lut_mode)
+        np.testing.assert_array_equal(ids.cpu().numpy(), np.tile(np.arange(20, dtype=np.int32), (2, 1)))
+        assert np.all(sc.cpu().numpy() == 0.0)
