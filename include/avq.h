@@ -255,6 +255,16 @@ int avq_debug_leaf_select(avq_index *idx, const float *queries, int32_t nq, int3
  * be NULL) receives the number of blocks; words_out may be NULL to query it. */
 int avq_debug_stream_codes(avq_index *idx, uint32_t *words_out, int64_t *n_blocks_out, void *hip_stream);
 
+/* Measurement aid: launches one kernel of the single-query / small-batch search `reps` times back to back on
+ * the stream, after the tables it needs (so that one event pair around the call times reps launches and nothing
+ * else). part 0: the full scan of Section 4.1's sums as avq_search runs it for nq <= 35 queries (block maxima of
+ * 8-bit table sums, or of the scores where the code size has no such kernel); part 1: the code stream alone
+ * (avq_debug_stream_codes' kernel); part 2: the scan's table lookups and additions alone, in its launch shape,
+ * on made-up code words (specialised code sizes only: AVQ_EINVAL otherwise). Results go to scratch. Flat index,
+ * nq <= 64. May allocate scratch. */
+int avq_debug_scan_parts(avq_index *idx, const float *queries, int32_t nq, int32_t lut_mode, int32_t part,
+                         int32_t reps, void *hip_stream);
+
 /* Measurement aid: after an avq_search with fp32 tables that took its candidates
  * from the 8-bit-table scan (see "scan_prefilter" below): counts_out[0] = the
  * number of queries of that call that were scanned again with fp32 tables

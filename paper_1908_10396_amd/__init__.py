@@ -24,7 +24,7 @@ SYMBOLS = [
     "avq_create", "avq_destroy", "avq_train", "avq_encode", "avq_update_codebooks", "avq_search", "avq_search_noalloc", "avq_brute_force",
     "avq_set_codebooks", "avq_get_codebooks", "avq_set_leaf_centers", "avq_get_leaf_centers",
     "avq_set_database", "avq_get_codes", "avq_get_leaf_assign", "avq_size", "avq_debug_lut",
-    "avq_debug_adc_scores", "avq_debug_leaf_select", "avq_debug_stream_codes", "avq_debug_unverified_queries", "avq_eta", "avq_set_tuning",
+    "avq_debug_adc_scores", "avq_debug_leaf_select", "avq_debug_stream_codes", "avq_debug_scan_parts", "avq_debug_unverified_queries", "avq_eta", "avq_set_tuning",
     "avq_profile_enable", "avq_profile_read", "avq_last_error", "avq_version",
 ]
 
@@ -78,6 +78,7 @@ def lib():
         L.avq_debug_adc_scores.argtypes = [vp, vp, i32, i32, vp, vp]
         L.avq_debug_leaf_select.argtypes = [vp, vp, i32, i32, vp, vp, vp]
         L.avq_debug_stream_codes.argtypes = [vp, vp, C.POINTER(i64), vp]
+        L.avq_debug_scan_parts.argtypes = [vp, vp, i32, i32, i32, i32, vp]
         L.avq_debug_unverified_queries.argtypes = [vp, C.POINTER(i32)]
         L.avq_eta.argtypes = [i32, C.c_double, C.c_double, i32]
         L.avq_eta.restype = C.c_double
@@ -111,11 +112,31 @@ def _stream_ptr(stream):
     return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
 
 
-def _dev(t, dtype, what):
+def _dev(t, dtype, what, shape=None):
+    """Device pointer of a contiguous CUDA tensor. shape: expected shape, None entries free. The C ABI sees
+    pointers only, so a wrong shape would make a kernel read or write out of bounds: it is refused here."""
     torch = _torch()
-    if not isinstance(t, torch.Tensor) or not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+    if not isinstance(t, torch.Tensor) or t.dtype != dtype or not t.is_contiguous():
+        raise TypeError("%s must be a contiguous CUDA tensor of dtype %s" % (what, dtype))
+    if shape is not None:
+        if t.dim() != len(shape) or any(e is not None and int(s) != int(e) for s, e in zip(t.shape, shape)):
+            raise ValueError("%s: shape %s, expected %s" % (what, tuple(t.shape), tuple("*" if e is None else e for e in shape)))
+    if not t.is_cuda:
         raise TypeError("%s must be a contiguous CUDA tensor of dtype %s" % (what, dtype))
     return t.data_ptr()
+
+
+def _check_shape(t, shape, what):
+    """Shape check alone (all of a call's shapes are checked before any of its device checks)."""
+    if hasattr(t, "shape") and (len(t.shape) != len(shape) or
+                                any(e is not None and int(s) != int(e) for s, e in zip(t.shape, shape))):
+        raise ValueError("%s: shape %s, expected %s" % (what, tuple(t.shape), tuple("*" if e is None else e for e in shape)))
+
+
+def _check_rows(a, cols, what):
+    """A host array or tensor of `cols` columns (any number of rows)."""
+    if a.ndim != 2 or int(a.shape[1]) != int(cols):
+        raise ValueError("%s: shape %s, expected (*, %d)" % (what, tuple(a.shape), cols))
 
 
 def _any_ptr(a, np_dtype, torch_dtype, what):
@@ -176,12 +197,12 @@ class Index:
     # -- build ---------------------------------------------------------------------
     def train(self, x, stream=None):
         torch = _torch()
-        p = _dev(x, torch.float32, "x")
+        p = _dev(x, torch.float32, "x", (None, self.d))
         _check(lib().avq_train(self._h, p, x.shape[0], _stream_ptr(stream)))
 
     def encode(self, x, stream=None):
         torch = _torch()
-        p = _dev(x, torch.float32, "x")
+        p = _dev(x, torch.float32, "x", (None, self.d))
         if self.cfg.borrow_x:
             self._keep = [x]
         _check(lib().avq_encode(self._h, p, x.shape[0], _stream_ptr(stream)))
@@ -189,7 +210,7 @@ class Index:
     def update_codebooks(self, x, max_iters=1000, tol=1e-10, stream=None):
         """Returns (iterations, relative residual)."""
         torch = _torch()
-        p = _dev(x, torch.float32, "x")
+        p = _dev(x, torch.float32, "x", (None, self.d))
         it, rel = C.c_int32(0), C.c_double(0.0)
         _check(lib().avq_update_codebooks(self._h, p, x.shape[0], max_iters, tol, C.byref(it), C.byref(rel),
                                           _stream_ptr(stream)))
@@ -198,6 +219,8 @@ class Index:
     def set_codebooks(self, codebooks):
         import numpy as np
         p, keep = _any_ptr(codebooks, np.float32, _torch().float32, "codebooks")
+        if tuple(keep.shape) != (self.M, self.kc, self.ds):
+            raise ValueError("codebooks: shape %s, expected %s" % (tuple(keep.shape), (self.M, self.kc, self.ds)))
         _check(lib().avq_set_codebooks(self._h, p))
 
     def get_codebooks(self):
@@ -209,6 +232,8 @@ class Index:
     def set_leaf_centers(self, centers):
         import numpy as np
         p, keep = _any_ptr(centers, np.float32, _torch().float32, "centers")
+        if tuple(keep.shape) != (self.n_leaves, self.d):
+            raise ValueError("centers: shape %s, expected %s" % (tuple(keep.shape), (self.n_leaves, self.d)))
         _check(lib().avq_set_leaf_centers(self._h, p))
 
     def get_leaf_centers(self):
@@ -220,11 +245,18 @@ class Index:
     def set_database(self, x, packed, leaf_assign=None, stream=None):
         import numpy as np
         torch = _torch()
-        xp = None if x is None else _dev(x, torch.float32, "x")
         pp, k1 = _any_ptr(packed, np.uint8, torch.uint8, "packed")
+        _check_rows(k1, self.nb, "packed")
+        n = k1.shape[0]
+        if x is not None:
+            _check_shape(x, (n, self.d), "x")
+        if leaf_assign is not None:
+            _check_shape(leaf_assign, (n,), "leaf_assign")
+        xp = None if x is None else _dev(x, torch.float32, "x", (n, self.d))
         ap, k2 = (None, None) if leaf_assign is None else _any_ptr(leaf_assign, np.int32, torch.int32,
                                                                    "leaf_assign")
-        n = k1.shape[0]
+        if k2 is not None and tuple(k2.shape) != (n,):
+            raise ValueError("leaf_assign: shape %s, expected (%d,)" % (tuple(k2.shape), n))
         if self.cfg.borrow_x:
             self._keep = [x]
         _check(lib().avq_set_database(self._h, xp, pp, ap, n, _stream_ptr(stream)))
@@ -246,7 +278,11 @@ class Index:
                stream=None):
         """avq_search. Returns (ids int32 [nq][k], scores fp32 [nq][k]) on the GPU."""
         torch = _torch()
-        qp = _dev(queries, torch.float32, "queries")
+        _check_shape(queries, (None, self.d), "queries")
+        if out is not None:
+            _check_shape(out[0], (queries.shape[0], k), "ids")
+            _check_shape(out[1], (queries.shape[0], k), "scores")
+        qp = _dev(queries, torch.float32, "queries", (None, self.d))
         nq = queries.shape[0]
         if out is None:
             ids = torch.empty((nq, k), dtype=torch.int32, device=queries.device)
@@ -254,23 +290,27 @@ class Index:
         else:
             ids, sc = out
         _check(lib().avq_search(self._h, qp, nq, k, reorder_k, lut_mode, leaves_to_search,
-                                _dev(ids, torch.int32, "ids"), _dev(sc, torch.float32, "scores"),
+                                _dev(ids, torch.int32, "ids", (nq, k)), _dev(sc, torch.float32, "scores", (nq, k)),
                                 _stream_ptr(stream)))
         return ids, sc
 
     def search_noalloc(self, queries, k, reorder_k, lut_mode=LUT_F32, out=None, stream=None):
         """avq_search_noalloc: the caller supplies `out` = (ids, scores) so that nothing is allocated."""
         torch = _torch()
-        qp = _dev(queries, torch.float32, "queries")
+        _check_shape(queries, (None, self.d), "queries")
+        _check_shape(out[0], (queries.shape[0], k), "ids")
+        _check_shape(out[1], (queries.shape[0], k), "scores")
+        qp = _dev(queries, torch.float32, "queries", (None, self.d))
         ids, sc = out
-        _check(lib().avq_search_noalloc(self._h, qp, queries.shape[0], k, reorder_k, lut_mode,
-                                        _dev(ids, torch.int32, "ids"), _dev(sc, torch.float32, "scores"),
+        nq = queries.shape[0]
+        _check(lib().avq_search_noalloc(self._h, qp, nq, k, reorder_k, lut_mode,
+                                        _dev(ids, torch.int32, "ids", (nq, k)), _dev(sc, torch.float32, "scores", (nq, k)),
                                         _stream_ptr(stream)))
         return ids, sc
 
     def brute_force(self, queries, k, stream=None):
         torch = _torch()
-        qp = _dev(queries, torch.float32, "queries")
+        qp = _dev(queries, torch.float32, "queries", (None, self.d))
         nq = queries.shape[0]
         ids = torch.empty((nq, k), dtype=torch.int32, device=queries.device)
         sc = torch.empty((nq, k), dtype=torch.float32, device=queries.device)
@@ -280,7 +320,7 @@ class Index:
 
     def debug_lut(self, queries, lut_mode, stream=None):
         torch = _torch()
-        qp = _dev(queries, torch.float32, "queries")
+        qp = _dev(queries, torch.float32, "queries", (None, self.d))
         nq = queries.shape[0]
         if lut_mode == LUT_F32:
             lut = torch.empty((nq, self.M, self.kc), dtype=torch.float32, device=queries.device)
@@ -296,7 +336,7 @@ class Index:
 
     def debug_adc_scores(self, queries, lut_mode, stream=None):
         torch = _torch()
-        qp = _dev(queries, torch.float32, "queries")
+        qp = _dev(queries, torch.float32, "queries", (None, self.d))
         nq = queries.shape[0]
         dt = torch.float32 if lut_mode == LUT_F32 else torch.int32
         out = torch.empty((nq, self.n), dtype=dt, device=queries.device)
@@ -322,9 +362,15 @@ class Index:
         _check(lib().avq_debug_stream_codes(self._h, out.data_ptr(), None, _stream_ptr(stream)))
         return out[:nb.value]
 
+    def debug_scan_parts(self, queries, lut_mode, part, reps, stream=None):
+        """avq_debug_scan_parts: `reps` back-to-back launches of one part of the small-batch scan."""
+        torch = _torch()
+        qp = _dev(queries, torch.float32, "queries", (None, self.d))
+        _check(lib().avq_debug_scan_parts(self._h, qp, queries.shape[0], lut_mode, part, reps, _stream_ptr(stream)))
+
     def debug_leaf_select(self, queries, L, stream=None):
         torch = _torch()
-        qp = _dev(queries, torch.float32, "queries")
+        qp = _dev(queries, torch.float32, "queries", (None, self.d))
         nq = queries.shape[0]
         ids = torch.empty((nq, L), dtype=torch.int32, device=queries.device)
         ip = torch.empty((nq, L), dtype=torch.float32, device=queries.device)

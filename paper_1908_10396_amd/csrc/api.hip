@@ -1284,6 +1284,45 @@ extern "C" int avq_debug_stream_codes(avq_index *idx, uint32_t *words_out, int64
     return launch_stream_codes(idx->codes_blocked.as<uint8_t>(), idx->n_blocks, idx->NB, words_out, (hipStream_t)hip_stream);
 }
 
+extern "C" int avq_debug_scan_parts(avq_index *idx, const float *queries, int32_t nq, int32_t lut_mode, int32_t part,
+                                    int32_t reps, void *hip_stream)
+{
+    AVQ_TRY(check_index(idx));
+    AVQ_TRY(check_query_args(idx, queries, nq, lut_mode));
+    if (idx->cfg.n_leaves > 0) { set_error("avq_debug_scan_parts: flat index only"); return AVQ_ESTATE; }
+    if (part < 0 || part > 2 || reps < 1 || nq > 64) { set_error("avq_debug_scan_parts: bad argument"); return AVQ_EINVAL; }
+    hipStream_t st = (hipStream_t)hip_stream;
+    const avq_config &c = idx->cfg;
+    const bool u8 = lut_mode == AVQ_LUT_U8;
+    const bool bounds = small_uses_bounds(idx);
+    if (part == 2 && !bounds) { set_error("avq_debug_scan_parts: no lookup-only kernel for this code size"); return AVQ_EINVAL; }
+    SmallWs w;
+    AVQ_TRY(small_ws_from_index(idx, nq, 1, &w));
+    const bool fuse_tables = small_batch_can_fuse_tables(c.bits, c.M, c.d, u8);
+    if (!fuse_tables)
+        AVQ_TRY(launch_lut(queries, nq, idx->codebooks.as<float>(), c.d, c.M, idx->kc, w.lut, u8 ? w.lut8 : nullptr, w.scale,
+                           w.bias, st));
+    ScanParams p;
+    fill_scan_params(idx, nq, 1, 1, &p);
+    p.lut = w.lut; p.lut8 = w.lut8; p.scale = w.scale; p.bias = w.bias;
+    if (fuse_tables) { p.fuse_queries = queries; p.fuse_codebooks = idx->codebooks.as<float>(); p.fuse_d = c.d; }
+    p.block_max = w.block_max;
+    p.block_bound = w.block_bound;
+    p.bound_meta = w.bound_meta;
+    p.bound_tbl = w.bound_tbl;
+    p.lut_out = fuse_tables ? w.lut : nullptr;
+    p.n_tiles = nq;
+    p.n_chunks = 1;
+    p.max_wgs = idx->tune_target_wgs;
+    if (bounds) AVQ_TRY(launch_bound_tables(p, u8, st));
+    for (int r = 0; r < reps; ++r) {
+        if (part == 1) AVQ_TRY(launch_stream_codes(idx->codes_blocked.as<uint8_t>(), idx->n_blocks, idx->NB, (uint32_t *)w.block_max, st));
+        else if (bounds) AVQ_TRY(launch_block_bound(p, idx->tune_waves, st, part == 2));
+        else AVQ_TRY(launch_block_max(p, u8, idx->tune_waves > 0 ? idx->tune_waves : 4, st));
+    }
+    return AVQ_OK;
+}
+
 extern "C" int avq_debug_unverified_queries(avq_index *idx, int32_t *counts_out)
 {
     AVQ_TRY(check_index(idx));

@@ -209,7 +209,8 @@ int small_finish_stage_rows(const ScanParams &p, int d, bool u8);
 // sizes only. launch_bound_tables -> launch_block_bound -> launch_select_bound_blocks -> launch_rescan_listed -> launch_small_final.
 bool block_bound_supported(int NB, int bits);
 int launch_bound_tables(const ScanParams &p, bool u8, hipStream_t st);
-int launch_block_bound(const ScanParams &p, int waves, hipStream_t st);
+// lookups_only: the same lookups in the same launch shape on made-up code words, no code stream (measurement)
+int launch_block_bound(const ScanParams &p, int waves, hipStream_t st, bool lookups_only = false);
 int launch_select_bound_blocks(const ScanParams &p, const FinishParams &f, bool u8, hipStream_t st);
 int launch_rescan_listed(const ScanParams &p, const FinishParams &f, bool u8, hipStream_t st);
 int launch_small_select(const ScanParams &p, const FinishParams &f, hipStream_t st);

@@ -1176,6 +1176,48 @@ block_bound_kernel(const ScanParams p)
     }
 }
 
+// Measurement aid: the lookups and additions of block_bound_kernel in its launch shape, with no code stream --
+// a wave's code words are made up from its block number (a different byte in every position, lane and block)
+// instead of being loaded. Its duration is what the table lookups of a scan cost by themselves.
+template <int NBT>
+__global__ void __launch_bounds__(1024)
+lookup_only_kernel(const ScanParams p)
+{
+    __shared__ __align__(16) unsigned char tbl8[NBT * 256];
+    const int tid = threadIdx.x, nt = blockDim.x;
+    const int lane = tid & 63, wave = tid >> 6, n_waves = nt >> 6;
+    const int q = blockIdx.y;
+    const int64_t step = (int64_t)gridDim.x * n_waves;
+    const uint32_t *src = (const uint32_t *)(p.bound_tbl + (size_t)q * NBT * 256);
+    for (int it = tid; it < NBT * 64; it += nt) ((uint32_t *)tbl8)[it] = src[it];
+    __syncthreads();
+    for (int64_t blk = (int64_t)blockIdx.x * n_waves + wave; blk < p.n_blocks; blk += step) {
+        uint32_t acc[4] = {0u, 0u, 0u, 0u};
+        uint32_t w = (uint32_t)blk * 2654435761u + (uint32_t)lane * 40503u;
+        auto plane = [&](const unsigned char *t) {
+            w = w * 1664525u + 1013904223u;
+            acc[0] += t[w & 0xffu];
+            acc[1] += t[(w >> 8) & 0xffu];
+            acc[2] += t[(w >> 16) & 0xffu];
+            acc[3] += t[w >> 24];
+        };
+#pragma unroll
+        for (int b = 0; b < NBT; ++b) {
+            plane(tbl8 + (size_t)b * 256);
+            if ((b & 3) == 3) asm volatile("" : "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3]));
+        }
+        uint32_t best = acc[0];
+#pragma unroll
+        for (int i = 1; i < 4; ++i) best = acc[i] > best ? acc[i] : best;
+#pragma unroll
+        for (int m = 32; m > 0; m >>= 1) {
+            const uint32_t o = (uint32_t)__shfl_xor((int)best, m, 64);
+            best = o > best ? o : best;
+        }
+        if (lane == 0) p.block_bound[(size_t)q * p.n_blocks + blk] = best;
+    }
+}
+
 // One workgroup per query: theta = the R-th largest block maximum of the 8-bit sums, the list of the blocks
 // whose maximum reaches theta - margin, and the lower bound of the R-th best exact score as a key
 // threshold (meta[q].t1). kind 0: fp32 tables (margin and bound from bound_meta, see above), 1: 8-bit
@@ -1747,7 +1789,7 @@ bool block_bound_supported(int NB, int bits)
 }
 
 template <int NBT>
-static int launch_block_bound_one(const ScanParams &p, int waves, hipStream_t st)
+static int launch_block_bound_one(const ScanParams &p, int waves, bool lookups_only, hipStream_t st)
 {
     // one block per wave while they all fit the chip at once (the table copy is cheap, and small workgroups
     // spread evenly over the compute units); beyond that the waves take the blocks in turn
@@ -1755,7 +1797,8 @@ static int launch_block_bound_one(const ScanParams &p, int waves, hipStream_t st
     const int64_t cap = p.max_wgs > 0 ? p.max_wgs : std::max<int64_t>(1, 2048 / p.B);
     int64_t gx = std::min<int64_t>((p.n_blocks + waves - 1) / waves, cap);
     if (gx < 1) gx = 1;
-    hipLaunchKernelGGL((block_bound_kernel<NBT>), dim3((unsigned)gx, p.B), dim3(waves * 64), 0, st, p);
+    if (lookups_only) hipLaunchKernelGGL((lookup_only_kernel<NBT>), dim3((unsigned)gx, p.B), dim3(waves * 64), 0, st, p);
+    else hipLaunchKernelGGL((block_bound_kernel<NBT>), dim3((unsigned)gx, p.B), dim3(waves * 64), 0, st, p);
     AVQ_HIP(hipGetLastError());
     return AVQ_OK;
 }
@@ -1774,15 +1817,15 @@ int launch_bound_tables(const ScanParams &p, bool u8, hipStream_t st)
     return AVQ_OK;
 }
 
-int launch_block_bound(const ScanParams &p, int waves, hipStream_t st)
+int launch_block_bound(const ScanParams &p, int waves, hipStream_t st, bool lookups_only)
 {
     if (waves < 0 || waves > 16) waves = 0;
     if (waves > 0 && waves < 4) waves = 4; // the table copy counts on 256 threads
     switch (p.NB) {
-    case 8: return launch_block_bound_one<8>(p, waves, st);
-    case 13: return launch_block_bound_one<13>(p, waves, st);
-    case 25: return launch_block_bound_one<25>(p, waves, st);
-    case 32: return launch_block_bound_one<32>(p, waves, st);
+    case 8: return launch_block_bound_one<8>(p, waves, lookups_only, st);
+    case 13: return launch_block_bound_one<13>(p, waves, lookups_only, st);
+    case 25: return launch_block_bound_one<25>(p, waves, lookups_only, st);
+    case 32: return launch_block_bound_one<32>(p, waves, lookups_only, st);
     default: set_error("block bounds: unsupported code size %d", p.NB); return AVQ_EINVAL;
     }
 }

@@ -75,3 +75,59 @@ def test_product_package_does_not_import_the_oracle():
                 with open(os.path.join(dirpath, fn)) as f:
                     src = f.read()
                 assert "oracle" not in src.replace("no oracle", ""), fn
+
+
+def _shell_index(d=100, M=50, bits=4, n_leaves=0):
+    """An Index object with its shape attributes but no library handle: the binding must refuse a wrong shape
+    before it passes any pointer on (no GPU is needed to see that)."""
+    idx = avq.Index.__new__(avq.Index)
+    idx.d, idx.M, idx.bits, idx.n_leaves = d, M, bits, n_leaves
+    idx.kc, idx.ds, idx.nb = 1 << bits, d // M, (M * bits + 7) // 8
+    idx.cfg = avq.AvqConfig(d, M, bits, 0.2, 0, 1.0, 1, 1, n_leaves, 1, 1, 0)
+    idx._h = None
+    idx._keep = []
+    return idx
+
+
+def test_binding_refuses_wrong_shapes_before_any_pointer_is_passed():
+    import numpy as np
+    import torch
+    idx = _shell_index()
+    f32 = lambda *shape: torch.zeros(shape, dtype=torch.float32)
+    i32 = lambda *shape: torch.zeros(shape, dtype=torch.int32)
+    with pytest.raises(ValueError):
+        idx.search(f32(4, 99), 10, 100)                                  # queries of the wrong dimension
+    with pytest.raises(ValueError):
+        idx.search(f32(4, 100), 10, 100, out=(i32(4, 9), f32(4, 10)))    # ids too narrow
+    with pytest.raises(ValueError):
+        idx.search(f32(4, 100), 10, 100, out=(i32(4, 10), f32(3, 10)))   # scores too short
+    with pytest.raises(ValueError):
+        idx.search_noalloc(f32(2, 100), 10, 100, out=(i32(2, 10), f32(2, 11)))
+    with pytest.raises(ValueError):
+        idx.brute_force(f32(4, 101), 10)
+    with pytest.raises(ValueError):
+        idx.train(f32(1000, 64))
+    with pytest.raises(ValueError):
+        idx.encode(f32(1000))
+    with pytest.raises(ValueError):
+        idx.update_codebooks(f32(1000, 50))
+    with pytest.raises(ValueError):
+        idx.set_codebooks(np.zeros((50, 16, 3), np.float32))
+    with pytest.raises(ValueError):
+        idx.set_database(None, np.zeros((100, 24), np.uint8))            # 25 code bytes per point expected
+    with pytest.raises(ValueError):
+        idx.set_database(f32(99, 100), np.zeros((100, 25), np.uint8))    # x and codes disagree on n
+    with pytest.raises(ValueError):
+        idx.debug_lut(f32(4, 10), 0)
+    with pytest.raises(ValueError):
+        idx.debug_adc_scores(f32(4, 10), 0)
+    ivf = _shell_index(n_leaves=8)
+    with pytest.raises(ValueError):
+        ivf.set_leaf_centers(np.zeros((8, 99), np.float32))
+    with pytest.raises(ValueError):
+        ivf.set_database(None, np.zeros((100, 25), np.uint8), np.zeros(99, np.int32))
+    with pytest.raises(ValueError):
+        ivf.debug_leaf_select(f32(2, 7), 4)
+    # right shapes but host tensors: the device check still refuses them
+    with pytest.raises(TypeError):
+        idx.search(f32(4, 100), 10, 100)
