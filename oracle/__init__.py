@@ -205,16 +205,48 @@ def vq_update(x_members, h_par, h_perp):
     return out
 
 
-def pq_joint_update(x, codes, eta_per_point, codebooks):
+def pq_joint_update(x, codes, eta_per_point, codebooks, centers=None, assign=None):
+    """Appendix 7.5's joint codeword update; with centers/assign, for residual PQ on a partitioned index."""
     x, codes = _f32(x), _u8(codes)
     cb = _f32(codebooks).copy()
     n, d = x.shape
     M, kc, _ = cb.shape
-    rc = lib().orc_pq_joint_update(_p(x), C.c_int64(n), C.c_int(d), C.c_int(M), C.c_int(kc),
-                                   _p(codes), _p(_f64(eta_per_point)), _p(cb))
+    if centers is None:
+        rc = lib().orc_pq_joint_update(_p(x), C.c_int64(n), C.c_int(d), C.c_int(M), C.c_int(kc),
+                                       _p(codes), _p(_f64(eta_per_point)), _p(cb))
+    else:
+        ce, la = _f32(centers), _i32(assign)
+        rc = lib().orc_pq_joint_update_resid(_p(x), C.c_int64(n), C.c_int(d), C.c_int(M), C.c_int(kc),
+                                             _p(codes), _p(_f64(eta_per_point)), _p(ce), _p(la), _p(cb))
     if rc:
         raise ValueError("orc_pq_joint_update rc=%d" % rc)
     return cb
+
+
+def assign_aniso(x, centers, T, eta_mode=0, eta_explicit=1.0):
+    """Every row to the center of smallest anisotropic loss (Definition 4.1's assignment step)."""
+    x, centers = _f32(x), _f32(centers)
+    out = np.empty(x.shape[0], np.int32)
+    lib().orc_assign_aniso(_p(x), C.c_int64(x.shape[0]), C.c_int(x.shape[1]), _p(centers),
+                           C.c_int(centers.shape[0]), C.c_int(eta_mode), C.c_double(T),
+                           C.c_double(eta_explicit), _p(out))
+    return out
+
+
+def vq_centers_update(x, assign, centers, T, eta_mode=0, eta_explicit=1.0):
+    """Theorem 4.2 for every partition: the center that minimises the anisotropic loss of its members
+    (h_perp = 1, h_par = eta_i); a partition without members keeps its center. Returns fp32 centers."""
+    x = _f32(x)
+    out = _f32(centers).copy()
+    d = x.shape[1]
+    for l in range(out.shape[0]):
+        mem = np.nonzero(np.asarray(assign) == l)[0]
+        if mem.size == 0:
+            continue
+        xm = x[mem].astype(np.float64)
+        h_par = np.array([eta(eta_mode, d, T, float(np.sqrt((r * r).sum())), eta_explicit) for r in xm])
+        out[l] = vq_update(xm, h_par, np.ones(mem.size)).astype(np.float32)
+    return out
 
 
 # ---- query path -----------------------------------------------------------------
@@ -318,3 +350,28 @@ def search(x, codebooks, codes, bits, queries, k, reorder_k, lut_mode, centers=N
     if rc:
         raise ValueError("orc_search rc=%d" % rc)
     return ids, sc
+
+
+# ---- quality metrics of Section 5 ---------------------------------------------------------
+
+def quality_metrics(x, queries, codebooks, codes, bits, top_n=(1, 2, 5, 10, 20, 50, 100)):
+    """Section 5.2's retrieval metric and Section 5.1's estimation error for one encoding, from the definitions:
+
+    hits[N] = number of queries whose true best datapoint (arg max <q, x_i>, exact search as in Section 1)
+    is among the N datapoints with the largest quantized scores <q, x~_i> (ADC with fp32 tables, ordered by
+    score descending then id ascending); Recall 1@N = hits[N] / number of queries.
+    rel[i] = |<q_i, x~> - <q_i, x>| / |<q_i, x>| for query i and its true best datapoint x (Figure 2b).
+    """
+    x, queries = _f32(x), _f32(queries)
+    nq, n = queries.shape[0], x.shape[0]
+    gt_ids, gt_sc = brute_force(x, queries, 1)
+    kmax = min(max(top_n), n)
+    hits = {N: 0 for N in top_n if N <= kmax}
+    rel = np.empty(nq, np.float64)
+    for i in range(nq):
+        keys, _, _ = adc_keys_flat(queries[i], codebooks, codes, bits, 0)
+        best, _ = topk(keys, kmax)
+        for N in hits:
+            hits[N] += int(gt_ids[i, 0] in best[:N])
+        rel[i] = abs(float(keys[gt_ids[i, 0]]) - float(gt_sc[i, 0])) / abs(float(gt_sc[i, 0]))
+    return hits, rel

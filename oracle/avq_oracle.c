@@ -513,6 +513,87 @@ int orc_pq_joint_update(const float *x, int64_t n, int d, int M, int kc,
     return rc ? ORC_EINVAL : ORC_OK;
 }
 
+/* Appendix 7.5 for a partitioned index: x~_i = center(leaf(i)) + B_i c, the
+ * loss still taken against the original x_i (its direction and norm define
+ * A_i). Minimising sum_i (x_i - g_i - B_i c)^T A_i (x_i - g_i - B_i c) over c,
+ * g_i the point's leaf center, gives the same matrix as the flat case and the
+ * right-hand side sum_i B_i^T A_i (x_i - g_i) with
+ * A_i v = v + w_i x_i (x_i^T v), w_i = (eta_i - 1)/||x_i||^2. centers == NULL:
+ * g_i = 0, the flat case (A_i x_i = eta_i x_i). */
+int orc_pq_joint_update_resid(const float *x, int64_t n, int d, int M, int kc,
+                              const uint8_t *codes, const double *eta, const float *centers,
+                              const int32_t *assign, float *codebooks)
+{
+    int ds = d / M;
+    int D = M * kc * ds;
+    double *A = (double *)calloc((size_t)D * D, sizeof(double));
+    double *b = (double *)calloc((size_t)D, sizeof(double));
+    double *r = (double *)malloc(sizeof(double) * (size_t)d);
+    int *col = (int *)malloc(sizeof(int) * (size_t)d);
+    char *used = (char *)calloc((size_t)M * kc, 1);
+    if (!A || !b || !r || !col || !used) { free(A); free(b); free(r); free(col); free(used); return ORC_ENOMEM; }
+    for (int64_t i = 0; i < n; ++i) {
+        const float *xi = x + (size_t)i * d;
+        double nx2 = 0.0, xr = 0.0;
+        for (int l = 0; l < d; ++l) {
+            double g = centers ? (double)centers[(size_t)assign[i] * d + l] : 0.0;
+            r[l] = (double)xi[l] - g;
+            nx2 += (double)xi[l] * (double)xi[l];
+            xr += (double)xi[l] * r[l];
+        }
+        double w = nx2 > 0.0 ? (eta[i] - 1.0) / nx2 : 0.0;
+        for (int m = 0; m < M; ++m) {
+            used[m * kc + codes[(size_t)i * M + m]] = 1;
+            for (int l = 0; l < ds; ++l)
+                col[m * ds + l] = (m * kc + codes[(size_t)i * M + m]) * ds + l;
+        }
+        for (int a = 0; a < d; ++a) {
+            A[(size_t)col[a] * D + col[a]] += 1.0;
+            for (int c = 0; c < d; ++c)
+                A[(size_t)col[a] * D + col[c]] += w * (double)xi[a] * (double)xi[c];
+            b[col[a]] += r[a] + w * xr * (double)xi[a];
+        }
+    }
+    for (int mj = 0; mj < M * kc; ++mj)
+        if (!used[mj])
+            for (int l = 0; l < ds; ++l) {
+                int rr = mj * ds + l;
+                A[(size_t)rr * D + rr] = 1.0;
+                b[rr] = (double)codebooks[rr];
+            }
+    int rc = spd_solve(A, b, D);
+    if (!rc)
+        for (int rr = 0; rr < D; ++rr) codebooks[rr] = (float)b[rr];
+    free(A); free(b); free(r); free(col); free(used);
+    return rc ? ORC_EINVAL : ORC_OK;
+}
+
+/* Definition 4.1's partition-assignment step for a vector quantizer whose
+ * codewords are the leaf centers: every row goes to the center with the
+ * smallest anisotropic loss eta*||r_par||^2 + ||r_perp||^2, r = x - center
+ * (Section 3.2), lowest index on equal loss; eta per point from its own norm. */
+void orc_assign_aniso(const float *x, int64_t n, int d, const float *centers, int k,
+                      int eta_mode, double T, double eta_explicit, int32_t *assign)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) {
+        double *xd = (double *)malloc(sizeof(double) * 4 * (size_t)d);
+        double *cd = xd + d, *ws = cd + d;
+        const float *xi = x + (size_t)i * d;
+        for (int l = 0; l < d; ++l) xd[l] = (double)xi[l];
+        double eta = orc_eta(eta_mode, d, T, norm_d(xi, d), eta_explicit);
+        int best = 0;
+        double best_loss = 0.0;
+        for (int j = 0; j < k; ++j) {
+            for (int l = 0; l < d; ++l) cd[l] = (double)centers[(size_t)j * d + l];
+            double v = aniso_loss_ws(xd, cd, d, eta, ws);
+            if (j == 0 || v < best_loss) { best_loss = v; best = j; }
+        }
+        assign[i] = best;
+        free(xd);
+    }
+}
+
 /* ------------------------------------------------------------------------ */
 /* query path: tables, ADC, top-k, re-ranking (Section 4.1, Section 2.2.2)   */
 /* ------------------------------------------------------------------------ */

@@ -261,3 +261,74 @@ def test_pq_joint_update_properties():
         dn[idx] -= 1e-3
         assert abs(total(up) - total(dn)) / 2e-3 < 2e-3 * max(1.0, base)
         assert total(up) >= base - 1e-7 and total(dn) >= base - 1e-7
+
+
+def _total_loss(x, xt, etas):
+    return sum(oracle.aniso_loss(x[i], xt[i], etas[i]) for i in range(x.shape[0]))
+
+
+def test_joint_update_with_leaf_centers_has_zero_gradient_and_reduces_to_the_flat_case():
+    # Appendix 7.5 on a partitioned index: x~ = center + PQ(residual), loss against the original x.
+    rng = np.random.default_rng(21)
+    n, d, M, kc, L = 400, 6, 3, 4, 5
+    x = rng.standard_normal((n, d)).astype(np.float32)
+    x *= rng.uniform(0.5, 1.5, (n, 1)).astype(np.float32)
+    centers = rng.standard_normal((L, d)).astype(np.float32) * 0.5
+    assign = rng.integers(0, L, n).astype(np.int32)
+    codes = rng.integers(0, kc, (n, M)).astype(np.uint8)
+    cb0 = rng.standard_normal((M, kc, d // M)).astype(np.float32)
+    etas = np.array([oracle.eta(0, d, 0.4, float(np.linalg.norm(r))) for r in x])
+    cb = oracle.pq_joint_update(x, codes, etas, cb0, centers, assign)
+
+    def loss(cbv):
+        xt = oracle.reconstruct(codes, cbv.astype(np.float32), centers, assign)
+        return _total_loss(x.astype(np.float64), xt, etas)
+
+    base = loss(cb)
+    assert base < loss(cb0)
+    # a stationary point of a convex quadratic: central differences vanish, any step increases the loss
+    h = 1e-3
+    for _ in range(12):
+        e = np.zeros_like(cb)
+        idx = tuple(rng.integers(0, s) for s in cb.shape)
+        e[idx] = h
+        up, dn = loss(cb + e), loss(cb - e)
+        assert abs(up - dn) / (2 * h) < 2e-3 * max(1.0, base), (idx, up, dn)
+        assert up >= base - 1e-6 and dn >= base - 1e-6
+    # zero centers: the flat update; eta = 1: the mean of the residuals of every codeword's members
+    flat = oracle.pq_joint_update(x, codes, etas, cb0)
+    np.testing.assert_allclose(oracle.pq_joint_update(x, codes, etas, cb0, np.zeros((L, d), np.float32), assign), flat,
+                               rtol=0, atol=1e-6)
+    ones = np.ones(n)
+    cb1 = oracle.pq_joint_update(x, codes, ones, cb0, centers, assign)
+    res = x - centers[assign]
+    for m in range(M):
+        for j in range(kc):
+            mem = codes[:, m] == j
+            np.testing.assert_allclose(cb1[m, j], res[mem][:, m * 2:(m + 1) * 2].mean(axis=0), rtol=0, atol=2e-6)
+
+
+def test_anisotropic_leaf_assignment_and_center_update():
+    rng = np.random.default_rng(22)
+    n, d, L = 300, 8, 7
+    x = rng.standard_normal((n, d)).astype(np.float32)
+    x /= np.linalg.norm(x, axis=1, keepdims=True)
+    centers = rng.standard_normal((L, d)).astype(np.float32) * 0.6
+    # eta = 1 (T = 0): the nearest center
+    np.testing.assert_array_equal(oracle.assign_aniso(x, centers, 0.0), oracle.assign_nearest(x, centers))
+    # T = 0.5: the arg min of the loss of Section 3.2 evaluated from its definition, by brute force
+    a = oracle.assign_aniso(x, centers, 0.5)
+    e = oracle.eta(0, d, 0.5, 1.0)
+    for i in range(0, n, 7):
+        losses = [oracle.aniso_loss(x[i], centers[j], oracle.eta(0, d, 0.5, float(np.linalg.norm(x[i])))) for j in range(L)]
+        assert a[i] == int(np.argmin(losses))
+    assert np.mean(a != oracle.assign_nearest(x, centers)) > 0.02 and e > 1.0   # the loss matters
+    # Theorem 4.2 per partition: no other center of a partition has a smaller loss; the total loss falls
+    new = oracle.vq_centers_update(x, a, centers, 0.5)
+    etas = np.array([oracle.eta(0, d, 0.5, float(np.linalg.norm(r))) for r in x])
+    before = _total_loss(x.astype(np.float64), centers[a].astype(np.float64), etas)
+    after = _total_loss(x.astype(np.float64), new[a].astype(np.float64), etas)
+    assert after < before
+    for _ in range(10):
+        pert = new + (rng.standard_normal(new.shape) * 1e-2).astype(np.float32)
+        assert _total_loss(x.astype(np.float64), pert[a].astype(np.float64), etas) >= after - 1e-9

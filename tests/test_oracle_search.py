@@ -244,3 +244,32 @@ def test_search_on_tiny_config_shapes():
     bids, _ = oracle.brute_force(x, q, 10)
     recall = np.mean([len(set(ids[i]) & set(bids[i])) / 10 for i in range(5)])
     assert recall > 0.5     # sanity only: quantized search finds most true neighbours
+
+
+def test_quality_metrics_on_a_hand_made_example_and_in_the_exact_limit():
+    # Recall 1@N (Section 5.2) and the relative error of the top-1 estimate (Section 5.1), pinned by a case
+    # small enough to do by hand: d = 2, one subspace, 4-bit codes; the codewords are the points of a grid.
+    cb = np.zeros((1, 16, 2), np.float32)
+    cb[0, :4] = [[1.0, 0.0], [0.0, 1.0], [0.5, 0.5], [-1.0, 0.0]]
+    x = np.array([[0.9, 0.1], [0.2, 0.8], [0.6, 0.5], [-0.7, 0.1]], np.float32)
+    codes = np.array([[0], [1], [2], [3]], np.uint8)          # x~ = (1,0), (0,1), (.5,.5), (-1,0)
+    q = np.array([[1.0, 0.0], [0.0, 1.0], [0.6, 0.6]], np.float32)
+    # exact scores:   q0: .9 .2 .6 -.7 -> best 0;  q1: .1 .8 .5 .1 -> best 1;  q2: .6 .6 .66 -.36 -> best 2
+    # quantized:      q0: 1 0 .5 -1 -> rank of 0 is 1;  q1: 0 1 .5 0 -> rank of 1 is 1;
+    #                 q2: .6 .6 .6 -.6 -> three equal scores, ids ascending: 0, 1, 2 -> rank of 2 is 3
+    hits, rel = oracle.quality_metrics(x, q, cb, codes, 4, top_n=(1, 2, 3, 4))
+    assert hits == {1: 2, 2: 2, 3: 3, 4: 3}
+    np.testing.assert_allclose(rel, [0.1 / 0.9, 0.2 / 0.8, 0.06 / 0.66], rtol=1e-6)
+    # a quantizer that reproduces every point exactly ranks exactly and estimates without error
+    rng = np.random.default_rng(0)
+    pts = rng.standard_normal((16, 2)).astype(np.float32)
+    cb2 = pts.reshape(1, 16, 2).copy()
+    hits, rel = oracle.quality_metrics(pts, rng.standard_normal((20, 2)).astype(np.float32), cb2,
+                                       np.arange(16, dtype=np.uint8).reshape(16, 1), 4, top_n=(1, 5))
+    assert hits == {1: 20, 5: 20} and np.all(rel < 1e-6)
+    # N = n: every datapoint is among the n best, whatever the quantizer
+    xs = rng.standard_normal((300, 8)).astype(np.float32)
+    cbs = oracle.train_pq(xs, 4, 16, 3, seed=1)
+    cds = oracle.encode(xs, cbs, T=0.2, passes=2)
+    hits, _ = oracle.quality_metrics(xs, rng.standard_normal((12, 8)).astype(np.float32), cbs, cds, 4, top_n=(1, 300))
+    assert hits[300] == 12 and hits[1] <= 12
