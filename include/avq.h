@@ -74,6 +74,14 @@ typedef struct {
                                    must stay valid and unchanged for the life
                                    of the index                                  */
     uint64_t seed;              /* seeds the draw of the initial codewords       */
+    int32_t leaf_aniso_iters;   /* partitioned index: 0 = the leaves are an l2 vector
+                                   quantizer (Lloyd, nearest-center assignment);
+                                   > 0: an anisotropic one (Section 4, Definition 4.1):
+                                   after Lloyd, this many rounds of (assignment of the
+                                   training rows to the center of smallest anisotropic
+                                   loss, Theorem 4.2's center update), and avq_train /
+                                   avq_encode assign every point to the leaf of smallest
+                                   anisotropic loss                                  */
 } avq_config;
 
 /* Validates cfg and allocates an empty index on the current device.
@@ -122,10 +130,26 @@ int avq_encode(avq_index *idx, const float *x, int64_t n, void *hip_stream);
  * fp32); the stored codes stay as they are, so alternate with avq_encode to
  * iterate Section 4.2. iters_out / rel_residual_out (host, may be NULL):
  * iterations done and ||residual||/||rhs|| at exit.
- * Flat index only (AVQ_EINVAL with leaves). AVQ_ESTATE: no codes yet.
+ * On a partitioned index x~_i = center(leaf(i)) + codewords, the loss still
+ * taken against x_i: same matrix, right-hand side sum_i B_i^T A_i (x_i - center),
+ * A_i v = v + w_i x_i (x_i^T v). AVQ_ESTATE: no codes yet.
  * Allocates scratch with hipMalloc; synchronises the stream. */
 int avq_update_codebooks(avq_index *idx, const float *x, int64_t n, int32_t max_iters, double tol,
                          int32_t *iters_out, double *rel_residual_out, void *hip_stream);
+
+/* Theorem 4.2 for the leaf centers of a partitioned index, with the leaf
+ * assignment of the last avq_encode / avq_set_database held fixed: every center
+ * becomes the minimiser of the anisotropic loss of its members,
+ *   c* = (sum_i A_i)^-1 sum_i eta_i x_i,  A_i = I + w_i x_i x_i^T,
+ * (the joint update of Appendix 7.5 with one dictionary whose codewords are the
+ * centers and whose codes are the assignments; same conjugate-gradient solve,
+ * fp64). A leaf without members keeps its center. x: device [n][d], n must equal
+ * avq_size. The stored residual codes refer to the old centers: follow with
+ * avq_encode (and avq_train's dictionaries may be refreshed with
+ * avq_update_codebooks afterwards) to iterate Section 4. AVQ_EINVAL on a flat
+ * index; AVQ_ESTATE without a database. Allocates scratch; synchronises. */
+int avq_update_leaf_centers(avq_index *idx, const float *x, int64_t n, int32_t max_iters, double tol,
+                            int32_t *iters_out, double *rel_residual_out, void *hip_stream);
 
 /* The query path (Sections 2.2.2 and 4.1 plus exact re-scoring).
  * queries: device [nq][d]; ids_out: device int32 [nq][k]; scores_out: device

@@ -21,7 +21,7 @@ STAGES = ("leaf_select", "lut", "scan", "merge", "finalize", "rescan", "sample")
 
 # every symbol include/avq.h declares
 SYMBOLS = [
-    "avq_create", "avq_destroy", "avq_train", "avq_encode", "avq_update_codebooks", "avq_search", "avq_search_noalloc", "avq_brute_force",
+    "avq_create", "avq_destroy", "avq_train", "avq_encode", "avq_update_codebooks", "avq_update_leaf_centers", "avq_search", "avq_search_noalloc", "avq_brute_force",
     "avq_set_codebooks", "avq_get_codebooks", "avq_set_leaf_centers", "avq_get_leaf_centers",
     "avq_set_database", "avq_get_codes", "avq_get_leaf_assign", "avq_size", "avq_debug_lut",
     "avq_debug_adc_scores", "avq_debug_leaf_select", "avq_debug_stream_codes", "avq_debug_scan_parts", "avq_debug_unverified_queries", "avq_eta", "avq_set_tuning",
@@ -34,7 +34,7 @@ class AvqConfig(C.Structure):
         ("d", C.c_int32), ("M", C.c_int32), ("bits", C.c_int32), ("T", C.c_float),
         ("eta_mode", C.c_int32), ("eta_explicit", C.c_float), ("kmeans_iters", C.c_int32),
         ("encode_passes", C.c_int32), ("n_leaves", C.c_int32), ("leaf_kmeans_iters", C.c_int32),
-        ("borrow_x", C.c_int32), ("seed", C.c_uint64),
+        ("borrow_x", C.c_int32), ("seed", C.c_uint64), ("leaf_aniso_iters", C.c_int32),
     ]
 
 
@@ -62,6 +62,7 @@ def lib():
         L.avq_train.argtypes = [vp, vp, i64, vp]
         L.avq_encode.argtypes = [vp, vp, i64, vp]
         L.avq_update_codebooks.argtypes = [vp, vp, i64, i32, C.c_double, C.POINTER(i32), C.POINTER(C.c_double), vp]
+        L.avq_update_leaf_centers.argtypes = [vp, vp, i64, i32, C.c_double, C.POINTER(i32), C.POINTER(C.c_double), vp]
         L.avq_search.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, vp, vp]
         L.avq_search_noalloc.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp]
         L.avq_brute_force.argtypes = [vp, vp, i32, i32, vp, vp, vp]
@@ -155,9 +156,9 @@ class Index:
     """Owns one avq_index. Tensors passed in must live on the index's GPU."""
 
     def __init__(self, d, M, bits, T=0.2, eta_mode=ETA_LIMIT, eta_explicit=1.0, kmeans_iters=20,
-                 encode_passes=10, n_leaves=0, leaf_kmeans_iters=10, borrow_x=True, seed=0):
+                 encode_passes=10, n_leaves=0, leaf_kmeans_iters=10, borrow_x=True, seed=0, leaf_aniso_iters=0):
         self.cfg = AvqConfig(d, M, bits, T, eta_mode, eta_explicit, kmeans_iters, encode_passes,
-                             n_leaves, leaf_kmeans_iters, 1 if borrow_x else 0, seed)
+                             n_leaves, leaf_kmeans_iters, 1 if borrow_x else 0, seed, leaf_aniso_iters)
         self.d, self.M, self.bits, self.n_leaves = d, M, bits, n_leaves
         self.kc = 1 << bits
         self.ds = d // M if M > 0 and d % M == 0 else 0
@@ -214,6 +215,15 @@ class Index:
         it, rel = C.c_int32(0), C.c_double(0.0)
         _check(lib().avq_update_codebooks(self._h, p, x.shape[0], max_iters, tol, C.byref(it), C.byref(rel),
                                           _stream_ptr(stream)))
+        return it.value, rel.value
+
+    def update_leaf_centers(self, x, max_iters=1000, tol=1e-10, stream=None):
+        """avq_update_leaf_centers. Returns (iterations, relative residual)."""
+        torch = _torch()
+        p = _dev(x, torch.float32, "x", (None, self.d))
+        it, rel = C.c_int32(0), C.c_double(0.0)
+        _check(lib().avq_update_leaf_centers(self._h, p, x.shape[0], max_iters, tol, C.byref(it), C.byref(rel),
+                                             _stream_ptr(stream)))
         return it.value, rel.value
 
     def set_codebooks(self, codebooks):

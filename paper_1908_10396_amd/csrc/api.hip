@@ -132,7 +132,8 @@ extern "C" int avq_create(const avq_config *cfg, avq_index **out)
         set_error("avq_create: eta_explicit must be >= 1");
         return AVQ_EINVAL;
     }
-    if (cfg->kmeans_iters < 0 || cfg->encode_passes < 0 || cfg->n_leaves < 0 || cfg->leaf_kmeans_iters < 0) {
+    if (cfg->kmeans_iters < 0 || cfg->encode_passes < 0 || cfg->n_leaves < 0 || cfg->leaf_kmeans_iters < 0 ||
+        cfg->leaf_aniso_iters < 0) {
         set_error("avq_create: negative count");
         return AVQ_EINVAL;
     }
@@ -265,6 +266,36 @@ extern "C" int avq_get_leaf_centers(avq_index *idx, float *out)
     return AVQ_OK;
 }
 
+// Assignment of rows to leaves: nearest center, or smallest anisotropic loss when the index learns its
+// leaves as an anisotropic vector quantizer (cfg.leaf_aniso_iters > 0).
+static int assign_to_leaves(avq_index *idx, const float *x, int64_t n, int32_t *assign, hipStream_t st)
+{
+    const avq_config &c = idx->cfg;
+    if (c.leaf_aniso_iters > 0)
+        return launch_assign_aniso(x, n, c.d, idx->centers.as<float>(), c.n_leaves, c.eta_mode, (double)c.T,
+                                   (double)c.eta_explicit, assign, st);
+    return launch_assign_nearest(x, n, c.d, idx->centers.as<float>(), c.n_leaves, assign, st);
+}
+
+// Theorem 4.2 for every leaf at once: the leaf centers are the codewords of a one-dictionary quantizer whose
+// codes are the leaf assignments, so the joint update of Appendix 7.5 with M = 1 is the theorem's closed form.
+static int update_leaf_centers(avq_index *idx, const float *x, int64_t n, const int32_t *assign, int max_iters, double tol,
+                               int *iters, double *rel, hipStream_t st)
+{
+    const avq_config &c = idx->cfg;
+    const int D = c.n_leaves * c.d;
+    DevBuf scratch;
+    int rc = scratch.reserve(pq_update_scratch_bytes(n, D, c.n_leaves));
+    if (rc == AVQ_OK)
+        rc = pq_joint_update_device(x, n, c.d, 1, c.n_leaves, 32, (const uint8_t *)assign, nullptr, nullptr, c.eta_mode,
+                                    (double)c.T, (double)c.eta_explicit, idx->centers.as<float>(), scratch.p, max_iters, tol,
+                                    iters, rel, st);
+    if (rc == AVQ_OK && hipStreamSynchronize(st) != hipSuccess) { set_error("leaf center update: stream error"); rc = AVQ_EHIP; }
+    scratch.release();
+    if (rc == AVQ_OK) rc = refresh_centers_t(idx, st);
+    return rc;
+}
+
 extern "C" int avq_train(avq_index *idx, const float *x, int64_t n_train, void *hip_stream)
 {
     AVQ_TRY(check_index(idx));
@@ -283,8 +314,14 @@ extern "C" int avq_train(avq_index *idx, const float *x, int64_t n_train, void *
         AVQ_TRY(refresh_centers_t(idx, st));
         idx->have_centers = true;
         AVQ_TRY(idx->tmp.reserve(sizeof(int32_t) * (size_t)n_train));
-        AVQ_TRY(launch_assign_nearest(x, n_train, c.d, idx->centers.as<float>(), c.n_leaves,
-                                      idx->tmp.as<int32_t>(), st));
+        // Section 4 with the leaf centers as codewords: alternate the assignment under the anisotropic loss
+        // (Definition 4.1) and Theorem 4.2's update, starting from the l2 centers
+        for (int it = 0; it < c.leaf_aniso_iters; ++it) {
+            AVQ_TRY(launch_assign_aniso(x, n_leaf_train, c.d, idx->centers.as<float>(), c.n_leaves, c.eta_mode, (double)c.T,
+                                        (double)c.eta_explicit, idx->tmp.as<int32_t>(), st));
+            AVQ_TRY(update_leaf_centers(idx, x, n_leaf_train, idx->tmp.as<int32_t>(), 500, 1e-10, nullptr, nullptr, st));
+        }
+        AVQ_TRY(assign_to_leaves(idx, x, n_train, idx->tmp.as<int32_t>(), st));
         assign = idx->tmp.as<int32_t>();
     }
     for (int m = 0; m < c.M; ++m)
@@ -409,8 +446,7 @@ extern "C" int avq_encode(avq_index *idx, const float *x, int64_t n, void *hip_s
     const int32_t *assign = nullptr;
     if (c.n_leaves > 0) {
         AVQ_TRY(idx->assign.reserve(sizeof(int32_t) * (size_t)n));
-        AVQ_TRY(launch_assign_nearest(x, n, c.d, idx->centers.as<float>(), c.n_leaves,
-                                      idx->assign.as<int32_t>(), st));
+        AVQ_TRY(assign_to_leaves(idx, x, n, idx->assign.as<int32_t>(), st));
         assign = idx->assign.as<int32_t>();
     }
     AVQ_TRY(launch_encode(x, n, c.d, c.M, idx->kc, c.bits, idx->codebooks.as<float>(),
@@ -426,7 +462,6 @@ extern "C" int avq_update_codebooks(avq_index *idx, const float *x, int64_t n, i
     hipStream_t st = (hipStream_t)hip_stream;
     const avq_config &c = idx->cfg;
     if (!x) { set_error("avq_update_codebooks: x is NULL"); return AVQ_EINVAL; }
-    if (c.n_leaves > 0) { set_error("avq_update_codebooks: flat index only"); return AVQ_EINVAL; }
     if (idx->n <= 0) { set_error("avq_update_codebooks: no codes yet (avq_encode first)"); return AVQ_ESTATE; }
     if (n != idx->n) {
         set_error("avq_update_codebooks: n = %lld but the codes are of %lld points", (long long)n, (long long)idx->n);
@@ -439,12 +474,36 @@ extern "C" int avq_update_codebooks(avq_index *idx, const float *x, int64_t n, i
     double rel = 0.0;
     int rc = scratch.reserve(pq_update_scratch_bytes(n, D, c.M * idx->kc));
     if (rc == AVQ_OK)
-        rc = pq_joint_update_device(x, n, c.d, c.M, idx->kc, c.bits, idx->codes_logical.as<uint8_t>(), c.eta_mode,
+        rc = pq_joint_update_device(x, n, c.d, c.M, idx->kc, c.bits, idx->codes_logical.as<uint8_t>(),
+                                    c.n_leaves > 0 ? idx->centers.as<float>() : nullptr,
+                                    c.n_leaves > 0 ? idx->assign.as<int32_t>() : nullptr, c.eta_mode,
                                     (double)c.T, (double)c.eta_explicit, idx->codebooks.as<float>(), scratch.p,
                                     max_iters, tol, &iters, &rel, st);
     if (rc == AVQ_OK && hipStreamSynchronize(st) != hipSuccess) { set_error("avq_update_codebooks: stream error"); rc = AVQ_EHIP; }
     scratch.release();
     if (rc != AVQ_OK) return rc;
+    if (iters_out) *iters_out = iters;
+    if (rel_residual_out) *rel_residual_out = rel;
+    return AVQ_OK;
+}
+
+extern "C" int avq_update_leaf_centers(avq_index *idx, const float *x, int64_t n, int32_t max_iters, double tol,
+                                       int32_t *iters_out, double *rel_residual_out, void *hip_stream)
+{
+    AVQ_TRY(check_index(idx));
+    hipStream_t st = (hipStream_t)hip_stream;
+    const avq_config &c = idx->cfg;
+    if (!x) { set_error("avq_update_leaf_centers: x is NULL"); return AVQ_EINVAL; }
+    if (c.n_leaves <= 0) { set_error("avq_update_leaf_centers: flat index"); return AVQ_EINVAL; }
+    if (idx->n <= 0) { set_error("avq_update_leaf_centers: no database yet (avq_encode first)"); return AVQ_ESTATE; }
+    if (n != idx->n) {
+        set_error("avq_update_leaf_centers: n = %lld but the stored assignment is of %lld points", (long long)n, (long long)idx->n);
+        return AVQ_EINVAL;
+    }
+    if (max_iters < 1 || !(tol >= 0.0)) { set_error("avq_update_leaf_centers: max_iters < 1 or tol < 0"); return AVQ_EINVAL; }
+    int iters = 0;
+    double rel = 0.0;
+    AVQ_TRY(update_leaf_centers(idx, x, n, idx->assign.as<int32_t>(), max_iters, tol, &iters, &rel, st));
     if (iters_out) *iters_out = iters;
     if (rel_residual_out) *rel_residual_out = rel;
     return AVQ_OK;

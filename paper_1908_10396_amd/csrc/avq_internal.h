@@ -326,11 +326,17 @@ int kmeans_device(const float *x, int64_t n, int ld, int col0, int dim, int k, i
                   const int32_t *resid_assign, float *centers, hipStream_t st);
 int launch_assign_nearest(const float *x, int64_t n, int d, const float *centers, int k,
                           int32_t *assign, hipStream_t st);
+// every row to the center of smallest anisotropic loss (fp64), lowest index on equal loss
+int launch_assign_aniso(const float *x, int64_t n, int d, const float *centers, int k, int eta_mode, double T,
+                        double eta_explicit, int32_t *assign, hipStream_t st);
 // Joint update of all dictionaries with the codes fixed (anisotropic loss; conjugate gradients on
 // the normal equations of the paper's Appendix 7.5, matrix-free, fp64). codes: logical [n][NB].
 // scratch: pq_update_scratch_bytes(n, M*kc*ds, M*kc) bytes of device memory. Synchronises the stream.
 size_t pq_update_scratch_bytes(int64_t n, int D, int slots);
+// centers / assign (both NULL or both set): residual quantization, x~ = centers[assign[i]] + codewords, the loss
+// against x itself. bits 32: codes are int32, one per subspace (Theorem 4.2 for leaf centers: M = 1, codes = assign).
 int pq_joint_update_device(const float *x, int64_t n, int d, int M, int kc, int bits, const uint8_t *codes,
+                           const float *centers, const int32_t *assign,
                            int eta_mode, double T, double eta_explicit, float *codebooks, void *scratch,
                            int max_iters, double tol, int *iters_out, double *rel_residual_out, hipStream_t st);
 int launch_encode(const float *x, int64_t n, int d, int M, int kc, int bits,

@@ -235,6 +235,71 @@ int launch_assign_nearest(const float *x, int64_t n, int d, const float *centers
     return AVQ_OK;
 }
 
+// Definition 4.1's assignment step with the leaf centers as codewords: every point to the center of smallest
+// anisotropic loss. With r = x - c: ||r||^2 = ||x||^2 - 2<c,x> + ||c||^2 and <r,x> = ||x||^2 - <c,x>, so the
+// loss ||r||^2 + (eta - 1) <r,x>^2 / ||x||^2 (Section 3.2) needs <c,x> and ||c||^2 only; fp64. A workgroup
+// holds 64 points in LDS; thread (point p, group g of 4) takes the centers j = g, g + 4, ...; lowest index
+// on equal loss.
+__global__ void __launch_bounds__(256)
+assign_aniso_kernel(const float *__restrict__ x, int64_t n, int d, const float *__restrict__ centers, int k,
+                    int eta_mode, double T, double eta_explicit, int32_t *__restrict__ assign)
+{
+    extern __shared__ double xs[]; // [64][d + 1], then best loss [4][64] and best index [4][64]
+    const int ld = d + 1;
+    double *best_loss = xs + (size_t)64 * ld;
+    int *best_idx = (int *)(best_loss + 256);
+    const int tid = threadIdx.x, p = tid & 63, g = tid >> 6;
+    const int64_t i0 = (int64_t)blockIdx.x * 64;
+    for (int e = tid; e < 64 * d; e += 256) {
+        const int pp = e / d, l = e - pp * d;
+        xs[(size_t)pp * ld + l] = i0 + pp < n ? (double)x[(size_t)(i0 + pp) * d + l] : 0.0;
+    }
+    __syncthreads();
+    const double *xp = xs + (size_t)p * ld;
+    double nx2 = 0.0;
+    for (int l = 0; l < d; ++l) nx2 += xp[l] * xp[l];
+    const double eta = eta_of_norm(d, T, sqrt(nx2), eta_mode, eta_explicit);
+    const double w = nx2 > 0.0 ? (eta - 1.0) / nx2 : 0.0;
+    double bl = 0.0;
+    int bi = -1;
+    for (int j = g; j < k; j += 4) {
+        const float *c = centers + (size_t)j * d;
+        double cx = 0.0, cc = 0.0;
+        for (int l = 0; l < d; ++l) {
+            const double cv = (double)c[l];
+            cx += cv * xp[l];
+            cc += cv * cv;
+        }
+        const double rx = nx2 - cx;
+        const double loss = (nx2 - 2.0 * cx + cc) + w * rx * rx;
+        if (bi < 0 || loss < bl) { bl = loss; bi = j; }
+    }
+    best_loss[g * 64 + p] = bl;
+    best_idx[g * 64 + p] = bi;
+    __syncthreads();
+    if (g == 0 && i0 + p < n) {
+        for (int gg = 1; gg < 4; ++gg) {
+            const double l2 = best_loss[gg * 64 + p];
+            const int j2 = best_idx[gg * 64 + p];
+            if (j2 >= 0 && (bi < 0 || l2 < bl || (l2 == bl && j2 < bi))) { bl = l2; bi = j2; }
+        }
+        assign[i0 + p] = bi;
+    }
+}
+
+int launch_assign_aniso(const float *x, int64_t n, int d, const float *centers, int k, int eta_mode, double T,
+                        double eta_explicit, int32_t *assign, hipStream_t st)
+{
+    const size_t lds = sizeof(double) * ((size_t)64 * (d + 1) + 256) + sizeof(int) * 256;
+    if (lds > kMaxDynLds) { set_error("assign: dimension %d too large", d); return AVQ_EINVAL; }
+    static LdsLimitOnce attr_done;
+    AVQ_TRY(set_lds_limit((const void *)assign_aniso_kernel, kMaxDynLds, &attr_done));
+    hipLaunchKernelGGL(assign_aniso_kernel, dim3((unsigned)((n + 63) / 64)), dim3(256), lds, st, x, n, d, centers, k,
+                       eta_mode, T, eta_explicit, assign);
+    AVQ_HIP(hipGetLastError());
+    return AVQ_OK;
+}
+
 // ---- encoding under the anisotropic loss ------------------------------------------
 
 constexpr int kMaxM = 256;
@@ -358,15 +423,18 @@ int launch_encode(const float *x, int64_t n, int d, int M, int kc, int bits,
 // a gather of d values of v, a dot product and a scatter-add. Codewords no point uses keep
 // their value (unit diagonal, right-hand side = old value). All in fp64.
 
+// bits 32: one int32 per subspace (the leaf assignment seen as the code of a one-dictionary quantizer)
 __device__ __forceinline__ int code_at(const uint8_t *row, int m, int bits)
 {
+    if (bits == 32) return ((const int32_t *)row)[m];
     return bits == 8 ? (int)row[m] : (int)((row[m >> 1] >> (4 * (m & 1))) & 15);
 }
 
 // One wave per point (grid-stride): w_i, counts, right-hand side and the rank-one part of A's diagonal.
 __global__ void __launch_bounds__(256)
 pq_update_setup_kernel(const float *__restrict__ x, int64_t n, int d, int M, int kc, int bits, int NB,
-                       const uint8_t *__restrict__ codes, int eta_mode, double T, double eta_explicit,
+                       const uint8_t *__restrict__ codes, const float *__restrict__ centers,
+                       const int32_t *__restrict__ assign, int eta_mode, double T, double eta_explicit,
                        double *__restrict__ w_out, double *__restrict__ eta_out, double *__restrict__ b,
                        double *__restrict__ dA, unsigned int *__restrict__ cnt)
 {
@@ -377,9 +445,15 @@ pq_update_setup_kernel(const float *__restrict__ x, int64_t n, int d, int M, int
     for (int64_t i = wave0; i < n; i += n_waves) {
         const float *xi = x + (size_t)i * d;
         const uint8_t *ci = codes + (size_t)i * NB;
-        double part = 0.0;
-        for (int a = lane; a < d; a += 64) part += (double)xi[a] * (double)xi[a];
-        for (int m = 32; m > 0; m >>= 1) part += __shfl_xor(part, m, 64);
+        // with leaf centers g: x~ = g + B c, the loss still against x; the right-hand side is B^T A (x - g),
+        // A v = v + w x (x^T v); without, A x = eta x
+        const float *gi = centers ? centers + (size_t)assign[i] * d : nullptr;
+        double part = 0.0, xr = 0.0;
+        for (int a = lane; a < d; a += 64) {
+            part += (double)xi[a] * (double)xi[a];
+            if (gi) xr += (double)xi[a] * ((double)xi[a] - (double)gi[a]);
+        }
+        for (int m = 32; m > 0; m >>= 1) { part += __shfl_xor(part, m, 64); xr += __shfl_xor(xr, m, 64); }
         const double nx2 = part;
         const double eta = eta_of_norm(d, T, sqrt(nx2), eta_mode, eta_explicit);
         const double wi = nx2 > 0.0 ? (eta - 1.0) / nx2 : 0.0;
@@ -390,7 +464,8 @@ pq_update_setup_kernel(const float *__restrict__ x, int64_t n, int d, int M, int
         for (int a = lane; a < d; a += 64) {
             const int m = a / ds;
             const int slot = m * kc + code_at(ci, m, bits);
-            unsafeAtomicAdd(&b[(size_t)slot * ds + (a - m * ds)], eta * (double)xi[a]);
+            const double rhs = gi ? ((double)xi[a] - (double)gi[a]) + wi * xr * (double)xi[a] : eta * (double)xi[a];
+            unsafeAtomicAdd(&b[(size_t)slot * ds + (a - m * ds)], rhs);
             if (wi != 0.0) unsafeAtomicAdd(&dA[(size_t)slot * ds + (a - m * ds)], wi * (double)xi[a] * (double)xi[a]);
             if (a == m * ds) atomicAdd(&cnt[slot], 1u);
         }
@@ -537,6 +612,7 @@ size_t pq_update_scratch_bytes(int64_t n, int D, int slots)
 }
 
 int pq_joint_update_device(const float *x, int64_t n, int d, int M, int kc, int bits, const uint8_t *codes,
+                           const float *centers, const int32_t *assign,
                            int eta_mode, double T, double eta_explicit, float *codebooks, void *scratch,
                            int max_iters, double tol, int *iters_out, double *rel_residual_out, hipStream_t st)
 {
@@ -548,7 +624,7 @@ int pq_joint_update_device(const float *x, int64_t n, int d, int M, int kc, int 
     AVQ_HIP(hipMemsetAsync(b, 0, sizeof(double) * ((size_t)6 * D + 4) + sizeof(unsigned int) * (size_t)slots, st));
     const int grid = (int)std::min<int64_t>(1024, (n + 3) / 4);
     hipLaunchKernelGGL(pq_update_setup_kernel, dim3(grid), dim3(256), 0, st, x, n, d, M, kc, bits, NB, codes,
-                       eta_mode, T, eta_explicit, w, eta, b, dA, cnt);
+                       centers, assign, eta_mode, T, eta_explicit, w, eta, b, dA, cnt);
     AVQ_HIP(hipGetLastError());
     const int vgrid = (D + 255) / 256;
     hipLaunchKernelGGL(pq_update_init_kernel, dim3(vgrid), dim3(256), 0, st, D, ds, cnt, codebooks, c, b, y, dA);

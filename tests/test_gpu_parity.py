@@ -830,3 +830,78 @@ def test_quality_metrics_and_T_sweep_equal_the_oracles():
         top1_err[T] = rel.mean()
     # the direction Figure 2b shows: the estimate of the top inner product improves as T grows from 0
     assert top1_err[0.2] < top1_err[0.0] and top1_err[0.5] < top1_err[0.0], top1_err
+
+
+@pytest.mark.parametrize("bits,M,d", [(4, 8, 16), (8, 3, 12)])
+def test_update_codebooks_on_a_partitioned_index_matches(bits, M, d):
+    # Appendix 7.5 with leaf centers: x~ = center + PQ(residual), the loss against x itself (Theorem 4.2's
+    # weights come from x, the right-hand side from the residual)
+    rng = np.random.default_rng(41 + bits)
+    n, L, kc = 3000, 6, 1 << bits
+    x = unit_rows(rng, n, d) * np.exp(0.2 * rng.standard_normal((n, 1))).astype(np.float32)
+    xd = dev(x)
+    idx = avq.Index(d, M, bits, T=0.3, n_leaves=L, kmeans_iters=3, leaf_kmeans_iters=3, encode_passes=3, seed=9)
+    idx.train(xd)
+    idx.encode(xd)
+    cb, centers, assign = idx.get_codebooks(), idx.get_leaf_centers(), idx.get_leaf_assign()
+    codes = unpack_codes(idx.get_codes(), M, bits)
+    eta = np.array([oracle.eta_limit(d, 0.3, float(np.linalg.norm(xi.astype(np.float64)))) for xi in x])
+    want = oracle.pq_joint_update(x, codes, eta, cb, centers, assign)
+    iters, rel = idx.update_codebooks(xd, max_iters=4000, tol=1e-12)
+    got = idx.get_codebooks()
+    assert rel <= 1e-12 and iters > 0
+    np.testing.assert_allclose(got, want, rtol=2e-5, atol=2e-6)
+
+    def total(cbx):
+        xt = oracle.reconstruct(codes, cbx, centers, assign)
+        return sum(oracle.aniso_loss(x[i], xt[i], eta[i]) for i in range(n))
+    assert total(got) < total(cb)
+
+
+def test_anisotropic_leaves_assignment_center_update_and_training():
+    # Section 4 with the leaf centers as the codewords of a vector quantizer: assignment to the center of
+    # smallest anisotropic loss (Definition 4.1), Theorem 4.2's update of every center, and avq_train's
+    # alternation of the two; each piece against the oracle, the whole by the loss it lowers.
+    rng = np.random.default_rng(51)
+    n, d, M, L, T = 5000, 16, 8, 9, 0.5
+    x = unit_rows(rng, n, d) * np.exp(0.15 * rng.standard_normal((n, 1))).astype(np.float32)
+    xd = dev(x)
+    l2 = avq.Index(d, M, 4, T=T, n_leaves=L, kmeans_iters=2, leaf_kmeans_iters=4, encode_passes=2, seed=3)
+    l2.train(xd)
+    centers = l2.get_leaf_centers()
+    # assignment: an index whose leaves are anisotropic, given the same centers
+    an = avq.Index(d, M, 4, T=T, n_leaves=L, kmeans_iters=2, leaf_kmeans_iters=4, encode_passes=2, seed=3,
+                   leaf_aniso_iters=2)
+    an.set_codebooks(l2.get_codebooks())
+    an.set_leaf_centers(centers)
+    an.encode(xd)
+    got_assign = an.get_leaf_assign()
+    want_assign = oracle.assign_aniso(x, centers, T)
+    assert np.mean(got_assign != want_assign) <= 1e-3
+    assert np.mean(want_assign != oracle.assign_nearest(x, centers)) > 0.01      # the loss changes the partition
+    # Theorem 4.2 for every leaf, with that assignment
+    iters, rel = an.update_leaf_centers(xd, max_iters=2000, tol=1e-12)
+    assert rel <= 1e-12 and iters > 0
+    want_centers = oracle.vq_centers_update(x, got_assign, centers, T)
+    np.testing.assert_allclose(an.get_leaf_centers(), want_centers, rtol=2e-5, atol=2e-6)
+    # training with the alternation lowers the anisotropic loss of the vector quantizer below Lloyd's
+    tr = avq.Index(d, M, 4, T=T, n_leaves=L, kmeans_iters=2, leaf_kmeans_iters=4, encode_passes=2, seed=3,
+                   leaf_aniso_iters=3)
+    tr.train(xd)
+    tr.encode(xd)
+    eta = np.array([oracle.eta_limit(d, T, float(np.linalg.norm(xi.astype(np.float64)))) for xi in x])
+
+    def vq_loss(c, a):
+        return sum(oracle.aniso_loss(x[i], c[a[i]], eta[i]) for i in range(n))
+    base = vq_loss(centers, oracle.assign_nearest(x, centers))
+    trained = vq_loss(tr.get_leaf_centers(), tr.get_leaf_assign())
+    assert trained < 0.995 * base, (trained, base)
+    # searches on such an index equal the oracle's (the oracle takes the centers and the assignment as given)
+    q = unit_rows(rng, 40, d)
+    oi, os_ = oracle.search(x, tr.get_codebooks(), unpack_codes(tr.get_codes(), M, 4), 4, q, 10, 50, 0,
+                            centers=tr.get_leaf_centers(), assign=tr.get_leaf_assign(), leaves_to_search=4)
+    ids, sc = tr.search(dev(q), 10, 50, 0, leaves_to_search=4)
+    np.testing.assert_array_equal(ids.cpu().numpy(), oi)
+    np.testing.assert_array_equal(sc.cpu().numpy(), os_)
+    with pytest.raises(avq.AvqError):
+        avq.Index(d, M, 4).update_leaf_centers(xd)               # flat index

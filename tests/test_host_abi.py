@@ -42,11 +42,11 @@ def test_eta_host_matches_oracle():
     dict(d=1, M=1), dict(d=100, M=7), dict(d=100, M=0), dict(d=100, M=50, bits=5),
     dict(d=100, M=50, T=-0.1), dict(d=100, M=50, eta_mode=3),
     dict(d=100, M=50, eta_mode=2, eta_explicit=0.5), dict(d=100, M=50, kmeans_iters=-1),
-    dict(d=100, M=50, n_leaves=-2), dict(d=512, M=512),
+    dict(d=100, M=50, n_leaves=-2), dict(d=512, M=512), dict(d=100, M=50, leaf_aniso_iters=-1),
 ])
 def test_create_rejects_bad_config_without_a_gpu(kw):
     base = dict(d=100, M=50, bits=4, T=0.2, eta_mode=0, eta_explicit=1.0, kmeans_iters=1,
-                encode_passes=1, n_leaves=0, leaf_kmeans_iters=1, borrow_x=1, seed=0)
+                encode_passes=1, n_leaves=0, leaf_kmeans_iters=1, borrow_x=1, seed=0, leaf_aniso_iters=0)
     base.update(kw)
     cfg = avq.AvqConfig(*[base[f[0]] for f in avq.AvqConfig._fields_])
     h = C.c_void_p()
@@ -83,7 +83,7 @@ def _shell_index(d=100, M=50, bits=4, n_leaves=0):
     idx = avq.Index.__new__(avq.Index)
     idx.d, idx.M, idx.bits, idx.n_leaves = d, M, bits, n_leaves
     idx.kc, idx.ds, idx.nb = 1 << bits, d // M, (M * bits + 7) // 8
-    idx.cfg = avq.AvqConfig(d, M, bits, 0.2, 0, 1.0, 1, 1, n_leaves, 1, 1, 0)
+    idx.cfg = avq.AvqConfig(d, M, bits, 0.2, 0, 1.0, 1, 1, n_leaves, 1, 1, 0, 0)
     idx._h = None
     idx._keep = []
     return idx
