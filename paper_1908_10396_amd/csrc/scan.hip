@@ -1237,7 +1237,15 @@ select_bound_blocks_kernel(const uint32_t *__restrict__ block_bound, int64_t n_b
     for (int b = tid; b < kBins; b += nt) hist[b] = 0u;
     if (tid == 0) { theta_s = 0u; n_sel = 0u; }
     __syncthreads();
-    for (int64_t b = tid; b < n_blocks; b += nt) atomicAdd(&hist[bb[b] < kBins ? bb[b] : kBins - 1], 1u);
+    // eight loads in flight per thread: with hundreds of thousands of blocks this pass is all memory latency
+    for (int64_t b0 = tid; b0 < n_blocks; b0 += (int64_t)8 * nt) {
+        uint32_t v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) { const int64_t b = b0 + (int64_t)u * nt; v[u] = b < n_blocks ? bb[b] : 0xffffffffu; }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (v[u] != 0xffffffffu) atomicAdd(&hist[v[u] < (uint32_t)kBins ? v[u] : kBins - 1], 1u);
+    }
     __syncthreads();
     const uint32_t need = (uint32_t)(n_blocks < R ? n_blocks : R);
     const int per = kBins / 1024; // bins per thread (nt == 1024)
@@ -1286,8 +1294,16 @@ select_bound_blocks_kernel(const uint32_t *__restrict__ block_bound, int64_t n_b
     }
     if (n_blocks < R) t1 = 1ull; // fewer blocks than R: no R points are known to reach any bound
     const uint32_t cut = theta > margin ? (uint32_t)(theta - margin) : 0u;
-    for (int64_t b = tid; b < n_blocks; b += nt)
-        if (bb[b] >= cut) sel_blk[(size_t)q * n_blocks + atomicAdd(&n_sel, 1u)] = (int32_t)b;
+    for (int64_t b0 = tid; b0 < n_blocks; b0 += (int64_t)8 * nt) {
+        uint32_t v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) { const int64_t b = b0 + (int64_t)u * nt; v[u] = b < n_blocks ? bb[b] : 0u; }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int64_t b = b0 + (int64_t)u * nt;
+            if (b < n_blocks && v[u] >= cut) sel_blk[(size_t)q * n_blocks + atomicAdd(&n_sel, 1u)] = (int32_t)b;
+        }
+    }
     __syncthreads();
     if (tid == 0) {
         meta[q].t1 = t1;

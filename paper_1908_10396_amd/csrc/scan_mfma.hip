@@ -343,7 +343,11 @@ adc_mfma_scan_kernel(const ScanParams p)
     int thr = thr_of();
     if (items && live) {
         // fma(sum, scale, off_q) >= bound can only hold from sum = floor((bound - off_q) / scale) - 2 on (two
-        // units for the rounding of this estimate); no bound, or tables without a range: everything is kept
+        // units for the rounding of this estimate) less what the roundings at the magnitude of the scores can
+        // move: the difference bound - off_q and the score itself (the fma, or the fp32 addition of <q, center>)
+        // are each within half an ulp of |bound| + |off_q|, which is many units when the table range is small
+        // against the leaf scores (tight leaves far from the origin); no bound, or tables without a range:
+        // everything is kept
         const uint32_t bound_o = p.item_bound[q]; // ordering value of the fp32 bound, 0: none
         const float sc = p.scale[q], bound = bound_o ? f32_from_ord(bound_o) : -INFINITY;
         const float off_q = __fadd_rn(p.bias[q], p.leaf_ip[(size_t)q * (p.leaf_stride ? p.leaf_stride : p.Lp) + (item_hi >> 21)]);
@@ -351,6 +355,9 @@ adc_mfma_scan_kernel(const ScanParams p)
         if (sc > 0.0f && bound > -INFINITY) {
             float a_f = floorf((bound - off_q) / sc);
             a_f = fminf(fmaxf(a_f, -1.0e9f), 1.0e9f);
+            const float ulp = (fabsf(bound) + fabsf(off_q)) * 1.1920929e-7f;
+            const float extra = fminf(ceilf(2.0f * ulp / sc), 1.0e9f);
+            a_f = fmaxf(a_f - extra, -1.0e9f);
             thr = (int)a_f - marg - 3 - off;
         }
     }

@@ -905,3 +905,33 @@ def test_anisotropic_leaves_assignment_center_update_and_training():
     np.testing.assert_array_equal(sc.cpu().numpy(), os_)
     with pytest.raises(avq.AvqError):
         avq.Index(d, M, 4).update_leaf_centers(xd)               # flat index
+
+
+@pytest.mark.parametrize("lut_mode", [0, 1])
+def test_partitioned_batch_with_tight_leaves_far_from_the_origin(lut_mode):
+    # Leaf centers of norm 50 and residuals of 1e-4: a unit of the 8-bit tables is far below the rounding of a
+    # score (<q, center> + table sum), so points tie after rounding and the lower id wins; the scan over leaves
+    # regrouped by leaf must keep every point that the rounding can lift to the bound. Against the oracle and
+    # the one-query-per-workgroup scan.
+    rng = np.random.default_rng(61)
+    n, d, M, L, nq, probe = 20_000, 16, 8, 32, 128, 16
+    centers = (unit_rows(rng, L, d) * 50.0).astype(np.float32)
+    assign = rng.integers(0, L, n).astype(np.int32)
+    cb = (rng.standard_normal((M, 16, d // M)) * 1e-4).astype(np.float32)
+    codes = rng.integers(0, 16, (n, M), dtype=np.uint8)
+    codes[1000:1400] = codes[1000]                   # exact duplicates inside and across blocks
+    assign[1000:1400] = assign[1000]
+    x = (centers[assign] + oracle.reconstruct(codes, cb).astype(np.float32)).astype(np.float32)
+    q = unit_rows(rng, nq, d)
+    idx = avq.Index(d, M, 4, T=0.2, n_leaves=L)
+    idx.set_codebooks(cb)
+    idx.set_leaf_centers(centers)
+    xd = dev(x)
+    idx.set_database(xd, oracle.pack_codes(codes, 4), assign)
+    idx.set_tuning("group_min_pairs", 1)
+    for k, R in ((10, 100), (50, 0)):
+        oi, os_ = oracle.search(x, cb, codes, 4, q, k, R, lut_mode, centers=centers, assign=assign, leaves_to_search=probe)
+        ids, sc = idx.search(dev(q), k, R, lut_mode, leaves_to_search=probe)
+        np.testing.assert_array_equal(ids.cpu().numpy(), oi)
+        np.testing.assert_array_equal(sc.cpu().numpy(), os_)
+    assert idx.debug_unverified_queries() < nq      # the regrouped path served queries
