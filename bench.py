@@ -249,10 +249,25 @@ def main():
     steps_per_pair = (nb + 1) // 2
     mfma_executed = 2.0 * (scanned if n_leaves else n_pad) * b_pad * steps_per_pair * 32
 
-    def lds_roofline(ms, batch):
-        """A scan that forms every sum from tables in LDS: bound by the plain ALU (adds) and the LDS gather."""
+    tiled = bits == 8 and not n_leaves and not small and nb in SPECIAL_NB   # batches of 8-bit codes: block bounds, 16 queries per tile
+
+    def lds_roofline(ms, batch, every_point=False):
+        """A scan that forms its sums from tables in LDS: bound by the plain ALU (adds) and the LDS gather."""
         adds = (2.0 if nib_tile else 1.0) * nb * scanned * batch
         lds_bytes = (8.0 if nib_tile else 4.0) * nb * scanned * batch
+        if tiled and not every_point:
+            # byte tables of six bits, sixteen queries per 16-byte entry: one byte of LDS per query, point and code byte;
+            # entries of four code bytes are added as packed bytes, then spread into 16-bit sums
+            r = {"bound": "alu", "achieved": 2.0 * M * scanned * batch / (ms * 1e-3) / 1e12, "peak": VALU_PEAK_TOPS,
+                 "unit": "TOP/s", "traffic": None, "kernel": "block_bound_tile_kernel<%d>" % nb, "avg_launch_ms": ms,
+                 "note": "the method's M lookups + M additions per query and point against the fp32 add peak; the kernel reads one "
+                         "16-byte LDS entry per point and code byte for sixteen queries and forms block maxima of 6-bit table sums "
+                         "(bounds); exact scores are formed afterwards for the blocks that can reach the R-th best",
+                 "lds_gather": {"achieved_GBs": nb * scanned * batch / (ms * 1e-3) / 1e9, "peak_GBs": LDS_PEAK_GBS,
+                                "frac": nb * scanned * batch / (ms * 1e-3) / 1e9 / LDS_PEAK_GBS},
+                 "code_stream_GBs": nb * scanned * ((batch + 15) // 16) / (ms * 1e-3) / 1e9}
+            r["frac"] = r["achieved"] / r["peak"]
+            return r
         if n_leaves:
             kern = "adc_scan_kernel<1,false,%d,1>" % (nb if nb in SPECIAL_NB else 0)
         else:
@@ -312,6 +327,14 @@ def main():
             % (B, fp32_direct["queries_per_s"], stage_d))
     else:
         batch_roof = lds_roofline(scan_ms, B)
+        if tiled:
+            idx.set_tuning("scan_prefilter", 1)
+            dt_d, stage_d = timed_batch(avq.LUT_F32, max(2, args.steps // 5))
+            idx.set_tuning("scan_prefilter", 0)
+            fp32_direct = {"queries_per_s": B * max(2, args.steps // 5) / dt_d, "stage_ms": stage_d,
+                           "roofline": lds_roofline(stage_d["scan"], B, every_point=True)}
+            log("[bench] fp32 batch %d, every point scored in fp32: %.0f q/s, stages(ms) %s"
+                % (B, fp32_direct["queries_per_s"], stage_d))
     log("[bench] fp32 batch %d: %.2f ms/step, %.0f q/s, stages(ms) %s" % (B, ms_per_step, qps, stage_ms))
 
     # ---- same with 8-bit tables ---------------------------------------------------------------
@@ -447,7 +470,7 @@ def main():
     scan_desc = ("int8 matrix-core candidate scan + fp32 re-scoring of the kept points (results equal a full fp32 scan)"
                  if (prefiltered or grouped) else
                  ("block bounds from 8-bit table sums, exact scores of the blocks that can reach the R-th best"
-                  if (small and bound_scan) else "fp32 table sums of every point"))
+                  if ((small and bound_scan) or tiled) else "fp32 table sums of every point"))
     out = {
         "metric": "queries/sec at Recall@10 vs brute force; ADC codes/sec and % HBM BW",
         "value": qps, "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

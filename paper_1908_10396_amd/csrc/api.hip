@@ -931,6 +931,7 @@ static bool small_uses_bounds(const avq_index *idx)
 // base == NULL: only the size.
 static size_t small_ws_carve(const avq_index *idx, int nq, int R, unsigned char *base, SmallWs *w)
 {
+    const int nq_tiles = (nq + 15) / 16 * 16; // the batch form of the block-bound scan lays its tables out in tiles of 16
     size_t off = 0;
     auto take = [&](size_t bytes) -> void * {
         const size_t at = (off + 255) & ~(size_t)255;
@@ -949,7 +950,7 @@ static size_t small_ws_carve(const avq_index *idx, int nq, int R, unsigned char 
     w->meta = (SmallMeta *)take(sizeof(SmallMeta) * (size_t)nq);
     w->block_bound = (uint32_t *)take(bounds ? sizeof(uint32_t) * (size_t)nq * idx->n_blocks : 0);
     w->bound_meta = (BoundMeta *)take(bounds ? sizeof(BoundMeta) * (size_t)nq : 0);
-    w->bound_tbl = (uint8_t *)take(bounds ? (size_t)nq * idx->NB * 256 : 0);
+    w->bound_tbl = (uint8_t *)take(bounds ? (size_t)nq_tiles * idx->NB * 256 : 0);
     return off;
 }
 
@@ -962,8 +963,9 @@ static int small_ws_from_index(avq_index *idx, int nq, int R, SmallWs *w)
 }
 
 // Launches only: no allocation, no synchronisation. timers: per-stage event pairs while profiling is on.
+// tile: the batch form (8-bit codes): the full scan takes the queries sixteen at a time, with 6-bit byte tables.
 static int search_small(avq_index *idx, const float *queries, int nq, int k, int reorder_k, bool u8, bool fuse_tables,
-                        const SmallWs &w, bool timers, int32_t *ids_out, float *scores_out, hipStream_t st)
+                        const SmallWs &w, bool timers, int32_t *ids_out, float *scores_out, hipStream_t st, bool tile = false)
 {
     const avq_config &c = idx->cfg;
     const int R = reorder_k ? reorder_k : k;
@@ -993,13 +995,20 @@ static int search_small(avq_index *idx, const float *queries, int nq, int k, int
     p.bound_meta = w.bound_meta;
     p.lut_out = fuse_tables ? w.lut : nullptr;
     p.bound_tbl = w.bound_tbl;
+    if (tile) {
+        p.bound_tile = 16;
+        p.bound_levels = 63;
+        p.bound_shift = 2;
+        p.blocks_per_chunk = block_bound_tile_chunk(idx->n_blocks, nq);
+    }
     if (bounds) {
         StageTimer t(idx, AVQ_STAGE_LUT, st, timers);
         AVQ_TRY(launch_bound_tables(p, u8, st));
     }
     {
         StageTimer t(idx, AVQ_STAGE_SCAN, st, timers);
-        if (bounds) AVQ_TRY(launch_block_bound(p, idx->tune_waves, st));
+        if (bounds && tile) AVQ_TRY(launch_block_bound_tile(p, st));
+        else if (bounds) AVQ_TRY(launch_block_bound(p, idx->tune_waves, st));
         else AVQ_TRY(launch_block_max(p, u8, idx->tune_waves > 0 ? idx->tune_waves : 4, st));
     }
     FinishParams f;
@@ -1088,6 +1097,13 @@ extern "C" int avq_search(avq_index *idx, const float *queries, int32_t nq, int3
         SmallWs w;
         AVQ_TRY(small_ws_from_index(idx, nq, R, &w));
         return search_small(idx, queries, nq, k, reorder_k, u8, fuse_tables, w, true, ids_out, scores_out, st);
+    }
+    // Batches of 8-bit codes on a flat index: the same search through block bounds, the full scan taking the queries
+    // sixteen at a time (byte tables of six bits); "scan_prefilter" = 1 scores every point instead
+    if (!ivf && !small && c.bits == 8 && idx->tune_prefilter != 1 && small_uses_bounds(idx)) {
+        SmallWs w;
+        AVQ_TRY(small_ws_from_index(idx, nq, R, &w));
+        return search_small(idx, queries, nq, k, reorder_k, u8, false, w, true, ids_out, scores_out, st, true);
     }
     if (!fuse_tables) {
         StageTimer t(idx, AVQ_STAGE_LUT, st);

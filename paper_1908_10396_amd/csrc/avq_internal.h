@@ -98,7 +98,11 @@ struct ScanParams {
     uint32_t *block_bound;
     struct BoundMeta *bound_meta;
     float *lut_out;
-    uint8_t *bound_tbl;    // [B][NB][256] the byte tables of the block-bound scan (made by launch_bound_tables)
+    uint8_t *bound_tbl;    // [B][NB][256] the byte tables of the block-bound scan (made by launch_bound_tables);
+                           // bound_tile = 16: [ceil(B / 16)][NB][256][16], the tables of 16 queries side by side
+    int32_t bound_tile;    // 0 or 16
+    int32_t bound_levels;  // largest table entry: 255 (0: 255), or 63 for the batch scan, which adds entries as packed bytes
+    int32_t bound_shift;   // 8-bit tables on 8-bit codes: the byte tables are the 8-bit tables >> bound_shift (0 or 2)
     u64 *partial;         // [n_tiles*QT][n_chunks][64*ns]
     u64 *lists_ws;        // NULL: candidate lists in LDS; else scratch [grid][waves][QT][64*ns]
     // matrix-core kernel, both zeroed before the launch: [B] best known bound of the R-th best
@@ -211,6 +215,10 @@ bool block_bound_supported(int NB, int bits);
 int launch_bound_tables(const ScanParams &p, bool u8, hipStream_t st);
 // lookups_only: the same lookups in the same launch shape on made-up code words, no code stream (measurement)
 int launch_block_bound(const ScanParams &p, int waves, hipStream_t st, bool lookups_only = false);
+// the batch form: tiles of 16 queries x chunks of p.blocks_per_chunk blocks (block_bound_tile_chunk); needs
+// bound_tile = 16, bound_levels = 63 (and bound_shift = 2 with 8-bit tables)
+int block_bound_tile_chunk(int64_t n_blocks, int B);
+int launch_block_bound_tile(const ScanParams &p, hipStream_t st);
 int launch_select_bound_blocks(const ScanParams &p, const FinishParams &f, bool u8, hipStream_t st);
 int launch_rescan_listed(const ScanParams &p, const FinishParams &f, bool u8, hipStream_t st);
 int launch_small_select(const ScanParams &p, const FinishParams &f, hipStream_t st);

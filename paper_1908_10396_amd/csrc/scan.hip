@@ -991,10 +991,28 @@ bound_tables_kernel(const ScanParams p)
     const int lane = tid & 63, wave = tid >> 6, n_waves = nt >> 6;
     const int q = blockIdx.x;
     const int NB = p.NB;
-    uint32_t *out = (uint32_t *)(p.bound_tbl + (size_t)q * NB * 256);
+    // Word `it` of a query's tables = the entries of byte position it / 64, byte values 4 (it % 64) .. + 3. Plain
+    // layout: [q][NB][256] bytes. Tile layout (p.bound_tile = 16, the batch scan): [q / 16][NB][256][16], the
+    // sixteen queries of a tile side by side in every entry; the launch covers whole tiles and the queries
+    // beyond the batch get zero tables (their bytes share words with live queries' in the scan's sums).
+    auto put = [&](int it, uint32_t pack) {
+        if (p.bound_tile == 0) {
+            ((uint32_t *)(p.bound_tbl + (size_t)q * NB * 256))[it] = pack;
+        } else {
+            uint8_t *dst = p.bound_tbl + (((size_t)(q >> 4) * NB * 256 + (size_t)it * 4) << 4) + (q & 15);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) dst[k * 16] = (uint8_t)(pack >> (8 * k));
+        }
+    };
+    if (q >= p.B) {
+        for (int it = tid; it < NB * 64; it += nt) put(it, 0u);
+        return;
+    }
+    const float levels = (float)(p.bound_levels > 0 ? p.bound_levels : 255);
     if constexpr (U8 && WIDE) {
         const uint32_t *L = (const uint32_t *)(p.lut8 + (size_t)q * NB * 256);
-        for (int it = tid; it < NB * 64; it += nt) out[it] = L[it];
+        const uint32_t keep = 0x01010101u * (0xffu >> p.bound_shift);
+        for (int it = tid; it < NB * 64; it += nt) put(it, (L[it] >> p.bound_shift) & keep);
         return;
     }
     if constexpr (U8 && !WIDE) {
@@ -1009,7 +1027,7 @@ bound_tables_kernel(const ScanParams p)
             uint32_t pack = 0;
 #pragma unroll
             for (int k = 0; k < 4; ++k) pack |= (((uint32_t)n8[32 * b + (v0 & 15) + k] + hi + 1u) >> 1) << (8 * k);
-            out[it] = pack;
+            put(it, pack);
         }
         return;
     }
@@ -1072,7 +1090,7 @@ bound_tables_kernel(const ScanParams p)
                 sum_lo += __shfl_xor(sum_lo, m, 64);
                 amax += __shfl_xor(amax, m, 64);
             }
-            const float c = range > 1e-30f ? __fdiv_rn(255.0f, range) : 0.0f;
+            const float c = range > 1e-30f ? __fdiv_rn(levels, range) : 0.0f;
             if (lane == 0) {
                 c_s = c;
                 BoundMeta bm;
@@ -1098,10 +1116,10 @@ bound_tables_kernel(const ScanParams p)
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 float u = rintf(__fmul_rn(__fsub_rn(t[k], lo_b), c));
-                u = fminf(fmaxf(u, 0.0f), 255.0f);
+                u = fminf(fmaxf(u, 0.0f), levels);
                 pack |= (uint32_t)u << (8 * k);
             }
-            out[it] = pack;
+            put(it, pack);
         }
     }
 }
@@ -1176,6 +1194,113 @@ block_bound_kernel(const ScanParams p)
     }
 }
 
+// The same block maxima for a batch: a workgroup holds the byte tables of sixteen queries in LDS, side by side in
+// every entry (16 bytes per byte position and byte value: one 16-byte read serves sixteen queries), and its
+// waves take the blocks of one chunk of the index in turn. Table entries are at most 63 here (six bits), so the
+// entries of four byte positions are added as packed bytes before they are spread into 16-bit sums: sums of 32
+// positions stay below 2^11. One 32-bit store per query and block.
+typedef unsigned short pk_u16 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b)
+{
+    const pk_u16 r = __builtin_elementwise_max(*(const pk_u16 *)&a, *(const pk_u16 *)&b);
+    return *(const uint32_t *)&r;
+}
+
+template <int NBT>
+__global__ void __launch_bounds__(1024)
+block_bound_tile_kernel(const ScanParams p)
+{
+    static_assert(NBT != 0 && NBT <= 32, "specialised code sizes only");
+    extern __shared__ __align__(16) unsigned char dyn_smem[];
+    const uint4 *tbl = (const uint4 *)dyn_smem; // [NBT][256] entries of 16 queries
+    const int tid = threadIdx.x, nt = blockDim.x;
+    const int lane = tid & 63, wave = tid >> 6, n_waves = nt >> 6;
+    const int tile = blockIdx.x, q0 = tile * 16;
+    const int64_t c0 = (int64_t)blockIdx.y * p.blocks_per_chunk;
+    const int64_t c1 = c0 + p.blocks_per_chunk < p.n_blocks ? c0 + p.blocks_per_chunk : p.n_blocks;
+    int64_t blk = c0 + wave;
+    BlockRegs<NBT> regs, nxt;
+    if (blk < c1) load_block<NBT>(regs, p.codes, blk, lane);
+    {
+        const uint4 *src = (const uint4 *)(p.bound_tbl + (size_t)tile * NBT * 256 * 16);
+        for (int it = tid; it < NBT * 256; it += nt) ((uint4 *)dyn_smem)[it] = src[it];
+    }
+    __syncthreads();
+    for (; blk < c1; blk += n_waves) {
+        const bool more = blk + n_waves < c1;
+        if (more) load_block<NBT>(nxt, p.codes, blk + n_waves, lane);
+        uint32_t even[4][4], odd[4][4]; // [point][word]: 16-bit sums of queries 4w, 4w + 2 (even) and 4w + 1, 4w + 3 (odd)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int w = 0; w < 4; ++w) { even[i][w] = 0u; odd[i][w] = 0u; }
+        auto spread = [&](int i, const uint4 &sum) {
+            const uint32_t sw[4] = {sum.x, sum.y, sum.z, sum.w};
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                even[i][w] += sw[w] & 0x00ff00ffu;
+                odd[i][w] += (sw[w] >> 8) & 0x00ff00ffu;
+            }
+        };
+        auto entry = [&](uint32_t word, int i, int b) -> uint4 { return tbl[b * 256 + ((word >> (8 * i)) & 0xffu)]; };
+        auto add4 = [](const uint4 &a, const uint4 &b) -> uint4 { return make_uint4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w); };
+#pragma unroll
+        for (int j = 0; j < NBT / 4; ++j) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                uint4 sum = add4(add4(entry(regs.rows[j].x, i, 4 * j), entry(regs.rows[j].y, i, 4 * j + 1)),
+                                 add4(entry(regs.rows[j].z, i, 4 * j + 2), entry(regs.rows[j].w, i, 4 * j + 3)));
+                spread(i, sum);
+                // keeps a point's four reads together and the sums where they are: left alone the compiler reads
+                // every entry of the block first and spills
+                asm volatile("" : "+v"(even[i][0]), "+v"(even[i][1]), "+v"(even[i][2]), "+v"(even[i][3]),
+                                  "+v"(odd[i][0]), "+v"(odd[i][1]), "+v"(odd[i][2]), "+v"(odd[i][3]));
+            }
+        }
+        if constexpr (NBT % 4 != 0) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                uint4 sum = entry(regs.tails[0], i, (NBT / 4) * 4);
+#pragma unroll
+                for (int tt = 1; tt < NBT % 4; ++tt) sum = add4(sum, entry(regs.tails[tt], i, (NBT / 4) * 4 + tt));
+                spread(i, sum);
+            }
+        }
+        // best of the lane's four points (padding slots of the last block count for nothing), then of the wave
+        uint32_t be[4], bo[4];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) { be[w] = 0u; bo[w] = 0u; }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const bool valid = blk * 256 + 4 * lane + i < p.n_valid;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                be[w] = pk_max_u16(be[w], valid ? even[i][w] : 0u);
+                bo[w] = pk_max_u16(bo[w], valid ? odd[i][w] : 0u);
+            }
+        }
+#pragma unroll
+        for (int m = 32; m > 0; m >>= 1) {
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                be[w] = pk_max_u16(be[w], (uint32_t)__shfl_xor((int)be[w], m, 64));
+                bo[w] = pk_max_u16(bo[w], (uint32_t)__shfl_xor((int)bo[w], m, 64));
+            }
+        }
+        if (lane < 16 && q0 + lane < p.B) {
+            // query lane of the tile: byte lane & 3 of word lane >> 2; bytes 0, 2 are in `even`, 1, 3 in `odd`
+            const int w = lane >> 2, byte = lane & 3;
+            uint32_t v = 0;
+#pragma unroll
+            for (int ww = 0; ww < 4; ++ww)
+                if (ww == w) v = (byte & 1) ? bo[ww] : be[ww];
+            v = (byte & 2) ? (v >> 16) : (v & 0xffffu);
+            p.block_bound[(size_t)(q0 + lane) * p.n_blocks + blk] = v;
+        }
+        if (more) regs = nxt;
+    }
+}
+
 // Measurement aid: the lookups and additions of block_bound_kernel in its launch shape, with no code stream --
 // a wave's code words are made up from its block number (a different byte in every position, lane and block)
 // instead of being loaded. Its duration is what the table lookups of a scan cost by themselves.
@@ -1221,9 +1346,10 @@ lookup_only_kernel(const ScanParams p)
 // One workgroup per query: theta = the R-th largest block maximum of the 8-bit sums, the list of the blocks
 // whose maximum reaches theta - margin, and the lower bound of the R-th best exact score as a key
 // threshold (meta[q].t1). kind 0: fp32 tables (margin and bound from bound_meta, see above), 1: 8-bit
-// tables on 4-bit codes (sums halved), 2: 8-bit tables on 8-bit codes (sums exact).
+// tables on 4-bit codes (sums halved), 2: 8-bit tables on 8-bit codes (the tables themselves, or without their
+// `shift` low bits).
 __global__ void __launch_bounds__(1024)
-select_bound_blocks_kernel(const uint32_t *__restrict__ block_bound, int64_t n_blocks, int R, int NB, int kind,
+select_bound_blocks_kernel(const uint32_t *__restrict__ block_bound, int64_t n_blocks, int R, int NB, int kind, int shift,
                            const BoundMeta *__restrict__ bound_meta, int32_t *__restrict__ sel_blk,
                            SmallMeta *__restrict__ meta)
 {
@@ -1289,8 +1415,10 @@ select_bound_blocks_kernel(const uint32_t *__restrict__ block_bound, int64_t n_b
         const int low = 2 * theta - NB;
         t1 = (u64)(uint32_t)((low > 0 ? low : 0) + 1) << 32;
     } else {
-        margin = 0;
-        t1 = (u64)(uint32_t)(theta + 1) << 32;
+        // the tables are the 8-bit tables less their `shift` low bits: the exact sum lies in [s I, s I + (s - 1) NB]
+        const int sc = 1 << shift;
+        margin = ((sc - 1) * NB + sc - 1) / sc;
+        t1 = (u64)(uint32_t)(sc * theta + 1) << 32;
     }
     if (n_blocks < R) t1 = 1ull; // fewer blocks than R: no R points are known to reach any bound
     const uint32_t cut = theta > margin ? (uint32_t)(theta - margin) : 0u;
@@ -1821,7 +1949,7 @@ static int launch_block_bound_one(const ScanParams &p, int waves, bool lookups_o
 
 int launch_bound_tables(const ScanParams &p, bool u8, hipStream_t st)
 {
-    const dim3 grid(p.B), block(1024);
+    const dim3 grid(p.bound_tile ? (p.B + p.bound_tile - 1) / p.bound_tile * p.bound_tile : p.B), block(1024);
     if (p.bits == 8) {
         if (u8) hipLaunchKernelGGL((bound_tables_kernel<true, true>), grid, block, 0, st, p);
         else hipLaunchKernelGGL((bound_tables_kernel<false, true>), grid, block, 0, st, p);
@@ -1846,10 +1974,46 @@ int launch_block_bound(const ScanParams &p, int waves, hipStream_t st, bool look
     }
 }
 
+template <int NBT>
+static int launch_block_bound_tile_one(const ScanParams &p, hipStream_t st)
+{
+    auto kern = block_bound_tile_kernel<NBT>;
+    static LdsLimitOnce attr_done;
+    AVQ_TRY(set_max_lds(kern, &attr_done));
+    const int tiles = (p.B + 15) / 16;
+    const int chunks = (int)((p.n_blocks + p.blocks_per_chunk - 1) / p.blocks_per_chunk);
+    // the tile index runs fastest: the workgroups that are resident together scan the same few chunks, so the
+    // codes they stream are shared through the caches beyond a compute unit
+    hipLaunchKernelGGL(kern, dim3(tiles, chunks), dim3(1024), (size_t)NBT * 256 * 16, st, p);
+    AVQ_HIP(hipGetLastError());
+    return AVQ_OK;
+}
+
+int block_bound_tile_chunk(int64_t n_blocks, int B)
+{
+    // about four rounds of one workgroup per compute unit, chunks of at least 128 blocks (eight per wave)
+    const int tiles = (B + 15) / 16;
+    int64_t chunks = std::max<int64_t>(1, 1024 / tiles);
+    chunks = std::min<int64_t>(chunks, std::max<int64_t>(1, n_blocks / 128));
+    return (int)((n_blocks + chunks - 1) / chunks);
+}
+
+int launch_block_bound_tile(const ScanParams &p, hipStream_t st)
+{
+    switch (p.NB) {
+    case 8: return launch_block_bound_tile_one<8>(p, st);
+    case 13: return launch_block_bound_tile_one<13>(p, st);
+    case 25: return launch_block_bound_tile_one<25>(p, st);
+    case 32: return launch_block_bound_tile_one<32>(p, st);
+    default: set_error("block bounds: unsupported code size %d", p.NB); return AVQ_EINVAL;
+    }
+}
+
 int launch_select_bound_blocks(const ScanParams &p, const FinishParams &f, bool u8, hipStream_t st)
 {
     const int kind = !u8 ? 0 : (p.bits == 4 ? 1 : 2);
     hipLaunchKernelGGL(select_bound_blocks_kernel, dim3(p.B), dim3(1024), 0, st, p.block_bound, p.n_blocks, p.R, p.NB, kind,
+                       kind == 2 ? p.bound_shift : 0,
                        p.bound_meta, f.sel_blk, f.meta);
     AVQ_HIP(hipGetLastError());
     return AVQ_OK;

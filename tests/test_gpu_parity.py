@@ -935,3 +935,36 @@ def test_partitioned_batch_with_tight_leaves_far_from_the_origin(lut_mode):
         np.testing.assert_array_equal(ids.cpu().numpy(), oi)
         np.testing.assert_array_equal(sc.cpu().numpy(), os_)
     assert idx.debug_unverified_queries() < nq      # the regrouped path served queries
+
+
+@pytest.mark.parametrize("M,d", [(32, 256), (8, 64), (13, 26), (25, 50)])
+@pytest.mark.parametrize("lut_mode", [0, 1])
+def test_batches_of_8bit_codes_through_block_bounds(M, d, lut_mode):
+    # Batches on a flat index of 8-bit codes: the full scan takes the queries sixteen at a time over 6-bit byte
+    # tables and records block maxima; the blocks that can reach the R-th best are scored exactly per query.
+    # 43 queries (two full tiles and one of 11), a ragged last block, a heap of 30,000 points that share the best
+    # code word of query 0 (its candidate list overflows and is rebuilt), the same point planted at both ends.
+    rng = np.random.default_rng(2000 + M + lut_mode)
+    n, nq = 41_003, 43
+    x = unit_rows(rng, n, d)
+    q = unit_rows(rng, nq, d)
+    cb = oracle.train_pq(x[:2000], M, 256, 2, seed=8)
+    codes = rng.integers(0, 256, (n, M), dtype=np.uint8)
+    best = np.argmax(oracle.lut_f32(q[0], cb), axis=1).astype(np.uint8)
+    codes[5_000:35_000] = best
+    codes[0] = codes[n - 1] = np.argmax(oracle.lut_f32(q[1], cb), axis=1).astype(np.uint8)
+    case = dict(x=x, q=q, cb=cb, codes=codes, n=n, d=d, M=M, bits=8, kc=256)
+    idx, xd = make_index(case)
+    qd = dev(q)
+    for k, R in ((10, 100), (100, 0), (7, 7)):
+        oi, os_ = oracle.search(x, cb, codes, 8, q, k, R, lut_mode)
+        if R == 0:
+            assert list(oi[0]) == list(range(5_000, 5_000 + k)) and oi[1][0] == 0 and oi[1][1] == n - 1
+        ids, sc = idx.search(qd, k, R, lut_mode)
+        np.testing.assert_array_equal(ids.cpu().numpy(), oi)
+        np.testing.assert_array_equal(sc.cpu().numpy(), os_)
+        idx.set_tuning("scan_prefilter", 1)                       # every point scored: the same answer
+        ids2, sc2 = idx.search(qd, k, R, lut_mode)
+        idx.set_tuning("scan_prefilter", 0)
+        np.testing.assert_array_equal(ids2.cpu().numpy(), oi)
+        np.testing.assert_array_equal(sc2.cpu().numpy(), os_)
