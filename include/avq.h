@@ -166,7 +166,7 @@ int avq_update_leaf_centers(avq_index *idx, const float *x, int64_t n, int32_t m
  *    accumulated in order; 8-bit tables: exact integer sum). With leaves the
  *    score is s + <q, center> (fp32) or fma(acc, scale, bias + <q, center>);
  *  keep the R = reorder_k best by (score descending, id ascending). Batches
- *    (16 queries or more) with fp32 tables on a flat index of 4-bit codes do
+ *    (36 queries or more) with fp32 tables on a flat index of 4-bit codes do
  *    not score every point in fp32: the 8-bit tables are built as well, the
  *    integer sums of all points are formed on the matrix cores, every point
  *    whose sum is within M + slack units of the R-th best sum is kept (the
@@ -184,7 +184,15 @@ int avq_update_leaf_centers(avq_index *idx, const float *x, int64_t n, int32_t m
  *    fma(sum, scale, bias + <q, center>) can reach the R-th best score of the
  *    query's first few leaves is kept, and the kept points are scored per
  *    query as above (fp32 tables: fp32 sums of the points within the rounding
- *    margin); same results;
+ *    margin); same results. A handful of queries on a flat index (up to 35 with
+ *    4-bit codes, up to 8 with 8-bit codes) and batches on a flat index of 8-bit
+ *    codes do not score every point either, where the code size has the kernels
+ *    for it (8, 13, 25 or 32 code bytes per point): the full scan sums 8-bit
+ *    (batches: 6-bit) images of the table entries, whose distance from the score is
+ *    bounded, and records the largest sum of every block of 256 points; the blocks
+ *    whose largest sum is within that bound of the R-th largest block maximum are
+ *    scored exactly (same order of additions), and the points at or above the lower
+ *    bound of the R-th best score are ranked. Same results, whatever the data;
  *  re-score those exactly, <q, x_i> as an fp32 fma chain in index order, and
  *    return the k best in the same order.
  * reorder_k == 0: no re-scoring; the k best ADC candidates are returned with

@@ -127,7 +127,7 @@ def test_full_partitioned_batch_matches_oracle_on_sampled_queries(lut_mode):
     np.testing.assert_array_equal(sc[sample], os_)
     assert np.all(np.diff(sc, axis=1) <= 0)
     if lut_mode == 0:
-        # leaf selection of the whole batch (one wave per query at this size)
+        # leaf selection of the whole batch (10,000 queries: eight queries per workgroup, leaf_select_tile_kernel)
         lids, lip = idx.debug_leaf_select(qd, L)
         lids, lip = lids.cpu().numpy(), lip.cpu().numpy()
         centers = idx.get_leaf_centers()
