@@ -211,9 +211,9 @@ int avq_search(avq_index *idx, const float *queries, int32_t nq, int32_t k, int3
  * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc. Same
  * results as avq_search for the same arguments, on a flat index, for a handful
  * of queries per call: it runs the launches avq_search uses for up to 35 queries
- * (block maxima of the whole code array, selection of the best blocks, scan of
- * those, exact re-scoring), and takes every scratch buffer of those kernels
- * (tables, block maxima, selected blocks, candidate keys) from one array of
+ * (block maxima or block bounds of the whole code array, selection of the blocks
+ * that matter, exact scores of those, exact re-scoring), and takes every scratch
+ * buffer of those kernels (tables, block maxima, listed blocks, candidate keys) from one array of
  * AVQ_NOALLOC_SCRATCH_BYTES that is part of the library's code object: each GPU
  * the library is loaded on holds its own copy from load time until the process
  * ends. The call itself allocates nothing, frees nothing, records no events and
@@ -221,7 +221,7 @@ int avq_search(avq_index *idx, const float *queries, int32_t nq, int32_t k, int3
  * once, on the first call. queries / ids_out / scores_out: device pointers as
  * for avq_search.
  * AVQ_EINVAL: a partitioned index; nq > AVQ_NOALLOC_MAX_QUERIES; a request whose
- * scratch (about 8 bytes per query and 256 stored points, plus 2 KiB per query
+ * scratch (8 to 16 bytes per query and 256 stored points, plus 2 KiB per query
  * and unit of reorder_k, plus the tables) exceeds the array -- the message
  * states the bytes needed; the argument errors of avq_search.
  * All calls on one GPU share that GPU's array, whatever the index or stream: two
