@@ -1531,7 +1531,9 @@ small_batch_final_kernel(const FinishParams f, int R, int key_kind, const float 
     u64 *fin2 = fin + R;                                                          // [R] re-scored
     uint32_t *counters = (uint32_t *)(fin2 + R);                                  // [4]
     float *qs = (float *)(counters + 4);                                          // [d]
-    unsigned char *region = (unsigned char *)(((uintptr_t)(qs + f.d) + 15) & ~(uintptr_t)15);
+    // (an offset from smem, not a rounded-up address: through an integer the pointer would lose its address space
+    // and every access below would become a flat one)
+    unsigned char *region = smem + ((((size_t)R * 16 + 16 + (size_t)f.d * 4) + 15) & ~(size_t)15);
     WgSelectScratch *sel = (WgSelectScratch *)region;
     u64 *clist = (u64 *)region;                                                   // [<= kSelList] candidate keys
     float *stage = (float *)region;                                               // [stage_rows][d + 1]
@@ -1891,7 +1893,6 @@ int small_finish_stage_rows(const ScanParams &p, int d, bool u8)
     const size_t row = (size_t)(d + 1) * 4;
     const size_t avail = kMaxDynLds - small_final_fixed_bytes(p.R, d) - 256;
     size_t want = (size_t)p.R * row;                       // all candidates at once if they fit
-    if (want > 96 * 1024) want = 96 * 1024;
     if (want < sizeof(WgSelectScratch)) want = sizeof(WgSelectScratch);
     if (want > avail) want = avail;
     const int rows = (int)(want / row);
