@@ -1363,15 +1363,31 @@ select_bound_blocks_kernel(const uint32_t *__restrict__ block_bound, int64_t n_b
     for (int b = tid; b < kBins; b += nt) hist[b] = 0u;
     if (tid == 0) { theta_s = 0u; n_sel = 0u; }
     __syncthreads();
-    // eight loads in flight per thread: with hundreds of thousands of blocks this pass is all memory latency
-    for (int64_t b0 = tid; b0 < n_blocks; b0 += (int64_t)8 * nt) {
-        uint32_t v[8];
+    // fn(block, its maximum) for every block. With hundreds of thousands of blocks a pass is all memory latency:
+    // 16-byte loads, four of them in flight per thread (the few values before the first 16-byte boundary of the
+    // query's row and after the last go one by one)
+    auto for_every_block = [&](auto fn) {
+        const int64_t mis = (int64_t)((4u - (uint32_t)(((size_t)bb >> 2) & 3u)) & 3u);
+        const int64_t head = mis < n_blocks ? mis : n_blocks;
+        const int64_t n4 = (n_blocks - head) / 4;
+        const uint4 *b4 = (const uint4 *)(bb + head);
+        if (tid < head) fn((int64_t)tid, bb[tid]);
+        for (int64_t i0 = tid; i0 < n4; i0 += (int64_t)4 * nt) {
+            uint4 v[4];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) { const int64_t b = b0 + (int64_t)u * nt; v[u] = b < n_blocks ? bb[b] : 0xffffffffu; }
+            for (int u = 0; u < 4; ++u) { const int64_t i = i0 + (int64_t)u * nt; v[u] = i < n4 ? b4[i] : make_uint4(0u, 0u, 0u, 0u); }
 #pragma unroll
-        for (int u = 0; u < 8; ++u)
-            if (v[u] != 0xffffffffu) atomicAdd(&hist[v[u] < (uint32_t)kBins ? v[u] : kBins - 1], 1u);
-    }
+            for (int u = 0; u < 4; ++u) {
+                const int64_t i = i0 + (int64_t)u * nt;
+                if (i >= n4) continue;
+                const int64_t b = head + 4 * i;
+                fn(b, v[u].x); fn(b + 1, v[u].y); fn(b + 2, v[u].z); fn(b + 3, v[u].w);
+            }
+        }
+        const int64_t b = head + 4 * n4 + tid;
+        if (b < n_blocks) fn(b, bb[b]);
+    };
+    for_every_block([&](int64_t, uint32_t v) { atomicAdd(&hist[v < (uint32_t)kBins ? v : kBins - 1], 1u); });
     __syncthreads();
     const uint32_t need = (uint32_t)(n_blocks < R ? n_blocks : R);
     const int per = kBins / 1024; // bins per thread (nt == 1024)
@@ -1422,16 +1438,9 @@ select_bound_blocks_kernel(const uint32_t *__restrict__ block_bound, int64_t n_b
     }
     if (n_blocks < R) t1 = 1ull; // fewer blocks than R: no R points are known to reach any bound
     const uint32_t cut = theta > margin ? (uint32_t)(theta - margin) : 0u;
-    for (int64_t b0 = tid; b0 < n_blocks; b0 += (int64_t)8 * nt) {
-        uint32_t v[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) { const int64_t b = b0 + (int64_t)u * nt; v[u] = b < n_blocks ? bb[b] : 0u; }
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int64_t b = b0 + (int64_t)u * nt;
-            if (b < n_blocks && v[u] >= cut) sel_blk[(size_t)q * n_blocks + atomicAdd(&n_sel, 1u)] = (int32_t)b;
-        }
-    }
+    for_every_block([&](int64_t b, uint32_t v) {
+        if (v >= cut) sel_blk[(size_t)q * n_blocks + atomicAdd(&n_sel, 1u)] = (int32_t)b;
+    });
     __syncthreads();
     if (tid == 0) {
         meta[q].t1 = t1;
