@@ -77,6 +77,30 @@ def test_lut_tables_match(case):
         assert scale[qi] == so and bias[qi] == bo
 
 
+@pytest.mark.parametrize("nq", [1, 7, 32, 33])
+def test_lut_tables_match_for_few_queries_and_for_batches(case, nq):
+    # up to 32 queries take the table kernel made for latency, more the one made for throughput; queries with
+    # repeated and zero components make equal table entries (the first minimum and maximum in index order count)
+    idx, _ = make_index(case)
+    rng = np.random.default_rng(77)
+    q = np.resize(case["q"], (nq, case["q"].shape[1])).copy()
+    q[0] = 0.0
+    if nq > 1:
+        q[1] = np.where(rng.random(q.shape[1]) < 0.5, 0.0, -0.0).astype(np.float32)
+    if nq > 2:
+        q[2] = np.round(q[2] * 2.0) / 2.0
+    qd = dev(q)
+    L = idx.debug_lut(qd, avq.LUT_F32).cpu().numpy()
+    Q8, scale, bias = (t.cpu().numpy() for t in idx.debug_lut(qd, avq.LUT_U8))
+    for qi in range(nq):
+        Lo = oracle.lut_f32(q[qi], case["cb"])
+        np.testing.assert_array_equal(L[qi].view(np.uint32), Lo.view(np.uint32))
+        Qo, so, bo = oracle.lut_u8(Lo)
+        np.testing.assert_array_equal(Q8[qi], Qo)
+        assert np.float32(scale[qi]).view(np.uint32) == np.float32(so).view(np.uint32)
+        assert np.float32(bias[qi]).view(np.uint32) == np.float32(bo).view(np.uint32)
+
+
 @pytest.mark.parametrize("nq", [1, 3, None])
 def test_adc_scores_match(case, nq):
     # nq = 1, 3: one query per workgroup; None: the full batch (query-tiled kernels)
