@@ -111,3 +111,37 @@ def test_noalloc_scratch_limit_is_enforced_on_the_host():
     torch.cuda.synchronize()
     np.testing.assert_array_equal(ids.cpu().numpy(), np.tile(np.arange(10, dtype=np.int32), (8, 1)))
     idx.close()
+
+
+@pytest.mark.parametrize("lut_mode", [0, 1])
+def test_noalloc_under_graph_capture_replays_like_eager_calls(lut_mode):
+    # one of the callers the entry point is for: its launches recorded into a HIP graph (no allocation, no
+    # memset nodes), replayed with other work of the program between the replays, every replay against avq_search
+    if not hasattr(torch.cuda, "CUDAGraph"):
+        pytest.skip("this torch has no graph capture")
+    idx, _ = _index(70_001, 100, 50, 4, seed=21)
+    rng = np.random.default_rng(6)
+    q = torch.from_numpy(unit_rows(rng, 6, 100)).cuda()
+    k, R = 10, 100
+    ids = torch.empty((1, k), dtype=torch.int32, device="cuda")
+    sc = torch.empty((1, k), dtype=torch.float32, device="cuda")
+    qbuf = q[0:1].clone()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        for _ in range(3):   # first calls: symbol look-up, kernel attributes -- none of that inside the capture
+            idx.search_noalloc(qbuf, k, R, lut_mode, out=(ids, sc))
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        idx.search_noalloc(qbuf, k, R, lut_mode, out=(ids, sc))
+    for i in range(6):
+        qbuf.copy_(q[i:i + 1])
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got_ids, got_sc = ids.clone(), sc.clone()
+        want_ids, want_sc = idx.search(q[i:i + 1].contiguous(), k, R, lut_mode)   # eager work between the replays
+        torch.cuda.synchronize()
+        assert torch.equal(got_ids, want_ids), i
+        assert torch.equal(got_sc, want_sc), i
+    idx.close()
