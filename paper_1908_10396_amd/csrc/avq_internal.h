@@ -308,7 +308,7 @@ int launch_gather_rows(const float *src, float *dst, const int32_t *row, const u
 // The (query, probed leaf) pairs of a batch regrouped by leaf, for the matrix-core scan (see
 // ScanParams::item_list). ws: group_by_leaf_words(...) 32-bit words of device scratch.
 struct LeafGroups {
-    uint32_t *leaf_cnt, *leaf_off, *item_off, *fill, *n_items, *qlist, *item_list;
+    uint32_t *leaf_cnt, *leaf_off, *item_off, *fill, *n_items, *qlist, *pos, *item_list; // pos[q][Lp]: the pair's place in its leaf's list
     int32_t max_items; // every 32 pairs of a leaf are an item: at most pairs / 32 + n_leaves of them
 };
 inline size_t group_by_leaf_max_items(int nq, int Lp, int n_leaves) { return ((size_t)nq * Lp + 31) / 32 + (size_t)n_leaves; }
@@ -316,9 +316,11 @@ size_t group_by_leaf_words(int nq, int Lp, int n_leaves);
 // prepare (lays out ws, clears the counts) -> launch_leaf_select(..., g.leaf_cnt) -> launch_group_by_leaf
 int group_by_leaf_prepare(int nq, int Lp, int n_leaves, uint32_t *ws, LeafGroups *g, hipStream_t st);
 int launch_group_by_leaf(const int32_t *leaf_ids, int nq, int Lp, int n_leaves, const LeafGroups &g, hipStream_t st);
-// leaf_cnt (optional): incremented once per selected (query, leaf) pair
+// leaf_cnt (optional): incremented once per selected (query, leaf) pair; leaf_pos (optional, [nq][L]): the count before
+// the pair's own increment, i.e. its place among the pairs of that leaf
 int launch_leaf_select(const float *centers_t, int n_leaves, int d, const float *queries, int nq,
-                       int L, int32_t *leaf_ids, float *leaf_ip, hipStream_t st, uint32_t *leaf_cnt = nullptr);
+                       int L, int32_t *leaf_ids, float *leaf_ip, hipStream_t st, uint32_t *leaf_cnt = nullptr,
+                       uint32_t *leaf_pos = nullptr);
 int launch_transpose(const float *in, int rows, int cols, float *out, hipStream_t st);
 
 // ---- layout.hip ------------------------------------------------------------

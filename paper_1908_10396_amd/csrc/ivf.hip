@@ -13,7 +13,8 @@ namespace avq {
 __global__ void __launch_bounds__(1024)
 leaf_select_kernel(const float *__restrict__ centers_t, int n_leaves, int d,
                    const float *__restrict__ queries, int L, int ns,
-                   int32_t *__restrict__ leaf_ids, float *__restrict__ leaf_ip, uint32_t *__restrict__ leaf_cnt)
+                   int32_t *__restrict__ leaf_ids, float *__restrict__ leaf_ip, uint32_t *__restrict__ leaf_cnt,
+                   uint32_t *__restrict__ leaf_pos)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const int C = 64 * ns;
@@ -56,7 +57,10 @@ leaf_select_kernel(const float *__restrict__ centers_t, int n_leaves, int d,
         const u64 key = list[j];
         leaf_ids[(size_t)q * L + j] = key ? key_id(key) : -1;
         leaf_ip[(size_t)q * L + j] = key ? f32_from_ord(key_ord(key)) : -INFINITY;
-        if (leaf_cnt != nullptr && key) atomicAdd(&leaf_cnt[key_id(key)], 1u); // how many queries probe each leaf
+        if (leaf_cnt != nullptr && key) { // how many queries probe each leaf, and this pair's place among them
+            const uint32_t at = atomicAdd(&leaf_cnt[key_id(key)], 1u);
+            if (leaf_pos != nullptr) leaf_pos[(size_t)q * L + j] = at;
+        }
     }
 }
 
@@ -69,7 +73,8 @@ constexpr int kLeafTile = 8;
 
 __global__ void __launch_bounds__(512)
 leaf_select_tile_kernel(const float *__restrict__ centers_t, int n_leaves, int d, const float *__restrict__ queries, int nq,
-                        int L, int32_t *__restrict__ leaf_ids, float *__restrict__ leaf_ip, uint32_t *__restrict__ leaf_cnt)
+                        int L, int32_t *__restrict__ leaf_ids, float *__restrict__ leaf_ip, uint32_t *__restrict__ leaf_cnt,
+                   uint32_t *__restrict__ leaf_pos)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -174,7 +179,10 @@ leaf_select_tile_kernel(const float *__restrict__ centers_t, int n_leaves, int d
             if (rank < L) {
                 leaf_ids[(size_t)q * L + rank] = key_id(k);
                 leaf_ip[(size_t)q * L + rank] = f32_from_ord(key_ord(k));
-                if (leaf_cnt != nullptr) atomicAdd(&leaf_cnt[key_id(k)], 1u);
+                if (leaf_cnt != nullptr) {
+                    const uint32_t at = atomicAdd(&leaf_cnt[key_id(k)], 1u);
+                    if (leaf_pos != nullptr) leaf_pos[(size_t)q * L + rank] = at;
+                }
             }
         }
         for (int j = want + lane; j < L; j += 64) { // fewer leaves than asked for
@@ -186,7 +194,7 @@ leaf_select_tile_kernel(const float *__restrict__ centers_t, int n_leaves, int d
 }
 
 int launch_leaf_select(const float *centers_t, int n_leaves, int d, const float *queries, int nq,
-                       int L, int32_t *leaf_ids, float *leaf_ip, hipStream_t st, uint32_t *leaf_cnt)
+                       int L, int32_t *leaf_ids, float *leaf_ip, hipStream_t st, uint32_t *leaf_cnt, uint32_t *leaf_pos)
 {
     const int ns = (L + 63) / 64;
     if (nq >= 2048) {
@@ -195,7 +203,7 @@ int launch_leaf_select(const float *centers_t, int n_leaves, int d, const float 
             static LdsLimitOnce tile_attr_done;
             AVQ_TRY(set_lds_limit((const void *)leaf_select_tile_kernel, kMaxDynLds, &tile_attr_done));
             hipLaunchKernelGGL(leaf_select_tile_kernel, dim3((nq + kLeafTile - 1) / kLeafTile), dim3(512), lds, st, centers_t, n_leaves,
-                               d, queries, nq, L, leaf_ids, leaf_ip, leaf_cnt);
+                               d, queries, nq, L, leaf_ids, leaf_ip, leaf_cnt, leaf_pos);
             AVQ_HIP(hipGetLastError());
             return AVQ_OK;
         }
@@ -208,7 +216,7 @@ int launch_leaf_select(const float *centers_t, int n_leaves, int d, const float 
     static LdsLimitOnce attr_done;
     AVQ_TRY(set_lds_limit((const void *)leaf_select_kernel, kMaxDynLds, &attr_done));
     hipLaunchKernelGGL(leaf_select_kernel, dim3(nq), dim3(waves * 64), lds, st, centers_t, n_leaves, d,
-                       queries, L, ns, leaf_ids, leaf_ip, leaf_cnt);
+                       queries, L, ns, leaf_ids, leaf_ip, leaf_cnt, leaf_pos);
     AVQ_HIP(hipGetLastError());
     return AVQ_OK;
 }
@@ -255,15 +263,16 @@ group_offsets_kernel(const uint32_t *__restrict__ leaf_cnt, int n_leaves, uint32
 }
 
 __global__ void __launch_bounds__(256)
-group_fill_kernel(const int32_t *__restrict__ leaf_ids, int64_t n_pairs, int Lp, const uint32_t *__restrict__ leaf_off,
-                  uint32_t *__restrict__ fill, uint32_t *__restrict__ qlist)
+group_fill_kernel(const int32_t *__restrict__ leaf_ids, const uint32_t *__restrict__ leaf_pos, int64_t n_pairs, int Lp,
+                  const uint32_t *__restrict__ leaf_off, uint32_t *__restrict__ qlist)
 {
+    // a pair's place in its leaf's list was taken when leaf selection counted it: a plain scatter, no atomics
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n_pairs) return;
     const int32_t leaf = leaf_ids[i];
     if (leaf < 0) return;
     const uint32_t q = (uint32_t)(i / Lp), slot = (uint32_t)(i % Lp);
-    qlist[leaf_off[leaf] + atomicAdd(&fill[leaf], 1u)] = (q << 9) | slot;
+    qlist[leaf_off[leaf] + leaf_pos[i]] = (q << 9) | slot;
 }
 
 __global__ void __launch_bounds__(256)
@@ -278,7 +287,7 @@ group_items_kernel(const uint32_t *__restrict__ leaf_cnt, const uint32_t *__rest
 
 size_t group_by_leaf_words(int nq, int Lp, int n_leaves)
 {
-    return (size_t)4 * n_leaves + 4 + (size_t)nq * Lp + group_by_leaf_max_items(nq, Lp, n_leaves);
+    return (size_t)4 * n_leaves + 4 + (size_t)2 * nq * Lp + group_by_leaf_max_items(nq, Lp, n_leaves);
 }
 
 // Lays the scratch out and clears the pair counts; leaf selection then counts (launch_leaf_select's
@@ -292,7 +301,8 @@ int group_by_leaf_prepare(int nq, int Lp, int n_leaves, uint32_t *ws, LeafGroups
     g->fill = g->item_off + n_leaves;
     g->n_items = g->fill + n_leaves;
     g->qlist = g->n_items + 4;
-    g->item_list = g->qlist + (size_t)nq * Lp;
+    g->pos = g->qlist + (size_t)nq * Lp;
+    g->item_list = g->pos + (size_t)nq * Lp;
     g->max_items = (int32_t)group_by_leaf_max_items(nq, Lp, n_leaves);
     AVQ_HIP(hipMemsetAsync(g->leaf_cnt, 0, sizeof(uint32_t) * (size_t)n_leaves, st));
     return AVQ_OK;
@@ -303,8 +313,8 @@ int launch_group_by_leaf(const int32_t *leaf_ids, int nq, int Lp, int n_leaves, 
     const int64_t n_pairs = (int64_t)nq * Lp;
     hipLaunchKernelGGL(group_offsets_kernel, dim3(1), dim3(1024), 0, st, g.leaf_cnt, n_leaves, g.leaf_off, g.item_off, g.fill,
                        g.n_items);
-    hipLaunchKernelGGL(group_fill_kernel, dim3((unsigned)((n_pairs + 255) / 256)), dim3(256), 0, st, leaf_ids, n_pairs, Lp, g.leaf_off,
-                       g.fill, g.qlist);
+    hipLaunchKernelGGL(group_fill_kernel, dim3((unsigned)((n_pairs + 255) / 256)), dim3(256), 0, st, leaf_ids, g.pos, n_pairs, Lp,
+                       g.leaf_off, g.qlist);
     hipLaunchKernelGGL(group_items_kernel, dim3((n_leaves + 255) / 256), dim3(256), 0, st, g.leaf_cnt, g.item_off, n_leaves,
                        g.item_list);
     AVQ_HIP(hipGetLastError());
