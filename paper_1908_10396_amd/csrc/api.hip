@@ -1072,6 +1072,103 @@ static int check_search_args(const avq_index *idx, const float *queries, int32_t
     return AVQ_OK;
 }
 
+// ---- a handful of queries on a partitioned index -------------------------------------------
+// Leaf selection, exact block maxima over the blocks of the probed leaves, selection of the R best blocks, the
+// points of those at or above the R-th best maximum, final selection with exact re-scoring: the first design of the
+// flat small-batch path, run on the few hundred blocks a query probes. Up to this many queries (measured crossover
+// with the one-query-per-workgroup scan over leaves, which keeps sorted lists per wave: between 64 and 96 queries at
+// 100 of 2,000 leaves).
+constexpr int kLeafSmallMaxQueries = 80;
+static bool use_leaf_small(const avq_index *idx, int nq, int L)
+{
+    const int max_q = idx->tune_small_batch >= 0 ? std::min(idx->tune_small_batch, 4096) : kLeafSmallMaxQueries;
+    return idx->cfg.n_leaves > 0 && idx->tune_small_impl != 1 && nq <= max_q && L <= 512 &&
+           leaf_small_supported(idx->NB, idx->cfg.bits);
+}
+
+static int search_leaves_small(avq_index *idx, const float *queries, int nq, int k, int reorder_k, int R, int L, bool u8,
+                               int32_t *ids_out, float *scores_out, hipStream_t st)
+{
+    const avq_config &c = idx->cfg;
+    const int ns = (R + 63) / 64;
+    // a few queries: every workgroup computes the short fp32 tables itself (one launch less); more: the table kernel
+    const bool fuse_tables = nq <= 4 && small_batch_can_fuse_tables(c.bits, c.M, c.d, u8);
+    const int64_t stride = std::min<int64_t>(idx->n_blocks, (int64_t)L * std::max<int64_t>(1, idx->max_leaf_blocks));
+    // scratch, 256-byte aligned pieces of idx->tmp
+    size_t off = 0;
+    auto take = [&](size_t bytes) -> size_t { const size_t at = (off + 255) & ~(size_t)255; off = at + bytes; return at; };
+    const size_t entries = (size_t)nq * c.M * idx->kc;
+    const size_t o_lut = take(entries * sizeof(float)), o_lut8 = take(entries), o_scale = take(sizeof(float) * (size_t)nq),
+                 o_bias = take(sizeof(float) * (size_t)nq), o_best = take(sizeof(u64) * (size_t)nq * stride),
+                 o_blk = take(sizeof(int32_t) * (size_t)nq * stride), o_ip = take(sizeof(float) * (size_t)nq * stride),
+                 o_n = take(sizeof(uint32_t) * (size_t)nq), o_sel = take(sizeof(int32_t) * (size_t)nq * R),
+                 o_meta = take(sizeof(SmallMeta) * (size_t)nq), o_cand = take(sizeof(u64) * (size_t)nq * 256 * R),
+                 o_keys = take(sizeof(u64) * (size_t)nq * c.n_leaves);
+    AVQ_TRY(idx->tmp.reserve(off));
+    unsigned char *base = (unsigned char *)idx->tmp.p;
+    AVQ_TRY(idx->leaf_ids.reserve(sizeof(int32_t) * (size_t)nq * L));
+    AVQ_TRY(idx->leaf_ip.reserve(sizeof(float) * (size_t)nq * L));
+    {
+        StageTimer t(idx, AVQ_STAGE_LEAF, st);
+        AVQ_TRY(launch_leaf_select_few(idx->centers_t.as<float>(), c.n_leaves, c.d, queries, nq, L, (u64 *)(base + o_keys),
+                                       idx->leaf_ids.as<int32_t>(), idx->leaf_ip.as<float>(), st));
+    }
+    ScanParams p;
+    fill_scan_params(idx, nq, R, ns, &p);
+    p.lut = (float *)(base + o_lut);
+    p.lut8 = base + o_lut8;
+    p.scale = (float *)(base + o_scale);
+    p.bias = (float *)(base + o_bias);
+    if (fuse_tables) {
+        p.fuse_queries = queries;
+        p.fuse_codebooks = idx->codebooks.as<float>();
+        p.fuse_d = c.d;
+    } else {
+        StageTimer t(idx, AVQ_STAGE_LUT, st);
+        AVQ_TRY(launch_lut(queries, nq, idx->codebooks.as<float>(), c.d, c.M, idx->kc, (float *)(base + o_lut),
+                           u8 ? base + o_lut8 : nullptr, (float *)(base + o_scale), (float *)(base + o_bias), st));
+    }
+    p.perm = idx->perm.as<int32_t>();
+    p.leaf_ids = idx->leaf_ids.as<int32_t>();
+    p.leaf_ip = idx->leaf_ip.as<float>();
+    p.leaf_blk = idx->leaf_blk.as<int32_t>();
+    p.Lp = L;
+    LeafSmallBuffers b;
+    b.best = (u64 *)(base + o_best);
+    b.blk = (int32_t *)(base + o_blk);
+    b.ip = (float *)(base + o_ip);
+    b.n_listed = (uint32_t *)(base + o_n);
+    b.stride = stride;
+    FinishParams f;
+    memset(&f, 0, sizeof(f));
+    f.x = idx->x;
+    f.queries = queries;
+    f.d = c.d;
+    f.k = k;
+    f.reorder = reorder_k != 0;
+    f.stage_rows = small_finish_stage_rows(p, c.d, u8);
+    f.cand_stride = (int64_t)256 * R;
+    f.cand = (u64 *)(base + o_cand);
+    f.sel_blk = (int32_t *)(base + o_sel);
+    f.meta = (SmallMeta *)(base + o_meta);
+    f.ids_out = ids_out;
+    f.scores_out = scores_out;
+    {
+        StageTimer t(idx, AVQ_STAGE_SCAN, st);
+        AVQ_TRY(launch_leaf_block_max(p, u8, b, st));
+    }
+    {
+        StageTimer t(idx, AVQ_STAGE_MERGE, st);
+        AVQ_TRY(launch_select_listed_blocks(p, f, b, st));
+    }
+    {
+        StageTimer t(idx, AVQ_STAGE_RESCAN, st);
+        AVQ_TRY(launch_rescan_leaf_blocks(p, f, u8, b, st));
+    }
+    StageTimer t(idx, AVQ_STAGE_FINAL, st);
+    return launch_small_final(p, f, false, st); // keys carry fp32 scores with either kind of table
+}
+
 extern "C" int avq_search(avq_index *idx, const float *queries, int32_t nq, int32_t k, int32_t reorder_k,
                           int32_t lut_mode, int32_t leaves_to_search, int32_t *ids_out, float *scores_out,
                           void *hip_stream)
@@ -1093,6 +1190,8 @@ extern "C" int avq_search(avq_index *idx, const float *queries, int32_t nq, int3
     const bool fuse_tables = small && idx->tune_small_impl != 1 && small_batch_can_fuse_tables(c.bits, c.M, c.d, u8);
     const bool prefilter = !small && use_prefilter(idx, nq, lut_mode, R);
     const bool grouped = ivf && use_grouped_leaves(idx, nq, leaves_to_search, R);
+    if (ivf && use_leaf_small(idx, nq, leaves_to_search))
+        return search_leaves_small(idx, queries, nq, k, reorder_k, R, leaves_to_search, u8, ids_out, scores_out, st);
     if (small && idx->tune_small_impl != 1) {
         SmallWs w;
         AVQ_TRY(small_ws_from_index(idx, nq, R, &w));

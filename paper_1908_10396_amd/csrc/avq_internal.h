@@ -223,6 +223,21 @@ int launch_select_bound_blocks(const ScanParams &p, const FinishParams &f, bool 
 int launch_rescan_listed(const ScanParams &p, const FinishParams &f, bool u8, hipStream_t st);
 int launch_small_select(const ScanParams &p, const FinishParams &f, hipStream_t st);
 int launch_small_rescan(const ScanParams &p, const FinishParams &f, bool u8, hipStream_t st);
+// A handful of queries on a partitioned index (4-bit codes, specialised code sizes): exact block maxima over the
+// blocks of the probed leaves (p.leaf_ids / leaf_ip / leaf_blk / perm, p.Lp leaves per query), listed per query in
+// probe order; selection of the R blocks with the largest maxima (positions in the list to f.sel_blk[q][R], f.meta);
+// the points of those at or above t1 to f.cand. launch_small_final finishes (keys carry fp32 scores and point ids).
+struct LeafSmallBuffers {
+    u64 *best;          // [B][stride]
+    int32_t *blk;       // [B][stride]
+    float *ip;          // [B][stride]
+    uint32_t *n_listed; // [B]
+    int64_t stride;     // at least the blocks of any query's probed leaves
+};
+bool leaf_small_supported(int NB, int bits);
+int launch_leaf_block_max(const ScanParams &p, bool u8, const LeafSmallBuffers &b, hipStream_t st);
+int launch_select_listed_blocks(const ScanParams &p, const FinishParams &f, const LeafSmallBuffers &b, hipStream_t st);
+int launch_rescan_leaf_blocks(const ScanParams &p, const FinishParams &f, bool u8, const LeafSmallBuffers &b, hipStream_t st);
 int launch_small_final(const ScanParams &p, const FinishParams &f, bool u8, hipStream_t st);
 
 // ---- select.hip ------------------------------------------------------------
@@ -316,6 +331,10 @@ size_t group_by_leaf_words(int nq, int Lp, int n_leaves);
 // prepare (lays out ws, clears the counts) -> launch_leaf_select(..., g.leaf_cnt) -> launch_group_by_leaf
 int group_by_leaf_prepare(int nq, int Lp, int n_leaves, uint32_t *ws, LeafGroups *g, hipStream_t st);
 int launch_group_by_leaf(const int32_t *leaf_ids, int nq, int Lp, int n_leaves, const LeafGroups &g, hipStream_t st);
+// The same selection for a handful of queries (L <= 512): scores by many small workgroups into keys[nq][n_leaves]
+// (scratch), then the L best per query.
+int launch_leaf_select_few(const float *centers_t, int n_leaves, int d, const float *queries, int nq, int L, u64 *keys,
+                           int32_t *leaf_ids, float *leaf_ip, hipStream_t st);
 // leaf_cnt (optional): incremented once per selected (query, leaf) pair; leaf_pos (optional, [nq][L]): the count before
 // the pair's own increment, i.e. its place among the pairs of that leaf
 int launch_leaf_select(const float *centers_t, int n_leaves, int d, const float *queries, int nq,

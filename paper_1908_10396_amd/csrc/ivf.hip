@@ -4,6 +4,7 @@
 // visits the leaves whose centers have the largest inner product with it).
 #include "avq_internal.h"
 #include "wave_topk.h"
+#include "wg_select.h"
 
 namespace avq {
 
@@ -191,6 +192,77 @@ leaf_select_tile_kernel(const float *__restrict__ centers_t, int n_leaves, int d
         }
         wave_lds_fence();
     }
+}
+
+// Leaf selection for a handful of queries, where the kernel above is all load latency in one workgroup: first every
+// leaf's score by a thread of its own, spread over many small workgroups (the same fma chain in index order, 25 loads
+// in flight), as keys (score, then lower leaf id) in keys[q][n_leaves]; then one workgroup per query finds the L-th
+// largest key, gathers the keys at or above it and ranks them by counting.
+__global__ void __launch_bounds__(64)
+leaf_scores_kernel(const float *__restrict__ centers_t, int n_leaves, int d, const float *__restrict__ queries,
+                   u64 *__restrict__ keys)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    float *qs = (float *)smem;
+    const int q = blockIdx.y;
+    for (int l = threadIdx.x; l < d; l += 64) qs[l] = queries[(size_t)q * d + l];
+    __syncthreads();
+    const int leaf = blockIdx.x * 64 + threadIdx.x;
+    if (leaf >= n_leaves) return;
+    const float *col = centers_t + leaf;
+    float s = 0.0f;
+#pragma unroll 25
+    for (int l = 0; l < d; ++l) s = __fmaf_rn(qs[l], col[(size_t)l * n_leaves], s);
+    keys[(size_t)q * n_leaves + leaf] = make_key(ord_from_f32(s), leaf);
+}
+
+__global__ void __launch_bounds__(1024)
+leaf_top_kernel(const u64 *__restrict__ keys, int n_leaves, int L, int32_t *__restrict__ leaf_ids, float *__restrict__ leaf_ip)
+{
+    __shared__ WgSelectScratch sel;
+    __shared__ u64 top[512];
+    __shared__ uint32_t n_top;
+    const int tid = threadIdx.x, q = blockIdx.x;
+    const u64 *row = keys + (size_t)q * n_leaves;
+    if (tid == 0) n_top = 0u;
+    const u64 t = wg_select_threshold(row, n_leaves, L, &sel);
+    __syncthreads();
+    for (int i = tid; i < n_leaves; i += 1024) {
+        const u64 key = row[i];
+        if (key >= t && key) {
+            const uint32_t at = atomicAdd(&n_top, 1u);
+            if (at < 512u) top[at] = key;
+        }
+    }
+    __syncthreads();
+    const int n = (int)(n_top < 512u ? n_top : 512u); // min(L, leaves)
+    for (int i = tid; i < n; i += 1024) {
+        const u64 mine = top[i];
+        int rank = 0;
+        for (int j = 0; j < n; ++j) rank += top[j] > mine;
+        if (rank < L) {
+            leaf_ids[(size_t)q * L + rank] = key_id(mine);
+            leaf_ip[(size_t)q * L + rank] = f32_from_ord(key_ord(mine));
+        }
+    }
+    for (int i = n + tid; i < L; i += 1024) { // fewer leaves than asked for
+        leaf_ids[(size_t)q * L + i] = -1;
+        leaf_ip[(size_t)q * L + i] = -INFINITY;
+    }
+}
+
+int launch_leaf_select_few(const float *centers_t, int n_leaves, int d, const float *queries, int nq, int L, u64 *keys,
+                           int32_t *leaf_ids, float *leaf_ip, hipStream_t st)
+{
+    if (L < 1 || L > 512 || nq < 1 || n_leaves < 1 || (size_t)d * 4 > 60 * 1024 || !keys) {
+        set_error("leaf select: bad arguments (L = %d)", L);
+        return AVQ_EINVAL;
+    }
+    hipLaunchKernelGGL(leaf_scores_kernel, dim3((n_leaves + 63) / 64, nq), dim3(64), (size_t)d * 4, st, centers_t, n_leaves, d,
+                       queries, keys);
+    hipLaunchKernelGGL(leaf_top_kernel, dim3(nq), dim3(1024), 0, st, keys, n_leaves, L, leaf_ids, leaf_ip);
+    AVQ_HIP(hipGetLastError());
+    return AVQ_OK;
 }
 
 int launch_leaf_select(const float *centers_t, int n_leaves, int d, const float *queries, int nq,

@@ -948,6 +948,179 @@ rescan_blocks_kernel(const ScanParams p, const FinishParams f)
     }
 }
 
+// ---- a handful of queries on a partitioned index: block maxima over the probed leaves ----
+//
+// A query's probed leaves hold a few hundred blocks, so the scheme of the first paragraph above runs on all of
+// them with exact scores: D. leaf_block_max_kernel (one workgroup per probed leaf and query) scores the leaf's blocks
+// and records, for the i-th block of the query's probe list (leaves in probe order, their blocks in order), the
+// best key, the block and the leaf's <q, center>; A. select_blocks_kernel finds t1 and the R blocks that reach it;
+// E. rescan_leaf_blocks_kernel scores those again and keeps the points at or above t1 (at most 256 R);
+// C. small_batch_final_kernel finishes. A point's score is what the one-query scan over leaves forms: the fp32
+// table sum (entries of a byte first, bytes in order) + <q, center>, or fma(integer sum, scale, bias + <q, center>);
+// its key carries the point's id (perm), padding slots have none.
+struct LeafBlockList {
+    u64 *best;           // [B][stride] best key of the listed block, 0: no point
+    int32_t *blk;        // [B][stride] the block
+    float *ip;           // [B][stride] its leaf's <q, center>
+    uint32_t *n_listed;  // [B] blocks in the query's list
+    int64_t stride;
+};
+
+template <bool U8>
+__device__ __forceinline__ float leaf_point_score(float accf, uint32_t acci, float ip, float scale, float bias)
+{
+    if (U8) return __fmaf_rn((float)(int)acci, scale, __fadd_rn(bias, ip));
+    return __fadd_rn(accf, ip);
+}
+
+template <bool U8, int NBT>
+__global__ void __launch_bounds__(256)
+leaf_block_max_kernel(const ScanParams p, const LeafBlockList list)
+{
+    static_assert(NBT != 0, "specialised code sizes only");
+    __shared__ __align__(16) unsigned char tables[2 * NBT * 16 * (U8 ? 1 : 4)];
+    __shared__ int red_before[4], red_total[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int j = blockIdx.x, q = blockIdx.y;
+    const int stride_l = p.leaf_stride ? p.leaf_stride : p.Lp;
+    const int32_t *lids = p.leaf_ids + (size_t)q * stride_l;
+    // blocks of the leaves before this one in the probe list, and of all of them
+    int before = 0, total = 0;
+    for (int t = tid; t < p.Lp; t += 256) {
+        const int32_t l = lids[t];
+        const int nb = l >= 0 ? p.leaf_blk[l + 1] - p.leaf_blk[l] : 0;
+        total += nb;
+        if (t < j) before += nb;
+    }
+#pragma unroll
+    for (int m = 32; m > 0; m >>= 1) { before += __shfl_xor(before, m, 64); total += __shfl_xor(total, m, 64); }
+    if (lane == 0) { red_before[wave] = before; red_total[wave] = total; }
+    const int32_t leaf = lids[j];
+    const int64_t b0 = leaf >= 0 ? p.leaf_blk[leaf] : 0, b1 = leaf >= 0 ? p.leaf_blk[leaf + 1] : 0;
+    BlockRegs<NBT> regs;
+    int64_t blk = b0 + wave;
+    if (blk < b1) load_block<NBT>(regs, p.codes, blk, lane); // in flight while the tables are filled
+    nibble_tables_fill<U8>(tables, p, q, NBT);
+    __syncthreads();
+    before = red_before[0] + red_before[1] + red_before[2] + red_before[3];
+    total = red_total[0] + red_total[1] + red_total[2] + red_total[3];
+    if (j == 0 && tid == 0) list.n_listed[q] = (uint32_t)((int64_t)total < list.stride ? total : list.stride);
+    const float ip = leaf >= 0 ? p.leaf_ip[(size_t)q * stride_l + j] : 0.0f;
+    const float scale = U8 ? p.scale[q] : 0.0f, bias = U8 ? p.bias[q] : 0.0f;
+    for (; blk < b1; blk += 4) {
+        float accf[4];
+        uint32_t acci[4];
+        nibble_accumulate<U8, NBT>(tables, regs, p.codes + (size_t)blk * 256 * NBT, NBT, lane, accf, acci);
+        const int64_t next = blk + 4;
+        if (next < b1) load_block<NBT>(regs, p.codes, next, lane);
+        u64 best = 0ull;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int32_t id = p.perm[blk * 256 + 4 * lane + i];
+            const float sc = leaf_point_score<U8>(accf[i], acci[i], ip, scale, bias);
+            const u64 key = id >= 0 ? make_key(ord_from_f32(sc), id) : 0ull;
+            best = key > best ? key : best;
+        }
+#pragma unroll
+        for (int m = 32; m > 0; m >>= 1) best = umax64(best, shfl_xor_u64(best, m));
+        const int64_t at = (int64_t)before + (blk - b0);
+        if (lane == 0 && at < list.stride) {
+            list.best[(size_t)q * list.stride + at] = best;
+            list.blk[(size_t)q * list.stride + at] = (int32_t)blk;
+            list.ip[(size_t)q * list.stride + at] = ip;
+        }
+    }
+}
+
+// A. for lists of different lengths: one workgroup per query over best[q][0 .. n_listed[q]); sel_blk[q][R] receives
+// positions in the list.
+__global__ void __launch_bounds__(1024)
+select_listed_blocks_kernel(const LeafBlockList list, int R, int32_t *__restrict__ sel_blk, SmallMeta *__restrict__ meta)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    WgSelectScratch *sel = (WgSelectScratch *)smem;
+    __shared__ uint32_t n_sel;
+    const int tid = threadIdx.x, nt = blockDim.x;
+    const int q = blockIdx.x;
+    const u64 *bm = list.best + (size_t)q * list.stride;
+    const int64_t n = (int64_t)list.n_listed[q];
+    if (tid == 0) n_sel = 0u;
+    if (n <= (int64_t)kSelList && nt == 1024) {
+        // the usual case, a few hundred blocks: a thread per block ranks its key by counting (keys are distinct)
+        __shared__ u64 t1_s;
+        const u64 mine = tid < n ? bm[tid] : 0ull;
+        sel->list[tid] = mine;
+        if (tid == 0) t1_s = 1ull; // fewer than R blocks with a point: all of them
+        __syncthreads();
+        int rank = 0;
+        for (int i = 0; i < (int)n; ++i) rank += sel->list[i] > mine;
+        if (mine && rank < R) sel_blk[(size_t)q * R + atomicAdd(&n_sel, 1u)] = tid;
+        if (mine && rank == R - 1) t1_s = mine;
+        __syncthreads();
+        if (tid == 0) {
+            meta[q].t1 = t1_s;
+            meta[q].n_sel = n_sel;
+            meta[q].n_cand = 0u;
+        }
+        return;
+    }
+    const u64 t1 = wg_select_threshold(bm, n, R, sel);
+    __syncthreads();
+    for (int64_t b = tid; b < n; b += nt) {
+        const u64 key = bm[b];
+        if (key >= t1 && key) sel_blk[(size_t)q * R + atomicAdd(&n_sel, 1u)] = (int32_t)b;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        meta[q].t1 = t1;
+        meta[q].n_sel = n_sel;
+        meta[q].n_cand = 0u;
+    }
+}
+
+// E. one wave per selected block: its points at or above t1 go to the query's candidates.
+template <bool U8, int NBT>
+__global__ void __launch_bounds__(256)
+rescan_leaf_blocks_kernel(const ScanParams p, const FinishParams f, const LeafBlockList list)
+{
+    static_assert(NBT != 0, "specialised code sizes only");
+    __shared__ __align__(16) unsigned char tables[2 * NBT * 16 * (U8 ? 1 : 4)];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n_waves = blockDim.x >> 6;
+    const int q = blockIdx.y;
+    const int j = blockIdx.x * n_waves + wave;
+    const int n_sel = (int)f.meta[q].n_sel;
+    if ((int)(blockIdx.x * n_waves) >= n_sel) return; // whole workgroup idle
+    const bool have = j < n_sel;
+    const int at = have ? f.sel_blk[(size_t)q * p.R + j] : 0;
+    const int64_t blk = have ? list.blk[(size_t)q * list.stride + at] : 0;
+    BlockRegs<NBT> regs;
+    if (have) load_block<NBT>(regs, p.codes, blk, lane);
+    nibble_tables_fill<U8>(tables, p, q, NBT);
+    __syncthreads();
+    if (!have) return;
+    const float ip = list.ip[(size_t)q * list.stride + at];
+    const float scale = U8 ? p.scale[q] : 0.0f, bias = U8 ? p.bias[q] : 0.0f;
+    float accf[4];
+    uint32_t acci[4];
+    nibble_accumulate<U8, NBT>(tables, regs, p.codes + (size_t)blk * 256 * NBT, NBT, lane, accf, acci);
+    const u64 t1 = f.meta[q].t1;
+    u64 *cand = f.cand + (size_t)q * f.cand_stride;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int32_t id = p.perm[blk * 256 + 4 * lane + i];
+        const float sc = leaf_point_score<U8>(accf[i], acci[i], ip, scale, bias);
+        const u64 key = id >= 0 ? make_key(ord_from_f32(sc), id) : 0ull;
+        const bool hit = key >= t1 && key != 0ull;
+        const u64 mask = __builtin_amdgcn_ballot_w64(hit);
+        if (mask == 0ull) continue;
+        uint32_t base_pos = 0;
+        if (lane == 0) base_pos = atomicAdd(&f.meta[q].n_cand, (uint32_t)__builtin_popcountll(mask));
+        base_pos = (uint32_t)__shfl((int)base_pos, 0, 64);
+        const u64 pos = (u64)base_pos + (u64)__builtin_popcountll(mask & ((1ull << lane) - 1ull));
+        if (hit && pos < (u64)f.cand_stride) cand[pos] = key;
+    }
+}
+
 // ---- a handful of queries: block bounds from 8-bit tables, then exact scores of few blocks ----
 //
 // The full scan of a single query is bound by reading the codes only if a point's score costs
@@ -2089,6 +2262,68 @@ int launch_small_rescan(const ScanParams &p, const FinishParams &f, bool u8, hip
         return AVQ_EINVAL;
     }
     return u8 ? launch_rescan_u<true>(p, f, st) : launch_rescan_u<false>(p, f, st);
+}
+
+bool leaf_small_supported(int NB, int bits)
+{
+    return bits == 4 && (NB == 8 || NB == 13 || NB == 25 || NB == 32);
+}
+
+template <bool U8>
+static int launch_leaf_small_u(const ScanParams &p, const FinishParams &f, const LeafBlockList &list, bool rescan, hipStream_t st)
+{
+    const dim3 grid = rescan ? dim3((unsigned)((p.R + 3) / 4), p.B) : dim3((unsigned)p.Lp, p.B);
+#define AVQ_LEAF_SMALL(N)                                                                                          \
+    case N:                                                                                                        \
+        if (rescan) hipLaunchKernelGGL((rescan_leaf_blocks_kernel<U8, N>), grid, dim3(256), 0, st, p, f, list);    \
+        else hipLaunchKernelGGL((leaf_block_max_kernel<U8, N>), grid, dim3(256), 0, st, p, list);                  \
+        break;
+    switch (p.NB) {
+        AVQ_LEAF_SMALL(8)
+        AVQ_LEAF_SMALL(13)
+        AVQ_LEAF_SMALL(25)
+        AVQ_LEAF_SMALL(32)
+    default: set_error("leaf block maxima: unsupported code size %d", p.NB); return AVQ_EINVAL;
+    }
+#undef AVQ_LEAF_SMALL
+    AVQ_HIP(hipGetLastError());
+    return AVQ_OK;
+}
+
+static int check_leaf_small(const ScanParams &p, const LeafSmallBuffers &b)
+{
+    if (!leaf_small_supported(p.NB, p.bits) || !p.perm || !p.leaf_ids || !p.leaf_ip || !p.leaf_blk || p.Lp < 1 || p.B < 1 ||
+        p.R < 1 || !b.best || !b.blk || !b.ip || !b.n_listed || b.stride < 1) {
+        set_error("leaf block maxima: bad arguments");
+        return AVQ_EINVAL;
+    }
+    return AVQ_OK;
+}
+
+int launch_leaf_block_max(const ScanParams &p, bool u8, const LeafSmallBuffers &b, hipStream_t st)
+{
+    AVQ_TRY(check_leaf_small(p, b));
+    const LeafBlockList list{b.best, b.blk, b.ip, b.n_listed, b.stride};
+    const FinishParams f{};
+    return u8 ? launch_leaf_small_u<true>(p, f, list, false, st) : launch_leaf_small_u<false>(p, f, list, false, st);
+}
+
+int launch_select_listed_blocks(const ScanParams &p, const FinishParams &f, const LeafSmallBuffers &b, hipStream_t st)
+{
+    AVQ_TRY(check_leaf_small(p, b));
+    static LdsLimitOnce attr;
+    AVQ_TRY(set_max_lds(select_listed_blocks_kernel, &attr));
+    const LeafBlockList list{b.best, b.blk, b.ip, b.n_listed, b.stride};
+    hipLaunchKernelGGL(select_listed_blocks_kernel, dim3(p.B), dim3(1024), sizeof(WgSelectScratch), st, list, p.R, f.sel_blk, f.meta);
+    AVQ_HIP(hipGetLastError());
+    return AVQ_OK;
+}
+
+int launch_rescan_leaf_blocks(const ScanParams &p, const FinishParams &f, bool u8, const LeafSmallBuffers &b, hipStream_t st)
+{
+    AVQ_TRY(check_leaf_small(p, b));
+    const LeafBlockList list{b.best, b.blk, b.ip, b.n_listed, b.stride};
+    return u8 ? launch_leaf_small_u<true>(p, f, list, true, st) : launch_leaf_small_u<false>(p, f, list, true, st);
 }
 
 int launch_small_final(const ScanParams &p, const FinishParams &f, bool u8, hipStream_t st)

@@ -522,6 +522,29 @@ def test_partitioned_search_matches(ivf_case, lut_mode, k, R, L):
     np.testing.assert_array_equal(sc.cpu().numpy(), os_)
 
 
+@pytest.mark.parametrize("lut_mode", [0, 1])
+@pytest.mark.parametrize("nq", [1, 3, 16, 17])
+def test_partitioned_search_of_a_few_queries_matches(ivf_case, lut_mode, nq):
+    # up to 16 queries: exact block maxima over the blocks of the probed leaves, the R best blocks scored again
+    # (17: the scan with one workgroup per query); probing every leaf, one leaf, and fewer blocks than R
+    c = ivf_case
+    idx, xd = make_ivf_index(c)
+    q = c["q"][:nq]
+    qd = dev(q)
+    for k, R, L in ((10, 100, 5), (10, 0, 5), (20, 60, 37), (10, 100, 1), (64, 512, 3), (1, 1, 37)):
+        ids, sc = idx.search(qd, k, R, lut_mode, leaves_to_search=L)
+        oi, os_ = oracle.search(c["x"], c["cb"], c["codes"], c["bits"], q, k, R, lut_mode,
+                                centers=c["centers"], assign=c["assign"], leaves_to_search=L)
+        np.testing.assert_array_equal(ids.cpu().numpy(), oi, err_msg="k=%d R=%d L=%d" % (k, R, L))
+        np.testing.assert_array_equal(sc.cpu().numpy(), os_, err_msg="k=%d R=%d L=%d" % (k, R, L))
+    idx.set_tuning("small_batch_impl", 1)   # the same through the scan with one workgroup per query
+    ids, sc = idx.search(qd, 10, 100, lut_mode, leaves_to_search=5)
+    oi, os_ = oracle.search(c["x"], c["cb"], c["codes"], c["bits"], q, 10, 100, lut_mode,
+                            centers=c["centers"], assign=c["assign"], leaves_to_search=5)
+    np.testing.assert_array_equal(ids.cpu().numpy(), oi)
+    np.testing.assert_array_equal(sc.cpu().numpy(), os_)
+
+
 @pytest.fixture(scope="module")
 def ivf_batch_case():
     # enough queries and probed leaves for the search that regroups the (query, leaf) pairs by leaf
