@@ -192,7 +192,11 @@ int avq_update_leaf_centers(avq_index *idx, const float *x, int64_t n, int32_t m
  *    bounded, and records the largest sum of every block of 256 points; the blocks
  *    whose largest sum is within that bound of the R-th largest block maximum are
  *    scored exactly (same order of additions), and the points at or above the lower
- *    bound of the R-th best score are ranked. Same results, whatever the data;
+ *    bound of the R-th best score are ranked. Up to 80 queries on a partitioned
+ *    index of 4-bit codes (same code sizes) score the blocks of their probed leaves
+ *    exactly, keep every block's best key, and score the R blocks with the largest
+ *    of those again for the points at or above the R-th largest. Same results,
+ *    whatever the data;
  *  re-score those exactly, <q, x_i> as an fp32 fma chain in index order, and
  *    return the k best in the same order.
  * reorder_k == 0: no re-scoring; the k best ADC candidates are returned with
@@ -315,11 +319,13 @@ double avq_eta(int32_t d, double T, double norm, int32_t eta_mode);
  * the most workgroups per query of the block-maxima scan), "scan_waves"
  * (waves per scan workgroup), "scan_qt" (queries per tile), "small_batch_max"
  * (v > 0: batches of fewer than v queries on a flat index take the block-maxima
- * path; 1 disables that path; built in: 36 with 4-bit codes, 9 with 8-bit codes), "small_batch_impl" (0: built in: where
+ * path; 1 disables that path; built in: 36 with 4-bit codes, 9 with 8-bit codes; on a partitioned index: fewer than v
+ * queries take the block maxima of their probed leaves; built in: 81), "small_batch_impl" (0: built in: where
  * the code size has the kernels for it (8, 13, 25 or 32 code bytes per point) the full scan records, per block
  * of 256 points, the largest sum of 8-bit images of the table entries -- a bound of the block's scores -- and
  * only the blocks whose bound can reach the R-th best score are scored exactly; 2: the full scan always records
- * exact block maxima; 1: that algorithm as three separate kernels), "scan_mfma"
+ * exact block maxima; 1: that algorithm as three separate kernels, and on a partitioned index the scan with one
+ * workgroup per query whatever the batch size), "scan_mfma"
  * (1: batches with 8-bit tables on 4-bit codes use the LDS-table scan instead
  * of the matrix-core scan; for that scan "scan_target_wgs" counts waves),
  * "scan_prefilter" (1: batches with fp32 tables on a flat index of 4-bit codes
