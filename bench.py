@@ -371,7 +371,8 @@ def main():
     code_bytes = float(nb) * scanned             # algorithmic bytes of one single-query scan
     bound_scan = not n_leaves and nb in SPECIAL_NB
     if n_leaves:
-        b1_kernel = "adc_scan_kernel<1,false,%d,1>" % nb
+        # up to 80 queries on a partitioned index of these code sizes: exact block maxima over the probed leaves
+        b1_kernel = ("leaf_block_max_kernel<false,%d>" % nb) if (bits == 4 and nb in SPECIAL_NB) else "adc_scan_kernel<1,false,%d,1>" % nb
         scan1_us = stage1_us["scan"]
         timing = "HIP event pair around the scan stage of every call (includes the pair's own cost)"
         parts = None
