@@ -591,17 +591,22 @@ def test_partitioned_batches_grouped_by_leaf(ivf_batch_case, lut_mode, variant):
         assert idx.debug_unverified_queries() >= 65
 
 
-def test_partitioned_search_pads_when_leaves_are_small():
-    # more results asked for than the probed leaves hold: padded with id -1, score -inf
-    c = make_ivf_case(32, 400, 16, 8, 4, 7, 40)
+@pytest.mark.parametrize("d,M", [(16, 8), (32, 16)])
+@pytest.mark.parametrize("lut_mode", [0, 1])
+def test_partitioned_search_pads_when_leaves_are_small(d, M, lut_mode):
+    # more results asked for than the probed leaves hold: padded with id -1, score -inf (4 code bytes per point: the
+    # scan with lists; 8: the block maxima of the probed leaves, with empty leaves among the 40)
+    c = make_ivf_case(32, 400, d, M, 4, 7, 40)
     idx, xd = make_ivf_index(c)
     qd = dev(c["q"])
-    ids, sc = idx.search(qd, 60, 100, 0, leaves_to_search=2)
-    oi, os_ = oracle.search(c["x"], c["cb"], c["codes"], 4, c["q"], 60, 100, 0, centers=c["centers"],
-                            assign=c["assign"], leaves_to_search=2)
-    assert (oi == -1).any()
-    np.testing.assert_array_equal(ids.cpu().numpy(), oi)
-    np.testing.assert_array_equal(sc.cpu().numpy(), os_)
+    for k, R, L in ((60, 100, 2), (5, 0, 1), (60, 60, 3)):
+        ids, sc = idx.search(qd, k, R, lut_mode, leaves_to_search=L)
+        oi, os_ = oracle.search(c["x"], c["cb"], c["codes"], 4, c["q"], k, R, lut_mode, centers=c["centers"],
+                                assign=c["assign"], leaves_to_search=L)
+        np.testing.assert_array_equal(ids.cpu().numpy(), oi)
+        np.testing.assert_array_equal(sc.cpu().numpy(), os_)
+        if k == 60 and L == 2:
+            assert (oi == -1).any()
 
 
 def test_partitioned_train_and_encode(ivf_case):
