@@ -142,3 +142,12 @@ def test_full_partitioned_batch_matches_oracle_on_sampled_queries(lut_mode):
     ids2, sc2 = idx.search(qd, k, R, lut_mode, leaves_to_search=L)
     np.testing.assert_array_equal(ids2.cpu().numpy(), ids)
     np.testing.assert_array_equal(sc2.cpu().numpy(), sc)
+    idx.set_tuning("scan_prefilter", 0)
+    # single queries and a batch of 16 (block maxima over the ~290 blocks of the probed leaves) give the batch's rows
+    for qi in sample[:4]:
+        i1, s1 = idx.search(qd[qi:qi + 1], k, R, lut_mode, leaves_to_search=L)
+        np.testing.assert_array_equal(i1.cpu().numpy()[0], ids[qi])
+        np.testing.assert_array_equal(s1.cpu().numpy()[0], sc[qi])
+    i16, s16 = idx.search(qd[4090:4106], k, R, lut_mode, leaves_to_search=L)
+    np.testing.assert_array_equal(i16.cpu().numpy(), ids[4090:4106])
+    np.testing.assert_array_equal(s16.cpu().numpy(), sc[4090:4106])
