@@ -591,6 +591,37 @@ def test_partitioned_batches_grouped_by_leaf(ivf_batch_case, lut_mode, variant):
         assert idx.debug_unverified_queries() >= 65
 
 
+@pytest.fixture(scope="module", params=[(100, 25), (128, 64)], ids=["nb13", "nb32"])
+def ivf_other_size_case(request):
+    d, M = request.param
+    return make_ivf_case(35, 12_345, d, M, 4, 140, 40)
+
+
+@pytest.mark.parametrize("lut_mode", [0, 1])
+def test_partitioned_search_at_other_code_sizes(ivf_other_size_case, lut_mode):
+    # 13 and 32 code bytes per point (the cases above hold 25 and 8): a few queries (block maxima of the probed
+    # leaves), the one-query-per-workgroup scan, and a batch regrouped by leaf
+    c = ivf_other_size_case
+    idx, xd = make_ivf_index(c)
+    idx.set_tuning("group_min_pairs", 1)
+    for nq in (2, 40, 140):
+        q = c["q"][:nq]
+        qd = dev(q)
+        for k, R, L in ((10, 100, 16), (10, 0, 40), (30, 300, 7)):
+            ids, sc = idx.search(qd, k, R, lut_mode, leaves_to_search=L)
+            oi, os_ = oracle.search(c["x"], c["cb"], c["codes"], c["bits"], q, k, R, lut_mode,
+                                    centers=c["centers"], assign=c["assign"], leaves_to_search=L)
+            np.testing.assert_array_equal(ids.cpu().numpy(), oi, err_msg="nq=%d k=%d R=%d L=%d" % (nq, k, R, L))
+            np.testing.assert_array_equal(sc.cpu().numpy(), os_, err_msg="nq=%d k=%d R=%d L=%d" % (nq, k, R, L))
+    idx.set_tuning("small_batch_impl", 1)
+    q = c["q"][:2]
+    ids, sc = idx.search(dev(q), 10, 100, lut_mode, leaves_to_search=16)
+    oi, os_ = oracle.search(c["x"], c["cb"], c["codes"], c["bits"], q, 10, 100, lut_mode,
+                            centers=c["centers"], assign=c["assign"], leaves_to_search=16)
+    np.testing.assert_array_equal(ids.cpu().numpy(), oi)
+    np.testing.assert_array_equal(sc.cpu().numpy(), os_)
+
+
 @pytest.mark.parametrize("d,M", [(16, 8), (32, 16)])
 @pytest.mark.parametrize("lut_mode", [0, 1])
 def test_partitioned_search_pads_when_leaves_are_small(d, M, lut_mode):
