@@ -622,6 +622,29 @@ def test_partitioned_search_at_other_code_sizes(ivf_other_size_case, lut_mode):
     np.testing.assert_array_equal(sc.cpu().numpy(), os_)
 
 
+@pytest.fixture(scope="module", params=[(64, 8), (24, 6)], ids=["nb8", "nb6"])
+def ivf_wide_code_case(request):
+    d, M = request.param
+    return make_ivf_case(36, 6_007, d, M, 8, 70, 24)
+
+
+@pytest.mark.parametrize("lut_mode", [0, 1])
+def test_partitioned_search_with_8bit_codes(ivf_wide_code_case, lut_mode):
+    # 256 codewords per subspace on a partitioned index: a few queries and a batch
+    c = ivf_wide_code_case
+    idx, xd = make_ivf_index(c)
+    idx.set_tuning("group_min_pairs", 1)
+    for nq in (1, 5, 70):
+        q = c["q"][:nq]
+        qd = dev(q)
+        for k, R, L in ((10, 100, 6), (10, 0, 24), (25, 200, 16)):
+            ids, sc = idx.search(qd, k, R, lut_mode, leaves_to_search=L)
+            oi, os_ = oracle.search(c["x"], c["cb"], c["codes"], c["bits"], q, k, R, lut_mode,
+                                    centers=c["centers"], assign=c["assign"], leaves_to_search=L)
+            np.testing.assert_array_equal(ids.cpu().numpy(), oi, err_msg="nq=%d k=%d R=%d L=%d" % (nq, k, R, L))
+            np.testing.assert_array_equal(sc.cpu().numpy(), os_, err_msg="nq=%d k=%d R=%d L=%d" % (nq, k, R, L))
+
+
 @pytest.mark.parametrize("d,M", [(16, 8), (32, 16)])
 @pytest.mark.parametrize("lut_mode", [0, 1])
 def test_partitioned_search_pads_when_leaves_are_small(d, M, lut_mode):
