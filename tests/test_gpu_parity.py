@@ -1074,3 +1074,48 @@ def test_batches_of_8bit_codes_through_block_bounds(M, d, lut_mode):
         idx.set_tuning("scan_prefilter", 0)
         np.testing.assert_array_equal(ids2.cpu().numpy(), oi)
         np.testing.assert_array_equal(sc2.cpu().numpy(), os_)
+
+
+# ---- drawn configurations -------------------------------------------------------------
+
+def draw_configuration(seed):
+    rng = np.random.default_rng(1000 + seed)
+    bits = int(rng.choice([4, 4, 8]))
+    ds = int(rng.choice([1, 2, 2, 3, 4, 8]))
+    M = int(rng.integers(2, 41)) if bits == 4 else int(rng.integers(2, 17))
+    if rng.random() < 0.4:  # a code size with kernels of its own
+        M = int(rng.choice([16, 25, 26, 50, 64])) if bits == 4 else int(rng.choice([8, 13, 25, 32]))
+    while M * ds > 256:
+        ds = max(1, ds // 2)
+    n = int(np.exp(rng.uniform(np.log(300.0), np.log(40000.0))))
+    nq = int(rng.choice([1, 2, 5, 16, 32, 33, 35, 36, 37, 64, 80, 81, 130, 300]))
+    R = int(rng.choice([0, 1, 10, 64, 100, 257, 512]))
+    k = int(rng.integers(1, max(1, min(R if R else 64, 100)) + 1))
+    leaves = int(rng.integers(3, 30)) if rng.random() < 0.5 else 0
+    L = int(rng.integers(1, leaves + 1)) if leaves else 0
+    return dict(bits=bits, M=M, d=M * ds, n=n, nq=nq, k=k, R=R, n_leaves=leaves, L=L)
+
+
+@pytest.mark.parametrize("seed", range(64))
+def test_drawn_configurations_match(seed):
+    # shapes, batch sizes, k, R and partitions drawn at random around the thresholds where the search
+    # changes its kernels; both table kinds, ids and scores against the oracle's
+    g = draw_configuration(seed)
+    msg = str(g)
+    if g["n_leaves"]:
+        c = make_ivf_case(200 + seed, g["n"], g["d"], g["M"], g["bits"], g["nq"], g["n_leaves"])
+        idx, xd = make_ivf_index(c)
+        if seed % 2:
+            idx.set_tuning("group_min_pairs", 1)
+        kw = dict(centers=c["centers"], assign=c["assign"], leaves_to_search=g["L"])
+        skw = dict(leaves_to_search=g["L"])
+    else:
+        c = make_case(200 + seed, g["n"], g["d"], g["M"], g["bits"], g["nq"], train_iters=2)
+        idx, xd = make_index(c)
+        kw, skw = {}, {}
+    qd = dev(c["q"])
+    for lut_mode in (0, 1):
+        ids, sc = idx.search(qd, g["k"], g["R"], lut_mode, **skw)
+        oi, os_ = oracle.search(c["x"], c["cb"], c["codes"], g["bits"], c["q"], g["k"], g["R"], lut_mode, **kw)
+        np.testing.assert_array_equal(ids.cpu().numpy(), oi, err_msg=msg)
+        np.testing.assert_array_equal(sc.cpu().numpy(), os_, err_msg=msg)
