@@ -767,7 +767,7 @@ static int search_leaves_grouped(avq_index *idx, const float *queries, int nq, i
         StageTimer t(idx, AVQ_STAGE_LEAF, st);
         AVQ_TRY(group_by_leaf_prepare(nq, L, c.n_leaves, idx->groups.as<uint32_t>(), &g, st));
         AVQ_TRY(launch_leaf_select(idx->centers_t.as<float>(), c.n_leaves, c.d, queries, nq, L,
-                                   idx->leaf_ids.as<int32_t>(), idx->leaf_ip.as<float>(), st, g.leaf_cnt, g.pos));
+                                   idx->leaf_ids.as<int32_t>(), idx->leaf_ip.as<float>(), st, g.cnt_wide, g.pos, g.cnt_stride));
     }
     // scratch: [4] counts | [nq] unverified queries | [nq] margins | [nq] bounds | [nq] kept counts
     AVQ_TRY(idx->fail.reserve(sizeof(int32_t) * (4 + (size_t)4 * nq)));

@@ -324,22 +324,24 @@ int launch_gather_rows(const float *src, float *dst, const int32_t *row, const u
 // ScanParams::item_list). ws: group_by_leaf_words(...) 32-bit words of device scratch.
 struct LeafGroups {
     uint32_t *leaf_cnt, *leaf_off, *item_off, *fill, *n_items, *qlist, *pos, *item_list; // pos[q][Lp]: the pair's place in its leaf's list
+    uint32_t *cnt_wide; // the counters leaf selection adds to: leaf l's is cnt_wide[l * cnt_stride]
+    int cnt_stride;
     int32_t max_items; // every 32 pairs of a leaf are an item: at most pairs / 32 + n_leaves of them
 };
 inline size_t group_by_leaf_max_items(int nq, int Lp, int n_leaves) { return ((size_t)nq * Lp + 31) / 32 + (size_t)n_leaves; }
 size_t group_by_leaf_words(int nq, int Lp, int n_leaves);
-// prepare (lays out ws, clears the counts) -> launch_leaf_select(..., g.leaf_cnt) -> launch_group_by_leaf
+// prepare (lays out ws, clears the counts) -> launch_leaf_select(..., g.cnt_wide, g.pos, g.cnt_stride) -> launch_group_by_leaf
 int group_by_leaf_prepare(int nq, int Lp, int n_leaves, uint32_t *ws, LeafGroups *g, hipStream_t st);
 int launch_group_by_leaf(const int32_t *leaf_ids, int nq, int Lp, int n_leaves, const LeafGroups &g, hipStream_t st);
 // The same selection for a handful of queries (L <= 512): scores by many small workgroups into keys[nq][n_leaves]
 // (scratch), then the L best per query.
 int launch_leaf_select_few(const float *centers_t, int n_leaves, int d, const float *queries, int nq, int L, u64 *keys,
                            int32_t *leaf_ids, float *leaf_ip, hipStream_t st);
-// leaf_cnt (optional): incremented once per selected (query, leaf) pair; leaf_pos (optional, [nq][L]): the count before
-// the pair's own increment, i.e. its place among the pairs of that leaf
+// leaf_cnt (optional): leaf_cnt[leaf * cnt_stride] is incremented once per selected (query, leaf) pair; leaf_pos
+// (optional, [nq][L]): the count before the pair's own increment, i.e. its place among the pairs of that leaf
 int launch_leaf_select(const float *centers_t, int n_leaves, int d, const float *queries, int nq,
                        int L, int32_t *leaf_ids, float *leaf_ip, hipStream_t st, uint32_t *leaf_cnt = nullptr,
-                       uint32_t *leaf_pos = nullptr);
+                       uint32_t *leaf_pos = nullptr, int cnt_stride = 1);
 int launch_transpose(const float *in, int rows, int cols, float *out, hipStream_t st);
 
 // ---- layout.hip ------------------------------------------------------------

@@ -15,7 +15,7 @@ __global__ void __launch_bounds__(1024)
 leaf_select_kernel(const float *__restrict__ centers_t, int n_leaves, int d,
                    const float *__restrict__ queries, int L, int ns,
                    int32_t *__restrict__ leaf_ids, float *__restrict__ leaf_ip, uint32_t *__restrict__ leaf_cnt,
-                   uint32_t *__restrict__ leaf_pos)
+                   uint32_t *__restrict__ leaf_pos, int cnt_stride)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const int C = 64 * ns;
@@ -59,7 +59,7 @@ leaf_select_kernel(const float *__restrict__ centers_t, int n_leaves, int d,
         leaf_ids[(size_t)q * L + j] = key ? key_id(key) : -1;
         leaf_ip[(size_t)q * L + j] = key ? f32_from_ord(key_ord(key)) : -INFINITY;
         if (leaf_cnt != nullptr && key) { // how many queries probe each leaf, and this pair's place among them
-            const uint32_t at = atomicAdd(&leaf_cnt[key_id(key)], 1u);
+            const uint32_t at = atomicAdd(&leaf_cnt[(size_t)key_id(key) * cnt_stride], 1u);
             if (leaf_pos != nullptr) leaf_pos[(size_t)q * L + j] = at;
         }
     }
@@ -75,41 +75,55 @@ constexpr int kLeafTile = 8;
 __global__ void __launch_bounds__(512)
 leaf_select_tile_kernel(const float *__restrict__ centers_t, int n_leaves, int d, const float *__restrict__ queries, int nq,
                         int L, int32_t *__restrict__ leaf_ids, float *__restrict__ leaf_ip, uint32_t *__restrict__ leaf_cnt,
-                   uint32_t *__restrict__ leaf_pos)
+                   uint32_t *__restrict__ leaf_pos, int cnt_stride)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     constexpr int nt = 512, n_waves = 8;
     const int q0 = blockIdx.x * kLeafTile;
     uint32_t *ords = (uint32_t *)smem;                                  // [8][n_leaves] ordering values of the scores
-    float *qs = (float *)(ords + (size_t)kLeafTile * n_leaves);         // [d][8]
-    u64 *fin = (u64 *)(qs + (size_t)d * kLeafTile);                     // [8 waves][n_fin_max]
+    u64 *fin = (u64 *)(ords + (size_t)kLeafTile * n_leaves);            // [8 waves][n_fin_max]
     const int n_fin_max = L;
-    for (int e = tid; e < d * kLeafTile; e += nt) {
-        const int l = e / kLeafTile, t = e % kLeafTile;
-        qs[e] = q0 + t < nq ? queries[(size_t)(q0 + t) * d + l] : 0.0f;
-    }
-    __syncthreads();
+    // The eight queries' components are the same for every lane: read straight from memory they are scalar
+    // loads and scalar operands of the fma chains, and the loop is vector loads of center values and
+    // arithmetic only. (Queries beyond the batch repeat the last one; their scores are never used.)
+    const float *qrow[kLeafTile];
+#pragma unroll
+    for (int t = 0; t < kLeafTile; ++t) qrow[t] = queries + (size_t)(q0 + t < nq ? q0 + t : nq - 1) * d;
     for (int leaf = tid; leaf < n_leaves; leaf += nt) {
         const float *col = centers_t + leaf;
         float s[kLeafTile];
 #pragma unroll
         for (int t = 0; t < kLeafTile; ++t) s[t] = 0.0f;
-        // sixteen center values in flight at a time
-        for (int l0 = 0; l0 < d; l0 += 16) {
-            float c[16];
+        // sixteen center values at a time, the next sixteen asked for before the current ones are used (the
+        // loads take longer than the 128 fused multiply-adds they feed)
+        constexpr int kChunk = 16;
+        const int full = d / kChunk;
+        float c[kChunk];
+        if (full > 0) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) c[i] = l0 + i < d ? col[(size_t)(l0 + i) * n_leaves] : 0.0f;
+            for (int i = 0; i < kChunk; ++i) c[i] = col[(size_t)i * n_leaves];
+        }
+        for (int ch = 0; ch < full; ++ch) {
+            float nx[kChunk];
+            const bool more = ch + 1 < full;
+            if (more) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                if (l0 + i >= d) break;
-                const float *ql = qs + (l0 + i) * kLeafTile;
-                const float4 qa = *(const float4 *)ql, qb = *(const float4 *)(ql + 4);
-                s[0] = __fmaf_rn(qa.x, c[i], s[0]); s[1] = __fmaf_rn(qa.y, c[i], s[1]);
-                s[2] = __fmaf_rn(qa.z, c[i], s[2]); s[3] = __fmaf_rn(qa.w, c[i], s[3]);
-                s[4] = __fmaf_rn(qb.x, c[i], s[4]); s[5] = __fmaf_rn(qb.y, c[i], s[5]);
-                s[6] = __fmaf_rn(qb.z, c[i], s[6]); s[7] = __fmaf_rn(qb.w, c[i], s[7]);
+                for (int i = 0; i < kChunk; ++i) nx[i] = col[(size_t)((ch + 1) * kChunk + i) * n_leaves];
             }
+#pragma unroll
+            for (int i = 0; i < kChunk; ++i)
+#pragma unroll
+                for (int t = 0; t < kLeafTile; ++t) s[t] = __fmaf_rn(qrow[t][ch * kChunk + i], c[i], s[t]);
+            if (more) {
+#pragma unroll
+                for (int i = 0; i < kChunk; ++i) c[i] = nx[i];
+            }
+        }
+        for (int l = full * kChunk; l < d; ++l) {
+            const float cl = col[(size_t)l * n_leaves];
+#pragma unroll
+            for (int t = 0; t < kLeafTile; ++t) s[t] = __fmaf_rn(qrow[t][l], cl, s[t]);
         }
 #pragma unroll
         for (int t = 0; t < kLeafTile; ++t) ords[(size_t)t * n_leaves + leaf] = ord_from_f32(s[t]);
@@ -131,10 +145,9 @@ leaf_select_tile_kernel(const float *__restrict__ centers_t, int n_leaves, int d
         }
         auto count_ge = [&](uint32_t v) -> int {
             if (in_regs) { // v >= 1 in every call, so the zeros that stand for "no leaf" never count
-                int cr = 0;
+                int cr = 0; // one compare per register; the counting is scalar work on the lane masks
 #pragma unroll
-                for (int i = 0; i < kReg; ++i) cr += mine[i] >= v;
-                for (int m = 32; m > 0; m >>= 1) cr += __shfl_xor(cr, m, 64);
+                for (int i = 0; i < kReg; ++i) cr += __popcll(__builtin_amdgcn_ballot_w64(mine[i] >= v));
                 return cr;
             }
             int cn = 0;
@@ -181,7 +194,7 @@ leaf_select_tile_kernel(const float *__restrict__ centers_t, int n_leaves, int d
                 leaf_ids[(size_t)q * L + rank] = key_id(k);
                 leaf_ip[(size_t)q * L + rank] = f32_from_ord(key_ord(k));
                 if (leaf_cnt != nullptr) {
-                    const uint32_t at = atomicAdd(&leaf_cnt[key_id(k)], 1u);
+                    const uint32_t at = atomicAdd(&leaf_cnt[(size_t)key_id(k) * cnt_stride], 1u);
                     if (leaf_pos != nullptr) leaf_pos[(size_t)q * L + rank] = at;
                 }
             }
@@ -266,16 +279,17 @@ int launch_leaf_select_few(const float *centers_t, int n_leaves, int d, const fl
 }
 
 int launch_leaf_select(const float *centers_t, int n_leaves, int d, const float *queries, int nq,
-                       int L, int32_t *leaf_ids, float *leaf_ip, hipStream_t st, uint32_t *leaf_cnt, uint32_t *leaf_pos)
+                       int L, int32_t *leaf_ids, float *leaf_ip, hipStream_t st, uint32_t *leaf_cnt, uint32_t *leaf_pos,
+                       int cnt_stride)
 {
     const int ns = (L + 63) / 64;
     if (nq >= 2048) {
-        const size_t lds = (size_t)kLeafTile * n_leaves * 4 + (size_t)d * kLeafTile * 4 + (size_t)8 * L * 8;
+        const size_t lds = (size_t)kLeafTile * n_leaves * 4 + (size_t)8 * L * 8;
         if (lds <= kMaxDynLds) {
             static LdsLimitOnce tile_attr_done;
             AVQ_TRY(set_lds_limit((const void *)leaf_select_tile_kernel, kMaxDynLds, &tile_attr_done));
             hipLaunchKernelGGL(leaf_select_tile_kernel, dim3((nq + kLeafTile - 1) / kLeafTile), dim3(512), lds, st, centers_t, n_leaves,
-                               d, queries, nq, L, leaf_ids, leaf_ip, leaf_cnt, leaf_pos);
+                               d, queries, nq, L, leaf_ids, leaf_ip, leaf_cnt, leaf_pos, cnt_stride);
             AVQ_HIP(hipGetLastError());
             return AVQ_OK;
         }
@@ -288,7 +302,7 @@ int launch_leaf_select(const float *centers_t, int n_leaves, int d, const float 
     static LdsLimitOnce attr_done;
     AVQ_TRY(set_lds_limit((const void *)leaf_select_kernel, kMaxDynLds, &attr_done));
     hipLaunchKernelGGL(leaf_select_kernel, dim3(nq), dim3(waves * 64), lds, st, centers_t, n_leaves, d,
-                       queries, L, ns, leaf_ids, leaf_ip, leaf_cnt, leaf_pos);
+                       queries, L, ns, leaf_ids, leaf_ip, leaf_cnt, leaf_pos, cnt_stride);
     AVQ_HIP(hipGetLastError());
     return AVQ_OK;
 }
@@ -302,17 +316,24 @@ int launch_leaf_select(const float *centers_t, int n_leaves, int d, const float 
 // 32 of them are one work item, item_list[i] = leaf << 11 | tile. The order of a leaf's pairs
 // depends on the order of atomic operations; no result depends on it.
 
-// One workgroup: running sums of the pair counts and of the item counts; clears the fill cursors.
+// One workgroup: running sums of the pair counts and of the item counts; clears the fill cursors. The counts
+// arrive spread out (cnt_wide[l * cnt_stride], see group_by_leaf_prepare) and leave side by side in leaf_cnt.
 __global__ void __launch_bounds__(1024)
-group_offsets_kernel(const uint32_t *__restrict__ leaf_cnt, int n_leaves, uint32_t *__restrict__ leaf_off,
-                     uint32_t *__restrict__ item_off, uint32_t *__restrict__ fill, uint32_t *__restrict__ n_items)
+group_offsets_kernel(const uint32_t *__restrict__ cnt_wide, int cnt_stride, uint32_t *__restrict__ leaf_cnt, int n_leaves,
+                     uint32_t *__restrict__ leaf_off, uint32_t *__restrict__ item_off, uint32_t *__restrict__ fill,
+                     uint32_t *__restrict__ n_items)
 {
     __shared__ uint32_t part_p[1024], part_i[1024];
     const int tid = threadIdx.x, nt = blockDim.x;
     const int per = (n_leaves + nt - 1) / nt;
     const int lo = tid * per, hi = lo + per < n_leaves ? lo + per : n_leaves;
     uint32_t sp = 0u, si = 0u;
-    for (int l = lo; l < hi; ++l) { sp += leaf_cnt[l]; si += (leaf_cnt[l] + 31u) / 32u; }
+    for (int l = lo; l < hi; ++l) {
+        const uint32_t cn = cnt_wide[(size_t)l * cnt_stride];
+        leaf_cnt[l] = cn;
+        sp += cn;
+        si += (cn + 31u) / 32u;
+    }
     part_p[tid] = sp;
     part_i[tid] = si;
     __syncthreads();
@@ -357,13 +378,24 @@ group_items_kernel(const uint32_t *__restrict__ leaf_cnt, const uint32_t *__rest
     for (uint32_t t = 0; t < tiles; ++t) item_list[item_off[l] + t] = ((uint32_t)l << 11) | t;
 }
 
+// Counting a batch's pairs is a million atomic additions to a few thousand words, and additions to words of one
+// cache line wait for one another: the counters that take them are spread out, one per 128 bytes while that
+// stays under a megabyte.
+static int leaf_cnt_stride(int n_leaves)
+{
+    int stride = 32;
+    while (stride > 1 && (size_t)n_leaves * stride > ((size_t)1 << 18)) stride /= 2;
+    return stride;
+}
+
 size_t group_by_leaf_words(int nq, int Lp, int n_leaves)
 {
-    return (size_t)4 * n_leaves + 4 + (size_t)2 * nq * Lp + group_by_leaf_max_items(nq, Lp, n_leaves);
+    return (size_t)4 * n_leaves + 4 + (size_t)2 * nq * Lp + group_by_leaf_max_items(nq, Lp, n_leaves) +
+           (size_t)n_leaves * leaf_cnt_stride(n_leaves);
 }
 
 // Lays the scratch out and clears the pair counts; leaf selection then counts (launch_leaf_select's
-// leaf_cnt), and launch_group_by_leaf does the rest.
+// leaf_cnt = g.cnt_wide with g.cnt_stride), and launch_group_by_leaf does the rest.
 int group_by_leaf_prepare(int nq, int Lp, int n_leaves, uint32_t *ws, LeafGroups *g, hipStream_t st)
 {
     if (Lp > 512 || nq > (1 << 16) || n_leaves > (1 << 21)) { set_error("grouping by leaf: batch or partition too large"); return AVQ_EINVAL; }
@@ -376,15 +408,17 @@ int group_by_leaf_prepare(int nq, int Lp, int n_leaves, uint32_t *ws, LeafGroups
     g->pos = g->qlist + (size_t)nq * Lp;
     g->item_list = g->pos + (size_t)nq * Lp;
     g->max_items = (int32_t)group_by_leaf_max_items(nq, Lp, n_leaves);
-    AVQ_HIP(hipMemsetAsync(g->leaf_cnt, 0, sizeof(uint32_t) * (size_t)n_leaves, st));
+    g->cnt_wide = g->item_list + g->max_items;
+    g->cnt_stride = leaf_cnt_stride(n_leaves);
+    AVQ_HIP(hipMemsetAsync(g->cnt_wide, 0, sizeof(uint32_t) * (size_t)n_leaves * g->cnt_stride, st));
     return AVQ_OK;
 }
 
 int launch_group_by_leaf(const int32_t *leaf_ids, int nq, int Lp, int n_leaves, const LeafGroups &g, hipStream_t st)
 {
     const int64_t n_pairs = (int64_t)nq * Lp;
-    hipLaunchKernelGGL(group_offsets_kernel, dim3(1), dim3(1024), 0, st, g.leaf_cnt, n_leaves, g.leaf_off, g.item_off, g.fill,
-                       g.n_items);
+    hipLaunchKernelGGL(group_offsets_kernel, dim3(1), dim3(1024), 0, st, g.cnt_wide, g.cnt_stride, g.leaf_cnt, n_leaves, g.leaf_off,
+                       g.item_off, g.fill, g.n_items);
     hipLaunchKernelGGL(group_fill_kernel, dim3((unsigned)((n_pairs + 255) / 256)), dim3(256), 0, st, leaf_ids, g.pos, n_pairs, Lp,
                        g.leaf_off, g.qlist);
     hipLaunchKernelGGL(group_items_kernel, dim3((n_leaves + 255) / 256), dim3(256), 0, st, g.leaf_cnt, g.item_off, n_leaves,

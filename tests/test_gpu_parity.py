@@ -565,6 +565,26 @@ def test_leaf_select_for_batches_matches(ivf_batch_case):
             np.testing.assert_array_equal(ip[qi], oip)
 
 
+@pytest.mark.parametrize("which", ["d100", "d32"])
+def test_leaf_select_for_thousands_of_queries_matches(ivf_case, ivf_batch_case, which):
+    # from 2,048 queries on a workgroup scores the leaves for eight queries at once; the last workgroup here
+    # holds two queries. d = 100 leaves a tail after the chunks of eight dimensions
+    c = ivf_case if which == "d100" else ivf_batch_case
+    idx, _ = make_ivf_index(c)
+    rng = np.random.default_rng(5)
+    nq = 2050
+    q = c["q"][rng.integers(0, c["q"].shape[0], nq)] + rng.normal(0.0, 0.05, (nq, c["d"])).astype(np.float32)
+    q = np.ascontiguousarray(q, dtype=np.float32)
+    qd = dev(q)
+    for L in (1, 16, min(100, c["n_leaves"]), c["n_leaves"]):
+        ids, ip = idx.debug_leaf_select(qd, L)
+        ids, ip = ids.cpu().numpy(), ip.cpu().numpy()
+        for qi in list(range(0, nq, 97)) + [2047, 2048, 2049]:
+            oi, oip = oracle.leaf_select(c["centers"], q[qi], L)
+            np.testing.assert_array_equal(ids[qi], oi, err_msg="L=%d query %d" % (L, qi))
+            np.testing.assert_array_equal(ip[qi], oip, err_msg="L=%d query %d" % (L, qi))
+
+
 @pytest.mark.parametrize("lut_mode", [0, 1])
 @pytest.mark.parametrize("variant", ["default", "plain", "odd_back", "small_buffers"])
 def test_partitioned_batches_grouped_by_leaf(ivf_batch_case, lut_mode, variant):
