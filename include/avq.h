@@ -344,7 +344,11 @@ double avq_eta(int32_t d, double T, double norm, int32_t eta_mode);
  * against; "scan_prefilter" = 1 also switches that regrouped scan off,
  * "prefilter_cap" is its kept keys per query), "group_min_pairs" (queries x
  * probed leaves from which a batch on a partitioned index is regrouped by
- * leaf; built in: 131072, below that one workgroup per query is faster).
+ * leaf; built in: 131072, below that one workgroup per query is faster),
+ * "select_split" (block-maxima path: 1: one workgroup per query selects the
+ * blocks to score exactly; v >= 2: several workgroups per query do, v blocks
+ * of the index each; built in: 8192 each for up to 16 queries on an index of
+ * 32768 blocks of 256 points or more).
  * Results never depend on these. Returns
  * AVQ_EINVAL for an unknown name. */
 int avq_set_tuning(avq_index *idx, const char *name, int32_t value);

@@ -59,7 +59,7 @@ struct avq_index {
     DevBuf x_own, codes_logical, codes_blocked, assign, perm, leaf_blk;
     // per-call scratch
     DevBuf lut, lut8, scale, bias, partial, cand, leaf_ids, leaf_ip, tmp, thr;
-    int tune_target_wgs = 0, tune_waves = 0, tune_qt = 0, tune_small_batch = -1, tune_small_impl = 0;
+    int tune_target_wgs = 0, tune_waves = 0, tune_qt = 0, tune_small_batch = -1, tune_small_impl = 0, tune_select_split = 0;
     int tune_mfma = 0; // 0 = use the matrix-core scan where it applies, 1 = never
     int tune_prefilter = 0; // 0 = fp32-table batches go through the 8-bit-table scan where it applies, 1 = never,
                             // 2 = as 0 but odd queries always take the plain scan afterwards (exercises that branch)
@@ -184,6 +184,7 @@ extern "C" int avq_set_tuning(avq_index *idx, const char *name, int32_t value)
     else if (!strcmp(name, "scan_sample")) idx->tune_sample = value;
     else if (!strcmp(name, "group_min_pairs")) idx->tune_group_min = value;
     else if (!strcmp(name, "bound_leaves")) idx->tune_bound_leaves = value;
+    else if (!strcmp(name, "select_split")) idx->tune_select_split = value;
     else { set_error("avq_set_tuning: unknown name '%s'", name); return AVQ_EINVAL; }
     return AVQ_OK;
 }
@@ -918,6 +919,7 @@ struct SmallWs {
     uint32_t *block_bound; // [nq][n_blocks]   (block-bound path)
     BoundMeta *bound_meta; // [nq]             (block-bound path)
     uint8_t *bound_tbl;    // [nq][NB][256]    (block-bound path)
+    uint32_t *sel_hist;    // [nq][8192]       (block-bound path, selection over several workgroups per query)
 };
 
 // 0: the scan records block maxima of 8-bit sums (bounds of the scores) where the code size has its
@@ -925,6 +927,17 @@ struct SmallWs {
 static bool small_uses_bounds(const avq_index *idx)
 {
     return idx->tune_small_impl == 0 && block_bound_supported(idx->NB, idx->cfg.bits);
+}
+
+// Blocks per workgroup when the selection of a query's blocks is spread over several workgroups; 0: one workgroup
+// per query. Built in: a few queries on an index of 32,768 blocks or more, where one compute unit's two passes over
+// the block maxima take longer than everything else after the scan. Tuning "select_split": 1 never, v >= 2: always,
+// v blocks per workgroup.
+static int small_select_split_per(const avq_index *idx, int nq)
+{
+    if (!small_uses_bounds(idx) || idx->tune_select_split == 1) return 0;
+    if (idx->tune_select_split >= 2) return std::min(idx->tune_select_split, 8192);
+    return nq <= 16 && idx->n_blocks >= 32768 ? 8192 : 0;
 }
 
 // Lays the scratch out from `base` (256-byte aligned pieces); returns the bytes needed.
@@ -951,6 +964,8 @@ static size_t small_ws_carve(const avq_index *idx, int nq, int R, unsigned char 
     w->block_bound = (uint32_t *)take(bounds ? sizeof(uint32_t) * (size_t)nq * idx->n_blocks : 0);
     w->bound_meta = (BoundMeta *)take(bounds ? sizeof(BoundMeta) * (size_t)nq : 0);
     w->bound_tbl = (uint8_t *)take(bounds ? (size_t)nq_tiles * idx->NB * 256 : 0);
+    const bool split = small_select_split_per(idx, nq) > 0;
+    w->sel_hist = (uint32_t *)take(split ? sizeof(uint32_t) * (size_t)nq * 8192 : 0);
     return off;
 }
 
@@ -995,6 +1010,8 @@ static int search_small(avq_index *idx, const float *queries, int nq, int k, int
     p.bound_meta = w.bound_meta;
     p.lut_out = fuse_tables ? w.lut : nullptr;
     p.bound_tbl = w.bound_tbl;
+    p.sel_split_per = small_select_split_per(idx, nq);
+    if (p.sel_split_per > 0) p.sel_hist = w.sel_hist;
     if (tile) {
         p.bound_tile = 16;
         p.bound_levels = 63;

@@ -103,6 +103,10 @@ struct ScanParams {
     int32_t bound_tile;    // 0 or 16
     int32_t bound_levels;  // largest table entry: 255 (0: 255), or 63 for the batch scan, which adds entries as packed bytes
     int32_t bound_shift;   // 8-bit tables on 8-bit codes: the byte tables are the 8-bit tables >> bound_shift (0 or 2)
+    // selection of the blocks over several workgroups per query (a few queries on a large index), else NULL:
+    // sel_hist [B][8192] scratch, sel_split_per blocks per workgroup (1 .. 8192)
+    uint32_t *sel_hist;
+    int32_t sel_split_per;
     u64 *partial;         // [n_tiles*QT][n_chunks][64*ns]
     u64 *lists_ws;        // NULL: candidate lists in LDS; else scratch [grid][waves][QT][64*ns]
     // matrix-core kernel, both zeroed before the launch: [B] best known bound of the R-th best

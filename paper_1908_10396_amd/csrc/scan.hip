@@ -1154,11 +1154,15 @@ rescan_leaf_blocks_kernel(const ScanParams p, const FinishParams f, const LeafBl
 // U8: the search uses 8-bit tables; WIDE: 8-bit codes (else 4-bit codes, two per byte). With 4-bit codes
 // the 16-entry tables are read (p.lut, p.lut8) or, for fp32 tables when p.fuse_queries is set, computed
 // here (the fma chain of the table kernel) and left in p.lut_out for the kernels that follow.
+constexpr int kBoundBins = 8192; // bins of the selection's histogram: sums of byte table entries are at most 255 * 32
+
 template <bool U8, bool WIDE>
 __global__ void __launch_bounds__(1024)
 bound_tables_kernel(const ScanParams p)
 {
     constexpr int kMaxNB = 32;
+    if (p.sel_hist != nullptr && (int)blockIdx.x < p.B) // the split selection adds to these: cleared here, two launches ahead
+        for (int b = threadIdx.x; b < kBoundBins; b += blockDim.x) p.sel_hist[(size_t)blockIdx.x * kBoundBins + b] = 0u;
     __shared__ __align__(16) float nib[WIDE ? 4 : 2 * kMaxNB * 16]; // 4-bit codes: the 16-entry tables (8-bit tables: as bytes)
     __shared__ float tmin[2 * kMaxNB], tmax[2 * kMaxNB], lo_s[kMaxNB], c_s;
     const int tid = threadIdx.x, nt = blockDim.x;
@@ -1517,54 +1521,40 @@ lookup_only_kernel(const ScanParams p)
     }
 }
 
-// One workgroup per query: theta = the R-th largest block maximum of the 8-bit sums, the list of the blocks
-// whose maximum reaches theta - margin, and the lower bound of the R-th best exact score as a key
-// threshold (meta[q].t1). kind 0: fp32 tables (margin and bound from bound_meta, see above), 1: 8-bit
-// tables on 4-bit codes (sums halved), 2: 8-bit tables on 8-bit codes (the tables themselves, or without their
-// `shift` low bits).
-__global__ void __launch_bounds__(1024)
-select_bound_blocks_kernel(const uint32_t *__restrict__ block_bound, int64_t n_blocks, int R, int NB, int kind, int shift,
-                           const BoundMeta *__restrict__ bound_meta, int32_t *__restrict__ sel_blk,
-                           SmallMeta *__restrict__ meta)
+// fn(block, its maximum) for the blocks [b0, b0 + cnt) of a query's row bb, by the calling workgroup. With
+// hundreds of thousands of blocks a pass is all memory latency: 16-byte loads, four of them in flight per thread
+// (the few values before the first 16-byte boundary and after the last go one by one).
+template <class F>
+__device__ __forceinline__ void for_every_block(const uint32_t *__restrict__ bb, int64_t b0, int64_t cnt, int tid, int nt, F fn)
 {
-    constexpr int kBins = 8192; // sums are at most 255 * 32
-    __shared__ uint32_t hist[kBins];
-    __shared__ uint32_t wave_sum[16];
-    __shared__ uint32_t theta_s, n_sel;
-    const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63, wave = tid >> 6, n_waves = nt >> 6;
-    const int q = blockIdx.x;
-    const uint32_t *bb = block_bound + (size_t)q * n_blocks;
-    for (int b = tid; b < kBins; b += nt) hist[b] = 0u;
-    if (tid == 0) { theta_s = 0u; n_sel = 0u; }
-    __syncthreads();
-    // fn(block, its maximum) for every block. With hundreds of thousands of blocks a pass is all memory latency:
-    // 16-byte loads, four of them in flight per thread (the few values before the first 16-byte boundary of the
-    // query's row and after the last go one by one)
-    auto for_every_block = [&](auto fn) {
-        const int64_t mis = (int64_t)((4u - (uint32_t)(((size_t)bb >> 2) & 3u)) & 3u);
-        const int64_t head = mis < n_blocks ? mis : n_blocks;
-        const int64_t n4 = (n_blocks - head) / 4;
-        const uint4 *b4 = (const uint4 *)(bb + head);
-        if (tid < head) fn((int64_t)tid, bb[tid]);
-        for (int64_t i0 = tid; i0 < n4; i0 += (int64_t)4 * nt) {
-            uint4 v[4];
+    const uint32_t *row = bb + b0;
+    const int64_t mis = (int64_t)((4u - (uint32_t)(((size_t)row >> 2) & 3u)) & 3u);
+    const int64_t head = mis < cnt ? mis : cnt;
+    const int64_t n4 = (cnt - head) / 4;
+    const uint4 *b4 = (const uint4 *)(row + head);
+    if (tid < head) fn(b0 + tid, row[tid]);
+    for (int64_t i0 = tid; i0 < n4; i0 += (int64_t)4 * nt) {
+        uint4 v[4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) { const int64_t i = i0 + (int64_t)u * nt; v[u] = i < n4 ? b4[i] : make_uint4(0u, 0u, 0u, 0u); }
+        for (int u = 0; u < 4; ++u) { const int64_t i = i0 + (int64_t)u * nt; v[u] = i < n4 ? b4[i] : make_uint4(0u, 0u, 0u, 0u); }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int64_t i = i0 + (int64_t)u * nt;
-                if (i >= n4) continue;
-                const int64_t b = head + 4 * i;
-                fn(b, v[u].x); fn(b + 1, v[u].y); fn(b + 2, v[u].z); fn(b + 3, v[u].w);
-            }
+        for (int u = 0; u < 4; ++u) {
+            const int64_t i = i0 + (int64_t)u * nt;
+            if (i >= n4) continue;
+            const int64_t b = b0 + head + 4 * i;
+            fn(b, v[u].x); fn(b + 1, v[u].y); fn(b + 2, v[u].z); fn(b + 3, v[u].w);
         }
-        const int64_t b = head + 4 * n4 + tid;
-        if (b < n_blocks) fn(b, bb[b]);
-    };
-    for_every_block([&](int64_t, uint32_t v) { atomicAdd(&hist[v < (uint32_t)kBins ? v : kBins - 1], 1u); });
-    __syncthreads();
-    const uint32_t need = (uint32_t)(n_blocks < R ? n_blocks : R);
-    const int per = kBins / 1024; // bins per thread (nt == 1024)
+    }
+    const int64_t b = head + 4 * n4 + tid;
+    if (b < cnt) fn(b0 + b, row[b]);
+}
+
+// theta = the largest bin with at least `need` counts at or above it (hist[kBoundBins] in LDS, 1,024 threads; ends
+// with a barrier, *theta_s valid afterwards; 0 when fewer than `need` counts exist).
+__device__ __forceinline__ int theta_from_hist(const uint32_t *hist, uint32_t need, uint32_t *wave_sum, uint32_t *theta_s, int tid)
+{
+    const int lane = tid & 63, wave = tid >> 6, n_waves = 16;
+    constexpr int per = kBoundBins / 1024; // bins per thread
     uint32_t mine = 0;
     for (int j = 0; j < per; ++j) mine += hist[tid * per + j];
     uint32_t suf = mine;
@@ -1578,15 +1568,21 @@ select_bound_blocks_kernel(const uint32_t *__restrict__ block_bound, int64_t n_b
     for (int w = wave + 1; w < n_waves; ++w) above += wave_sum[w];
     for (int j = per - 1; j >= 0; --j) {
         const uint32_t h = hist[tid * per + j];
-        if (above < need && need <= above + h) theta_s = (uint32_t)(tid * per + j);
+        if (above < need && need <= above + h) *theta_s = (uint32_t)(tid * per + j);
         above += h;
     }
     __syncthreads();
-    const int theta = (int)theta_s;
+    return (int)*theta_s;
+}
+
+// From theta: the smallest block maximum worth a look (returned) and the lower bound of the R-th best exact score
+// as a key threshold (*t1). kind 0: fp32 tables (margin and bound from bm, see above), 1: 8-bit tables on 4-bit
+// codes (sums halved), 2: 8-bit tables on 8-bit codes (the tables themselves, or without their `shift` low bits).
+__device__ __forceinline__ uint32_t cut_from_theta(int theta, int kind, int NB, int shift, const BoundMeta &bm, bool few_blocks, u64 *t1_out)
+{
     int margin;
     u64 t1;
     if (kind == 0) {
-        const BoundMeta bm = bound_meta[q];
         const double E = (double)NB * (0.5 + 4e-5);
         const double rho = (double)NB * 5.9604644775390625e-8 * bm.amax * 1.000001;
         const double c = (double)bm.c;
@@ -1597,7 +1593,7 @@ select_bound_blocks_kernel(const uint32_t *__restrict__ block_bound, int64_t n_b
             if ((double)lf > low) lf = nextafterf(lf, -INFINITY);
             t1 = (u64)ord_from_f32(lf) << 32;
         } else {
-            margin = kBins; // flat tables: every block, every point
+            margin = kBoundBins; // flat tables: every block, every point
             t1 = 1ull;
         }
     } else if (kind == 1) {
@@ -1610,9 +1606,34 @@ select_bound_blocks_kernel(const uint32_t *__restrict__ block_bound, int64_t n_b
         margin = ((sc - 1) * NB + sc - 1) / sc;
         t1 = (u64)(uint32_t)(sc * theta + 1) << 32;
     }
-    if (n_blocks < R) t1 = 1ull; // fewer blocks than R: no R points are known to reach any bound
-    const uint32_t cut = theta > margin ? (uint32_t)(theta - margin) : 0u;
-    for_every_block([&](int64_t b, uint32_t v) {
+    if (few_blocks) t1 = 1ull; // fewer blocks than R: no R points are known to reach any bound
+    *t1_out = t1;
+    return theta > margin ? (uint32_t)(theta - margin) : 0u;
+}
+
+// One workgroup per query: theta = the R-th largest block maximum of the 8-bit sums, the list of the blocks
+// whose maximum reaches theta - margin, and the key threshold meta[q].t1.
+__global__ void __launch_bounds__(1024)
+select_bound_blocks_kernel(const uint32_t *__restrict__ block_bound, int64_t n_blocks, int R, int NB, int kind, int shift,
+                           const BoundMeta *__restrict__ bound_meta, int32_t *__restrict__ sel_blk,
+                           SmallMeta *__restrict__ meta)
+{
+    __shared__ uint32_t hist[kBoundBins];
+    __shared__ uint32_t wave_sum[16];
+    __shared__ uint32_t theta_s, n_sel;
+    const int tid = threadIdx.x, nt = blockDim.x;
+    const int q = blockIdx.x;
+    const uint32_t *bb = block_bound + (size_t)q * n_blocks;
+    for (int b = tid; b < kBoundBins; b += nt) hist[b] = 0u;
+    if (tid == 0) { theta_s = 0u; n_sel = 0u; }
+    __syncthreads();
+    for_every_block(bb, 0, n_blocks, tid, nt, [&](int64_t, uint32_t v) { atomicAdd(&hist[v < (uint32_t)kBoundBins ? v : kBoundBins - 1], 1u); });
+    __syncthreads();
+    const int theta = theta_from_hist(hist, (uint32_t)(n_blocks < R ? n_blocks : R), wave_sum, &theta_s, tid);
+    u64 t1;
+    const BoundMeta bm = kind == 0 ? bound_meta[q] : BoundMeta{};
+    const uint32_t cut = cut_from_theta(theta, kind, NB, shift, bm, n_blocks < R, &t1);
+    for_every_block(bb, 0, n_blocks, tid, nt, [&](int64_t b, uint32_t v) {
         if (v >= cut) sel_blk[(size_t)q * n_blocks + atomicAdd(&n_sel, 1u)] = (int32_t)b;
     });
     __syncthreads();
@@ -1621,6 +1642,77 @@ select_bound_blocks_kernel(const uint32_t *__restrict__ block_bound, int64_t n_b
         meta[q].n_sel = n_sel;
         meta[q].n_cand = 0u;
     }
+}
+
+// The same over several compute units, for a few queries on a large index, where one workgroup's two passes
+// over the block maxima are bound by what a single compute unit draws from memory. Two launches of one
+// workgroup per `per` blocks and query. The first counts its blocks into a histogram in LDS and adds the bins it
+// filled to the query's histogram in global memory (sel_hist[q][8192], cleared by bound_tables_kernel). In the
+// second every workgroup reads that histogram back, finds theta for itself, and lists those of its blocks that
+// reach the cut, taking room in the query's list with one atomic addition to meta[q].n_sel.
+constexpr int kSelSplitMaxPer = 8192; // blocks per workgroup (its list in LDS)
+
+__global__ void __launch_bounds__(1024)
+select_split_count_kernel(const uint32_t *__restrict__ block_bound, int64_t n_blocks, int per, uint32_t *__restrict__ sel_hist,
+                          SmallMeta *__restrict__ meta)
+{
+    __shared__ uint32_t hist[kBoundBins];
+    const int tid = threadIdx.x, nt = blockDim.x;
+    const int q = blockIdx.y;
+    const uint32_t *bb = block_bound + (size_t)q * n_blocks;
+    uint32_t *gh = sel_hist + (size_t)q * kBoundBins;
+    for (int b = tid; b < kBoundBins; b += nt) hist[b] = 0u;
+    if (blockIdx.x == 0 && tid == 0) meta[q].n_sel = 0u;
+    __syncthreads();
+    const int64_t b0 = (int64_t)blockIdx.x * per;
+    const int64_t cnt = b0 + per <= n_blocks ? per : (b0 < n_blocks ? n_blocks - b0 : 0);
+    for_every_block(bb, b0, cnt, tid, nt, [&](int64_t, uint32_t v) { atomicAdd(&hist[v < (uint32_t)kBoundBins ? v : kBoundBins - 1], 1u); });
+    __syncthreads();
+    for (int b = tid; b < kBoundBins; b += nt)
+        if (hist[b]) atomicAdd(&gh[b], hist[b]);
+}
+
+__global__ void __launch_bounds__(1024)
+select_split_list_kernel(const uint32_t *__restrict__ block_bound, int64_t n_blocks, int per, int R, int NB, int kind, int shift,
+                         const BoundMeta *__restrict__ bound_meta, const uint32_t *__restrict__ sel_hist,
+                         int32_t *__restrict__ sel_blk, SmallMeta *__restrict__ meta)
+{
+    __shared__ __align__(16) uint32_t hist[kBoundBins]; // then the workgroup's list
+    __shared__ uint32_t wave_sum[16];
+    __shared__ uint32_t theta_s, n_loc, base;
+    const int tid = threadIdx.x, nt = blockDim.x;
+    const int q = blockIdx.y;
+    const uint32_t *bb = block_bound + (size_t)q * n_blocks;
+    {
+        const uint4 *gh = (const uint4 *)(sel_hist + (size_t)q * kBoundBins);
+        uint4 h[kBoundBins / 4096];
+#pragma unroll
+        for (int u = 0; u < kBoundBins / 4096; ++u) h[u] = gh[tid + u * 1024];
+#pragma unroll
+        for (int u = 0; u < kBoundBins / 4096; ++u) ((uint4 *)hist)[tid + u * 1024] = h[u];
+    }
+    if (tid == 0) { theta_s = 0u; n_loc = 0u; }
+    __syncthreads();
+    const int theta = theta_from_hist(hist, (uint32_t)(n_blocks < R ? n_blocks : R), wave_sum, &theta_s, tid);
+    u64 t1;
+    const BoundMeta bm = kind == 0 ? bound_meta[q] : BoundMeta{};
+    const uint32_t cut = cut_from_theta(theta, kind, NB, shift, bm, n_blocks < R, &t1);
+    if (blockIdx.x == 0 && tid == 0) {
+        meta[q].t1 = t1;
+        meta[q].n_cand = 0u;
+    }
+    __syncthreads(); // every thread has read its bins: the array becomes the list
+    int32_t *loc = (int32_t *)hist;
+    const int64_t b0 = (int64_t)blockIdx.x * per;
+    const int64_t cnt = b0 + per <= n_blocks ? per : (b0 < n_blocks ? n_blocks - b0 : 0);
+    for_every_block(bb, b0, cnt, tid, nt, [&](int64_t b, uint32_t v) {
+        if (v >= cut) loc[atomicAdd(&n_loc, 1u)] = (int32_t)b;
+    });
+    __syncthreads();
+    if (tid == 0) base = n_loc ? atomicAdd(&meta[q].n_sel, n_loc) : 0u;
+    __syncthreads();
+    int32_t *dst = sel_blk + (size_t)q * n_blocks + base;
+    for (uint32_t i = tid; i < n_loc; i += nt) dst[i] = loc[i];
 }
 
 // Exact scores of the listed blocks of every query, the waves of a query's workgroups taking the blocks
@@ -2196,8 +2288,18 @@ int launch_block_bound_tile(const ScanParams &p, hipStream_t st)
 int launch_select_bound_blocks(const ScanParams &p, const FinishParams &f, bool u8, hipStream_t st)
 {
     const int kind = !u8 ? 0 : (p.bits == 4 ? 1 : 2);
-    hipLaunchKernelGGL(select_bound_blocks_kernel, dim3(p.B), dim3(1024), 0, st, p.block_bound, p.n_blocks, p.R, p.NB, kind,
-                       kind == 2 ? p.bound_shift : 0,
+    const int shift = kind == 2 ? p.bound_shift : 0;
+    if (p.sel_hist != nullptr) {
+        const int per = p.sel_split_per;
+        if (per < 1 || per > kSelSplitMaxPer) { set_error("split selection: bad arguments"); return AVQ_EINVAL; }
+        const dim3 grid((unsigned)((p.n_blocks + per - 1) / per), p.B);
+        hipLaunchKernelGGL(select_split_count_kernel, grid, dim3(1024), 0, st, p.block_bound, p.n_blocks, per, p.sel_hist, f.meta);
+        hipLaunchKernelGGL(select_split_list_kernel, grid, dim3(1024), 0, st, p.block_bound, p.n_blocks, per, p.R, p.NB, kind, shift,
+                           p.bound_meta, p.sel_hist, f.sel_blk, f.meta);
+        AVQ_HIP(hipGetLastError());
+        return AVQ_OK;
+    }
+    hipLaunchKernelGGL(select_bound_blocks_kernel, dim3(p.B), dim3(1024), 0, st, p.block_bound, p.n_blocks, p.R, p.NB, kind, shift,
                        p.bound_meta, f.sel_blk, f.meta);
     AVQ_HIP(hipGetLastError());
     return AVQ_OK;

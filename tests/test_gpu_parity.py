@@ -327,8 +327,10 @@ def test_small_batch_paths_agree_with_oracle(case, lut_mode):
     for k, R in ((10, 100), (10, 0), (100, 512)):
         oi, os_ = oracle.search(case["x"], case["cb"], case["codes"], case["bits"], q, k, R, lut_mode)
         # scan_target_wgs = 2: two workgroups per query, so every wave loops over many blocks
+        # select_split: the blocks to score exactly are chosen by several workgroups per query, 5 or 3 blocks each
+        # (the slices start at every alignment of the 16-byte loads), as on a large index
         for name, val in (("small_batch_impl", 0), ("small_batch_impl", 1), ("small_batch_max", 1),
-                          ("scan_target_wgs", 2)):
+                          ("scan_target_wgs", 2), ("select_split", 5), ("select_split", 3), ("select_split", 8192)):
             idx.set_tuning(name, val)
             ids, sc = idx.search(qd, k, R, lut_mode)
             np.testing.assert_array_equal(ids.cpu().numpy(), oi, err_msg="%s=%d" % (name, val))
@@ -902,9 +904,10 @@ def test_small_batches_through_block_bounds_with_a_heap_of_equal_scores(bits, M,
         oi, os_ = oracle.search(x, cb, codes, bits, q, k, R, lut_mode)
         if R == 0:
             assert list(oi[0]) == list(range(5_000, 5_000 + k))
-        for impl in (0, 2):
+        for impl, split in ((0, 0), (2, 0), (0, 41)):   # 41: the blocks are selected by four workgroups per query
             idx.set_tuning("small_batch_impl", impl)
             idx.set_tuning("small_batch_max", 1000)
+            idx.set_tuning("select_split", split)
             ids, sc = idx.search(qd, k, R, lut_mode)
             np.testing.assert_array_equal(ids.cpu().numpy(), oi)
             np.testing.assert_array_equal(sc.cpu().numpy(), os_)
@@ -912,6 +915,7 @@ def test_small_batches_through_block_bounds_with_a_heap_of_equal_scores(bits, M,
             np.testing.assert_array_equal(ids1.cpu().numpy(), oi[:1])
             np.testing.assert_array_equal(sc1.cpu().numpy(), os_[:1])
         idx.set_tuning("small_batch_impl", 0)
+        idx.set_tuning("select_split", 0)
 
 
 def test_small_batch_block_bounds_degenerate_tables():
@@ -1094,6 +1098,11 @@ def test_batches_of_8bit_codes_through_block_bounds(M, d, lut_mode):
         idx.set_tuning("scan_prefilter", 0)
         np.testing.assert_array_equal(ids2.cpu().numpy(), oi)
         np.testing.assert_array_equal(sc2.cpu().numpy(), os_)
+        idx.set_tuning("select_split", 37)                        # blocks chosen by five workgroups per query
+        ids3, sc3 = idx.search(qd, k, R, lut_mode)
+        idx.set_tuning("select_split", 0)
+        np.testing.assert_array_equal(ids3.cpu().numpy(), oi)
+        np.testing.assert_array_equal(sc3.cpu().numpy(), os_)
 
 
 # ---- drawn configurations -------------------------------------------------------------
