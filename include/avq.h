@@ -348,7 +348,10 @@ double avq_eta(int32_t d, double T, double norm, int32_t eta_mode);
  * "select_split" (block-maxima path: 1: one workgroup per query selects the
  * blocks to score exactly; v >= 2: several workgroups per query do, v blocks
  * of the index each; built in: 8192 each for up to 16 queries on an index of
- * 32768 blocks of 256 points or more).
+ * 32768 blocks of 256 points or more), "rerank_split" (1: the exact
+ * re-scoring of a query's candidates is done by one workgroup; v >= 2: by
+ * several, v candidates each; built in: 64 each for up to 16 queries whose
+ * reorder_k rows do not fit one workgroup's LDS at once).
  * Results never depend on these. Returns
  * AVQ_EINVAL for an unknown name. */
 int avq_set_tuning(avq_index *idx, const char *name, int32_t value);

@@ -59,7 +59,7 @@ struct avq_index {
     DevBuf x_own, codes_logical, codes_blocked, assign, perm, leaf_blk;
     // per-call scratch
     DevBuf lut, lut8, scale, bias, partial, cand, leaf_ids, leaf_ip, tmp, thr;
-    int tune_target_wgs = 0, tune_waves = 0, tune_qt = 0, tune_small_batch = -1, tune_small_impl = 0, tune_select_split = 0;
+    int tune_target_wgs = 0, tune_waves = 0, tune_qt = 0, tune_small_batch = -1, tune_small_impl = 0, tune_select_split = 0, tune_rerank_split = 0;
     int tune_mfma = 0; // 0 = use the matrix-core scan where it applies, 1 = never
     int tune_prefilter = 0; // 0 = fp32-table batches go through the 8-bit-table scan where it applies, 1 = never,
                             // 2 = as 0 but odd queries always take the plain scan afterwards (exercises that branch)
@@ -185,6 +185,7 @@ extern "C" int avq_set_tuning(avq_index *idx, const char *name, int32_t value)
     else if (!strcmp(name, "group_min_pairs")) idx->tune_group_min = value;
     else if (!strcmp(name, "bound_leaves")) idx->tune_bound_leaves = value;
     else if (!strcmp(name, "select_split")) idx->tune_select_split = value;
+    else if (!strcmp(name, "rerank_split")) idx->tune_rerank_split = value;
     else { set_error("avq_set_tuning: unknown name '%s'", name); return AVQ_EINVAL; }
     return AVQ_OK;
 }
@@ -920,6 +921,8 @@ struct SmallWs {
     BoundMeta *bound_meta; // [nq]             (block-bound path)
     uint8_t *bound_tbl;    // [nq][NB][256]    (block-bound path)
     uint32_t *sel_hist;    // [nq][8192]       (block-bound path, selection over several workgroups per query)
+    u64 *fin_out;          // [nq][R]          (exact re-scoring over several workgroups per query)
+    uint32_t *fin_n;       // [nq][2]
 };
 
 // 0: the scan records block maxima of 8-bit sums (bounds of the scores) where the code size has its
@@ -938,6 +941,19 @@ static int small_select_split_per(const avq_index *idx, int nq)
     if (!small_uses_bounds(idx) || idx->tune_select_split == 1) return 0;
     if (idx->tune_select_split >= 2) return std::min(idx->tune_select_split, 8192);
     return nq <= 16 && idx->n_blocks >= 32768 ? 8192 : 0;
+}
+
+// Candidates per workgroup when the exact re-scoring of a query's candidates is spread over several workgroups; 0:
+// the final kernel does it. Built in: up to 16 queries whose R rows of d values one workgroup would stage in more
+// than one pass (its LDS holds `stage_rows` of them): 64 rows per workgroup. Tuning "rerank_split": 1 never,
+// v >= 2: always, v rows per workgroup (as many as fit LDS at most).
+static int small_rerank_rows(const avq_index *idx, int nq, int R, int stage_rows, bool reorder)
+{
+    if (!reorder || idx->tune_rerank_split == 1) return 0;
+    const int fit = (int)std::min<size_t>(1024, ((size_t)128 * 1024) / ((size_t)(idx->cfg.d + 1) * 4));
+    if (fit < 1) return 0;
+    if (idx->tune_rerank_split >= 2) return std::min(idx->tune_rerank_split, fit);
+    return nq <= 16 && R > stage_rows ? std::min(64, fit) : 0;
 }
 
 // Lays the scratch out from `base` (256-byte aligned pieces); returns the bytes needed.
@@ -966,6 +982,8 @@ static size_t small_ws_carve(const avq_index *idx, int nq, int R, unsigned char 
     w->bound_tbl = (uint8_t *)take(bounds ? (size_t)nq_tiles * idx->NB * 256 : 0);
     const bool split = small_select_split_per(idx, nq) > 0;
     w->sel_hist = (uint32_t *)take(split ? sizeof(uint32_t) * (size_t)nq * 8192 : 0);
+    w->fin_out = (u64 *)take(sizeof(u64) * (size_t)nq * R);
+    w->fin_n = (uint32_t *)take(sizeof(uint32_t) * (size_t)nq * 2);
     return off;
 }
 
@@ -1042,6 +1060,9 @@ static int search_small(avq_index *idx, const float *queries, int nq, int k, int
     f.meta = w.meta;
     f.ids_out = ids_out;
     f.scores_out = scores_out;
+    f.rerank_rows = small_rerank_rows(idx, nq, R, f.stage_rows, f.reorder != 0);
+    f.fin_out = w.fin_out;
+    f.fin_n = w.fin_n;
     if (bounds) {
         f.block_max = w.block_max;
         f.n_blocks = idx->n_blocks;

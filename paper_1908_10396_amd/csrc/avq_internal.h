@@ -211,6 +211,11 @@ struct FinishParams {
     const uint8_t *codes_logical; // [n][NB]
     const float *lut;             // [B][M][kc] fp32 tables (u8 == 0)
     const uint8_t *lut8;          // [B][M][kc] 8-bit tables (u8 == 1)
+    // exact re-scoring over several workgroups per query (a few queries, many or long rows): rerank_rows > 0
+    // candidates per workgroup (at most 1024, their rows must fit LDS), fin_out [B][R] and fin_n [B][2] scratch
+    int32_t rerank_rows;
+    u64 *fin_out;
+    uint32_t *fin_n;
 };
 int small_finish_stage_rows(const ScanParams &p, int d, bool u8);
 // The same search through block maxima of 8-bit sums (bounds, not scores: scan.hip): specialised code

@@ -1902,6 +1902,12 @@ small_batch_final_kernel(const FinishParams f, int R, int key_kind, const float 
     }
     const int k = f.k;
     const u64 *ranked = fin;
+    if (f.reorder && f.rerank_rows > 0) {
+        // the exact re-scoring is spread over several workgroups per query (rerank_split_kernel, next launch)
+        for (int i = tid; i < n_fin; i += nt) f.fin_out[(size_t)q * R + i] = fin[i];
+        if (tid == 0) { f.fin_n[2 * q] = (uint32_t)n_fin; f.fin_n[2 * q + 1] = 0u; }
+        return;
+    }
     if (f.reorder) {
         // exact re-scoring: the candidates' rows are copied to LDS by the whole workgroup
         // (eight threads per row, all loads in flight at once), then one thread per candidate
@@ -1947,6 +1953,75 @@ small_batch_final_kernel(const FinishParams f, int R, int key_kind, const float 
             if (f.reorder || !key_kind) sc = f32_from_ord(key_ord(mine));
             else sc = __fmaf_rn((float)(int)(key_ord(mine) - 1u), scale[q], bias[q]);
             f.scores_out[(size_t)q * k + rank] = sc;
+        }
+    }
+    for (int j = n_fin + tid; j < k; j += nt) { // fewer than k candidates exist
+        f.ids_out[(size_t)q * k + j] = -1;
+        f.scores_out[(size_t)q * k + j] = -INFINITY;
+    }
+}
+
+// The exact re-scoring of a query's R candidates over several workgroups, for a few queries with so many or so
+// long rows that one workgroup stages them in several passes through the one compute unit it runs on. Workgroup
+// g takes the candidates [g rows, (g + 1) rows) of fin_out[q] (left there in rank order by small_batch_final_kernel,
+// fin_n[2 q] of them), copies their rows to LDS (sixteen threads per row), runs the fma chain in index order, one
+// thread per row, and writes the key of the exact score over the candidate's. The workgroup that finishes last
+// (a ticket in fin_n[2 q + 1]) ranks the keys and writes the k best.
+__global__ void __launch_bounds__(1024)
+rerank_split_kernel(const FinishParams f, int R)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    __shared__ uint32_t last;
+    const int tid = threadIdx.x, nt = blockDim.x;
+    const int q = blockIdx.y;
+    const int d = f.d, ld = f.d + 1, rows_per = f.rerank_rows;
+    float *qs = (float *)smem;               // [d]
+    float *stage = qs + ((d + 3) & ~3);      // [rows_per][d + 1]; the last workgroup: keys [R]
+    u64 *keys = f.fin_out + (size_t)q * R;
+    const int n_fin = (int)f.fin_n[2 * q];
+    const int r0 = blockIdx.x * rows_per;
+    const int rows = r0 < n_fin ? (n_fin - r0 < rows_per ? n_fin - r0 : rows_per) : 0;
+    for (int l = tid; l < d; l += nt) qs[l] = f.queries[(size_t)q * d + l];
+    const bool vec = (d & 3) == 0;
+    for (int rb = 0; rb < rows; rb += nt / 16) {
+        const int r = rb + (tid >> 4);
+        if (r >= rows) continue;
+        const float *src = f.x + (size_t)key_id(keys[r0 + r]) * d;
+        float *dst = stage + r * ld;
+        if (vec) {
+            for (int c4 = tid & 15; c4 < d / 4; c4 += 16) {
+                const float4 v = ((const float4 *)src)[c4];
+                dst[4 * c4] = v.x; dst[4 * c4 + 1] = v.y; dst[4 * c4 + 2] = v.z; dst[4 * c4 + 3] = v.w;
+            }
+        } else {
+            for (int l = tid & 15; l < d; l += 16) dst[l] = src[l];
+        }
+    }
+    __syncthreads();
+    for (int r = tid; r < rows; r += nt) {
+        const float *row = stage + r * ld;
+        float sc = 0.0f;
+#pragma unroll 20
+        for (int l = 0; l < d; ++l) sc = __fmaf_rn(qs[l], row[l], sc);
+        keys[r0 + r] = make_key(ord_from_f32(sc), key_id(keys[r0 + r]));
+    }
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) last = atomicAdd(&f.fin_n[2 * q + 1], 1u) == gridDim.x - 1 ? 1u : 0u;
+    __syncthreads();
+    if (!last) return;
+    __threadfence();
+    u64 *ranked = (u64 *)stage;
+    for (int i = tid; i < n_fin; i += nt) ranked[i] = __hip_atomic_load(&keys[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    const int k = f.k;
+    for (int j0 = 0; j0 < n_fin; j0 += nt / 4) {
+        const int j = j0 + (tid >> 2);
+        const u64 mine = j < n_fin ? ranked[j] : ~0ull;
+        const int rank = rank_by_four(ranked, n_fin, mine, tid & 3);
+        if (j < n_fin && (tid & 3) == 0 && rank < k) {
+            f.ids_out[(size_t)q * k + rank] = key_id(mine);
+            f.scores_out[(size_t)q * k + rank] = f32_from_ord(key_ord(mine));
         }
     }
     for (int j = n_fin + tid; j < k; j += nt) { // fewer than k candidates exist
@@ -2437,6 +2512,15 @@ int launch_small_final(const ScanParams &p, const FinishParams &f, bool u8, hipS
     if (stage > region) region = stage;
     const size_t lds = small_final_fixed_bytes(p.R, f.d) + region + 16;
     hipLaunchKernelGGL(small_batch_final_kernel, dim3(p.B), dim3(1024), lds, st, f, p.R, u8 ? 1 : 0, p.scale, p.bias);
+    if (f.reorder && f.rerank_rows > 0) {
+        if (!f.fin_out || !f.fin_n || f.rerank_rows > 1024) { set_error("split re-scoring: bad arguments"); return AVQ_EINVAL; }
+        static LdsLimitOnce attr2;
+        AVQ_TRY(set_max_lds(rerank_split_kernel, &attr2));
+        const size_t rows_b = (size_t)f.rerank_rows * (f.d + 1) * 4, keys_b = (size_t)p.R * 8;
+        const size_t lds2 = (size_t)((f.d + 3) & ~3) * 4 + (rows_b > keys_b ? rows_b : keys_b) + 16;
+        if (lds2 > kMaxDynLds) { set_error("split re-scoring: %d rows of %d values do not fit LDS", f.rerank_rows, f.d); return AVQ_EINVAL; }
+        hipLaunchKernelGGL(rerank_split_kernel, dim3((p.R + f.rerank_rows - 1) / f.rerank_rows, p.B), dim3(1024), lds2, st, f, p.R);
+    }
     AVQ_HIP(hipGetLastError());
     return AVQ_OK;
 }

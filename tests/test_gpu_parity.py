@@ -328,9 +328,11 @@ def test_small_batch_paths_agree_with_oracle(case, lut_mode):
         oi, os_ = oracle.search(case["x"], case["cb"], case["codes"], case["bits"], q, k, R, lut_mode)
         # scan_target_wgs = 2: two workgroups per query, so every wave loops over many blocks
         # select_split: the blocks to score exactly are chosen by several workgroups per query, 5 or 3 blocks each
-        # (the slices start at every alignment of the 16-byte loads), as on a large index
+        # (the slices start at every alignment of the 16-byte loads), as on a large index; rerank_split: the exact
+        # scores of the candidates by several workgroups per query, 7 or 64 candidates each (1000: by one)
         for name, val in (("small_batch_impl", 0), ("small_batch_impl", 1), ("small_batch_max", 1),
-                          ("scan_target_wgs", 2), ("select_split", 5), ("select_split", 3), ("select_split", 8192)):
+                          ("scan_target_wgs", 2), ("select_split", 5), ("select_split", 3), ("select_split", 8192),
+                          ("rerank_split", 7), ("rerank_split", 64), ("rerank_split", 1000)):
             idx.set_tuning(name, val)
             ids, sc = idx.search(qd, k, R, lut_mode)
             np.testing.assert_array_equal(ids.cpu().numpy(), oi, err_msg="%s=%d" % (name, val))
@@ -1098,9 +1100,11 @@ def test_batches_of_8bit_codes_through_block_bounds(M, d, lut_mode):
         idx.set_tuning("scan_prefilter", 0)
         np.testing.assert_array_equal(ids2.cpu().numpy(), oi)
         np.testing.assert_array_equal(sc2.cpu().numpy(), os_)
-        idx.set_tuning("select_split", 37)                        # blocks chosen by five workgroups per query
+        idx.set_tuning("select_split", 37)                        # blocks chosen by five workgroups per query,
+        idx.set_tuning("rerank_split", 16)                        # exact scores by several, sixteen candidates each
         ids3, sc3 = idx.search(qd, k, R, lut_mode)
         idx.set_tuning("select_split", 0)
+        idx.set_tuning("rerank_split", 0)
         np.testing.assert_array_equal(ids3.cpu().numpy(), oi)
         np.testing.assert_array_equal(sc3.cpu().numpy(), os_)
 
