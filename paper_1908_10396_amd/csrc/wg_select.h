@@ -12,7 +12,8 @@ namespace avq {
 typedef unsigned long long u64;
 
 constexpr int kSelBins = 2048;  // histogram bins per pass
-constexpr int kSelList = 1024;  // once this few keys remain in range they are ranked directly
+constexpr int kSelList = 512;   // once this few keys remain in range they are ranked directly (by counting pairs:
+                                // beyond a few hundred keys another pass over the histogram is cheaper)
 constexpr int kSelRegs = 8;     // keys a thread caches in registers (N <= kSelRegs * threads)
 
 struct WgSelectScratch {
