@@ -5,6 +5,8 @@ follows the oracle's operation order, so it is held to exact equality too
 (tighter than the 1e-5 relative tolerance the target states), and the
 tolerance is asserted separately so a regression shows which bar broke.
 """
+import os
+
 import numpy as np
 import pytest
 
@@ -1129,7 +1131,7 @@ def draw_configuration(seed):
     return dict(bits=bits, M=M, d=M * ds, n=n, nq=nq, k=k, R=R, n_leaves=leaves, L=L)
 
 
-@pytest.mark.parametrize("seed", range(64))
+@pytest.mark.parametrize("seed", range(int(os.environ.get("AVQ_DRAWN_CONFIGS", "64"))))
 def test_drawn_configurations_match(seed):
     # shapes, batch sizes, k, R and partitions drawn at random around the thresholds where the search
     # changes its kernels; both table kinds, ids and scores against the oracle's
@@ -1146,6 +1148,14 @@ def test_drawn_configurations_match(seed):
         c = make_case(200 + seed, g["n"], g["d"], g["M"], g["bits"], g["nq"], train_iters=2)
         idx, xd = make_index(c)
         kw, skw = {}, {}
+    # every third configuration with launch shapes that the built-in choices reach on large indexes only
+    trng = np.random.default_rng(5000 + seed)
+    if seed % 3 == 2:
+        for name, val in (("select_split", int(trng.integers(2, 12))), ("rerank_split", int(trng.integers(2, 50))),
+                          ("scan_target_wgs", int(trng.integers(1, 9)))):
+            if trng.random() < 0.6:
+                idx.set_tuning(name, val)
+                msg += " %s=%d" % (name, val)
     qd = dev(c["q"])
     for lut_mode in (0, 1):
         ids, sc = idx.search(qd, g["k"], g["R"], lut_mode, **skw)
