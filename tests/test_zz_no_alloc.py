@@ -68,6 +68,22 @@ def test_noalloc_equals_search_on_consecutive_calls(bits, M, d):
             np.testing.assert_array_equal(ids.cpu().numpy(), wi.cpu().numpy())
             np.testing.assert_array_equal(sc.cpu().numpy(), ws.cpu().numpy())
             assert ids.min().item() >= 0
+    # the same with the selection of the blocks and the exact re-scoring spread over several workgroups per
+    # query (launch shapes of large indexes: their counters live in the scratch array too)
+    for idx in (idx_a, idx_b):
+        idx.set_tuning("select_split", 16)
+        idx.set_tuning("rerank_split", 12)
+    for lut_mode in (avq.LUT_F32, avq.LUT_U8):
+        for idx, qd, k, R in calls:
+            rc, ids, sc = _raw_noalloc(idx, qd.contiguous(), k, R, lut_mode)
+            assert rc == avq.AVQ_OK, avq.lib().avq_last_error()
+            for name in ("select_split", "rerank_split"):
+                idx.set_tuning(name, 1)
+            wi, ws = idx.search(qd.contiguous(), k, R, lut_mode)
+            idx.set_tuning("select_split", 16)
+            idx.set_tuning("rerank_split", 12)
+            np.testing.assert_array_equal(ids.cpu().numpy(), wi.cpu().numpy())
+            np.testing.assert_array_equal(sc.cpu().numpy(), ws.cpu().numpy())
     idx_a.close()
     idx_b.close()
 
