@@ -802,7 +802,7 @@ static int search_leaves_grouped(avq_index *idx, const float *queries, int nq, i
         AVQ_TRY(idx->lists.reserve(sizeof(u64) * (size_t)nq * shape.waves * shape.qt * C));
         pl.lists_ws = idx->lists.as<u64>();
     }
-    const int bound_leaves = idx->tune_bound_leaves > 0 ? std::min(L, idx->tune_bound_leaves) : std::min(L, std::max(8, (L + 11) / 12));
+    const int bound_leaves = idx->tune_bound_leaves > 0 ? std::min(L, idx->tune_bound_leaves) : std::min(L, std::max(8, u8 ? (L + 11) / 12 : (2 * L + 24) / 25));
     ScanParams pi;
     {
         StageTimer t(idx, AVQ_STAGE_SAMPLE, st); // here: margins, bounds from the first leaves, regrouping

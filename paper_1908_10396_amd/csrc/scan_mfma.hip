@@ -512,13 +512,16 @@ adc_mfma_scan_kernel(const ScanParams p)
                         // over leaves the bound comes from a query's first few leaves only and most accumulators
                         // hold a candidate in some lane: no tests that skip, one predicated append per accumulator
                         // (padding slots are told from points afterwards)
+                        // The key is (sum + off + 1) << kIdBits | ~(id - id_base) & kIdMask with id = id0 + c(v); ids of a
+                        // leaf's blocks stay below id_base + 2^kIdBits, so the id part is that of id0 less c(v) and the
+                        // whole key one shift-and-add per accumulator; the store is the only predicated instruction.
+                        const uint32_t kb = ((uint32_t)(off + 1) << kIdBits) + (~(uint32_t)(id0 - id_base) & kIdMask);
 #pragma unroll
                         for (int v = 0; v < 16; ++v) {
-                            if (acc[a][v] > thr) {
-                                const int32_t id = id0 + 32 * (v / 4) + 4 * (v % 4);
-                                *pend = ((uint32_t)(acc[a][v] + off + 1) << kIdBits) | (~(uint32_t)(id - id_base) & kIdMask);
-                                ++pend;
-                            }
+                            const uint32_t key = ((uint32_t)acc[a][v] << kIdBits) + (kb - (uint32_t)(32 * (v / 4) + 4 * (v % 4)));
+                            const bool hit = acc[a][v] > thr;
+                            if (hit) *pend = key;
+                            pend += hit ? 1 : 0;
                         }
                     }
                     int32_t gmax[4];
