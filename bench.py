@@ -82,7 +82,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", default="glove", choices=["tiny", "glove", "glove100", "glove_ivf", "large4", "large8"],
+    ap.add_argument("--config", default="glove", choices=["tiny", "glove", "glove100", "glove8", "glove_ivf", "large4", "large8"],
                     help="workload (default: the Glove-shaped one the headline metric is quoted on)")
     ap.add_argument("--batch", type=int, default=0, help="queries per step (default: the configuration's)")
     ap.add_argument("--n", type=int, default=0, help="override the number of points (debugging)")
@@ -256,19 +256,16 @@ def main():
         adds = (2.0 if nib_tile else 1.0) * nb * scanned * batch
         lds_bytes = (8.0 if nib_tile else 4.0) * nb * scanned * batch
         if tiled and not every_point:
-            # byte tables of six bits, sixteen queries per 16-byte entry: one byte of LDS per query, point and code byte;
-            # entries of four code bytes are added as packed bytes, then spread into 16-bit sums
+            # byte tables of seven bits, sixteen queries per 16-byte entry: one byte of LDS per query, point and code byte;
+            # entries of two code bytes are added as packed bytes, then spread into 16-bit sums
             # byte-sized integer additions, four to a 32-bit lane operation: 256 CUs x 4 SIMDs x 32 lanes x 2.4 GHz x 4
             r = {"bound": "alu", "achieved": 2.0 * M * scanned * batch / (ms * 1e-3) / 1e12, "peak": VALU_PEAK_TOPS * 4,
-                 "unit": "TOP/s", "traffic": None, "kernel": "block_bound_tile_kernel<%d>" % nb, "avg_launch_ms": ms,
-                 "valu_issue_util": 1421.0 * 64 * ((scanned + 255) // 256) * ((batch + 15) // 16) / (ms * 1e-3) / 1e12 / VALU_PEAK_TOPS
-                                    if nb == 32 else None,
+                 "unit": "TOP/s", "traffic": None, "kernel": "block_bound_tile_kernel<%d,2>" % nb, "avg_launch_ms": ms,
                  "note": "the method's M lookups + M additions per query and point against the peak of byte-sized integer adds "
                          "(four to a 32-bit lane operation: 4 x 78.6 TOP/s); the kernel reads one 16-byte LDS entry per point and "
-                         "code byte for sixteen queries, adds the entries of four code bytes as packed bytes and forms block maxima "
-                         "of these 6-bit table sums (bounds); exact scores are formed afterwards for the blocks that can reach the "
-                         "R-th best. valu_issue_util: the 1,421 vector instructions it executes per block of 256 points and tile "
-                         "against one lane operation per lane and clock",
+                         "code byte for sixteen queries, adds the entries of two code bytes as packed bytes and forms block maxima "
+                         "of these 7-bit table sums (bounds); exact scores are formed afterwards for the blocks that can reach the "
+                         "R-th best",
                  "lds_gather": {"achieved_GBs": nb * scanned * batch / (ms * 1e-3) / 1e9, "peak_GBs": LDS_PEAK_GBS,
                                 "frac": nb * scanned * batch / (ms * 1e-3) / 1e9 / LDS_PEAK_GBS},
                  "code_stream_GBs": nb * scanned * ((batch + 15) // 16) / (ms * 1e-3) / 1e9}

@@ -351,7 +351,9 @@ double avq_eta(int32_t d, double T, double norm, int32_t eta_mode);
  * 32768 blocks of 256 points or more), "rerank_split" (1: the exact
  * re-scoring of a query's candidates is done by one workgroup; v >= 2: by
  * several, v candidates each; built in: 64 each for up to 16 queries whose
- * reorder_k rows do not fit one workgroup's LDS at once).
+ * reorder_k rows do not fit one workgroup's LDS at once), "bound_bits" (batches
+ * of 8-bit codes: 6, 7 or 8 bits per entry of the byte tables whose sums bound
+ * a block's scores; built in: 7).
  * Results never depend on these. Returns
  * AVQ_EINVAL for an unknown name. */
 int avq_set_tuning(avq_index *idx, const char *name, int32_t value);

@@ -59,7 +59,7 @@ struct avq_index {
     DevBuf x_own, codes_logical, codes_blocked, assign, perm, leaf_blk;
     // per-call scratch
     DevBuf lut, lut8, scale, bias, partial, cand, leaf_ids, leaf_ip, tmp, thr;
-    int tune_target_wgs = 0, tune_waves = 0, tune_qt = 0, tune_small_batch = -1, tune_small_impl = 0, tune_select_split = 0, tune_rerank_split = 0;
+    int tune_target_wgs = 0, tune_waves = 0, tune_qt = 0, tune_small_batch = -1, tune_small_impl = 0, tune_select_split = 0, tune_rerank_split = 0, tune_bound_bits = 0;
     int tune_mfma = 0; // 0 = use the matrix-core scan where it applies, 1 = never
     int tune_prefilter = 0; // 0 = fp32-table batches go through the 8-bit-table scan where it applies, 1 = never,
                             // 2 = as 0 but odd queries always take the plain scan afterwards (exercises that branch)
@@ -186,6 +186,7 @@ extern "C" int avq_set_tuning(avq_index *idx, const char *name, int32_t value)
     else if (!strcmp(name, "bound_leaves")) idx->tune_bound_leaves = value;
     else if (!strcmp(name, "select_split")) idx->tune_select_split = value;
     else if (!strcmp(name, "rerank_split")) idx->tune_rerank_split = value;
+    else if (!strcmp(name, "bound_bits")) idx->tune_bound_bits = value;
     else { set_error("avq_set_tuning: unknown name '%s'", name); return AVQ_EINVAL; }
     return AVQ_OK;
 }
@@ -1032,8 +1033,12 @@ static int search_small(avq_index *idx, const float *queries, int nq, int k, int
     if (p.sel_split_per > 0) p.sel_hist = w.sel_hist;
     if (tile) {
         p.bound_tile = 16;
-        p.bound_levels = 63;
-        p.bound_shift = 2;
+        // Entries of 6, 7 or 8 bits (tuning "bound_bits"): each bit more halves the width of the bounds, so fewer
+        // blocks are scored exactly, and halves how many entries the full scan adds as packed bytes before it must
+        // spread them into 16-bit sums. Seven is the best of the three at 1.2 and at 50 million points.
+        const int bits_e = idx->tune_bound_bits >= 6 && idx->tune_bound_bits <= 8 ? idx->tune_bound_bits : 7;
+        p.bound_levels = (1 << bits_e) - 1;
+        p.bound_shift = 8 - bits_e;
         p.blocks_per_chunk = block_bound_tile_chunk(idx->n_blocks, nq);
     }
     if (bounds) {

@@ -1374,9 +1374,11 @@ block_bound_kernel(const ScanParams p)
 
 // The same block maxima for a batch: a workgroup holds the byte tables of sixteen queries in LDS, side by side in
 // every entry (16 bytes per byte position and byte value: one 16-byte read serves sixteen queries), and its
-// waves take the blocks of one chunk of the index in turn. Table entries are at most 63 here (six bits), so the
-// entries of four byte positions are added as packed bytes before they are spread into 16-bit sums: sums of 32
-// positions stay below 2^11. One 32-bit store per query and block.
+// waves take the blocks of one chunk of the index in turn. Table entries are at most 63 (six bits, GROUP = 4), so
+// that the entries of four byte positions are added as packed bytes before they are spread into 16-bit sums, at
+// most 127 (seven bits, GROUP = 2: two positions per packed sum, bounds half as wide, so a third as many blocks
+// are scored exactly afterwards) or the full 8 bits (GROUP = 1: every entry spread by itself). One 32-bit store
+// per query and block.
 typedef unsigned short pk_u16 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b)
 {
@@ -1384,10 +1386,11 @@ __device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b)
     return *(const uint32_t *)&r;
 }
 
-template <int NBT>
+template <int NBT, int GROUP>
 __global__ void __launch_bounds__(1024)
 block_bound_tile_kernel(const ScanParams p)
 {
+    static_assert(GROUP == 4 || GROUP == 2 || GROUP == 1, "packed sums of four or two entries, or none");
     static_assert(NBT != 0 && NBT <= 32, "specialised code sizes only");
     extern __shared__ __align__(16) unsigned char dyn_smem[];
     const uint4 *tbl = (const uint4 *)dyn_smem; // [NBT][256] entries of 16 queries
@@ -1426,9 +1429,19 @@ block_bound_tile_kernel(const ScanParams p)
         for (int j = 0; j < NBT / 4; ++j) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                uint4 sum = add4(add4(entry(regs.rows[j].x, i, 4 * j), entry(regs.rows[j].y, i, 4 * j + 1)),
-                                 add4(entry(regs.rows[j].z, i, 4 * j + 2), entry(regs.rows[j].w, i, 4 * j + 3)));
-                spread(i, sum);
+                const uint4 lo2 = add4(entry(regs.rows[j].x, i, 4 * j), entry(regs.rows[j].y, i, 4 * j + 1));
+                const uint4 hi2 = add4(entry(regs.rows[j].z, i, 4 * j + 2), entry(regs.rows[j].w, i, 4 * j + 3));
+                if constexpr (GROUP == 4) {
+                    spread(i, add4(lo2, hi2));
+                } else if constexpr (GROUP == 2) {
+                    spread(i, lo2);
+                    spread(i, hi2);
+                } else {
+                    spread(i, entry(regs.rows[j].x, i, 4 * j));
+                    spread(i, entry(regs.rows[j].y, i, 4 * j + 1));
+                    spread(i, entry(regs.rows[j].z, i, 4 * j + 2));
+                    spread(i, entry(regs.rows[j].w, i, 4 * j + 3));
+                }
                 // keeps a point's four reads together and the sums where they are: left alone the compiler reads
                 // every entry of the block first and spills
                 asm volatile("" : "+v"(even[i][0]), "+v"(even[i][1]), "+v"(even[i][2]), "+v"(even[i][3]),
@@ -1440,7 +1453,14 @@ block_bound_tile_kernel(const ScanParams p)
             for (int i = 0; i < 4; ++i) {
                 uint4 sum = entry(regs.tails[0], i, (NBT / 4) * 4);
 #pragma unroll
-                for (int tt = 1; tt < NBT % 4; ++tt) sum = add4(sum, entry(regs.tails[tt], i, (NBT / 4) * 4 + tt));
+                for (int tt = 1; tt < NBT % 4; ++tt) {
+                    if ((GROUP == 2 && tt == 2) || GROUP == 1) { // the third of three goes by itself
+                        spread(i, sum);
+                        sum = entry(regs.tails[tt], i, (NBT / 4) * 4 + tt);
+                    } else {
+                        sum = add4(sum, entry(regs.tails[tt], i, (NBT / 4) * 4 + tt));
+                    }
+                }
                 spread(i, sum);
             }
         }
@@ -2325,10 +2345,10 @@ int launch_block_bound(const ScanParams &p, int waves, hipStream_t st, bool look
     }
 }
 
-template <int NBT>
+template <int NBT, int GROUP>
 static int launch_block_bound_tile_one(const ScanParams &p, hipStream_t st)
 {
-    auto kern = block_bound_tile_kernel<NBT>;
+    auto kern = block_bound_tile_kernel<NBT, GROUP>;
     static LdsLimitOnce attr_done;
     AVQ_TRY(set_max_lds(kern, &attr_done));
     const int tiles = (p.B + 15) / 16;
@@ -2351,13 +2371,23 @@ int block_bound_tile_chunk(int64_t n_blocks, int B)
 
 int launch_block_bound_tile(const ScanParams &p, hipStream_t st)
 {
+    if (p.bound_tile != 16 || (p.bound_levels != 63 && p.bound_levels != 127 && p.bound_levels != 255)) {
+        set_error("block bounds: tiles of 16 queries take byte tables of 63, 127 or 255 levels");
+        return AVQ_EINVAL;
+    }
+    const int group = p.bound_levels == 63 ? 4 : (p.bound_levels == 127 ? 2 : 1);
+#define AVQ_TILE_CASE(NB_)                                                                     \
+    case NB_:                                                                                  \
+        return group == 4 ? launch_block_bound_tile_one<NB_, 4>(p, st)                         \
+                          : (group == 2 ? launch_block_bound_tile_one<NB_, 2>(p, st) : launch_block_bound_tile_one<NB_, 1>(p, st));
     switch (p.NB) {
-    case 8: return launch_block_bound_tile_one<8>(p, st);
-    case 13: return launch_block_bound_tile_one<13>(p, st);
-    case 25: return launch_block_bound_tile_one<25>(p, st);
-    case 32: return launch_block_bound_tile_one<32>(p, st);
+        AVQ_TILE_CASE(8)
+        AVQ_TILE_CASE(13)
+        AVQ_TILE_CASE(25)
+        AVQ_TILE_CASE(32)
     default: set_error("block bounds: unsupported code size %d", p.NB); return AVQ_EINVAL;
     }
+#undef AVQ_TILE_CASE
 }
 
 int launch_select_bound_blocks(const ScanParams &p, const FinishParams &f, bool u8, hipStream_t st)
@@ -2388,8 +2418,10 @@ static int launch_rescan_listed_one(const ScanParams &p, const FinishParams &f, 
     AVQ_TRY(set_max_lds(kern, &attr_done));
     const int waves = 4;
     const size_t lds = NIB ? (size_t)2 * p.NB * 16 * (U8 ? 1 : 4) : (size_t)p.NB * 256 * 4;
-    // a wave per listed block while there are few (the usual case), in turns beyond
-    const int64_t gx = std::min<int64_t>((p.n_blocks + waves - 1) / waves, std::max<int64_t>(16, 256 / p.B));
+    // a wave per listed block while there are few (the usual case), in turns beyond; every workgroup builds the
+    // query's tables for itself, so batches of thousands of queries get one or two workgroups per query
+    const int64_t per_query = std::max<int64_t>(256 / p.B, std::min<int64_t>(16, std::max<int64_t>(1, 16384 / p.B)));
+    const int64_t gx = std::min<int64_t>((p.n_blocks + waves - 1) / waves, per_query);
     hipLaunchKernelGGL(kern, dim3((unsigned)gx, p.B), dim3(waves * 64), lds, st, p, f);
     AVQ_HIP(hipGetLastError());
     return AVQ_OK;

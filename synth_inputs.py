@@ -79,6 +79,9 @@ CONFIGS = {
     # the paper's 100-bit setting on the same data: 25 subspaces of 4 dims x 16 codewords
     "glove100": dict(n=1_183_514, d=100, M=25, bits=4, T=0.2, nq=10_000, k=10, reorder_k=100,
                      kind="mixture", n_comp=1000, sigma=0.3, seed=1),
+    # 8-bit codes on the same data: 25 subspaces of 4 dims x 256 codewords (200 bits, 25 B/point)
+    "glove8": dict(n=1_183_514, d=100, M=25, bits=8, T=0.2, nq=10_000, k=10, reorder_k=100,
+                   kind="mixture", n_comp=1000, sigma=0.3, seed=1),
     "glove_ivf": dict(n=1_183_514, d=100, M=50, bits=4, T=0.2, nq=10_000, k=10, reorder_k=100,
                       kind="mixture", n_comp=1000, sigma=0.3, seed=1, n_leaves=2000,
                       leaves_to_search=100),

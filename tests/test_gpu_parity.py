@@ -1103,10 +1103,12 @@ def test_batches_of_8bit_codes_through_block_bounds(M, d, lut_mode):
         np.testing.assert_array_equal(ids2.cpu().numpy(), oi)
         np.testing.assert_array_equal(sc2.cpu().numpy(), os_)
         idx.set_tuning("select_split", 37)                        # blocks chosen by five workgroups per query,
-        idx.set_tuning("rerank_split", 16)                        # exact scores by several, sixteen candidates each
+        idx.set_tuning("rerank_split", 16)                        # exact scores by several, sixteen candidates each,
+        idx.set_tuning("bound_bits", 6 if k == 10 else 8)         # byte tables of six or eight bits (built in: seven)
         ids3, sc3 = idx.search(qd, k, R, lut_mode)
         idx.set_tuning("select_split", 0)
         idx.set_tuning("rerank_split", 0)
+        idx.set_tuning("bound_bits", 0)
         np.testing.assert_array_equal(ids3.cpu().numpy(), oi)
         np.testing.assert_array_equal(sc3.cpu().numpy(), os_)
 
