@@ -755,6 +755,7 @@ leaf_bound_kernel(const ScanParams p, int cap_blocks, uint32_t *__restrict__ bou
     __shared__ __align__(16) unsigned char tables[2 * NBT * 16 * (U8 ? 1 : 4)];
     __shared__ int first_blk[65], blk_of[65]; // probed leaf j: its blocks start at blk_of[j], at position first_blk[j] here
     __shared__ int wave_cnt[2][n_waves], short_n;
+    __shared__ uint32_t ord_max; // the largest ordering value: no search needs to look above it
     uint32_t *ords = (uint32_t *)dyn_smem;      // [cap_blocks * 256], 0 = no point
     uint32_t *shortlist = ords + (size_t)cap_blocks * 256; // [kShort]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -778,10 +779,12 @@ leaf_bound_kernel(const ScanParams p, int cap_blocks, uint32_t *__restrict__ bou
         }
         first_blk[Lb] = at;
         short_n = 0;
+        ord_max = 0u;
     }
     __syncthreads();
     const int total = first_blk[Lb];
     const float scale = U8 ? p.scale[q] : 0.0f, bias = U8 ? p.bias[q] : 0.0f;
+    uint32_t my_max = 0u;
     for (int b = wave; b < total; b += n_waves) {
         int j = 0;
         while (b >= first_blk[j + 1]) ++j;
@@ -800,9 +803,16 @@ leaf_bound_kernel(const ScanParams p, int cap_blocks, uint32_t *__restrict__ bou
         for (int i = 0; i < 4; ++i) {
             const float sc = U8 ? __fmaf_rn((float)(int)acci[i], scale, __fadd_rn(bias, ip)) : __fadd_rn(accf[i], ip);
             ov[i] = idv[i] >= 0 ? ord_from_f32(sc) : 0u;
+            my_max = ov[i] > my_max ? ov[i] : my_max;
         }
         ((uint4 *)(ords + (size_t)b * 256))[lane] = o;
     }
+#pragma unroll
+    for (int m = 32; m > 0; m >>= 1) {
+        const uint32_t om = (uint32_t)__shfl_xor((int)my_max, m, 64);
+        my_max = om > my_max ? om : my_max;
+    }
+    if (lane == 0 && my_max) atomicMax(&ord_max, my_max);
     __syncthreads();
     const int n = total * 256;
     // number of a[at(i)], i < m, that are >= v (v >= 1: empty slots never count), known to every thread;
@@ -828,9 +838,13 @@ leaf_bound_kernel(const ScanParams p, int cap_blocks, uint32_t *__restrict__ bou
         parity ^= 1;
         return tot;
     };
-    // largest v in [lo, 2^32) with at least R values >= v, given that lo has
+    // largest v in [lo, 2^32) with at least R values >= v, given that lo has. No value is above ord_max; and the R-th
+    // best of thousands of scores is mostly within a factor of two of the best one: when the ordering value one
+    // binade below the maximum still has R values at or above it, the search starts there (23 rounds instead of 32).
+    const uint32_t top = ord_max;
     auto rth_best = [&](const uint32_t *a, int m, int R, uint32_t lo, auto at) -> uint32_t {
-        uint32_t hi = 0xffffffffu; // no value reaches it
+        uint32_t hi = top == 0xffffffffu ? top : top + 1u; // no value reaches it
+        if (top > 0x80800000u && top - 0x00800000u > lo && count_ge(a, m, top - 0x00800000u, at) >= R) lo = top - 0x00800000u;
         while (hi - lo > 1u) {
             const uint32_t mid = lo + ((hi - lo) >> 1);
             if (count_ge(a, m, mid, at) >= R) lo = mid; else hi = mid;
