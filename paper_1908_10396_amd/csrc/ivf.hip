@@ -164,6 +164,19 @@ leaf_select_tile_kernel(const float *__restrict__ centers_t, int n_leaves, int d
             return cn;
         };
         uint32_t lo = 0u, hi = 0xffffffffu; // count_ge(lo) >= want > count_ge(hi)
+        if (in_regs) {
+            // no score is above the best one, and the L-th best of a few thousand is mostly within a factor of two
+            // of it: then the search covers one binade (23 rounds instead of 32)
+            uint32_t top = 0u;
+#pragma unroll
+            for (int i = 0; i < kReg; ++i) top = mine[i] > top ? mine[i] : top;
+            for (int m = 32; m > 0; m >>= 1) {
+                const uint32_t o_top = (uint32_t)__shfl_xor((int)top, m, 64);
+                top = o_top > top ? o_top : top;
+            }
+            if (top != 0xffffffffu) hi = top + 1u;
+            if (top > 0x80800000u && count_ge(top - 0x00800000u) >= want) lo = top - 0x00800000u;
+        }
         while (hi - lo > 1u) {
             const uint32_t mid = lo + ((hi - lo) >> 1);
             if (count_ge(mid) >= want) lo = mid; else hi = mid;
