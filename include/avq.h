@@ -319,7 +319,7 @@ double avq_eta(int32_t d, double T, double norm, int32_t eta_mode);
  * the most workgroups per query of the block-maxima scan), "scan_waves"
  * (waves per scan workgroup), "scan_qt" (queries per tile), "small_batch_max"
  * (v > 0: batches of fewer than v queries on a flat index take the block-maxima
- * path; 1 disables that path; built in: 36 with 4-bit codes; with 8-bit codes 9, or where batches take their block
+ * path; 1 disables that path; built in: 36 with 4-bit codes (21 from 12000 blocks of 256 points on); with 8-bit codes 9, or where batches take their block
  * bounds sixteen queries at a time, up to 33 while queries x blocks of 256 points stay below 120000; on a partitioned index: fewer than v
  * queries take the block maxima of their probed leaves; built in: 81), "small_batch_impl" (0: built in: where
  * the code size has the kernels for it (8, 13, 25 or 32 code bytes per point) the full scan records, per block

@@ -1230,7 +1230,7 @@ extern "C" int avq_search(avq_index *idx, const float *queries, int32_t nq, int3
     // 8-bit codes: a query by itself costs a scan of its own, sixteen together about one scan and a half (byte
     // tables side by side): the tile of sixteen wins from about 120,000 query-blocks on (24 queries at 1.2 million
     // points, 4 at 8 million), where the code size has the kernels for it; else up to 8 queries
-    int small_max = c.bits == 4 ? 35 : 8;
+    int small_max = c.bits == 4 ? (idx->n_blocks < 12000 ? 35 : 20) : 8; // 10 million points: measured crossover near 20
     if (c.bits == 8 && block_bound_supported(idx->NB, c.bits) && idx->tune_small_impl == 0)
         small_max = (int)std::min<int64_t>(32, std::max<int64_t>(1, 120000 / std::max<int64_t>(1, idx->n_blocks)));
     if (idx->tune_small_batch >= 0) small_max = idx->tune_small_batch;
