@@ -178,7 +178,7 @@ int avq_update_leaf_centers(avq_index *idx, const float *x, int64_t n, int32_t m
  *    sorted lists: it compares against a bound guessed from a sample of the
  *    points and checked afterwards; a query whose guess fails is scanned
  *    again, so results never depend on it.) Large batches on a partitioned
- *    index of 4-bit codes (131072 (query, probed leaf) pairs or more, 16
+ *    index of 4-bit codes (100000 (query, probed leaf) pairs or more, 16
  *    leaves or more per query; see avq_set_tuning) are regrouped by leaf: a leaf's codes are scored once per 32 of the queries
  *    that probe it (8-bit tables, matrix cores), every point whose estimate
  *    fma(sum, scale, bias + <q, center>) can reach the R-th best score of the
@@ -345,7 +345,7 @@ double avq_eta(int32_t d, double T, double norm, int32_t eta_mode);
  * against; "scan_prefilter" = 1 also switches that regrouped scan off,
  * "prefilter_cap" is its kept keys per query), "group_min_pairs" (queries x
  * probed leaves from which a batch on a partitioned index is regrouped by
- * leaf; built in: 131072, below that one workgroup per query is faster),
+ * leaf; built in: 100000, below that one workgroup per query is faster),
  * "select_split" (block-maxima path: 1: one workgroup per query selects the
  * blocks to score exactly; v >= 2: several workgroups per query do, v blocks
  * of the index each; built in: 8192 each for up to 16 queries on an index of

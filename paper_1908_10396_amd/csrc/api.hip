@@ -750,7 +750,7 @@ static bool use_grouped_leaves(const avq_index *idx, int nq, int L, int R)
 {
     // below about 1.3e5 pairs (1,300 queries x 100 leaves) one workgroup per query is faster: regrouping, bounds and
     // the hand-over of kept points cost a fixed 0.2 ms
-    const int64_t min_pairs = idx->tune_group_min > 0 ? idx->tune_group_min : 131072;
+    const int64_t min_pairs = idx->tune_group_min > 0 ? idx->tune_group_min : 100000;
     return idx->tune_prefilter != 1 && idx->tune_mfma == 0 && idx->cfg.n_leaves > 0 && nq >= 64 && nq <= (1 << 16) &&
            (int64_t)nq * L >= min_pairs &&
            scan_mfma_supported(idx->NB, idx->cfg.bits) && idx->cfg.M <= 64 && L >= 16 && L <= 512 &&

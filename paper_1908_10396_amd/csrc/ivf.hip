@@ -296,7 +296,7 @@ int launch_leaf_select(const float *centers_t, int n_leaves, int d, const float 
                        int cnt_stride)
 {
     const int ns = (L + 63) / 64;
-    if (nq >= 2048) {
+    if (nq >= 768) {
         const size_t lds = (size_t)kLeafTile * n_leaves * 4 + (size_t)8 * L * 8;
         if (lds <= kMaxDynLds) {
             static LdsLimitOnce tile_attr_done;

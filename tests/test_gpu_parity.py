@@ -573,7 +573,7 @@ def test_leaf_select_for_batches_matches(ivf_batch_case):
 
 @pytest.mark.parametrize("which", ["d100", "d32"])
 def test_leaf_select_for_thousands_of_queries_matches(ivf_case, ivf_batch_case, which):
-    # from 2,048 queries on a workgroup scores the leaves for eight queries at once; the last workgroup here
+    # from 768 queries on a workgroup scores the leaves for eight queries at once; the last workgroup here
     # holds two queries. d = 100 leaves a tail after the chunks of eight dimensions
     c = ivf_case if which == "d100" else ivf_batch_case
     idx, _ = make_ivf_index(c)
@@ -599,7 +599,7 @@ def test_partitioned_batches_grouped_by_leaf(ivf_batch_case, lut_mode, variant):
     # "odd_back" / "small_buffers": every other query, or most of them, handed back to that scan
     c = ivf_batch_case
     idx, xd = make_ivf_index(c)
-    idx.set_tuning("group_min_pairs", 1)   # regroup whatever the batch size (built in: from 131,072 pairs)
+    idx.set_tuning("group_min_pairs", 1)   # regroup whatever the batch size (built in: from 100,000 pairs)
     if variant == "plain":
         idx.set_tuning("scan_prefilter", 1)
     elif variant == "odd_back":
