@@ -278,7 +278,8 @@ int avq_debug_lut(avq_index *idx, const float *queries, int32_t nq, int32_t lut_
 int avq_debug_adc_scores(avq_index *idx, const float *queries, int32_t nq, int32_t lut_mode,
                          void *scores_out, void *hip_stream);
 /* Leaf selection alone: leaf_ids_out int32 [nq][L], leaf_ip_out fp32 [nq][L],
- * device pointers; best leaf first. */
+ * device pointers; best leaf first. Up to 32 queries run the kernels that
+ * avq_search uses for a few queries, more run those of its batch path. */
 int avq_debug_leaf_select(avq_index *idx, const float *queries, int32_t nq, int32_t L,
                           int32_t *leaf_ids_out, float *leaf_ip_out, void *hip_stream);
 
@@ -319,7 +320,8 @@ double avq_eta(int32_t d, double T, double norm, int32_t eta_mode);
  * the most workgroups per query of the block-maxima scan), "scan_waves"
  * (waves per scan workgroup), "scan_qt" (queries per tile), "small_batch_max"
  * (v > 0: batches of fewer than v queries on a flat index take the block-maxima
- * path; 1 disables that path; built in: 36 with 4-bit codes (21 from 12000 blocks of 256 points on); with 8-bit codes 9, or where batches take their block
+ * path; 1 disables that path; built in with 4-bit codes: from measured costs of the two paths, about 44 at 1.2 million
+ * points, 21 at 10 million, 200 at 100000, thousands on indexes of a few thousand points; with 8-bit codes 9, or where batches take their block
  * bounds sixteen queries at a time, up to 33 while queries x blocks of 256 points stay below 120000; on a partitioned index: fewer than v
  * queries take the block maxima of their probed leaves; built in: 81), "small_batch_impl" (0: built in: where
  * the code size has the kernels for it (8, 13, 25 or 32 code bytes per point) the full scan records, per block

@@ -1230,7 +1230,22 @@ extern "C" int avq_search(avq_index *idx, const float *queries, int32_t nq, int3
     // 8-bit codes: a query by itself costs a scan of its own, sixteen together about one scan and a half (byte
     // tables side by side): the tile of sixteen wins from about 120,000 query-blocks on (24 queries at 1.2 million
     // points, 4 at 8 million), where the code size has the kernels for it; else up to 8 queries
-    int small_max = c.bits == 4 ? (idx->n_blocks < 12000 ? 35 : 20) : 8; // 10 million points: measured crossover near 20
+    // 4-bit codes: the per-query path costs about 40 us + (0.1 + 0.00093 x blocks) us per query, the batch path
+    // 150 us + 0.017 us per block up to a few hundred queries -- or 600 us on an index so small that its bounds
+    // cannot be guessed from the class maxima of a sample and sorted lists take nearly every point. Measured
+    // crossovers: 36 to 44 queries at 1.2 million points, 20 at 10 million, about 200 at 100,000, thousands at
+    // 10,000 points.
+    int small_max = c.bits == 4 ? (idx->n_blocks < 12000 ? 35 : 20) : 8; // code sizes without kernels of their own: as measured at first
+    if (c.bits == 4 && small_uses_bounds(idx)) {
+        const double nb = (double)idx->n_blocks;
+        double batch_us = 150.0 + 0.017 * nb;
+        ScanParams plan, sample;
+        fill_scan_params(idx, nq, R, ns, &plan);
+        scan_mfma_plan(nq, idx->n_blocks, idx->tune_target_wgs, &plan);
+        const bool guessed = scan_mfma_sample_plan(plan, &sample) && sample.n_chunks * 32 >= 8 * sample.R && sample.n_chunks * 32 <= 8192;
+        if (!guessed) batch_us = 600.0;
+        small_max = (int)std::min(4096.0, std::max(8.0, (batch_us - 40.0) / (0.1 + 0.00093 * nb)));
+    }
     if (c.bits == 8 && block_bound_supported(idx->NB, c.bits) && idx->tune_small_impl == 0)
         small_max = (int)std::min<int64_t>(32, std::max<int64_t>(1, 120000 / std::max<int64_t>(1, idx->n_blocks)));
     if (idx->tune_small_batch >= 0) small_max = idx->tune_small_batch;
@@ -1569,6 +1584,11 @@ extern "C" int avq_debug_leaf_select(avq_index *idx, const float *queries, int32
     if (!queries || nq < 1 || !leaf_ids_out || !leaf_ip_out || L < 1 || L > c.n_leaves || L > AVQ_MAX_SELECT) {
         set_error("avq_debug_leaf_select: bad argument");
         return AVQ_EINVAL;
+    }
+    if (nq <= 32) { // the kernels the few-query search uses
+        AVQ_TRY(idx->tmp.reserve(sizeof(u64) * (size_t)nq * c.n_leaves));
+        return launch_leaf_select_few(idx->centers_t.as<float>(), c.n_leaves, c.d, queries, nq, L, (u64 *)idx->tmp.p,
+                                      leaf_ids_out, leaf_ip_out, (hipStream_t)hip_stream);
     }
     return launch_leaf_select(idx->centers_t.as<float>(), c.n_leaves, c.d, queries, nq, L, leaf_ids_out,
                               leaf_ip_out, (hipStream_t)hip_stream);

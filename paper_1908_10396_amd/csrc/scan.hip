@@ -1063,7 +1063,7 @@ select_listed_blocks_kernel(const LeafBlockList list, int R, int32_t *__restrict
         // the usual case, a few hundred blocks: a thread per block ranks its key by counting (keys are distinct)
         __shared__ u64 t1_s;
         const u64 mine = tid < n ? bm[tid] : 0ull;
-        sel->list[tid] = mine;
+        if (tid < kSelList) sel->list[tid] = mine; // the list holds kSelList keys; the threads beyond hold none
         if (tid == 0) t1_s = 1ull; // fewer than R blocks with a point: all of them
         __syncthreads();
         int rank = 0;

@@ -11,7 +11,7 @@ namespace avq {
 
 typedef unsigned long long u64;
 
-constexpr int kSelBins = 2048;  // histogram bins per pass
+constexpr int kSelBins = 2048;  // histogram bins per pass (a power of two: the bin index is packed into 11 bits)
 constexpr int kSelList = 512;   // once this few keys remain in range they are ranked directly (by counting pairs:
                                 // beyond a few hundred keys another pass over the histogram is cheaper)
 constexpr int kSelRegs = 8;     // keys a thread caches in registers (N <= kSelRegs * threads)
@@ -22,7 +22,11 @@ struct WgSelectScratch {
     u64 red_max[16], red_min[16];
     uint32_t red_cnt[16];
     uint32_t wave_sum[16];
-    uint32_t found_bin, found_above, found_pop, list_cnt;
+    u64 found;       // published by the thread that owns the bin of the wanted key, in ONE word: population of the bin
+                     // << 32 | keys above the bin << 11 | bin. As three adjacent 32-bit words (which the compiler stores
+                     // and loads with one 96-bit LDS access) a 16-wave workgroup returned a wrong threshold about once
+                     // in ten calls on MI355X; a second barrier before the loads, or words placed apart, removed that.
+    uint32_t list_cnt;
     u64 result;
 };
 
@@ -30,7 +34,7 @@ struct WgSelectScratch {
 // Keys equal to 0 are empty slots and never selected. Returns the R-th largest
 // non-empty key, or 1 when there are fewer than R of them (so "key >= result"
 // selects min(R, count) keys; keys are distinct). The keys are read from global
-// memory once when N <= kSelRegs * blockDim.x, else once per pass.
+// memory once when N <= kSelRegs * blockDim.x, else once per pass. R <= 2^21, N < 2^32.
 __device__ inline u64 wg_select_threshold(const u64 *__restrict__ keys, int64_t N, int R, WgSelectScratch *s)
 {
     const int tid = threadIdx.x, nt = blockDim.x;
@@ -134,13 +138,14 @@ __device__ inline u64 wg_select_threshold(const u64 *__restrict__ keys, int64_t 
             const int b = b0 + j;
             if (b >= kSelBins) continue;
             const uint32_t h = s->hist[b];
-            if (above < need && need <= above + h) { s->found_bin = (uint32_t)b; s->found_above = above; s->found_pop = h; }
+            if (above < need && need <= above + h) s->found = ((u64)h << 32) | (above << 11) | (uint32_t)b; // above < R <= 2^21
             above += h;
         }
         __syncthreads();
-        const uint32_t fb = s->found_bin;
-        need -= s->found_above;
-        pop = s->found_pop;
+        const u64 found = s->found;
+        const uint32_t fb = (uint32_t)found & (uint32_t)(kSelBins - 1);
+        need -= ((uint32_t)found >> 11);
+        pop = (uint32_t)(found >> 32);
         const u64 nlo = lo + ((u64)fb << shift);
         u64 nhi = nlo + (((u64)1 << shift) - 1ull);
         if (nhi > hi || nhi < nlo) nhi = hi;

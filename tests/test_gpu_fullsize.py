@@ -151,3 +151,37 @@ def test_full_partitioned_batch_matches_oracle_on_sampled_queries(lut_mode):
     i16, s16 = idx.search(qd[4090:4106], k, R, lut_mode, leaves_to_search=L)
     np.testing.assert_array_equal(i16.cpu().numpy(), ids[4090:4106])
     np.testing.assert_array_equal(s16.cpu().numpy(), sc[4090:4106])
+    # many times over: one call in ten once came back with a row wrong (the 16 waves of the workgroup that selects
+    # the leaves did not all see the same narrowed key range)
+    for rep in range(12):
+        lo = 100 + 613 * rep
+        for nq in (16, 80):
+            ib, sb = idx.search(qd[lo:lo + nq], k, R, lut_mode, leaves_to_search=L)
+            np.testing.assert_array_equal(ib.cpu().numpy(), ids[lo:lo + nq], err_msg="rows %d..%d" % (lo, lo + nq))
+            np.testing.assert_array_equal(sb.cpu().numpy(), sc[lo:lo + nq])
+
+
+def test_leaf_select_for_few_queries_is_repeatable():
+    # up to 32 queries take a kernel pair of their own (scores by many small workgroups, then one 1024-thread
+    # workgroup per query that selects): same leaves as the batch kernels and the oracle, call after call
+    cfg = si.CONFIGS["glove_ivf"]
+    x = si.make_data(cfg)
+    q = si.make_queries(cfg, 2048)
+    xd, qd = torch.from_numpy(x).cuda(), torch.from_numpy(q).cuda()
+    idx = avq.Index(cfg["d"], cfg["M"], cfg["bits"], T=cfg["T"], n_leaves=cfg["n_leaves"], kmeans_iters=10,
+                    encode_passes=5, seed=cfg["seed"])
+    idx.train(xd[: si.CHUNK])
+    centers = idx.get_leaf_centers()
+    for L in (1, 100, 512):
+        ref_ids, ref_ip = idx.debug_leaf_select(qd, L)
+        ref_ids, ref_ip = ref_ids.cpu().numpy(), ref_ip.cpu().numpy()
+        for qi in (0, 777, 2047):
+            li, lp = oracle.leaf_select(centers, q[qi], L)
+            np.testing.assert_array_equal(ref_ids[qi], li)
+            np.testing.assert_array_equal(ref_ip[qi], lp)
+        for rep in range(60):
+            lo = (53 * rep) % 2000
+            for nq in (1, 5, 16, 32):
+                ids, ip = idx.debug_leaf_select(qd[lo:lo + nq], L)
+                np.testing.assert_array_equal(ids.cpu().numpy(), ref_ids[lo:lo + nq], err_msg="L=%d rows %d..%d" % (L, lo, lo + nq))
+                np.testing.assert_array_equal(ip.cpu().numpy(), ref_ip[lo:lo + nq])
