@@ -99,6 +99,14 @@ def test_large4_batches_of_1024_64_and_1_match_oracle(large4, lut_mode):
         i1, s1 = g["idx"].search(g["qd"][qi:qi + 1], k, R, lut_mode)
         np.testing.assert_array_equal(i1.cpu().numpy()[0], oi[j])
         np.testing.assert_array_equal(s1.cpu().numpy()[0], os_[j])
+    # single- and few-query calls again and again (selection split over many workgroups, the last one finishing):
+    # always the rows of the 1,024-query launch
+    for nq in (1, 3, 12, 20):
+        for rep in range(60):
+            lo = (37 * rep + nq) % (cfg["nq"] - nq)
+            i1, s1 = g["idx"].search(g["qd"][lo:lo + nq], k, R, lut_mode)
+            np.testing.assert_array_equal(i1.cpu().numpy(), ids[lo:lo + nq], err_msg="%d queries from %d, call %d" % (nq, lo, rep))
+            np.testing.assert_array_equal(s1.cpu().numpy(), sc[lo:lo + nq])
 
 
 def test_large4_adc_candidates_without_reranking(large4):
@@ -205,6 +213,12 @@ def test_large8_slice_batches_of_1024_and_1_match_oracle(large8, lut_mode):
         i1, s1 = g["idx"].search(g["qd"][qi:qi + 1], k, R, lut_mode)
         np.testing.assert_array_equal(i1.cpu().numpy()[0], oi[j])
         np.testing.assert_array_equal(s1.cpu().numpy()[0], os_[j])
+    for nq in (1, 2, 5):
+        for rep in range(40):
+            lo = (41 * rep + nq) % (cfg["nq"] - nq)
+            i1, s1 = g["idx"].search(g["qd"][lo:lo + nq], k, R, lut_mode)
+            np.testing.assert_array_equal(i1.cpu().numpy(), ids[lo:lo + nq], err_msg="%d queries from %d, call %d" % (nq, lo, rep))
+            np.testing.assert_array_equal(s1.cpu().numpy(), sc[lo:lo + nq])
 
 
 def test_large8_adc_scores_at_sampled_points(large8):
