@@ -178,6 +178,23 @@ def test_full_partitioned_batch_matches_oracle_on_sampled_queries(lut_mode):
             np.testing.assert_array_equal(ib.cpu().numpy(), ids[lo:lo + nq], err_msg="rows %d..%d" % (lo, lo + nq))
             np.testing.assert_array_equal(sb.cpu().numpy(), sc[lo:lo + nq])
 
+    # 300 leaves: about 870 blocks of 256 points per query, more than the few-query selection of the blocks ranks
+    # directly (it narrows the range of their maxima first)
+    L3 = 300
+    ids3, sc3 = idx.search(qd[:2048], k, R, lut_mode, leaves_to_search=L3)
+    ids3, sc3 = ids3.cpu().numpy(), sc3.cpu().numpy()
+    o3, os3 = oracle.search(x, idx.get_codebooks(), unpack_codes(idx.get_codes(), cfg["M"], cfg["bits"]), cfg["bits"],
+                            q[[5, 2047]], k, R, lut_mode, centers=idx.get_leaf_centers(), assign=idx.get_leaf_assign(),
+                            leaves_to_search=L3)
+    np.testing.assert_array_equal(ids3[[5, 2047]], o3)
+    np.testing.assert_array_equal(sc3[[5, 2047]], os3)
+    for rep in range(10):
+        lo = 11 + 197 * rep
+        for nq in (1, 5, 16):
+            ib, sb = idx.search(qd[lo:lo + nq], k, R, lut_mode, leaves_to_search=L3)
+            np.testing.assert_array_equal(ib.cpu().numpy(), ids3[lo:lo + nq], err_msg="300 leaves, rows %d..%d" % (lo, lo + nq))
+            np.testing.assert_array_equal(sb.cpu().numpy(), sc3[lo:lo + nq])
+
 
 def test_leaf_select_for_few_queries_is_repeatable():
     # up to 32 queries take a kernel pair of their own (scores by many small workgroups, then one 1024-thread
