@@ -374,7 +374,9 @@ def main():
         timing = "HIP event pair around the scan stage of every call (includes the pair's own cost)"
         parts = None
     else:
-        b1_kernel = ("block_bound_kernel<%d>" % nb) if bound_scan else (
+        # a code array beyond the 256 MB Infinity Cache is scanned by the variant with nontemporal loads
+        streamed = ((n + 255) // 256) * 256 * nb > (256 << 20)
+        b1_kernel = (("block_bound_stream_kernel<%d>" if streamed else "block_bound_kernel<%d>") % nb) if bound_scan else (
             ("block_max_nibble_kernel<false,%d>" % (nb if nb in SPECIAL_NB else 0)) if bits == 4 else "block_max_kernel<false,%d>" % nb)
         scan1_us = launches_us(0, avq.LUT_F32)
         timing = "200 launches back to back on the stream inside one HIP event pair"

@@ -356,7 +356,10 @@ double avq_eta(int32_t d, double T, double norm, int32_t eta_mode);
  * several, v candidates each; built in: 64 each for up to 16 queries whose
  * reorder_k rows do not fit one workgroup's LDS at once), "bound_bits" (batches
  * of 8-bit codes: 6, 7 or 8 bits per entry of the byte tables whose sums bound
- * a block's scores; built in: 7).
+ * a block's scores; built in: 7), "stream_loads" (the scan of the whole code
+ * array for one or a few queries: 1 = plain loads, 2 = nontemporal loads and
+ * one block of 256 points per wave; built in: 2 when the code array exceeds
+ * 256 MB, the Infinity Cache, else 1).
  * Results never depend on these. Returns
  * AVQ_EINVAL for an unknown name. */
 int avq_set_tuning(avq_index *idx, const char *name, int32_t value);

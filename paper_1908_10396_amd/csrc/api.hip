@@ -60,6 +60,7 @@ struct avq_index {
     // per-call scratch
     DevBuf lut, lut8, scale, bias, partial, cand, leaf_ids, leaf_ip, tmp, thr;
     int tune_target_wgs = 0, tune_waves = 0, tune_qt = 0, tune_small_batch = -1, tune_small_impl = 0, tune_select_split = 0, tune_rerank_split = 0, tune_bound_bits = 0;
+    int tune_stream_loads = 0; // single-query scan of the code array: 0 = nontemporal loads when the array exceeds the Infinity Cache, 1 = never, 2 = always
     int tune_mfma = 0; // 0 = use the matrix-core scan where it applies, 1 = never
     int tune_prefilter = 0; // 0 = fp32-table batches go through the 8-bit-table scan where it applies, 1 = never,
                             // 2 = as 0 but odd queries always take the plain scan afterwards (exercises that branch)
@@ -187,6 +188,7 @@ extern "C" int avq_set_tuning(avq_index *idx, const char *name, int32_t value)
     else if (!strcmp(name, "select_split")) idx->tune_select_split = value;
     else if (!strcmp(name, "rerank_split")) idx->tune_rerank_split = value;
     else if (!strcmp(name, "bound_bits")) idx->tune_bound_bits = value;
+    else if (!strcmp(name, "stream_loads")) idx->tune_stream_loads = value;
     else { set_error("avq_set_tuning: unknown name '%s'", name); return AVQ_EINVAL; }
     return AVQ_OK;
 }
@@ -545,6 +547,16 @@ static int build_tables(avq_index *idx, const float *queries, int nq, int lut_mo
     return launch_lut(queries, nq, idx->codebooks.as<float>(), c.d, c.M, idx->kc, idx->lut.as<float>(),
                       lut_mode == AVQ_LUT_U8 ? idx->lut8.as<uint8_t>() : nullptr, idx->scale.as<float>(),
                       idx->bias.as<float>(), st);
+}
+
+// The single-query scan reads a code array that does not fit the 256 MB Infinity Cache once per launch:
+// nontemporal loads then (measured: 1.6 GB 288 -> see the design notes; an array that fits stays resident and is
+// loaded the plain way).
+static bool stream_loads_nontemporal(const avq_index *idx)
+{
+    if (idx->tune_stream_loads == 1) return false;
+    if (idx->tune_stream_loads == 2) return true;
+    return (size_t)idx->n_blocks * 256 * (size_t)idx->NB > ((size_t)256 << 20);
 }
 
 static void fill_scan_params(const avq_index *idx, int nq, int R, int ns, ScanParams *p)
@@ -1025,6 +1037,7 @@ static int search_small(avq_index *idx, const float *queries, int nq, int k, int
     p.n_tiles = nq;
     p.n_chunks = 1;
     p.max_wgs = idx->tune_target_wgs;
+    p.nt_loads = stream_loads_nontemporal(idx) ? 1 : 0;
     p.block_bound = w.block_bound;
     p.bound_meta = w.bound_meta;
     p.lut_out = fuse_tables ? w.lut : nullptr;
@@ -1519,7 +1532,8 @@ extern "C" int avq_debug_stream_codes(avq_index *idx, uint32_t *words_out, int64
     if (idx->n <= 0) { set_error("avq_debug_stream_codes: no codes yet"); return AVQ_ESTATE; }
     if (n_blocks_out) *n_blocks_out = idx->n_blocks;
     if (!words_out) return AVQ_OK;
-    return launch_stream_codes(idx->codes_blocked.as<uint8_t>(), idx->n_blocks, idx->NB, words_out, (hipStream_t)hip_stream);
+    return launch_stream_codes(idx->codes_blocked.as<uint8_t>(), idx->n_blocks, idx->NB, words_out, (hipStream_t)hip_stream,
+                               stream_loads_nontemporal(idx));
 }
 
 extern "C" int avq_debug_scan_parts(avq_index *idx, const float *queries, int32_t nq, int32_t lut_mode, int32_t part,
@@ -1552,9 +1566,10 @@ extern "C" int avq_debug_scan_parts(avq_index *idx, const float *queries, int32_
     p.n_tiles = nq;
     p.n_chunks = 1;
     p.max_wgs = idx->tune_target_wgs;
+    p.nt_loads = stream_loads_nontemporal(idx) ? 1 : 0;
     if (bounds) AVQ_TRY(launch_bound_tables(p, u8, st));
     for (int r = 0; r < reps; ++r) {
-        if (part == 1) AVQ_TRY(launch_stream_codes(idx->codes_blocked.as<uint8_t>(), idx->n_blocks, idx->NB, (uint32_t *)w.block_max, st));
+        if (part == 1) AVQ_TRY(launch_stream_codes(idx->codes_blocked.as<uint8_t>(), idx->n_blocks, idx->NB, (uint32_t *)w.block_max, st, stream_loads_nontemporal(idx)));
         else if (bounds) AVQ_TRY(launch_block_bound(p, idx->tune_waves, st, part == 2));
         else AVQ_TRY(launch_block_max(p, u8, idx->tune_waves > 0 ? idx->tune_waves : 4, st));
     }

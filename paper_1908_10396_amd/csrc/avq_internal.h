@@ -138,6 +138,7 @@ struct ScanParams {
     uint32_t *kept_cnt;
     int32_t kept_cap, max_items;
     int32_t leaf_stride;  // partitioned scans: row stride of leaf_ids / leaf_ip when it is not Lp (0: Lp)
+    int32_t nt_loads;     // single-query block bounds: the code stream with nontemporal loads (arrays beyond the Infinity Cache)
     int32_t max_wgs;      // block-max kernels: workgroups per query at most (0 = built-in); waves loop beyond it
     // flat scan of a compacted query list whose length only the device knows (NULL: all B
     // queries are live): the kernel derives tiles and chunks from *active_queries, n_chunks is
@@ -188,7 +189,7 @@ constexpr int kLeafBoundMaxBlocks = 96;
 int launch_leaf_bound(const ScanParams &p, bool u8, int max_leaf_blocks, int mean_leaf_blocks, uint32_t *bound,
                       hipStream_t st);
 // reads the blocked code array once, in the single-query scan's launch shape; out[blk] = xor of the block's words
-int launch_stream_codes(const uint8_t *codes, int64_t n_blocks, int NB, uint32_t *out, hipStream_t st);
+int launch_stream_codes(const uint8_t *codes, int64_t n_blocks, int NB, uint32_t *out, hipStream_t st, bool nt = false);
 // Small batches, after launch_block_max: block selection, scan of the selected blocks,
 // final selection with exact re-scoring and output (three kernels).
 struct SmallMeta { u64 t1; uint32_t n_sel; uint32_t n_cand; };

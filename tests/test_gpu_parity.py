@@ -334,7 +334,8 @@ def test_small_batch_paths_agree_with_oracle(case, lut_mode):
         # scores of the candidates by several workgroups per query, 7 or 64 candidates each (1000: by one)
         for name, val in (("small_batch_impl", 0), ("small_batch_impl", 1), ("small_batch_max", 1),
                           ("scan_target_wgs", 2), ("select_split", 5), ("select_split", 3), ("select_split", 8192),
-                          ("rerank_split", 7), ("rerank_split", 64), ("rerank_split", 1000)):
+                          ("rerank_split", 7), ("rerank_split", 64), ("rerank_split", 1000),
+                          ("stream_loads", 2)):  # the code stream with nontemporal loads, one block per wave (large arrays)
             idx.set_tuning(name, val)
             ids, sc = idx.search(qd, k, R, lut_mode)
             np.testing.assert_array_equal(ids.cpu().numpy(), oi, err_msg="%s=%d" % (name, val))
