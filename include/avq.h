@@ -359,7 +359,8 @@ double avq_eta(int32_t d, double T, double norm, int32_t eta_mode);
  * a block's scores; built in: 7), "stream_loads" (the scan of the whole code
  * array for one or a few queries: 1 = plain loads, 2 = nontemporal loads and
  * one block of 256 points per wave; built in: 2 when the code array exceeds
- * 256 MB, the Infinity Cache, else 1).
+ * 256 MB, the Infinity Cache, and the call has one or two queries, or up to
+ * eight over more than 1 GiB of codes; else 1).
  * Results never depend on these. Returns
  * AVQ_EINVAL for an unknown name. */
 int avq_set_tuning(avq_index *idx, const char *name, int32_t value);

@@ -549,14 +549,18 @@ static int build_tables(avq_index *idx, const float *queries, int nq, int lut_mo
                       idx->bias.as<float>(), st);
 }
 
-// The single-query scan reads a code array that does not fit the 256 MB Infinity Cache once per launch:
-// nontemporal loads then (measured: 1.6 GB 288 -> see the design notes; an array that fits stays resident and is
-// loaded the plain way).
-static bool stream_loads_nontemporal(const avq_index *idx)
+// The scan of the whole code array for one or a few queries reads an array that does not fit the 256 MB Infinity
+// Cache once per query: nontemporal loads and a wave per block then (block_bound_stream_kernel). Measured per call,
+// plain against streamed: 320 MB 80 / 73 us for one query, 127 / 118 for two, equal at four, 614 / 766 at sixteen
+// (the queries of a call share what the caches hold when few workgroups per query walk the array together);
+// 1.6 GB 326 / 262, 606 / 494, 1139 / 967, 2220 / 1899 (eight queries), 3291 / 3765 (sixteen). An array that fits
+// the cache stays resident between calls and is loaded the plain way.
+static bool stream_loads_nontemporal(const avq_index *idx, int nq)
 {
     if (idx->tune_stream_loads == 1) return false;
     if (idx->tune_stream_loads == 2) return true;
-    return (size_t)idx->n_blocks * 256 * (size_t)idx->NB > ((size_t)256 << 20);
+    const size_t bytes = (size_t)idx->n_blocks * 256 * (size_t)idx->NB;
+    return bytes > ((size_t)256 << 20) && (nq <= 2 || (nq <= 8 && bytes > ((size_t)1 << 30)));
 }
 
 static void fill_scan_params(const avq_index *idx, int nq, int R, int ns, ScanParams *p)
@@ -1037,7 +1041,7 @@ static int search_small(avq_index *idx, const float *queries, int nq, int k, int
     p.n_tiles = nq;
     p.n_chunks = 1;
     p.max_wgs = idx->tune_target_wgs;
-    p.nt_loads = stream_loads_nontemporal(idx) ? 1 : 0;
+    p.nt_loads = stream_loads_nontemporal(idx, nq) ? 1 : 0;
     p.block_bound = w.block_bound;
     p.bound_meta = w.bound_meta;
     p.lut_out = fuse_tables ? w.lut : nullptr;
@@ -1533,7 +1537,7 @@ extern "C" int avq_debug_stream_codes(avq_index *idx, uint32_t *words_out, int64
     if (n_blocks_out) *n_blocks_out = idx->n_blocks;
     if (!words_out) return AVQ_OK;
     return launch_stream_codes(idx->codes_blocked.as<uint8_t>(), idx->n_blocks, idx->NB, words_out, (hipStream_t)hip_stream,
-                               stream_loads_nontemporal(idx));
+                               stream_loads_nontemporal(idx, 1));
 }
 
 extern "C" int avq_debug_scan_parts(avq_index *idx, const float *queries, int32_t nq, int32_t lut_mode, int32_t part,
@@ -1566,10 +1570,10 @@ extern "C" int avq_debug_scan_parts(avq_index *idx, const float *queries, int32_
     p.n_tiles = nq;
     p.n_chunks = 1;
     p.max_wgs = idx->tune_target_wgs;
-    p.nt_loads = stream_loads_nontemporal(idx) ? 1 : 0;
+    p.nt_loads = stream_loads_nontemporal(idx, nq) ? 1 : 0;
     if (bounds) AVQ_TRY(launch_bound_tables(p, u8, st));
     for (int r = 0; r < reps; ++r) {
-        if (part == 1) AVQ_TRY(launch_stream_codes(idx->codes_blocked.as<uint8_t>(), idx->n_blocks, idx->NB, (uint32_t *)w.block_max, st, stream_loads_nontemporal(idx)));
+        if (part == 1) AVQ_TRY(launch_stream_codes(idx->codes_blocked.as<uint8_t>(), idx->n_blocks, idx->NB, (uint32_t *)w.block_max, st, stream_loads_nontemporal(idx, nq)));
         else if (bounds) AVQ_TRY(launch_block_bound(p, idx->tune_waves, st, part == 2));
         else AVQ_TRY(launch_block_max(p, u8, idx->tune_waves > 0 ? idx->tune_waves : 4, st));
     }
