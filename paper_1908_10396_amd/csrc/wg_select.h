@@ -14,6 +14,7 @@ typedef unsigned long long u64;
 constexpr int kSelBins = 2048;  // histogram bins per pass (a power of two: the bin index is packed into 11 bits)
 constexpr int kSelList = 512;   // once this few keys remain in range they are ranked directly (by counting pairs:
                                 // beyond a few hundred keys another pass over the histogram is cheaper)
+static_assert((kSelBins & (kSelBins - 1)) == 0 && kSelBins <= 2048, "the bin index travels in 11 bits");
 constexpr int kSelRegs = 8;     // keys a thread caches in registers (N <= kSelRegs * threads)
 
 struct WgSelectScratch {
