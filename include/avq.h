@@ -322,7 +322,7 @@ double avq_eta(int32_t d, double T, double norm, int32_t eta_mode);
  * (v > 0: batches of fewer than v queries on a flat index take the block-maxima
  * path; 1 disables that path; built in with 4-bit codes: from measured costs of the two paths, about 44 at 1.2 million
  * points, 21 at 10 million, 200 at 100000, thousands on indexes of a few thousand points; with 8-bit codes 9, or where batches take their block
- * bounds sixteen queries at a time, up to 33 while queries x blocks of 256 points stay below 120000; on a partitioned index: fewer than v
+ * bounds sixteen queries at a time, up to 33 while queries x blocks of 256 points stay below 120000, and three in any case; on a partitioned index: fewer than v
  * queries take the block maxima of their probed leaves; built in: 81), "small_batch_impl" (0: built in: where
  * the code size has the kernels for it (8, 13, 25 or 32 code bytes per point) the full scan records, per block
  * of 256 points, the largest sum of 8-bit images of the table entries -- a bound of the block's scores -- and

@@ -1264,7 +1264,9 @@ extern "C" int avq_search(avq_index *idx, const float *queries, int32_t nq, int3
         small_max = (int)std::min(4096.0, std::max(8.0, (batch_us - 40.0) / (0.1 + 0.00093 * nb)));
     }
     if (c.bits == 8 && block_bound_supported(idx->NB, c.bits) && idx->tune_small_impl == 0)
-        small_max = (int)std::min<int64_t>(32, std::max<int64_t>(1, 120000 / std::max<int64_t>(1, idx->n_blocks)));
+        // two queries at least: measured per call, per-query path / batch path, at 8, 20 and 50 million points:
+        // 125 / 165, 229 / 399 and 500 / 716 us for two queries, equal for three
+        small_max = (int)std::min<int64_t>(32, std::max<int64_t>(2, 120000 / std::max<int64_t>(1, idx->n_blocks)));
     if (idx->tune_small_batch >= 0) small_max = idx->tune_small_batch;
     const bool small = !ivf && nq <= small_max;
     // the single-query kernels compute short fp32 tables themselves (one launch less)
