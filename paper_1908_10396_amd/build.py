@@ -49,7 +49,8 @@ def build(force=True, verbose=False, jobs=8):
         obj = os.path.join(OBJ, u + ".o")
         if not force and _newer(obj, [src] + headers):
             return obj
-        cmd = [hipcc] + FLAGS + ["-c", src, "-o", obj]
+        # -save-temps=obj leaves the device assembly beside the object: it is checked below, then the extras go
+        cmd = [hipcc] + FLAGS + ["-save-temps=obj", "-c", src, "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         r = subprocess.run(cmd, capture_output=True, text=True)
@@ -57,7 +58,28 @@ def build(force=True, verbose=False, jobs=8):
             raise RuntimeError("hipcc failed for %s:\n%s\n%s" % (u, r.stdout, r.stderr))
         if verbose and r.stderr.strip():
             print(r.stderr, file=sys.stderr)
+        _check_device_code(u)
         return obj
+
+    def _check_device_code(u):
+        # No 96-bit LDS access may be left in a kernel: a value of three adjacent words that one thread
+        # published for its workgroup through such a store and load came out wrong now and then on MI355X
+        # (the selection in wg_select.h; it publishes one 64-bit word since). The compiler forms these
+        # accesses by itself from neighbouring 32-bit ones, so the check is on its output.
+        asm = os.path.join(OBJ, u + "-hip-amdgcn-amd-amdhsa-gfx950.s")
+        bad, kernel = [], "?"
+        if os.path.exists(asm):
+            with open(asm) as f:
+                for line in f:
+                    if line.startswith("_Z") and ":" in line:
+                        kernel = line.split(":")[0]
+                    elif "ds_read_b96" in line or "ds_write_b96" in line:
+                        bad.append(kernel)
+        for f in os.listdir(OBJ):
+            if f.startswith(u + "-hip-") or f.startswith(u + "-host-") or f.startswith(u + ".hip-"):
+                os.remove(os.path.join(OBJ, f))
+        if bad:
+            raise RuntimeError("%s.hip: 96-bit LDS accesses in %s" % (u, ", ".join(sorted(set(bad)))))
 
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         objs = list(ex.map(compile_one, UNITS))
