@@ -270,6 +270,7 @@ def main():
                                 "frac": nb * scanned * batch / (ms * 1e-3) / 1e9 / LDS_PEAK_GBS},
                  "code_stream_GBs": nb * scanned * ((batch + 15) // 16) / (ms * 1e-3) / 1e9}
             r["frac"] = r["achieved"] / r["peak"]
+            r["traffic"], r["traffic_source"] = traffic_from_profiles(r["kernel"], "%s_b%d" % (workload, batch))
             return r
         if n_leaves:
             kern = "adc_scan_kernel<1,false,%d,1>" % (nb if nb in SPECIAL_NB else 0)
@@ -283,6 +284,7 @@ def main():
              "lds_gather": {"achieved_GBs": lds_bytes / (ms * 1e-3) / 1e9, "peak_GBs": LDS_PEAK_GBS,
                             "frac": lds_bytes / (ms * 1e-3) / 1e9 / LDS_PEAK_GBS}}
         r["frac"] = r["achieved"] / r["peak"]
+        r["traffic"], r["traffic_source"] = traffic_from_profiles(kern, "%s_b%d" % (workload, batch))
         return r
 
     def mfma_roofline(ms, kernel, extra):
