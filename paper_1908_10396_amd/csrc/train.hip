@@ -310,6 +310,11 @@ constexpr int kMaxM = 256;
 // codeword of subspace m only changes that subspace's terms, so the terms of the
 // current codewords are kept per subspace and only summed again (in subspace order,
 // never updated in place: no drift) when another subspace is revisited.
+// DS = dimensions per subspace known at compile time (0: any): the point's sub-vector of the
+// subspace at hand then stays in registers while its kc codewords (wave-uniform, read through
+// the scalar cache) pass by, instead of being read again for every codeword from a row that
+// no neighbouring lane shares.
+template <int DS>
 __global__ void __launch_bounds__(128)
 encode_kernel(const float *__restrict__ x, int64_t n, int d, int M, int kc, int bits,
               const float *__restrict__ codebooks, const float *__restrict__ leaf_centers,
@@ -318,9 +323,11 @@ encode_kernel(const float *__restrict__ x, int64_t n, int d, int M, int kc, int 
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
-    const int ds = d / M;
+    const int ds = DS ? DS : d / M;
     const float *xi = x + (size_t)i * d;
     const float *ce = leaf_centers ? leaf_centers + (size_t)leaf_assign[i] * d : nullptr;
+    constexpr int kReg = DS ? DS : 1;
+    double xv_m[kReg], xr_m[kReg]; // DS != 0: x^(m) and x^(m) - center^(m) of the subspace entered last
     uint8_t code[kMaxM];
     double pm_cur[kMaxM], em_cur[kMaxM]; // terms of the current codeword of every subspace
 
@@ -330,15 +337,33 @@ encode_kernel(const float *__restrict__ x, int64_t n, int d, int M, int kc, int 
     const double w = nx2 > 0.0 ? (eta - 1.0) / nx2 : 0.0;
 
     // terms of subspace m for codeword j: pm = <r^(m), x^(m)>, em = ||r^(m)||^2
+    auto enter = [&](int m) {
+        if constexpr (DS != 0) {
+#pragma unroll
+            for (int l = 0; l < DS; ++l) {
+                xv_m[l] = (double)xi[m * DS + l];
+                xr_m[l] = xv_m[l] - (ce ? (double)ce[m * DS + l] : 0.0);
+            }
+        }
+    };
     auto terms = [&](int m, int j, double &pm, double &em) {
         const float *c = codebooks + ((size_t)m * kc + j) * ds;
         pm = 0.0;
         em = 0.0;
-        for (int l = 0; l < ds; ++l) {
-            const double xv = (double)xi[m * ds + l];
-            const double r = (xv - (ce ? (double)ce[m * ds + l] : 0.0)) - (double)c[l];
-            pm += r * xv;
-            em += r * r;
+        if constexpr (DS != 0) {
+#pragma unroll
+            for (int l = 0; l < DS; ++l) {
+                const double r = xr_m[l] - (double)c[l];
+                pm += r * xv_m[l];
+                em += r * r;
+            }
+        } else {
+            for (int l = 0; l < ds; ++l) {
+                const double xv = (double)xi[m * ds + l];
+                const double r = (xv - (ce ? (double)ce[m * ds + l] : 0.0)) - (double)c[l];
+                pm += r * xv;
+                em += r * r;
+            }
         }
     };
 
@@ -346,6 +371,7 @@ encode_kernel(const float *__restrict__ x, int64_t n, int d, int M, int kc, int 
     for (int m = 0; m < M; ++m) {
         int best = 0;
         double bestd = INFINITY, bestp = 0.0;
+        enter(m);
         for (int j = 0; j < kc; ++j) {
             double pm, em;
             terms(m, j, pm, em);
@@ -367,6 +393,7 @@ encode_kernel(const float *__restrict__ x, int64_t n, int d, int M, int kc, int 
             }
             int best = 0;
             double bestv = INFINITY, bestp = 0.0, beste = 0.0;
+            enter(m);
             for (int j = 0; j < kc; ++j) {
                 double pm, em;
                 terms(m, j, pm, em);
@@ -402,9 +429,18 @@ int launch_encode(const float *x, int64_t n, int d, int M, int kc, int bits,
                   hipStream_t st)
 {
     if (M > kMaxM) { set_error("encode: M = %d exceeds %d", M, kMaxM); return AVQ_EINVAL; }
-    hipLaunchKernelGGL(encode_kernel, dim3((unsigned)((n + 127) / 128)), dim3(128), 0, st, x, n, d, M, kc,
-                       bits, codebooks, leaf_centers, leaf_assign, eta_mode, T, eta_explicit, passes,
-                       packed);
+    if (M < 1 || d % M != 0) { set_error("encode: d = %d is not a multiple of M = %d", d, M); return AVQ_EINVAL; }
+    const dim3 grid((unsigned)((n + 127) / 128)), block(128);
+#define AVQ_ENCODE(DS)                                                                                        \
+    hipLaunchKernelGGL(encode_kernel<DS>, grid, block, 0, st, x, n, d, M, kc, bits, codebooks, leaf_centers, \
+                       leaf_assign, eta_mode, T, eta_explicit, passes, packed)
+    switch (d / M) {
+    case 2: AVQ_ENCODE(2); break;
+    case 4: AVQ_ENCODE(4); break;
+    case 8: AVQ_ENCODE(8); break;
+    default: AVQ_ENCODE(0); break;
+    }
+#undef AVQ_ENCODE
     AVQ_HIP(hipGetLastError());
     return AVQ_OK;
 }
