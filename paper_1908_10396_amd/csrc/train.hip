@@ -308,8 +308,8 @@ constexpr int kMaxM = 256;
 // ||r_par||^2 = p^2/||x||^2 and ||r_perp||^2 = e - p^2/||x||^2, so the loss is
 // e + (eta - 1) p^2 / ||x||^2. p and e are sums over subspaces; changing the
 // codeword of subspace m only changes that subspace's terms, so the terms of the
-// current codewords are kept per subspace and only summed again (in subspace order,
-// never updated in place: no drift) when another subspace is revisited.
+// current codewords are kept per subspace and only summed again (every pass forms
+// the sums before and after each subspace afresh from the kept terms: no drift).
 // DS = dimensions per subspace known at compile time (0: any): the point's sub-vector of the
 // subspace at hand then stays in registers while its kc codewords (wave-uniform, read through
 // the scalar cache) pass by, instead of being read again for every codeword from a row that
@@ -330,6 +330,7 @@ encode_kernel(const float *__restrict__ x, int64_t n, int d, int M, int kc, int 
     double xv_m[kReg], xr_m[kReg]; // DS != 0: x^(m) and x^(m) - center^(m) of the subspace entered last
     uint8_t code[kMaxM];
     double pm_cur[kMaxM], em_cur[kMaxM]; // terms of the current codeword of every subspace
+    double pm_after[kMaxM], em_after[kMaxM]; // their sums over the subspaces after m, as of the start of a pass
 
     double nx2 = 0.0;
     for (int l = 0; l < d; ++l) nx2 += (double)xi[l] * (double)xi[l];
@@ -383,14 +384,18 @@ encode_kernel(const float *__restrict__ x, int64_t n, int d, int M, int kc, int 
     }
     for (int pass = 0; pass < passes; ++pass) {
         bool changed = false;
+        // p and e of the other subspaces = the subspaces before m (running sums of this pass) + those after
+        // it (sums formed here, from the last subspace down): M additions per pass instead of M per subspace
+        double after_p = 0.0, after_e = 0.0;
+        for (int m = M - 1; m >= 0; --m) {
+            pm_after[m] = after_p;
+            em_after[m] = after_e;
+            after_p += pm_cur[m];
+            after_e += em_cur[m];
+        }
+        double before_p = 0.0, before_e = 0.0;
         for (int m = 0; m < M; ++m) {
-            // p and e of the other subspaces
-            double Pr = 0.0, Er = 0.0;
-            for (int m2 = 0; m2 < M; ++m2) {
-                if (m2 == m) continue;
-                Pr += pm_cur[m2];
-                Er += em_cur[m2];
-            }
+            const double Pr = before_p + pm_after[m], Er = before_e + em_after[m];
             int best = 0;
             double bestv = INFINITY, bestp = 0.0, beste = 0.0;
             enter(m);
@@ -407,6 +412,8 @@ encode_kernel(const float *__restrict__ x, int64_t n, int d, int M, int kc, int 
                 em_cur[m] = beste;
                 changed = true;
             }
+            before_p += pm_cur[m];
+            before_e += em_cur[m];
         }
         if (!changed) break;
     }
