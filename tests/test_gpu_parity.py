@@ -421,7 +421,7 @@ def test_error_paths():
 
 # ---- training and encoding ---------------------------------------------------------
 
-@pytest.mark.parametrize("name", ["tiny_nb8", "glove_nb25", "large8_nb32", "odd_m_nb4"])
+@pytest.mark.parametrize("name", ["tiny_nb8", "glove_nb25", "large8_nb32", "odd_m_nb4", "bits100_nb13", "bits8_nb3"])
 def test_encode_matches(name):
     n, d, M, bits, nq = CASES[name]
     n = min(n, 3000)
