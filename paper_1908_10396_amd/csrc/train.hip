@@ -337,7 +337,8 @@ encode_kernel(const float *__restrict__ x, int64_t n, int d, int M, int kc, int 
     const double eta = eta_of_norm(d, T, sqrt(nx2), eta_mode, eta_explicit);
     const double w = nx2 > 0.0 ? (eta - 1.0) / nx2 : 0.0;
 
-    // terms of subspace m for codeword j: pm = <r^(m), x^(m)>, em = ||r^(m)||^2
+    // terms of subspace m for codeword j: pm = <r^(m), x^(m)>, em = ||r^(m)||^2 (fused multiply-adds: one
+    // rounding per term instead of two, a third fewer fp64 operations per codeword)
     auto enter = [&](int m) {
         if constexpr (DS != 0) {
 #pragma unroll
@@ -355,15 +356,15 @@ encode_kernel(const float *__restrict__ x, int64_t n, int d, int M, int kc, int 
 #pragma unroll
             for (int l = 0; l < DS; ++l) {
                 const double r = xr_m[l] - (double)c[l];
-                pm += r * xv_m[l];
-                em += r * r;
+                pm = fma(r, xv_m[l], pm);
+                em = fma(r, r, em);
             }
         } else {
             for (int l = 0; l < ds; ++l) {
                 const double xv = (double)xi[m * ds + l];
                 const double r = (xv - (ce ? (double)ce[m * ds + l] : 0.0)) - (double)c[l];
-                pm += r * xv;
-                em += r * r;
+                pm = fma(r, xv, pm);
+                em = fma(r, r, em);
             }
         }
     };
