@@ -97,40 +97,43 @@ __global__ void init_centers_kernel(const float *__restrict__ x, int ld, int col
 // ACCUM with k*dim <= kLdsAccMax: sums are first added up per workgroup in LDS.
 constexpr int kLdsAccMax = 4096;
 
-template <bool ACCUM>
+// XT: type of the staged values. float (half the LDS, so twice the waves per compute unit at large dim) holds
+// them exactly when no residual is formed (rc == nullptr: the values are the floats of x).
+template <bool ACCUM, typename XT = double>
 __global__ void __launch_bounds__(256)
 nearest_kernel(const float *__restrict__ x, int64_t n, int ld, int col0, int dim, int k,
                const float *__restrict__ rc, const int32_t *__restrict__ ra,
                const float *__restrict__ centers, double *__restrict__ sums,
                unsigned long long *__restrict__ counts, int32_t *__restrict__ assign)
 {
-    extern __shared__ double xs[]; // [dim][blockDim.x], then (ACCUM, small k*dim) [k*dim] + [k]
+    extern __shared__ double xs_raw[]; // XT [dim][blockDim.x], then (ACCUM, small k*dim) double [k*dim] + [k]
+    XT *xs = (XT *)xs_raw;
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const bool valid = i < n;
     const int bs = blockDim.x;
     const bool lds_acc = ACCUM && k * dim <= kLdsAccMax;
-    double *lsum = xs + (size_t)dim * bs;
+    double *lsum = (double *)(xs + (size_t)dim * bs); // 8-byte aligned: bs is a multiple of 64
     unsigned long long *lcnt = (unsigned long long *)(lsum + k * dim);
     if (lds_acc) {
         for (int t = threadIdx.x; t < k * dim; t += bs) lsum[t] = 0.0;
         for (int t = threadIdx.x; t < k; t += bs) lcnt[t] = 0ull;
         __syncthreads();
     }
-    for (int l = 0; l < dim; ++l) xs[l * bs + threadIdx.x] = valid ? sub_value(x, i, ld, col0 + l, rc, ra) : 0.0;
+    for (int l = 0; l < dim; ++l) xs[l * bs + threadIdx.x] = valid ? (XT)sub_value(x, i, ld, col0 + l, rc, ra) : (XT)0;
     int best = 0;
     double bestd = INFINITY;
     for (int j = 0; j < k; ++j) {
         const float *c = centers + (size_t)j * dim;
         double dd = 0.0;
         for (int l = 0; l < dim; ++l) {
-            const double t = xs[l * bs + threadIdx.x] - (double)c[l];
+            const double t = (double)xs[l * bs + threadIdx.x] - (double)c[l];
             dd += t * t;
         }
         if (dd < bestd) { bestd = dd; best = j; }
     }
     if (lds_acc) {
         if (valid) {
-            for (int l = 0; l < dim; ++l) atomicAdd(&lsum[best * dim + l], xs[l * bs + threadIdx.x]);
+            for (int l = 0; l < dim; ++l) atomicAdd(&lsum[best * dim + l], (double)xs[l * bs + threadIdx.x]);
             atomicAdd(&lcnt[best], 1ull);
         }
         __syncthreads();
@@ -143,7 +146,7 @@ nearest_kernel(const float *__restrict__ x, int64_t n, int ld, int col0, int dim
     }
     if (!valid) return;
     if (ACCUM) {
-        for (int l = 0; l < dim; ++l) atomicAdd(&sums[(size_t)best * dim + l], xs[l * bs + threadIdx.x]);
+        for (int l = 0; l < dim; ++l) atomicAdd(&sums[(size_t)best * dim + l], (double)xs[l * bs + threadIdx.x]);
         atomicAdd(&counts[best], 1ull);
     } else {
         assign[i] = best;
@@ -167,13 +170,28 @@ static int nearest_block_size(int dim)
     return bs;
 }
 
+// Values staged as floats (no residual, and doubles would leave room for one small workgroup per compute
+// unit only): workgroups of at most 64 KB, so that several share a compute unit.
+static bool nearest_stage_floats(int dim, bool residual)
+{
+    return !residual && (size_t)256 * dim * sizeof(double) > 64 * 1024;
+}
+static int nearest_block_size_floats(int dim)
+{
+    int bs = 256;
+    while (bs > 64 && (size_t)bs * dim * sizeof(float) > 64 * 1024) bs /= 2;
+    return bs;
+}
+
 int kmeans_device(const float *x, int64_t n, int ld, int col0, int dim, int k, int iters,
                   uint64_t seed, uint32_t stream_id, const float *resid_centers,
                   const int32_t *resid_assign, float *centers, hipStream_t st)
 {
     if (n < k) { set_error("k-means: %lld points for %d centers", (long long)n, k); return AVQ_EINVAL; }
-    const int bs = nearest_block_size(dim);
-    if ((size_t)bs * dim * sizeof(double) > 150 * 1024) {
+    const bool floats = nearest_stage_floats(dim, resid_centers != nullptr);
+    const int bs = floats ? nearest_block_size_floats(dim) : nearest_block_size(dim);
+    const size_t stage = (size_t)bs * dim * (floats ? sizeof(float) : sizeof(double));
+    if (stage > 150 * 1024) {
         set_error("k-means: dimension %d too large", dim);
         return AVQ_EINVAL;
     }
@@ -193,15 +211,20 @@ int kmeans_device(const float *x, int64_t n, int ld, int col0, int dim, int k, i
         AVQ_HIP(hipGetLastError());
         AVQ_HIP(hipFuncSetAttribute((const void *)nearest_kernel<true>,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynLds));
+        AVQ_HIP(hipFuncSetAttribute((const void *)nearest_kernel<true, float>,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynLds));
         const unsigned grid = (unsigned)((n + bs - 1) / bs);
         for (int it = 0; it < iters; ++it) {
             AVQ_HIP(hipMemsetAsync(sums, 0, sizeof(double) * (size_t)k * dim, st));
             AVQ_HIP(hipMemsetAsync(counts, 0, sizeof(unsigned long long) * k, st));
-            const size_t lds = (size_t)bs * dim * sizeof(double) +
-                               (k * dim <= kLdsAccMax ? (size_t)(k * dim + k) * sizeof(double) : 0);
-            hipLaunchKernelGGL(nearest_kernel<true>, dim3(grid), dim3(bs), lds,
-                               st, x, n, ld, col0, dim, k, resid_centers, resid_assign, centers, sums,
-                               counts, (int32_t *)nullptr);
+            const size_t lds = stage + (k * dim <= kLdsAccMax ? (size_t)(k * dim + k) * sizeof(double) : 0);
+            if (floats)
+                hipLaunchKernelGGL((nearest_kernel<true, float>), dim3(grid), dim3(bs), lds, st, x, n, ld, col0, dim,
+                                   k, resid_centers, resid_assign, centers, sums, counts, (int32_t *)nullptr);
+            else
+                hipLaunchKernelGGL(nearest_kernel<true>, dim3(grid), dim3(bs), lds,
+                                   st, x, n, ld, col0, dim, k, resid_centers, resid_assign, centers, sums,
+                                   counts, (int32_t *)nullptr);
             AVQ_HIP(hipGetLastError());
             hipLaunchKernelGGL(update_centers_kernel, dim3((k * dim + 255) / 256), dim3(256), 0, st, sums,
                                counts, k, dim, centers);
@@ -220,17 +243,26 @@ int kmeans_device(const float *x, int64_t n, int ld, int col0, int dim, int k, i
 int launch_assign_nearest(const float *x, int64_t n, int d, const float *centers, int k,
                           int32_t *assign, hipStream_t st)
 {
-    const int bs = nearest_block_size(d);
-    if ((size_t)bs * d * sizeof(double) > 150 * 1024) {
+    const bool floats = nearest_stage_floats(d, false);
+    const int bs = floats ? nearest_block_size_floats(d) : nearest_block_size(d);
+    const size_t stage = (size_t)bs * d * (floats ? sizeof(float) : sizeof(double));
+    if (stage > 150 * 1024) {
         set_error("assign: dimension %d too large", d);
         return AVQ_EINVAL;
     }
-    AVQ_HIP(hipFuncSetAttribute((const void *)nearest_kernel<false>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynLds));
-    hipLaunchKernelGGL(nearest_kernel<false>, dim3((unsigned)((n + bs - 1) / bs)), dim3(bs),
-                       (size_t)bs * d * sizeof(double), st, x, n, d, 0, d, k, (const float *)nullptr,
-                       (const int32_t *)nullptr, centers, (double *)nullptr,
-                       (unsigned long long *)nullptr, assign);
+    if (floats) {
+        AVQ_HIP(hipFuncSetAttribute((const void *)nearest_kernel<false, float>,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynLds));
+        hipLaunchKernelGGL((nearest_kernel<false, float>), dim3((unsigned)((n + bs - 1) / bs)), dim3(bs), stage, st,
+                           x, n, d, 0, d, k, (const float *)nullptr, (const int32_t *)nullptr, centers,
+                           (double *)nullptr, (unsigned long long *)nullptr, assign);
+    } else {
+        AVQ_HIP(hipFuncSetAttribute((const void *)nearest_kernel<false>,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynLds));
+        hipLaunchKernelGGL(nearest_kernel<false>, dim3((unsigned)((n + bs - 1) / bs)), dim3(bs), stage, st, x, n, d,
+                           0, d, k, (const float *)nullptr, (const int32_t *)nullptr, centers, (double *)nullptr,
+                           (unsigned long long *)nullptr, assign);
+    }
     AVQ_HIP(hipGetLastError());
     return AVQ_OK;
 }
